@@ -1,0 +1,206 @@
+"""Pins for the oracle's attention with the Region-Instruction KV cache (Eq.6) and the
+block around it (CPU only).  Expected values come from torch CPU library routines, from
+closed forms of softmax attention and from the structural identities of Eq.6: with every
+token fresh it is ordinary attention, and with a cache stored on the same input a region
+forward equals the full forward restricted to the fresh rows.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import regione_oracle as orc
+from paper_2510_25590_amd import inputs
+
+
+def _rand_qkv(rng, n, heads, d):
+    return (rng.standard_normal((n, heads, d)) for _ in range(3))
+
+
+def test_all_fresh_equals_library_attention():
+    rng = np.random.default_rng(10)
+    q, k, v = _rand_qkv(rng, 37, 3, 16)
+    out = orc.attention_kvcache(q, k, v)
+    tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(x.transpose(1, 0, 2))) for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).numpy().transpose(1, 0, 2)
+    assert np.max(np.abs(out - ref)) < 1e-12
+
+
+def test_fresh_plus_cache_equals_library_attention_on_concatenation():
+    rng = np.random.default_rng(11)
+    q, kf, vf = _rand_qkv(rng, 9, 2, 8)
+    kc, vc = rng.standard_normal((21, 2, 8)), rng.standard_normal((21, 2, 8))
+    idx = np.array([0, 3, 4, 20, 7], dtype=np.int32)
+    out = orc.attention_kvcache(q, kf, vf, kc, vc, idx)
+    k = np.concatenate([kf, kc[idx]])
+    v = np.concatenate([vf, vc[idx]])
+    tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(x.transpose(1, 0, 2))) for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).numpy().transpose(1, 0, 2)
+    assert np.max(np.abs(out - ref)) < 1e-12
+    # the rows left out of cache_index must not matter
+    kc2 = kc.copy(); kc2[1] += 100.0
+    assert np.array_equal(out, orc.attention_kvcache(q, kf, vf, kc2, vc, idx))
+
+
+def test_attention_closed_forms():
+    rng = np.random.default_rng(12)
+    q, _, _ = _rand_qkv(rng, 5, 2, 8)
+    # one key: output is that value
+    k1, v1 = rng.standard_normal((1, 2, 8)), rng.standard_normal((1, 2, 8))
+    assert np.allclose(orc.attention_kvcache(q, k1, v1), np.broadcast_to(v1, (5, 2, 8)), atol=1e-14)
+    # identical keys: output is the mean of the values
+    k = np.broadcast_to(k1, (6, 2, 8)).copy()
+    v = rng.standard_normal((6, 2, 8))
+    assert np.allclose(orc.attention_kvcache(q, k[:2], v[:2], k[2:], v[2:]), np.broadcast_to(v.mean(0), (5, 2, 8)), atol=1e-13)
+    # zero query: mean of the values, fresh and cached alike
+    kk = rng.standard_normal((6, 2, 8))
+    assert np.allclose(orc.attention_kvcache(np.zeros((5, 2, 8)), kk[:2], v[:2], kk[2:], v[2:]),
+                       np.broadcast_to(v.mean(0), (5, 2, 8)), atol=1e-13)
+    # two keys, d = 1, by hand: weights softmax(q*k*scale)
+    qq = np.array([[[2.0]]]); k2 = np.array([[[1.0]], [[-1.0]]]); v2 = np.array([[[10.0]], [[20.0]]])
+    w0 = math.exp(2.0) / (math.exp(2.0) + math.exp(-2.0))
+    assert orc.attention_kvcache(qq, k2[:1], v2[:1], k2[1:], v2[1:])[0, 0, 0] == pytest.approx(10 * w0 + 20 * (1 - w0), rel=1e-14)
+    # scale = 1/sqrt(d): d = 4, q.k = 4 -> logit 2
+    q4 = np.ones((1, 1, 4)); k4 = np.stack([np.ones((1, 4)), -np.ones((1, 4))]); v4 = np.array([[[1.0] * 4], [[0.0] * 4]])
+    assert orc.attention_kvcache(q4, k4, v4)[0, 0, 0] == pytest.approx(w0, rel=1e-14)
+
+
+def test_key_order_invariance_and_empty_cache():
+    rng = np.random.default_rng(13)
+    q, kf, vf = _rand_qkv(rng, 7, 2, 8)
+    kc, vc = rng.standard_normal((15, 2, 8)), rng.standard_normal((15, 2, 8))
+    base = orc.attention_kvcache(q, kf, vf, kc, vc)
+    perm = rng.permutation(15)
+    assert np.allclose(base, orc.attention_kvcache(q, kf, vf, kc[perm], vc[perm]), atol=1e-13)
+    # n_c = 0 ("w/o RIKVCache" of the ablation): local attention over the fresh rows
+    assert np.array_equal(orc.attention_kvcache(q, kf, vf, kc[:0], vc[:0]), orc.attention_kvcache(q, kf, vf))
+
+
+def test_layer_norm_gelu_linear_against_library():
+    rng = np.random.default_rng(14)
+    x = rng.standard_normal((11, 32)) * 3 + 1
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(x), (32,), eps=1e-6).numpy()
+    assert np.max(np.abs(orc.layer_norm(x) - ref)) < 1e-12
+    g = torch.nn.functional.gelu(torch.from_numpy(x), approximate="tanh").numpy()
+    assert np.max(np.abs(orc.gelu_tanh(x) - g)) < 1e-12
+    assert orc.gelu_tanh(np.array([0.0]))[0] == 0.0
+    assert orc.gelu_tanh(np.array([10.0]))[0] == pytest.approx(10.0, rel=1e-12)
+    w = rng.standard_normal((5, 32)); b = rng.standard_normal(5)
+    y = orc.linear(x, w, b)
+    brute = np.array([[sum(x[i, k] * w[o, k] for k in range(32)) + b[o] for o in range(5)] for i in range(11)])
+    assert np.max(np.abs(y - brute)) < 1e-12
+    sh, sc = rng.standard_normal(32), rng.standard_normal(32)
+    assert np.allclose(orc.modulate(x, sh, sc), x * (1 + sc) + sh)
+    assert orc.modulate(x, None, None) is x
+
+
+def _tiny_model(seed, kind, hidden=32, mlp=64):
+    rng = np.random.default_rng(seed)
+    n_streams = 2 if kind == "double" else 1
+    return [inputs.stream_weights(rng, hidden, mlp, kind, "f32", std=0.2) for _ in range(n_streams)], rng
+
+
+@pytest.mark.parametrize("kind", ["double", "single"])
+def test_same_step_cache_equals_full_forward_restricted_to_fresh_rows(kind):
+    heads, hidden = 4, 32
+    streams, rng = _tiny_model(20, kind)
+    n_txt, n_img, n_ref = 3, 16, 16
+    n_all = n_txt + n_img + n_ref
+    h = rng.standard_normal((n_all, hidden))
+    kc = np.zeros((n_all, heads, hidden // heads)); vc = np.zeros_like(kc)
+    full = orc.block_forward(streams, kind, h, n_txt, np.arange(n_all), kc, vc, orc.FLAG_STORE, heads)
+    plain = orc.block_forward(streams, kind, h, n_txt, np.arange(n_all), None, None, 0, heads)
+    assert np.array_equal(full, plain)                       # storing does not change the output
+    assert np.abs(kc).sum() > 0
+    e = np.array([1, 2, 5, 11], dtype=np.int32)              # edited image tokens
+    kc0, vc0 = kc.copy(), vc.copy()
+    # mode B: only the edited image rows are fresh
+    slots = n_txt + e
+    out_b = orc.block_forward(streams, kind, h[slots], 0, slots, kc, vc, orc.FLAG_RETRIEVE, heads)
+    assert np.max(np.abs(out_b - full[slots])) < 1e-12
+    # mode A (Eq.6 as printed): text rows and edited rows are fresh
+    slots_a = np.concatenate([np.arange(n_txt), n_txt + e])
+    out_a = orc.block_forward(streams, kind, h[slots_a], n_txt, slots_a, kc, vc, orc.FLAG_RETRIEVE, heads)
+    assert np.max(np.abs(out_a - full[slots_a])) < 1e-12
+    assert np.array_equal(kc, kc0) and np.array_equal(vc, vc0)  # retrieving never writes the cache
+    # all image rows edited: region forward == full forward on those rows
+    slots_all = np.arange(n_txt + n_img)
+    out_all = orc.block_forward(streams, kind, h[slots_all], n_txt, slots_all, kc, vc, orc.FLAG_RETRIEVE, heads)
+    assert np.max(np.abs(out_all - full[slots_all])) < 1e-12
+    with pytest.raises(ValueError):
+        orc.block_forward(streams, kind, h, n_txt, np.arange(n_all), kc, vc, 3, heads)
+
+
+def test_stale_cache_changes_only_through_attention():
+    # perturbing a cached (unedited) row changes the region output; perturbing the stale cache
+    # entry of an edited row does not (Eq.6 never reads it)
+    heads, hidden = 4, 32
+    streams, rng = _tiny_model(21, "double")
+    n_txt, n_all = 2, 2 + 8 + 8
+    h = rng.standard_normal((n_all, hidden))
+    kc = np.zeros((n_all, heads, 8)); vc = np.zeros_like(kc)
+    orc.block_forward(streams, "double", h, n_txt, np.arange(n_all), kc, vc, orc.FLAG_STORE, heads)
+    slots = np.array([3, 4])
+    base = orc.block_forward(streams, "double", h[slots], 0, slots, kc, vc, orc.FLAG_RETRIEVE, heads)
+    kc2 = kc.copy(); kc2[3] += 5.0
+    assert np.array_equal(base, orc.block_forward(streams, "double", h[slots], 0, slots, kc2, vc, orc.FLAG_RETRIEVE, heads))
+    kc3 = kc.copy(); kc3[6] += 5.0
+    assert np.max(np.abs(base - orc.block_forward(streams, "double", h[slots], 0, slots, kc3, vc, orc.FLAG_RETRIEVE, heads))) > 1e-6
+
+
+def test_double_block_brute_force_tiny():
+    # explicit loops over every index on a 2-token, hidden-4, 1-head block
+    rng = np.random.default_rng(22)
+    hidden, mlp, heads = 4, 8, 1
+    w = inputs.stream_weights(rng, hidden, mlp, "double", "f32", std=0.5)
+    h = rng.standard_normal((2, hidden))
+
+    def ln(x):
+        m = sum(x) / len(x); var = sum((a - m) ** 2 for a in x) / len(x)
+        return [(a - m) / math.sqrt(var + 1e-6) for a in x]
+
+    def lin(x, W, b):
+        return [sum(x[k] * float(W[o][k]) for k in range(len(x))) + float(b[o]) for o in range(len(W))]
+
+    def gelu(a):
+        return 0.5 * a * (1 + math.tanh(math.sqrt(2 / math.pi) * (a + 0.044715 * a ** 3)))
+
+    qkv = []
+    for r in range(2):
+        u = [a * (1 + float(w["scale1"][c])) + float(w["shift1"][c]) for c, a in enumerate(ln(list(h[r])))]
+        qkv.append(lin(u, w["w_qkv"], w["b_qkv"]))
+    out = []
+    for r in range(2):
+        q = qkv[r][:4]
+        logits = [sum(q[c] * qkv[s][4 + c] for c in range(4)) / 2.0 for s in range(2)]
+        mx = max(logits); p = [math.exp(a - mx) for a in logits]; z = sum(p)
+        a = [sum(p[s] / z * qkv[s][8 + c] for s in range(2)) for c in range(4)]
+        o = lin(a, w["w_o"], w["b_o"])
+        h1 = [float(h[r][c]) + float(w["gate1"][c]) * o[c] for c in range(4)]
+        u2 = [x * (1 + float(w["scale2"][c])) + float(w["shift2"][c]) for c, x in enumerate(ln(h1))]
+        m = lin([gelu(x) for x in lin(u2, w["w_1"], w["b_1"])], w["w_2"], w["b_2"])
+        out.append([h1[c] + float(w["gate2"][c]) * m[c] for c in range(4)])
+    got = orc.block_forward([w, w], "double", h, 0, np.arange(2), None, None, 0, heads)
+    assert np.max(np.abs(got - np.array(out))) < 1e-12
+
+
+def test_single_block_brute_force_tiny():
+    rng = np.random.default_rng(23)
+    hidden, mlp, heads = 4, 6, 2
+    w = inputs.stream_weights(rng, hidden, mlp, "single", "f32", std=0.5)
+    h = rng.standard_normal((3, hidden))
+    u = orc.modulate(orc.layer_norm(h), w["shift1"], w["scale1"])
+    y = u @ w["w_1"].astype(np.float64).T + w["b_1"]
+    q, k, v, m = y[:, :4], y[:, 4:8], y[:, 8:12], y[:, 12:]
+    a = np.zeros((3, 4))
+    for hd in range(2):
+        cols = slice(2 * hd, 2 * hd + 2)
+        for r in range(3):
+            lg = np.array([q[r, cols] @ k[s, cols] / math.sqrt(2) for s in range(3)])
+            p = np.exp(lg - lg.max()); p /= p.sum()
+            a[r, cols] = sum(p[s] * v[s, cols] for s in range(3))
+    cat = np.concatenate([a, orc.gelu_tanh(m)], axis=1)
+    want = h + w["gate1"] * (cat @ w["w_2"].astype(np.float64).T + w["b_2"])
+    got = orc.block_forward([w], "single", h, 0, np.arange(3), None, None, 0, heads)
+    assert np.max(np.abs(got - want)) < 1e-12
