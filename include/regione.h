@@ -1,0 +1,192 @@
+/*
+ * regione.h - C ABI of the RegionE region-aware denoising step for AMD MI355X (gfx950).
+ *
+ * The library implements the data-parallel part of one region-aware step of RegionE
+ * (arXiv 2510.25590, section "Methodology" and Algorithm 1): adaptive region partition,
+ * gather of the edited tokens, transformer blocks on those tokens with attention over the
+ * Region-Instruction KV cache (Eq.6), the adaptive velocity decay cache (Eq.7-9) with the
+ * Euler update (Eq.4), and the scatter back by spatial position.
+ *
+ * Conventions
+ *  - Every function returns REGIONE_OK (0) or a negative error code; regione_last_error()
+ *    returns a message for the last failure on the calling thread.  Nothing throws.
+ *  - Pointers are DEVICE pointers unless the name ends in _host.  The caller owns every
+ *    tensor (inputs, outputs, KV cache, velocity cache); the library owns only the context
+ *    and the workspace inside it.  Tensors are row-major with the innermost dimension
+ *    contiguous; base addresses must be 16-byte aligned.
+ *  - Work is enqueued on the HIP stream given to regione_create and is asynchronous; the
+ *    only call that waits for the stream is regione_partition with a non-null
+ *    n_edited_host.  Calls on one context must not overlap (they share its workspace).
+ *  - Token order of the cached sequence is [P (text) | X (image) | I (reference image)].
+ *  - Linear weights are bf16 [out_features, in_features]; biases and modulation vectors
+ *    are float32.
+ *  - Empty inputs (no edited token, no cache rows) are not errors: the call does nothing
+ *    or degenerates as Eq.6 does.
+ */
+#ifndef REGIONE_H
+#define REGIONE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    REGIONE_OK = 0,
+    REGIONE_ERR_INVALID_ARG = -1, /* null pointer, negative size, bad enum, both flags */
+    REGIONE_ERR_BAD_SHAPE = -2,   /* sizes inconsistent with each other or with the context */
+    REGIONE_ERR_UNSUPPORTED = -3, /* e.g. head dimension other than 64 or 128 */
+    REGIONE_ERR_WORKSPACE = -4,   /* call needs more rows than the context was created for */
+    REGIONE_ERR_HIP = -5          /* a HIP runtime call failed */
+};
+
+enum { REGIONE_BF16 = 0, REGIONE_FP32 = 1 };
+enum { REGIONE_BLOCK_DOUBLE = 0, REGIONE_BLOCK_SINGLE = 1 };
+/* The flag pair f = (store, retrieve) of Algorithm 1. */
+enum { REGIONE_FLAG_STORE = 1, REGIONE_FLAG_RETRIEVE = 2 };
+enum { REGIONE_ACT_NONE = 0, REGIONE_ACT_GELU_TANH = 1 };
+
+typedef struct regione_ctx regione_ctx;
+
+/* Sizes the workspace is allocated for. */
+typedef struct regione_dims {
+    int32_t hidden;     /* H = heads * head_dim */
+    int32_t heads;
+    int32_t head_dim;   /* 64 or 128 */
+    int32_t mlp;        /* MLP width M */
+    int32_t max_fresh;  /* most rows one regione_block_forward call will carry */
+    int32_t max_tokens; /* most tokens one regione_partition call will carry */
+} regione_dims;
+
+/* Weights of one stream of a block (host struct of device pointers).
+ * Double-stream block: w_qkv [3H,H], w_o [H,H], w_1 [M,H], w_2 [H,M].
+ * Single-stream block: w_1 [3H+M,H] producing [q|k|v|m], w_2 [H,H+M] applied to
+ * [attention | gelu(m)]; w_qkv, w_o and the *2 modulation vectors are ignored.
+ * Modulation vectors [H] may be NULL (shift = scale = 0, gate = 1). */
+typedef struct regione_stream_weights {
+    const void* w_qkv; const float* b_qkv;
+    const void* w_o;   const float* b_o;
+    const void* w_1;   const float* b_1;
+    const void* w_2;   const float* b_2;
+    const float* shift1; const float* scale1; const float* gate1;
+    const float* shift2; const float* scale2; const float* gate2;
+} regione_stream_weights;
+
+typedef struct regione_block_weights {
+    regione_stream_weights txt; /* text rows of a double-stream block */
+    regione_stream_weights img; /* image / reference rows; the only set of a single-stream block */
+} regione_block_weights;
+
+/* State of the adaptive velocity decay cache between steps (host). */
+typedef struct regione_avd_state {
+    int32_t valid; /* 0: the cache holds no velocity yet */
+    double prod;   /* product of Eq.7 factors since the cached velocity was computed */
+} regione_avd_state;
+
+const char* regione_last_error(void);
+
+/* Creates a context bound to `hip_stream` (a hipStream_t, NULL = default stream) on the
+ * current device and allocates its workspace for `dims`.  The context is released with
+ * regione_destroy, which first waits for the stream. */
+int regione_create(regione_ctx** out, const regione_dims* dims, void* hip_stream);
+int regione_destroy(regione_ctx* ctx);
+
+/* Adaptive region partition (section "Adaptive Region Partition", Algorithm 1 lines of the
+ * ARP comment) without the morphological clean-up: one-step estimate x0 = x_t - sigma_t*v
+ * (Eq.5 with t_f = 0), cosine similarity of each token of x0 with the same token of x_ref
+ * over the c channels, unedited iff score > eta, and the ascending index lists.
+ *   x_t, v, x_ref : [n_tokens, c] of `dtype`.
+ *   score_opt     : [n_tokens] float32 or NULL.
+ *   mask          : [n_tokens] uint8, 1 = edited.
+ *   e_index, u_index : [n_tokens] int32 each; the first *n_edited entries of e_index and
+ *                   the first n_tokens - *n_edited entries of u_index are written.
+ *   n_edited_dev  : device int32.  n_edited_host_opt: host int32 or NULL; when given the
+ *                   call waits for the stream and stores the count there.
+ * Arithmetic: x0 in float32 (product and difference rounded separately), the three sums in
+ * float64, score = dot / max(sqrt(|x0|^2) sqrt(|ref|^2), 1e-8) rounded to float32 and
+ * compared with (float)eta.  A zero vector scores 0; NaN counts as edited. */
+int regione_partition(regione_ctx* ctx, const void* x_t, const void* v, const void* x_ref,
+                      int64_t n_tokens, int32_t c, int32_t dtype, float sigma_t, float eta,
+                      float* score_opt, uint8_t* mask, int32_t* e_index, int32_t* u_index,
+                      int32_t* n_edited_dev, int32_t* n_edited_host_opt);
+
+/* Row gather X[index] (Algorithm 1, "X^E = X[E_index]"): dst[i,:] = src[index[i],:] for
+ * i < n, with n = *n_dev when n_dev is non-null (clamped to n_max) and n_max otherwise.
+ * Rows have row_elems elements of `dtype`; the copy is bit-exact. src and dst must not overlap. */
+int regione_gather(regione_ctx* ctx, const void* src, int32_t row_elems, int32_t dtype,
+                   const int32_t* index, const int32_t* n_dev, int64_t n_max, void* dst);
+
+/* Merge by spatial position (Algorithm 1, the line after the inner loop):
+ * dst_full[index[i],:] = src[i,:] for i < n; every other row of dst_full is left untouched.
+ * Indices must be distinct. */
+int regione_scatter(regione_ctx* ctx, void* dst_full, int32_t row_elems, int32_t dtype,
+                    const int32_t* index, const int32_t* n_dev, int64_t n_max, const void* src);
+
+/* Attention with the Region-Instruction KV cache, Eq.6:
+ *   out = softmax(q [k_fresh; k_cache']^T * scale) [v_fresh; v_cache']
+ * per head, where cache' is all n_c cache rows when cache_index_opt is NULL and the
+ * n_cache_index rows it lists otherwise.  bf16 tensors, float32 softmax and accumulation.
+ *   q, out           : [n_q, heads, d]
+ *   k_fresh, v_fresh : [n_fresh, heads, d]; may be NULL when n_fresh == 0
+ *   k_cache, v_cache : [n_c, heads, d]; may be NULL when n_c == 0
+ * n_c == 0 is local attention (the "w/o RIKVCache" ablation).  At least one key is needed
+ * when n_q > 0.  d is 64 or 128.  scale <= 0 selects 1/sqrt(d). */
+int regione_attn_kvcache(regione_ctx* ctx, const void* q, int32_t n_q,
+                         const void* k_fresh, const void* v_fresh, int32_t n_fresh,
+                         const void* k_cache, const void* v_cache, int32_t n_c,
+                         const int32_t* cache_index_opt, int32_t n_cache_index,
+                         int32_t heads, int32_t d, float scale, void* out);
+
+/* y = act(x W^T + b): x [m,k] bf16, w [n,k] bf16, b [n] float32 or NULL, y [m,n] of
+ * out_dtype.  k must be a multiple of 8.  Used for the token embedding and the final
+ * projection around the blocks, and by the block itself. */
+int regione_linear(regione_ctx* ctx, const void* x, const void* w, const float* b_opt,
+                   int32_t m, int32_t n, int32_t k, int32_t act, int32_t out_dtype, void* y);
+
+/* One transformer block on the fresh rows: one layer of Phi(tokens, C_KV, f) in
+ * Algorithm 1.  The block is LayerNorm (no affine, eps 1e-6) -> modulation -> QKV linear ->
+ * attention -> gated residual -> LayerNorm -> modulation -> MLP with tanh-GELU -> gated
+ * residual (double-stream), or the fused single-stream form described at
+ * regione_stream_weights.
+ *   h_in, h_out : [n_fresh, H] of h_dtype (the residual stream; may be the same buffer).
+ *   n_txt_fresh : rows [0, n_txt_fresh) use w->txt, the rest w->img (double-stream only).
+ *   slot_index  : [n_fresh] int32, position of each fresh row in the cached sequence;
+ *                 needed when a flag is set.
+ *   k_cache, v_cache : [n_all, heads, head_dim] bf16, the layer's C_KV.
+ *   flags = REGIONE_FLAG_STORE    : full forward; n_fresh must equal n_all; the fresh K,V
+ *                                   are written to the cache rows slot_index.
+ *   flags = REGIONE_FLAG_RETRIEVE : Eq.6; keys/values are the fresh rows plus every cache
+ *                                   row that is not refreshed.  The fresh K,V overwrite
+ *                                   their own slots in the cache (those slots are never
+ *                                   read stale by Eq.6); all other cache rows are untouched.
+ *   flags = 0                     : plain attention over the fresh rows, cache unused.
+ *   both flags                    : REGIONE_ERR_INVALID_ARG. */
+int regione_block_forward(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
+                          const void* h_in, void* h_out, int32_t h_dtype,
+                          int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index,
+                          void* k_cache, void* v_cache, int32_t n_all, int32_t flags);
+
+/* Adaptive velocity decay cache, host decision (Eq.7, Eq.8): pure function of the
+ * schedule.  t_host has n_steps+1 entries with t[n_steps] = 1 and t[0] = 0; gamma_host has
+ * n_steps+1 entries (gamma[j] corrects the step at index j).  For the step at index j
+ * (1 <= j < n_steps) updates *st and returns *reuse (0: run the DiT and cache its velocity,
+ * 1: use the cached velocity times *factor). */
+int regione_velocity_decision_host(const float* t_host, const float* gamma_host, int32_t n_steps,
+                                   float delta, int32_t j, regione_avd_state* st,
+                                   int32_t* reuse, float* factor);
+
+/* Adaptive velocity decay cache, device part (Eq.9) fused with the Euler update (Eq.4) on
+ * the edited rows, for i < n rows of c channels (n as in regione_gather):
+ *   reuse == 0: c_a = v_fresh;           v_used = v_fresh
+ *   reuse != 0: c_a unchanged;           v_used = factor * c_a
+ *   x_e -= dt * v_used;  v_out_opt (if non-null) = v_used.
+ * All tensors [n, c] of `dtype`; float32 arithmetic. */
+int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float factor, float dt,
+                           const void* v_fresh_opt, void* c_a, void* v_out_opt, void* x_e,
+                           const int32_t* n_dev, int64_t n_max, int32_t c, int32_t dtype);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REGIONE_H */

@@ -1,0 +1,179 @@
+"""Thin ctypes binding over libregione.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA tensors (used for device memory and streams only); every step of the
+path runs in the library's HIP kernels.  The library is loaded on first use and the load
+fails loudly if it has not been built (`python -m paper_2510_25590_amd.build`); there is no
+fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libregione.so")
+
+OK = 0
+ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2, -3, -4, -5
+BF16, FP32 = 0, 1
+BLOCK_DOUBLE, BLOCK_SINGLE = 0, 1
+FLAG_STORE, FLAG_RETRIEVE = 1, 2
+ACT_NONE, ACT_GELU_TANH = 0, 1
+
+EXPORTS = (
+    "regione_last_error", "regione_create", "regione_destroy", "regione_partition", "regione_gather",
+    "regione_scatter", "regione_attn_kvcache", "regione_linear", "regione_block_forward",
+    "regione_velocity_decision_host", "regione_velocity_cache",
+)
+
+
+class Dims(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32), ("mlp", C.c_int32),
+                ("max_fresh", C.c_int32), ("max_tokens", C.c_int32)]
+
+
+_STREAM_FIELDS = ("w_qkv", "b_qkv", "w_o", "b_o", "w_1", "b_1", "w_2", "b_2",
+                  "shift1", "scale1", "gate1", "shift2", "scale2", "gate2")
+
+
+class StreamWeights(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in _STREAM_FIELDS]
+
+
+class BlockWeights(C.Structure):
+    _fields_ = [("txt", StreamWeights), ("img", StreamWeights)]
+
+
+class AvdState(C.Structure):
+    _fields_ = [("valid", C.c_int32), ("prod", C.c_double)]
+
+
+class RegionEError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"regione error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2510_25590_amd.build`")
+        _lib = C.CDLL(LIB_PATH)
+        _lib.regione_last_error.restype = C.c_char_p
+        vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+        sig = {
+            "regione_create": [C.POINTER(vp), C.POINTER(Dims), vp],
+            "regione_destroy": [vp],
+            "regione_partition": [vp, vp, vp, vp, i64, i32, i32, f32, f32, vp, vp, vp, vp, vp, C.POINTER(i32)],
+            "regione_gather": [vp, vp, i32, i32, vp, vp, i64, vp],
+            "regione_scatter": [vp, vp, i32, i32, vp, vp, i64, vp],
+            "regione_attn_kvcache": [vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, i32, i32, i32, f32, vp],
+            "regione_linear": [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
+            "regione_block_forward": [vp, C.POINTER(BlockWeights), i32, vp, vp, i32, i32, i32, vp, vp, vp, i32, i32],
+            "regione_velocity_decision_host": [C.POINTER(f32), C.POINTER(f32), i32, f32, i32, C.POINTER(AvdState),
+                                               C.POINTER(i32), C.POINTER(f32)],
+            "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
+        }
+        for name, args in sig.items():
+            fn = getattr(_lib, name)
+            fn.argtypes = args
+            fn.restype = C.c_int
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise RegionEError(rc, lib().regione_last_error().decode())
+
+
+def _p(t):
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+class Context:
+    """Owns a regione_ctx bound to a torch stream (default: the current one)."""
+
+    def __init__(self, hidden: int, heads: int, head_dim: int, mlp: int, max_fresh: int, max_tokens: int, stream=None):
+        import torch
+        self._torch = torch
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        self.dims = Dims(hidden, heads, head_dim, mlp, max_fresh, max_tokens)
+        handle = C.c_void_p()
+        _check(lib().regione_create(C.byref(handle), C.byref(self.dims), C.c_void_p(self.stream.cuda_stream)))
+        self.handle = handle
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().regione_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def make_stream_weights(tensors: dict) -> StreamWeights:
+    """dict name -> torch CUDA tensor (missing names become NULL).  The caller keeps the tensors alive."""
+    w = StreamWeights()
+    for name in _STREAM_FIELDS:
+        t = tensors.get(name)
+        setattr(w, name, None if t is None else t.data_ptr())
+    return w
+
+
+def regione_partition(ctx, x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta, score, mask, e_index, u_index,
+                      n_edited_dev, read_count: bool = True):
+    host = C.c_int32(-1)
+    _check(lib().regione_partition(ctx.handle, _p(x_t), _p(v), _p(x_ref), n_tokens, c, dtype, sigma_t, eta,
+                                   _p(score), _p(mask), _p(e_index), _p(u_index), _p(n_edited_dev),
+                                   C.byref(host) if read_count else None))
+    return host.value if read_count else None
+
+
+def regione_gather(ctx, src, row_elems, dtype, index, n_dev, n_max, dst):
+    _check(lib().regione_gather(ctx.handle, _p(src), row_elems, dtype, _p(index), _p(n_dev), n_max, _p(dst)))
+
+
+def regione_scatter(ctx, dst_full, row_elems, dtype, index, n_dev, n_max, src):
+    _check(lib().regione_scatter(ctx.handle, _p(dst_full), row_elems, dtype, _p(index), _p(n_dev), n_max, _p(src)))
+
+
+def regione_attn_kvcache(ctx, q, n_q, k_fresh, v_fresh, n_fresh, k_cache, v_cache, n_c, cache_index, n_cache_index,
+                         heads, d, scale, out):
+    _check(lib().regione_attn_kvcache(ctx.handle, _p(q), n_q, _p(k_fresh), _p(v_fresh), n_fresh, _p(k_cache), _p(v_cache),
+                                      n_c, _p(cache_index), n_cache_index, heads, d, scale, _p(out)))
+
+
+def regione_linear(ctx, x, w, b, m, n, k, act, out_dtype, y):
+    _check(lib().regione_linear(ctx.handle, _p(x), _p(w), _p(b), m, n, k, act, out_dtype, _p(y)))
+
+
+def regione_block_forward(ctx, weights: BlockWeights, block_type, h_in, h_out, h_dtype, n_fresh, n_txt_fresh,
+                          slot_index, k_cache, v_cache, n_all, flags):
+    _check(lib().regione_block_forward(ctx.handle, C.byref(weights), block_type, _p(h_in), _p(h_out), h_dtype, n_fresh,
+                                       n_txt_fresh, _p(slot_index), _p(k_cache), _p(v_cache), n_all, flags))
+
+
+def regione_velocity_decision_host(t, gamma, n_steps, delta, j, state: AvdState):
+    """t, gamma: sequences of n_steps+1 floats.  Returns (reuse, factor) and updates `state`."""
+    arr_t = (C.c_float * len(t))(*[float(x) for x in t])
+    arr_g = (C.c_float * len(gamma))(*[float(x) for x in gamma])
+    reuse, factor = C.c_int32(0), C.c_float(0.0)
+    _check(lib().regione_velocity_decision_host(arr_t, arr_g, n_steps, delta, j, C.byref(state), C.byref(reuse), C.byref(factor)))
+    return bool(reuse.value), factor.value
+
+
+def regione_velocity_cache(ctx, reuse, factor, dt, v_fresh, c_a, v_out, x_e, n_dev, n_max, c, dtype):
+    _check(lib().regione_velocity_cache(ctx.handle, int(bool(reuse)), factor, dt, _p(v_fresh), _p(c_a), _p(v_out), _p(x_e),
+                                        _p(n_dev), n_max, c, dtype))

@@ -1,0 +1,206 @@
+// Context, error reporting, the host-side decision of the adaptive velocity decay cache
+// (Eq.7, Eq.8) and the composition of one transformer block out of the library's kernels.
+#include "common.h"
+#include <string.h>
+#include <new>
+
+static thread_local char g_last_error[512] = "";
+
+void regione_set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_last_error, sizeof(g_last_error), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char* regione_last_error(void) { return g_last_error; }
+
+namespace {
+template <typename T>
+int dev_alloc(T** p, size_t count) {
+    *p = nullptr;
+    if (count == 0) return REGIONE_OK;
+    RG_HIP(hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T)));
+    return REGIONE_OK;
+}
+void free_all(regione_ctx* c) {
+    void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->attn_part};
+    for (void* p : ptrs) if (p) (void)hipFree(p);
+}
+}  // namespace
+
+extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void* hip_stream) {
+    if (!out || !dims) RG_FAIL(REGIONE_ERR_INVALID_ARG, "create: null argument");
+    *out = nullptr;
+    if (dims->hidden <= 0 || dims->heads <= 0 || dims->head_dim <= 0 || dims->mlp <= 0 || dims->max_fresh < 0 || dims->max_tokens < 0)
+        RG_FAIL(REGIONE_ERR_INVALID_ARG, "create: sizes must be positive");
+    if (dims->hidden != dims->heads * dims->head_dim)
+        RG_FAIL(REGIONE_ERR_BAD_SHAPE, "create: hidden %d != heads %d * head_dim %d", dims->hidden, dims->heads, dims->head_dim);
+    if (dims->head_dim != 64 && dims->head_dim != 128)
+        RG_FAIL(REGIONE_ERR_UNSUPPORTED, "create: head dimension %d (64 or 128 supported)", dims->head_dim);
+    if (dims->hidden % 8 || dims->mlp % 8) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "create: hidden and mlp must be multiples of 8");
+    regione_ctx* c = new (std::nothrow) regione_ctx();
+    if (!c) RG_FAIL(REGIONE_ERR_HIP, "create: out of host memory");
+    memset(c, 0, sizeof(*c));
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->dims = *dims;
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; RG_FAIL(REGIONE_ERR_HIP, "create: no HIP device"); }
+    const size_t n = static_cast<size_t>(dims->max_fresh), H = dims->hidden, M = dims->mlp;
+    c->part_counts_cap = dims->max_tokens / 4 + 8;
+    const size_t split_rows = n < 2048 ? n : 2048;
+    c->attn_part_bytes = static_cast<size_t>(8) * dims->heads * split_rows * (dims->head_dim + 2) * sizeof(float);
+    int rc = dev_alloc(&c->part_counts, static_cast<size_t>(c->part_counts_cap));
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->u, n * H);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->q, n * H);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->kf, n * H);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->vf, n * H);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->a, n * (H + M));
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->h1, n * H);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->m, n * M);
+    if (rc == REGIONE_OK) rc = dev_alloc(reinterpret_cast<char**>(&c->attn_part), c->attn_part_bytes);
+    if (rc != REGIONE_OK) { free_all(c); delete c; return rc; }
+    *out = c;
+    return REGIONE_OK;
+}
+
+extern "C" int regione_destroy(regione_ctx* ctx) {
+    if (!ctx) return REGIONE_OK;
+    (void)hipStreamSynchronize(ctx->stream);
+    free_all(ctx);
+    delete ctx;
+    return REGIONE_OK;
+}
+
+extern "C" int regione_velocity_decision_host(const float* t_host, const float* gamma_host, int32_t n_steps,
+                                              float delta, int32_t j, regione_avd_state* st,
+                                              int32_t* reuse, float* factor) {
+    if (!t_host || !gamma_host || !st || !reuse || !factor) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_decision: null argument");
+    if (n_steps < 1 || j < 1 || j >= n_steps) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_decision: step index %d outside [1, %d)", j, n_steps);
+    // Eq.7: factor of the step at index j relative to the step before it (index j+1)
+    const double d = (1.0 - (static_cast<double>(t_host[j + 1]) - static_cast<double>(t_host[j]))) * static_cast<double>(gamma_host[j]);
+    const double prod = st->prod * d;
+    const double criterion = 1.0 - prod;  // Eq.8, product over the steps after the cached one up to j
+    if (!st->valid || criterion > static_cast<double>(delta)) {
+        st->valid = 1;
+        st->prod = 1.0;
+        *reuse = 0;
+        *factor = 1.0f;
+    } else {
+        st->prod = prod;
+        *reuse = 1;
+        *factor = static_cast<float>(prod);
+    }
+    return REGIONE_OK;
+}
+
+namespace {
+
+int check_stream_weights(const regione_stream_weights& w, int block_type, const char* which) {
+    if (block_type == REGIONE_BLOCK_DOUBLE) {
+        if (!w.w_qkv || !w.w_o || !w.w_1 || !w.w_2) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: null weight in the %s stream", which);
+    } else {
+        if (!w.w_1 || !w.w_2) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: null weight in the %s stream", which);
+    }
+    return REGIONE_OK;
+}
+
+}  // namespace
+
+extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
+                                     const void* h_in, void* h_out, int32_t h_dtype,
+                                     int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index,
+                                     void* k_cache, void* v_cache, int32_t n_all, int32_t flags) {
+    if (!ctx || !w) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: null context or weights");
+    if (block_type != REGIONE_BLOCK_DOUBLE && block_type != REGIONE_BLOCK_SINGLE) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: bad block type %d", block_type);
+    if (h_dtype != REGIONE_BF16 && h_dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: bad h_dtype %d", h_dtype);
+    if (flags & ~(REGIONE_FLAG_STORE | REGIONE_FLAG_RETRIEVE)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: unknown flag bits %d", flags);
+    if (flags == (REGIONE_FLAG_STORE | REGIONE_FLAG_RETRIEVE)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: store and retrieve together are not a mode of the algorithm");
+    if (n_fresh < 0 || n_txt_fresh < 0 || n_txt_fresh > n_fresh) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: n_fresh=%d n_txt_fresh=%d", n_fresh, n_txt_fresh);
+    if (n_fresh > ctx->dims.max_fresh) RG_FAIL(REGIONE_ERR_WORKSPACE, "block_forward: %d rows, context made for %d", n_fresh, ctx->dims.max_fresh);
+    if (flags) {
+        if (n_all <= 0 || n_fresh > n_all) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "block_forward: n_fresh=%d n_all=%d", n_fresh, n_all);
+        if (!k_cache || !v_cache) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: a flag is set but the cache is null");
+        if (n_fresh > 0 && !slot_index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: a flag is set but slot_index is null");
+        if ((flags & REGIONE_FLAG_STORE) && n_fresh != n_all) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "block_forward: a storing forward carries every row (n_fresh=%d, n_all=%d)", n_fresh, n_all);
+    }
+    const bool dbl = block_type == REGIONE_BLOCK_DOUBLE;
+    const int n_txt = dbl ? n_txt_fresh : 0;
+    int rc;
+    if (n_fresh - n_txt > 0 && (rc = check_stream_weights(w->img, block_type, "image")) != REGIONE_OK) return rc;
+    if (n_txt > 0 && (rc = check_stream_weights(w->txt, block_type, "text")) != REGIONE_OK) return rc;
+    if (n_fresh == 0) return REGIONE_OK;
+    if (!h_in || !h_out) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: null hidden state");
+
+    const int H = ctx->dims.hidden, M = ctx->dims.mlp, heads = ctx->dims.heads, D = ctx->dims.head_dim;
+    const int h_f32 = h_dtype == REGIONE_FP32;
+    const size_t h_elem = h_f32 ? 4 : 2;
+    const int lda_attn = dbl ? H : H + M;   // single-stream: attention output and gelu(m) share rows of ctx->a
+    bf16_t* kc = static_cast<bf16_t*>(k_cache);
+    bf16_t* vc = static_cast<bf16_t*>(v_cache);
+    struct Rows { int r0, n; const regione_stream_weights* w; };
+    const Rows groups[2] = {{0, n_txt, &w->txt}, {n_txt, n_fresh - n_txt, &w->img}};
+
+    // ---- first half: LayerNorm + modulation, QKV (and MLP-in for single-stream) projection
+    for (const Rows& g : groups) {
+        if (g.n <= 0) continue;
+        const char* hin = static_cast<const char*>(h_in) + static_cast<size_t>(g.r0) * H * h_elem;
+        bf16_t* u = ctx->u + static_cast<size_t>(g.r0) * H;
+        if ((rc = rg_layernorm_mod(ctx, hin, h_f32, g.n, H, g.w->shift1, g.w->scale1, u)) != REGIONE_OK) return rc;
+        GemmEpilogue ep = {};
+        ep.kind = EPI_QKV; ep.hidden = H;
+        ep.q = ctx->q + static_cast<size_t>(g.r0) * H; ep.ldq = H;
+        if (flags) { ep.k = kc; ep.v = vc; ep.slot = slot_index + g.r0; }
+        else { ep.k = ctx->kf + static_cast<size_t>(g.r0) * H; ep.v = ctx->vf + static_cast<size_t>(g.r0) * H; ep.slot = nullptr; }
+        ep.ldkv = H;
+        if (dbl) {
+            ep.bias = g.w->b_qkv;
+            rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_qkv), H, g.n, 3 * H, H, ep);
+        } else {
+            ep.bias = g.w->b_1; ep.act = REGIONE_ACT_GELU_TANH;
+            ep.y = ctx->a + static_cast<size_t>(g.r0) * lda_attn; ep.ldy = lda_attn; ep.y_col0 = H;
+            rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_1), H, g.n, 3 * H + M, H, ep);
+        }
+        if (rc != REGIONE_OK) return rc;
+    }
+
+    // ---- attention (Eq.6).  With a flag set the fresh K,V already sit in their cache slots, so the
+    // key list is the whole cached sequence; without a flag it is the fresh rows only.
+    if (flags) rc = rg_attention(ctx, ctx->q, H, n_fresh, nullptr, nullptr, H, 0, kc, vc, H, n_all, nullptr, heads, D, 0.f, ctx->a, lda_attn);
+    else rc = rg_attention(ctx, ctx->q, H, n_fresh, ctx->kf, ctx->vf, H, n_fresh, nullptr, nullptr, H, 0, nullptr, heads, D, 0.f, ctx->a, lda_attn);
+    if (rc != REGIONE_OK) return rc;
+
+    // ---- second half
+    for (const Rows& g : groups) {
+        if (g.n <= 0) continue;
+        const char* hin = static_cast<const char*>(h_in) + static_cast<size_t>(g.r0) * H * h_elem;
+        char* hout = static_cast<char*>(h_out) + static_cast<size_t>(g.r0) * H * h_elem;
+        const bf16_t* a = ctx->a + static_cast<size_t>(g.r0) * lda_attn;
+        GemmEpilogue ep = {};
+        ep.kind = EPI_RESID;
+        if (!dbl) {
+            ep.bias = g.w->b_2; ep.gate = g.w->gate1;
+            ep.resid = hin; ep.ldr = H; ep.resid_f32 = h_f32;
+            ep.y = hout; ep.ldy = H; ep.y_f32 = h_f32;
+            if ((rc = rg_gemm(ctx, a, lda_attn, static_cast<const bf16_t*>(g.w->w_2), H + M, g.n, H, H + M, ep)) != REGIONE_OK) return rc;
+            continue;
+        }
+        float* h1 = ctx->h1 + static_cast<size_t>(g.r0) * H;
+        ep.bias = g.w->b_o; ep.gate = g.w->gate1;
+        ep.resid = hin; ep.ldr = H; ep.resid_f32 = h_f32;
+        ep.y = h1; ep.ldy = H; ep.y_f32 = 1;
+        if ((rc = rg_gemm(ctx, a, H, static_cast<const bf16_t*>(g.w->w_o), H, g.n, H, H, ep)) != REGIONE_OK) return rc;
+        bf16_t* u = ctx->u + static_cast<size_t>(g.r0) * H;
+        if ((rc = rg_layernorm_mod(ctx, h1, 1, g.n, H, g.w->shift2, g.w->scale2, u)) != REGIONE_OK) return rc;
+        bf16_t* m = ctx->m + static_cast<size_t>(g.r0) * M;
+        GemmEpilogue up = {};
+        up.kind = EPI_PLAIN; up.bias = g.w->b_1; up.act = REGIONE_ACT_GELU_TANH; up.act_from = 0;
+        up.y = m; up.ldy = M; up.y_f32 = 0;
+        if ((rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_1), H, g.n, M, H, up)) != REGIONE_OK) return rc;
+        GemmEpilogue dn = {};
+        dn.kind = EPI_RESID; dn.bias = g.w->b_2; dn.gate = g.w->gate2;
+        dn.resid = h1; dn.ldr = H; dn.resid_f32 = 1;
+        dn.y = hout; dn.ldy = H; dn.y_f32 = h_f32;
+        if ((rc = rg_gemm(ctx, m, M, static_cast<const bf16_t*>(g.w->w_2), M, g.n, H, M, dn)) != REGIONE_OK) return rc;
+    }
+    return REGIONE_OK;
+}

@@ -1,0 +1,66 @@
+// Shared declarations of the library's translation units (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include "regione.h"
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits in memory
+
+struct regione_ctx {
+    hipStream_t stream;
+    regione_dims dims;
+    int device;
+    // workspace (device)
+    int32_t* part_counts;  // per-block edited counts of the partition
+    int64_t part_counts_cap;
+    bf16_t* u;     // [max_fresh, H]     normalised + modulated rows
+    bf16_t* q;     // [max_fresh, H]
+    bf16_t* kf;    // [max_fresh, H]     fresh keys when the cache is not used
+    bf16_t* vf;    // [max_fresh, H]
+    bf16_t* a;     // [max_fresh, H+M]   attention output (+ activated MLP part, single-stream)
+    float* h1;     // [max_fresh, H]     residual stream between the two halves of a block
+    bf16_t* m;     // [max_fresh, M]     activated MLP hidden rows
+    float* attn_part;  // split-KV partial results
+    size_t attn_part_bytes;
+};
+
+void regione_set_error(const char* fmt, ...);
+#define RG_FAIL(code, ...) do { regione_set_error(__VA_ARGS__); return (code); } while (0)
+#define RG_HIP(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { \
+    regione_set_error("%s failed: %s", #call, hipGetErrorString(e_)); return REGIONE_ERR_HIP; } } while (0)
+#define RG_LAUNCH_CHECK() RG_HIP(hipGetLastError())
+
+static inline bool rg_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- device helpers
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    __bf16 h = static_cast<__bf16>(f);  // round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
+    return __builtin_bit_cast(bf16_t, h);
+}
+
+// ---- internal launchers (each enqueues on ctx->stream and returns an error code)
+enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESID = 2 };
+
+struct GemmEpilogue {
+    int kind;            // EPI_*
+    const float* bias;   // [N] or null
+    int act;             // REGIONE_ACT_* (applied to columns >= act_from)
+    int act_from;
+    // EPI_PLAIN: y[row*ldy + col] (bf16 or f32)
+    void* y; int ldy; int y_f32;
+    // EPI_QKV: columns [0,H) -> q[row*ldq+col]; [H,2H) -> k[slot(row)*ldkv + col-H]; [2H,3H) -> v[...];
+    //          columns >= 3H -> y[row*ldy + y_col0 + col-3H] (single-stream MLP part)
+    bf16_t* q; int ldq; bf16_t* k; bf16_t* v; int ldkv; const int32_t* slot; int hidden; int y_col0;
+    // EPI_RESID: y[row*ldy+col] = resid[row*ldr+col] + gate[col]*(acc+bias)
+    const void* resid; int ldr; int resid_f32; const float* gate;
+};
+
+int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int ldw, int m, int n, int k, const GemmEpilogue& ep);
+int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, bf16_t* u);
+int rg_attention(regione_ctx* ctx, const bf16_t* q, int ldq, int n_q,
+                 const bf16_t* k0, const bf16_t* v0, int ldkv0, int n0,
+                 const bf16_t* k1, const bf16_t* v1, int ldkv1, int n1, const int32_t* idx1,
+                 int heads, int d, float scale, bf16_t* out, int ldo);

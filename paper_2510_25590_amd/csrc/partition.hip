@@ -1,0 +1,215 @@
+// Adaptive region partition: one-step estimate (Eq.5 with t_f = 0), per-token cosine score
+// against the reference latent, threshold, and a deterministic two-kernel compaction of the
+// edited / unedited index lists (Algorithm 1, ARP lines; section "Adaptive Region Partition").
+//
+// Kernel 1 streams x_t, v, x_ref once (16-byte loads, a group of LPT lanes per token), reduces
+// the three sums in float64 inside the lane group, writes score and mask and one edited count
+// per block.  Kernel 2 gives every block the sum of the counts before it and writes the index
+// lists with a ballot/popcount rank; no atomics, so the lists come out in ascending order.
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+template <typename T> struct Vec16;
+template <> struct Vec16<bf16_t> { static constexpr int N = 8; };
+template <> struct Vec16<float> { static constexpr int N = 4; };
+
+template <typename T, int VEC>
+__device__ __forceinline__ void load_chunk(const T* p, float (&out)[VEC]);
+
+template <> __device__ __forceinline__ void load_chunk<bf16_t, 8>(const bf16_t* p, float (&out)[8]) {
+    uint4 r = *reinterpret_cast<const uint4*>(p);
+    uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        out[2 * i] = __uint_as_float(w[i] << 16);
+        out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+template <> __device__ __forceinline__ void load_chunk<float, 4>(const float* p, float (&out)[4]) {
+    float4 r = *reinterpret_cast<const float4*>(p);
+    out[0] = r.x; out[1] = r.y; out[2] = r.z; out[3] = r.w;
+}
+template <> __device__ __forceinline__ void load_chunk<bf16_t, 1>(const bf16_t* p, float (&out)[1]) { out[0] = bf16_to_f32(*p); }
+template <> __device__ __forceinline__ void load_chunk<float, 1>(const float* p, float (&out)[1]) { out[0] = *p; }
+
+__device__ __forceinline__ double shfl_xor_f64(double x, int m) {
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __shfl_xor(lo, m, 64);
+    hi = __shfl_xor(hi, m, 64);
+    return __hiloint2double(hi, lo);
+}
+
+// One block handles tokens [blockIdx.x * tok_per_block, +tok_per_block).
+template <typename T, int VEC, int LPT>
+__global__ void __launch_bounds__(kThreads)
+score_mask_kernel(const T* __restrict__ x_t, const T* __restrict__ v, const T* __restrict__ x_ref,
+                  int64_t n_tokens, int c, int tok_per_block, float sigma, float eta,
+                  float* __restrict__ score, uint8_t* __restrict__ mask, int32_t* __restrict__ counts) {
+    constexpr int TOK_PER_WAVE = 64 / LPT;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane % LPT, tok_in_wave = lane / LPT;
+    const int nchunks = c / VEC;
+    const int64_t block_first = static_cast<int64_t>(blockIdx.x) * tok_per_block;
+    int edited_count = 0;
+    for (int pass = wave * TOK_PER_WAVE; pass < tok_per_block; pass += kWaves * TOK_PER_WAVE) {
+        const int64_t tok = block_first + pass + tok_in_wave;
+        const bool live = (pass + tok_in_wave) < tok_per_block && tok < n_tokens;
+        double dot = 0.0, na = 0.0, nb = 0.0;
+        if (live) {
+            const int64_t base = tok * c;
+            for (int ch = sub; ch < nchunks; ch += LPT) {
+                float a[VEC], b[VEC], r[VEC];
+                load_chunk<T, VEC>(x_t + base + ch * VEC, a);
+                load_chunk<T, VEC>(v + base + ch * VEC, b);
+                load_chunk<T, VEC>(x_ref + base + ch * VEC, r);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    const float est = __fsub_rn(a[i], __fmul_rn(sigma, b[i]));  // two roundings, never an fma
+                    const double e = est, rr = r[i];
+                    dot = fma(e, rr, dot);
+                    na = fma(e, e, na);
+                    nb = fma(rr, rr, nb);
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 1; m < LPT; m <<= 1) {
+            dot += shfl_xor_f64(dot, m);
+            na += shfl_xor_f64(na, m);
+            nb += shfl_xor_f64(nb, m);
+        }
+        bool edited = false;
+        if (live && sub == 0) {
+            const double denom = fmax(sqrt(na) * sqrt(nb), 1e-8);
+            const float s = static_cast<float>(dot / denom);
+            edited = !(s > eta);
+            if (score) score[tok] = s;
+            mask[tok] = edited ? 1 : 0;
+        }
+        edited_count += __popcll(__ballot(edited));
+    }
+    __shared__ int wave_counts[kWaves];
+    if (lane == 0) wave_counts[wave] = edited_count;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int s = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) s += wave_counts[w];
+        counts[blockIdx.x] = s;
+    }
+}
+
+__global__ void __launch_bounds__(kThreads)
+write_index_kernel(const uint8_t* __restrict__ mask, const int32_t* __restrict__ counts,
+                   int64_t n_tokens, int tok_per_block,
+                   int32_t* __restrict__ e_index, int32_t* __restrict__ u_index, int32_t* __restrict__ n_edited) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ int red[kWaves];
+    __shared__ int wave_e[kWaves];
+    // edited tokens in all blocks before this one
+    int part = 0;
+    for (int b = threadIdx.x; b < static_cast<int>(blockIdx.x); b += kThreads) part += counts[b];
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) part += __shfl_xor(part, m, 64);
+    if (lane == 0) red[wave] = part;
+    __syncthreads();
+    int base_e = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) base_e += red[w];
+    const int64_t block_first = static_cast<int64_t>(blockIdx.x) * tok_per_block;
+    int64_t base_u = block_first - base_e;
+    for (int off = 0; off < tok_per_block; off += kThreads) {
+        const int64_t tok = block_first + off + threadIdx.x;
+        const bool live = (off + static_cast<int>(threadIdx.x)) < tok_per_block && tok < n_tokens;
+        const bool ed = live && mask[tok] != 0;
+        const unsigned long long bal = __ballot(ed);
+        const int rank_in_wave = __popcll(bal & ((1ull << lane) - 1ull));
+        __syncthreads();  // wave_e of the previous round has been read
+        if (lane == 0) wave_e[wave] = __popcll(bal);
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) { if (w < wave) before += wave_e[w]; total += wave_e[w]; }
+        const int rank_e = before + rank_in_wave;                      // edited tokens before this one in the round
+        const int pos_in_round = static_cast<int>(threadIdx.x);
+        if (live) {
+            if (ed) e_index[base_e + rank_e] = static_cast<int32_t>(tok);
+            else u_index[base_u + (pos_in_round - rank_e)] = static_cast<int32_t>(tok);
+        }
+        base_e += total;
+        base_u += kThreads - total;   // tail rounds past n_tokens write nothing, so over-counting there is harmless
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *n_edited = base_e;
+}
+
+__global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
+
+template <typename T, int VEC>
+int launch_score(regione_ctx* ctx, int lpt, dim3 grid, const void* x_t, const void* v, const void* x_ref, int64_t n, int c,
+                 int tpb, float sigma, float eta, float* score, uint8_t* mask) {
+    const T* a = static_cast<const T*>(x_t); const T* b = static_cast<const T*>(v); const T* r = static_cast<const T*>(x_ref);
+#define RG_CASE(L) case L: hipLaunchKernelGGL((score_mask_kernel<T, VEC, L>), grid, dim3(kThreads), 0, ctx->stream, \
+        a, b, r, n, c, tpb, sigma, eta, score, mask, ctx->part_counts); break;
+    switch (lpt) { RG_CASE(1) RG_CASE(2) RG_CASE(4) RG_CASE(8) RG_CASE(16) RG_CASE(32) RG_CASE(64)
+        default: RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: bad lane group %d", lpt); }
+#undef RG_CASE
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+}  // namespace
+
+extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* v, const void* x_ref,
+                                 int64_t n_tokens, int32_t c, int32_t dtype, float sigma_t, float eta,
+                                 float* score_opt, uint8_t* mask, int32_t* e_index, int32_t* u_index,
+                                 int32_t* n_edited_dev, int32_t* n_edited_host_opt) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: null context");
+    if (n_tokens < 0 || c <= 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: n_tokens=%lld c=%d", (long long)n_tokens, c);
+    if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: bad dtype %d", dtype);
+    if (!n_edited_dev) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: n_edited_dev is null");
+    if (n_tokens > ctx->dims.max_tokens) RG_FAIL(REGIONE_ERR_WORKSPACE, "partition: %lld tokens, context made for %d", (long long)n_tokens, ctx->dims.max_tokens);
+    if (n_tokens > 0) {
+        if (!x_t || !v || !x_ref || !mask || !e_index || !u_index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: null tensor");
+        if (!rg_aligned16(x_t) || !rg_aligned16(v) || !rg_aligned16(x_ref)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: inputs must be 16-byte aligned");
+    }
+    if (n_tokens == 0) {
+        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, n_edited_dev, 0);
+        RG_LAUNCH_CHECK();
+    } else {
+        const int full_vec = dtype == REGIONE_BF16 ? 8 : 4;
+        const int vec = (c % full_vec == 0) ? full_vec : 1;
+        const int nchunks = c / vec;
+        int lpt = 1;
+        while (lpt * 2 <= nchunks && lpt < 64) lpt *= 2;
+        const int tok_per_pass = kWaves * (64 / lpt);
+        // small inputs: one pass per block so that one image still spreads over many CUs
+        // (the index kernel sums the counts of all earlier blocks, so huge inputs get larger blocks)
+        int passes = 1;
+        while (passes < 32 && (n_tokens / (static_cast<int64_t>(tok_per_pass) * passes * 2)) >= 2048) passes *= 2;
+        const int tpb = tok_per_pass * passes;
+        const int64_t nblocks = (n_tokens + tpb - 1) / tpb;
+        if (nblocks > ctx->part_counts_cap) RG_FAIL(REGIONE_ERR_WORKSPACE, "partition: %lld blocks exceed the workspace", (long long)nblocks);
+        dim3 grid(static_cast<unsigned>(nblocks));
+        int rc;
+        if (dtype == REGIONE_BF16) {
+            rc = vec == 8 ? launch_score<bf16_t, 8>(ctx, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask)
+                          : launch_score<bf16_t, 1>(ctx, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask);
+        } else {
+            rc = vec == 4 ? launch_score<float, 4>(ctx, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask)
+                          : launch_score<float, 1>(ctx, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask);
+        }
+        if (rc != REGIONE_OK) return rc;
+        hipLaunchKernelGGL(write_index_kernel, grid, dim3(kThreads), 0, ctx->stream,
+                           mask, ctx->part_counts, n_tokens, tpb, e_index, u_index, n_edited_dev);
+        RG_LAUNCH_CHECK();
+    }
+    if (n_edited_host_opt) {
+        RG_HIP(hipMemcpyAsync(n_edited_host_opt, n_edited_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+        RG_HIP(hipStreamSynchronize(ctx->stream));
+    }
+    return REGIONE_OK;
+}

@@ -1,0 +1,159 @@
+// Memory-bound row kernels: gather / scatter by index list (Algorithm 1, "X[E_index]" and the
+// merge line), the adaptive velocity decay cache fused with the Euler update (Eq.9, Eq.4), and
+// LayerNorm + modulation of the block.
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// unit = one 16-byte (or ELEM-byte) piece of one row; GATHER: dst[i] = src[index[i]], else dst[index[i]] = src[i]
+template <typename V, bool GATHER>
+__global__ void __launch_bounds__(kThreads)
+rows_by_index_kernel(const V* __restrict__ src, V* __restrict__ dst, const int32_t* __restrict__ index,
+                     const int32_t* __restrict__ n_dev, int64_t n_max, int pieces_per_row) {
+    int64_t n = n_max;
+    if (n_dev) { const int64_t nd = *n_dev; n = nd < n_max ? (nd < 0 ? 0 : nd) : n_max; }
+    const int64_t total = n * pieces_per_row;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t u = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; u < total; u += stride) {
+        const int64_t row = u / pieces_per_row;
+        const int piece = static_cast<int>(u - row * pieces_per_row);
+        const int64_t other = index[row];
+        if (GATHER) dst[row * pieces_per_row + piece] = src[other * pieces_per_row + piece];
+        else dst[other * pieces_per_row + piece] = src[row * pieces_per_row + piece];
+    }
+}
+
+template <bool GATHER>
+int rows_by_index(regione_ctx* ctx, const void* src, void* dst, int32_t row_elems, int32_t dtype,
+                  const int32_t* index, const int32_t* n_dev, int64_t n_max, const char* who) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "%s: null context", who);
+    if (row_elems <= 0 || n_max < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "%s: row_elems=%d n_max=%lld", who, row_elems, (long long)n_max);
+    if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "%s: bad dtype %d", who, dtype);
+    if (n_max == 0) return REGIONE_OK;
+    if (!src || !dst || !index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "%s: null tensor", who);
+    const int64_t row_bytes = static_cast<int64_t>(row_elems) * (dtype == REGIONE_BF16 ? 2 : 4);
+    const bool wide = (row_bytes % 16 == 0) && rg_aligned16(src) && rg_aligned16(dst);
+    const int piece_bytes = wide ? 16 : (dtype == REGIONE_BF16 ? 2 : 4);
+    const int ppr = static_cast<int>(row_bytes / piece_bytes);
+    const int64_t total = n_max * ppr;
+    int64_t blocks = (total + kThreads - 1) / kThreads;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    dim3 grid(static_cast<unsigned>(blocks));
+    if (piece_bytes == 16)
+        hipLaunchKernelGGL((rows_by_index_kernel<uint4, GATHER>), grid, dim3(kThreads), 0, ctx->stream,
+                           static_cast<const uint4*>(src), static_cast<uint4*>(dst), index, n_dev, n_max, ppr);
+    else if (piece_bytes == 4)
+        hipLaunchKernelGGL((rows_by_index_kernel<uint32_t, GATHER>), grid, dim3(kThreads), 0, ctx->stream,
+                           static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst), index, n_dev, n_max, ppr);
+    else
+        hipLaunchKernelGGL((rows_by_index_kernel<uint16_t, GATHER>), grid, dim3(kThreads), 0, ctx->stream,
+                           static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), index, n_dev, n_max, ppr);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+template <typename T> __device__ __forceinline__ float ld(const T* p);
+template <> __device__ __forceinline__ float ld<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <> __device__ __forceinline__ float ld<float>(const float* p) { return *p; }
+template <typename T> __device__ __forceinline__ void st(T* p, float v);
+template <> __device__ __forceinline__ void st<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+template <> __device__ __forceinline__ void st<float>(float* p, float v) { *p = v; }
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+velocity_cache_kernel(int reuse, float factor, float dt, const T* __restrict__ v_fresh, T* __restrict__ c_a,
+                      T* __restrict__ v_out, T* __restrict__ x_e, const int32_t* __restrict__ n_dev, int64_t n_max, int c) {
+    int64_t n = n_max;
+    if (n_dev) { const int64_t nd = *n_dev; n = nd < n_max ? (nd < 0 ? 0 : nd) : n_max; }
+    const int64_t total = n * c;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < total; i += stride) {
+        float vu;
+        if (reuse) {
+            vu = __fmul_rn(factor, ld<T>(c_a + i));
+        } else {
+            vu = ld<T>(v_fresh + i);
+            st<T>(c_a + i, vu);
+        }
+        if (v_out) st<T>(v_out + i, vu);
+        st<T>(x_e + i, __fsub_rn(ld<T>(x_e + i), __fmul_rn(dt, vu)));
+    }
+}
+
+// LayerNorm over H (no affine, biased variance, eps 1e-6) then u = y*(1+scale)+shift.  One wave per row.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+layernorm_mod_kernel(const T* __restrict__ h, int n, int hidden, const float* __restrict__ shift,
+                     const float* __restrict__ scale, bf16_t* __restrict__ u) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (row >= n) return;
+    const T* hr = h + static_cast<int64_t>(row) * hidden;
+    float sum = 0.f;
+    for (int c = lane; c < hidden; c += 64) sum += ld<T>(hr + c);
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 64);
+    const float mean = sum / hidden;
+    float sq = 0.f;
+    for (int c = lane; c < hidden; c += 64) { const float d = ld<T>(hr + c) - mean; sq += d * d; }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) sq += __shfl_xor(sq, m, 64);
+    const float rstd = rsqrtf(sq / hidden + 1e-6f);
+    bf16_t* ur = u + static_cast<int64_t>(row) * hidden;
+    for (int c = lane; c < hidden; c += 64) {
+        float y = (ld<T>(hr + c) - mean) * rstd;
+        const float sc = scale ? scale[c] : 0.f, sh = shift ? shift[c] : 0.f;
+        y = y * (1.f + sc) + sh;
+        ur[c] = f32_to_bf16(y);
+    }
+}
+
+}  // namespace
+
+extern "C" int regione_gather(regione_ctx* ctx, const void* src, int32_t row_elems, int32_t dtype,
+                              const int32_t* index, const int32_t* n_dev, int64_t n_max, void* dst) {
+    return rows_by_index<true>(ctx, src, dst, row_elems, dtype, index, n_dev, n_max, "gather");
+}
+
+extern "C" int regione_scatter(regione_ctx* ctx, void* dst_full, int32_t row_elems, int32_t dtype,
+                               const int32_t* index, const int32_t* n_dev, int64_t n_max, const void* src) {
+    return rows_by_index<false>(ctx, src, dst_full, row_elems, dtype, index, n_dev, n_max, "scatter");
+}
+
+extern "C" int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float factor, float dt,
+                                      const void* v_fresh_opt, void* c_a, void* v_out_opt, void* x_e,
+                                      const int32_t* n_dev, int64_t n_max, int32_t c, int32_t dtype) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_cache: null context");
+    if (c <= 0 || n_max < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_cache: c=%d n_max=%lld", c, (long long)n_max);
+    if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_cache: bad dtype %d", dtype);
+    if (n_max == 0) return REGIONE_OK;
+    if (!c_a || !x_e) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_cache: null c_a or x_e");
+    if (!reuse && !v_fresh_opt) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_cache: a fresh step needs v_fresh");
+    const int64_t total = n_max * c;
+    int64_t blocks = (total + kThreads - 1) / kThreads;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    dim3 grid(static_cast<unsigned>(blocks));
+    if (dtype == REGIONE_BF16)
+        hipLaunchKernelGGL(velocity_cache_kernel<bf16_t>, grid, dim3(kThreads), 0, ctx->stream, reuse, factor, dt,
+                           static_cast<const bf16_t*>(v_fresh_opt), static_cast<bf16_t*>(c_a), static_cast<bf16_t*>(v_out_opt),
+                           static_cast<bf16_t*>(x_e), n_dev, n_max, c);
+    else
+        hipLaunchKernelGGL(velocity_cache_kernel<float>, grid, dim3(kThreads), 0, ctx->stream, reuse, factor, dt,
+                           static_cast<const float*>(v_fresh_opt), static_cast<float*>(c_a), static_cast<float*>(v_out_opt),
+                           static_cast<float*>(x_e), n_dev, n_max, c);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, bf16_t* u) {
+    if (n <= 0) return REGIONE_OK;
+    dim3 grid((n + kThreads / 64 - 1) / (kThreads / 64));
+    if (h_f32)
+        hipLaunchKernelGGL(layernorm_mod_kernel<float>, grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(h), n, hidden, shift, scale, u);
+    else
+        hipLaunchKernelGGL(layernorm_mod_kernel<bf16_t>, grid, dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(h), n, hidden, shift, scale, u);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}

@@ -1,0 +1,75 @@
+"""Helpers for the GPU parity tests: host<->device marshalling and the error measures."""
+import numpy as np
+import torch
+
+from paper_2510_25590_amd import binding as rg
+from paper_2510_25590_amd import inputs
+
+MAX_ABS = 2e-2    # tolerance of the bf16 path against the float64 oracle (both stated by the benchmark spec)
+MEAN_REL = 5e-3
+
+
+def dev(x: np.ndarray, dtype: str):
+    """numpy array (float32 values, already bf16-representable when dtype == 'bf16') -> CUDA tensor."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    return t.cuda()
+
+
+def host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def mean_rel(a: np.ndarray, b: np.ndarray) -> float:
+    """mean |a-b| / mean |b| over the tensor."""
+    return float(np.mean(np.abs(a - b)) / max(np.mean(np.abs(b)), 1e-30))
+
+
+def half_ulp_bf16(x: np.ndarray) -> np.ndarray:
+    """Largest error that storing x as bfloat16 (8 significand bits) can add: half a unit in the last place."""
+    ax = np.maximum(np.abs(np.asarray(x, dtype=np.float64)), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(ax)) - 8)
+
+
+def assert_close(got: np.ndarray, want: np.ndarray, what: str, max_abs=MAX_ABS, mean_rel_tol=MEAN_REL, stored_bf16=False):
+    """|got - want| <= max_abs everywhere and mean|got - want| / mean|want| <= mean_rel_tol.
+    stored_bf16: the output is a bfloat16 tensor whose values may exceed 4 (residual stream, K/V cache); the bound on
+    each element is then max_abs for the arithmetic plus the half ulp that the storage format itself can add
+    (0.0156 in [4, 8), already most of 2e-2)."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values"
+    err = np.abs(got - want)
+    bound = max_abs + (half_ulp_bf16(want) if stored_bf16 else 0.0)
+    ma = float(np.max(err)) if got.size else 0.0
+    mr = mean_rel(got, want) if got.size else 0.0
+    worst = float(np.max(err - bound)) if got.size else -1.0
+    assert worst <= 0 and mr <= mean_rel_tol, f"{what}: max abs {ma:.3e} (tol {max_abs}, exceeded by {worst:.3e}), mean rel {mr:.3e} (tol {mean_rel_tol})"
+    return ma, mr
+
+
+def stream_to_device(w: dict):
+    """Weights dict from inputs.stream_weights (bf16-rounded float32) -> (dict of CUDA tensors, StreamWeights)."""
+    t = {}
+    for name, arr in w.items():
+        if name.startswith("w_"):
+            t[name] = dev(arr, "bf16")
+        else:
+            t[name] = torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).cuda()
+    return t, rg.make_stream_weights(t)
+
+
+def block_to_device(streams, kind):
+    keep = []
+    bw = rg.BlockWeights()
+    if kind == "double":
+        t0, s0 = stream_to_device(streams[0]); t1, s1 = stream_to_device(streams[1])
+        bw.txt, bw.img = s0, s1
+        keep = [t0, t1]
+    else:
+        t1, s1 = stream_to_device(streams[0])
+        bw.img = s1
+        keep = [t1]
+    return bw, keep

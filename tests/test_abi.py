@@ -1,0 +1,58 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and the pure-host entry point (the velocity-cache decision, Eq.7-8) agrees with the oracle."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import regione_oracle as orc
+from paper_2510_25590_amd import binding as rg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "regione.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(regione_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = rg.lib()
+    names = _declared()
+    assert set(names) == set(rg.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_error_paths_without_gpu():
+    lib = rg.lib()
+    assert lib.regione_partition(None, None, None, None, 0, 64, 0, 0.5, 0.9, None, None, None, None, None, None) == rg.ERR_INVALID_ARG
+    assert b"null context" in lib.regione_last_error()
+    assert lib.regione_gather(None, None, 64, 0, None, None, 0, None) == rg.ERR_INVALID_ARG
+    assert lib.regione_destroy(None) == rg.OK
+    st = rg.AvdState(0, 1.0)
+    with pytest.raises(rg.RegionEError):
+        rg.regione_velocity_decision_host([0.0, 1.0], [1.0, 1.0], 1, 0.1, 1, st)   # j outside [1, n_steps)
+    import ctypes as C
+    bad = rg.Dims(256, 4, 32, 1024, 16, 16)
+    h = C.c_void_p()
+    assert lib.regione_create(C.byref(h), C.byref(bad), None) == rg.ERR_BAD_SHAPE
+    bad = rg.Dims(128, 4, 32, 1024, 16, 16)
+    assert lib.regione_create(C.byref(h), C.byref(bad), None) == rg.ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("delta", [0.04, 0.03, 0.08, -1.0, 10.0])
+def test_host_decision_matches_oracle(delta):
+    T = 28
+    t = np.arange(T + 1, dtype=np.float64) / T
+    rng = np.random.default_rng(7)
+    for gamma in (np.ones(T + 1), 1.0 + 0.02 * rng.standard_normal(T + 1)):
+        st_o, st_c = orc.AvdState(), rg.AvdState(0, 1.0)
+        t32, g32 = t.astype(np.float32), gamma.astype(np.float32)
+        for j in range(22, 12, -1):
+            want = orc.avd_decision(t32.astype(np.float64), g32.astype(np.float64), delta, j, st_o)
+            got = rg.regione_velocity_decision_host(t32, g32, T, delta, j, st_c)
+            assert got[0] == want[0]
+            assert got[1] == pytest.approx(want[1], rel=1e-6)

@@ -1,0 +1,195 @@
+"""GPU parity: adaptive region partition, gather/scatter and the velocity cache against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import regione_oracle as orc
+from paper_2510_25590_amd import binding as rg
+from paper_2510_25590_amd import inputs
+from gpu_util import dev, host, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = rg.Context(256, 4, 64, 1024, 64, 1 << 21)
+    yield c
+    c.close()
+
+
+def run_partition(ctx, x_t, v, ref, sigma, eta, dtype):
+    n, c = x_t.shape
+    dx, dv, dr = dev(x_t, dtype), dev(v, dtype), dev(ref, dtype)
+    score = torch.full((max(n, 1),), -7.0, device="cuda")
+    mask = torch.full((max(n, 1),), 9, dtype=torch.uint8, device="cuda")
+    e = torch.full((max(n, 1),), -1, dtype=torch.int32, device="cuda")
+    u = torch.full((max(n, 1),), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    n_e = rg.regione_partition(ctx, dx, dv, dr, n, c, rg.BF16 if dtype == "bf16" else rg.FP32, sigma, eta, score, mask, e, u, cnt)
+    assert n_e == int(cnt.item())
+    return n_e, score.cpu().numpy()[:n], mask.cpu().numpy()[:n], e.cpu().numpy(), u.cpu().numpy()
+
+
+def check_partition(ctx, x_t, v, ref, sigma, eta, dtype):
+    n = x_t.shape[0]
+    s_o, m_o, e_o, u_o = orc.partition(x_t, v, ref, sigma, eta)
+    n_e, s, m, e, u = run_partition(ctx, x_t, v, ref, sigma, eta, dtype)
+    assert n_e == len(e_o)
+    assert np.array_equal(m, m_o)
+    assert np.array_equal(e[:n_e], e_o) and np.array_equal(u[:n - n_e], u_o)
+    assert np.all(e[n_e:] == -1) and np.all(u[n - n_e:] == -1)      # nothing written past the counts
+    assert np.max(np.abs(s - s_o)) <= 2e-7 if n else True
+    return n_e
+
+
+def test_config1_fp32_returns_the_rectangle(ctx):
+    rng = np.random.default_rng(inputs.workload_seed(1))
+    want = inputs.rect_mask(rng, 16, 16, 6, 6)
+    x_t, v, ref = inputs.latents_for_mask(rng, want, 64, 0.7, "f32")
+    assert check_partition(ctx, x_t, v, ref, 0.7, 0.9, "f32") == 36
+
+
+@pytest.mark.parametrize("n_e", [205, 819, 2048, 4096, 0])
+def test_config3_bf16_blob_masks(ctx, n_e):
+    rng = np.random.default_rng(inputs.workload_seed(3, n_e))
+    want = inputs.blob_mask(rng, 64, 64, n_e)
+    x_t, v, ref = inputs.latents_for_mask(rng, want, 64, 0.7, "bf16")
+    assert check_partition(ctx, x_t, v, ref, 0.7, 0.9, "bf16") == n_e
+
+
+@pytest.mark.parametrize("n", [0, 1, 31, 32, 33, 63, 64, 65, 255, 256, 257, 1000])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_ragged_sizes(ctx, n, dtype):
+    rng = np.random.default_rng(100 + n)
+    want = rng.random(n) < 0.37
+    x_t, v, ref = inputs.latents_for_mask(rng, want, 64, 0.6, dtype)
+    check_partition(ctx, x_t, v, ref, 0.6, 0.9, dtype)
+
+
+@pytest.mark.parametrize("c", [8, 16, 48, 128, 512, 1024, 7, 20])
+def test_channel_counts(ctx, c):
+    rng = np.random.default_rng(200 + c)
+    want = rng.random(300) < 0.5
+    for dtype in ("bf16", "f32"):
+        x_t, v, ref = inputs.latents_for_mask(rng, want, c, 0.5, dtype)
+        # low channel counts leave no margin around a 0.9 threshold; use the oracle's own scores to pick a safe eta
+        s = orc.partition(x_t, v, ref, 0.5, 0.0)[0]
+        srt = np.sort(s)
+        gaps = np.diff(srt)
+        k = int(np.argmax(gaps))
+        eta = float((srt[k] + srt[k + 1]) / 2)
+        check_partition(ctx, x_t, v, ref, 0.5, eta, dtype)
+
+
+def test_wave_boundary_patterns(ctx):
+    n = 640
+    rng = np.random.default_rng(300)
+    for pattern in ("none", "all", "lane0", "lane63", "alternate", "one_wave_full"):
+        want = np.zeros(n, dtype=bool)
+        if pattern == "all": want[:] = True
+        if pattern == "lane0": want[::64] = True
+        if pattern == "lane63": want[63::64] = True
+        if pattern == "alternate": want[::2] = True
+        if pattern == "one_wave_full": want[128:192] = True
+        x_t, v, ref = inputs.latents_for_mask(rng, want, 64, 0.7, "bf16")
+        assert check_partition(ctx, x_t, v, ref, 0.7, 0.9, "bf16") == int(want.sum())
+
+
+def test_integer_inputs_decide_exactly_at_the_threshold(ctx):
+    # small integers: every product and sum is exact in both implementations, so scores on the
+    # threshold itself must fall on the same side (== eta -> edited)
+    ref = np.array([[3, 4] + [0] * 6, [3, 4] + [0] * 6, [1, 0] + [0] * 6, [0] * 8], dtype=np.float32)
+    xhat = np.array([[4, 3] + [0] * 6, [3, 4] + [0] * 6, [0, 1] + [0] * 6, [1] * 8], dtype=np.float32)
+    v = np.ones_like(ref)
+    x_t = xhat + 0.5 * v
+    eta = float(np.float32(24.0 / 25.0))
+    for dtype in ("f32", "bf16"):
+        n_e, s, m, e, u = run_partition(ctx, x_t, v, ref, 0.5, eta, dtype)
+        assert s[0] == np.float32(0.96) and m.tolist() == [1, 0, 1, 1]
+        check_partition(ctx, x_t, v, ref, 0.5, eta, dtype)
+
+
+def test_large_batch_of_images(ctx):
+    # 256 images of 64x64 tokens as one token list: several passes per block and many blocks
+    rng = np.random.default_rng(400)
+    n = 256 * 4096
+    want = rng.random(n) < 0.2
+    x_t, v, ref = inputs.latents_for_mask(rng, want, 64, 0.7, "bf16")
+    s_o = orc.cosine_scores(orc.one_step_estimate_f32(x_t, v, 0.7), ref)
+    m_o = orc.threshold_mask(s_o, 0.9)
+    assert np.array_equal(m_o.astype(bool), want)
+    n_e, s, m, e, u = run_partition(ctx, x_t, v, ref, 0.7, 0.9, "bf16")
+    assert n_e == int(want.sum())
+    assert np.array_equal(m, m_o)
+    assert np.array_equal(e[:n_e], np.nonzero(want)[0]) and np.array_equal(u[:n - n_e], np.nonzero(~want)[0])
+
+
+@pytest.mark.parametrize("row_elems,dtype", [(64, "bf16"), (3072, "bf16"), (64, "f32"), (5, "bf16"), (3, "f32"), (12, "bf16")])
+def test_gather_scatter_bit_exact(ctx, row_elems, dtype):
+    rng = np.random.default_rng(500 + row_elems)
+    n = 777
+    x = inputs.bf16_round(rng.standard_normal((n, row_elems)).astype(np.float32)) if dtype == "bf16" else rng.standard_normal((n, row_elems)).astype(np.float32)
+    mask = rng.random(n) < 0.3
+    e_o, u_o = orc.compact(mask.astype(np.uint8))
+    code = rg.BF16 if dtype == "bf16" else rg.FP32
+    dx = dev(x, dtype)
+    idx = torch.from_numpy(np.concatenate([e_o, -np.ones(n - len(e_o), dtype=np.int32)])).cuda()   # tail must never be read
+    cnt = torch.tensor([len(e_o)], dtype=torch.int32, device="cuda")
+    g = torch.zeros((n, row_elems), dtype=dx.dtype, device="cuda")
+    rg.regione_gather(ctx, dx, row_elems, code, idx, cnt, n, g)
+    assert np.array_equal(host(g)[:len(e_o)], orc.gather(x, e_o))
+    assert np.all(host(g)[len(e_o):] == 0)
+    # scatter(gather(x)) leaves the unedited rows bit-identical, edited rows take the new values
+    y = dx.clone()
+    new = (g.float() + 1.0).to(dx.dtype)
+    rg.regione_scatter(ctx, y, row_elems, code, idx, cnt, n, new)
+    want = orc.scatter(x.copy(), e_o, host(new)[:len(e_o)])
+    bits = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(y.view(bits)[~torch.from_numpy(mask).cuda()], dx.view(bits)[~torch.from_numpy(mask).cuda()])
+    assert np.array_equal(host(y), want)
+    # host-side count (n_dev null) and identity / permutation index
+    perm = torch.from_numpy(rng.permutation(n).astype(np.int32)).cuda()
+    g2 = torch.empty_like(dx)
+    rg.regione_gather(ctx, dx, row_elems, code, perm, None, n, g2)
+    z = torch.zeros_like(dx)
+    rg.regione_scatter(ctx, z, row_elems, code, perm, None, n, g2)
+    assert torch.equal(z.view(bits), dx.view(bits))
+    # empty list is a no-op
+    zero = torch.zeros(1, dtype=torch.int32, device="cuda")
+    before = y.clone()
+    rg.regione_scatter(ctx, y, row_elems, code, idx, zero, n, new)
+    assert torch.equal(before.view(bits), y.view(bits))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_velocity_cache_matches_oracle(ctx, dtype):
+    rng = np.random.default_rng(600)
+    n, c = 819, 64
+    rnd = (lambda a: inputs.bf16_round(a)) if dtype == "bf16" else (lambda a: a)
+    v = rnd(rng.standard_normal((n, c)).astype(np.float32))
+    ca0 = rnd(rng.standard_normal((n, c)).astype(np.float32))
+    x = rnd(rng.standard_normal((n, c)).astype(np.float32))
+    code = rg.BF16 if dtype == "bf16" else rg.FP32
+    sb = dtype == "bf16"
+    tol = dict(max_abs=2e-2, stored_bf16=True) if sb else dict(max_abs=1e-6, mean_rel_tol=1e-6)
+    cnt = torch.tensor([n - 19], dtype=torch.int32, device="cuda")
+    live = n - 19
+    # fresh step
+    dca, dx, dvo = dev(ca0, dtype), dev(x, dtype), dev(np.zeros((n, c), np.float32), dtype)
+    rg.regione_velocity_cache(ctx, False, 1.0, 1 / 28, dev(v, dtype), dca, dvo, dx, cnt, n, c, code)
+    vu, cn, xn = orc.velocity_cache_apply(False, 1.0, 1 / 28, v[:live], ca0[:live], x[:live])
+    assert np.array_equal(host(dca)[:live], v[:live]) and np.array_equal(host(dca)[live:], ca0[live:])
+    assert np.array_equal(host(dvo)[:live], v[:live])
+    assert_close(host(dx)[:live], xn, "x after a fresh step", **tol)
+    assert np.array_equal(host(dx)[live:], x[live:])
+    # reuse step
+    dca, dx = dev(ca0, dtype), dev(x, dtype)
+    f = float(np.float32((27 / 28) ** 2))
+    rg.regione_velocity_cache(ctx, True, f, 1 / 28, None, dca, dvo, dx, cnt, n, c, code)
+    vu, cn, xn = orc.velocity_cache_apply(True, f, 1 / 28, None, ca0[:live], x[:live])
+    assert np.array_equal(host(dca), ca0)
+    assert_close(host(dvo)[:live], vu, "reused velocity", **tol)
+    assert_close(host(dx)[:live], xn, "x after a reuse step", **tol)
+    with pytest.raises(rg.RegionEError):
+        rg.regione_velocity_cache(ctx, False, 1.0, 0.1, None, dca, None, dx, cnt, n, c, code)
