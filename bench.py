@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the RegionE region-aware step on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic image: adaptive region
+partition, gather of the edited tokens, one 3072-wide double-stream transformer block on
+them with attention over the Region-Instruction KV cache, the velocity head, the velocity
+cache + Euler update and the scatter back.  Inputs are resident in HBM before the timed
+region.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def cpu_baseline(cfg, hst, reps):
+    """The oracle as it stands, timed on the host cores: the same step on the same inputs."""
+    from oracle import step_reference as ref
+    kc, vc = ref.build_cache(hst["streams"], cfg.kind, hst["h_store"], cfg.n_txt, cfg.heads)   # setup, like the GPU's cache fill
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        out = ref.region_step(hst["x_t"], hst["v_prev"], hst["x_ref"], hst["h_now"], hst["streams"], cfg.kind, hst["w_head"],
+                              hst["b_head"], kc, vc, cfg.n_txt, cfg.heads, cfg.sigma, cfg.eta, cfg.dt)
+    dt = (time.perf_counter() - t0) / reps
+    n = len(out["e_index"])
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    return {"value": n / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"the whole workload ({n} edited tokens), {reps} step(s) of the numpy float64 oracle, {dt:.2f} s per step"}
+
+
+def membound(torch, rg):
+    """HBM-bound kernels on a working set far larger than the 256 MB Infinity Cache (a batch of images as one token list)."""
+    res = {}
+    n_tok, c = 2048 * 4096, 64                      # 2048 images of 64x64 tokens: 3 x 1 GiB of bf16 latents
+    ctx = rg.Context(256, 4, 64, 1024, 16, n_tok)
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    ref = torch.randn((n_tok, c), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    noise = torch.randn((n_tok, c), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    edited = (torch.rand(n_tok, generator=g, device="cuda") < 0.2).to(torch.bfloat16).unsqueeze(1)
+    x_t = (0.3 * (ref.float() + edited.float() * noise.float())).to(torch.bfloat16)   # sigma 0.7, v = -x0  =>  x0_hat = x0
+    v = (-(ref.float() + edited.float() * noise.float())).to(torch.bfloat16)
+    del noise, edited
+    score = torch.empty(n_tok, dtype=torch.float32, device="cuda")
+    mask = torch.empty(n_tok, dtype=torch.uint8, device="cuda")
+    e_idx = torch.empty(n_tok, dtype=torch.int32, device="cuda"); u_idx = torch.empty_like(e_idx)
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for _ in range(2):
+        n_e = rg.regione_partition(ctx, x_t, v, ref, n_tok, c, rg.BF16, 0.7, 0.9, score, mask, e_idx, u_idx, cnt)
+    rg.regione_profile_enable(ctx, True)
+    reps = 5
+    for _ in range(reps):
+        rg.regione_partition(ctx, x_t, v, ref, n_tok, c, rg.BF16, 0.7, 0.9, score, mask, e_idx, u_idx, cnt, read_count=False)
+    ms = rg.regione_profile_read(ctx)["partition"][0] / reps
+    nbytes = n_tok * (3 * c * 2 + 4 + 1 + 4)        # three latents in; score, mask, one index out
+    res["partition"] = {"tokens": n_tok, "edited": n_e, "ms": ms, "GB/s": nbytes / ms / 1e6, "frac_hbm": nbytes / ms / 1e6 / PEAK_HBM_GBS}
+    # gather / scatter of 128-byte latent rows through the index list just built
+    dst = torch.empty((n_e, c), dtype=torch.bfloat16, device="cuda")
+    for name, fn in (("gather_latent", lambda: rg.regione_gather(ctx, x_t, c, rg.BF16, e_idx, cnt, n_e, dst)),
+                     ("scatter_latent", lambda: rg.regione_scatter(ctx, x_t, c, rg.BF16, e_idx, cnt, n_e, dst))):
+        fn(); rg.regione_profile_read(ctx)
+        for _ in range(reps):
+            fn()
+        ms = rg.regione_profile_read(ctx)["rows"][0] / reps
+        nb = n_e * (2 * c * 2 + 4)
+        res[name] = {"rows": n_e, "row_bytes": 2 * c, "ms": ms, "GB/s": nb / ms / 1e6, "frac_hbm": nb / ms / 1e6 / PEAK_HBM_GBS}
+    del x_t, v, ref, score, mask, dst
+    # gather / scatter of 6 KiB hidden rows: 20 % of 256 images' tokens
+    hidden = 3072
+    n_rows_full = 256 * 4096
+    src = torch.empty((n_rows_full, hidden), dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    n_h = int((e_idx[:n_e] < n_rows_full).sum().item())
+    dst = torch.empty((n_h, hidden), dtype=torch.bfloat16, device="cuda")
+    for name, fn in (("gather_hidden", lambda: rg.regione_gather(ctx, src, hidden, rg.BF16, e_idx, None, n_h, dst)),
+                     ("scatter_hidden", lambda: rg.regione_scatter(ctx, src, hidden, rg.BF16, e_idx, None, n_h, dst))):
+        fn(); rg.regione_profile_read(ctx)
+        for _ in range(reps):
+            fn()
+        ms = rg.regione_profile_read(ctx)["rows"][0] / reps
+        nb = n_h * (2 * hidden * 2 + 4)
+        res[name] = {"rows": n_h, "row_bytes": 2 * hidden, "ms": ms, "GB/s": nb / ms / 1e6, "frac_hbm": nb / ms / 1e6 / PEAK_HBM_GBS}
+    ctx.close()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-membound", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="time the steps without the per-kernel event pairs")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); run it with --gpus 1")
+
+    import torch
+    from paper_2510_25590_amd import binding as rg
+    from paper_2510_25590_amd import step
+
+    rg.lib()   # fails loudly if the HIP library has not been built
+    cfg = step.CONFIG_BLOCK
+    wl = step.RegionStepWorkload(cfg)
+    for _ in range(args.warmup):
+        n = wl.step()
+    torch.cuda.synchronize()
+    rg.regione_profile_enable(wl.ctx, not args.no_profile)
+    rg.regione_profile_read(wl.ctx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        n = wl.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = rg.regione_profile_read(wl.ctx)
+    rg.regione_profile_enable(wl.ctx, False)
+    ms_per_step = elapsed * 1e3 / args.steps
+    gemm_flops, attn_flops = wl.flops(n)
+    kernels = {k: {"ms_per_step": v[0] / args.steps, "launch_groups_per_step": v[1] / args.steps} for k, v in prof.items()}
+    out = {
+        "metric": "edited-token DiT block tokens/s", "value": n / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "n_edited": n, "keys_per_query": wl.n_all},
+    }
+    if not args.no_profile and prof["gemm"][1] > 0:
+        g_ms = prof["gemm"][0] / args.steps
+        a_ms = prof["attention"][0] / args.steps
+        ach = gemm_flops / (g_ms * 1e-3) / 1e12
+        out["roofline"] = {"kernel": "gemm_bf16_kernel (5 launches per step: QKV, attention output, MLP up, MLP down, velocity head)",
+                           "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                           "traffic": None, "avg_launch_ms": prof["gemm"][0] / max(prof["gemm"][1], 1)}
+        out["attention"] = {"achieved": attn_flops / (a_ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+                            "frac": attn_flops / (a_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "ms_per_step": a_ms}
+        out["gemm_plus_attention_tflops"] = (gemm_flops + attn_flops) / ((g_ms + a_ms) * 1e-3) / 1e12
+        out["kernels"] = kernels
+    host = wl.host
+    wl.close()
+    del wl
+    torch.cuda.empty_cache()
+    if not args.no_membound:
+        out["membound"] = membound(torch, rg)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, host, reps=2)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

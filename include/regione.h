@@ -151,11 +151,12 @@ int regione_linear(regione_ctx* ctx, const void* x, const void* w, const float* 
  * regione_stream_weights.
  *   h_in, h_out : [n_fresh, H] of h_dtype (the residual stream; may be the same buffer).
  *   n_txt_fresh : rows [0, n_txt_fresh) use w->txt, the rest w->img (double-stream only).
- *   slot_index  : [n_fresh] int32, position of each fresh row in the cached sequence;
- *                 needed when a flag is set.
+ *   slot_index, slot_offset : fresh row i sits at position slot_index[i] + slot_offset of the
+ *                 cached sequence (e.g. E_index and the number of text tokens); slot_index is
+ *                 [n_fresh] int32 and is needed when a flag is set.
  *   k_cache, v_cache : [n_all, heads, head_dim] bf16, the layer's C_KV.
  *   flags = REGIONE_FLAG_STORE    : full forward; n_fresh must equal n_all; the fresh K,V
- *                                   are written to the cache rows slot_index.
+ *                                   are written to their cache rows.
  *   flags = REGIONE_FLAG_RETRIEVE : Eq.6; keys/values are the fresh rows plus every cache
  *                                   row that is not refreshed.  The fresh K,V overwrite
  *                                   their own slots in the cache (those slots are never
@@ -164,7 +165,7 @@ int regione_linear(regione_ctx* ctx, const void* x, const void* w, const float* 
  *   both flags                    : REGIONE_ERR_INVALID_ARG. */
 int regione_block_forward(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
                           const void* h_in, void* h_out, int32_t h_dtype,
-                          int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index,
+                          int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
                           void* k_cache, void* v_cache, int32_t n_all, int32_t flags);
 
 /* Adaptive velocity decay cache, host decision (Eq.7, Eq.8): pure function of the
@@ -185,6 +186,16 @@ int regione_velocity_decision_host(const float* t_host, const float* gamma_host,
 int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float factor, float dt,
                            const void* v_fresh_opt, void* c_a, void* v_out_opt, void* x_e,
                            const int32_t* n_dev, int64_t n_max, int32_t c, int32_t dtype);
+
+/* Per-kernel-class timing for benchmarks (not part of the method).  While enabled, every
+ * kernel launch group of the context is bracketed by a HIP event pair on its stream (at most
+ * 8192 pairs between two reads).  regione_profile_read waits for the stream, adds the elapsed
+ * milliseconds and the number of launch groups of each class into the two host arrays of
+ * n_classes entries (index = REGIONE_PROF_*), and clears the recorded pairs. */
+enum { REGIONE_PROF_PARTITION = 0, REGIONE_PROF_ROWS = 1, REGIONE_PROF_LAYERNORM = 2, REGIONE_PROF_GEMM = 3,
+       REGIONE_PROF_ATTENTION = 4, REGIONE_PROF_VELOCITY = 5, REGIONE_PROF_CLASSES = 6 };
+int regione_profile_enable(regione_ctx* ctx, int32_t on);
+int regione_profile_read(regione_ctx* ctx, double* total_ms_host, int64_t* launches_host, int32_t n_classes);
 
 #ifdef __cplusplus
 }

@@ -23,8 +23,9 @@ ACT_NONE, ACT_GELU_TANH = 0, 1
 EXPORTS = (
     "regione_last_error", "regione_create", "regione_destroy", "regione_partition", "regione_gather",
     "regione_scatter", "regione_attn_kvcache", "regione_linear", "regione_block_forward",
-    "regione_velocity_decision_host", "regione_velocity_cache",
+    "regione_velocity_decision_host", "regione_velocity_cache", "regione_profile_enable", "regione_profile_read",
 )
+PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
 
 
 class Dims(C.Structure):
@@ -73,10 +74,12 @@ def lib() -> C.CDLL:
             "regione_scatter": [vp, vp, i32, i32, vp, vp, i64, vp],
             "regione_attn_kvcache": [vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, i32, i32, i32, f32, vp],
             "regione_linear": [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
-            "regione_block_forward": [vp, C.POINTER(BlockWeights), i32, vp, vp, i32, i32, i32, vp, vp, vp, i32, i32],
+            "regione_block_forward": [vp, C.POINTER(BlockWeights), i32, vp, vp, i32, i32, i32, vp, i32, vp, vp, i32, i32],
             "regione_velocity_decision_host": [C.POINTER(f32), C.POINTER(f32), i32, f32, i32, C.POINTER(AvdState),
                                                C.POINTER(i32), C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
+            "regione_profile_enable": [vp, i32],
+            "regione_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(i64), i32],
         }
         for name, args in sig.items():
             fn = getattr(_lib, name)
@@ -160,9 +163,9 @@ def regione_linear(ctx, x, w, b, m, n, k, act, out_dtype, y):
 
 
 def regione_block_forward(ctx, weights: BlockWeights, block_type, h_in, h_out, h_dtype, n_fresh, n_txt_fresh,
-                          slot_index, k_cache, v_cache, n_all, flags):
+                          slot_index, slot_offset, k_cache, v_cache, n_all, flags):
     _check(lib().regione_block_forward(ctx.handle, C.byref(weights), block_type, _p(h_in), _p(h_out), h_dtype, n_fresh,
-                                       n_txt_fresh, _p(slot_index), _p(k_cache), _p(v_cache), n_all, flags))
+                                       n_txt_fresh, _p(slot_index), slot_offset, _p(k_cache), _p(v_cache), n_all, flags))
 
 
 def regione_velocity_decision_host(t, gamma, n_steps, delta, j, state: AvdState):
@@ -177,3 +180,16 @@ def regione_velocity_decision_host(t, gamma, n_steps, delta, j, state: AvdState)
 def regione_velocity_cache(ctx, reuse, factor, dt, v_fresh, c_a, v_out, x_e, n_dev, n_max, c, dtype):
     _check(lib().regione_velocity_cache(ctx.handle, int(bool(reuse)), factor, dt, _p(v_fresh), _p(c_a), _p(v_out), _p(x_e),
                                         _p(n_dev), n_max, c, dtype))
+
+
+def regione_profile_enable(ctx, on: bool):
+    _check(lib().regione_profile_enable(ctx.handle, int(bool(on))))
+
+
+def regione_profile_read(ctx):
+    """Returns {class name: (total milliseconds, launch groups)} since the last read."""
+    n = len(PROF_NAMES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(lib().regione_profile_read(ctx.handle, ms, cnt, n))
+    return {name: (ms[i], cnt[i]) for i, name in enumerate(PROF_NAMES)}

@@ -26,6 +26,11 @@ int dev_alloc(T** p, size_t count) {
 void free_all(regione_ctx* c) {
     void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->attn_part};
     for (void* p : ptrs) if (p) (void)hipFree(p);
+    if (c->prof_ev) {
+        for (int i = 0; i < 2 * c->prof_cap; ++i) if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
+        delete[] c->prof_ev;
+    }
+    delete[] c->prof_class;
 }
 }  // namespace
 
@@ -71,6 +76,33 @@ extern "C" int regione_destroy(regione_ctx* ctx) {
     return REGIONE_OK;
 }
 
+extern "C" int regione_profile_enable(regione_ctx* ctx, int32_t on) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "profile_enable: null context");
+    if (on && !ctx->prof_ev) {
+        ctx->prof_cap = 8192;
+        ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * ctx->prof_cap]();
+        ctx->prof_class = new (std::nothrow) int[ctx->prof_cap]();
+        if (!ctx->prof_ev || !ctx->prof_class) RG_FAIL(REGIONE_ERR_HIP, "profile_enable: out of host memory");
+        for (int i = 0; i < 2 * ctx->prof_cap; ++i) RG_HIP(hipEventCreate(&ctx->prof_ev[i]));
+    }
+    ctx->prof_on = on ? 1 : 0;
+    return REGIONE_OK;
+}
+
+extern "C" int regione_profile_read(regione_ctx* ctx, double* total_ms_host, int64_t* launches_host, int32_t n_classes) {
+    if (!ctx || !total_ms_host || !launches_host || n_classes <= 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "profile_read: null argument");
+    for (int i = 0; i < n_classes; ++i) { total_ms_host[i] = 0.0; launches_host[i] = 0; }
+    RG_HIP(hipStreamSynchronize(ctx->stream));
+    for (int s = 0; s < ctx->prof_used; ++s) {
+        float ms = 0.f;
+        RG_HIP(hipEventElapsedTime(&ms, ctx->prof_ev[2 * s], ctx->prof_ev[2 * s + 1]));
+        const int k = ctx->prof_class[s];
+        if (k >= 0 && k < n_classes) { total_ms_host[k] += ms; launches_host[k] += 1; }
+    }
+    ctx->prof_used = 0;
+    return REGIONE_OK;
+}
+
 extern "C" int regione_velocity_decision_host(const float* t_host, const float* gamma_host, int32_t n_steps,
                                               float delta, int32_t j, regione_avd_state* st,
                                               int32_t* reuse, float* factor) {
@@ -108,7 +140,7 @@ int check_stream_weights(const regione_stream_weights& w, int block_type, const 
 
 extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
                                      const void* h_in, void* h_out, int32_t h_dtype,
-                                     int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index,
+                                     int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
                                      void* k_cache, void* v_cache, int32_t n_all, int32_t flags) {
     if (!ctx || !w) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: null context or weights");
     if (block_type != REGIONE_BLOCK_DOUBLE && block_type != REGIONE_BLOCK_SINGLE) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: bad block type %d", block_type);
@@ -149,7 +181,7 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
         GemmEpilogue ep = {};
         ep.kind = EPI_QKV; ep.hidden = H;
         ep.q = ctx->q + static_cast<size_t>(g.r0) * H; ep.ldq = H;
-        if (flags) { ep.k = kc; ep.v = vc; ep.slot = slot_index + g.r0; }
+        if (flags) { ep.k = kc; ep.v = vc; ep.slot = slot_index + g.r0; ep.slot_offset = slot_offset; }
         else { ep.k = ctx->kf + static_cast<size_t>(g.r0) * H; ep.v = ctx->vf + static_cast<size_t>(g.r0) * H; ep.slot = nullptr; }
         ep.ldkv = H;
         if (dbl) {

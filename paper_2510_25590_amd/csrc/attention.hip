@@ -50,42 +50,41 @@ template <int D> struct Swz {
     }
 };
 
+// Global -> register -> LDS staging of one 64-key tile.  Thread t owns 16-byte chunk t%CPR of rows t/CPR + i*(256/CPR).
 template <int D>
-struct KvLoader {
-    static constexpr int CPR = D / 8;
-    static constexpr int PER_THREAD = KT * CPR / kThreads;  // 4 (D=128) or 2 (D=64)
-    uint4 kr[PER_THREAD], vr[PER_THREAD];
-    __device__ __forceinline__ void load(const AttnArgs& a, int head, int key0, int n_keys) {
+__device__ __forceinline__ void kv_tile_load(const AttnArgs& a, int head, int key0, int n_keys,
+                                             uint4 (&kr)[KT * (D / 8) / kThreads], uint4 (&vr)[KT * (D / 8) / kThreads]) {
+    constexpr int CPR = D / 8;
+    constexpr int PER_THREAD = KT * CPR / kThreads;
+    const int r0 = threadIdx.x / CPR, c = threadIdx.x % CPR;
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int idx = threadIdx.x + i * kThreads;
-            const int r = idx / CPR, c = idx % CPR;
-            int key = key0 + r;
-            key = key < n_keys ? key : n_keys - 1;  // tail rows repeat a valid row; their scores are masked
-            const bf16_t *kp, *vp;
-            if (key < a.n0) {
-                const int64_t off = static_cast<int64_t>(key) * a.ldkv0 + head * D + c * 8;
-                kp = a.k0 + off; vp = a.v0 + off;
-            } else {
-                int64_t row = key - a.n0;
-                if (a.idx1) row = a.idx1[row];
-                const int64_t off = row * a.ldkv1 + head * D + c * 8;
-                kp = a.k1 + off; vp = a.v1 + off;
-            }
-            kr[i] = *reinterpret_cast<const uint4*>(kp);
-            vr[i] = *reinterpret_cast<const uint4*>(vp);
-        }
+    for (int i = 0; i < PER_THREAD; ++i) {
+        int key = key0 + r0 + i * (kThreads / CPR);
+        key = key < n_keys ? key : n_keys - 1;  // tail rows repeat a valid row; their scores are masked
+        const bool fresh = key < a.n0;
+        int64_t row = fresh ? key : key - a.n0;
+        if (!fresh && a.idx1) row = a.idx1[row];
+        const int64_t off = row * (fresh ? a.ldkv0 : a.ldkv1) + head * D + c * 8;
+        const bf16_t* kb = fresh ? a.k0 : a.k1;
+        const bf16_t* vb = fresh ? a.v0 : a.v1;
+        kr[i] = *reinterpret_cast<const uint4*>(kb + off);
+        vr[i] = *reinterpret_cast<const uint4*>(vb + off);
     }
-    __device__ __forceinline__ void store(bf16_t* k_lds, bf16_t* v_lds) const {
+}
+
+template <int D>
+__device__ __forceinline__ void kv_tile_store(bf16_t* k_lds, bf16_t* v_lds,
+                                              const uint4 (&kr)[KT * (D / 8) / kThreads], const uint4 (&vr)[KT * (D / 8) / kThreads]) {
+    constexpr int CPR = D / 8;
+    constexpr int PER_THREAD = KT * CPR / kThreads;
+    const int r0 = threadIdx.x / CPR, c = threadIdx.x % CPR;
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int idx = threadIdx.x + i * kThreads;
-            const int r = idx / CPR, c = idx % CPR;
-            *reinterpret_cast<uint4*>(k_lds + r * D + (Swz<D>::k(r, c) << 3)) = kr[i];
-            *reinterpret_cast<uint4*>(v_lds + r * D + (Swz<D>::v(r, c) << 3)) = vr[i];
-        }
+    for (int i = 0; i < PER_THREAD; ++i) {
+        const int r = r0 + i * (kThreads / CPR);
+        *reinterpret_cast<uint4*>(k_lds + r * D + (Swz<D>::k(r, c) << 3)) = kr[i];
+        *reinterpret_cast<uint4*>(v_lds + r * D + (Swz<D>::v(r, c) << 3)) = vr[i];
     }
-};
+}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -131,16 +130,18 @@ attn_kvcache_kernel(AttnArgs a) {
             for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
     }
 
-    KvLoader<D> ld;
+    constexpr int LD_N = KT * (D / 8) / kThreads;
+    uint4 kr[LD_N], vr[LD_N];
     if (tile_begin < tile_end) {
-        ld.load(a, head, tile_begin * KT, n_keys);
-        ld.store(k_lds[0], v_lds[0]);
+        kv_tile_load<D>(a, head, tile_begin * KT, n_keys, kr, vr);
+        kv_tile_store<D>(k_lds[0], v_lds[0], kr, vr);
     }
     __syncthreads();
 
     for (int t = tile_begin; t < tile_end; ++t) {
         const int cur = (t - tile_begin) & 1;
-        if (t + 1 < tile_end) ld.load(a, head, (t + 1) * KT, n_keys);
+        // the last iteration re-loads its own tile into the idle buffer: unconditional code keeps the staging registers in VGPRs
+        kv_tile_load<D>(a, head, (t + 1 < tile_end ? t + 1 : t) * KT, n_keys, kr, vr);
         const bf16_t* kt = k_lds[cur];
         const bf16_t* vt = v_lds[cur];
 
@@ -230,7 +231,7 @@ attn_kvcache_kernel(AttnArgs a) {
                 }
             }
 
-        if (t + 1 < tile_end) ld.store(k_lds[cur ^ 1], v_lds[cur ^ 1]);
+        kv_tile_store<D>(k_lds[cur ^ 1], v_lds[cur ^ 1], kr, vr);
         __syncthreads();
     }
 
@@ -343,6 +344,7 @@ int rg_attention(regione_ctx* ctx, const bf16_t* q, int ldq, int n_q,
     if (d != 64 && d != 128) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "attention: head dimension %d (64 or 128 supported)", d);
     if ((ldq & 7) || (ldo & 3) || (n0 > 0 && (ldkv0 & 7)) || (n1 > 0 && (ldkv1 & 7)))
         RG_FAIL(REGIONE_ERR_BAD_SHAPE, "attention: row strides must keep 16-byte alignment");
+    ProfScope prof(ctx, REGIONE_PROF_ATTENTION);
     AttnArgs a = {};
     a.q = q; a.ldq = ldq; a.n_q = n_q;
     a.k0 = k0; a.v0 = v0; a.ldkv0 = ldkv0; a.n0 = n0;

@@ -24,6 +24,25 @@ struct regione_ctx {
     bf16_t* m;     // [max_fresh, M]     activated MLP hidden rows
     float* attn_part;  // split-KV partial results
     size_t attn_part_bytes;
+    // optional per-kernel-class timing with HIP events on the context's stream
+    int prof_on;
+    int prof_used;
+    int prof_cap;
+    hipEvent_t* prof_ev;   // 2 * prof_cap events: start/stop pairs
+    int* prof_class;       // class of each pair
+};
+
+// Brackets the launches of one kernel class with an event pair when profiling is on.
+struct ProfScope {
+    regione_ctx* c; int slot;
+    ProfScope(regione_ctx* ctx, int kernel_class) : c(ctx), slot(-1) {
+        if (c && c->prof_on && c->prof_used < c->prof_cap) {
+            slot = c->prof_used++;
+            c->prof_class[slot] = kernel_class;
+            (void)hipEventRecord(c->prof_ev[2 * slot], c->stream);
+        }
+    }
+    ~ProfScope() { if (slot >= 0) (void)hipEventRecord(c->prof_ev[2 * slot + 1], c->stream); }
 };
 
 void regione_set_error(const char* fmt, ...);
@@ -53,7 +72,7 @@ struct GemmEpilogue {
     void* y; int ldy; int y_f32;
     // EPI_QKV: columns [0,H) -> q[row*ldq+col]; [H,2H) -> k[slot(row)*ldkv + col-H]; [2H,3H) -> v[...];
     //          columns >= 3H -> y[row*ldy + y_col0 + col-3H] (single-stream MLP part)
-    bf16_t* q; int ldq; bf16_t* k; bf16_t* v; int ldkv; const int32_t* slot; int hidden; int y_col0;
+    bf16_t* q; int ldq; bf16_t* k; bf16_t* v; int ldkv; const int32_t* slot; int slot_offset; int hidden; int y_col0;
     // EPI_RESID: y[row*ldy+col] = resid[row*ldr+col] + gate[col]*(acc+bias)
     const void* resid; int ldr; int resid_f32; const float* gate;
 };

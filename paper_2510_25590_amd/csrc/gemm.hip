@@ -40,7 +40,7 @@ __device__ __forceinline__ void epilogue_store(const GemmEpilogue& ep, int row, 
         if (col < H) {
             ep.q[static_cast<int64_t>(row) * ep.ldq + col] = f32_to_bf16(val);
         } else if (col < 3 * H) {
-            const int64_t r = ep.slot ? ep.slot[row] : row;
+            const int64_t r = ep.slot ? static_cast<int64_t>(ep.slot[row]) + ep.slot_offset : row;
             if (col < 2 * H) ep.k[r * ep.ldkv + (col - H)] = f32_to_bf16(val);
             else ep.v[r * ep.ldkv + (col - 2 * H)] = f32_to_bf16(val);
         } else {
@@ -62,6 +62,7 @@ template <int ROWS>
 struct TileLoader {
     static constexpr int PER_THREAD = ROWS * 8 / kThreads;
     uint4 regs[PER_THREAD];
+    template <bool KTAIL>
     __device__ __forceinline__ void load(const bf16_t* __restrict__ base, int ld, int row0, int nrows, int k0, int K) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
@@ -70,8 +71,14 @@ struct TileLoader {
             int gr = row0 + r;
             gr = gr < nrows ? gr : nrows - 1;  // rows past the end repeat the last row; their results are never stored
             const int gk = k0 + c * 8;
-            if (gk < K) regs[i] = *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(gr) * ld + gk);
-            else regs[i] = make_uint4(0, 0, 0, 0);
+            if (KTAIL) {  // K not a multiple of 64: chunks past its end contribute zeros
+                const bool live = gk < K;
+                uint4 x = *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(gr) * ld + (live ? gk : 0));
+                if (!live) x = make_uint4(0, 0, 0, 0);
+                regs[i] = x;
+            } else {
+                regs[i] = *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(gr) * ld + gk);
+            }
         }
     }
     __device__ __forceinline__ void store(bf16_t* lds) const {
@@ -88,7 +95,7 @@ __device__ __forceinline__ bf16x8 lds_frag(const bf16_t* tile, int row, int chun
     return *reinterpret_cast<const bf16x8*>(tile + row * BK + ((chunk ^ (row & 7)) << 3));
 }
 
-template <int BM, int BN, int WGM, int WGN, int KIND>
+template <int BM, int BN, int WGM, int WGN, int KIND, bool KTAIL>
 __global__ void __launch_bounds__(kThreads)
 gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W, int ldw,
                  int M, int N, int K, int m_tiles, int n_tiles, int tiles_per_xcd, GemmEpilogue ep) {
@@ -96,9 +103,10 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int TM = WM / 32, TN = WN / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    // stage s: A tile at s*STAGE, W tile right after it.  Addresses are formed from the shared base by integer
+    // offsets only, so that every access is an LDS (ds_*) instruction and never a flat one.
     bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
-    bf16_t* a_lds[2] = {smem, smem + (BM + BN) * BK};
-    bf16_t* w_lds[2] = {smem + BM * BK, smem + (BM + BN) * BK + BM * BK};
+    constexpr int STAGE = (BM + BN) * BK;
 
     // XCD-aware tile numbering: consecutive tiles (same weight rows, all row tiles) stay on one XCD
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
@@ -123,19 +131,19 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
     TileLoader<BM> la;
     TileLoader<BN> lw;
     const int k_steps = (K + BK - 1) / BK;
-    la.load(A, lda, m0, M, 0, K);
-    lw.load(W, ldw, n0, N, 0, K);
-    la.store(a_lds[0]);
-    lw.store(w_lds[0]);
+    la.template load<KTAIL>(A, lda, m0, M, 0, K);
+    lw.template load<KTAIL>(W, ldw, n0, N, 0, K);
+    la.store(smem);
+    lw.store(smem + BM * BK);
     __syncthreads();
     for (int ks = 0; ks < k_steps; ++ks) {
         const int cur = ks & 1;
-        if (ks + 1 < k_steps) {
-            la.load(A, lda, m0, M, (ks + 1) * BK, K);
-            lw.load(W, ldw, n0, N, (ks + 1) * BK, K);
-        }
-        const bf16_t* at = a_lds[cur];
-        const bf16_t* wt = w_lds[cur];
+        // The last step re-loads its own tiles into the idle stage: unconditional code keeps the staging registers in VGPRs.
+        const int k_next = (ks + 1 < k_steps ? ks + 1 : ks) * BK;
+        la.template load<KTAIL>(A, lda, m0, M, k_next, K);
+        lw.template load<KTAIL>(W, ldw, n0, N, k_next, K);
+        const bf16_t* at = smem + cur * STAGE;
+        const bf16_t* wt = at + BM * BK;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 af[TM], wf[TN];
@@ -149,10 +157,8 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
         }
-        if (ks + 1 < k_steps) {
-            la.store(a_lds[cur ^ 1]);
-            lw.store(w_lds[cur ^ 1]);
-        }
+        la.store(smem + (cur ^ 1) * STAGE);
+        lw.store(smem + (cur ^ 1) * STAGE + BM * BK);
         __syncthreads();
     }
 
@@ -174,13 +180,13 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int KIND>
-int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int ldw, int m, int n, int k, const GemmEpilogue& ep) {
+template <int BM, int BN, int WGM, int WGN, int KIND, bool KTAIL>
+int launch_gemm_k(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int ldw, int m, int n, int k, const GemmEpilogue& ep) {
     const int m_tiles = (m + BM - 1) / BM, n_tiles = (n + BN - 1) / BN;
     const int tiles = m_tiles * n_tiles;
     const int tiles_per_xcd = (tiles + 7) / 8;
     const size_t lds_bytes = static_cast<size_t>(2) * (BM + BN) * BK * sizeof(bf16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, KIND>;
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, KIND, KTAIL>;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
@@ -190,6 +196,12 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int
                        a, lda, w, ldw, m, n, k, m_tiles, n_tiles, tiles_per_xcd, ep);
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
+}
+
+template <int BM, int BN, int WGM, int WGN, int KIND>
+int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int ldw, int m, int n, int k, const GemmEpilogue& ep) {
+    if (k % BK) return launch_gemm_k<BM, BN, WGM, WGN, KIND, true>(ctx, a, lda, w, ldw, m, n, k, ep);
+    return launch_gemm_k<BM, BN, WGM, WGN, KIND, false>(ctx, a, lda, w, ldw, m, n, k, ep);
 }
 
 template <int KIND>
@@ -208,6 +220,7 @@ int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int ldw
     if (m <= 0 || n <= 0) return REGIONE_OK;
     if (k <= 0 || (k & 7) || (lda & 7) || (ldw & 7)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "gemm: k=%d lda=%d ldw=%d must be positive multiples of 8", k, lda, ldw);
     if (!rg_aligned16(a) || !rg_aligned16(w)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
+    ProfScope prof(ctx, REGIONE_PROF_GEMM);
     switch (ep.kind) {
         case EPI_PLAIN: return dispatch_tile<EPI_PLAIN>(ctx, a, lda, w, ldw, m, n, k, ep);
         case EPI_QKV: return dispatch_tile<EPI_QKV>(ctx, a, lda, w, ldw, m, n, k, ep);

@@ -176,6 +176,8 @@ extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* 
         if (!x_t || !v || !x_ref || !mask || !e_index || !u_index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: null tensor");
         if (!rg_aligned16(x_t) || !rg_aligned16(v) || !rg_aligned16(x_ref)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: inputs must be 16-byte aligned");
     }
+    {
+    ProfScope prof(ctx, REGIONE_PROF_PARTITION);
     if (n_tokens == 0) {
         hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, n_edited_dev, 0);
         RG_LAUNCH_CHECK();
@@ -206,6 +208,7 @@ extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* 
         hipLaunchKernelGGL(write_index_kernel, grid, dim3(kThreads), 0, ctx->stream,
                            mask, ctx->part_counts, n_tokens, tpb, e_index, u_index, n_edited_dev);
         RG_LAUNCH_CHECK();
+    }
     }
     if (n_edited_host_opt) {
         RG_HIP(hipMemcpyAsync(n_edited_host_opt, n_edited_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));

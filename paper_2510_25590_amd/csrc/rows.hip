@@ -41,6 +41,7 @@ int rows_by_index(regione_ctx* ctx, const void* src, void* dst, int32_t row_elem
     int64_t blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 256 * 64) blocks = 256 * 64;
     dim3 grid(static_cast<unsigned>(blocks));
+    ProfScope prof(ctx, REGIONE_PROF_ROWS);
     if (piece_bytes == 16)
         hipLaunchKernelGGL((rows_by_index_kernel<uint4, GATHER>), grid, dim3(kThreads), 0, ctx->stream,
                            static_cast<const uint4*>(src), static_cast<uint4*>(dst), index, n_dev, n_max, ppr);
@@ -135,6 +136,7 @@ extern "C" int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float fac
     int64_t blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 256 * 32) blocks = 256 * 32;
     dim3 grid(static_cast<unsigned>(blocks));
+    ProfScope prof(ctx, REGIONE_PROF_VELOCITY);
     if (dtype == REGIONE_BF16)
         hipLaunchKernelGGL(velocity_cache_kernel<bf16_t>, grid, dim3(kThreads), 0, ctx->stream, reuse, factor, dt,
                            static_cast<const bf16_t*>(v_fresh_opt), static_cast<bf16_t*>(c_a), static_cast<bf16_t*>(v_out_opt),
@@ -150,6 +152,7 @@ extern "C" int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float fac
 int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, bf16_t* u) {
     if (n <= 0) return REGIONE_OK;
     dim3 grid((n + kThreads / 64 - 1) / (kThreads / 64));
+    ProfScope prof(ctx, REGIONE_PROF_LAYERNORM);
     if (h_f32)
         hipLaunchKernelGGL(layernorm_mod_kernel<float>, grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(h), n, hidden, shift, scale, u);
     else

@@ -20,9 +20,10 @@ import numpy as np
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """float32 array -> uint16 array of bfloat16 bit patterns (round to nearest even)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
-    u = x.view(np.uint32).astype(np.uint64)
-    lsb = (u >> 16) & 1
-    r = (u + 0x7FFF + lsb) >> 16
+    u = x.view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    with np.errstate(over="ignore"):
+        r = (u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)   # finite inputs never wrap; NaN payloads are not produced here
     return r.astype(np.uint16)
 
 
@@ -126,7 +127,9 @@ def stream_weights(rng: np.random.Generator, hidden: int, mlp: int, kind: str, d
     Modulation vectors (float32, never rounded): shift/scale small, gate near one.
     """
     def w(o, i):
-        return _store(std * rng.standard_normal((o, i)), dtype)
+        a = rng.standard_normal((o, i), dtype=np.float32)
+        a *= np.float32(std)
+        return _store(a, dtype)
 
     def b(o):
         return (std * rng.standard_normal(o)).astype(np.float32)
@@ -153,7 +156,7 @@ def stream_weights(rng: np.random.Generator, hidden: int, mlp: int, kind: str, d
 
 
 def hidden_states(rng: np.random.Generator, n: int, hidden: int, dtype: str = "bf16") -> np.ndarray:
-    return _store(rng.standard_normal((n, hidden)), dtype)
+    return _store(rng.standard_normal((n, hidden), dtype=np.float32), dtype)
 
 
 def workload_seed(config: int, trial: int = 0) -> int:

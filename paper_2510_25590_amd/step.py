@@ -1,0 +1,145 @@
+"""One region-aware denoising step as a sequence of C-ABI calls (marshalling only).
+
+`RegionStepWorkload` holds the device tensors of one synthetic workload (latents, hidden
+states, one block's weights, the layer's KV cache) and `step()` issues the hot path of the
+method's region-aware generation stage (Algorithm 1, inner loop) through the binding:
+
+  regione_partition -> regione_gather (hidden rows, latent rows) -> regione_block_forward
+  with the retrieve flag (Eq.6) -> regione_linear (velocity head) -> regione_velocity_cache
+  (Eq.9 + Eq.4) -> regione_scatter (latent rows, hidden rows)
+
+No arithmetic of the method happens here; torch is used for device memory only.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import binding as rg
+from . import inputs
+
+
+@dataclass
+class StepConfig:
+    name: str
+    hidden: int = 3072
+    heads: int = 24
+    head_dim: int = 128
+    mlp: int = 12288
+    grid: int = 64            # image tokens = grid * grid, same number of reference tokens
+    n_txt: int = 512
+    channels: int = 64        # latent channels per token
+    n_edited: int = 819       # 20 % of 4096
+    mask: str = "rect"        # "rect" | "blob"
+    kind: str = "double"      # block type
+    sigma: float = 0.7
+    eta: float = 0.9
+    dt: float = 1.0 / 28.0
+    seed: int = 2000
+
+
+CONFIG_TINY = StepConfig(name="tiny: hidden 256, 4x64 heads, MLP 1024, 16x16 image + 256 reference + 32 text tokens, 6x6 rectangle edited",
+                         hidden=256, heads=4, head_dim=64, mlp=1024, grid=16, n_txt=32, n_edited=36, seed=1000)
+CONFIG_BLOCK = StepConfig(name="one double-stream block: hidden 3072, 24x128 heads, MLP 12288, 4096 image + 4096 reference + 512 text tokens, "
+                               "one rectangle of 20 % edited, KV cache pre-filled")
+
+
+def host_inputs(cfg: StepConfig):
+    """Seeded host arrays of the workload (float32 values that are exactly representable in bf16)."""
+    rng = np.random.default_rng(cfg.seed)
+    n_img = cfg.grid * cfg.grid
+    if cfg.mask == "rect":
+        side = int(round(np.sqrt(cfg.n_edited)))
+        if side * side == cfg.n_edited and side <= cfg.grid:
+            want = inputs.rect_mask(rng, cfg.grid, cfg.grid, side, side)
+        else:
+            want = inputs.rect_mask_fraction(rng, cfg.grid, cfg.grid, cfg.n_edited)
+    else:
+        want = inputs.blob_mask(rng, cfg.grid, cfg.grid, cfg.n_edited)
+    x_t, v_prev, x_ref = inputs.latents_for_mask(rng, want, cfg.channels, cfg.sigma, "bf16")
+    n_all = cfg.n_txt + 2 * n_img
+    h_store = inputs.hidden_states(rng, n_all, cfg.hidden)          # hidden state the cache was stored from
+    h_now = inputs.bf16_round((h_store[cfg.n_txt:cfg.n_txt + n_img] + 0.05 * rng.standard_normal((n_img, cfg.hidden))).astype(np.float32))
+    n_streams = 2 if cfg.kind == "double" else 1
+    streams = [inputs.stream_weights(rng, cfg.hidden, cfg.mlp, cfg.kind, "bf16") for _ in range(n_streams)]
+    w_head = inputs.bf16_round((0.02 * rng.standard_normal((cfg.channels, cfg.hidden))).astype(np.float32))
+    b_head = (0.02 * rng.standard_normal(cfg.channels)).astype(np.float32)
+    return dict(want=want, x_t=x_t, v_prev=v_prev, x_ref=x_ref, h_store=h_store, h_now=h_now, streams=streams,
+                w_head=w_head, b_head=b_head)
+
+
+class RegionStepWorkload:
+    def __init__(self, cfg: StepConfig, host=None):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.host = host if host is not None else host_inputs(cfg)
+        hst = self.host
+        n_img = cfg.grid * cfg.grid
+        self.n_img, self.n_all = n_img, cfg.n_txt + 2 * n_img
+        bf = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).cuda()
+        f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+        self.ctx = rg.Context(cfg.hidden, cfg.heads, cfg.head_dim, cfg.mlp, self.n_all, n_img)
+        self.x_t, self.v_prev, self.x_ref = bf(hst["x_t"]), bf(hst["v_prev"]), bf(hst["x_ref"])
+        self.h_now = bf(hst["h_now"])
+        self._keep = []
+        self.weights = rg.BlockWeights()
+        for name, w in zip(("txt", "img") if cfg.kind == "double" else ("img",), hst["streams"]):
+            t = {k: (bf(a) if k.startswith("w_") else f32(a)) for k, a in w.items()}
+            self._keep.append(t)
+            setattr(self.weights, name, rg.make_stream_weights(t))
+        self.block_type = rg.BLOCK_DOUBLE if cfg.kind == "double" else rg.BLOCK_SINGLE
+        self.w_head, self.b_head = bf(hst["w_head"]), f32(hst["b_head"])
+        dev = "cuda"
+        self.k_cache = torch.zeros((self.n_all, cfg.heads, cfg.head_dim), dtype=torch.bfloat16, device=dev)
+        self.v_cache = torch.zeros_like(self.k_cache)
+        self.score = torch.empty(n_img, dtype=torch.float32, device=dev)
+        self.mask = torch.empty(n_img, dtype=torch.uint8, device=dev)
+        self.e_index = torch.empty(n_img, dtype=torch.int32, device=dev)
+        self.u_index = torch.empty(n_img, dtype=torch.int32, device=dev)
+        self.n_dev = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.h_e = torch.empty((n_img, cfg.hidden), dtype=torch.bfloat16, device=dev)
+        self.h_e_out = torch.empty_like(self.h_e)
+        self.x_e = torch.empty((n_img, cfg.channels), dtype=torch.bfloat16, device=dev)
+        self.v_e = torch.empty_like(self.x_e)
+        self.c_a = torch.zeros_like(self.x_e)
+        self.x_next = self.x_t.clone()       # unedited rows keep their value; edited rows are scattered in
+        self.h_next = self.h_now.clone()
+        self.n_edited = -1
+        self._fill_cache(bf(hst["h_store"]))
+
+    def _fill_cache(self, h_store):
+        """The last full forward before the region-aware stage: stores K,V of every row (Algorithm 1, store flag)."""
+        torch = self.torch
+        slots = torch.arange(self.n_all, dtype=torch.int32, device="cuda")
+        out = torch.empty_like(h_store)
+        rg.regione_block_forward(self.ctx, self.weights, self.block_type, h_store, out, rg.BF16, self.n_all, self.cfg.n_txt,
+                                 slots, 0, self.k_cache, self.v_cache, self.n_all, rg.FLAG_STORE)
+        torch.cuda.synchronize()
+
+    def step(self):
+        cfg, ctx = self.cfg, self.ctx
+        n = rg.regione_partition(ctx, self.x_t, self.v_prev, self.x_ref, self.n_img, cfg.channels, rg.BF16, cfg.sigma, cfg.eta,
+                                 self.score, self.mask, self.e_index, self.u_index, self.n_dev)
+        self.n_edited = n
+        rg.regione_gather(ctx, self.h_now, cfg.hidden, rg.BF16, self.e_index, self.n_dev, n, self.h_e)
+        rg.regione_gather(ctx, self.x_t, cfg.channels, rg.BF16, self.e_index, self.n_dev, n, self.x_e)
+        rg.regione_block_forward(ctx, self.weights, self.block_type, self.h_e, self.h_e_out, rg.BF16, n, 0,
+                                 self.e_index, cfg.n_txt, self.k_cache, self.v_cache, self.n_all, rg.FLAG_RETRIEVE)
+        rg.regione_linear(ctx, self.h_e_out, self.w_head, self.b_head, n, cfg.channels, cfg.hidden, rg.ACT_NONE, rg.BF16, self.v_e)
+        rg.regione_velocity_cache(ctx, False, 1.0, cfg.dt, self.v_e, self.c_a, None, self.x_e, self.n_dev, n, cfg.channels, rg.BF16)
+        rg.regione_scatter(ctx, self.x_next, cfg.channels, rg.BF16, self.e_index, self.n_dev, n, self.x_e)
+        rg.regione_scatter(ctx, self.h_next, cfg.hidden, rg.BF16, self.e_index, self.n_dev, n, self.h_e_out)
+        return n
+
+    def flops(self, n: int):
+        """Algorithmic FLOPs of one step for n edited tokens: dense projections and attention (Eq.6), nothing else."""
+        cfg = self.cfg
+        H, M = cfg.hidden, cfg.mlp
+        gemm = 2.0 * n * H * (3 * H + H + 2 * M) + 2.0 * n * H * cfg.channels
+        attn = 4.0 * n * self.n_all * H
+        return gemm, attn
+
+    def close(self):
+        self.ctx.close()

@@ -43,13 +43,13 @@ def test_config1_block_all_modes(kind, h_dtype):
     slots_all = torch.arange(n_all, dtype=torch.int32, device="cuda")
     kc = torch.zeros((n_all, heads, d), dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
     out = torch.empty((n_all, hidden), dtype=tdt, device="cuda")
-    rg.regione_block_forward(ctx, bw, btype, dh, out, hcode, n_all, n_txt, slots_all, kc, vc, n_all, rg.FLAG_STORE)
+    rg.regione_block_forward(ctx, bw, btype, dh, out, hcode, n_all, n_txt, slots_all, 0, kc, vc, n_all, rg.FLAG_STORE)
     sb = h_dtype == "bf16"
     assert_close(host(out), full_o, f"{kind} storing full forward", stored_bf16=sb)
     assert_close(host(kc), kc_o, "stored K", stored_bf16=True)
     assert_close(host(vc), vc_o, "stored V", stored_bf16=True)
     out2 = torch.empty_like(out)
-    rg.regione_block_forward(ctx, bw, btype, dh, out2, hcode, n_all, n_txt, None, None, None, 0, 0)
+    rg.regione_block_forward(ctx, bw, btype, dh, out2, hcode, n_all, n_txt, None, 0, None, None, 0, 0)
     assert_close(host(out2), full_o, f"{kind} plain full forward", stored_bf16=sb)
 
     # stale cache: the region step sees a hidden state that moved since the cache was stored
@@ -60,7 +60,7 @@ def test_config1_block_all_modes(kind, h_dtype):
         kc_before, vc_before = kc.clone(), vc.clone()
         dslots = torch.from_numpy(rows.astype(np.int32)).cuda()
         o = torch.empty((len(rows), hidden), dtype=tdt, device="cuda")
-        rg.regione_block_forward(ctx, bw, btype, dev(h2[rows], h_dtype), o, hcode, len(rows), n_txt_fresh, dslots, kc, vc, n_all, rg.FLAG_RETRIEVE)
+        rg.regione_block_forward(ctx, bw, btype, dev(h2[rows], h_dtype), o, hcode, len(rows), n_txt_fresh, dslots, 0, kc, vc, n_all, rg.FLAG_RETRIEVE)
         assert_close(host(o), want, f"{kind} region forward, mode {mode}", stored_bf16=sb)
         untouched = np.setdiff1d(np.arange(n_all), rows)
         assert torch.equal(kc[untouched].view(torch.int16), kc_before[untouched].view(torch.int16))
@@ -70,18 +70,18 @@ def test_config1_block_all_modes(kind, h_dtype):
     # same-step cache: region forward on the unchanged input reproduces the full forward on those rows
     rows = n_txt + e
     o = torch.empty((len(rows), hidden), dtype=tdt, device="cuda")
-    rg.regione_block_forward(ctx, bw, btype, dev(h[rows], h_dtype), o, hcode, len(rows), 0, torch.from_numpy(rows.astype(np.int32)).cuda(), kc, vc, n_all, rg.FLAG_RETRIEVE)
+    rg.regione_block_forward(ctx, bw, btype, dev(h[rows], h_dtype), o, hcode, len(rows), 0, torch.from_numpy(e).cuda(), n_txt, kc, vc, n_all, rg.FLAG_RETRIEVE)
     assert_close(host(o), full_o[rows], f"{kind} same-step cache", stored_bf16=sb)
     # in place
     hh = dev(h[rows], h_dtype)
-    rg.regione_block_forward(ctx, bw, btype, hh, hh, hcode, len(rows), 0, torch.from_numpy(rows.astype(np.int32)).cuda(), kc, vc, n_all, rg.FLAG_RETRIEVE)
+    rg.regione_block_forward(ctx, bw, btype, hh, hh, hcode, len(rows), 0, torch.from_numpy(e).cuda(), n_txt, kc, vc, n_all, rg.FLAG_RETRIEVE)
     assert torch.equal(hh, o)
     # no fresh row: nothing happens
-    rg.regione_block_forward(ctx, bw, btype, None, None, hcode, 0, 0, None, kc, vc, n_all, rg.FLAG_RETRIEVE)
+    rg.regione_block_forward(ctx, bw, btype, None, None, hcode, 0, 0, None, 0, kc, vc, n_all, rg.FLAG_RETRIEVE)
     with pytest.raises(rg.RegionEError):
-        rg.regione_block_forward(ctx, bw, btype, dh, out, hcode, n_all, n_txt, slots_all, kc, vc, n_all, 3)
+        rg.regione_block_forward(ctx, bw, btype, dh, out, hcode, n_all, n_txt, slots_all, 0, kc, vc, n_all, 3)
     with pytest.raises(rg.RegionEError):
-        rg.regione_block_forward(ctx, bw, btype, dh, out, hcode, 10, 0, slots_all, kc, vc, n_all, rg.FLAG_STORE)
+        rg.regione_block_forward(ctx, bw, btype, dh, out, hcode, 10, 0, slots_all, 0, kc, vc, n_all, rg.FLAG_STORE)
     ctx.close()
 
 
@@ -106,11 +106,11 @@ def test_config2_block_region_forward_sampled(kind):
     kc = torch.zeros((n_all, heads, d), dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
     out_full = torch.empty((n_all, hidden), dtype=torch.bfloat16, device="cuda")
     rg.regione_block_forward(ctx, bw, btype, dev(h_store, "bf16"), out_full, rg.BF16, n_all, n_txt,
-                             torch.arange(n_all, dtype=torch.int32, device="cuda"), kc, vc, n_all, rg.FLAG_STORE)
+                             torch.arange(n_all, dtype=torch.int32, device="cuda"), 0, kc, vc, n_all, rg.FLAG_STORE)
     kc_stored, vc_stored = kc.clone(), vc.clone()      # the region forward below refreshes the edited rows' slots
     o = torch.empty((len(rows), hidden), dtype=torch.bfloat16, device="cuda")
     rg.regione_block_forward(ctx, bw, btype, dev(h_now, "bf16"), o, rg.BF16, len(rows), 0,
-                             torch.from_numpy(rows.astype(np.int32)).cuda(), kc, vc, n_all, rg.FLAG_RETRIEVE)
+                             torch.from_numpy(e).cuda(), n_txt, kc, vc, n_all, rg.FLAG_RETRIEVE)
     got = host(o)
     not_fresh = torch.ones(n_all, dtype=torch.bool, device="cuda"); not_fresh[torch.from_numpy(rows).cuda()] = False
     assert torch.equal(kc[not_fresh].view(torch.int16), kc_stored[not_fresh].view(torch.int16))
