@@ -18,8 +18,9 @@
  *    only call that waits for the stream is regione_partition with a non-null
  *    n_edited_host.  Calls on one context must not overlap (they share its workspace).
  *  - Token order of the cached sequence is [P (text) | X (image) | I (reference image)].
- *  - Linear weights are bf16 [out_features, in_features]; biases and modulation vectors
- *    are float32.
+ *  - Linear weights reach the library in its PACKED bf16 layout, made once per weight by
+ *    regione_pack_weight from the usual row-major [out_features, in_features] matrix;
+ *    biases and modulation vectors are float32.
  *  - Empty inputs (no edited token, no cache rows) are not errors: the call does nothing
  *    or degenerates as Eq.6 does.
  */
@@ -59,7 +60,7 @@ typedef struct regione_dims {
     int32_t max_tokens; /* most tokens one regione_partition call will carry */
 } regione_dims;
 
-/* Weights of one stream of a block (host struct of device pointers).
+/* Weights of one stream of a block (host struct of device pointers to PACKED weights).
  * Double-stream block: w_qkv [3H,H], w_o [H,H], w_1 [M,H], w_2 [H,M].
  * Single-stream block: w_1 [3H+M,H] producing [q|k|v|m], w_2 [H,H+M] applied to
  * [attention | gelu(m)]; w_qkv, w_o and the *2 modulation vectors are ignored.
@@ -138,11 +139,24 @@ int regione_attn_kvcache(regione_ctx* ctx, const void* q, int32_t n_q,
                          const int32_t* cache_index_opt, int32_t n_cache_index,
                          int32_t heads, int32_t d, float scale, void* out);
 
-/* y = act(x W^T + b): x [m,k] bf16, w [n,k] bf16, b [n] float32 or NULL, y [m,n] of
- * out_dtype.  k must be a multiple of 8.  Used for the token embedding and the final
- * projection around the blocks, and by the block itself. */
-int regione_linear(regione_ctx* ctx, const void* x, const void* w, const float* b_opt,
+/* Weight packing.  The GEMM kernels read weights in the register layout of the matrix-core
+ * operand: for W [n, k] (k a multiple of 64) the packed array holds, for every block of 32
+ * output features and 16 input features, 64 x 8 bf16 with entry (lane, e) =
+ * W[32*block_n + lane%32][16*block_k + 8*(lane/32) + e]; blocks are ordered block_n major.
+ * Rows past n are zero.  regione_packed_weight_elems gives the element count of the packed
+ * array (n rounded up to 32, times k).  Packing is a one-time copy on the context's stream. */
+int64_t regione_packed_weight_elems(int32_t n, int32_t k);
+int regione_pack_weight(regione_ctx* ctx, const void* w /*[n,k] bf16 row-major*/, int32_t n, int32_t k, void* w_packed);
+
+/* y = act(x W^T + b): x [m,k] bf16, W packed from [n,k], b [n] float32 or NULL, y [m,n] of
+ * out_dtype.  k must be a multiple of 64.  Used for the token embedding and the velocity
+ * head around the blocks, and by the block itself. */
+int regione_linear(regione_ctx* ctx, const void* x, const void* w_packed, const float* b_opt,
                    int32_t m, int32_t n, int32_t k, int32_t act, int32_t out_dtype, void* y);
+
+/* Tuning knob for experiments: forces the GEMM wave tile (1 or 2 blocks of 32 columns) and the
+ * number of K splits of every later GEMM of this context; 0 restores the automatic choice. */
+int regione_tune_gemm(regione_ctx* ctx, int32_t wave_tile_blocks, int32_t k_splits);
 
 /* One transformer block on the fresh rows: one layer of Phi(tokens, C_KV, f) in
  * Algorithm 1.  The block is LayerNorm (no affine, eps 1e-6) -> modulation -> QKV linear ->

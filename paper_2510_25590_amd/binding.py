@@ -24,6 +24,7 @@ EXPORTS = (
     "regione_last_error", "regione_create", "regione_destroy", "regione_partition", "regione_gather",
     "regione_scatter", "regione_attn_kvcache", "regione_linear", "regione_block_forward",
     "regione_velocity_decision_host", "regione_velocity_cache", "regione_profile_enable", "regione_profile_read",
+    "regione_packed_weight_elems", "regione_pack_weight", "regione_tune_gemm",
 )
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
 
@@ -78,6 +79,8 @@ def lib() -> C.CDLL:
             "regione_velocity_decision_host": [C.POINTER(f32), C.POINTER(f32), i32, f32, i32, C.POINTER(AvdState),
                                                C.POINTER(i32), C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
+            "regione_pack_weight": [vp, vp, i32, i32, vp],
+            "regione_tune_gemm": [vp, i32, i32],
             "regione_profile_enable": [vp, i32],
             "regione_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(i64), i32],
         }
@@ -85,6 +88,8 @@ def lib() -> C.CDLL:
             fn = getattr(_lib, name)
             fn.argtypes = args
             fn.restype = C.c_int
+        _lib.regione_packed_weight_elems.argtypes = [i32, i32]
+        _lib.regione_packed_weight_elems.restype = C.c_int64
     return _lib
 
 
@@ -193,3 +198,24 @@ def regione_profile_read(ctx):
     cnt = (C.c_int64 * n)()
     _check(lib().regione_profile_read(ctx.handle, ms, cnt, n))
     return {name: (ms[i], cnt[i]) for i, name in enumerate(PROF_NAMES)}
+
+
+def regione_packed_weight_elems(n: int, k: int) -> int:
+    return int(lib().regione_packed_weight_elems(n, k))
+
+
+def regione_pack_weight(ctx, w, n, k, w_packed):
+    _check(lib().regione_pack_weight(ctx.handle, _p(w), n, k, _p(w_packed)))
+
+
+def regione_tune_gemm(ctx, wave_tile_blocks: int, k_splits: int):
+    _check(lib().regione_tune_gemm(ctx.handle, wave_tile_blocks, k_splits))
+
+
+def pack_weight(ctx, w):
+    """Convenience: packs a row-major bf16 CUDA tensor [n, k] into a new tensor in the library's layout."""
+    import torch
+    n, k = w.shape
+    out = torch.empty(regione_packed_weight_elems(n, k), dtype=torch.bfloat16, device=w.device)
+    regione_pack_weight(ctx, w.contiguous(), n, k, out)
+    return out

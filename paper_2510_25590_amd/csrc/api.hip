@@ -24,7 +24,7 @@ int dev_alloc(T** p, size_t count) {
     return REGIONE_OK;
 }
 void free_all(regione_ctx* c) {
-    void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->attn_part};
+    void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->attn_part, c->gemm_part};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     if (c->prof_ev) {
         for (int i = 0; i < 2 * c->prof_cap; ++i) if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
@@ -43,7 +43,7 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
         RG_FAIL(REGIONE_ERR_BAD_SHAPE, "create: hidden %d != heads %d * head_dim %d", dims->hidden, dims->heads, dims->head_dim);
     if (dims->head_dim != 64 && dims->head_dim != 128)
         RG_FAIL(REGIONE_ERR_UNSUPPORTED, "create: head dimension %d (64 or 128 supported)", dims->head_dim);
-    if (dims->hidden % 8 || dims->mlp % 8) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "create: hidden and mlp must be multiples of 8");
+    if (dims->hidden % 64 || dims->mlp % 64) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "create: hidden and mlp must be multiples of 64");
     regione_ctx* c = new (std::nothrow) regione_ctx();
     if (!c) RG_FAIL(REGIONE_ERR_HIP, "create: out of host memory");
     memset(c, 0, sizeof(*c));
@@ -63,6 +63,8 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
     if (rc == REGIONE_OK) rc = dev_alloc(&c->h1, n * H);
     if (rc == REGIONE_OK) rc = dev_alloc(&c->m, n * M);
     if (rc == REGIONE_OK) rc = dev_alloc(reinterpret_cast<char**>(&c->attn_part), c->attn_part_bytes);
+    c->gemm_part_bytes = n > 0 ? static_cast<size_t>(128) << 20 : 0;
+    if (rc == REGIONE_OK) rc = dev_alloc(reinterpret_cast<char**>(&c->gemm_part), c->gemm_part_bytes);
     if (rc != REGIONE_OK) { free_all(c); delete c; return rc; }
     *out = c;
     return REGIONE_OK;
@@ -186,11 +188,11 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
         ep.ldkv = H;
         if (dbl) {
             ep.bias = g.w->b_qkv;
-            rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_qkv), H, g.n, 3 * H, H, ep);
+            rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_qkv), g.n, 3 * H, H, ep);
         } else {
             ep.bias = g.w->b_1; ep.act = REGIONE_ACT_GELU_TANH;
             ep.y = ctx->a + static_cast<size_t>(g.r0) * lda_attn; ep.ldy = lda_attn; ep.y_col0 = H;
-            rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_1), H, g.n, 3 * H + M, H, ep);
+            rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_1), g.n, 3 * H + M, H, ep);
         }
         if (rc != REGIONE_OK) return rc;
     }
@@ -213,26 +215,26 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
             ep.bias = g.w->b_2; ep.gate = g.w->gate1;
             ep.resid = hin; ep.ldr = H; ep.resid_f32 = h_f32;
             ep.y = hout; ep.ldy = H; ep.y_f32 = h_f32;
-            if ((rc = rg_gemm(ctx, a, lda_attn, static_cast<const bf16_t*>(g.w->w_2), H + M, g.n, H, H + M, ep)) != REGIONE_OK) return rc;
+            if ((rc = rg_gemm(ctx, a, lda_attn, static_cast<const bf16_t*>(g.w->w_2), g.n, H, H + M, ep)) != REGIONE_OK) return rc;
             continue;
         }
         float* h1 = ctx->h1 + static_cast<size_t>(g.r0) * H;
         ep.bias = g.w->b_o; ep.gate = g.w->gate1;
         ep.resid = hin; ep.ldr = H; ep.resid_f32 = h_f32;
         ep.y = h1; ep.ldy = H; ep.y_f32 = 1;
-        if ((rc = rg_gemm(ctx, a, H, static_cast<const bf16_t*>(g.w->w_o), H, g.n, H, H, ep)) != REGIONE_OK) return rc;
+        if ((rc = rg_gemm(ctx, a, H, static_cast<const bf16_t*>(g.w->w_o), g.n, H, H, ep)) != REGIONE_OK) return rc;
         bf16_t* u = ctx->u + static_cast<size_t>(g.r0) * H;
         if ((rc = rg_layernorm_mod(ctx, h1, 1, g.n, H, g.w->shift2, g.w->scale2, u)) != REGIONE_OK) return rc;
         bf16_t* m = ctx->m + static_cast<size_t>(g.r0) * M;
         GemmEpilogue up = {};
         up.kind = EPI_PLAIN; up.bias = g.w->b_1; up.act = REGIONE_ACT_GELU_TANH; up.act_from = 0;
         up.y = m; up.ldy = M; up.y_f32 = 0;
-        if ((rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_1), H, g.n, M, H, up)) != REGIONE_OK) return rc;
+        if ((rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_1), g.n, M, H, up)) != REGIONE_OK) return rc;
         GemmEpilogue dn = {};
         dn.kind = EPI_RESID; dn.bias = g.w->b_2; dn.gate = g.w->gate2;
         dn.resid = h1; dn.ldr = H; dn.resid_f32 = 1;
         dn.y = hout; dn.ldy = H; dn.y_f32 = h_f32;
-        if ((rc = rg_gemm(ctx, m, M, static_cast<const bf16_t*>(g.w->w_2), M, g.n, H, M, dn)) != REGIONE_OK) return rc;
+        if ((rc = rg_gemm(ctx, m, M, static_cast<const bf16_t*>(g.w->w_2), g.n, H, M, dn)) != REGIONE_OK) return rc;
     }
     return REGIONE_OK;
 }

@@ -24,6 +24,9 @@ struct regione_ctx {
     bf16_t* m;     // [max_fresh, M]     activated MLP hidden rows
     float* attn_part;  // split-KV partial results
     size_t attn_part_bytes;
+    float* gemm_part;  // split-K partial sums
+    size_t gemm_part_bytes;
+    int gemm_force_tn, gemm_force_splits;  // 0 = chosen per call
     // optional per-kernel-class timing with HIP events on the context's stream
     int prof_on;
     int prof_used;
@@ -77,7 +80,7 @@ struct GemmEpilogue {
     const void* resid; int ldr; int resid_f32; const float* gate;
 };
 
-int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int ldw, int m, int n, int k, const GemmEpilogue& ep);
+int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w_packed, int m, int n, int k, const GemmEpilogue& ep);
 int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, bf16_t* u);
 int rg_attention(regione_ctx* ctx, const bf16_t* q, int ldq, int n_q,
                  const bf16_t* k0, const bf16_t* v0, int ldkv0, int n0,

@@ -1,25 +1,38 @@
 // bf16 GEMM on the CDNA4 matrix cores for the block's dense projections (QKV, attention
 // output, MLP up/down; section "Region-Aware Generation": the DiT runs on [X^P, X^E] only).
 //
-//   C[m, n] = sum_k A[m, k] * W[n, k]      A: activations [M, K], W: weights [N, K] (both K-contiguous)
+//   C[m, n] = sum_k A[m, k] * W[n, k]      A: activations [M, K] row-major, W: weights, PACKED (see below)
 //
-// One workgroup (4 waves) computes a BM x BN tile with v_mfma_f32_32x32x16_bf16.  K is walked in
-// steps of 64; the A and W tiles of a step are staged in LDS as rows of eight 16-byte chunks whose
-// position is XOR-swizzled with the row so that the ds_read_b128 of a fragment is conflict free,
-// double buffered, with the next step's global loads in flight during the MFMAs.  The MFMA "A"
-// operand is the activation tile and "B" the weight tile, so a lane's accumulators belong to one
-// output column and the lanes of a half-wave write 32 consecutive columns of a row.
-// Workgroups are numbered so that each XCD (blockIdx % 8) owns a contiguous range of weight rows:
-// every weight tile then streams through one L2 only.
+// The number of rows M is the number of edited tokens (a few hundred to a few thousand), so the
+// kernel is built around a 128-row tile: seven row tiles at 20 % of a 64x64 image.
+//
+//  * Weights never go through LDS.  regione_pack_weight stores them once in the register layout of
+//    the "B" operand of v_mfma_f32_32x32x16_bf16: block (n/32, k/16) is 64 lanes x 16 bytes, lane l
+//    holding W[32*(n/32) + l%32][16*(k/16) + 8*(l/32) .. +8].  A wave reads a fragment as one fully
+//    coalesced 1 KiB load straight into VGPRs, two K-steps ahead of its use.
+//  * The four waves of a workgroup split the tile along N only (wave tile 128 x 32*TN), so no weight
+//    fragment is needed by two waves; the activation tile (128 x 64 per K-step) is shared through
+//    LDS, XOR-swizzled so that ds_read_b128 of a fragment is conflict free, double buffered, its
+//    global loads two K-steps ahead.
+//  * Few row tiles means few workgroups: GEMMs with a narrow N are split along K over blockIdx.y
+//    into float partial sums, merged by a second kernel that applies the epilogue.
+//  * Workgroups are numbered so that each XCD (blockIdx.x % 8) owns a contiguous range of weight
+//    blocks: every weight byte then streams through one L2 only.
 #include "common.h"
+#include <math.h>
+#include <type_traits>
 
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // a native 16-byte vector: copies are single loads/stores
 
-constexpr int BK = 64;        // k elements per step (8 chunks of 16 bytes per row)
+constexpr int BM = 128;       // rows per workgroup tile
+constexpr int TM = BM / 32;
+constexpr int BK = 64;        // k elements per step
 constexpr int kThreads = 256;
+constexpr int A_PER_THREAD = BM * 8 / kThreads;  // 16-byte chunks of the A tile per thread
 
 __device__ __forceinline__ float gelu_tanh_f32(float x) {
     // 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
@@ -27,8 +40,15 @@ __device__ __forceinline__ float gelu_tanh_f32(float x) {
     return x / (1.0f + __expf(-2.0f * u));
 }
 
+// Row of the key/value destination for output row `row` (its cache slot when a slot list is given).
 template <int KIND>
-__device__ __forceinline__ void epilogue_store(const GemmEpilogue& ep, int row, int col, float acc, float bias, float gate) {
+__device__ __forceinline__ int64_t epilogue_kv_row(const GemmEpilogue& ep, int row) {
+    if (KIND != EPI_QKV) return row;
+    return ep.slot ? static_cast<int64_t>(ep.slot[row]) + ep.slot_offset : row;
+}
+
+template <int KIND>
+__device__ __forceinline__ void epilogue_store(const GemmEpilogue& ep, int row, int64_t kv_row, int col, float acc, float bias, float gate) {
     float val = acc + bias;
     if (KIND == EPI_PLAIN) {
         if (ep.act == REGIONE_ACT_GELU_TANH && col >= ep.act_from) val = gelu_tanh_f32(val);
@@ -40,9 +60,8 @@ __device__ __forceinline__ void epilogue_store(const GemmEpilogue& ep, int row, 
         if (col < H) {
             ep.q[static_cast<int64_t>(row) * ep.ldq + col] = f32_to_bf16(val);
         } else if (col < 3 * H) {
-            const int64_t r = ep.slot ? static_cast<int64_t>(ep.slot[row]) + ep.slot_offset : row;
-            if (col < 2 * H) ep.k[r * ep.ldkv + (col - H)] = f32_to_bf16(val);
-            else ep.v[r * ep.ldkv + (col - 2 * H)] = f32_to_bf16(val);
+            if (col < 2 * H) ep.k[kv_row * ep.ldkv + (col - H)] = f32_to_bf16(val);
+            else ep.v[kv_row * ep.ldkv + (col - 2 * H)] = f32_to_bf16(val);
         } else {
             if (ep.act == REGIONE_ACT_GELU_TANH) val = gelu_tanh_f32(val);
             static_cast<bf16_t*>(ep.y)[static_cast<int64_t>(row) * ep.ldy + ep.y_col0 + (col - 3 * H)] = f32_to_bf16(val);
@@ -57,68 +76,76 @@ __device__ __forceinline__ void epilogue_store(const GemmEpilogue& ep, int row, 
     }
 }
 
-// Tile loader: ROWS x 64 bf16 from a K-contiguous matrix into swizzled LDS, through registers.
-template <int ROWS>
-struct TileLoader {
-    static constexpr int PER_THREAD = ROWS * 8 / kThreads;
-    uint4 regs[PER_THREAD];
-    template <bool KTAIL>
-    __device__ __forceinline__ void load(const bf16_t* __restrict__ base, int ld, int row0, int nrows, int k0, int K) {
+// A-tile staging: thread t owns 16-byte chunk (t & 7) of rows (t >> 3) + 32*i.
+__device__ __forceinline__ void a_load(u32x4 (&regs)[A_PER_THREAD], const bf16_t* const (&a_rows)[A_PER_THREAD], int k0) {
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int idx = threadIdx.x + i * kThreads;
-            const int r = idx >> 3, c = idx & 7;
-            int gr = row0 + r;
-            gr = gr < nrows ? gr : nrows - 1;  // rows past the end repeat the last row; their results are never stored
-            const int gk = k0 + c * 8;
-            if (KTAIL) {  // K not a multiple of 64: chunks past its end contribute zeros
-                const bool live = gk < K;
-                uint4 x = *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(gr) * ld + (live ? gk : 0));
-                if (!live) x = make_uint4(0, 0, 0, 0);
-                regs[i] = x;
-            } else {
-                regs[i] = *reinterpret_cast<const uint4*>(base + static_cast<int64_t>(gr) * ld + gk);
-            }
-        }
-    }
-    __device__ __forceinline__ void store(bf16_t* lds) const {
+    for (int i = 0; i < A_PER_THREAD; ++i) regs[i] = *reinterpret_cast<const u32x4*>(a_rows[i] + k0);
+}
+__device__ __forceinline__ void a_store(bf16_t* lds, const u32x4 (&regs)[A_PER_THREAD]) {
+    const int r0 = threadIdx.x >> 3, c = threadIdx.x & 7;
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int idx = threadIdx.x + i * kThreads;
-            const int r = idx >> 3, c = idx & 7;
-            *reinterpret_cast<uint4*>(lds + r * BK + ((c ^ (r & 7)) << 3)) = regs[i];
-        }
+    for (int i = 0; i < A_PER_THREAD; ++i) {
+        const int r = r0 + 32 * i;
+        *reinterpret_cast<u32x4*>(lds + r * BK + ((c ^ ((r >> 1) & 7)) << 3)) = regs[i];
     }
-};
-
-__device__ __forceinline__ bf16x8 lds_frag(const bf16_t* tile, int row, int chunk) {
-    return *reinterpret_cast<const bf16x8*>(tile + row * BK + ((chunk ^ (row & 7)) << 3));
+}
+__device__ __forceinline__ bf16x8 a_frag(const bf16_t* tile, int row, int chunk) {
+    // rows are 128 bytes: 16 consecutive rows x one logical chunk cover all 64 banks exactly once
+    return *reinterpret_cast<const bf16x8*>(tile + row * BK + ((chunk ^ ((row >> 1) & 7)) << 3));
 }
 
-template <int BM, int BN, int WGM, int WGN, int KIND, bool KTAIL>
-__global__ void __launch_bounds__(kThreads)
-gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W, int ldw,
-                 int M, int N, int K, int m_tiles, int n_tiles, int tiles_per_xcd, GemmEpilogue ep) {
-    static_assert(WGM * WGN == 4, "four waves");
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int TM = WM / 32, TN = WN / 32;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    // stage s: A tile at s*STAGE, W tile right after it.  Addresses are formed from the shared base by integer
-    // offsets only, so that every access is an LDS (ds_*) instruction and never a flat one.
-    bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
-    constexpr int STAGE = (BM + BN) * BK;
+template <int TN>
+__device__ __forceinline__ void w_load(u32x4 (&regs)[TN * 4], const bf16_t* const (&w_blk)[TN], int64_t k_step) {
+    // one K-step of one 32-column block is 4 consecutive fragments of 1 KiB
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            regs[j * 4 + kk] = *reinterpret_cast<const u32x4*>(w_blk[j] + (k_step * 4 + kk) * 512);
+}
 
-    // XCD-aware tile numbering: consecutive tiles (same weight rows, all row tiles) stay on one XCD
+template <int TN, int KIND>
+__global__ void __launch_bounds__(kThreads)
+gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ Wp,
+                 int M, int N, int K, int m_tiles, int n_tiles, int tiles_per_xcd,
+                 int steps_per_split, float* __restrict__ partial, GemmEpilogue ep) {
+    constexpr int WN = 32 * TN, BN = 4 * WN;
+    __shared__ __attribute__((aligned(16))) bf16_t a_lds[2][BM * BK];
+
+    // XCD-aware tile numbering: consecutive tiles (same weight columns, all row tiles) stay on one XCD
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-    if (local >= tiles_per_xcd) return;
     const int tile = xcd * tiles_per_xcd + local;
-    if (tile >= m_tiles * n_tiles) return;
+    if (local >= tiles_per_xcd || tile >= m_tiles * n_tiles) return;
     const int n_tile = tile / m_tiles, m_tile = tile - n_tile * m_tiles;
     const int m0 = m_tile * BM, n0 = n_tile * BN;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
     const int l32 = lane & 31, lh = lane >> 5;
+    const int wn0 = wave * WN;
+
+    const int total_steps = K / BK;           // K is a multiple of 64 (checked by the launcher)
+    const int ks_begin = blockIdx.y * steps_per_split;
+    int nks = total_steps - ks_begin;
+    nks = nks < steps_per_split ? nks : steps_per_split;
+
+    // per-thread source rows of the A tile (rows past M repeat the last row; their results are never stored)
+    const bf16_t* a_rows[A_PER_THREAD];
+#pragma unroll
+    for (int i = 0; i < A_PER_THREAD; ++i) {
+        int r = m0 + (threadIdx.x >> 3) + 32 * i;
+        r = r < M ? r : M - 1;
+        a_rows[i] = A + static_cast<int64_t>(r) * lda + (threadIdx.x & 7) * 8;
+    }
+    // per-wave weight blocks (blocks past N repeat the last block)
+    const int n_blocks = (N + 31) >> 5;
+    const int64_t blk_stride = static_cast<int64_t>(K >> 4) * 512;  // elements per 32-column block
+    const bf16_t* w_blk[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        int nb = ((n0 + wn0) >> 5) + j;
+        nb = nb < n_blocks ? nb : n_blocks - 1;
+        w_blk[j] = Wp + nb * blk_stride + lane * 8;
+    }
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -128,118 +155,220 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    TileLoader<BM> la;
-    TileLoader<BN> lw;
-    const int k_steps = (K + BK - 1) / BK;
-    la.template load<KTAIL>(A, lda, m0, M, 0, K);
-    lw.template load<KTAIL>(W, ldw, n0, N, 0, K);
-    la.store(smem);
-    lw.store(smem + BM * BK);
+    u32x4 areg[3][A_PER_THREAD];
+    u32x4 wreg[3][TN * 4];
+    // steps past the end of this split re-load its last step
+    const int step1 = ks_begin + (nks > 1 ? 1 : 0);
+    a_load(areg[0], a_rows, ks_begin * BK);
+    w_load<TN>(wreg[0], w_blk, ks_begin);
+    a_load(areg[1], a_rows, step1 * BK);
+    w_load<TN>(wreg[1], w_blk, step1);
+    a_store(a_lds[0], areg[0]);
     __syncthreads();
-    for (int ks = 0; ks < k_steps; ++ks) {
-        const int cur = ks & 1;
-        // The last step re-loads its own tiles into the idle stage: unconditional code keeps the staging registers in VGPRs.
-        const int k_next = (ks + 1 < k_steps ? ks + 1 : ks) * BK;
-        la.template load<KTAIL>(A, lda, m0, M, k_next, K);
-        lw.template load<KTAIL>(W, ldw, n0, N, k_next, K);
-        const bf16_t* at = smem + cur * STAGE;
-        const bf16_t* wt = at + BM * BK;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 af[TM], wf[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = lds_frag(at, wm0 + i * 32 + l32, kk * 2 + lh);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) wf[j] = lds_frag(wt, wn0 + j * 32 + l32, kk * 2 + lh);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
-        }
-        la.store(smem + (cur ^ 1) * STAGE);
-        lw.store(smem + (cur ^ 1) * STAGE + BM * BK);
-        __syncthreads();
+
+    // One K-step.  S = j % 3 names the register set that holds step j; everything is unconditional except the MFMAs,
+    // so the three register sets stay in VGPRs.  (A macro, not a lambda: captured arrays would live in memory.)
+#define RG_GEMM_STEP(J, S, S1, S2)                                                                        \
+    {                                                                                                     \
+        const int j_ = (J);                                                                               \
+        a_load(areg[S2], a_rows, (ks_begin + (j_ + 2 < nks ? j_ + 2 : nks - 1)) * BK);                    \
+        w_load<TN>(wreg[S2], w_blk, ks_begin + (j_ + 2 < nks ? j_ + 2 : nks - 1));                        \
+        if (j_ < nks) {                                                                                   \
+            const bf16_t* at = a_lds[j_ & 1];                                                             \
+            _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                            \
+                bf16x8 af[TM];                                                                            \
+                _Pragma("unroll") for (int i = 0; i < TM; ++i) af[i] = a_frag(at, i * 32 + l32, kk * 2 + lh); \
+                _Pragma("unroll") for (int jn = 0; jn < TN; ++jn) {                                       \
+                    const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[S][jn * 4 + kk]);                   \
+                    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                        \
+                        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf, acc[i][jn], 0, 0, 0); \
+                }                                                                                         \
+            }                                                                                             \
+        }                                                                                                 \
+        a_store(a_lds[(j_ + 1) & 1], areg[S1]);                                                           \
+        __syncthreads();                                                                                  \
     }
+    for (int j = 0; j < nks; j += 3) {
+        RG_GEMM_STEP(j, 0, 1, 2)
+        RG_GEMM_STEP(j + 1, 1, 2, 0)
+        RG_GEMM_STEP(j + 2, 2, 0, 1)
+    }
+#undef RG_GEMM_STEP
 
     // accumulator (i, j, r) of a lane: row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32 of the 32x32 block
+    int col[TN];
+    float bias[TN], gate[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn0 + j * 32 + l32;
-        if (col >= N) continue;
-        const float bias = ep.bias ? ep.bias[col] : 0.f;
-        const float gate = (KIND == EPI_RESID && ep.gate) ? ep.gate[col] : 1.f;
+        col[j] = n0 + wn0 + j * 32 + l32;
+        const bool live = col[j] < N;
+        bias[j] = (!partial && live && ep.bias) ? ep.bias[col[j]] : 0.f;
+        gate[j] = (!partial && live && KIND == EPI_RESID && ep.gate) ? ep.gate[col[j]] : 1.f;
+    }
+    float* part_base = partial ? partial + (static_cast<int64_t>(blockIdx.y) * M) * N : nullptr;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                if (row < M) epilogue_store<KIND>(ep, row, col, acc[i][j][r], bias, gate);
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            if (row >= M) continue;
+            if (partial) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    if (col[j] < N) part_base[static_cast<int64_t>(row) * N + col[j]] = acc[i][j][r];
+            } else {
+                const int64_t kv_row = epilogue_kv_row<KIND>(ep, row);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    if (col[j] < N) epilogue_store<KIND>(ep, row, kv_row, col[j], acc[i][j][r], bias[j], gate[j]);
             }
         }
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int KIND, bool KTAIL>
-int launch_gemm_k(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int ldw, int m, int n, int k, const GemmEpilogue& ep) {
+// Sums the split-K partial results and applies the epilogue.  One thread per output element, columns fastest.
+template <int KIND>
+__global__ void __launch_bounds__(kThreads)
+splitk_epilogue_kernel(const float* __restrict__ partial, int splits, int M, int N, GemmEpilogue ep) {
+    const int64_t total = static_cast<int64_t>(M) * N;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t e = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; e < total; e += stride) {
+        const int row = static_cast<int>(e / N), col = static_cast<int>(e - static_cast<int64_t>(row) * N);
+        float s = 0.f;
+        for (int p = 0; p < splits; ++p) s += partial[p * total + e];
+        const float bias = ep.bias ? ep.bias[col] : 0.f;
+        const float gate = (KIND == EPI_RESID && ep.gate) ? ep.gate[col] : 1.f;
+        epilogue_store<KIND>(ep, row, epilogue_kv_row<KIND>(ep, row), col, s, bias, gate);
+    }
+}
+
+// [n, k] row-major -> fragment-major packed layout (rows past n are zero)
+__global__ void __launch_bounds__(kThreads)
+pack_weight_kernel(const bf16_t* __restrict__ w, int n, int k, bf16_t* __restrict__ wp) {
+    const int64_t chunks = static_cast<int64_t>((n + 31) >> 5) * (k >> 4) * 64;   // 16-byte chunks of the packed array
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
+        const int lane = static_cast<int>(c & 63);
+        const int64_t blk = c >> 6;
+        const int kb = static_cast<int>(blk % (k >> 4));
+        const int nb = static_cast<int>(blk / (k >> 4));
+        const int row = nb * 32 + (lane & 31), col = kb * 16 + 8 * (lane >> 5);
+        uint4 x = make_uint4(0, 0, 0, 0);
+        if (row < n) x = *reinterpret_cast<const uint4*>(w + static_cast<int64_t>(row) * k + col);
+        *reinterpret_cast<uint4*>(wp + c * 8) = x;
+    }
+}
+
+struct GemmPlan { int tn; int splits; };
+
+// Picks the wave-tile width and the K split that finish soonest under a simple model: a workgroup's time is its
+// K-steps times the MFMA time of a step (with a floor for the fixed per-step cost), workgroups run 256 at a time.
+GemmPlan plan_gemm(const regione_ctx* ctx, int m, int n, int k) {
+    if (ctx->gemm_force_tn > 0) return {ctx->gemm_force_tn, ctx->gemm_force_splits > 0 ? ctx->gemm_force_splits : 1};
+    const int m_tiles = (m + BM - 1) / BM, steps = k / BK;
+    GemmPlan best = {2, 1};
+    double best_t = 1e30;
+    for (int tn = 1; tn <= 2; ++tn) {
+        const int n_tiles = (n + 128 * tn - 1) / (128 * tn);
+        for (int s : {1, 2, 3, 4, 6, 8}) {
+            if (s > 1 && (steps / s < 8 || static_cast<size_t>(s) * m * n * sizeof(float) > ctx->gemm_part_bytes)) continue;
+            const int per = (steps + s - 1) / s;
+            const double wg_cycles = per * (tn == 2 ? 1100.0 : 700.0) + 4000.0;
+            const double rounds = ceil(static_cast<double>(m_tiles) * n_tiles * s / 256.0);
+            double t = rounds * wg_cycles;
+            if (s > 1) t += 3000.0 + 0.004 * m * n * (s + 1);
+            if (t < best_t) { best_t = t; best = {tn, s}; }
+        }
+    }
+    return best;
+}
+
+template <int TN, int KIND>
+int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, int splits, const GemmEpilogue& ep) {
+    constexpr int BN = 128 * TN;
     const int m_tiles = (m + BM - 1) / BM, n_tiles = (n + BN - 1) / BN;
     const int tiles = m_tiles * n_tiles;
     const int tiles_per_xcd = (tiles + 7) / 8;
-    const size_t lds_bytes = static_cast<size_t>(2) * (BM + BN) * BK * sizeof(bf16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, KIND, KTAIL>;
-    static bool attr_set = false;  // per instantiation
-    if (!attr_set) {
-        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(tiles_per_xcd * 8), dim3(kThreads), lds_bytes, ctx->stream,
-                       a, lda, w, ldw, m, n, k, m_tiles, n_tiles, tiles_per_xcd, ep);
+    const int steps = k / BK;
+    const int per = (steps + splits - 1) / splits;
+    const int used_splits = (steps + per - 1) / per;
+    if (used_splits > 1 && static_cast<size_t>(used_splits) * m * n * sizeof(float) > ctx->gemm_part_bytes)
+        RG_FAIL(REGIONE_ERR_WORKSPACE, "gemm: %d K-splits of a %d x %d result exceed the workspace", used_splits, m, n);
+    float* partial = used_splits > 1 ? ctx->gemm_part : nullptr;
+    hipLaunchKernelGGL((gemm_bf16_kernel<TN, KIND>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads), 0, ctx->stream,
+                       a, lda, wp, m, n, k, m_tiles, n_tiles, tiles_per_xcd, per, partial, ep);
     RG_LAUNCH_CHECK();
+    if (used_splits > 1) {
+        const int64_t total = static_cast<int64_t>(m) * n;
+        int64_t blocks = (total + kThreads - 1) / kThreads;
+        if (blocks > 256 * 16) blocks = 256 * 16;
+        hipLaunchKernelGGL((splitk_epilogue_kernel<KIND>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+                           partial, used_splits, m, n, ep);
+        RG_LAUNCH_CHECK();
+    }
     return REGIONE_OK;
 }
 
-template <int BM, int BN, int WGM, int WGN, int KIND>
-int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int ldw, int m, int n, int k, const GemmEpilogue& ep) {
-    if (k % BK) return launch_gemm_k<BM, BN, WGM, WGN, KIND, true>(ctx, a, lda, w, ldw, m, n, k, ep);
-    return launch_gemm_k<BM, BN, WGM, WGN, KIND, false>(ctx, a, lda, w, ldw, m, n, k, ep);
-}
-
 template <int KIND>
-int dispatch_tile(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int ldw, int m, int n, int k, const GemmEpilogue& ep) {
-    // Pick the tile that keeps the most CUs busy with the least padding.
-    const long t_big = static_cast<long>((m + 127) / 128) * ((n + 255) / 256);
-    if (t_big >= 200 || m > 2048) return launch_gemm<128, 256, 2, 2, KIND>(ctx, a, lda, w, ldw, m, n, k, ep);
-    const long t_mid = static_cast<long>((m + 127) / 128) * ((n + 127) / 128);
-    if (t_mid >= 160 || m > 64) return launch_gemm<128, 128, 2, 2, KIND>(ctx, a, lda, w, ldw, m, n, k, ep);
-    return launch_gemm<64, 128, 2, 2, KIND>(ctx, a, lda, w, ldw, m, n, k, ep);
+int dispatch(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, const GemmEpilogue& ep) {
+    const GemmPlan p = plan_gemm(ctx, m, n, k);
+    if (p.tn == 1) return launch_gemm<1, KIND>(ctx, a, lda, wp, m, n, k, p.splits, ep);
+    return launch_gemm<2, KIND>(ctx, a, lda, wp, m, n, k, p.splits, ep);
 }
 
 }  // namespace
 
-int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w, int ldw, int m, int n, int k, const GemmEpilogue& ep) {
+int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, const GemmEpilogue& ep) {
     if (m <= 0 || n <= 0) return REGIONE_OK;
-    if (k <= 0 || (k & 7) || (lda & 7) || (ldw & 7)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "gemm: k=%d lda=%d ldw=%d must be positive multiples of 8", k, lda, ldw);
-    if (!rg_aligned16(a) || !rg_aligned16(w)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
+    if (k <= 0 || (k % BK) || (lda & 7)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "gemm: k=%d must be a positive multiple of 64 and lda=%d of 8", k, lda);
+    if (!rg_aligned16(a) || !rg_aligned16(wp)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
     ProfScope prof(ctx, REGIONE_PROF_GEMM);
     switch (ep.kind) {
-        case EPI_PLAIN: return dispatch_tile<EPI_PLAIN>(ctx, a, lda, w, ldw, m, n, k, ep);
-        case EPI_QKV: return dispatch_tile<EPI_QKV>(ctx, a, lda, w, ldw, m, n, k, ep);
-        case EPI_RESID: return dispatch_tile<EPI_RESID>(ctx, a, lda, w, ldw, m, n, k, ep);
+        case EPI_PLAIN: return dispatch<EPI_PLAIN>(ctx, a, lda, wp, m, n, k, ep);
+        case EPI_QKV: return dispatch<EPI_QKV>(ctx, a, lda, wp, m, n, k, ep);
+        case EPI_RESID: return dispatch<EPI_RESID>(ctx, a, lda, wp, m, n, k, ep);
     }
     RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm: bad epilogue kind %d", ep.kind);
 }
 
-extern "C" int regione_linear(regione_ctx* ctx, const void* x, const void* w, const float* b_opt,
+extern "C" int64_t regione_packed_weight_elems(int32_t n, int32_t k) {
+    if (n <= 0 || k <= 0) return 0;
+    return static_cast<int64_t>((n + 31) / 32) * 32 * k;
+}
+
+extern "C" int regione_pack_weight(regione_ctx* ctx, const void* w, int32_t n, int32_t k, void* w_packed) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "pack_weight: null context");
+    if (n <= 0 || k <= 0 || (k % BK)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "pack_weight: n=%d, k=%d (k must be a multiple of 64)", n, k);
+    if (!w || !w_packed || !rg_aligned16(w) || !rg_aligned16(w_packed)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "pack_weight: null or unaligned tensor");
+    if (w == w_packed) RG_FAIL(REGIONE_ERR_INVALID_ARG, "pack_weight: cannot pack in place");
+    const int64_t chunks = regione_packed_weight_elems(n, k) / 8;
+    int64_t blocks = (chunks + kThreads - 1) / kThreads;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(pack_weight_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+                       static_cast<const bf16_t*>(w), n, k, static_cast<bf16_t*>(w_packed));
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+extern "C" int regione_tune_gemm(regione_ctx* ctx, int32_t wave_tile_blocks, int32_t k_splits) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "tune_gemm: null context");
+    if (wave_tile_blocks < 0 || wave_tile_blocks > 2 || k_splits < 0 || k_splits > 16) RG_FAIL(REGIONE_ERR_INVALID_ARG, "tune_gemm: wave_tile_blocks in 0..2, k_splits in 0..16");
+    ctx->gemm_force_tn = wave_tile_blocks;
+    ctx->gemm_force_splits = k_splits;
+    return REGIONE_OK;
+}
+
+extern "C" int regione_linear(regione_ctx* ctx, const void* x, const void* w_packed, const float* b_opt,
                               int32_t m, int32_t n, int32_t k, int32_t act, int32_t out_dtype, void* y) {
     if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear: null context");
     if (m < 0 || n <= 0 || k <= 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear: m=%d n=%d k=%d", m, n, k);
     if (act != REGIONE_ACT_NONE && act != REGIONE_ACT_GELU_TANH) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear: bad act %d", act);
     if (out_dtype != REGIONE_BF16 && out_dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear: bad out_dtype %d", out_dtype);
-    if (k % 8) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "linear: k=%d must be a multiple of 8", k);
+    if (k % BK) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "linear: k=%d must be a multiple of 64", k);
     if (m == 0) return REGIONE_OK;
-    if (!x || !w || !y) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear: null tensor");
+    if (!x || !w_packed || !y) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear: null tensor");
     GemmEpilogue ep = {};
     ep.kind = EPI_PLAIN; ep.bias = b_opt; ep.act = act; ep.act_from = 0;
     ep.y = y; ep.ldy = n; ep.y_f32 = out_dtype == REGIONE_FP32;
-    return rg_gemm(ctx, static_cast<const bf16_t*>(x), k, static_cast<const bf16_t*>(w), k, m, n, k, ep);
+    return rg_gemm(ctx, static_cast<const bf16_t*>(x), k, static_cast<const bf16_t*>(w_packed), m, n, k, ep);
 }

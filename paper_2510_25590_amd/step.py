@@ -86,11 +86,11 @@ class RegionStepWorkload:
         self._keep = []
         self.weights = rg.BlockWeights()
         for name, w in zip(("txt", "img") if cfg.kind == "double" else ("img",), hst["streams"]):
-            t = {k: (bf(a) if k.startswith("w_") else f32(a)) for k, a in w.items()}
+            t = {k: (rg.pack_weight(self.ctx, bf(a)) if k.startswith("w_") else f32(a)) for k, a in w.items()}
             self._keep.append(t)
             setattr(self.weights, name, rg.make_stream_weights(t))
         self.block_type = rg.BLOCK_DOUBLE if cfg.kind == "double" else rg.BLOCK_SINGLE
-        self.w_head, self.b_head = bf(hst["w_head"]), f32(hst["b_head"])
+        self.w_head, self.b_head = rg.pack_weight(self.ctx, bf(hst["w_head"])), f32(hst["b_head"])
         dev = "cuda"
         self.k_cache = torch.zeros((self.n_all, cfg.heads, cfg.head_dim), dtype=torch.bfloat16, device=dev)
         self.v_cache = torch.zeros_like(self.k_cache)

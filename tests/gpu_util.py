@@ -50,26 +50,27 @@ def assert_close(got: np.ndarray, want: np.ndarray, what: str, max_abs=MAX_ABS, 
     return ma, mr
 
 
-def stream_to_device(w: dict):
-    """Weights dict from inputs.stream_weights (bf16-rounded float32) -> (dict of CUDA tensors, StreamWeights)."""
+def stream_to_device(w: dict, ctx):
+    """Weights dict from inputs.stream_weights (bf16-rounded float32) -> (dict of CUDA tensors, StreamWeights).
+    Linear weights are packed into the library's layout."""
     t = {}
     for name, arr in w.items():
         if name.startswith("w_"):
-            t[name] = dev(arr, "bf16")
+            t[name] = rg.pack_weight(ctx, dev(arr, "bf16"))
         else:
             t[name] = torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).cuda()
     return t, rg.make_stream_weights(t)
 
 
-def block_to_device(streams, kind):
+def block_to_device(streams, kind, ctx):
     keep = []
     bw = rg.BlockWeights()
     if kind == "double":
-        t0, s0 = stream_to_device(streams[0]); t1, s1 = stream_to_device(streams[1])
+        t0, s0 = stream_to_device(streams[0], ctx); t1, s1 = stream_to_device(streams[1], ctx)
         bw.txt, bw.img = s0, s1
         keep = [t0, t1]
     else:
-        t1, s1 = stream_to_device(streams[0])
+        t1, s1 = stream_to_device(streams[0], ctx)
         bw.img = s1
         keep = [t1]
     return bw, keep

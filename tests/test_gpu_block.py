@@ -30,7 +30,7 @@ def test_config1_block_all_modes(kind, h_dtype):
     want_mask = inputs.rect_mask(rng, 16, 16, 6, 6)
     e = np.nonzero(want_mask)[0].astype(np.int32)
     ctx = rg.Context(hidden, heads, d, mlp, n_all, 4096)
-    bw, keep = block_to_device(streams, kind)
+    bw, keep = block_to_device(streams, kind, ctx)
     btype = rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE
     hcode = rg.BF16 if h_dtype == "bf16" else rg.FP32
     tdt = torch.bfloat16 if h_dtype == "bf16" else torch.float32
@@ -101,7 +101,7 @@ def test_config2_block_region_forward_sampled(kind):
     h_now = inputs.bf16_round((h_store[rows] + 0.05 * rng.standard_normal((len(rows), hidden))).astype(np.float32))
 
     ctx = rg.Context(hidden, heads, d, mlp, n_all, 4096)
-    bw, keep = block_to_device(streams, kind)
+    bw, keep = block_to_device(streams, kind, ctx)
     btype = rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE
     kc = torch.zeros((n_all, heads, d), dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
     out_full = torch.empty((n_all, hidden), dtype=torch.bfloat16, device="cuda")

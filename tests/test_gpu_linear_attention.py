@@ -19,8 +19,8 @@ def ctx():
     c.close()
 
 
-@pytest.mark.parametrize("m,n,k", [(1, 8, 8), (37, 100, 64), (129, 257, 72), (300, 520, 256), (64, 64, 64),
-                                   (819, 1000, 512), (130, 3072, 1024), (33, 96, 3072)])
+@pytest.mark.parametrize("m,n,k", [(1, 8, 64), (37, 100, 64), (129, 257, 128), (300, 520, 256), (64, 64, 64),
+                                   (819, 1000, 512), (130, 3072, 1024), (33, 96, 3072), (820, 640, 3072), (700, 256, 6144)])
 @pytest.mark.parametrize("act", [rg.ACT_NONE, rg.ACT_GELU_TANH])
 def test_linear_matches_oracle(ctx, m, n, k, act):
     rng = np.random.default_rng(1000 + m + n + k)
@@ -31,9 +31,10 @@ def test_linear_matches_oracle(ctx, m, n, k, act):
     if act == rg.ACT_GELU_TANH:
         want = orc.gelu_tanh(want)
     db = torch.from_numpy(b).cuda()
+    wp = rg.pack_weight(ctx, dev(w, "bf16"))
     for out_dtype, tdt in ((rg.FP32, torch.float32), (rg.BF16, torch.bfloat16)):
         y = torch.full((m + 1, n), 77.0, dtype=tdt, device="cuda")
-        rg.regione_linear(ctx, dev(x, "bf16"), dev(w, "bf16"), db, m, n, k, act, out_dtype, y)
+        rg.regione_linear(ctx, dev(x, "bf16"), wp, db, m, n, k, act, out_dtype, y)
         got = host(y)
         assert np.all(got[m] == 77.0)                       # the row after the last is untouched
         if out_dtype == rg.FP32:
@@ -42,8 +43,16 @@ def test_linear_matches_oracle(ctx, m, n, k, act):
             assert_close(got[:m], want, f"linear bf16 {m}x{n}x{k}")
     # no bias
     y = torch.empty((m, n), dtype=torch.float32, device="cuda")
-    rg.regione_linear(ctx, dev(x, "bf16"), dev(w, "bf16"), None, m, n, k, rg.ACT_NONE, rg.FP32, y)
+    rg.regione_linear(ctx, dev(x, "bf16"), wp, None, m, n, k, rg.ACT_NONE, rg.FP32, y)
     assert_close(host(y), orc.linear(x, w, None), "linear no bias", max_abs=2e-4, mean_rel_tol=1e-5)
+    # every wave-tile width and K split gives the same result
+    for tn, splits in ((1, 1), (2, 1), (1, 3), (2, 2), (2, 4)):
+        rg.regione_tune_gemm(ctx, tn, splits)
+        y2 = torch.full((m + 1, n), 77.0, dtype=torch.float32, device="cuda")
+        rg.regione_linear(ctx, dev(x, "bf16"), wp, db, m, n, k, act, rg.FP32, y2)
+        assert np.all(host(y2)[m] == 77.0)
+        assert_close(host(y2)[:m], want, f"linear tn={tn} splits={splits}", max_abs=2e-4, mean_rel_tol=1e-5)
+    rg.regione_tune_gemm(ctx, 0, 0)
 
 
 def test_linear_integer_values_are_exact(ctx):
@@ -52,7 +61,7 @@ def test_linear_integer_values_are_exact(ctx):
     x = rng.integers(-4, 5, size=(200, 192)).astype(np.float32)
     w = rng.integers(-4, 5, size=(333, 192)).astype(np.float32)
     y = torch.empty((200, 333), dtype=torch.float32, device="cuda")
-    rg.regione_linear(ctx, dev(x, "bf16"), dev(w, "bf16"), None, 200, 333, 192, rg.ACT_NONE, rg.FP32, y)
+    rg.regione_linear(ctx, dev(x, "bf16"), rg.pack_weight(ctx, dev(w, "bf16")), None, 200, 333, 192, rg.ACT_NONE, rg.FP32, y)
     assert np.array_equal(host(y), (x.astype(np.int64) @ w.astype(np.int64).T).astype(np.float32))
 
 
