@@ -40,67 +40,162 @@ struct AttnArgs {
     int n_q_pad;
 };
 
-template <int D> struct Swz {
-    static constexpr int CPR = D / 8;  // 16-byte chunks per row
-    // K tile: spread the rows of one fragment read (same logical chunk, consecutive rows) over all banks
-    __device__ static __forceinline__ int k(int row, int chunk) { return chunk ^ (row & (CPR - 1)); }
-    // V tile: a transposing read touches 4 consecutive keys x 4 consecutive chunks per lane half
-    __device__ static __forceinline__ int v(int row, int chunk) {
-        return D == 128 ? (chunk ^ ((row & 3) << 2)) : (chunk ^ (((row >> 1) & 1) << 2));
-    }
-};
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // native 16-byte vector (plain loads/stores, no memcpy)
 
-// Global -> register -> LDS staging of one 64-key tile.  Thread t owns 16-byte chunk t%CPR of rows t/CPR + i*(256/CPR).
-template <int D>
-__device__ __forceinline__ void kv_tile_load(const AttnArgs& a, int head, int key0, int n_keys,
-                                             uint4 (&kr)[KT * (D / 8) / kThreads], uint4 (&vr)[KT * (D / 8) / kThreads]) {
-    constexpr int CPR = D / 8;
-    constexpr int PER_THREAD = KT * CPR / kThreads;
-    const int r0 = threadIdx.x / CPR, c = threadIdx.x % CPR;
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-        int key = key0 + r0 + i * (kThreads / CPR);
-        key = key < n_keys ? key : n_keys - 1;  // tail rows repeat a valid row; their scores are masked
-        const bool fresh = key < a.n0;
-        int64_t row = fresh ? key : key - a.n0;
-        if (!fresh && a.idx1) row = a.idx1[row];
-        const int64_t off = row * (fresh ? a.ldkv0 : a.ldkv1) + head * D + c * 8;
-        const bf16_t* kb = fresh ? a.k0 : a.k1;
-        const bf16_t* vb = fresh ? a.v0 : a.v1;
-        kr[i] = *reinterpret_cast<const uint4*>(kb + off);
-        vr[i] = *reinterpret_cast<const uint4*>(vb + off);
-    }
+// LDS swizzles (16-byte chunk index -> physical chunk).  K tile: the 16 rows read together with one logical chunk
+// must cover all 64 banks once; rows are 256 bytes (D = 128) or 128 bytes (D = 64).  V tile: a transposing read
+// touches, per lane half, 4 consecutive keys x 4 consecutive chunks.
+template <int D> __device__ __forceinline__ int k_swz(int row, int chunk) {
+    return D == 128 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7));
 }
-
-template <int D>
-__device__ __forceinline__ void kv_tile_store(bf16_t* k_lds, bf16_t* v_lds,
-                                              const uint4 (&kr)[KT * (D / 8) / kThreads], const uint4 (&vr)[KT * (D / 8) / kThreads]) {
-    constexpr int CPR = D / 8;
-    constexpr int PER_THREAD = KT * CPR / kThreads;
-    const int r0 = threadIdx.x / CPR, c = threadIdx.x % CPR;
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const int r = r0 + i * (kThreads / CPR);
-        *reinterpret_cast<uint4*>(k_lds + r * D + (Swz<D>::k(r, c) << 3)) = kr[i];
-        *reinterpret_cast<uint4*>(v_lds + r * D + (Swz<D>::v(r, c) << 3)) = vr[i];
-    }
+template <int D> __device__ __forceinline__ int v_swz(int row, int chunk) {
+    return D == 128 ? (chunk ^ ((row & 3) << 2)) : (chunk ^ (((row >> 1) & 1) << 2));
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <int D, int QB>
+// Global loads of one 64-key tile into staging registers.  Thread t owns 16-byte chunk t % CPR of rows t / CPR + i * (256 / CPR).
+// INDEXED: the cache rows go through the index list (all the index loads are issued before the first dependent load).
+template <int D, bool INDEXED>
+__device__ __forceinline__ void kv_tile_load(const AttnArgs& a, int head_off, int key0, int n_keys,
+                                             u32x4 (&kr)[KT * (D / 8) / kThreads], u32x4 (&vr)[KT * (D / 8) / kThreads]) {
+    constexpr int CPR = D / 8;
+    constexpr int PER_THREAD = KT * CPR / kThreads;
+    const int r0 = threadIdx.x / CPR;
+    int key[PER_THREAD];
+    int64_t row[PER_THREAD];
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+        const int kx = key0 + r0 + i * (kThreads / CPR);
+        key[i] = kx < n_keys ? kx : n_keys - 1;  // tail rows repeat a valid row; their scores are masked
+        row[i] = key[i] < a.n0 ? key[i] : key[i] - a.n0;
+        if (INDEXED) { if (key[i] >= a.n0) row[i] = a.idx1[row[i]]; }
+    }
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+        const bool fresh = key[i] < a.n0;
+        const int64_t off = row[i] * (fresh ? a.ldkv0 : a.ldkv1) + head_off;
+        kr[i] = *reinterpret_cast<const u32x4*>((fresh ? a.k0 : a.k1) + off);
+        vr[i] = *reinterpret_cast<const u32x4*>((fresh ? a.v0 : a.v1) + off);
+    }
+}
+
+// One 64-key tile for the 32 queries of a wave.  STAGE selects the LDS buffer (compile time, so that every LDS
+// address is a per-lane constant plus an immediate).
+template <int D, int STAGE>
+__device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys, float c, int lh,
+                                          const int (&koff)[D / 16], const int (&voff)[D / 32], const bf16x8 (&qf)[D / 16],
+                                          f32x16 (&o)[D / 32], float& m_run, float& l_run) {
+    constexpr int DB = D / 32, KK = D / 16, TILE = KT * D;
+    const bf16_t* kt = smem + STAGE * 2 * TILE;
+    const bf16_t* vt = kt + TILE;
+
+    // ---- S^T = K Q^T for the two 32-key blocks: K fragments are fetched half a tile ahead of their MFMAs
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+    // K fragments are fetched two k-steps (four reads) ahead of their MFMAs
+    constexpr int PF = 2;
+    bf16x8 kf[KK][2];
+#pragma unroll
+    for (int kk = 0; kk < PF; ++kk)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) kf[kk][kb] = *reinterpret_cast<const bf16x8*>(kt + koff[kk] + kb * 32 * D);
+    s16x4 vlo[DB], vhi[DB];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        if (kk + PF < KK) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) kf[kk + PF][kb] = *reinterpret_cast<const bf16x8*>(kt + koff[kk + PF] + kb * 32 * D);
+        } else if (kk + PF == KK) {
+            // first group of V^T fragments: in flight during the last MFMAs of S and the softmax
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                vlo[db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vt + voff[db]));
+                vhi[db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vt + voff[db] + 8 * D));
+            }
+        }
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][kb], qf[kk], s[kb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- online softmax on raw scores; accumulator r of block kb is key t*64 + kb*32 + 8*(r/4) + 4*lh + r%4
+    if ((t + 1) * KT > n_keys) {   // the last tile may run past the key list
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (t * KT + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3) >= n_keys) s[kb][r] = -INFINITY;
+    }
+    float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);     // finite: every tile holds at least one live key
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // wave-uniform: the running maximum rarely moves after the first tiles
+        const float alpha = fast_exp2((m_run - m_new) * c);
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        m_run = m_new;
+    }
+    const float neg_mc = -m_new * c;
+    float psum = 0.f;
+    bf16x8 pf[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float p = fast_exp2(__builtin_fmaf(s[kb][8 * j + e], c, neg_mc));
+                psum += p;
+                pf[kb][j][e] = static_cast<__bf16>(p);
+            }
+    l_run += psum;
+
+    // ---- O^T += V^T P^T, one (kb, j) group of DB MFMAs at a time, the next group's fragments in flight
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int kb = g >> 1, j = g & 1;
+        bf16x8 vf[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const s16x8 both = {vlo[db][0], vlo[db][1], vlo[db][2], vlo[db][3], vhi[db][0], vhi[db][1], vhi[db][2], vhi[db][3]};
+            vf[db] = __builtin_bit_cast(bf16x8, both);
+        }
+        if (g < 3) {
+            const int row_off = (((g + 1) >> 1) * 32 + 16 * ((g + 1) & 1)) * D;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                vlo[db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vt + voff[db] + row_off));
+                vhi[db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vt + voff[db] + row_off + 8 * D));
+            }
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db], pf[kb][j], o[db], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int D, bool INDEXED>
 __global__ void __launch_bounds__(kThreads)
 attn_kvcache_kernel(AttnArgs a) {
     constexpr int DB = D / 32;   // 32-wide d blocks of the output
     constexpr int KK = D / 16;   // k-steps of the first product
-    __shared__ __attribute__((aligned(16))) bf16_t k_lds[2][KT * D];
-    __shared__ __attribute__((aligned(16))) bf16_t v_lds[2][KT * D];
+    constexpr int CPR = D / 8, LD_N = KT * CPR / kThreads, TILE = KT * D;
+    __shared__ __attribute__((aligned(16))) bf16_t smem[2 * 2 * TILE];   // two stages of (K tile, V tile)
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
     const int head = blockIdx.y;
     const int split = blockIdx.z;
-    const int q_base = blockIdx.x * (QB * 128) + wave * (QB * 32);
+    const int q_base = blockIdx.x * 128 + wave * 32;
     const int n_keys = a.n0 + a.n1;
     const int n_tiles = (n_keys + KT - 1) / KT;
     const int tile_begin = split * a.tiles_per_split;
@@ -108,166 +203,106 @@ attn_kvcache_kernel(AttnArgs a) {
     tile_end = tile_end < n_tiles ? tile_end : n_tiles;
 
     // Q fragments ("B" operand): lane holds query l32 of the block, d = kk*16 + 8*lh + 0..7
-    bf16x8 qf[QB][KK];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        int qrow = q_base + qb * 32 + l32;
+    bf16x8 qf[KK];
+    {
+        int qrow = q_base + l32;
         qrow = qrow < a.n_q ? qrow : a.n_q - 1;
         const bf16_t* qp = a.q + static_cast<int64_t>(qrow) * a.ldq + head * D + 8 * lh;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+        for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
     }
 
-    f32x16 o[QB][DB];
-    float m_run[QB], l_run[QB];
+    // per-lane LDS offsets (elements) of the fragment reads
+    int koff[KK], voff[DB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        m_run[qb] = -INFINITY;
-        l_run[qb] = 0.f;
+    for (int kk = 0; kk < KK; ++kk) koff[kk] = l32 * D + (k_swz<D>(l32, kk * 2 + lh) << 3);
+    {
+        const int src_key = 4 * lh + ((lane & 15) >> 2);      // row this lane addresses in a transposing read (plus a multiple of 8)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
+        for (int db = 0; db < DB; ++db) {
+            const int d_src = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);   // 4 consecutive d = 8 bytes
+            voff[db] = src_key * D + (v_swz<D>(src_key, d_src >> 3) << 3) + (d_src & 7);
+        }
     }
+    // staging: LDS store offsets of this thread's chunks
+    int ks_off[LD_N], vs_off[LD_N];
+#pragma unroll
+    for (int i = 0; i < LD_N; ++i) {
+        const int r = threadIdx.x / CPR + i * (kThreads / CPR), cc = threadIdx.x % CPR;
+        ks_off[i] = r * D + (k_swz<D>(r, cc) << 3);
+        vs_off[i] = TILE + r * D + (v_swz<D>(r, cc) << 3);
+    }
+    const int head_off = head * D + (threadIdx.x % CPR) * 8;
 
-    constexpr int LD_N = KT * (D / 8) / kThreads;
-    uint4 kr[LD_N], vr[LD_N];
+    f32x16 o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const float c = a.scale_log2e;
+
+    u32x4 kr[LD_N], vr[LD_N];
     if (tile_begin < tile_end) {
-        kv_tile_load<D>(a, head, tile_begin * KT, n_keys, kr, vr);
-        kv_tile_store<D>(k_lds[0], v_lds[0], kr, vr);
+        kv_tile_load<D, INDEXED>(a, head_off, tile_begin * KT, n_keys, kr, vr);
+#pragma unroll
+        for (int i = 0; i < LD_N; ++i) {
+            *reinterpret_cast<u32x4*>(smem + ks_off[i]) = kr[i];
+            *reinterpret_cast<u32x4*>(smem + vs_off[i]) = vr[i];
+        }
     }
     __syncthreads();
 
-    for (int t = tile_begin; t < tile_end; ++t) {
-        const int cur = (t - tile_begin) & 1;
-        // the last iteration re-loads its own tile into the idle buffer: unconditional code keeps the staging registers in VGPRs
-        kv_tile_load<D>(a, head, (t + 1 < tile_end ? t + 1 : t) * KT, n_keys, kr, vr);
-        const bf16_t* kt = k_lds[cur];
-        const bf16_t* vt = v_lds[cur];
-
-        // ---- S^T = K Q^T for the two 32-key blocks of the tile
-        f32x16 s[QB][2];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[qb][kb][r] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            bf16x8 kf[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const int row = kb * 32 + l32;
-                kf[kb] = *reinterpret_cast<const bf16x8*>(kt + row * D + (Swz<D>::k(row, kk * 2 + lh) << 3));
-            }
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-                    s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[qb][kk], s[qb][kb], 0, 0, 0);
-        }
-
-        // ---- online softmax; accumulator r of block kb is key  t*64 + kb*32 + 8*(r/4) + 4*lh + r%4
-        const bool tail = (t + 1) * KT > n_keys;
-        bf16x8 pf[QB][2][2];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float x = s[qb][kb][r] * a.scale_log2e;
-                    if (tail) {
-                        const int key = t * KT + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                        if (key >= n_keys) x = -INFINITY;
-                    }
-                    s[qb][kb][r] = x;
-                    mx = fmaxf(mx, x);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[qb], mx);   // finite: every tile holds at least one live key
-            const float alpha = fast_exp2(m_run[qb] - m_new);
-            m_run[qb] = m_new;
-            float psum = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float p = fast_exp2(s[qb][kb][8 * j + e] - m_new);
-                        psum += p;
-                        pf[qb][kb][j][e] = static_cast<__bf16>(p);
-                    }
-            l_run[qb] = l_run[qb] * alpha + psum;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
-        }
-
-        // ---- O^T += V^T P^T
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int key_base = kb * 32 + 16 * j + 4 * lh;      // slots 0..3: key_base + s ; slots 4..7: key_base + 8 + (s-4)
-                const int src_key = key_base + ((lane & 15) >> 2);  // source row this lane addresses in the transposing read
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const int d_src = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // 4 consecutive d = 8 bytes
-                    const int chunk = d_src >> 3, within = d_src & 7;
-                    const bf16_t* p0 = vt + src_key * D + (Swz<D>::v(src_key, chunk) << 3) + within;
-                    const bf16_t* p1 = vt + (src_key + 8) * D + (Swz<D>::v(src_key + 8, chunk) << 3) + within;
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p1));
-                    const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-                        o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][kb][j], o[qb][db], 0, 0, 0);
-                }
-            }
-
-        kv_tile_store<D>(k_lds[cur ^ 1], v_lds[cur ^ 1], kr, vr);
-        __syncthreads();
+    // Two tiles per trip so that the LDS stage is a compile-time constant.  The loads of the next tile are issued
+    // first (pinned there by the scheduling barrier) and land in the idle stage after this tile's MFMAs; the last
+    // tile re-loads itself, which keeps the code unconditional and the staging values in registers.
+#define RG_ATTN_TILE(T, STAGE)                                                                            \
+    {                                                                                                     \
+        const int t_ = (T);                                                                               \
+        kv_tile_load<D, INDEXED>(a, head_off, (t_ + 1 < tile_end ? t_ + 1 : t_) * KT, n_keys, kr, vr);    \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        attn_tile<D, STAGE>(smem, t_, n_keys, c, lh, koff, voff, qf, o, m_run, l_run);                    \
+        _Pragma("unroll") for (int i = 0; i < LD_N; ++i) {                                                \
+            *reinterpret_cast<u32x4*>(smem + (1 - STAGE) * 2 * TILE + ks_off[i]) = kr[i];                 \
+            *reinterpret_cast<u32x4*>(smem + (1 - STAGE) * 2 * TILE + vs_off[i]) = vr[i];                 \
+        }                                                                                                 \
+        __syncthreads();                                                                                  \
     }
+    for (int t = tile_begin; t < tile_end; t += 2) {
+        RG_ATTN_TILE(t, 0)
+        if (t + 1 < tile_end) RG_ATTN_TILE(t + 1, 1)
+    }
+#undef RG_ATTN_TILE
 
     // ---- finish: O^T accumulator r of d-block db: d = db*32 + 8*(r/4) + 4*lh + r%4, query = l32
+    const int qrow = q_base + l32;
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (qrow >= a.n_q) return;
+    if (a.splits == 1) {
+        const float inv = 1.0f / l_tot;
+        bf16_t* op = a.out + static_cast<int64_t>(qrow) * a.ldo + head * D;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int qrow = q_base + qb * 32 + l32;
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
-        if (qrow >= a.n_q) continue;
-        if (a.splits == 1) {
-            const float inv = 1.0f / l_tot;
-            bf16_t* op = a.out + static_cast<int64_t>(qrow) * a.ldo + head * D;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+            for (int g = 0; g < 4; ++g) {
+                const int d = db * 32 + 8 * g + 4 * lh;
+                bf16x4 pk;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int d = db * 32 + 8 * g + 4 * lh;
-                    bf16x4 pk;
+                for (int e = 0; e < 4; ++e) pk[e] = static_cast<__bf16>(o[db][4 * g + e] * inv);
+                *reinterpret_cast<bf16x4*>(op + d) = pk;
+            }
+    } else {
+        // partial result: unnormalised O, running max (raw score domain) and sum
+        float* pp = a.part + ((static_cast<int64_t>(split) * a.heads + head) * a.n_q_pad + qrow) * (D + 2);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) pk[e] = static_cast<__bf16>(o[qb][db][4 * g + e] * inv);
-                    *reinterpret_cast<bf16x4*>(op + d) = pk;
-                }
-        } else {
-            // partial result: unnormalised O, running max (log2 domain) and sum
-            float* pp = a.part + ((static_cast<int64_t>(split) * a.heads + head) * a.n_q_pad + qrow) * (D + 2);
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int d = db * 32 + 8 * g + 4 * lh;
-                    float4 f = make_float4(o[qb][db][4 * g], o[qb][db][4 * g + 1], o[qb][db][4 * g + 2], o[qb][db][4 * g + 3]);
-                    *reinterpret_cast<float2*>(pp + d) = make_float2(f.x, f.y);
-                    *reinterpret_cast<float2*>(pp + d + 2) = make_float2(f.z, f.w);
-                }
-            if (lh == 0) { pp[D] = m_run[qb]; pp[D + 1] = l_tot; }
-        }
+            for (int g = 0; g < 4; ++g) {
+                const int d = db * 32 + 8 * g + 4 * lh;
+                *reinterpret_cast<float2*>(pp + d) = make_float2(o[db][4 * g], o[db][4 * g + 1]);
+                *reinterpret_cast<float2*>(pp + d + 2) = make_float2(o[db][4 * g + 2], o[db][4 * g + 3]);
+            }
+        if (lh == 0) { pp[D] = m_run * c; pp[D + 1] = l_tot; }   // maximum in the log2 domain, as the merge kernel expects
     }
 }
 
@@ -306,14 +341,14 @@ attn_combine_kernel(const float* __restrict__ part, int splits, int heads, int n
     *reinterpret_cast<bf16x4*>(out + static_cast<int64_t>(qrow) * ldo + head * D + 4 * g) = pk;
 }
 
-template <int D, int QB>
+template <int D>
 int launch_attention(regione_ctx* ctx, AttnArgs a) {
-    const int q_tiles = (a.n_q + QB * 128 - 1) / (QB * 128);
+    const int q_tiles = (a.n_q + 127) / 128;
     const int n_tiles = (a.n0 + a.n1 + KT - 1) / KT;
     // split the key range when the (query tile, head) grid would leave most CUs idle
     int splits = 1;
     const int wgs = q_tiles * a.heads;
-    while (wgs * splits < 256 && splits * 2 <= n_tiles / 8 && splits < 16) splits *= 2;
+    while (wgs * splits < 512 && splits * 2 <= n_tiles / 8 && splits < 8) splits *= 2;   // two workgroups fit a CU
     a.n_q_pad = a.n_q;
     if (splits > 1) {
         const size_t need = static_cast<size_t>(splits) * a.heads * a.n_q_pad * (D + 2) * sizeof(float);
@@ -322,7 +357,8 @@ int launch_attention(regione_ctx* ctx, AttnArgs a) {
     a.splits = splits;
     a.tiles_per_split = (n_tiles + splits - 1) / splits;
     a.part = ctx->attn_part;
-    hipLaunchKernelGGL((attn_kvcache_kernel<D, QB>), dim3(q_tiles, a.heads, splits), dim3(kThreads), 0, ctx->stream, a);
+    if (a.idx1) hipLaunchKernelGGL((attn_kvcache_kernel<D, true>), dim3(q_tiles, a.heads, splits), dim3(kThreads), 0, ctx->stream, a);
+    else hipLaunchKernelGGL((attn_kvcache_kernel<D, false>), dim3(q_tiles, a.heads, splits), dim3(kThreads), 0, ctx->stream, a);
     RG_LAUNCH_CHECK();
     if (splits > 1) {
         const int64_t total = static_cast<int64_t>(a.n_q) * a.heads * (D / 4);
@@ -352,8 +388,8 @@ int rg_attention(regione_ctx* ctx, const bf16_t* q, int ldq, int n_q,
     a.heads = heads;
     a.scale_log2e = (scale > 0.f ? scale : 1.0f / sqrtf(static_cast<float>(d))) * 1.4426950408889634f;
     a.out = out; a.ldo = ldo;
-    if (d == 128) return launch_attention<128, 1>(ctx, a);
-    return launch_attention<64, 1>(ctx, a);
+    if (d == 128) return launch_attention<128>(ctx, a);
+    return launch_attention<64>(ctx, a);
 }
 
 extern "C" int regione_attn_kvcache(regione_ctx* ctx, const void* q, int32_t n_q,

@@ -68,6 +68,7 @@ enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESID = 2 };
 
 struct GemmEpilogue {
     int kind;            // EPI_*
+    int vec_ok;          // set by rg_gemm: the wide (8 columns per lane) epilogue may be used
     const float* bias;   // [N] or null
     int act;             // REGIONE_ACT_* (applied to columns >= act_from)
     int act_from;

@@ -9,11 +9,12 @@
 //  * Weights never go through LDS.  regione_pack_weight stores them once in the register layout of
 //    the "B" operand of v_mfma_f32_32x32x16_bf16: block (n/32, k/16) is 64 lanes x 16 bytes, lane l
 //    holding W[32*(n/32) + l%32][16*(k/16) + 8*(l/32) .. +8].  A wave reads a fragment as one fully
-//    coalesced 1 KiB load straight into VGPRs, two K-steps ahead of its use.
+//    coalesced 1 KiB load straight into VGPRs, three K-steps ahead of its use.
 //  * The four waves of a workgroup split the tile along N only (wave tile 128 x 32*TN), so no weight
 //    fragment is needed by two waves; the activation tile (128 x 64 per K-step) is shared through
 //    LDS, XOR-swizzled so that ds_read_b128 of a fragment is conflict free, double buffered, its
-//    global loads two K-steps ahead.
+//    global loads three K-steps ahead (L2 latency under load is about a microsecond, i.e.
+//    more than two K-steps of matrix-core work).
 //  * Few row tiles means few workgroups: GEMMs with a narrow N are split along K over blockIdx.y
 //    into float partial sums, merged by a second kernel that applies the epilogue.
 //  * Workgroups are numbered so that each XCD (blockIdx.x % 8) owns a contiguous range of weight
@@ -33,6 +34,9 @@ constexpr int TM = BM / 32;
 constexpr int BK = 64;        // k elements per step
 constexpr int kThreads = 256;
 constexpr int A_PER_THREAD = BM * 8 / kThreads;  // 16-byte chunks of the A tile per thread
+constexpr int DEPTH = 3;      // K-steps between a global load and its use
+constexpr int NSETS = DEPTH + 1;
+
 
 __device__ __forceinline__ float gelu_tanh_f32(float x) {
     // 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
@@ -73,6 +77,69 @@ __device__ __forceinline__ void epilogue_store(const GemmEpilogue& ep, int row, 
         const int64_t o = static_cast<int64_t>(row) * ep.ldy + col;
         if (ep.y_f32) static_cast<float*>(ep.y)[o] = val;
         else static_cast<bf16_t*>(ep.y)[o] = f32_to_bf16(val);
+    }
+}
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+__device__ __forceinline__ void store8(void* base, int64_t elem, int as_f32, const float (&v)[8]) {
+    if (as_f32) {
+        float* p = static_cast<float*>(base) + elem;
+        *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]};
+        *reinterpret_cast<f32x4*>(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
+    } else {
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(v[e]);
+        *reinterpret_cast<bf16x8*>(static_cast<bf16_t*>(base) + elem) = o;
+    }
+}
+
+// Epilogue for eight consecutive columns col0..col0+7 of one row (all inside N, col0 a multiple of 8):
+// 16- or 32-byte loads and stores only.
+template <int KIND>
+__device__ __forceinline__ void epilogue_store8(const GemmEpilogue& ep, int row, int col0, const float (&acc)[8],
+                                                const float (&bias)[8], const float (&gate)[8]) {
+    float val[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) val[e] = acc[e] + bias[e];
+    if (KIND == EPI_PLAIN) {
+        if (ep.act == REGIONE_ACT_GELU_TANH) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) if (col0 + e >= ep.act_from) val[e] = gelu_tanh_f32(val[e]);
+        }
+        store8(ep.y, static_cast<int64_t>(row) * ep.ldy + col0, ep.y_f32, val);
+    } else if (KIND == EPI_QKV) {
+        const int H = ep.hidden;   // a multiple of 8, so a group never straddles two destinations
+        if (col0 < H) {
+            store8(ep.q, static_cast<int64_t>(row) * ep.ldq + col0, 0, val);
+        } else if (col0 < 3 * H) {
+            const int64_t kv_row = epilogue_kv_row<KIND>(ep, row);
+            if (col0 < 2 * H) store8(ep.k, kv_row * ep.ldkv + (col0 - H), 0, val);
+            else store8(ep.v, kv_row * ep.ldkv + (col0 - 2 * H), 0, val);
+        } else {
+            if (ep.act == REGIONE_ACT_GELU_TANH) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) val[e] = gelu_tanh_f32(val[e]);
+            }
+            store8(ep.y, static_cast<int64_t>(row) * ep.ldy + ep.y_col0 + (col0 - 3 * H), 0, val);
+        }
+    } else {  // EPI_RESID
+        const int64_t ri = static_cast<int64_t>(row) * ep.ldr + col0;
+        float res[8];
+        if (ep.resid_f32) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.resid) + ri);
+            const f32x4 b = *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.resid) + ri + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { res[e] = a[e]; res[4 + e] = b[e]; }
+        } else {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(static_cast<const bf16_t*>(ep.resid) + ri);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) res[e] = static_cast<float>(a[e]);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) val[e] = res[e] + gate[e] * val[e];
+        store8(ep.y, static_cast<int64_t>(row) * ep.ldy + col0, ep.y_f32, val);
     }
 }
 
@@ -155,47 +222,102 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    u32x4 areg[3][A_PER_THREAD];
-    u32x4 wreg[3][TN * 4];
+    u32x4 areg[NSETS][A_PER_THREAD];
+    u32x4 wreg[NSETS][TN * 4];
     // steps past the end of this split re-load its last step
-    const int step1 = ks_begin + (nks > 1 ? 1 : 0);
-    a_load(areg[0], a_rows, ks_begin * BK);
-    w_load<TN>(wreg[0], w_blk, ks_begin);
-    a_load(areg[1], a_rows, step1 * BK);
-    w_load<TN>(wreg[1], w_blk, step1);
+#pragma unroll
+    for (int p = 0; p < DEPTH; ++p) {
+        const int st = ks_begin + (p < nks ? p : nks - 1);
+        a_load(areg[p], a_rows, st * BK);
+        w_load<TN>(wreg[p], w_blk, st);
+    }
     a_store(a_lds[0], areg[0]);
     __syncthreads();
 
-    // One K-step.  S = j % 3 names the register set that holds step j; everything is unconditional except the MFMAs,
-    // so the three register sets stay in VGPRs.  (A macro, not a lambda: captured arrays would live in memory.)
-#define RG_GEMM_STEP(J, S, S1, S2)                                                                        \
+    // One K-step.  S = j % NSETS names the register set that holds step j; the loads of step j + DEPTH go to the
+    // set freed by step j - 1; they are issued a quarter at a time in front of each quarter's MFMAs, together with the
+    // LDS reads of the next quarter, so that the memory pipes work in the shadow of the matrix cores.
+    // (A macro, not a lambda: captured arrays would live in memory.)
+#define RG_GEMM_STEP(J, S, S1, SD)                                                                        \
     {                                                                                                     \
         const int j_ = (J);                                                                               \
-        a_load(areg[S2], a_rows, (ks_begin + (j_ + 2 < nks ? j_ + 2 : nks - 1)) * BK);                    \
-        w_load<TN>(wreg[S2], w_blk, ks_begin + (j_ + 2 < nks ? j_ + 2 : nks - 1));                        \
+        const int st_ = ks_begin + (j_ + DEPTH < nks ? j_ + DEPTH : nks - 1);                             \
         if (j_ < nks) {                                                                                   \
             const bf16_t* at = a_lds[j_ & 1];                                                             \
+            bf16x8 af[2][TM];                                                                             \
+            _Pragma("unroll") for (int i = 0; i < TM; ++i) af[0][i] = a_frag(at, i * 32 + l32, lh);       \
             _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                            \
-                bf16x8 af[TM];                                                                            \
-                _Pragma("unroll") for (int i = 0; i < TM; ++i) af[i] = a_frag(at, i * 32 + l32, kk * 2 + lh); \
+                /* memory instructions of this quarter first, then its MFMAs: they run under the MFMAs */   \
+                if (kk < 3) {                                                                             \
+                    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                        \
+                        af[(kk + 1) & 1][i] = a_frag(at, i * 32 + l32, (kk + 1) * 2 + lh);                \
+                }                                                                                         \
+                areg[SD][kk] = *reinterpret_cast<const u32x4*>(a_rows[kk] + st_ * BK);                    \
+                _Pragma("unroll") for (int jn = 0; jn < TN; ++jn)                                         \
+                    wreg[SD][jn * 4 + kk] = *reinterpret_cast<const u32x4*>(w_blk[jn] + (static_cast<int64_t>(st_) * 4 + kk) * 512); \
                 _Pragma("unroll") for (int jn = 0; jn < TN; ++jn) {                                       \
                     const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[S][jn * 4 + kk]);                   \
                     _Pragma("unroll") for (int i = 0; i < TM; ++i)                                        \
-                        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf, acc[i][jn], 0, 0, 0); \
+                        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], wf, acc[i][jn], 0, 0, 0); \
                 }                                                                                         \
+                __builtin_amdgcn_sched_barrier(0);                                                        \
             }                                                                                             \
+        } else {                                                                                          \
+            a_load(areg[SD], a_rows, st_ * BK);                                                           \
+            w_load<TN>(wreg[SD], w_blk, st_);                                                             \
         }                                                                                                 \
         a_store(a_lds[(j_ + 1) & 1], areg[S1]);                                                           \
         __syncthreads();                                                                                  \
     }
-    for (int j = 0; j < nks; j += 3) {
-        RG_GEMM_STEP(j, 0, 1, 2)
+    static_assert(NSETS == 4 && DEPTH == 3, "the unrolled schedule below is written for four register sets");
+    for (int j = 0; j < nks; j += 4) {
+        RG_GEMM_STEP(j, 0, 1, 3)
         RG_GEMM_STEP(j + 1, 1, 2, 0)
-        RG_GEMM_STEP(j + 2, 2, 0, 1)
+        RG_GEMM_STEP(j + 2, 2, 3, 1)
+        RG_GEMM_STEP(j + 3, 3, 0, 2)
     }
 #undef RG_GEMM_STEP
 
     // accumulator (i, j, r) of a lane: row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32 of the 32x32 block
+    float* part_base = partial ? partial + (static_cast<int64_t>(blockIdx.y) * M) * N : nullptr;
+    if (ep.vec_ok) {
+        // Transpose through LDS, 32 rows at a time, so that every lane ends up with eight consecutive columns of one
+        // row: bias, gate, residual and result then move in 16- or 32-byte pieces.  Each wave stages in its own 8 KiB.
+        __syncthreads();   // every wave has finished reading the A tiles
+        float* stage = reinterpret_cast<float*>(&a_lds[0][0]) + wave * (32 * 64);
+        constexpr int G = WN / 8;            // column groups per row
+        constexpr int ROWS_PER_PASS = 64 / G;
+        const int cg = lane % G, rsub = lane / G;
+        const int col0 = n0 + wn0 + cg * 8;
+        const bool col_live = col0 < N;      // N is a multiple of 8 on this path
+        float bias[8], gate[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            bias[e] = (!partial && col_live && ep.bias) ? ep.bias[col0 + e] : 0.f;
+            gate[e] = (!partial && col_live && KIND == EPI_RESID && ep.gate) ? ep.gate[col0 + e] : 1.f;
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    stage[(8 * (r >> 2) + 4 * lh + (r & 3)) * WN + j * 32 + l32] = acc[i][j][r];
+#pragma unroll
+            for (int p = 0; p < 32 / ROWS_PER_PASS; ++p) {
+                const int rr = p * ROWS_PER_PASS + rsub;
+                const int row = m0 + i * 32 + rr;
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(stage + rr * WN + cg * 8);
+                const f32x4 hi = *reinterpret_cast<const f32x4*>(stage + rr * WN + cg * 8 + 4);
+                const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                if (row < M && col_live) {
+                    if (partial) store8(part_base, static_cast<int64_t>(row) * N + col0, 1, v);
+                    else epilogue_store8<KIND>(ep, row, col0, v, bias, gate);
+                }
+            }
+        }
+        return;
+    }
     int col[TN];
     float bias[TN], gate[TN];
 #pragma unroll
@@ -205,7 +327,6 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
         bias[j] = (!partial && live && ep.bias) ? ep.bias[col[j]] : 0.f;
         gate[j] = (!partial && live && KIND == EPI_RESID && ep.gate) ? ep.gate[col[j]] : 1.f;
     }
-    float* part_base = partial ? partial + (static_cast<int64_t>(blockIdx.y) * M) * N : nullptr;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -261,8 +382,9 @@ pack_weight_kernel(const bf16_t* __restrict__ w, int n, int k, bf16_t* __restric
 
 struct GemmPlan { int tn; int splits; };
 
-// Picks the wave-tile width and the K split that finish soonest under a simple model: a workgroup's time is its
-// K-steps times the MFMA time of a step (with a floor for the fixed per-step cost), workgroups run 256 at a time.
+// Picks the wave-tile width and the K split that finish soonest under a model fitted to measurements on MI355X:
+// a K-step of a 128 x 256 workgroup takes about 1.05 us; a 128 x 128 workgroup takes 0.65 us alone on a CU and
+// 1.1 us when two share one (its registers allow that); split-K adds a pass over the float partial sums.
 GemmPlan plan_gemm(const regione_ctx* ctx, int m, int n, int k) {
     if (ctx->gemm_force_tn > 0) return {ctx->gemm_force_tn, ctx->gemm_force_splits > 0 ? ctx->gemm_force_splits : 1};
     const int m_tiles = (m + BM - 1) / BM, steps = k / BK;
@@ -273,10 +395,13 @@ GemmPlan plan_gemm(const regione_ctx* ctx, int m, int n, int k) {
         for (int s : {1, 2, 3, 4, 6, 8}) {
             if (s > 1 && (steps / s < 8 || static_cast<size_t>(s) * m * n * sizeof(float) > ctx->gemm_part_bytes)) continue;
             const int per = (steps + s - 1) / s;
-            const double wg_cycles = per * (tn == 2 ? 1100.0 : 700.0) + 4000.0;
-            const double rounds = ceil(static_cast<double>(m_tiles) * n_tiles * s / 256.0);
-            double t = rounds * wg_cycles;
-            if (s > 1) t += 3000.0 + 0.004 * m * n * (s + 1);
+            const long wgs = static_cast<long>(m_tiles) * n_tiles * s;
+            const long cap = tn == 1 ? 512 : 256;
+            const long full = wgs / cap, rem = wgs % cap;
+            const double t_full = tn == 1 ? 1.1 : 1.05;
+            const double t_rem = tn == 1 ? (rem <= 256 ? 0.65 : 1.1) : 1.05;
+            double t = per * (full * t_full + (rem > 0 ? t_rem : 0.0)) + 4.0;
+            if (s > 1) t += 3.0 + (s + 1.0) * m * n * 4.0 / 3.0e6;
             if (t < best_t) { best_t = t; best = {tn, s}; }
         }
     }
@@ -318,11 +443,18 @@ int dispatch(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m
 
 }  // namespace
 
-int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, const GemmEpilogue& ep) {
+int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, const GemmEpilogue& ep_in) {
     if (m <= 0 || n <= 0) return REGIONE_OK;
     if (k <= 0 || (k % BK) || (lda & 7)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "gemm: k=%d must be a positive multiple of 64 and lda=%d of 8", k, lda);
     if (!rg_aligned16(a) || !rg_aligned16(wp)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
     ProfScope prof(ctx, REGIONE_PROF_GEMM);
+    GemmEpilogue ep = ep_in;
+    // the wide epilogue needs every eight-column group whole and every touched row 16-byte aligned
+    ep.vec_ok = (n % 8 == 0);
+    if (ep.kind == EPI_PLAIN) ep.vec_ok = ep.vec_ok && (ep.ldy % 8 == 0) && rg_aligned16(ep.y) && (ep.act_from % 8 == 0);
+    if (ep.kind == EPI_QKV) ep.vec_ok = ep.vec_ok && (ep.hidden % 8 == 0) && (ep.ldq % 8 == 0) && (ep.ldkv % 8 == 0) && rg_aligned16(ep.q) &&
+                                        rg_aligned16(ep.k) && rg_aligned16(ep.v) && (n <= 3 * ep.hidden || ((ep.ldy % 8 == 0) && (ep.y_col0 % 8 == 0) && rg_aligned16(ep.y)));
+    if (ep.kind == EPI_RESID) ep.vec_ok = ep.vec_ok && (ep.ldy % 8 == 0) && (ep.ldr % 8 == 0) && rg_aligned16(ep.y) && rg_aligned16(ep.resid);
     switch (ep.kind) {
         case EPI_PLAIN: return dispatch<EPI_PLAIN>(ctx, a, lda, wp, m, n, k, ep);
         case EPI_QKV: return dispatch<EPI_QKV>(ctx, a, lda, wp, m, n, k, ep);
