@@ -124,6 +124,7 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
 
     // ---- online softmax on raw scores; accumulator r of block kb is key t*64 + kb*32 + 8*(r/4) + 4*lh + r%4
     if ((t + 1) * KT > n_keys) {   // the last tile may run past the key list
+        asm volatile("" ::: "memory");   // keep this a branch: as selects it would cost every tile 64 instructions
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll

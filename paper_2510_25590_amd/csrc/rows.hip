@@ -83,7 +83,78 @@ velocity_cache_kernel(int reuse, float factor, float dt, const T* __restrict__ v
     }
 }
 
-// LayerNorm over H (no affine, biased variance, eps 1e-6) then u = y*(1+scale)+shift.  One wave per row.
+// LayerNorm over H (no affine, biased variance, eps 1e-6) then u = y*(1+scale)+shift.  One wave per row; the row is
+// read once with 16-byte loads and kept in registers (H <= 64 lanes * 8 * MAXV elements), two-pass mean/variance.
+typedef __attribute__((ext_vector_type(8))) __bf16 ln_bf16x8;
+typedef __attribute__((ext_vector_type(4))) float ln_f32x4;
+
+template <typename T> __device__ __forceinline__ void ld8(const T* p, float (&v)[8]);
+template <> __device__ __forceinline__ void ld8<bf16_t>(const bf16_t* p, float (&v)[8]) {
+    const ln_bf16x8 x = *reinterpret_cast<const ln_bf16x8*>(p);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = static_cast<float>(x[e]);
+}
+template <> __device__ __forceinline__ void ld8<float>(const float* p, float (&v)[8]) {
+    const ln_f32x4 a = *reinterpret_cast<const ln_f32x4*>(p), b = *reinterpret_cast<const ln_f32x4*>(p + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] = a[e]; v[4 + e] = b[e]; }
+}
+
+template <typename T, int MAXV>
+__global__ void __launch_bounds__(kThreads)
+layernorm_mod_vec_kernel(const T* __restrict__ h, int n, int hidden, const float* __restrict__ shift,
+                         const float* __restrict__ scale, bf16_t* __restrict__ u) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (row >= n) return;
+    const T* hr = h + static_cast<int64_t>(row) * hidden;
+    const int groups = hidden >> 3;          // 8-element groups in a row; lane owns groups lane, lane + 64, ...
+    float x[MAXV][8];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int g = lane + 64 * i;
+        if (g < groups) {
+            ld8<T>(hr + g * 8, x[i]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum += x[i][e];
+        }
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 64);
+    const float mean = sum / hidden;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        if (lane + 64 * i < groups) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { const float d = x[i][e] - mean; sq += d * d; }
+        }
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) sq += __shfl_xor(sq, m, 64);
+    const float rstd = rsqrtf(sq / hidden + 1e-6f);
+    bf16_t* ur = u + static_cast<int64_t>(row) * hidden;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int g = lane + 64 * i;
+        if (g < groups) {
+            float sc[8], sh[8];
+            if (scale) ld8<float>(scale + g * 8, sc);
+            if (shift) ld8<float>(shift + g * 8, sh);
+            ln_bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float y = (x[i][e] - mean) * rstd;
+                y = y * (1.f + (scale ? sc[e] : 0.f)) + (shift ? sh[e] : 0.f);
+                o[e] = static_cast<__bf16>(y);
+            }
+            *reinterpret_cast<ln_bf16x8*>(ur + g * 8) = o;
+        }
+    }
+}
+
+// Any H: scalar loads, three passes over the row.
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
 layernorm_mod_kernel(const T* __restrict__ h, int n, int hidden, const float* __restrict__ shift,
@@ -153,7 +224,13 @@ int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidd
     if (n <= 0) return REGIONE_OK;
     dim3 grid((n + kThreads / 64 - 1) / (kThreads / 64));
     ProfScope prof(ctx, REGIONE_PROF_LAYERNORM);
-    if (h_f32)
+    const bool vec = (hidden % 8 == 0) && hidden <= 64 * 8 * 8 && rg_aligned16(h) && rg_aligned16(u) &&
+                     (!shift || rg_aligned16(shift)) && (!scale || rg_aligned16(scale));
+    if (vec && h_f32)
+        hipLaunchKernelGGL((layernorm_mod_vec_kernel<float, 8>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(h), n, hidden, shift, scale, u);
+    else if (vec)
+        hipLaunchKernelGGL((layernorm_mod_vec_kernel<bf16_t, 8>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(h), n, hidden, shift, scale, u);
+    else if (h_f32)
         hipLaunchKernelGGL(layernorm_mod_kernel<float>, grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(h), n, hidden, shift, scale, u);
     else
         hipLaunchKernelGGL(layernorm_mod_kernel<bf16_t>, grid, dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(h), n, hidden, shift, scale, u);
