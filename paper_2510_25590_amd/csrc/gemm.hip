@@ -398,8 +398,9 @@ GemmPlan plan_gemm(const regione_ctx* ctx, int m, int n, int k) {
             const long wgs = static_cast<long>(m_tiles) * n_tiles * s;
             const long cap = tn == 1 ? 512 : 256;
             const long full = wgs / cap, rem = wgs % cap;
-            const double t_full = tn == 1 ? 1.1 : 1.05;
-            const double t_rem = tn == 1 ? (rem <= 256 ? 0.65 : 1.1) : 1.05;
+            const double t_wide = s > 1 ? 1.6 : 1.05;   // measured: the wide tile loses more than the narrow one under split-K
+            const double t_full = tn == 1 ? 1.1 : t_wide;
+            const double t_rem = tn == 1 ? (rem <= 256 ? 0.65 : 1.1) : t_wide;
             double t = per * (full * t_full + (rem > 0 ? t_rem : 0.0)) + 4.0;
             if (s > 1) t += 3.0 + (s + 1.0) * m * n * 4.0 / 3.0e6;
             if (t < best_t) { best_t = t; best = {tn, s}; }
