@@ -102,11 +102,21 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-membound", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="time the steps without the per-kernel event pairs")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run a plain 1 GiB device copy three times (calibration of the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); run it with --gpus 1")
 
     import torch
+    if args.copy_probe:
+        a = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": a.numel() * 4, "copy_probe_bytes_written": b.numel() * 4, "copies": 3}))
+        return
     from paper_2510_25590_amd import binding as rg
     from paper_2510_25590_amd import step
 

@@ -38,6 +38,7 @@ struct AttnArgs {
     // split-KV
     int splits; int tiles_per_split; float* part;  // [splits][heads][n_q_pad][D + 2] when splits > 1
     int n_q_pad;
+    int q_tiles;
 };
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // native 16-byte vector (plain loads/stores, no memcpy)
@@ -194,9 +195,15 @@ attn_kvcache_kernel(AttnArgs a) {
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
-    const int head = blockIdx.y;
-    const int split = blockIdx.z;
-    const int q_base = blockIdx.x * 128 + wave * 32;
+    // XCD-aware numbering (workgroup i runs on XCD i % 8): all query tiles of one (head, key split) get consecutive
+    // slots on ONE XCD, so that the K/V range they share is filled into a single L2 once instead of once per query tile.
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int group = (local / a.q_tiles) * 8 + xcd;            // (head, split) pair
+    if (group >= a.heads * a.splits) return;
+    const int q_tile = local % a.q_tiles;
+    const int head = group % a.heads;
+    const int split = group / a.heads;
+    const int q_base = q_tile * 128 + wave * 32;
     const int n_keys = a.n0 + a.n1;
     const int n_tiles = (n_keys + KT - 1) / KT;
     const int tile_begin = split * a.tiles_per_split;
@@ -358,8 +365,11 @@ int launch_attention(regione_ctx* ctx, AttnArgs a) {
     a.splits = splits;
     a.tiles_per_split = (n_tiles + splits - 1) / splits;
     a.part = ctx->attn_part;
-    if (a.idx1) hipLaunchKernelGGL((attn_kvcache_kernel<D, true>), dim3(q_tiles, a.heads, splits), dim3(kThreads), 0, ctx->stream, a);
-    else hipLaunchKernelGGL((attn_kvcache_kernel<D, false>), dim3(q_tiles, a.heads, splits), dim3(kThreads), 0, ctx->stream, a);
+    a.q_tiles = q_tiles;
+    const int groups_per_xcd = (a.heads * splits + 7) / 8;
+    const dim3 grid(static_cast<unsigned>(groups_per_xcd) * q_tiles * 8);
+    if (a.idx1) hipLaunchKernelGGL((attn_kvcache_kernel<D, true>), grid, dim3(kThreads), 0, ctx->stream, a);
+    else hipLaunchKernelGGL((attn_kvcache_kernel<D, false>), grid, dim3(kThreads), 0, ctx->stream, a);
     RG_LAUNCH_CHECK();
     if (splits > 1) {
         const int64_t total = static_cast<int64_t>(a.n_q) * a.heads * (D / 4);
