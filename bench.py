@@ -19,6 +19,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# L2 <-> fabric bytes of the GEMM launches of one step of the default workload (820 edited tokens), from two
+# rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): see
+# profiles/gemm_attention_hbm_traffic.txt.  Per launch = per step / 5 launches, like `achieved`.
+MEASURED_GEMM_TRAFFIC_BYTES_PER_STEP = {820: 716.0e6}
 
 
 def cpu_baseline(cfg, hst, reps):
@@ -151,7 +155,9 @@ def main():
         ach = gemm_flops / (g_ms * 1e-3) / 1e12
         out["roofline"] = {"kernel": "gemm_bf16_kernel (5 launches per step: QKV, attention output, MLP up, MLP down, velocity head)",
                            "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                           "traffic": None, "avg_launch_ms": prof["gemm"][0] / max(prof["gemm"][1], 1)}
+                           "traffic": (MEASURED_GEMM_TRAFFIC_BYTES_PER_STEP[n] / 5 if n in MEASURED_GEMM_TRAFFIC_BYTES_PER_STEP else None),
+                           "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE at the L2-fabric boundary)",
+                           "algorithmic_flops_per_launch": gemm_flops / 5, "avg_launch_ms": prof["gemm"][0] / max(prof["gemm"][1], 1)}
         out["attention"] = {"achieved": attn_flops / (a_ms * 1e-3) / 1e12, "unit": "TFLOP/s",
                             "frac": attn_flops / (a_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "ms_per_step": a_ms}
         out["gemm_plus_attention_tflops"] = (gemm_flops + attn_flops) / ((g_ms + a_ms) * 1e-3) / 1e12

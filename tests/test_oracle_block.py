@@ -204,3 +204,24 @@ def test_single_block_brute_force_tiny():
     want = h + w["gate1"] * (cat @ w["w_2"].astype(np.float64).T + w["b_2"])
     got = orc.block_forward([w], "single", h, 0, np.arange(3), None, None, 0, heads)
     assert np.max(np.abs(got - want)) < 1e-12
+
+
+def test_sampled_row_composition_used_by_the_gpu_tests_equals_block_forward():
+    # the large GPU parity tests evaluate the oracle only on sampled fresh rows; that composition must be the same function
+    from test_gpu_block import _oracle_region_rows
+    from oracle import step_reference as ref
+    for kind in ("double", "single"):
+        heads, hidden = 4, 32
+        streams, rng = _tiny_model(40, kind)
+        n_txt, n_all = 3, 3 + 16 + 16
+        h_store = rng.standard_normal((n_all, hidden))
+        kc, vc = ref.build_cache(streams, kind, h_store, n_txt, heads)
+        kc2 = np.zeros_like(kc); vc2 = np.zeros_like(vc)
+        orc.block_forward(streams, kind, h_store, n_txt, np.arange(n_all), kc2, vc2, orc.FLAG_STORE, heads)
+        assert np.max(np.abs(kc - kc2)) < 1e-12 and np.max(np.abs(vc - vc2)) < 1e-12
+        slots = n_txt + np.array([0, 3, 4, 9, 15])
+        h_now = h_store[slots] + 0.1 * rng.standard_normal((5, hidden))
+        full = orc.block_forward(streams, kind, h_now, 0, slots, kc, vc, orc.FLAG_RETRIEVE, heads)
+        sample = np.array([0, 2, 4])
+        part = _oracle_region_rows(streams, kind, h_now, slots, kc, vc, heads, sample)
+        assert np.max(np.abs(part - full[sample])) < 1e-12
