@@ -20,8 +20,9 @@ rows_by_index_kernel(const V* __restrict__ src, V* __restrict__ dst, const int32
         const int64_t row = u / pieces_per_row;
         const int piece = static_cast<int>(u - row * pieces_per_row);
         const int64_t other = index[row];
-        if (GATHER) dst[row * pieces_per_row + piece] = src[other * pieces_per_row + piece];
-        else dst[other * pieces_per_row + piece] = src[row * pieces_per_row + piece];
+        // every row is touched once: non-temporal accesses
+        if (GATHER) __builtin_nontemporal_store(__builtin_nontemporal_load(src + other * pieces_per_row + piece), dst + row * pieces_per_row + piece);
+        else __builtin_nontemporal_store(__builtin_nontemporal_load(src + row * pieces_per_row + piece), dst + other * pieces_per_row + piece);
     }
 }
 
@@ -42,9 +43,10 @@ int rows_by_index(regione_ctx* ctx, const void* src, void* dst, int32_t row_elem
     if (blocks > 256 * 64) blocks = 256 * 64;
     dim3 grid(static_cast<unsigned>(blocks));
     ProfScope prof(ctx, REGIONE_PROF_ROWS);
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     if (piece_bytes == 16)
-        hipLaunchKernelGGL((rows_by_index_kernel<uint4, GATHER>), grid, dim3(kThreads), 0, ctx->stream,
-                           static_cast<const uint4*>(src), static_cast<uint4*>(dst), index, n_dev, n_max, ppr);
+        hipLaunchKernelGGL((rows_by_index_kernel<u32x4, GATHER>), grid, dim3(kThreads), 0, ctx->stream,
+                           static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), index, n_dev, n_max, ppr);
     else if (piece_bytes == 4)
         hipLaunchKernelGGL((rows_by_index_kernel<uint32_t, GATHER>), grid, dim3(kThreads), 0, ctx->stream,
                            static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst), index, n_dev, n_max, ppr);
