@@ -1,11 +1,11 @@
 // Adaptive region partition: one-step estimate (Eq.5 with t_f = 0), per-token cosine score
-// against the reference latent, threshold, and a deterministic two-kernel compaction of the
+// against the reference latent, threshold, and a deterministic three-kernel compaction of the
 // edited / unedited index lists (Algorithm 1, ARP lines; section "Adaptive Region Partition").
 //
 // Kernel 1 streams x_t, v, x_ref once (16-byte loads, a group of LPT lanes per token), reduces
 // the three sums in float64 inside the lane group, writes score and mask and one edited count
-// per block.  Kernel 2 gives every block the sum of the counts before it and writes the index
-// lists with a ballot/popcount rank; no atomics, so the lists come out in ascending order.
+// per block.  Kernel 2 (one workgroup) turns the counts into exclusive offsets; kernel 3 writes the
+// index lists with a ballot/popcount rank.  No atomics, so the lists come out in ascending order.
 #include "common.h"
 
 namespace {
@@ -61,8 +61,9 @@ score_mask_kernel(const T* __restrict__ x_t, const T* __restrict__ v, const T* _
     const int64_t block_first = static_cast<int64_t>(blockIdx.x) * tok_per_block;
     int edited_count = 0;
     // Tokens past the end re-read token 0 (valid memory) and are dropped afterwards, so the loads are branch free.
-    // Four passes are handled together: all their loads are issued before the first reduction starts.
-    constexpr int UNROLL = 4;
+    // Two passes are handled together: all their loads are issued before the first reduction starts (four at a time
+    // cost too many registers for the float64 sums and ran slower).
+    constexpr int UNROLL = 2;
     constexpr int PASS_STRIDE = kWaves * TOK_PER_WAVE;
     for (int pass0 = wave * TOK_PER_WAVE; pass0 < tok_per_block; pass0 += UNROLL * PASS_STRIDE) {
         double dot[UNROLL], na[UNROLL], nb[UNROLL];
@@ -125,23 +126,41 @@ score_mask_kernel(const T* __restrict__ x_t, const T* __restrict__ v, const T* _
     }
 }
 
-__global__ void __launch_bounds__(kThreads)
-write_index_kernel(const uint8_t* __restrict__ mask, const int32_t* __restrict__ counts,
-                   int64_t n_tokens, int tok_per_block,
-                   int32_t* __restrict__ e_index, int32_t* __restrict__ u_index, int32_t* __restrict__ n_edited) {
+// Exclusive prefix sum of the per-block counts, in place, by one workgroup: thread t owns a contiguous run of
+// entries.  Also writes the total.
+constexpr int kScanThreads = 1024;
+__global__ void __launch_bounds__(kScanThreads)
+scan_counts_kernel(int32_t* __restrict__ counts, int n_blocks, int32_t* __restrict__ n_edited) {
+    __shared__ int wave_sum[kScanThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    __shared__ int red[kWaves];
-    __shared__ int wave_e[kWaves];
-    // edited tokens in all blocks before this one
-    int part = 0;
-    for (int b = threadIdx.x; b < static_cast<int>(blockIdx.x); b += kThreads) part += counts[b];
+    const int per = (n_blocks + kScanThreads - 1) / kScanThreads;
+    const int first = threadIdx.x * per;
+    int local = 0;
+    for (int i = first; i < first + per && i < n_blocks; ++i) local += counts[i];
+    // inclusive scan of `local` inside the wave, then across the waves
+    int incl = local;
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) part += __shfl_xor(part, m, 64);
-    if (lane == 0) red[wave] = part;
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
     __syncthreads();
-    int base_e = 0;
+    int before = 0, total = 0;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) base_e += red[w];
+    for (int w = 0; w < kScanThreads / 64; ++w) { if (w < wave) before += wave_sum[w]; total += wave_sum[w]; }
+    int run = before + incl - local;   // exclusive prefix of this thread's first entry
+    for (int i = first; i < first + per && i < n_blocks; ++i) { const int cnt = counts[i]; counts[i] = run; run += cnt; }
+    if (threadIdx.x == 0) *n_edited = total;
+}
+
+__global__ void __launch_bounds__(kThreads)
+write_index_kernel(const uint8_t* __restrict__ mask, const int32_t* __restrict__ offsets,
+                   int64_t n_tokens, int tok_per_block,
+                   int32_t* __restrict__ e_index, int32_t* __restrict__ u_index) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ int wave_e[kWaves];
+    int base_e = offsets[blockIdx.x];   // edited tokens in all blocks before this one
     const int64_t block_first = static_cast<int64_t>(blockIdx.x) * tok_per_block;
     int64_t base_u = block_first - base_e;
     for (int off = 0; off < tok_per_block; off += kThreads) {
@@ -165,7 +184,6 @@ write_index_kernel(const uint8_t* __restrict__ mask, const int32_t* __restrict__
         base_e += total;
         base_u += kThreads - total;   // tail rounds past n_tokens write nothing, so over-counting there is harmless
     }
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *n_edited = base_e;
 }
 
 __global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
@@ -210,8 +228,7 @@ extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* 
         int lpt = 1;
         while (lpt * 2 <= nchunks && lpt < 64) lpt *= 2;
         const int tok_per_pass = kWaves * (64 / lpt);
-        // small inputs: one pass per block so that one image still spreads over many CUs
-        // (the index kernel sums the counts of all earlier blocks, so huge inputs get larger blocks)
+        // small inputs: few passes per block so that one image still spreads over many CUs
         int passes = 1;
         while (passes < 32 && (n_tokens / (static_cast<int64_t>(tok_per_pass) * passes * 2)) >= 2048) passes *= 2;
         const int tpb = tok_per_pass * passes;
@@ -227,8 +244,10 @@ extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* 
                           : launch_score<float, 1>(ctx, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask);
         }
         if (rc != REGIONE_OK) return rc;
+        hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, ctx->stream, ctx->part_counts, static_cast<int>(nblocks), n_edited_dev);
+        RG_LAUNCH_CHECK();
         hipLaunchKernelGGL(write_index_kernel, grid, dim3(kThreads), 0, ctx->stream,
-                           mask, ctx->part_counts, n_tokens, tpb, e_index, u_index, n_edited_dev);
+                           mask, ctx->part_counts, n_tokens, tpb, e_index, u_index);
         RG_LAUNCH_CHECK();
     }
     }
