@@ -34,8 +34,8 @@ constexpr int TM = BM / 32;
 constexpr int BK = 64;        // k elements per step
 constexpr int kThreads = 256;
 constexpr int A_PER_THREAD = BM * 8 / kThreads;  // 16-byte chunks of the A tile per thread
-constexpr int DEPTH = 3;      // K-steps between a global load and its use
-constexpr int NSETS = DEPTH + 1;
+// K-steps between a global load and its use (four did not measure faster than three for the narrow tile)
+template <int TN> struct Pipe { static constexpr int DEPTH = 3; static constexpr int NSETS = DEPTH + 1; };
 
 
 __device__ __forceinline__ float gelu_tanh_f32(float x) {
@@ -143,11 +143,46 @@ __device__ __forceinline__ void epilogue_store8(const GemmEpilogue& ep, int row,
     }
 }
 
-// A-tile staging: thread t owns 16-byte chunk (t & 7) of rows (t >> 3) + 32*i.
-__device__ __forceinline__ void a_load(u32x4 (&regs)[A_PER_THREAD], const bf16_t* const (&a_rows)[A_PER_THREAD], int k0) {
-#pragma unroll
-    for (int i = 0; i < A_PER_THREAD; ++i) regs[i] = *reinterpret_cast<const u32x4*>(a_rows[i] + k0);
+// Global loads of the pipeline are written in assembly and waited for by hand.  Left to the compiler, the rotating
+// register sets made its wait-count insertion drain nearly every outstanding load at the top of a K-step (it reuses
+// the registers of a consumed set for LDS fragments and then protects them against loads it believes pending), which
+// shortened the prefetch distance from three steps to less than one.  An asm load is invisible to that pass; the
+// matching rg_wait_loads below names the registers it makes valid, so no use can be scheduled above it.
+__device__ __forceinline__ void rg_load16(u32x4& dst, const bf16_t* p) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p));
 }
+template <int BYTES>
+__device__ __forceinline__ void rg_load16_off(u32x4& dst, const bf16_t* p) {
+    asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(dst) : "v"(p), "n"(BYTES));
+}
+// Waits until at most N of this wave's vector-memory loads are outstanding (they complete in issue order).
+template <int N, int TN>
+__device__ __forceinline__ void rg_wait_loads(u32x4 (&a)[4], u32x4 (&w)[TN * 4]) {
+    if constexpr (TN == 1)
+        asm volatile("s_waitcnt vmcnt(%8)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]) : "n"(N));
+    else
+        asm volatile("s_waitcnt vmcnt(%12)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]),
+                     "+v"(w[4]), "+v"(w[5]), "+v"(w[6]), "+v"(w[7]) : "n"(N));
+}
+
+// Quarter q of the loads of one K-step: one 16-byte chunk of the A tile per thread (thread t owns chunk t & 7 of rows
+// (t >> 3) + 32*q) and fragment q of every 32-column weight block of the wave.
+template <int TN, int Q>
+__device__ __forceinline__ void load_quarter(u32x4 (&areg)[A_PER_THREAD], u32x4 (&wreg)[TN * 4], const bf16_t* const (&a_rows)[A_PER_THREAD],
+                                             const bf16_t* const (&w_blk)[TN], int step) {
+    rg_load16(areg[Q], a_rows[Q] + step * BK);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) rg_load16_off<Q * 1024>(wreg[j * 4 + Q], w_blk[j] + static_cast<int64_t>(step) * 2048);
+}
+template <int TN>
+__device__ __forceinline__ void load_step(u32x4 (&areg)[A_PER_THREAD], u32x4 (&wreg)[TN * 4], const bf16_t* const (&a_rows)[A_PER_THREAD],
+                                          const bf16_t* const (&w_blk)[TN], int step) {
+    load_quarter<TN, 0>(areg, wreg, a_rows, w_blk, step);
+    load_quarter<TN, 1>(areg, wreg, a_rows, w_blk, step);
+    load_quarter<TN, 2>(areg, wreg, a_rows, w_blk, step);
+    load_quarter<TN, 3>(areg, wreg, a_rows, w_blk, step);
+}
+
 __device__ __forceinline__ void a_store(bf16_t* lds, const u32x4 (&regs)[A_PER_THREAD]) {
     const int r0 = threadIdx.x >> 3, c = threadIdx.x & 7;
 #pragma unroll
@@ -159,16 +194,6 @@ __device__ __forceinline__ void a_store(bf16_t* lds, const u32x4 (&regs)[A_PER_T
 __device__ __forceinline__ bf16x8 a_frag(const bf16_t* tile, int row, int chunk) {
     // rows are 128 bytes: 16 consecutive rows x one logical chunk cover all 64 banks exactly once
     return *reinterpret_cast<const bf16x8*>(tile + row * BK + ((chunk ^ ((row >> 1) & 7)) << 3));
-}
-
-template <int TN>
-__device__ __forceinline__ void w_load(u32x4 (&regs)[TN * 4], const bf16_t* const (&w_blk)[TN], int64_t k_step) {
-    // one K-step of one 32-column block is 4 consecutive fragments of 1 KiB
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-            regs[j * 4 + kk] = *reinterpret_cast<const u32x4*>(w_blk[j] + (k_step * 4 + kk) * 512);
 }
 
 template <int TN, int KIND>
@@ -222,15 +247,14 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    constexpr int DEPTH = Pipe<TN>::DEPTH, NSETS = Pipe<TN>::NSETS;
     u32x4 areg[NSETS][A_PER_THREAD];
     u32x4 wreg[NSETS][TN * 4];
     // steps past the end of this split re-load its last step
+    constexpr int L = A_PER_THREAD + 4 * TN;        // loads per thread and K-step
 #pragma unroll
-    for (int p = 0; p < DEPTH; ++p) {
-        const int st = ks_begin + (p < nks ? p : nks - 1);
-        a_load(areg[p], a_rows, st * BK);
-        w_load<TN>(wreg[p], w_blk, st);
-    }
+    for (int p = 0; p < DEPTH; ++p) load_step<TN>(areg[p], wreg[p], a_rows, w_blk, ks_begin + (p < nks ? p : nks - 1));
+    rg_wait_loads<(DEPTH - 1) * L, TN>(areg[0], wreg[0]);
     a_store(a_lds[0], areg[0]);
     __syncthreads();
 
@@ -238,6 +262,21 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
     // set freed by step j - 1; they are issued a quarter at a time in front of each quarter's MFMAs, together with the
     // LDS reads of the next quarter, so that the memory pipes work in the shadow of the matrix cores.
     // (A macro, not a lambda: captured arrays would live in memory.)
+#define RG_GEMM_QUARTER(KK, S, SD)                                                                        \
+    {                                                                                                     \
+        /* memory instructions of this quarter first, then its MFMAs: they run under the MFMAs */           \
+        if (KK < 3) {                                                                                     \
+            _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                \
+                af[(KK + 1) & 1][i] = a_frag(at, i * 32 + l32, (KK + 1) * 2 + lh);                        \
+        }                                                                                                 \
+        load_quarter<TN, KK>(areg[SD], wreg[SD], a_rows, w_blk, st_);                                     \
+        _Pragma("unroll") for (int jn = 0; jn < TN; ++jn) {                                               \
+            const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[S][jn * 4 + KK]);                           \
+            _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                \
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[KK & 1][i], wf, acc[i][jn], 0, 0, 0); \
+        }                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+    }
 #define RG_GEMM_STEP(J, S, S1, SD)                                                                        \
     {                                                                                                     \
         const int j_ = (J);                                                                               \
@@ -246,37 +285,39 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
             const bf16_t* at = a_lds[j_ & 1];                                                             \
             bf16x8 af[2][TM];                                                                             \
             _Pragma("unroll") for (int i = 0; i < TM; ++i) af[0][i] = a_frag(at, i * 32 + l32, lh);       \
-            _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                            \
-                /* memory instructions of this quarter first, then its MFMAs: they run under the MFMAs */   \
-                if (kk < 3) {                                                                             \
-                    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                        \
-                        af[(kk + 1) & 1][i] = a_frag(at, i * 32 + l32, (kk + 1) * 2 + lh);                \
-                }                                                                                         \
-                areg[SD][kk] = *reinterpret_cast<const u32x4*>(a_rows[kk] + st_ * BK);                    \
-                _Pragma("unroll") for (int jn = 0; jn < TN; ++jn)                                         \
-                    wreg[SD][jn * 4 + kk] = *reinterpret_cast<const u32x4*>(w_blk[jn] + (static_cast<int64_t>(st_) * 4 + kk) * 512); \
-                _Pragma("unroll") for (int jn = 0; jn < TN; ++jn) {                                       \
-                    const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[S][jn * 4 + kk]);                   \
-                    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                        \
-                        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], wf, acc[i][jn], 0, 0, 0); \
-                }                                                                                         \
-                __builtin_amdgcn_sched_barrier(0);                                                        \
-            }                                                                                             \
+            RG_GEMM_QUARTER(0, S, SD)                                                                     \
+            RG_GEMM_QUARTER(1, S, SD)                                                                     \
+            RG_GEMM_QUARTER(2, S, SD)                                                                     \
+            RG_GEMM_QUARTER(3, S, SD)                                                                     \
         } else {                                                                                          \
-            a_load(areg[SD], a_rows, st_ * BK);                                                           \
-            w_load<TN>(wreg[SD], w_blk, st_);                                                             \
+            load_step<TN>(areg[SD], wreg[SD], a_rows, w_blk, st_);                                        \
         }                                                                                                 \
+        /* steps j+1 .. j+DEPTH are in flight; step j+1 is needed now (its A tile here, its weights next step) */ \
+        rg_wait_loads<(DEPTH - 1) * L, TN>(areg[S1], wreg[S1]);                                           \
         a_store(a_lds[(j_ + 1) & 1], areg[S1]);                                                           \
         __syncthreads();                                                                                  \
     }
-    static_assert(NSETS == 4 && DEPTH == 3, "the unrolled schedule below is written for four register sets");
-    for (int j = 0; j < nks; j += 4) {
-        RG_GEMM_STEP(j, 0, 1, 3)
-        RG_GEMM_STEP(j + 1, 1, 2, 0)
-        RG_GEMM_STEP(j + 2, 2, 3, 1)
-        RG_GEMM_STEP(j + 3, 3, 0, 2)
+    if constexpr (NSETS == 4) {
+        for (int j = 0; j < nks; j += 4) {
+            RG_GEMM_STEP(j, 0, 1, 3)
+            RG_GEMM_STEP(j + 1, 1, 2, 0)
+            RG_GEMM_STEP(j + 2, 2, 3, 1)
+            RG_GEMM_STEP(j + 3, 3, 0, 2)
+        }
+    } else {
+        static_assert(NSETS == 4 || NSETS == 5, "unrolled schedules exist for four and five register sets");
+        for (int j = 0; j < nks; j += 5) {
+            RG_GEMM_STEP(j, 0, 1, 4)
+            RG_GEMM_STEP(j + 1, 1, 2, 0)
+            RG_GEMM_STEP(j + 2, 2, 3, 1)
+            RG_GEMM_STEP(j + 3, 3, 4, 2)
+            RG_GEMM_STEP(j + 4, 4, 0, 3)
+        }
     }
 #undef RG_GEMM_STEP
+#undef RG_GEMM_QUARTER
+    // the loads issued for steps past the end are still in flight; they must land before their registers are reused
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // accumulator (i, j, r) of a lane: row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32 of the 32x32 block
     float* part_base = partial ? partial + (static_cast<int64_t>(blockIdx.y) * M) * N : nullptr;
