@@ -5,7 +5,7 @@
 //
 // Flash-style streaming with an online softmax.  A workgroup of 4 waves owns QB*128 query rows of
 // one head; each wave owns QB blocks of 32 queries, whose Q fragments stay in registers.  Keys and
-// values are staged 64 rows at a time in LDS (double buffered).  The scores are computed
+// values are staged 64 rows at a time in LDS by asynchronous global->LDS copies, three stages deep.  The scores are computed
 // TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then holds, for ONE query
 // (column lane%32), 16 of every 32 keys, so the running maximum and the rescaling factor are
 // per-lane scalars, and the exponentiated scores are already in the register layout of the "B"
@@ -54,31 +54,46 @@ template <int D> __device__ __forceinline__ int v_swz(int row, int chunk) {
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 
-// Global loads of one 64-key tile into staging registers.  Thread t owns 16-byte chunk t % CPR of rows t / CPR + i * (256 / CPR).
-// INDEXED: the cache rows go through the index list (all the index loads are issued before the first dependent load).
+// Asynchronous global -> LDS copy of one 16-byte chunk per lane (gfx950 global_load_lds_dwordx4): lane l of the wave
+// writes LDS[lds_base + 16*l].  The copy bypasses the VGPRs and is counted in vmcnt; it is written in assembly so
+// that the compiler's wait-count pass does not see it (it would wait for it before every later LDS read); the kernel
+// waits by hand before the barrier that publishes a stage.
+__device__ __forceinline__ void async_copy16(const bf16_t* src, unsigned lds_base_bytes) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(src), "s"(lds_base_bytes) : "memory", "m0");
+}
+
+// Issues the copies of one 64-key tile into an LDS stage.  The tile is 64 * CPR chunks; wave w issues blocks
+// b = w*LD_N + i of 64 consecutive chunk positions, position P = row*CPR + physical chunk.  Since the LDS side is
+// linear in the lane, the swizzle is applied on the global side: the lane that owns physical chunk p of a row loads
+// the logical chunk p ^ f(row) (both swizzles are XORs, hence their own inverses).
 template <int D, bool INDEXED>
-__device__ __forceinline__ void kv_tile_load(const AttnArgs& a, int head_off, int key0, int n_keys,
-                                             u32x4 (&kr)[KT * (D / 8) / kThreads], u32x4 (&vr)[KT * (D / 8) / kThreads]) {
-    constexpr int CPR = D / 8;
-    constexpr int PER_THREAD = KT * CPR / kThreads;
-    const int r0 = threadIdx.x / CPR;
-    int key[PER_THREAD];
-    int64_t row[PER_THREAD];
+__device__ __forceinline__ void kv_tile_issue(const AttnArgs& a, int head, int key0, int n_keys, unsigned stage_base_bytes) {
+    constexpr int CPR = D / 8, LD_N = KT * CPR / kThreads, TILE = KT * D;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const int kx = key0 + r0 + i * (kThreads / CPR);
-        key[i] = kx < n_keys ? kx : n_keys - 1;  // tail rows repeat a valid row; their scores are masked
-        row[i] = key[i] < a.n0 ? key[i] : key[i] - a.n0;
-        if (INDEXED) { if (key[i] >= a.n0) row[i] = a.idx1[row[i]]; }
+    for (int i = 0; i < LD_N; ++i) {
+        const int b = wave * LD_N + i;
+        const int pos = b * 64 + lane;
+        const int row = pos / CPR, phys = pos % CPR;
+        int key = key0 + row;
+        key = key < n_keys ? key : n_keys - 1;   // tail rows repeat a valid row; their scores are masked
+        const bool fresh = key < a.n0;
+        int64_t grow = fresh ? key : key - a.n0;
+        if (INDEXED) { if (!fresh) grow = a.idx1[grow]; }
+        const int64_t base = grow * (fresh ? a.ldkv0 : a.ldkv1) + head * D;
+        const unsigned lds_blk = __builtin_amdgcn_readfirstlane(stage_base_bytes + static_cast<unsigned>(b) * 1024u);
+        async_copy16((fresh ? a.k0 : a.k1) + base + (k_swz<D>(row, phys) << 3), lds_blk);
+        async_copy16((fresh ? a.v0 : a.v1) + base + (v_swz<D>(row, phys) << 3), lds_blk + TILE * 2u);
     }
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-        const bool fresh = key[i] < a.n0;
-        const int64_t off = row[i] * (fresh ? a.ldkv0 : a.ldkv1) + head_off;
-        kr[i] = *reinterpret_cast<const u32x4*>((fresh ? a.k0 : a.k1) + off);
-        vr[i] = *reinterpret_cast<const u32x4*>((fresh ? a.v0 : a.v1) + off);
-    }
+}
+template <int N> __device__ __forceinline__ void wait_async_copies() {   // at most N of this wave's copies still in flight
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
 // One 64-key tile for the 32 queries of a wave.  STAGE selects the LDS buffer (compile time, so that every LDS
@@ -93,10 +108,9 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
 
     // ---- S^T = K Q^T for the two 32-key blocks: K fragments are fetched half a tile ahead of their MFMAs
     f32x16 s[2];
+    f32x16 zero;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+    for (int r = 0; r < 16; ++r) zero[r] = 0.f;   // becomes the inline constant 0 of the first MFMA's accumulator operand
     // K fragments are fetched two k-steps (four reads) ahead of their MFMAs
     constexpr int PF = 2;
     bf16x8 kf[KK][2];
@@ -119,7 +133,7 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
             }
         }
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][kb], qf[kk], s[kb], 0, 0, 0);
+        for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][kb], qf[kk], kk == 0 ? zero : s[kb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
 
@@ -132,11 +146,17 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
             for (int r = 0; r < 16; ++r)
                 if (t * KT + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3) >= n_keys) s[kb][r] = -INFINITY;
     }
-    float mx = fmaxf(s[0][0], s[1][0]);
+    // maximum of the lane's 32 scores with three-input maxima (plain fmaxf costs an extra canonicalising instruction
+    // per MFMA result); -inf entries of a masked tail are ordinary operands
+    float mx = max3(s[0][0], s[0][1], s[0][2]);
 #pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);     // finite: every tile holds at least one live key
+    for (int r = 3; r < 15; r += 2) mx = max3(mx, s[0][r], s[0][r + 1]);
+    mx = max3(mx, s[0][15], s[1][0]);
+#pragma unroll
+    for (int r = 1; r < 15; r += 2) mx = max3(mx, s[1][r], s[1][r + 1]);
+    mx = max3(mx, s[1][15], s[1][15]);
+    mx = max3(mx, __shfl_xor(mx, 32, 64), m_run);
+    const float m_new = mx;                   // finite: every tile holds at least one live key
     if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // wave-uniform: the running maximum rarely moves after the first tiles
         const float alpha = fast_exp2((m_run - m_new) * c);
         l_run *= alpha;
@@ -191,7 +211,10 @@ attn_kvcache_kernel(AttnArgs a) {
     constexpr int DB = D / 32;   // 32-wide d blocks of the output
     constexpr int KK = D / 16;   // k-steps of the first product
     constexpr int CPR = D / 8, LD_N = KT * CPR / kThreads, TILE = KT * D;
-    __shared__ __attribute__((aligned(16))) bf16_t smem[2 * 2 * TILE];   // two stages of (K tile, V tile)
+    constexpr int COPIES = 2 * LD_N;                    // asynchronous copies per thread and tile
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];   // three stages of (K tile, V tile)
+    bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+    const unsigned smem_bytes0 = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) void*)(smem_raw)));   // LDS byte address
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
@@ -232,16 +255,6 @@ attn_kvcache_kernel(AttnArgs a) {
             voff[db] = src_key * D + (v_swz<D>(src_key, d_src >> 3) << 3) + (d_src & 7);
         }
     }
-    // staging: LDS store offsets of this thread's chunks
-    int ks_off[LD_N], vs_off[LD_N];
-#pragma unroll
-    for (int i = 0; i < LD_N; ++i) {
-        const int r = threadIdx.x / CPR + i * (kThreads / CPR), cc = threadIdx.x % CPR;
-        ks_off[i] = r * D + (k_swz<D>(r, cc) << 3);
-        vs_off[i] = TILE + r * D + (v_swz<D>(r, cc) << 3);
-    }
-    const int head_off = head * D + (threadIdx.x % CPR) * 8;
-
     f32x16 o[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -250,37 +263,30 @@ attn_kvcache_kernel(AttnArgs a) {
     float m_run = -INFINITY, l_run = 0.f;
     const float c = a.scale_log2e;
 
-    u32x4 kr[LD_N], vr[LD_N];
+    // Three LDS stages, copies two tiles ahead.  Per tile: wait until this tile's copies (issued two tiles ago) have
+    // landed, barrier (publishes them and retires the stage read one tile ago), issue the copies of tile t+2 into that
+    // retired stage, compute.  Tiles past the end re-copy the last tile so that the copy count per tile is constant.
+    constexpr unsigned STAGE_BYTES = 2u * TILE * 2u;
+    auto tile_key0 = [&](int t) __attribute__((always_inline)) { return (t < tile_end ? t : tile_end - 1) * KT; };
     if (tile_begin < tile_end) {
-        kv_tile_load<D, INDEXED>(a, head_off, tile_begin * KT, n_keys, kr, vr);
-#pragma unroll
-        for (int i = 0; i < LD_N; ++i) {
-            *reinterpret_cast<u32x4*>(smem + ks_off[i]) = kr[i];
-            *reinterpret_cast<u32x4*>(smem + vs_off[i]) = vr[i];
-        }
+        kv_tile_issue<D, INDEXED>(a, head, tile_key0(tile_begin), n_keys, smem_bytes0);
+        kv_tile_issue<D, INDEXED>(a, head, tile_key0(tile_begin + 1), n_keys, smem_bytes0 + STAGE_BYTES);
     }
-    __syncthreads();
-
-    // Two tiles per trip so that the LDS stage is a compile-time constant.  The loads of the next tile are issued
-    // first (pinned there by the scheduling barrier) and land in the idle stage after this tile's MFMAs; the last
-    // tile re-loads itself, which keeps the code unconditional and the staging values in registers.
 #define RG_ATTN_TILE(T, STAGE)                                                                            \
     {                                                                                                     \
         const int t_ = (T);                                                                               \
-        kv_tile_load<D, INDEXED>(a, head_off, (t_ + 1 < tile_end ? t_ + 1 : t_) * KT, n_keys, kr, vr);    \
-        __builtin_amdgcn_sched_barrier(0);                                                                \
-        attn_tile<D, STAGE>(smem, t_, n_keys, c, lh, koff, voff, qf, o, m_run, l_run);                    \
-        _Pragma("unroll") for (int i = 0; i < LD_N; ++i) {                                                \
-            *reinterpret_cast<u32x4*>(smem + (1 - STAGE) * 2 * TILE + ks_off[i]) = kr[i];                 \
-            *reinterpret_cast<u32x4*>(smem + (1 - STAGE) * 2 * TILE + vs_off[i]) = vr[i];                 \
-        }                                                                                                 \
+        wait_async_copies<COPIES>();                                                                      \
         __syncthreads();                                                                                  \
+        kv_tile_issue<D, INDEXED>(a, head, tile_key0(t_ + 2), n_keys, smem_bytes0 + ((STAGE + 2) % 3) * STAGE_BYTES); \
+        attn_tile<D, STAGE>(smem, t_, n_keys, c, lh, koff, voff, qf, o, m_run, l_run);                    \
     }
-    for (int t = tile_begin; t < tile_end; t += 2) {
+    for (int t = tile_begin; t < tile_end; t += 3) {
         RG_ATTN_TILE(t, 0)
         if (t + 1 < tile_end) RG_ATTN_TILE(t + 1, 1)
+        if (t + 2 < tile_end) RG_ATTN_TILE(t + 2, 2)
     }
 #undef RG_ATTN_TILE
+    wait_async_copies<0>();   // nothing may still be writing LDS when the workgroup ends
 
     // ---- finish: O^T accumulator r of d-block db: d = db*32 + 8*(r/4) + 4*lh + r%4, query = l32
     const int qrow = q_base + l32;
@@ -368,8 +374,15 @@ int launch_attention(regione_ctx* ctx, AttnArgs a) {
     a.q_tiles = q_tiles;
     const int groups_per_xcd = (a.heads * splits + 7) / 8;
     const dim3 grid(static_cast<unsigned>(groups_per_xcd) * q_tiles * 8);
-    if (a.idx1) hipLaunchKernelGGL((attn_kvcache_kernel<D, true>), grid, dim3(kThreads), 0, ctx->stream, a);
-    else hipLaunchKernelGGL((attn_kvcache_kernel<D, false>), grid, dim3(kThreads), 0, ctx->stream, a);
+    constexpr size_t lds_bytes = static_cast<size_t>(3) * 2 * KT * D * sizeof(bf16_t);
+    static bool attr_set = false;   // per instantiation: more than 64 KiB of LDS has to be granted explicitly
+    if (!attr_set) {
+        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, false>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+        attr_set = true;
+    }
+    if (a.idx1) hipLaunchKernelGGL((attn_kvcache_kernel<D, true>), grid, dim3(kThreads), lds_bytes, ctx->stream, a);
+    else hipLaunchKernelGGL((attn_kvcache_kernel<D, false>), grid, dim3(kThreads), lds_bytes, ctx->stream, a);
     RG_LAUNCH_CHECK();
     if (splits > 1) {
         const int64_t total = static_cast<int64_t>(a.n_q) * a.heads * (D / 4);
