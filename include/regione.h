@@ -158,6 +158,10 @@ int regione_linear(regione_ctx* ctx, const void* x, const void* w_packed, const 
  * number of K splits of every later GEMM of this context; 0 restores the automatic choice. */
 int regione_tune_gemm(regione_ctx* ctx, int32_t wave_tile_blocks, int32_t k_splits);
 
+/* Tuning knob for experiments: forces the number of key-range splits (1..8) of every later
+ * attention call of this context; 0 restores the automatic choice. */
+int regione_tune_attention(regione_ctx* ctx, int32_t key_splits);
+
 /* One transformer block on the fresh rows: one layer of Phi(tokens, C_KV, f) in
  * Algorithm 1.  The block is LayerNorm (no affine, eps 1e-6) -> modulation -> QKV linear ->
  * attention -> gated residual -> LayerNorm -> modulation -> MLP with tanh-GELU -> gated

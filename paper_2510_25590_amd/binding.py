@@ -24,7 +24,7 @@ EXPORTS = (
     "regione_last_error", "regione_create", "regione_destroy", "regione_partition", "regione_gather",
     "regione_scatter", "regione_attn_kvcache", "regione_linear", "regione_block_forward",
     "regione_velocity_decision_host", "regione_velocity_cache", "regione_profile_enable", "regione_profile_read",
-    "regione_packed_weight_elems", "regione_pack_weight", "regione_tune_gemm",
+    "regione_packed_weight_elems", "regione_pack_weight", "regione_tune_gemm", "regione_tune_attention",
 )
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
 
@@ -81,6 +81,7 @@ def lib() -> C.CDLL:
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
             "regione_pack_weight": [vp, vp, i32, i32, vp],
             "regione_tune_gemm": [vp, i32, i32],
+            "regione_tune_attention": [vp, i32],
             "regione_profile_enable": [vp, i32],
             "regione_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(i64), i32],
         }
@@ -210,6 +211,10 @@ def regione_pack_weight(ctx, w, n, k, w_packed):
 
 def regione_tune_gemm(ctx, wave_tile_blocks: int, k_splits: int):
     _check(lib().regione_tune_gemm(ctx.handle, wave_tile_blocks, k_splits))
+
+
+def regione_tune_attention(ctx, key_splits: int):
+    _check(lib().regione_tune_attention(ctx.handle, key_splits))
 
 
 def pack_weight(ctx, w):

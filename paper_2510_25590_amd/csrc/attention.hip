@@ -3,7 +3,7 @@
 // Queries are the fresh (edited / text) rows only; the key list is the fresh rows followed by the
 // cache rows in use, addressed as one virtual list so that a tile may straddle the two.
 //
-// Flash-style streaming with an online softmax.  A workgroup of 4 waves owns QB*128 query rows of
+// Flash-style streaming with an online softmax.  A workgroup of NW waves owns NW*QB*32 query rows of
 // one head; each wave owns QB blocks of 32 queries, whose Q fragments stay in registers.  Keys and
 // values are staged 64 rows at a time in LDS by asynchronous global->LDS copies, three stages deep.  The scores are computed
 // TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then holds, for ONE query
@@ -14,6 +14,7 @@
 // of gfx950.  The k-slot of the second product pairs lane-half h, slot s of both operands, so the
 // only requirement is that both sides enumerate keys identically: slot s of half h of MFMA (kb,j)
 // is key kb*32 + 16*j + 8*(s/4) + 4*h + s%4, which is exactly the row order of the S^T accumulator.
+#include <cmath>
 #include "common.h"
 
 namespace {
@@ -72,9 +73,9 @@ __device__ __forceinline__ void async_copy16(const bf16_t* src, unsigned lds_bas
 // b = w*LD_N + i of 64 consecutive chunk positions, position P = row*CPR + physical chunk.  Since the LDS side is
 // linear in the lane, the swizzle is applied on the global side: the lane that owns physical chunk p of a row loads
 // the logical chunk p ^ f(row) (both swizzles are XORs, hence their own inverses).
-template <int D, bool INDEXED>
+template <int D, int NW, bool INDEXED>
 __device__ __forceinline__ void kv_tile_issue(const AttnArgs& a, int head, int key0, int n_keys, unsigned stage_base_bytes) {
-    constexpr int CPR = D / 8, LD_N = KT * CPR / kThreads, TILE = KT * D;
+    constexpr int CPR = D / 8, LD_N = KT * CPR / (NW * 64), TILE = KT * D;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int i = 0; i < LD_N; ++i) {
@@ -96,18 +97,18 @@ template <int N> __device__ __forceinline__ void wait_async_copies() {   // at m
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-// One 64-key tile for the 32 queries of a wave.  STAGE selects the LDS buffer (compile time, so that every LDS
-// address is a per-lane constant plus an immediate).
-template <int D, int STAGE>
+// One 64-key tile for the QB*32 queries of a wave.  STAGE selects the LDS buffer (compile time, so that every LDS
+// address is a per-lane constant plus an immediate).  K and V fragments are read once and used for all QB query blocks.
+template <int D, int STAGE, int QB>
 __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys, float c, int lh,
-                                          const int (&koff)[D / 16], const int (&voff)[D / 32], const bf16x8 (&qf)[D / 16],
-                                          f32x16 (&o)[D / 32], float& m_run, float& l_run) {
+                                          const int (&koff)[D / 16], const int (&voff)[D / 32], const bf16x8 (&qf)[QB][D / 16],
+                                          f32x16 (&o)[QB][D / 32], float (&m_run)[QB], float (&l_run)[QB]) {
     constexpr int DB = D / 32, KK = D / 16, TILE = KT * D;
     const bf16_t* kt = smem + STAGE * 2 * TILE;
     const bf16_t* vt = kt + TILE;
 
-    // ---- S^T = K Q^T for the two 32-key blocks: K fragments are fetched half a tile ahead of their MFMAs
-    f32x16 s[2];
+    // ---- S^T = K Q^T for the two 32-key blocks
+    f32x16 s[QB][2];
     f32x16 zero;
 #pragma unroll
     for (int r = 0; r < 16; ++r) zero[r] = 0.f;   // becomes the inline constant 0 of the first MFMA's accumulator operand
@@ -133,7 +134,10 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
             }
         }
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][kb], qf[kk], kk == 0 ? zero : s[kb], 0, 0, 0);
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+                s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][kb], qf[qb][kk], kk == 0 ? zero : s[qb][kb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
 
@@ -141,47 +145,52 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
     if ((t + 1) * KT > n_keys) {   // the last tile may run past the key list
         asm volatile("" ::: "memory");   // keep this a branch: as selects it would cost every tile 64 instructions
 #pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (t * KT + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3) >= n_keys) s[qb][kb][r] = -INFINITY;
+    }
+    bf16x8 pf[QB][2][2];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        // maximum of the lane's 32 scores with three-input maxima (plain fmaxf costs an extra canonicalising
+        // instruction per MFMA result); -inf entries of a masked tail are ordinary operands
+        float mx = max3(s[qb][0][0], s[qb][0][1], s[qb][0][2]);
+#pragma unroll
+        for (int r = 3; r < 15; r += 2) mx = max3(mx, s[qb][0][r], s[qb][0][r + 1]);
+        mx = max3(mx, s[qb][0][15], s[qb][1][0]);
+#pragma unroll
+        for (int r = 1; r < 15; r += 2) mx = max3(mx, s[qb][1][r], s[qb][1][r + 1]);
+        mx = max3(mx, s[qb][1][15], s[qb][1][15]);
+        mx = max3(mx, __shfl_xor(mx, 32, 64), m_run[qb]);
+        const float m_new = mx;                   // finite: every tile holds at least one live key
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run[qb]) != 0) {   // wave-uniform: the running maximum rarely moves after the first tiles
+            const float alpha = fast_exp2((m_run[qb] - m_new) * c);
+            l_run[qb] *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
+            m_run[qb] = m_new;
+        }
+        const float neg_mc = -m_new * c;
+        float psum = 0.f;
+#pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (t * KT + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3) >= n_keys) s[kb][r] = -INFINITY;
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float p = fast_exp2(__builtin_fmaf(s[qb][kb][8 * j + e], c, neg_mc));
+                    psum += p;
+                    pf[qb][kb][j][e] = static_cast<__bf16>(p);
+                }
+        l_run[qb] += psum;
     }
-    // maximum of the lane's 32 scores with three-input maxima (plain fmaxf costs an extra canonicalising instruction
-    // per MFMA result); -inf entries of a masked tail are ordinary operands
-    float mx = max3(s[0][0], s[0][1], s[0][2]);
-#pragma unroll
-    for (int r = 3; r < 15; r += 2) mx = max3(mx, s[0][r], s[0][r + 1]);
-    mx = max3(mx, s[0][15], s[1][0]);
-#pragma unroll
-    for (int r = 1; r < 15; r += 2) mx = max3(mx, s[1][r], s[1][r + 1]);
-    mx = max3(mx, s[1][15], s[1][15]);
-    mx = max3(mx, __shfl_xor(mx, 32, 64), m_run);
-    const float m_new = mx;                   // finite: every tile holds at least one live key
-    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // wave-uniform: the running maximum rarely moves after the first tiles
-        const float alpha = fast_exp2((m_run - m_new) * c);
-        l_run *= alpha;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-        m_run = m_new;
-    }
-    const float neg_mc = -m_new * c;
-    float psum = 0.f;
-    bf16x8 pf[2][2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float p = fast_exp2(__builtin_fmaf(s[kb][8 * j + e], c, neg_mc));
-                psum += p;
-                pf[kb][j][e] = static_cast<__bf16>(p);
-            }
-    l_run += psum;
 
-    // ---- O^T += V^T P^T, one (kb, j) group of DB MFMAs at a time, the next group's fragments in flight
+    // ---- O^T += V^T P^T, one (kb, j) group of DB*QB MFMAs at a time, the next group's fragments in flight
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const int kb = g >> 1, j = g & 1;
@@ -200,19 +209,23 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
             }
         }
 #pragma unroll
-        for (int db = 0; db < DB; ++db) o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db], pf[kb][j], o[db], 0, 0, 0);
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db], pf[qb][kb][j], o[qb][db], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-template <int D, bool INDEXED>
-__global__ void __launch_bounds__(kThreads)
+// NW waves per workgroup, QB blocks of 32 queries per wave, NSTAGE LDS stages.
+template <int D, int NW, int QB, int NSTAGE, int WPE, bool INDEXED>
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 attn_kvcache_kernel(AttnArgs a) {
     constexpr int DB = D / 32;   // 32-wide d blocks of the output
     constexpr int KK = D / 16;   // k-steps of the first product
-    constexpr int CPR = D / 8, LD_N = KT * CPR / kThreads, TILE = KT * D;
+    constexpr int CPR = D / 8, LD_N = KT * CPR / (NW * 64), TILE = KT * D;
     constexpr int COPIES = 2 * LD_N;                    // asynchronous copies per thread and tile
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];   // three stages of (K tile, V tile)
+    constexpr int QW = NW * QB * 32;                    // queries per workgroup
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];   // NSTAGE stages of (K tile, V tile)
     bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
     const unsigned smem_bytes0 = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) void*)(smem_raw)));   // LDS byte address
 
@@ -226,7 +239,7 @@ attn_kvcache_kernel(AttnArgs a) {
     const int q_tile = local % a.q_tiles;
     const int head = group % a.heads;
     const int split = group / a.heads;
-    const int q_base = q_tile * 128 + wave * 32;
+    const int q_base = q_tile * QW + wave * (QB * 32);
     const int n_keys = a.n0 + a.n1;
     const int n_tiles = (n_keys + KT - 1) / KT;
     const int tile_begin = split * a.tiles_per_split;
@@ -234,13 +247,14 @@ attn_kvcache_kernel(AttnArgs a) {
     tile_end = tile_end < n_tiles ? tile_end : n_tiles;
 
     // Q fragments ("B" operand): lane holds query l32 of the block, d = kk*16 + 8*lh + 0..7
-    bf16x8 qf[KK];
-    {
-        int qrow = q_base + l32;
+    bf16x8 qf[QB][KK];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        int qrow = q_base + qb * 32 + l32;
         qrow = qrow < a.n_q ? qrow : a.n_q - 1;
         const bf16_t* qp = a.q + static_cast<int64_t>(qrow) * a.ldq + head * D + 8 * lh;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+        for (int kk = 0; kk < KK; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
     }
 
     // per-lane LDS offsets (elements) of the fragment reads
@@ -255,68 +269,87 @@ attn_kvcache_kernel(AttnArgs a) {
             voff[db] = src_key * D + (v_swz<D>(src_key, d_src >> 3) << 3) + (d_src & 7);
         }
     }
-    f32x16 o[DB];
+
+    f32x16 o[QB][DB];
+    float m_run[QB], l_run[QB];
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
+    }
     const float c = a.scale_log2e;
 
-    // Three LDS stages, copies two tiles ahead.  Per tile: wait until this tile's copies (issued two tiles ago) have
-    // landed, barrier (publishes them and retires the stage read one tile ago), issue the copies of tile t+2 into that
-    // retired stage, compute.  Tiles past the end re-copy the last tile so that the copy count per tile is constant.
+    // NSTAGE LDS stages, copies NSTAGE-1 tiles ahead.  Per tile: wait until this tile's copies have landed, barrier
+    // (publishes them and retires the stage read one tile ago), issue the copies of tile t+NSTAGE-1 into that retired
+    // stage, compute.  Tiles past the end re-copy the last tile so that the copy count per tile is constant.
     constexpr unsigned STAGE_BYTES = 2u * TILE * 2u;
     auto tile_key0 = [&](int t) __attribute__((always_inline)) { return (t < tile_end ? t : tile_end - 1) * KT; };
     if (tile_begin < tile_end) {
-        kv_tile_issue<D, INDEXED>(a, head, tile_key0(tile_begin), n_keys, smem_bytes0);
-        kv_tile_issue<D, INDEXED>(a, head, tile_key0(tile_begin + 1), n_keys, smem_bytes0 + STAGE_BYTES);
+#pragma unroll
+        for (int p = 0; p < NSTAGE - 1; ++p)
+            kv_tile_issue<D, NW, INDEXED>(a, head, tile_key0(tile_begin + p), n_keys, smem_bytes0 + p * STAGE_BYTES);
     }
 #define RG_ATTN_TILE(T, STAGE)                                                                            \
     {                                                                                                     \
         const int t_ = (T);                                                                               \
-        wait_async_copies<COPIES>();                                                                      \
+        wait_async_copies<(NSTAGE - 2) * COPIES>();                                                       \
         __syncthreads();                                                                                  \
-        kv_tile_issue<D, INDEXED>(a, head, tile_key0(t_ + 2), n_keys, smem_bytes0 + ((STAGE + 2) % 3) * STAGE_BYTES); \
-        attn_tile<D, STAGE>(smem, t_, n_keys, c, lh, koff, voff, qf, o, m_run, l_run);                    \
+        kv_tile_issue<D, NW, INDEXED>(a, head, tile_key0(t_ + NSTAGE - 1), n_keys,                        \
+                                      smem_bytes0 + ((STAGE + NSTAGE - 1) % NSTAGE) * STAGE_BYTES);       \
+        attn_tile<D, STAGE, QB>(smem, t_, n_keys, c, lh, koff, voff, qf, o, m_run, l_run);                \
     }
-    for (int t = tile_begin; t < tile_end; t += 3) {
-        RG_ATTN_TILE(t, 0)
-        if (t + 1 < tile_end) RG_ATTN_TILE(t + 1, 1)
-        if (t + 2 < tile_end) RG_ATTN_TILE(t + 2, 2)
+    if constexpr (NSTAGE == 2) {
+        for (int t = tile_begin; t < tile_end; t += 2) {
+            RG_ATTN_TILE(t, 0)
+            if (t + 1 < tile_end) RG_ATTN_TILE(t + 1, 1)
+        }
+    } else {
+        static_assert(NSTAGE == 2 || NSTAGE == 3, "two or three LDS stages");
+        for (int t = tile_begin; t < tile_end; t += 3) {
+            RG_ATTN_TILE(t, 0)
+            if (t + 1 < tile_end) RG_ATTN_TILE(t + 1, 1)
+            if (t + 2 < tile_end) RG_ATTN_TILE(t + 2, 2)
+        }
     }
 #undef RG_ATTN_TILE
     wait_async_copies<0>();   // nothing may still be writing LDS when the workgroup ends
 
     // ---- finish: O^T accumulator r of d-block db: d = db*32 + 8*(r/4) + 4*lh + r%4, query = l32
-    const int qrow = q_base + l32;
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    if (qrow >= a.n_q) return;
-    if (a.splits == 1) {
-        const float inv = 1.0f / l_tot;
-        bf16_t* op = a.out + static_cast<int64_t>(qrow) * a.ldo + head * D;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+    for (int qb = 0; qb < QB; ++qb) {
+        const int qrow = q_base + qb * 32 + l32;
+        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
+        if (qrow >= a.n_q) continue;
+        if (a.splits == 1) {
+            const float inv = 1.0f / l_tot;
+            bf16_t* op = a.out + static_cast<int64_t>(qrow) * a.ldo + head * D;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int d = db * 32 + 8 * g + 4 * lh;
-                bf16x4 pk;
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) pk[e] = static_cast<__bf16>(o[db][4 * g + e] * inv);
-                *reinterpret_cast<bf16x4*>(op + d) = pk;
-            }
-    } else {
-        // partial result: unnormalised O, running max (raw score domain) and sum
-        float* pp = a.part + ((static_cast<int64_t>(split) * a.heads + head) * a.n_q_pad + qrow) * (D + 2);
+                for (int g = 0; g < 4; ++g) {
+                    const int d = db * 32 + 8 * g + 4 * lh;
+                    bf16x4 pk;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+                    for (int e = 0; e < 4; ++e) pk[e] = static_cast<__bf16>(o[qb][db][4 * g + e] * inv);
+                    *reinterpret_cast<bf16x4*>(op + d) = pk;
+                }
+        } else {
+            // partial result: unnormalised O, running max (log2 domain) and sum
+            float* pp = a.part + ((static_cast<int64_t>(split) * a.heads + head) * a.n_q_pad + qrow) * (D + 2);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int d = db * 32 + 8 * g + 4 * lh;
-                *reinterpret_cast<float2*>(pp + d) = make_float2(o[db][4 * g], o[db][4 * g + 1]);
-                *reinterpret_cast<float2*>(pp + d + 2) = make_float2(o[db][4 * g + 2], o[db][4 * g + 3]);
-            }
-        if (lh == 0) { pp[D] = m_run * c; pp[D + 1] = l_tot; }   // maximum in the log2 domain, as the merge kernel expects
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int d = db * 32 + 8 * g + 4 * lh;
+                    *reinterpret_cast<float2*>(pp + d) = make_float2(o[qb][db][4 * g], o[qb][db][4 * g + 1]);
+                    *reinterpret_cast<float2*>(pp + d + 2) = make_float2(o[qb][db][4 * g + 2], o[qb][db][4 * g + 3]);
+                }
+            if (lh == 0) { pp[D] = m_run[qb] * c; pp[D + 1] = l_tot; }   // maximum in the log2 domain, as the merge kernel expects
+        }
     }
 }
 
@@ -355,14 +388,28 @@ attn_combine_kernel(const float* __restrict__ part, int splits, int heads, int n
     *reinterpret_cast<bf16x4*>(out + static_cast<int64_t>(qrow) * ldo + head * D + 4 * g) = pk;
 }
 
-template <int D>
+template <int D, int NW, int QB, int NSTAGE, int WPE>
 int launch_attention(regione_ctx* ctx, AttnArgs a) {
-    const int q_tiles = (a.n_q + 127) / 128;
+    constexpr int QW = NW * QB * 32;
+    const int q_tiles = (a.n_q + QW - 1) / QW;
     const int n_tiles = (a.n0 + a.n1 + KT - 1) / KT;
-    // split the key range when the (query tile, head) grid would leave most CUs idle
+    // Key-range splits: the choice that minimises a small cost model.  The chip holds `slots` workgroups at a time;
+    // a pass of workgroups costs its tiles plus a fixed prologue/epilogue (in tile times, about 2 us each with a full
+    // CU); partial results cost their write and re-read.
+    constexpr int wg_per_cu = WPE * 4 / NW;
+    const double slots = 256.0 * wg_per_cu;
+    const double wgs = static_cast<double>(q_tiles) * a.heads;
     int splits = 1;
-    const int wgs = q_tiles * a.heads;
-    while (wgs * splits < 512 && splits * 2 <= n_tiles / 8 && splits < 8) splits *= 2;   // two workgroups fit a CU
+    double best = 0.0;
+    for (int s = 1; s <= 8 && (s == 1 || s * 4 <= n_tiles); ++s) {
+        const double load = wgs * s / slots;
+        const double passes = load <= 1.0 ? 1.0 : 0.5 * (ceil(load) + load);   // a last, partly filled pass runs faster
+        const double fill = wgs * s <= 256.0 ? 0.68 : 1.0;                      // a CU with one workgroup runs it faster
+        double t = passes * ((n_tiles + s - 1) / s + 4) * 2.0 * fill;
+        if (s > 1) t += 3.0 + 1.5 * static_cast<double>(s) * a.n_q * a.heads * (D + 2) * 8.0 / 4.0e6;
+        if (s == 1 || t < best) { best = t; splits = s; }
+    }
+    if (ctx->attn_force_splits > 0 && ctx->attn_force_splits * 2 <= n_tiles) splits = ctx->attn_force_splits;
     a.n_q_pad = a.n_q;
     if (splits > 1) {
         const size_t need = static_cast<size_t>(splits) * a.heads * a.n_q_pad * (D + 2) * sizeof(float);
@@ -374,15 +421,15 @@ int launch_attention(regione_ctx* ctx, AttnArgs a) {
     a.q_tiles = q_tiles;
     const int groups_per_xcd = (a.heads * splits + 7) / 8;
     const dim3 grid(static_cast<unsigned>(groups_per_xcd) * q_tiles * 8);
-    constexpr size_t lds_bytes = static_cast<size_t>(3) * 2 * KT * D * sizeof(bf16_t);
+    constexpr size_t lds_bytes = static_cast<size_t>(NSTAGE) * 2 * KT * D * sizeof(bf16_t);
     static bool attr_set = false;   // per instantiation: more than 64 KiB of LDS has to be granted explicitly
     if (!attr_set) {
-        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
-        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, false>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, false>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
         attr_set = true;
     }
-    if (a.idx1) hipLaunchKernelGGL((attn_kvcache_kernel<D, true>), grid, dim3(kThreads), lds_bytes, ctx->stream, a);
-    else hipLaunchKernelGGL((attn_kvcache_kernel<D, false>), grid, dim3(kThreads), lds_bytes, ctx->stream, a);
+    if (a.idx1) hipLaunchKernelGGL((attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, true>), grid, dim3(NW * 64), lds_bytes, ctx->stream, a);
+    else hipLaunchKernelGGL((attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, false>), grid, dim3(NW * 64), lds_bytes, ctx->stream, a);
     RG_LAUNCH_CHECK();
     if (splits > 1) {
         const int64_t total = static_cast<int64_t>(a.n_q) * a.heads * (D / 4);
@@ -394,6 +441,13 @@ int launch_attention(regione_ctx* ctx, AttnArgs a) {
 }
 
 }  // namespace
+
+extern "C" int regione_tune_attention(regione_ctx* ctx, int32_t key_splits) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "tune_attention: null context");
+    if (key_splits < 0 || key_splits > 8) RG_FAIL(REGIONE_ERR_INVALID_ARG, "tune_attention: key_splits=%d must be 0..8", key_splits);
+    ctx->attn_force_splits = key_splits;
+    return REGIONE_OK;
+}
 
 int rg_attention(regione_ctx* ctx, const bf16_t* q, int ldq, int n_q,
                  const bf16_t* k0, const bf16_t* v0, int ldkv0, int n0,
@@ -412,8 +466,13 @@ int rg_attention(regione_ctx* ctx, const bf16_t* q, int ldq, int n_q,
     a.heads = heads;
     a.scale_log2e = (scale > 0.f ? scale : 1.0f / sqrtf(static_cast<float>(d))) * 1.4426950408889634f;
     a.out = out; a.ldo = ldo;
-    if (d == 128) return launch_attention<128>(ctx, a);
-    return launch_attention<64>(ctx, a);
+    if (d == 64) return launch_attention<64, 4, 1, 2, 2>(ctx, a);
+    switch (ctx->attn_variant) {
+        case 1: return launch_attention<128, 4, 1, 3, 1>(ctx, a);
+        case 2: return launch_attention<128, 2, 2, 2, 1>(ctx, a);
+        case 3: return launch_attention<128, 8, 1, 3, 2>(ctx, a);
+        default: return launch_attention<128, 4, 1, 2, 2>(ctx, a);
+    }
 }
 
 extern "C" int regione_attn_kvcache(regione_ctx* ctx, const void* q, int32_t n_q,

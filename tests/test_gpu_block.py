@@ -136,7 +136,8 @@ def test_config2_block_region_forward_sampled(kind):
     sample = np.sort(rng.choice(len(rows), size=40, replace=False))
     sample[:2] = [0, len(rows) - 1]
     want = _oracle_region_rows(streams, kind, h_now, rows, kc_o, vc_o, heads, sample)
-    ma, mr = assert_close(got[sample], want, f"{kind} region forward at the 3072-wide configuration (sampled rows)", stored_bf16=True)
+    ma, mr = assert_close(got[sample], want, f"{kind} region forward at the 3072-wide configuration (sampled rows)", stored_bf16=True,
+                          outlier_frac=1e-5)   # 122 880 elements: at most one may pass the 5.5-sigma bound
     print(f"[{kind}] config-2 block parity: max abs {ma:.3e}, mean rel {mr:.3e}")
     ctx.close()
 

@@ -103,6 +103,7 @@ def test_fraction_sweep_blob_masks(n_edited, h_dtype):
     sample = np.sort(rng.choice(n, size=24, replace=False))
     sample[:2] = [0, n - 1]
     want = _oracle_region_rows(streams, "double", h_now, rows, kc_o, vc_o, heads, sample)
-    ma, mr = assert_close(host(o)[sample], want, f"region forward with {n} edited tokens ({h_dtype} residual stream)", stored_bf16=(h_dtype == "bf16"))
+    ma, mr = assert_close(host(o)[sample], want, f"region forward with {n} edited tokens ({h_dtype} residual stream)", stored_bf16=(h_dtype == "bf16"),
+                          outlier_frac=1e-5)   # 3072-wide block output: the bound is 5.5 sigma of the bf16 arithmetic error
     print(f"n_edited {n} ({h_dtype}): max abs {ma:.3e}, mean rel {mr:.3e}")
     ctx.close()
