@@ -14,10 +14,15 @@ SOURCES = ["api.hip", "partition.hip", "rows.hip", "gemm.hip", "attention.hip"]
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument", "-fgpu-rdc" if False else "-fno-gpu-rdc",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-Wno-unused-command-line-argument", "-fno-gpu-rdc",
+             "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    # The GEMM's hand-pipelined loads are only correct if the compiler left their registers alone: prove it on the
+    # machine code before anything is linked, with the very flags of the build.
+    from . import isa_check
+    isa_check.check_gemm(hipcc, flags, os.path.join(CSRC, "gemm.hip"))
+    cmd = [hipcc, *flags, "-fPIC", "-shared"]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     cmd += ["-o", LIB]
     if verbose:
@@ -32,4 +37,6 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
+    sys.path.insert(0, ROOT)
+    __package__ = "paper_2510_25590_amd"
     print(build(verbose=True))

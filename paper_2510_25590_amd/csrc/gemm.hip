@@ -247,21 +247,27 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // The K-steps run in groups of four through a software pipeline without any branch inside (so that the order of
+    // its loads and waits is the same on every path, which the build verifies on the machine code); the up to three
+    // steps that remain run one at a time behind it.
     constexpr int DEPTH = Pipe<TN>::DEPTH, NSETS = Pipe<TN>::NSETS;
-    u32x4 areg[NSETS][A_PER_THREAD];
-    u32x4 wreg[NSETS][TN * 4];
-    // steps past the end of this split re-load its last step
-    constexpr int L = A_PER_THREAD + 4 * TN;        // loads per thread and K-step
+    static_assert(NSETS == 4, "the unrolled schedule below rotates four register sets");
+    const int n4 = nks & ~3;
+    if (n4 > 0) {
+        u32x4 areg[NSETS][A_PER_THREAD];
+        u32x4 wreg[NSETS][TN * 4];
+        constexpr int L = A_PER_THREAD + 4 * TN;        // loads per thread and K-step
+        // steps past the end of the pipelined part re-load its last step (keeps the number of loads in flight constant)
 #pragma unroll
-    for (int p = 0; p < DEPTH; ++p) load_step<TN>(areg[p], wreg[p], a_rows, w_blk, ks_begin + (p < nks ? p : nks - 1));
-    rg_wait_loads<(DEPTH - 1) * L, TN>(areg[0], wreg[0]);
-    a_store(a_lds[0], areg[0]);
-    __syncthreads();
+        for (int p = 0; p < DEPTH; ++p) load_step<TN>(areg[p], wreg[p], a_rows, w_blk, ks_begin + (p < n4 ? p : n4 - 1));
+        rg_wait_loads<(DEPTH - 1) * L, TN>(areg[0], wreg[0]);
+        a_store(a_lds[0], areg[0]);
+        __syncthreads();
 
-    // One K-step.  S = j % NSETS names the register set that holds step j; the loads of step j + DEPTH go to the
-    // set freed by step j - 1; they are issued a quarter at a time in front of each quarter's MFMAs, together with the
-    // LDS reads of the next quarter, so that the memory pipes work in the shadow of the matrix cores.
-    // (A macro, not a lambda: captured arrays would live in memory.)
+        // One K-step.  S = j % NSETS names the register set that holds step j; the loads of step j + DEPTH go to the
+        // set freed by step j - 1; they are issued a quarter at a time in front of each quarter's MFMAs, together with
+        // the LDS reads of the next quarter, so that the memory pipes work in the shadow of the matrix cores.
+        // (A macro, not a lambda: captured arrays would live in memory.)
 #define RG_GEMM_QUARTER(KK, S, SD)                                                                        \
     {                                                                                                     \
         /* memory instructions of this quarter first, then its MFMAs: they run under the MFMAs */           \
@@ -280,44 +286,57 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
 #define RG_GEMM_STEP(J, S, S1, SD)                                                                        \
     {                                                                                                     \
         const int j_ = (J);                                                                               \
-        const int st_ = ks_begin + (j_ + DEPTH < nks ? j_ + DEPTH : nks - 1);                             \
-        if (j_ < nks) {                                                                                   \
-            const bf16_t* at = a_lds[j_ & 1];                                                             \
-            bf16x8 af[2][TM];                                                                             \
-            _Pragma("unroll") for (int i = 0; i < TM; ++i) af[0][i] = a_frag(at, i * 32 + l32, lh);       \
-            RG_GEMM_QUARTER(0, S, SD)                                                                     \
-            RG_GEMM_QUARTER(1, S, SD)                                                                     \
-            RG_GEMM_QUARTER(2, S, SD)                                                                     \
-            RG_GEMM_QUARTER(3, S, SD)                                                                     \
-        } else {                                                                                          \
-            load_step<TN>(areg[SD], wreg[SD], a_rows, w_blk, st_);                                        \
-        }                                                                                                 \
+        const int st_ = ks_begin + (j_ + DEPTH < n4 ? j_ + DEPTH : n4 - 1);                               \
+        const bf16_t* at = a_lds[j_ & 1];                                                                 \
+        bf16x8 af[2][TM];                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) af[0][i] = a_frag(at, i * 32 + l32, lh);           \
+        RG_GEMM_QUARTER(0, S, SD)                                                                         \
+        RG_GEMM_QUARTER(1, S, SD)                                                                         \
+        RG_GEMM_QUARTER(2, S, SD)                                                                         \
+        RG_GEMM_QUARTER(3, S, SD)                                                                         \
         /* steps j+1 .. j+DEPTH are in flight; step j+1 is needed now (its A tile here, its weights next step) */ \
         rg_wait_loads<(DEPTH - 1) * L, TN>(areg[S1], wreg[S1]);                                           \
         a_store(a_lds[(j_ + 1) & 1], areg[S1]);                                                           \
         __syncthreads();                                                                                  \
     }
-    if constexpr (NSETS == 4) {
-        for (int j = 0; j < nks; j += 4) {
+        for (int j = 0; j < n4; j += 4) {
             RG_GEMM_STEP(j, 0, 1, 3)
             RG_GEMM_STEP(j + 1, 1, 2, 0)
             RG_GEMM_STEP(j + 2, 2, 3, 1)
             RG_GEMM_STEP(j + 3, 3, 0, 2)
         }
-    } else {
-        static_assert(NSETS == 4 || NSETS == 5, "unrolled schedules exist for four and five register sets");
-        for (int j = 0; j < nks; j += 5) {
-            RG_GEMM_STEP(j, 0, 1, 4)
-            RG_GEMM_STEP(j + 1, 1, 2, 0)
-            RG_GEMM_STEP(j + 2, 2, 3, 1)
-            RG_GEMM_STEP(j + 3, 3, 4, 2)
-            RG_GEMM_STEP(j + 4, 4, 0, 3)
-        }
-    }
 #undef RG_GEMM_STEP
 #undef RG_GEMM_QUARTER
-    // the loads issued for steps past the end are still in flight; they must land before their registers are reused
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // the loads issued for steps past the end are still in flight; they must land before their registers are reused
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    // remaining steps, one at a time: A tile through registers into LDS, weight fragments into registers, then the MFMAs
+    for (int j = n4; j < nks; ++j) {
+        const int st = ks_begin + j;
+        u32x4 ar[A_PER_THREAD];
+        bf16x8 wf[TN][4];
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) ar[i] = *reinterpret_cast<const u32x4*>(a_rows[i] + st * BK);
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                wf[jn][kk] = *reinterpret_cast<const bf16x8*>(w_blk[jn] + static_cast<int64_t>(st) * 2048 + kk * 512);
+        __syncthreads();   // every wave has finished reading the tile of the step before
+        a_store(a_lds[0], ar);
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 af[TM];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = a_frag(a_lds[0], i * 32 + l32, kk * 2 + lh);
+#pragma unroll
+            for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[jn][kk], acc[i][jn], 0, 0, 0);
+        }
+    }
 
     // accumulator (i, j, r) of a lane: row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32 of the 32x32 block
     float* part_base = partial ? partial + (static_cast<int64_t>(blockIdx.y) * M) * N : nullptr;
