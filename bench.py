@@ -22,7 +22,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # L2 <-> fabric bytes of the GEMM launches of one step of the default workload (820 edited tokens), from two
 # rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): see
 # profiles/gemm_attention_hbm_traffic.txt.  Per launch = per step / 5 launches, like `achieved`.
-MEASURED_GEMM_TRAFFIC_BYTES_PER_STEP = {820: 716.0e6}
+MEASURED_GEMM_TRAFFIC_BYTES_PER_STEP = {820: 785.0e6}
 
 
 def cpu_baseline(cfg, hst, reps):
