@@ -143,6 +143,84 @@ __device__ __forceinline__ void epilogue_store8(const GemmEpilogue& ep, int row,
     }
 }
 
+// Writes a workgroup's accumulators.  `stage_lds`: at least 32 KiB of LDS that no wave reads any more once all waves
+// have passed the barrier inside.  accumulator (i, j, r) of a lane: row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32
+// of the 32x32 block (i, j) of the wave tile.
+template <int TN, int KIND>
+__device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[TM][TN], float* stage_lds, int M, int N, int m0, int n0,
+                                              float* __restrict__ partial, const GemmEpilogue& ep) {
+    constexpr int WN = 32 * TN;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int wn0 = wave * WN;
+    float* part_base = partial ? partial + (static_cast<int64_t>(blockIdx.y) * M) * N : nullptr;
+    if (ep.vec_ok) {
+        // Transpose through LDS, 32 rows at a time, so that every lane ends up with eight consecutive columns of one
+        // row: bias, gate, residual and result then move in 16- or 32-byte pieces.  Each wave stages in its own 8 KiB.
+        __syncthreads();   // every wave has finished reading the A tiles
+        float* stage = stage_lds + wave * (32 * 64);
+        constexpr int G = WN / 8;            // column groups per row
+        constexpr int ROWS_PER_PASS = 64 / G;
+        const int cg = lane % G, rsub = lane / G;
+        const int col0 = n0 + wn0 + cg * 8;
+        const bool col_live = col0 < N;      // N is a multiple of 8 on this path
+        float bias[8], gate[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            bias[e] = (!partial && col_live && ep.bias) ? ep.bias[col0 + e] : 0.f;
+            gate[e] = (!partial && col_live && KIND == EPI_RESID && ep.gate) ? ep.gate[col0 + e] : 1.f;
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    stage[(8 * (r >> 2) + 4 * lh + (r & 3)) * WN + j * 32 + l32] = acc[i][j][r];
+#pragma unroll
+            for (int p = 0; p < 32 / ROWS_PER_PASS; ++p) {
+                const int rr = p * ROWS_PER_PASS + rsub;
+                const int row = m0 + i * 32 + rr;
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(stage + rr * WN + cg * 8);
+                const f32x4 hi = *reinterpret_cast<const f32x4*>(stage + rr * WN + cg * 8 + 4);
+                const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                if (row < M && col_live) {
+                    if (partial) store8(part_base, static_cast<int64_t>(row) * N + col0, 1, v);
+                    else epilogue_store8<KIND>(ep, row, col0, v, bias, gate);
+                }
+            }
+        }
+        return;
+    }
+    int col[TN];
+    float bias[TN], gate[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        col[j] = n0 + wn0 + j * 32 + l32;
+        const bool live = col[j] < N;
+        bias[j] = (!partial && live && ep.bias) ? ep.bias[col[j]] : 0.f;
+        gate[j] = (!partial && live && KIND == EPI_RESID && ep.gate) ? ep.gate[col[j]] : 1.f;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            if (row >= M) continue;
+            if (partial) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    if (col[j] < N) part_base[static_cast<int64_t>(row) * N + col[j]] = acc[i][j][r];
+            } else {
+                const int64_t kv_row = epilogue_kv_row<KIND>(ep, row);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    if (col[j] < N) epilogue_store<KIND>(ep, row, kv_row, col[j], acc[i][j][r], bias[j], gate[j]);
+            }
+        }
+    }
+}
+
 // Global loads of the pipeline are written in assembly and waited for by hand.  Left to the compiler, the rotating
 // register sets made its wait-count insertion drain nearly every outstanding load at the top of a K-step (it reuses
 // the registers of a consumed set for LDS fragments and then protects them against loads it believes pending), which
@@ -338,73 +416,144 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
         }
     }
 
-    // accumulator (i, j, r) of a lane: row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32 of the 32x32 block
-    float* part_base = partial ? partial + (static_cast<int64_t>(blockIdx.y) * M) * N : nullptr;
-    if (ep.vec_ok) {
-        // Transpose through LDS, 32 rows at a time, so that every lane ends up with eight consecutive columns of one
-        // row: bias, gate, residual and result then move in 16- or 32-byte pieces.  Each wave stages in its own 8 KiB.
-        __syncthreads();   // every wave has finished reading the A tiles
-        float* stage = reinterpret_cast<float*>(&a_lds[0][0]) + wave * (32 * 64);
-        constexpr int G = WN / 8;            // column groups per row
-        constexpr int ROWS_PER_PASS = 64 / G;
-        const int cg = lane % G, rsub = lane / G;
-        const int col0 = n0 + wn0 + cg * 8;
-        const bool col_live = col0 < N;      // N is a multiple of 8 on this path
-        float bias[8], gate[8];
+    gemm_epilogue<TN, KIND>(acc, reinterpret_cast<float*>(&a_lds[0][0]), M, N, m0, n0, partial, ep);
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Second GEMM kernel: both operands through LDS by asynchronous global-to-LDS copies, no staging registers.
+// 128 x (128*TN) workgroup tile, four waves split N as above, K in stages of 32.  Without register sets for the
+// pipeline a wave needs fewer than 256 registers, so two workgroups share a CU: while one waits at a barrier or on
+// LDS, the other keeps the matrix cores busy.
+//   stage = A tile [128 rows x 32 k] (rows of 64 bytes, 16-byte chunk c of row r stored at chunk c ^ ((r >> 2) & 3):
+//           the 16 rows of a ds_read_b128 phase then cover all 64 banks once)
+//         + per wave, TN blocks x 2 k-groups of packed-weight fragments (1 KiB each, lane l's 16 bytes at 16*l:
+//           exactly what the packed layout holds, so the copy is linear and the read conflict-free)
+constexpr int LK = 32;                 // k elements per stage
+constexpr int L_STAGES = 3;
+template <int TN> struct LdsGemm {
+    static constexpr unsigned A_BYTES = BM * LK * 2;                 // 8 KiB
+    static constexpr unsigned W_BYTES = 4 * TN * 2 * 1024;           // 8 KiB per 32 columns of wave tile
+    static constexpr unsigned STAGE_BYTES = A_BYTES + W_BYTES;
+    static constexpr unsigned LDS_BYTES = (L_STAGES * STAGE_BYTES > 32768u ? L_STAGES * STAGE_BYTES : 32768u);   // epilogue staging needs 32 KiB
+    static constexpr int COPIES = 2 + 2 * TN;                        // asynchronous copies per thread and stage
+};
+
+// lane l of the wave writes LDS[lds_base + 16*l .. +16) from src (wave-uniform lds_base); counted in vmcnt
+__device__ __forceinline__ void rg_async_copy16(const bf16_t* src, unsigned lds_base_bytes) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(src), "s"(lds_base_bytes) : "memory", "m0");
+}
+
+template <int TN, int KIND>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+gemm_lds_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ Wp,
+                int M, int N, int K, int m_tiles, int n_tiles, int tiles_per_xcd,
+                int steps_per_split, float* __restrict__ partial, GemmEpilogue ep) {
+    using G = LdsGemm<TN>;
+    constexpr int WN = 32 * TN, BN = 4 * WN;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const unsigned lds0 = static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) void*)(lds_raw)));
+
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int tile = xcd * tiles_per_xcd + local;
+    if (local >= tiles_per_xcd || tile >= m_tiles * n_tiles) return;
+    const int n_tile = tile / m_tiles, m_tile = tile - n_tile * m_tiles;
+    const int m0 = m_tile * BM, n0 = n_tile * BN;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int wn0 = wave * WN;
+
+    const int total_steps = K / BK;            // split-K bookkeeping stays in steps of 64
+    const int ks_begin = blockIdx.y * steps_per_split;
+    int nks = total_steps - ks_begin;
+    nks = nks < steps_per_split ? nks : steps_per_split;
+    const int n_stages = nks * (BK / LK);
+    const int k_begin = ks_begin * BK;
+
+    // copy sources.  A: thread t owns LDS slots t and t + 256 of the stage's A tile (slot = row*4 + physical chunk);
+    // the swizzle is applied on the global side: the lane that owns physical chunk p of a row loads logical chunk
+    // p ^ ((row >> 2) & 3).  Rows past M repeat the last row; their results are never stored.
+    const bf16_t* a_src[2];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            bias[e] = (!partial && col_live && ep.bias) ? ep.bias[col0 + e] : 0.f;
-            gate[e] = (!partial && col_live && KIND == EPI_RESID && ep.gate) ? ep.gate[col0 + e] : 1.f;
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    stage[(8 * (r >> 2) + 4 * lh + (r & 3)) * WN + j * 32 + l32] = acc[i][j][r];
-#pragma unroll
-            for (int p = 0; p < 32 / ROWS_PER_PASS; ++p) {
-                const int rr = p * ROWS_PER_PASS + rsub;
-                const int row = m0 + i * 32 + rr;
-                const f32x4 lo = *reinterpret_cast<const f32x4*>(stage + rr * WN + cg * 8);
-                const f32x4 hi = *reinterpret_cast<const f32x4*>(stage + rr * WN + cg * 8 + 4);
-                const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                if (row < M && col_live) {
-                    if (partial) store8(part_base, static_cast<int64_t>(row) * N + col0, 1, v);
-                    else epilogue_store8<KIND>(ep, row, col0, v, bias, gate);
-                }
-            }
-        }
-        return;
+    for (int i = 0; i < 2; ++i) {
+        const int slot = threadIdx.x + 256 * i;
+        const int row = slot >> 2, phys = slot & 3;
+        int r = m0 + row;
+        r = r < M ? r : M - 1;
+        a_src[i] = A + static_cast<int64_t>(r) * lda + k_begin + ((phys ^ ((row >> 2) & 3)) << 3);
     }
-    int col[TN];
-    float bias[TN], gate[TN];
+    const int n_blocks = (N + 31) >> 5;
+    const int64_t blk_stride = static_cast<int64_t>(K >> 4) * 512;   // elements per 32-column block
+    const bf16_t* w_src[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        col[j] = n0 + wn0 + j * 32 + l32;
-        const bool live = col[j] < N;
-        bias[j] = (!partial && live && ep.bias) ? ep.bias[col[j]] : 0.f;
-        gate[j] = (!partial && live && KIND == EPI_RESID && ep.gate) ? ep.gate[col[j]] : 1.f;
+        int nb = ((n0 + wn0) >> 5) + j;
+        nb = nb < n_blocks ? nb : n_blocks - 1;                      // blocks past N repeat the last block
+        w_src[j] = Wp + nb * blk_stride + static_cast<int64_t>(k_begin >> 4) * 512 + lane * 8;
     }
+    const unsigned a_dst = __builtin_amdgcn_readfirstlane(lds0 + static_cast<unsigned>(wave) * 1024u);
+    const unsigned w_dst = __builtin_amdgcn_readfirstlane(lds0 + G::A_BYTES + static_cast<unsigned>(wave) * (TN * 2048u));
+    auto issue = [&](int st, unsigned stage_off) __attribute__((always_inline)) {   // st: stage index, clamped by the caller
+        rg_async_copy16(a_src[0] + st * LK, a_dst + stage_off);
+        rg_async_copy16(a_src[1] + st * LK, a_dst + stage_off + 4096u);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-            if (row >= M) continue;
-            if (partial) {
+            for (int g = 0; g < 2; ++g)
+                rg_async_copy16(w_src[j] + (static_cast<int64_t>(st) * 2 + g) * 512, w_dst + stage_off + static_cast<unsigned>(j * 2 + g) * 1024u);
+    };
+
+    // fragment read offsets (bytes inside a stage)
+    unsigned a_off[2][TM];
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    if (col[j] < N) part_base[static_cast<int64_t>(row) * N + col[j]] = acc[i][j][r];
-            } else {
-                const int64_t kv_row = epilogue_kv_row<KIND>(ep, row);
+    for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    if (col[j] < N) epilogue_store<KIND>(ep, row, kv_row, col[j], acc[i][j][r], bias[j], gate[j]);
-            }
+        for (int i = 0; i < TM; ++i) {
+            const int row = i * 32 + l32;
+            a_off[kk][i] = static_cast<unsigned>(row) * 64u + static_cast<unsigned>(((2 * kk + lh) ^ ((row >> 2) & 3)) << 4);
         }
+    const unsigned w_off = G::A_BYTES + static_cast<unsigned>(wave) * (TN * 2048u) + static_cast<unsigned>(lane) * 16u;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // L_STAGES LDS stages, copies L_STAGES-1 stages ahead.  Per stage: wait until its copies have landed, barrier
+    // (publishes them and retires the stage read one iteration ago), issue the copies of stage t + L_STAGES - 1 into
+    // the retired buffer, compute.  Stages past the end re-copy the last one, so the copy count per stage is constant.
+    auto clamp_stage = [&](int t) __attribute__((always_inline)) { return t < n_stages ? t : n_stages - 1; };
+#pragma unroll
+    for (int p = 0; p < L_STAGES - 1; ++p) issue(clamp_stage(p), p * G::STAGE_BYTES);
+#define RG_LDS_STAGE(T, S)                                                                                \
+    {                                                                                                     \
+        const int t_ = (T);                                                                               \
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((L_STAGES - 2) * G::COPIES) : "memory");                 \
+        __syncthreads();                                                                                  \
+        issue(clamp_stage(t_ + L_STAGES - 1), ((S + L_STAGES - 1) % L_STAGES) * G::STAGE_BYTES);          \
+        const unsigned char* st_ = lds_raw + (S) * G::STAGE_BYTES;                                        \
+        bf16x8 af[2][TM], wf[2][TN];                                                                      \
+        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                \
+            _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                \
+                af[kk][i] = *reinterpret_cast<const bf16x8*>(st_ + a_off[kk][i]);                         \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                \
+                wf[kk][j] = *reinterpret_cast<const bf16x8*>(st_ + w_off + (j * 2 + kk) * 1024);          \
+        }                                                                                                 \
+        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk)                                                  \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                \
+                _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], wf[kk][j], acc[i][j], 0, 0, 0); \
     }
+    for (int t = 0; t < n_stages; t += 3) {
+        RG_LDS_STAGE(t, 0)
+        if (t + 1 < n_stages) RG_LDS_STAGE(t + 1, 1)
+        if (t + 2 < n_stages) RG_LDS_STAGE(t + 2, 2)
+    }
+#undef RG_LDS_STAGE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may still be writing LDS when the epilogue reuses it
+    gemm_epilogue<TN, KIND>(acc, reinterpret_cast<float*>(lds_raw), M, N, m0, n0, partial, ep);
 }
 
 // Sums the split-K partial results and applies the epilogue.  One thread per output element, columns fastest.
@@ -440,15 +589,16 @@ pack_weight_kernel(const bf16_t* __restrict__ w, int n, int k, bf16_t* __restric
     }
 }
 
-struct GemmPlan { int tn; int splits; };
+struct GemmPlan { int tn; int splits; bool lds; };
 
 // Picks the wave-tile width and the K split that finish soonest under a model fitted to measurements on MI355X:
 // a K-step of a 128 x 256 workgroup takes about 1.05 us; a 128 x 128 workgroup takes 0.65 us alone on a CU and
 // 1.1 us when two share one (its registers allow that); split-K adds a pass over the float partial sums.
 GemmPlan plan_gemm(const regione_ctx* ctx, int m, int n, int k) {
-    if (ctx->gemm_force_tn > 0) return {ctx->gemm_force_tn, ctx->gemm_force_splits > 0 ? ctx->gemm_force_splits : 1};
+    if (ctx->gemm_force_tn > 0)
+        return {ctx->gemm_force_tn > 2 ? ctx->gemm_force_tn - 2 : ctx->gemm_force_tn, ctx->gemm_force_splits > 0 ? ctx->gemm_force_splits : 1, ctx->gemm_force_tn > 2};
     const int m_tiles = (m + BM - 1) / BM, steps = k / BK;
-    GemmPlan best = {2, 1};
+    GemmPlan best = {2, 1, false};
     double best_t = 1e30;
     for (int tn = 1; tn <= 2; ++tn) {
         const int n_tiles = (n + 128 * tn - 1) / (128 * tn);
@@ -463,13 +613,13 @@ GemmPlan plan_gemm(const regione_ctx* ctx, int m, int n, int k) {
             const double t_rem = tn == 1 ? (rem <= 256 ? 0.65 : 1.1) : t_wide;
             double t = per * (full * t_full + (rem > 0 ? t_rem : 0.0)) + 4.0;
             if (s > 1) t += 3.0 + (s + 1.0) * m * n * 4.0 / 3.0e6;
-            if (t < best_t) { best_t = t; best = {tn, s}; }
+            if (t < best_t) { best_t = t; best = {tn, s, false}; }
         }
     }
     return best;
 }
 
-template <int TN, int KIND>
+template <int TN, int KIND, bool LDSK>
 int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, int splits, const GemmEpilogue& ep) {
     constexpr int BN = 128 * TN;
     const int m_tiles = (m + BM - 1) / BM, n_tiles = (n + BN - 1) / BN;
@@ -481,8 +631,19 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, in
     if (used_splits > 1 && static_cast<size_t>(used_splits) * m * n * sizeof(float) > ctx->gemm_part_bytes)
         RG_FAIL(REGIONE_ERR_WORKSPACE, "gemm: %d K-splits of a %d x %d result exceed the workspace", used_splits, m, n);
     float* partial = used_splits > 1 ? ctx->gemm_part : nullptr;
-    hipLaunchKernelGGL((gemm_bf16_kernel<TN, KIND>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads), 0, ctx->stream,
-                       a, lda, wp, m, n, k, m_tiles, n_tiles, tiles_per_xcd, per, partial, ep);
+    if (LDSK) {
+        constexpr unsigned lds_bytes = LdsGemm<TN>::LDS_BYTES;
+        static bool attr_set = false;   // per instantiation: more than 64 KiB of LDS has to be granted explicitly
+        if (!attr_set) {
+            RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel<TN, KIND>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL((gemm_lds_kernel<TN, KIND>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads), lds_bytes, ctx->stream,
+                           a, lda, wp, m, n, k, m_tiles, n_tiles, tiles_per_xcd, per, partial, ep);
+    } else {
+        hipLaunchKernelGGL((gemm_bf16_kernel<TN, KIND>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads), 0, ctx->stream,
+                           a, lda, wp, m, n, k, m_tiles, n_tiles, tiles_per_xcd, per, partial, ep);
+    }
     RG_LAUNCH_CHECK();
     if (used_splits > 1) {
         const int64_t total = static_cast<int64_t>(m) * n;
@@ -498,8 +659,12 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, in
 template <int KIND>
 int dispatch(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, const GemmEpilogue& ep) {
     const GemmPlan p = plan_gemm(ctx, m, n, k);
-    if (p.tn == 1) return launch_gemm<1, KIND>(ctx, a, lda, wp, m, n, k, p.splits, ep);
-    return launch_gemm<2, KIND>(ctx, a, lda, wp, m, n, k, p.splits, ep);
+    if (p.lds) {
+        if (p.tn == 1) return launch_gemm<1, KIND, true>(ctx, a, lda, wp, m, n, k, p.splits, ep);
+        return launch_gemm<2, KIND, true>(ctx, a, lda, wp, m, n, k, p.splits, ep);
+    }
+    if (p.tn == 1) return launch_gemm<1, KIND, false>(ctx, a, lda, wp, m, n, k, p.splits, ep);
+    return launch_gemm<2, KIND, false>(ctx, a, lda, wp, m, n, k, p.splits, ep);
 }
 
 }  // namespace
@@ -545,7 +710,7 @@ extern "C" int regione_pack_weight(regione_ctx* ctx, const void* w, int32_t n, i
 
 extern "C" int regione_tune_gemm(regione_ctx* ctx, int32_t wave_tile_blocks, int32_t k_splits) {
     if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "tune_gemm: null context");
-    if (wave_tile_blocks < 0 || wave_tile_blocks > 2 || k_splits < 0 || k_splits > 16) RG_FAIL(REGIONE_ERR_INVALID_ARG, "tune_gemm: wave_tile_blocks in 0..2, k_splits in 0..16");
+    if (wave_tile_blocks < 0 || wave_tile_blocks > 4 || k_splits < 0 || k_splits > 16) RG_FAIL(REGIONE_ERR_INVALID_ARG, "tune_gemm: wave_tile_blocks in 0..4, k_splits in 0..16");
     ctx->gemm_force_tn = wave_tile_blocks;
     ctx->gemm_force_splits = k_splits;
     return REGIONE_OK;
