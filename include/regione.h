@@ -187,6 +187,38 @@ int regione_block_forward(regione_ctx* ctx, const regione_block_weights* w, int3
                           int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
                           void* k_cache, void* v_cache, int32_t n_all, int32_t flags);
 
+/* dst[i] = src[i] converted between the storage types (to bf16: round to nearest even).  Lets a
+ * caller keep the latents of the sampling loop in float32 and feed bf16 rows to the token
+ * embedding.  Same dtype on both sides is a plain copy. */
+int regione_cast(regione_ctx* ctx, const void* src, int32_t src_dtype, void* dst, int32_t dst_dtype, int64_t n_elems);
+
+/* LayerNorm over the hidden width (no affine parameters, biased variance, eps 1e-6) followed
+ * by the optional modulation u = y * (1 + scale) + shift: the normalisation in front of the
+ * velocity head around the blocks (the blocks apply the same operation internally).
+ * h [n, hidden] of h_dtype; shift_opt / scale_opt [hidden] float32 or NULL (identity);
+ * u [n, hidden] bf16. */
+int regione_layernorm(regione_ctx* ctx, const void* h, int32_t h_dtype, int32_t n, int32_t hidden,
+                      const float* shift_opt, const float* scale_opt, void* u);
+
+/* Control flow of Algorithm 1 (host, pure function of its hyper-parameters).  Timestep
+ * indices run i = T..1; the step at index i moves X_{t_i} to X_{t_{i-1}}.  The stabilization
+ * stage is t_st full steps, the last of which stores the KV cache; forced_k[n_forced] are
+ * 0-based forward step counters (k = T - i) of forced full steps inside the region-aware
+ * stage; every segment of region steps is closed by one storing full step; the last
+ * segment's closing step is the first of the t_sm smooth steps.  Writes the steps in the
+ * order they run.  seg_next of a region step is the index `next` of its segment (the
+ * unedited rows jump to t_{next+1} at the segment's first step); -1 for full steps.
+ * Returns REGIONE_ERR_INVALID_ARG if the stages do not fit T or max_steps is too small. */
+enum { REGIONE_STEP_FULL = 0, REGIONE_STEP_FULL_STORE = 1, REGIONE_STEP_REGION = 2 };
+typedef struct regione_plan_step {
+    int32_t i;         /* timestep index of the step */
+    int32_t kind;      /* REGIONE_STEP_* */
+    int32_t seg_first; /* 1 for the first region step of a segment, else 0 */
+    int32_t seg_next;  /* region steps: `next` of the segment; full steps: -1 */
+} regione_plan_step;
+int regione_stage_plan_host(int32_t T, int32_t t_st, int32_t t_sm, const int32_t* forced_k, int32_t n_forced,
+                            regione_plan_step* steps_out, int32_t max_steps, int32_t* n_steps_out);
+
 /* Adaptive velocity decay cache, host decision (Eq.7, Eq.8): pure function of the
  * schedule.  t_host has n_steps+1 entries with t[n_steps] = 1 and t[0] = 0; gamma_host has
  * n_steps+1 entries (gamma[j] corrects the step at index j).  For the step at index j

@@ -25,7 +25,9 @@ EXPORTS = (
     "regione_scatter", "regione_attn_kvcache", "regione_linear", "regione_block_forward",
     "regione_velocity_decision_host", "regione_velocity_cache", "regione_profile_enable", "regione_profile_read",
     "regione_packed_weight_elems", "regione_pack_weight", "regione_tune_gemm", "regione_tune_attention",
+    "regione_layernorm", "regione_stage_plan_host", "regione_cast",
 )
+STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
 
 
@@ -48,6 +50,10 @@ class BlockWeights(C.Structure):
 
 class AvdState(C.Structure):
     _fields_ = [("valid", C.c_int32), ("prod", C.c_double)]
+
+
+class PlanStep(C.Structure):
+    _fields_ = [("i", C.c_int32), ("kind", C.c_int32), ("seg_first", C.c_int32), ("seg_next", C.c_int32)]
 
 
 class RegionEError(RuntimeError):
@@ -82,6 +88,9 @@ def lib() -> C.CDLL:
             "regione_pack_weight": [vp, vp, i32, i32, vp],
             "regione_tune_gemm": [vp, i32, i32],
             "regione_tune_attention": [vp, i32],
+            "regione_layernorm": [vp, vp, i32, i32, i32, vp, vp, vp],
+            "regione_cast": [vp, vp, i32, vp, i32, i64],
+            "regione_stage_plan_host": [i32, i32, i32, C.POINTER(i32), i32, C.POINTER(PlanStep), i32, C.POINTER(i32)],
             "regione_profile_enable": [vp, i32],
             "regione_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(i64), i32],
         }
@@ -186,6 +195,24 @@ def regione_velocity_decision_host(t, gamma, n_steps, delta, j, state: AvdState)
 def regione_velocity_cache(ctx, reuse, factor, dt, v_fresh, c_a, v_out, x_e, n_dev, n_max, c, dtype):
     _check(lib().regione_velocity_cache(ctx.handle, int(bool(reuse)), factor, dt, _p(v_fresh), _p(c_a), _p(v_out), _p(x_e),
                                         _p(n_dev), n_max, c, dtype))
+
+
+def regione_cast(ctx, src, src_dtype, dst, dst_dtype, n_elems):
+    _check(lib().regione_cast(ctx.handle, _p(src), src_dtype, _p(dst), dst_dtype, n_elems))
+
+
+def regione_layernorm(ctx, h, h_dtype, n, hidden, shift, scale, u):
+    _check(lib().regione_layernorm(ctx.handle, _p(h), h_dtype, n, hidden, _p(shift), _p(scale), _p(u)))
+
+
+def regione_stage_plan_host(T: int, t_st: int, t_sm: int, forced_k):
+    """Returns the steps of Algorithm 1 in the order they run, as a list of PlanStep."""
+    forced = [int(k) for k in forced_k]
+    arr = (C.c_int32 * max(len(forced), 1))(*forced)
+    steps = (PlanStep * (T + 1))()
+    n = C.c_int32(0)
+    _check(lib().regione_stage_plan_host(T, t_st, t_sm, arr, len(forced), steps, T + 1, C.byref(n)))
+    return [steps[k] for k in range(n.value)]
 
 
 def regione_profile_enable(ctx, on: bool):

@@ -1,6 +1,9 @@
 // Context, error reporting, the host-side decision of the adaptive velocity decay cache
 // (Eq.7, Eq.8) and the composition of one transformer block out of the library's kernels.
 #include <cstdlib>
+#include <functional>
+#include <algorithm>
+#include <vector>
 #include "common.h"
 #include <string.h>
 #include <new>
@@ -104,6 +107,52 @@ extern "C" int regione_profile_read(regione_ctx* ctx, double* total_ms_host, int
         if (k >= 0 && k < n_classes) { total_ms_host[k] += ms; launches_host[k] += 1; }
     }
     ctx->prof_used = 0;
+    return REGIONE_OK;
+}
+
+extern "C" int regione_layernorm(regione_ctx* ctx, const void* h, int32_t h_dtype, int32_t n, int32_t hidden,
+                                 const float* shift_opt, const float* scale_opt, void* u) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "layernorm: null context");
+    if (n < 0 || hidden <= 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "layernorm: n=%d hidden=%d", n, hidden);
+    if (h_dtype != REGIONE_BF16 && h_dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "layernorm: bad dtype %d", h_dtype);
+    if (n == 0) return REGIONE_OK;
+    if (!h || !u) RG_FAIL(REGIONE_ERR_INVALID_ARG, "layernorm: null tensor");
+    return rg_layernorm_mod(ctx, h, h_dtype == REGIONE_FP32, n, hidden, shift_opt, scale_opt, static_cast<bf16_t*>(u));
+}
+
+extern "C" int regione_stage_plan_host(int32_t T, int32_t t_st, int32_t t_sm, const int32_t* forced_k, int32_t n_forced,
+                                       regione_plan_step* steps_out, int32_t max_steps, int32_t* n_steps_out) {
+    if (!steps_out || !n_steps_out || (n_forced > 0 && !forced_k)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "stage_plan: null argument");
+    if (T < 1 || t_st < 1 || t_sm < 1 || n_forced < 0 || t_st + t_sm > T)
+        RG_FAIL(REGIONE_ERR_INVALID_ARG, "stage_plan: T=%d t_st=%d t_sm=%d do not fit", T, t_st, t_sm);
+    // boundaries of the segments, as timestep indices in descending order: the index after the stabilization stage,
+    // one below every forced step, and t_sm - 1
+    std::vector<int32_t> forced_i(forced_k, forced_k + n_forced);
+    for (auto& k : forced_i) k = T - k;
+    std::sort(forced_i.begin(), forced_i.end(), std::greater<int32_t>());
+    std::vector<int32_t> bounds;
+    bounds.push_back(T - t_st);
+    for (int32_t i : forced_i) {
+        // a forced step has to lie strictly inside the region-aware stage and below the step before it
+        if (i - 1 >= bounds.back() - 0 || i - 1 <= t_sm - 1)
+            RG_FAIL(REGIONE_ERR_INVALID_ARG, "stage_plan: forced step k=%d outside the region-aware stage or not descending", T - i);
+        bounds.push_back(i - 1);
+    }
+    bounds.push_back(t_sm - 1);
+    int32_t n = 0;
+    auto put = [&](int32_t i, int32_t kind, int32_t first, int32_t next) {
+        if (n < max_steps) steps_out[n] = regione_plan_step{i, kind, first, next};
+        ++n;
+    };
+    for (int32_t i = T; i > T - t_st; --i) put(i, i == T - t_st + 1 ? REGIONE_STEP_FULL_STORE : REGIONE_STEP_FULL, 0, -1);
+    for (size_t s = 0; s + 1 < bounds.size(); ++s) {
+        const int32_t prev = bounds[s], next = bounds[s + 1];
+        for (int32_t j = prev; j > next + 1; --j) put(j, REGIONE_STEP_REGION, j == prev, next);
+        put(next + 1, REGIONE_STEP_FULL_STORE, 0, -1);
+    }
+    for (int32_t i = t_sm - 1; i >= 1; --i) put(i, REGIONE_STEP_FULL, 0, -1);
+    *n_steps_out = n;
+    if (n > max_steps) RG_FAIL(REGIONE_ERR_INVALID_ARG, "stage_plan: %d steps do not fit max_steps=%d", n, max_steps);
     return REGIONE_OK;
 }
 

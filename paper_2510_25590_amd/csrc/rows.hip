@@ -184,6 +184,13 @@ layernorm_mod_kernel(const T* __restrict__ h, int n, int hidden, const float* __
     }
 }
 
+// element-wise conversion between the two storage types (round to nearest even towards bf16)
+template <typename S, typename D>
+__global__ void __launch_bounds__(kThreads) cast_kernel(const S* __restrict__ src, D* __restrict__ dst, int64_t n) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride) st<D>(dst + i, ld<S>(src + i));
+}
+
 }  // namespace
 
 extern "C" int regione_gather(regione_ctx* ctx, const void* src, int32_t row_elems, int32_t dtype,
@@ -218,6 +225,29 @@ extern "C" int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float fac
         hipLaunchKernelGGL(velocity_cache_kernel<float>, grid, dim3(kThreads), 0, ctx->stream, reuse, factor, dt,
                            static_cast<const float*>(v_fresh_opt), static_cast<float*>(c_a), static_cast<float*>(v_out_opt),
                            static_cast<float*>(x_e), n_dev, n_max, c);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+extern "C" int regione_cast(regione_ctx* ctx, const void* src, int32_t src_dtype, void* dst, int32_t dst_dtype, int64_t n_elems) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "cast: null context");
+    if ((src_dtype != REGIONE_BF16 && src_dtype != REGIONE_FP32) || (dst_dtype != REGIONE_BF16 && dst_dtype != REGIONE_FP32))
+        RG_FAIL(REGIONE_ERR_INVALID_ARG, "cast: bad dtype %d -> %d", src_dtype, dst_dtype);
+    if (n_elems < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "cast: n_elems=%lld", (long long)n_elems);
+    if (n_elems == 0) return REGIONE_OK;
+    if (!src || !dst) RG_FAIL(REGIONE_ERR_INVALID_ARG, "cast: null tensor");
+    int64_t blocks = (n_elems + kThreads - 1) / kThreads;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    const dim3 grid(static_cast<unsigned>(blocks));
+    ProfScope prof(ctx, REGIONE_PROF_ROWS);
+    if (src_dtype == REGIONE_FP32 && dst_dtype == REGIONE_BF16)
+        hipLaunchKernelGGL((cast_kernel<float, bf16_t>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(src), static_cast<bf16_t*>(dst), n_elems);
+    else if (src_dtype == REGIONE_BF16 && dst_dtype == REGIONE_FP32)
+        hipLaunchKernelGGL((cast_kernel<bf16_t, float>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(src), static_cast<float*>(dst), n_elems);
+    else if (src_dtype == REGIONE_FP32)
+        hipLaunchKernelGGL((cast_kernel<float, float>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(src), static_cast<float*>(dst), n_elems);
+    else
+        hipLaunchKernelGGL((cast_kernel<bf16_t, bf16_t>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(src), static_cast<bf16_t*>(dst), n_elems);
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
 }

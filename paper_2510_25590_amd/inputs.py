@@ -161,3 +161,35 @@ def hidden_states(rng: np.random.Generator, n: int, hidden: int, dtype: str = "b
 
 def workload_seed(config: int, trial: int = 0) -> int:
     return 1000 * config + trial
+
+
+# ----------------------------------------------------------------------------- a whole synthetic editor (sampling loop)
+
+
+def model_weights(rng: np.random.Generator, hidden: int, mlp: int, channels: int, n_double: int, n_single: int, n_txt: int,
+                  std: float = 0.02):
+    """Random weights of a small MMDiT-shaped editor for the sampling loop (Algorithm 1): token embedding
+    Linear(channels -> hidden) whose bias carries the timestep (b + t * b_time), n_double double-stream and
+    n_single single-stream blocks, LayerNorm + Linear(hidden -> channels) velocity head, and the text tokens'
+    hidden states (the encoded instruction, fixed over the loop).  bf16-representable float32 arrays."""
+    embed = {"w": bf16_round((std * 4.0 * rng.standard_normal((hidden, channels))).astype(np.float32)),
+             "b": (0.1 * rng.standard_normal(hidden)).astype(np.float32),
+             "b_time": (0.5 * rng.standard_normal(hidden)).astype(np.float32)}
+    blocks = [("double", [stream_weights(rng, hidden, mlp, "double", "bf16", std) for _ in range(2)]) for _ in range(n_double)]
+    blocks += [("single", [stream_weights(rng, hidden, mlp, "single", "bf16", std)]) for _ in range(n_single)]
+    head = {"w": bf16_round((std * rng.standard_normal((channels, hidden))).astype(np.float32)),
+            "b": (std * rng.standard_normal(channels)).astype(np.float32)}
+    h_txt = hidden_states(rng, n_txt, hidden)
+    return {"embed": embed, "blocks": blocks, "head": head, "h_txt": h_txt}
+
+
+def loop_latents(rng: np.random.Generator, want_edited: np.ndarray, channels: int, noise: float = 0.1):
+    """Start of a sampling loop whose partition is decided by construction: reference latents ~ N(0,1); the
+    starting latents equal the reference plus a little noise on the rows that should stay unedited and are
+    independent N(0,1) rows where the edit is.  float32."""
+    n = want_edited.shape[0]
+    x_ref = rng.standard_normal((n, channels)).astype(np.float32)
+    x_T = (x_ref + noise * rng.standard_normal((n, channels))).astype(np.float32)
+    fresh = rng.standard_normal((n, channels)).astype(np.float32)
+    x_T[want_edited] = fresh[want_edited]
+    return x_T, x_ref

@@ -1,0 +1,149 @@
+"""The sampling loop of the method (Algorithm 1) as a sequence of C-ABI calls (marshalling only).
+
+`EditorModel` keeps a small MMDiT-shaped editor on the device (embedding, double- and single-stream
+blocks with one KV cache per block, velocity head) and runs its two forwards through the library:
+the full forward over [text | image | reference] rows, which can store every block's K,V
+(Algorithm 1, stabilization stage and forced steps), and the region forward over the edited rows
+only, which attends to the cached rows (Eq.6).  `run_loop` walks the plan that
+`regione_stage_plan_host` returns: full steps, the partition after the stabilization stage, the
+one-step jump of the unedited rows (Eq.5), region steps under the adaptive velocity decay cache
+(Eq.7-9) and the merges.  Latents, velocities and the velocity cache are float32; rows enter the
+embedding as bf16.  No arithmetic of the method happens here; torch is used for device memory only.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding as rg
+
+
+class EditorModel:
+    def __init__(self, weights: dict, hidden: int, heads: int, head_dim: int, mlp: int, channels: int, n_img: int):
+        import torch
+        self.torch = torch
+        self.hidden, self.heads, self.head_dim, self.mlp, self.channels = hidden, heads, head_dim, mlp, channels
+        self.n_img = n_img
+        self.n_txt = weights["h_txt"].shape[0]
+        self.n_all = self.n_txt + 2 * n_img
+        bf = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).cuda()
+        f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+        self.ctx = rg.Context(hidden, heads, head_dim, mlp, self.n_all, max(self.n_all, n_img))
+        ctx = self.ctx
+        self.w_embed = rg.pack_weight(ctx, bf(weights["embed"]["w"]))
+        self.b_embed_host = np.asarray(weights["embed"]["b"], dtype=np.float32)
+        self.b_time_host = np.asarray(weights["embed"]["b_time"], dtype=np.float32)
+        self.w_head, self.b_head = rg.pack_weight(ctx, bf(weights["head"]["w"])), f32(weights["head"]["b"])
+        self.h_txt = bf(weights["h_txt"])
+        self.blocks, self._keep = [], []
+        for kind, streams in weights["blocks"]:
+            bw = rg.BlockWeights()
+            for name, w in zip(("txt", "img") if kind == "double" else ("img",), streams):
+                t = {k: (rg.pack_weight(ctx, bf(a)) if k.startswith("w_") else f32(a)) for k, a in w.items()}
+                self._keep.append(t)
+                setattr(bw, name, rg.make_stream_weights(t))
+            kc = torch.zeros((self.n_all, heads, head_dim), dtype=torch.bfloat16, device="cuda")
+            self.blocks.append((rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE, bw, kc, torch.zeros_like(kc)))
+        dev = "cuda"
+        self.h_a = torch.empty((self.n_all, hidden), dtype=torch.bfloat16, device=dev)
+        self.h_b = torch.empty_like(self.h_a)
+        self.rows_bf = torch.empty((2 * n_img, channels), dtype=torch.bfloat16, device=dev)
+        self.u = torch.empty((n_img, hidden), dtype=torch.bfloat16, device=dev)
+        self.all_slots = torch.arange(self.n_all, dtype=torch.int32, device=dev)
+        self.h_a[:self.n_txt].copy_(self.h_txt)     # text rows of the block input never change
+
+    def _embed_bias(self, t: float):
+        """Bias of the token embedding at time t (input marshalling: a float32 vector b + t * b_time)."""
+        b = (self.b_embed_host + np.float32(t) * self.b_time_host).astype(np.float32)
+        return self.torch.from_numpy(b).cuda()
+
+    def _head(self, h_rows, n, v_out):
+        rg.regione_layernorm(self.ctx, h_rows, rg.BF16, n, self.hidden, None, None, self.u)
+        rg.regione_linear(self.ctx, self.u, self.w_head, self.b_head, n, self.channels, self.hidden, rg.ACT_NONE, rg.FP32, v_out)
+
+    def full_forward(self, x, x_ref, t: float, store: bool, v_out):
+        """Velocity of all image rows from the full sequence; with `store`, every block writes its K,V cache."""
+        ctx, n_img, n_txt = self.ctx, self.n_img, self.n_txt
+        rg.regione_cast(ctx, x, rg.FP32, self.rows_bf[:n_img], rg.BF16, n_img * self.channels)
+        rg.regione_cast(ctx, x_ref, rg.FP32, self.rows_bf[n_img:], rg.BF16, n_img * self.channels)
+        bias = self._embed_bias(t)
+        rg.regione_linear(ctx, self.rows_bf, self.w_embed, bias, 2 * n_img, self.hidden, self.channels, rg.ACT_NONE, rg.BF16,
+                          self.h_a[n_txt:])
+        self.h_a[:n_txt].copy_(self.h_txt)
+        src, dst = self.h_a, self.h_b
+        for block_type, bw, kc, vc in self.blocks:
+            rg.regione_block_forward(ctx, bw, block_type, src, dst, rg.BF16, self.n_all, n_txt, self.all_slots, 0, kc, vc,
+                                     self.n_all, rg.FLAG_STORE if store else 0)
+            src, dst = dst, src
+        self._head(src[n_txt:n_txt + n_img], n_img, v_out)
+
+    def region_forward(self, x_e, e_index, n_e: int, t: float, v_out):
+        """Velocity of the edited rows alone; keys and values of all other rows come from the caches (Eq.6)."""
+        ctx = self.ctx
+        if n_e == 0:
+            return
+        rg.regione_cast(ctx, x_e, rg.FP32, self.rows_bf, rg.BF16, n_e * self.channels)
+        bias = self._embed_bias(t)
+        rg.regione_linear(ctx, self.rows_bf, self.w_embed, bias, n_e, self.hidden, self.channels, rg.ACT_NONE, rg.BF16, self.h_a)
+        src, dst = self.h_a, self.h_b
+        for block_type, bw, kc, vc in self.blocks:
+            rg.regione_block_forward(ctx, bw, block_type, src, dst, rg.BF16, n_e, 0, e_index, self.n_txt, kc, vc, self.n_all,
+                                     rg.FLAG_RETRIEVE)
+            src, dst = dst, src
+        self._head(src, n_e, v_out)
+
+    def close(self):
+        self.ctx.close()
+
+
+def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: int, forced_k, eta: float, delta: float):
+    """Algorithm 1.  x_T, x_ref: float32 CUDA tensors [n_img, channels]; t, gamma: host sequences of T+1 floats
+    (t[T] = 1, t[0] = 0).  Returns (x_0 tensor, log) with log entries (i, what) for every step and one
+    ("partition", n_edited); what is "full", "full_store", "region_fresh" or "region_reuse"."""
+    torch = model.torch
+    ctx, n_img, c = model.ctx, model.n_img, model.channels
+    dev = "cuda"
+    x = x_T.clone()
+    v = torch.zeros_like(x)                  # velocity of the last full step
+    scratch = torch.empty_like(x)
+    n_img_dev = torch.full((1,), n_img, dtype=torch.int32, device=dev)
+    mask = torch.empty(n_img, dtype=torch.uint8, device=dev)
+    e_index = torch.empty(n_img, dtype=torch.int32, device=dev)
+    u_index = torch.empty(n_img, dtype=torch.int32, device=dev)
+    n_e_dev = torch.zeros(1, dtype=torch.int32, device=dev)
+    n_u_dev = torch.zeros(1, dtype=torch.int32, device=dev)
+    x_e, v_e, c_a = torch.empty_like(x), torch.empty_like(x), torch.zeros_like(x)
+    x_u, v_u = torch.empty_like(x), torch.empty_like(x)
+    n_e = None
+    log = []
+    state = rg.AvdState()
+    steps = rg.regione_stage_plan_host(T, t_st, t_sm, forced_k)
+    for pos, st in enumerate(steps):
+        i = st.i
+        if st.kind != rg.STEP_REGION:
+            model.full_forward(x, x_ref, t[i], st.kind == rg.STEP_FULL_STORE, v)
+            # Eq.4 on all rows: x <- x - (t_i - t_{i-1}) v   (the fresh-velocity form of the cache update, cache unused)
+            rg.regione_velocity_cache(ctx, False, 1.0, float(t[i] - t[i - 1]), v, scratch, None, x, n_img_dev, n_img, c, rg.FP32)
+            log.append((i, "full_store" if st.kind == rg.STEP_FULL_STORE else "full"))
+            continue
+        if st.seg_first:
+            if n_e is None:   # adaptive region partition, once, from the last full velocity (Eq.5 + cosine + threshold)
+                n_e = rg.regione_partition(ctx, x, v, x_ref, n_img, c, rg.FP32, float(t[i]), eta, None, mask, e_index, u_index, n_e_dev)
+                n_u_dev.fill_(n_img - n_e)
+                log.append(("partition", n_e))
+            rg.regione_gather(ctx, x, c, rg.FP32, e_index, n_e_dev, n_e, x_e)
+            rg.regione_gather(ctx, x, c, rg.FP32, u_index, n_u_dev, n_img - n_e, x_u)
+            rg.regione_gather(ctx, v, c, rg.FP32, u_index, n_u_dev, n_img - n_e, v_u)
+            # one jump of the unedited rows to the end of the segment with the last full velocity (Eq.5)
+            rg.regione_velocity_cache(ctx, True, 1.0, float(t[i] - t[st.seg_next + 1]), None, v_u, None, x_u, n_u_dev, n_img - n_e, c, rg.FP32)
+            state = rg.AvdState()
+        reuse, factor = rg.regione_velocity_decision_host(t, gamma, T, delta, i, state)
+        if not reuse:
+            model.region_forward(x_e, e_index, n_e, t[i], v_e)
+        rg.regione_velocity_cache(ctx, reuse, factor, float(t[i] - t[i - 1]), None if reuse else v_e, c_a, None, x_e, n_e_dev, n_e, c, rg.FP32)
+        log.append((i, "region_reuse" if reuse else "region_fresh"))
+        last_of_segment = pos + 1 == len(steps) or steps[pos + 1].kind != rg.STEP_REGION
+        if last_of_segment:   # merge: edited and unedited rows are both at t_{next+1} now
+            rg.regione_scatter(ctx, x, c, rg.FP32, e_index, n_e_dev, n_e, x_e)
+            rg.regione_scatter(ctx, x, c, rg.FP32, u_index, n_u_dev, n_img - n_e, x_u)
+    torch.cuda.synchronize()
+    return x, log

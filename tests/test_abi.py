@@ -56,3 +56,25 @@ def test_host_decision_matches_oracle(delta):
             got = rg.regione_velocity_decision_host(t32, g32, T, delta, j, st_c)
             assert got[0] == want[0]
             assert got[1] == pytest.approx(want[1], rel=1e-6)
+
+
+@pytest.mark.parametrize("T, t_st, t_sm, forced", [(28, 6, 2, [16]), (28, 6, 2, []), (28, 6, 2, [20, 10, 16]), (10, 2, 1, [5]),
+                                                   (12, 3, 3, []), (50, 10, 4, [20, 30]), (4, 1, 1, [])])
+def test_host_stage_plan_matches_oracle(T, t_st, t_sm, forced):
+    plan, segments = orc.stage_plan(T, t_st, t_sm, forced)
+    kinds = {"full": rg.STEP_FULL, "full_store": rg.STEP_FULL_STORE, "region": rg.STEP_REGION}
+    got = rg.regione_stage_plan_host(T, t_st, t_sm, forced)
+    assert [(s.i, s.kind) for s in got] == [(i, kinds[k]) for i, k in plan]
+    # every segment's first region step is marked and carries the segment's end
+    firsts = [(s.i, s.seg_next) for s in got if s.seg_first]
+    assert firsts == [(prev, nxt) for prev, nxt in segments if prev > nxt + 1]
+    assert all(s.seg_next == -1 for s in got if s.kind != rg.STEP_REGION)
+    # the paper's counts for its own hyper-parameters (Experiments, implementation details)
+    if (T, t_st, t_sm, forced) == (28, 6, 2, [16]):
+        assert sum(s.kind == rg.STEP_REGION for s in got) == 19 and sum(s.kind != rg.STEP_REGION for s in got) == 9
+
+
+def test_host_stage_plan_rejects_stages_that_do_not_fit():
+    for args in ((28, 20, 10, []), (28, 6, 2, [3]), (28, 6, 2, [27]), (28, 6, 2, [16, 16]), (0, 1, 1, [])):
+        with pytest.raises(rg.RegionEError):
+            rg.regione_stage_plan_host(*args)

@@ -1,0 +1,66 @@
+"""Algorithm 1 end to end on the device against the oracle's loop, on a reduced editor: 256 wide, 4 heads of 64,
+2 double-stream + 3 single-stream blocks, 16x16 image + 256 reference + 32 text tokens, 28 steps with the paper's
+stage lengths (6 stabilization steps, forced step at k = 16, 2 smooth steps)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_25590_amd import binding as rg, inputs, loop
+from oracle import regione_oracle as orc
+from oracle.editor_reference import EditorReference
+from gpu_util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+HIDDEN, HEADS, D, MLP, C, GRID, N_TXT = 256, 4, 64, 1024, 64, 16, 32
+T, T_ST, T_SM, FORCED = 28, 6, 2, [16]
+ETA = 0.8
+
+
+def _setup(seed, n_double=2, n_single=3, rect=(6, 6)):
+    rng = np.random.default_rng(seed)
+    want = inputs.rect_mask(rng, GRID, GRID, *rect)
+    x_T, x_ref = inputs.loop_latents(rng, want, C)
+    weights = inputs.model_weights(rng, HIDDEN, MLP, C, n_double, n_single, N_TXT)
+    t = np.linspace(0.0, 1.0, T + 1)
+    return want, x_T, x_ref, weights, t
+
+
+@pytest.mark.parametrize("delta, gamma_kind", [(0.04, "one"), (-1.0, "one"), (0.08, "table")])
+def test_loop_matches_oracle_loop(delta, gamma_kind):
+    want, x_T, x_ref, weights, t = _setup(inputs.workload_seed(4, 0))
+    gamma = np.ones(T + 1) if gamma_kind == "one" else 1.0 - 0.01 * np.sin(np.arange(T + 1))
+    ref_model = EditorReference(weights, HEADS, GRID * GRID, x_ref, t)
+    x0_want, log_want = orc.regione_loop(ref_model.phi, x_T, x_ref, t, gamma, T, T_ST, T_SM, FORCED, ETA, delta)
+    n_e_want = [w for w in log_want if w[0] == "partition"][0][1]
+    assert n_e_want == int(want.sum())    # the constructed edit is what the oracle's partition finds
+
+    model = loop.EditorModel(weights, HIDDEN, HEADS, D, MLP, C, GRID * GRID)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    x0, log = loop.run_loop(model, dev(x_T), dev(x_ref), [float(v) for v in t], [float(g) for g in gamma], T, T_ST, T_SM, FORCED, ETA, delta)
+    assert log == log_want                # same stages, same cache decisions, same number of edited tokens
+    got = x0.cpu().numpy().astype(np.float64)
+    # what the loop did to the latents, not the latents themselves (which start at the same x_T)
+    moved_want, moved_got = x0_want - x_T, got - x_T
+    ma, mr = assert_close(moved_got, moved_want, f"displacement of the latents over the loop (delta {delta})")
+    print(f"delta {delta}: {sum(1 for w in log if w[1] == 'region_reuse')} reused steps, max abs {ma:.3e}, mean rel {mr:.3e}, "
+          f"mean |displacement| {np.abs(moved_want).mean():.3f}")
+    model.close()
+
+
+def test_loop_all_edited_and_none_edited():
+    """Degenerate partitions: every token edited (region forward = image rows of a full forward with text and
+    reference from the cache) and no token edited (region steps become no-ops, the unedited rows jump)."""
+    for rect, eta in (((GRID, GRID), ETA), ((6, 6), -2.0)):
+        want, x_T, x_ref, weights, t = _setup(inputs.workload_seed(4, 1), n_double=1, n_single=1, rect=rect)
+        gamma = np.ones(T + 1)
+        ref_model = EditorReference(weights, HEADS, GRID * GRID, x_ref, t)
+        x0_want, log_want = orc.regione_loop(ref_model.phi, x_T, x_ref, t, gamma, T, T_ST, T_SM, FORCED, eta, 0.04)
+        n_e = [w for w in log_want if w[0] == "partition"][0][1]
+        assert n_e == (GRID * GRID if eta > 0 else 0)
+        model = loop.EditorModel(weights, HIDDEN, HEADS, D, MLP, C, GRID * GRID)
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+        x0, log = loop.run_loop(model, dev(x_T), dev(x_ref), [float(v) for v in t], [float(g) for g in gamma], T, T_ST, T_SM, FORCED, eta, 0.04)
+        assert log == log_want
+        assert_close(x0.cpu().numpy().astype(np.float64) - x_T, x0_want - x_T, f"displacement with {n_e} edited tokens")
+        model.close()
