@@ -14,8 +14,8 @@ cache as a decayed velocity cache).
 
 Parity pins (tests/test_oracle_*.py): closed forms (Eq.2+Eq.5 recover X_0, appendix Eq.13
 with gamma = 1), hand cases, brute force on tiny inputs, torch CPU library routines
-(cosine_similarity, scaled_dot_product_attention, layer_norm, gelu) and the structural
-identities of Eq.6.  Unpinned: none of the functions below; what stays unpinned is the
+(cosine_similarity, scaled_dot_product_attention, layer_norm, gelu; scipy.ndimage's binary
+erosion and dilation for the mask clean-up) and the structural identities of Eq.6.  Unpinned: none of the functions below; what stays unpinned is the
 fidelity of the method on real model weights (PSNR/SSIM figures), which needs the models.
 
 The transformer block is NOT described by the paper (it treats the DiT as a black box
@@ -82,6 +82,56 @@ def partition(x_t, v, x_ref, sigma_t: float, eta: float):
     mask = threshold_mask(score, eta)
     e_index, u_index = compact(mask)
     return score, mask, e_index, u_index
+
+
+# --------------------------------------------------------------------------- morphological clean-up of the partition
+
+
+def erode3x3(m: np.ndarray) -> np.ndarray:
+    """Binary erosion of a 2-D boolean array with the 3x3 square: a cell stays set iff every
+    neighbour INSIDE the grid (itself included) is set.  Cells outside the grid never decide."""
+    h, w = m.shape
+    out = np.zeros((h, w), dtype=bool)
+    for r in range(h):
+        for c in range(w):
+            ok = True
+            for dr in (-1, 0, 1):
+                for dc in (-1, 0, 1):
+                    rr, cc = r + dr, c + dc
+                    if 0 <= rr < h and 0 <= cc < w and not m[rr, cc]:
+                        ok = False
+            out[r, c] = ok
+    return out
+
+
+def dilate3x3(m: np.ndarray) -> np.ndarray:
+    """Binary dilation with the 3x3 square: a cell is set iff some neighbour inside the grid is set."""
+    h, w = m.shape
+    out = np.zeros((h, w), dtype=bool)
+    for r in range(h):
+        for c in range(w):
+            hit = False
+            for dr in (-1, 0, 1):
+                for dc in (-1, 0, 1):
+                    rr, cc = r + dr, c + dc
+                    if 0 <= rr < h and 0 <= cc < w and m[rr, cc]:
+                        hit = True
+            out[r, c] = hit
+    return out
+
+
+def mask_cleanup(edited_mask: np.ndarray, grid_h: int, grid_w: int) -> np.ndarray:
+    """Morphological opening, then closing, of the region partition (section "Adaptive Region
+    Partition"; Algorithm 1 applies erosion and dilation to the map cos > eta, i.e. to the
+    UNEDITED region).  Opening = erosion then dilation: unedited specks smaller than the 3x3
+    element become edited.  Closing = dilation then erosion: edited holes smaller than the
+    element become unedited.  Readings (the paper names neither element nor border): 3x3 square,
+    cells outside the token grid never decide.  edited_mask: flat uint8/bool [grid_h*grid_w],
+    1 = edited; returns the cleaned flat uint8 mask."""
+    unedited = ~np.asarray(edited_mask, dtype=bool).reshape(grid_h, grid_w)
+    opened = dilate3x3(erode3x3(unedited))
+    closed = erode3x3(dilate3x3(opened))
+    return (~closed).reshape(-1).astype(np.uint8)
 
 
 # --------------------------------------------------------------------------- gather / scatter
