@@ -112,6 +112,19 @@ int regione_partition(regione_ctx* ctx, const void* x_t, const void* v, const vo
                       float* score_opt, uint8_t* mask, int32_t* e_index, int32_t* u_index,
                       int32_t* n_edited_dev, int32_t* n_edited_host_opt);
 
+/* Morphological clean-up of the partition on the token grid (section "Adaptive Region
+ * Partition": opening and closing make the two regions more continuous; Algorithm 1 applies
+ * erosion and dilation to the map cos > eta, i.e. to the unedited region).  Opening (erosion
+ * then dilation) then closing (dilation then erosion) of the UNEDITED map with the 3x3 square;
+ * cells outside the grid never decide (the paper names neither element nor border: both are
+ * this library's reading).  mask_in [n_images * grid_h * grid_w] uint8, 1 = edited, as written
+ * by regione_partition; mask_out the cleaned mask (may alias mask_in); e_index / u_index /
+ * n_edited_dev / n_edited_host_opt as in regione_partition, rebuilt from the cleaned mask.
+ * grid_h * grid_w <= 16384, else REGIONE_ERR_UNSUPPORTED. */
+int regione_mask_cleanup(regione_ctx* ctx, const uint8_t* mask_in, int32_t grid_h, int32_t grid_w, int32_t n_images,
+                         uint8_t* mask_out, int32_t* e_index, int32_t* u_index,
+                         int32_t* n_edited_dev, int32_t* n_edited_host_opt);
+
 /* Row gather X[index] (Algorithm 1, "X^E = X[E_index]"): dst[i,:] = src[index[i],:] for
  * i < n, with n = *n_dev when n_dev is non-null (clamped to n_max) and n_max otherwise.
  * Rows have row_elems elements of `dtype`; the copy is bit-exact. src and dst must not overlap. */

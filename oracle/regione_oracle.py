@@ -362,11 +362,12 @@ def stage_plan(T: int, t_st: int, t_sm: int, forced_k):
     return plan, segments
 
 
-def regione_loop(phi, x_T, x_ref, t, gamma, T, t_st, t_sm, forced_k, eta, delta):
+def regione_loop(phi, x_T, x_ref, t, gamma, T, t_st, t_sm, forced_k, eta, delta, grid=None):
     """Algorithm 1 on latents [N, C].  `phi(x_rows, row_index, i, mode)` returns the velocity
     for the rows given (mode "full", "full_store" or "region"; row_index None = all rows).
     Returns (x_0, log) where log lists (i, what) with what in {"full", "full_store",
-    "region_fresh", "region_reuse"} and, once, ("partition", n_E)."""
+    "region_fresh", "region_reuse"} and, once, ("partition", n_E).  grid = (rows, columns) of
+    the token grid applies the morphological clean-up to the partition; None leaves it as thresholded."""
     plan, segments = stage_plan(T, t_st, t_sm, forced_k)
     x = np.asarray(x_T, dtype=F64).copy()
     log = []
@@ -390,7 +391,9 @@ def regione_loop(phi, x_T, x_ref, t, gamma, T, t_st, t_sm, forced_k, eta, delta)
         prev = i
         nxt = seg_start[prev]
         if e_index is None:
-            _, _, e_index, u_index = partition(x.astype(np.float32), v_last_full.astype(np.float32), x_ref, t[prev], eta)
+            _, mask, e_index, u_index = partition(x.astype(np.float32), v_last_full.astype(np.float32), x_ref, t[prev], eta)
+            if grid is not None:
+                e_index, u_index = compact(mask_cleanup(mask, grid[0], grid[1]))
             log.append(("partition", int(len(e_index))))
         x_e = gather(x, e_index)
         x_u = gather(x, u_index)

@@ -25,7 +25,7 @@ EXPORTS = (
     "regione_scatter", "regione_attn_kvcache", "regione_linear", "regione_block_forward",
     "regione_velocity_decision_host", "regione_velocity_cache", "regione_profile_enable", "regione_profile_read",
     "regione_packed_weight_elems", "regione_pack_weight", "regione_tune_gemm", "regione_tune_attention",
-    "regione_layernorm", "regione_stage_plan_host", "regione_cast",
+    "regione_layernorm", "regione_stage_plan_host", "regione_cast", "regione_mask_cleanup",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
             "regione_tune_attention": [vp, i32],
             "regione_layernorm": [vp, vp, i32, i32, i32, vp, vp, vp],
             "regione_cast": [vp, vp, i32, vp, i32, i64],
+            "regione_mask_cleanup": [vp, vp, i32, i32, i32, vp, vp, vp, vp, C.POINTER(i32)],
             "regione_stage_plan_host": [i32, i32, i32, C.POINTER(i32), i32, C.POINTER(PlanStep), i32, C.POINTER(i32)],
             "regione_profile_enable": [vp, i32],
             "regione_profile_read": [vp, C.POINTER(C.c_double), C.POINTER(i64), i32],
@@ -156,6 +157,13 @@ def regione_partition(ctx, x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta, scor
     _check(lib().regione_partition(ctx.handle, _p(x_t), _p(v), _p(x_ref), n_tokens, c, dtype, sigma_t, eta,
                                    _p(score), _p(mask), _p(e_index), _p(u_index), _p(n_edited_dev),
                                    C.byref(host) if read_count else None))
+    return host.value if read_count else None
+
+
+def regione_mask_cleanup(ctx, mask_in, grid_h, grid_w, n_images, mask_out, e_index, u_index, n_edited_dev, read_count: bool = True):
+    host = C.c_int32(-1)
+    _check(lib().regione_mask_cleanup(ctx.handle, _p(mask_in), grid_h, grid_w, n_images, _p(mask_out), _p(e_index), _p(u_index),
+                                      _p(n_edited_dev), C.byref(host) if read_count else None))
     return host.value if read_count else None
 
 

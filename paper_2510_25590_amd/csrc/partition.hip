@@ -201,6 +201,68 @@ int launch_score(regione_ctx* ctx, int lpt, dim3 grid, const void* x_t, const vo
     return REGIONE_OK;
 }
 
+// ---- morphological clean-up of the partition on the token grid
+// One workgroup per image.  The unedited map lives in LDS as bytes; four passes with the 3x3 square (erosion,
+// dilation = opening; dilation, erosion = closing), cells outside the grid never decide.  Writes the cleaned
+// edited mask.
+constexpr int kMorphThreads = 1024;
+constexpr int kMorphMaxCells = 128 * 128;
+template <bool ERODE>
+__device__ __forceinline__ void morph_pass(const uint8_t* __restrict__ in, uint8_t* __restrict__ out, int gh, int gw) {
+    for (int p = threadIdx.x; p < gh * gw; p += kMorphThreads) {
+        const int r = p / gw, c = p - r * gw;
+        bool acc = ERODE;
+        for (int dr = -1; dr <= 1; ++dr) {
+            const int rr = r + dr;
+            if (rr < 0 || rr >= gh) continue;
+            for (int dc = -1; dc <= 1; ++dc) {
+                const int cc = c + dc;
+                if (cc < 0 || cc >= gw) continue;
+                const bool v = in[rr * gw + cc] != 0;
+                acc = ERODE ? (acc && v) : (acc || v);
+            }
+        }
+        out[p] = acc ? 1 : 0;
+    }
+    __syncthreads();
+}
+__global__ void __launch_bounds__(kMorphThreads)
+morph_open_close_kernel(const uint8_t* mask_in, uint8_t* mask_out, int gh, int gw) {   // the two may be the same buffer
+    __shared__ uint8_t a[kMorphMaxCells], b[kMorphMaxCells];
+    const int cells = gh * gw;
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * cells;
+    for (int p = threadIdx.x; p < cells; p += kMorphThreads) a[p] = mask_in[base + p] ? 0 : 1;   // unedited map
+    __syncthreads();
+    morph_pass<true>(a, b, gh, gw);    // opening: erosion ...
+    morph_pass<false>(b, a, gh, gw);   // ... then dilation
+    morph_pass<false>(a, b, gh, gw);   // closing: dilation ...
+    morph_pass<true>(b, a, gh, gw);    // ... then erosion
+    for (int p = threadIdx.x; p < cells; p += kMorphThreads) mask_out[base + p] = a[p] ? 0 : 1;
+}
+
+// edited tokens per block of tok_per_block tokens (the layout scan_counts_kernel and write_index_kernel expect)
+__global__ void __launch_bounds__(kThreads)
+count_mask_kernel(const uint8_t* __restrict__ mask, int64_t n_tokens, int tok_per_block, int32_t* __restrict__ counts) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t block_first = static_cast<int64_t>(blockIdx.x) * tok_per_block;
+    int cnt = 0;
+    for (int off = threadIdx.x; off < tok_per_block; off += kThreads) {
+        const int64_t tok = block_first + off;
+        cnt += (tok < n_tokens && mask[tok] != 0) ? 1 : 0;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d, 64);
+    __shared__ int wave_counts[kWaves];
+    if (lane == 0) wave_counts[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int s = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) s += wave_counts[w];
+        counts[blockIdx.x] = s;
+    }
+}
+
 }  // namespace
 
 extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* v, const void* x_ref,
@@ -248,6 +310,43 @@ extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* 
         RG_LAUNCH_CHECK();
         hipLaunchKernelGGL(write_index_kernel, grid, dim3(kThreads), 0, ctx->stream,
                            mask, ctx->part_counts, n_tokens, tpb, e_index, u_index);
+        RG_LAUNCH_CHECK();
+    }
+    }
+    if (n_edited_host_opt) {
+        RG_HIP(hipMemcpyAsync(n_edited_host_opt, n_edited_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+        RG_HIP(hipStreamSynchronize(ctx->stream));
+    }
+    return REGIONE_OK;
+}
+
+extern "C" int regione_mask_cleanup(regione_ctx* ctx, const uint8_t* mask_in, int32_t grid_h, int32_t grid_w, int32_t n_images,
+                                    uint8_t* mask_out, int32_t* e_index, int32_t* u_index,
+                                    int32_t* n_edited_dev, int32_t* n_edited_host_opt) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "mask_cleanup: null context");
+    if (grid_h <= 0 || grid_w <= 0 || n_images < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "mask_cleanup: grid %d x %d, %d images", grid_h, grid_w, n_images);
+    if (static_cast<int64_t>(grid_h) * grid_w > kMorphMaxCells) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "mask_cleanup: grid %d x %d exceeds %d cells per image", grid_h, grid_w, kMorphMaxCells);
+    if (!n_edited_dev) RG_FAIL(REGIONE_ERR_INVALID_ARG, "mask_cleanup: n_edited_dev is null");
+    const int64_t n_tokens = static_cast<int64_t>(grid_h) * grid_w * n_images;
+    if (n_tokens > ctx->dims.max_tokens) RG_FAIL(REGIONE_ERR_WORKSPACE, "mask_cleanup: %lld tokens, context made for %d", (long long)n_tokens, ctx->dims.max_tokens);
+    {
+    ProfScope prof(ctx, REGIONE_PROF_PARTITION);
+    if (n_tokens == 0) {
+        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, n_edited_dev, 0);
+        RG_LAUNCH_CHECK();
+    } else {
+        if (!mask_in || !mask_out || !e_index || !u_index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "mask_cleanup: null tensor");
+        const int tpb = kThreads;
+        const int64_t nblocks = (n_tokens + tpb - 1) / tpb;
+        if (nblocks > ctx->part_counts_cap) RG_FAIL(REGIONE_ERR_WORKSPACE, "mask_cleanup: %lld blocks exceed the workspace", (long long)nblocks);
+        hipLaunchKernelGGL(morph_open_close_kernel, dim3(static_cast<unsigned>(n_images)), dim3(kMorphThreads), 0, ctx->stream, mask_in, mask_out, grid_h, grid_w);
+        RG_LAUNCH_CHECK();
+        const dim3 grid(static_cast<unsigned>(nblocks));
+        hipLaunchKernelGGL(count_mask_kernel, grid, dim3(kThreads), 0, ctx->stream, mask_out, n_tokens, tpb, ctx->part_counts);
+        RG_LAUNCH_CHECK();
+        hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, ctx->stream, ctx->part_counts, static_cast<int>(nblocks), n_edited_dev);
+        RG_LAUNCH_CHECK();
+        hipLaunchKernelGGL(write_index_kernel, grid, dim3(kThreads), 0, ctx->stream, mask_out, ctx->part_counts, n_tokens, tpb, e_index, u_index);
         RG_LAUNCH_CHECK();
     }
     }

@@ -95,10 +95,11 @@ class EditorModel:
         self.ctx.close()
 
 
-def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: int, forced_k, eta: float, delta: float):
+def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: int, forced_k, eta: float, delta: float, grid=None):
     """Algorithm 1.  x_T, x_ref: float32 CUDA tensors [n_img, channels]; t, gamma: host sequences of T+1 floats
     (t[T] = 1, t[0] = 0).  Returns (x_0 tensor, log) with log entries (i, what) for every step and one
-    ("partition", n_edited); what is "full", "full_store", "region_fresh" or "region_reuse"."""
+    ("partition", n_edited); what is "full", "full_store", "region_fresh" or "region_reuse".  grid = (rows, columns)
+    of the token grid applies the morphological clean-up to the partition."""
     torch = model.torch
     ctx, n_img, c = model.ctx, model.n_img, model.channels
     dev = "cuda"
@@ -128,6 +129,8 @@ def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: 
         if st.seg_first:
             if n_e is None:   # adaptive region partition, once, from the last full velocity (Eq.5 + cosine + threshold)
                 n_e = rg.regione_partition(ctx, x, v, x_ref, n_img, c, rg.FP32, float(t[i]), eta, None, mask, e_index, u_index, n_e_dev)
+                if grid is not None:
+                    n_e = rg.regione_mask_cleanup(ctx, mask, grid[0], grid[1], 1, mask, e_index, u_index, n_e_dev)
                 n_u_dev.fill_(n_img - n_e)
                 log.append(("partition", n_e))
             rg.regione_gather(ctx, x, c, rg.FP32, e_index, n_e_dev, n_e, x_e)

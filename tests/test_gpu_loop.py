@@ -64,3 +64,39 @@ def test_loop_all_edited_and_none_edited():
         assert log == log_want
         assert_close(x0.cpu().numpy().astype(np.float64) - x_T, x0_want - x_T, f"displacement with {n_e} edited tokens")
         model.close()
+
+
+def test_loop_with_mask_cleanup():
+    """Segmentation noise in the thresholded partition (one stray edited token far from the edit, one stray unedited token
+    inside it) is removed by the opening and closing on the token grid; the loop then runs on the cleaned partition (the rectangle,
+    plus any unedited strip too thin for the 3x3 element between it and the border of the grid)."""
+    seed = inputs.workload_seed(4, 2)
+    rng = np.random.default_rng(seed)
+    want = inputs.rect_mask(rng, GRID, GRID, 6, 6)
+    noisy = want.copy().reshape(GRID, GRID)
+    rows, cols = np.nonzero(noisy)
+    noisy[rows.min() + 2, cols.min() + 3] = False          # a hole in the edit
+    far_r = (rows.min() + 11) % GRID
+    far_c = (cols.min() + 11) % GRID
+    assert not want.reshape(GRID, GRID)[max(far_r - 1, 0):far_r + 2, max(far_c - 1, 0):far_c + 2].any()
+    noisy[far_r, far_c] = True                             # a speck outside
+    noisy = noisy.reshape(-1)
+    x_T, x_ref = inputs.loop_latents(rng, noisy, C)
+    weights = inputs.model_weights(rng, HIDDEN, MLP, C, 1, 2, N_TXT)
+    t = np.linspace(0.0, 1.0, T + 1)
+    gamma = np.ones(T + 1)
+    ref_model = EditorReference(weights, HEADS, GRID * GRID, x_ref, t)
+    x0_raw, log_raw = orc.regione_loop(ref_model.phi, x_T, x_ref, t, gamma, T, T_ST, T_SM, FORCED, ETA, 0.04)
+    assert ("partition", int(noisy.sum())) in log_raw       # without the clean-up the noise is part of the partition
+    ref_model = EditorReference(weights, HEADS, GRID * GRID, x_ref, t)
+    x0_want, log_want = orc.regione_loop(ref_model.phi, x_T, x_ref, t, gamma, T, T_ST, T_SM, FORCED, ETA, 0.04, grid=(GRID, GRID))
+    cleaned = orc.mask_cleanup(noisy.astype(np.uint8), GRID, GRID).reshape(GRID, GRID)
+    assert cleaned[rows.min() + 2, cols.min() + 3] == 1 and cleaned[far_r, far_c] == 0    # hole filled, speck gone
+    assert ("partition", int(cleaned.sum())) in log_want
+    model = loop.EditorModel(weights, HIDDEN, HEADS, D, MLP, C, GRID * GRID)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    x0, log = loop.run_loop(model, dev(x_T), dev(x_ref), [float(v) for v in t], [float(g) for g in gamma], T, T_ST, T_SM, FORCED, ETA, 0.04,
+                            grid=(GRID, GRID))
+    assert log == log_want
+    assert_close(x0.cpu().numpy().astype(np.float64) - x_T, x0_want - x_T, "displacement of the latents, cleaned partition")
+    model.close()

@@ -193,3 +193,54 @@ def test_velocity_cache_matches_oracle(ctx, dtype):
     assert_close(host(dx)[:live], xn, "x after a reuse step", **tol)
     with pytest.raises(rg.RegionEError):
         rg.regione_velocity_cache(ctx, False, 1.0, 0.1, None, dca, None, dx, cnt, n, c, code)
+
+
+# ---------------------------------------------------------------- morphological clean-up of the partition
+
+
+@pytest.mark.parametrize("gh, gw, n_images, density", [(1, 1, 1, 0.5), (1, 9, 1, 0.5), (7, 1, 2, 0.4), (16, 16, 1, 0.15), (64, 64, 1, 0.2),
+                                                        (64, 64, 3, 0.6), (96, 96, 1, 0.9), (37, 53, 2, 0.3), (128, 128, 1, 0.5)])
+def test_mask_cleanup_matches_oracle(gh, gw, n_images, density):
+    rng = np.random.default_rng(gh * 1000 + gw * 10 + n_images)
+    cells = gh * gw
+    # blobs plus salt-and-pepper noise: what the clean-up is for
+    masks = []
+    for _ in range(n_images):
+        m = inputs.blob_mask(rng, gh, gw, int(density * cells)) if min(gh, gw) >= 4 else (rng.random(cells) < density)
+        flip = rng.random(cells) < 0.03
+        masks.append(np.logical_xor(m, flip))
+    mask = np.concatenate(masks).astype(np.uint8)
+    want = np.concatenate([orc.mask_cleanup(m.astype(np.uint8), gh, gw) for m in masks])
+    e_want, u_want = orc.compact(want)
+    n = cells * n_images
+    ctx = rg.Context(256, 4, 64, 1024, 16, n)
+    d_in = torch.from_numpy(mask).cuda()
+    d_out = torch.empty_like(d_in)
+    e = torch.full((n,), -7, dtype=torch.int32, device="cuda"); u = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    n_e = rg.regione_mask_cleanup(ctx, d_in, gh, gw, n_images, d_out, e, u, cnt)
+    assert n_e == len(e_want) == int(cnt.item())
+    assert np.array_equal(d_out.cpu().numpy(), want)
+    assert np.array_equal(e.cpu().numpy()[:n_e], e_want)
+    assert np.array_equal(u.cpu().numpy()[:n - n_e], u_want)
+    assert (e.cpu().numpy()[n_e:] == -7).all() and (u.cpu().numpy()[n - n_e:] == -7).all()   # nothing written past the lists
+    # in place, and applying it twice changes nothing (opening then closing is an idempotent filter)
+    n_e2 = rg.regione_mask_cleanup(ctx, d_out, gh, gw, n_images, d_out, e, u, cnt)
+    assert n_e2 == n_e and np.array_equal(d_out.cpu().numpy(), want)
+    ctx.close()
+
+
+def test_mask_cleanup_degenerate_and_errors():
+    ctx = rg.Context(256, 4, 64, 1024, 16, 128 * 128)
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for fill in (0, 1):
+        m = torch.full((64,), fill, dtype=torch.uint8, device="cuda")
+        e = torch.empty(64, dtype=torch.int32, device="cuda"); u = torch.empty_like(e)
+        assert rg.regione_mask_cleanup(ctx, m, 8, 8, 1, m, e, u, cnt) == 64 * fill
+        assert (m.cpu().numpy() == fill).all()
+    assert rg.regione_mask_cleanup(ctx, None, 8, 8, 0, None, None, None, cnt) == 0    # no image: count 0, nothing touched
+    with pytest.raises(rg.RegionEError):
+        rg.regione_mask_cleanup(ctx, m, 129, 128, 1, m, e, u, cnt)                    # more cells than a workgroup's LDS holds
+    with pytest.raises(rg.RegionEError):
+        rg.regione_mask_cleanup(ctx, m, 0, 8, 1, m, e, u, cnt)
+    ctx.close()
