@@ -51,7 +51,6 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
     regione_ctx* c = new (std::nothrow) regione_ctx();
     if (!c) RG_FAIL(REGIONE_ERR_HIP, "create: out of host memory");
     memset(c, 0, sizeof(*c));
-    if (const char* e = getenv("REGIONE_ATTN_VARIANT")) c->attn_variant = atoi(e);
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->dims = *dims;
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; RG_FAIL(REGIONE_ERR_HIP, "create: no HIP device"); }

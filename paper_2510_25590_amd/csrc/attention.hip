@@ -69,11 +69,21 @@ __device__ __forceinline__ void async_copy16(const bf16_t* src, unsigned lds_bas
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(src), "s"(lds_base_bytes) : "memory", "m0");
 }
 
+// Same copy with the address split into a wave-uniform 64-bit base (scalar registers) and a 32-bit byte offset per
+// lane: the base moves from tile to tile with scalar arithmetic and the lanes' offsets never change.
+__device__ __forceinline__ void async_copy16_sbase(unsigned lane_off_bytes, const bf16_t* base, unsigned lds_base_bytes) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(lane_off_bytes), "s"(base), "s"(lds_base_bytes) : "memory", "m0");
+}
+
+// Which rows a call reads: one contiguous array (fresh rows only, or the whole cache), fresh rows followed by cache
+// rows, or cache rows picked by an index list.
+enum { SRC_CONTIG = 0, SRC_TWO = 1, SRC_INDEXED = 2 };
+
 // Issues the copies of one 64-key tile into an LDS stage.  The tile is 64 * CPR chunks; wave w issues blocks
 // b = w*LD_N + i of 64 consecutive chunk positions, position P = row*CPR + physical chunk.  Since the LDS side is
 // linear in the lane, the swizzle is applied on the global side: the lane that owns physical chunk p of a row loads
 // the logical chunk p ^ f(row) (both swizzles are XORs, hence their own inverses).
-template <int D, int NW, bool INDEXED>
+template <int D, int NW, int MODE>
 __device__ __forceinline__ void kv_tile_issue(const AttnArgs& a, int head, int key0, int n_keys, unsigned stage_base_bytes) {
     constexpr int CPR = D / 8, LD_N = KT * CPR / (NW * 64), TILE = KT * D;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -86,7 +96,7 @@ __device__ __forceinline__ void kv_tile_issue(const AttnArgs& a, int head, int k
         key = key < n_keys ? key : n_keys - 1;   // tail rows repeat a valid row; their scores are masked
         const bool fresh = key < a.n0;
         int64_t grow = fresh ? key : key - a.n0;
-        if (INDEXED) { if (!fresh) grow = a.idx1[grow]; }
+        if (MODE == SRC_INDEXED) { if (!fresh) grow = a.idx1[grow]; }
         const int64_t base = grow * (fresh ? a.ldkv0 : a.ldkv1) + head * D;
         const unsigned lds_blk = __builtin_amdgcn_readfirstlane(stage_base_bytes + static_cast<unsigned>(b) * 1024u);
         async_copy16((fresh ? a.k0 : a.k1) + base + (k_swz<D>(row, phys) << 3), lds_blk);
@@ -99,7 +109,7 @@ template <int N> __device__ __forceinline__ void wait_async_copies() {   // at m
 
 // One 64-key tile for the QB*32 queries of a wave.  STAGE selects the LDS buffer (compile time, so that every LDS
 // address is a per-lane constant plus an immediate).  K and V fragments are read once and used for all QB query blocks.
-template <int D, int STAGE, int QB>
+template <int D, int STAGE, int QB, bool MASK>
 __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys, float c, int lh,
                                           const int (&koff)[D / 16], const int (&voff)[D / 32], const bf16x8 (&qf)[QB][D / 16],
                                           f32x16 (&o)[QB][D / 32], float (&m_run)[QB], float (&l_run)[QB]) {
@@ -142,8 +152,7 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
     }
 
     // ---- online softmax on raw scores; accumulator r of block kb is key t*64 + kb*32 + 8*(r/4) + 4*lh + r%4
-    if ((t + 1) * KT > n_keys) {   // the last tile may run past the key list
-        asm volatile("" ::: "memory");   // keep this a branch: as selects it would cost every tile 64 instructions
+    if (MASK) {   // only the last tile of the key list can run past it: the kernel peels that tile off its main loop
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -217,7 +226,7 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
 }
 
 // NW waves per workgroup, QB blocks of 32 queries per wave, NSTAGE LDS stages.
-template <int D, int NW, int QB, int NSTAGE, int WPE, bool INDEXED>
+template <int D, int NW, int QB, int NSTAGE, int WPE, int MODE>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 attn_kvcache_kernel(AttnArgs a) {
     constexpr int DB = D / 32;   // 32-wide d blocks of the output
@@ -283,37 +292,60 @@ attn_kvcache_kernel(AttnArgs a) {
     }
     const float c = a.scale_log2e;
 
-    // NSTAGE LDS stages, copies NSTAGE-1 tiles ahead.  Per tile: wait until this tile's copies have landed, barrier
-    // (publishes them and retires the stage read one tile ago), issue the copies of tile t+NSTAGE-1 into that retired
-    // stage, compute.  Tiles past the end re-copy the last tile so that the copy count per tile is constant.
+    // Two LDS stages, copies one tile ahead.  Per tile: wait until this tile's copies have landed, barrier (publishes
+    // them and retires the stage read one tile ago), issue the copies of the next tile into that retired stage, compute.
+    // Tiles past the end re-copy the last tile so that the copy count per tile is constant.
+    static_assert(NSTAGE == 2, "the tile loop below alternates two stages");
     constexpr unsigned STAGE_BYTES = 2u * TILE * 2u;
-    auto tile_key0 = [&](int t) __attribute__((always_inline)) { return (t < tile_end ? t : tile_end - 1) * KT; };
-    if (tile_begin < tile_end) {
+    // contiguous source: per-lane byte offsets of this thread's chunk positions inside a tile, for K and for V
+    const bf16_t* const src_k = a.n0 > 0 ? a.k0 : a.k1;
+    const bf16_t* const src_v = a.n0 > 0 ? a.v0 : a.v1;
+    const int src_ld = a.n0 > 0 ? a.ldkv0 : a.ldkv1;
+    unsigned off_k[LD_N], off_v[LD_N];
+    if (MODE == SRC_CONTIG) {
 #pragma unroll
-        for (int p = 0; p < NSTAGE - 1; ++p)
-            kv_tile_issue<D, NW, INDEXED>(a, head, tile_key0(tile_begin + p), n_keys, smem_bytes0 + p * STAGE_BYTES);
+        for (int i = 0; i < LD_N; ++i) {
+            const int pos = (wave * LD_N + i) * 64 + lane;
+            const int row = pos / CPR, phys = pos % CPR;
+            const unsigned row_off = static_cast<unsigned>(row) * static_cast<unsigned>(src_ld) + static_cast<unsigned>(head * D);
+            off_k[i] = (row_off + static_cast<unsigned>(k_swz<D>(row, phys) << 3)) * 2u;
+            off_v[i] = (row_off + static_cast<unsigned>(v_swz<D>(row, phys) << 3)) * 2u;
+        }
     }
-#define RG_ATTN_TILE(T, STAGE)                                                                            \
+    const unsigned wave_lds = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(wave * LD_N) * 1024u);
+    auto issue_tile = [&](int t, unsigned stage_bytes) __attribute__((always_inline)) {
+        const int tc = t < tile_end ? t : tile_end - 1;
+        if (MODE == SRC_CONTIG && (tc + 1) * KT <= n_keys) {     // a full tile of one array: scalar base + fixed lane offsets
+            const bf16_t* kb = src_k + static_cast<int64_t>(tc) * KT * src_ld;
+            const bf16_t* vb = src_v + static_cast<int64_t>(tc) * KT * src_ld;
+#pragma unroll
+            for (int i = 0; i < LD_N; ++i) {
+                const unsigned lds_blk = stage_bytes + wave_lds + static_cast<unsigned>(i) * 1024u;
+                async_copy16_sbase(off_k[i], kb, lds_blk);
+                async_copy16_sbase(off_v[i], vb, lds_blk + TILE * 2u);
+            }
+        } else {
+            kv_tile_issue<D, NW, MODE == SRC_CONTIG ? SRC_TWO : MODE>(a, head, tc * KT, n_keys, stage_bytes);
+        }
+    };
+    if (tile_begin < tile_end) issue_tile(tile_begin, smem_bytes0);
+#define RG_ATTN_TILE(T, STAGE, MASK)                                                                      \
     {                                                                                                     \
         const int t_ = (T);                                                                               \
-        wait_async_copies<(NSTAGE - 2) * COPIES>();                                                       \
+        wait_async_copies<0>();                                                                           \
         __syncthreads();                                                                                  \
-        kv_tile_issue<D, NW, INDEXED>(a, head, tile_key0(t_ + NSTAGE - 1), n_keys,                        \
-                                      smem_bytes0 + ((STAGE + NSTAGE - 1) % NSTAGE) * STAGE_BYTES);       \
-        attn_tile<D, STAGE, QB>(smem, t_, n_keys, c, lh, koff, voff, qf, o, m_run, l_run);                \
+        issue_tile(t_ + 1, smem_bytes0 + ((STAGE) ^ 1) * STAGE_BYTES);                                    \
+        attn_tile<D, STAGE, QB, MASK>(smem, t_, n_keys, c, lh, koff, voff, qf, o, m_run, l_run);          \
     }
-    if constexpr (NSTAGE == 2) {
-        for (int t = tile_begin; t < tile_end; t += 2) {
-            RG_ATTN_TILE(t, 0)
-            if (t + 1 < tile_end) RG_ATTN_TILE(t + 1, 1)
-        }
-    } else {
-        static_assert(NSTAGE == 2 || NSTAGE == 3, "two or three LDS stages");
-        for (int t = tile_begin; t < tile_end; t += 3) {
-            RG_ATTN_TILE(t, 0)
-            if (t + 1 < tile_end) RG_ATTN_TILE(t + 1, 1)
-            if (t + 2 < tile_end) RG_ATTN_TILE(t + 2, 2)
-        }
+    // only the very last tile of the key list can be partial; it runs outside the main loop with the masking code
+    const bool last_partial = tile_end * KT > n_keys;
+    const int full_end = last_partial ? tile_end - 1 : tile_end;
+    for (int t = tile_begin; t < full_end; t += 2) {
+        RG_ATTN_TILE(t, 0, false)
+        if (t + 1 < full_end) RG_ATTN_TILE(t + 1, 1, false)
+    }
+    if (full_end < tile_end && tile_begin < tile_end) {   // its stage follows from the number of full tiles before it
+        if (((full_end - tile_begin) & 1) == 0) RG_ATTN_TILE(full_end, 0, true) else RG_ATTN_TILE(full_end, 1, true)
     }
 #undef RG_ATTN_TILE
     wait_async_copies<0>();   // nothing may still be writing LDS when the workgroup ends
@@ -424,12 +456,17 @@ int launch_attention(regione_ctx* ctx, AttnArgs a) {
     constexpr size_t lds_bytes = static_cast<size_t>(NSTAGE) * 2 * KT * D * sizeof(bf16_t);
     static bool attr_set = false;   // per instantiation: more than 64 KiB of LDS has to be granted explicitly
     if (!attr_set) {
-        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
-        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, false>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, SRC_INDEXED>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, SRC_TWO>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, SRC_CONTIG>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
         attr_set = true;
     }
-    if (a.idx1) hipLaunchKernelGGL((attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, true>), grid, dim3(NW * 64), lds_bytes, ctx->stream, a);
-    else hipLaunchKernelGGL((attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, false>), grid, dim3(NW * 64), lds_bytes, ctx->stream, a);
+    // a lane's byte offset inside a tile of a contiguous source has to fit 32 bits
+    const int64_t src_ld = a.n0 > 0 ? a.ldkv0 : a.ldkv1;
+    const bool contig = !a.idx1 && (a.n0 == 0 || a.n1 == 0) && (KT * src_ld + a.heads * D) * 2 < (int64_t{1} << 31);
+    if (a.idx1) hipLaunchKernelGGL((attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, SRC_INDEXED>), grid, dim3(NW * 64), lds_bytes, ctx->stream, a);
+    else if (contig) hipLaunchKernelGGL((attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, SRC_CONTIG>), grid, dim3(NW * 64), lds_bytes, ctx->stream, a);
+    else hipLaunchKernelGGL((attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, SRC_TWO>), grid, dim3(NW * 64), lds_bytes, ctx->stream, a);
     RG_LAUNCH_CHECK();
     if (splits > 1) {
         const int64_t total = static_cast<int64_t>(a.n_q) * a.heads * (D / 4);
@@ -467,12 +504,7 @@ int rg_attention(regione_ctx* ctx, const bf16_t* q, int ldq, int n_q,
     a.scale_log2e = (scale > 0.f ? scale : 1.0f / sqrtf(static_cast<float>(d))) * 1.4426950408889634f;
     a.out = out; a.ldo = ldo;
     if (d == 64) return launch_attention<64, 4, 1, 2, 2>(ctx, a);
-    switch (ctx->attn_variant) {
-        case 1: return launch_attention<128, 4, 1, 3, 1>(ctx, a);
-        case 2: return launch_attention<128, 2, 2, 2, 1>(ctx, a);
-        case 3: return launch_attention<128, 8, 1, 3, 2>(ctx, a);
-        default: return launch_attention<128, 4, 1, 2, 2>(ctx, a);
-    }
+    return launch_attention<128, 4, 1, 2, 2>(ctx, a);
 }
 
 extern "C" int regione_attn_kvcache(regione_ctx* ctx, const void* q, int32_t n_q,

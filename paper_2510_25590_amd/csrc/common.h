@@ -27,7 +27,6 @@ struct regione_ctx {
     float* gemm_part;  // split-K partial sums
     size_t gemm_part_bytes;
     int gemm_force_tn, gemm_force_splits;  // 0 = chosen per call
-    int attn_variant;  // experiments: kernel shape
     int attn_force_splits;  // 0 = chosen per call
     // optional per-kernel-class timing with HIP events on the context's stream
     int prof_on;
