@@ -98,6 +98,44 @@ def membound(torch, rg):
     return res
 
 
+def loop_benchmark(n_double: int, n_single: int):
+    """Whole sampling loop on the device: the method's 28-step schedule (6 stabilization steps, forced step at k = 16,
+    2 smooth steps, velocity-decay cache with delta = 0.04 on a linear schedule) against 28 plain full steps of the same
+    editor.  3072 wide, 24 heads of 128, MLP 12288, 64x64 image + 4096 reference + 512 text tokens, one 25 % blob edited
+    (constructed so that the partition finds exactly it), random weights drawn on the device."""
+    import numpy as np
+    import torch
+    from paper_2510_25590_amd import binding as rg, inputs, loop
+    T, t_st, t_sm, forced = 28, 6, 2, [16]
+    grid, channels, n_txt = 64, 64, 512
+    n_img = grid * grid
+    rng = np.random.default_rng(inputs.workload_seed(4, 9))
+    want = inputs.blob_mask(rng, grid, grid, n_img // 4)
+    x_T, x_ref = inputs.loop_latents(rng, want, channels)
+    model = loop.EditorModel.synthetic(3072, 24, 128, 12288, channels, n_img, n_txt, n_double, n_single, seed=4)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    x_T_d, x_ref_d = dev(x_T), dev(x_ref)
+    t = [k / T for k in range(T + 1)]
+    gamma = [1.0] * (T + 1)
+    out = {"workload": f"28-step sampling loop, {n_double} double + {n_single} single blocks at 3072 wide, 4096 image + 4096 reference + 512 text tokens"}
+    for name, kwargs in (("regione", dict(t_st=t_st, t_sm=t_sm, forced_k=forced, delta=0.04)),
+                         ("vanilla", dict(t_st=T - 1, t_sm=1, forced_k=[], delta=-1.0))):    # every step a full step
+        for rep in range(2):    # first pass warms up (allocations, first launches)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            x0, log = loop.run_loop(model, x_T_d, x_ref_d, t, gamma, T, kwargs["t_st"], kwargs["t_sm"], kwargs["forced_k"], 0.8, kwargs["delta"])
+            torch.cuda.synchronize()
+            sec = time.perf_counter() - t0
+        kinds = [w[1] for w in log if w[0] != "partition"]
+        out[name] = {"seconds": sec, "full_steps": sum(k.startswith("full") for k in kinds), "region_fresh": kinds.count("region_fresh"),
+                     "region_reuse": kinds.count("region_reuse"), "n_edited": next((w[1] for w in log if w[0] == "partition"), None),
+                     "finite": bool(torch.isfinite(x0).all().item())}
+    out["speedup"] = out["vanilla"]["seconds"] / out["regione"]["seconds"]
+    out["n_edited_constructed"] = int(want.sum())
+    model.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,6 +146,10 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="time the steps without the per-kernel event pairs")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy three times (calibration of the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--loop", action="store_true",
+                    help="instead of the step benchmark: time the whole sampling loop (Algorithm 1, 28 steps) of a 3072-wide editor with "
+                         "19 double- and 38 single-stream blocks against 28 plain full steps, and print one JSON line about it")
+    ap.add_argument("--loop-blocks", type=str, default="19,38", help="double,single block counts for --loop")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); run it with --gpus 1")
@@ -125,6 +167,9 @@ def main():
     from paper_2510_25590_amd import step
 
     rg.lib()   # fails loudly if the HIP library has not been built
+    if args.loop:
+        print(json.dumps(loop_benchmark(*[int(v) for v in args.loop_blocks.split(",")])))
+        return
     cfg = step.CONFIG_BLOCK
     wl = step.RegionStepWorkload(cfg)
     for _ in range(args.warmup):

@@ -19,37 +19,84 @@ from . import binding as rg
 
 class EditorModel:
     def __init__(self, weights: dict, hidden: int, heads: int, head_dim: int, mlp: int, channels: int, n_img: int):
+        """weights: host arrays as made by inputs.model_weights (embed, blocks, head, h_txt)."""
+        import torch
+        bf = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).cuda()
+        f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+        self._setup(hidden, heads, head_dim, mlp, channels, n_img, weights["h_txt"].shape[0])
+        self.w_embed = rg.pack_weight(self.ctx, bf(weights["embed"]["w"]))
+        self.b_embed_host = np.asarray(weights["embed"]["b"], dtype=np.float32)
+        self.b_time_host = np.asarray(weights["embed"]["b_time"], dtype=np.float32)
+        self.w_head, self.b_head = rg.pack_weight(self.ctx, bf(weights["head"]["w"])), f32(weights["head"]["b"])
+        self.h_txt = bf(weights["h_txt"])
+        for kind, streams in weights["blocks"]:
+            self._add_block(kind, [{k: (rg.pack_weight(self.ctx, bf(a)) if k.startswith("w_") else f32(a)) for k, a in w.items()}
+                                   for w in streams])
+        self.h_a[:self.n_txt].copy_(self.h_txt)     # text rows of the block input never change
+
+    @classmethod
+    def synthetic(cls, hidden: int, heads: int, head_dim: int, mlp: int, channels: int, n_img: int, n_txt: int,
+                  n_double: int, n_single: int, seed: int = 0, std: float = 0.02):
+        """The same architecture with N(0, std) weights drawn on the device (for models too large to draw on the host:
+        19 double + 38 single blocks at 3072 wide are 17 GB).  For timing only: no oracle sees these weights."""
+        import torch
+        self = cls.__new__(cls)
+        self._setup(hidden, heads, head_dim, mlp, channels, n_img, n_txt)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seed)
+        rnd = lambda *shape, scale=std: (torch.randn(shape, device="cuda", generator=g) * scale)
+        wt = lambda o, i, scale=std: rg.pack_weight(self.ctx, rnd(o, i, scale=scale).to(torch.bfloat16))
+        self.w_embed = wt(hidden, channels, 4 * std)
+        self.b_embed_host = (0.1 * np.random.default_rng(seed).standard_normal(hidden)).astype(np.float32)
+        self.b_time_host = (0.5 * np.random.default_rng(seed + 1).standard_normal(hidden)).astype(np.float32)
+        # head scaled so that the velocity has the spread of the small test models (0.02 * sqrt(256) = 0.32) at any width
+        self.w_head, self.b_head = wt(channels, hidden, 0.32 / float(np.sqrt(hidden))), rnd(channels)
+        self.h_txt = rnd(n_txt, hidden, scale=1.0).to(torch.bfloat16)
+
+        def stream(kind):
+            t = {}
+            if kind == "double":
+                t["w_qkv"], t["b_qkv"] = wt(3 * hidden, hidden), rnd(3 * hidden)
+                t["w_o"], t["b_o"] = wt(hidden, hidden), rnd(hidden)
+                t["w_1"], t["b_1"] = wt(mlp, hidden), rnd(mlp)
+                t["w_2"], t["b_2"] = wt(hidden, mlp), rnd(hidden)
+            else:
+                t["w_1"], t["b_1"] = wt(3 * hidden + mlp, hidden), rnd(3 * hidden + mlp)
+                t["w_2"], t["b_2"] = wt(hidden, hidden + mlp), rnd(hidden)
+            for name in ("shift1", "scale1", "gate1") + (("shift2", "scale2", "gate2") if kind == "double" else ()):
+                t[name] = 1.0 + rnd(hidden, scale=0.1) if name.startswith("gate") else rnd(hidden, scale=0.1)
+            return t
+        for _ in range(n_double):
+            self._add_block("double", [stream("double"), stream("double")])
+        for _ in range(n_single):
+            self._add_block("single", [stream("single")])
+        self.h_a[:self.n_txt].copy_(self.h_txt)
+        return self
+
+    def _setup(self, hidden, heads, head_dim, mlp, channels, n_img, n_txt):
         import torch
         self.torch = torch
         self.hidden, self.heads, self.head_dim, self.mlp, self.channels = hidden, heads, head_dim, mlp, channels
-        self.n_img = n_img
-        self.n_txt = weights["h_txt"].shape[0]
-        self.n_all = self.n_txt + 2 * n_img
-        bf = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).cuda()
-        f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
-        self.ctx = rg.Context(hidden, heads, head_dim, mlp, self.n_all, max(self.n_all, n_img))
-        ctx = self.ctx
-        self.w_embed = rg.pack_weight(ctx, bf(weights["embed"]["w"]))
-        self.b_embed_host = np.asarray(weights["embed"]["b"], dtype=np.float32)
-        self.b_time_host = np.asarray(weights["embed"]["b_time"], dtype=np.float32)
-        self.w_head, self.b_head = rg.pack_weight(ctx, bf(weights["head"]["w"])), f32(weights["head"]["b"])
-        self.h_txt = bf(weights["h_txt"])
+        self.n_img, self.n_txt = n_img, n_txt
+        self.n_all = n_txt + 2 * n_img
+        self.ctx = rg.Context(hidden, heads, head_dim, mlp, self.n_all, n_img)
         self.blocks, self._keep = [], []
-        for kind, streams in weights["blocks"]:
-            bw = rg.BlockWeights()
-            for name, w in zip(("txt", "img") if kind == "double" else ("img",), streams):
-                t = {k: (rg.pack_weight(ctx, bf(a)) if k.startswith("w_") else f32(a)) for k, a in w.items()}
-                self._keep.append(t)
-                setattr(bw, name, rg.make_stream_weights(t))
-            kc = torch.zeros((self.n_all, heads, head_dim), dtype=torch.bfloat16, device="cuda")
-            self.blocks.append((rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE, bw, kc, torch.zeros_like(kc)))
         dev = "cuda"
         self.h_a = torch.empty((self.n_all, hidden), dtype=torch.bfloat16, device=dev)
         self.h_b = torch.empty_like(self.h_a)
         self.rows_bf = torch.empty((2 * n_img, channels), dtype=torch.bfloat16, device=dev)
         self.u = torch.empty((n_img, hidden), dtype=torch.bfloat16, device=dev)
         self.all_slots = torch.arange(self.n_all, dtype=torch.int32, device=dev)
-        self.h_a[:self.n_txt].copy_(self.h_txt)     # text rows of the block input never change
+
+    def _add_block(self, kind: str, streams):
+        """streams: one dict per stream, name -> device tensor (linear weights already packed)."""
+        torch = self.torch
+        bw = rg.BlockWeights()
+        for name, t in zip(("txt", "img") if kind == "double" else ("img",), streams):
+            self._keep.append(t)
+            setattr(bw, name, rg.make_stream_weights(t))
+        kc = torch.zeros((self.n_all, self.heads, self.head_dim), dtype=torch.bfloat16, device="cuda")
+        self.blocks.append((rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE, bw, kc, torch.zeros_like(kc)))
 
     def _embed_bias(self, t: float):
         """Bias of the token embedding at time t (input marshalling: a float32 vector b + t * b_time)."""
