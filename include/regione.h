@@ -168,8 +168,9 @@ int regione_linear(regione_ctx* ctx, const void* x, const void* w_packed, const 
                    int32_t m, int32_t n, int32_t k, int32_t act, int32_t out_dtype, void* y);
 
 /* Tuning knob for experiments: forces the GEMM wave tile (1 or 2 blocks of 32 columns; 3 or 4 =
- * the same two widths with the kernel that stages both operands through LDS) and the number of
- * K splits of every later GEMM of this context; 0 restores the automatic choice. */
+ * the same two widths with the kernel that stages both operands through LDS, 5 or 6 = that
+ * kernel with 256-row workgroup tiles) and the number of K splits of every later GEMM of this
+ * context; 0 restores the automatic choice. */
 int regione_tune_gemm(regione_ctx* ctx, int32_t wave_tile_blocks, int32_t k_splits);
 
 /* Tuning knob for experiments: forces the number of key-range splits (1..8) of every later

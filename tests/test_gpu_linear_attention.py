@@ -45,8 +45,9 @@ def test_linear_matches_oracle(ctx, m, n, k, act):
     y = torch.empty((m, n), dtype=torch.float32, device="cuda")
     rg.regione_linear(ctx, dev(x, "bf16"), wp, None, m, n, k, rg.ACT_NONE, rg.FP32, y)
     assert_close(host(y), orc.linear(x, w, None), "linear no bias", max_abs=2e-4, mean_rel_tol=1e-5)
-    # every wave-tile width and K split gives the same result
-    for tn, splits in ((1, 1), (2, 1), (1, 3), (2, 2), (2, 4)):
+    # every kernel variant (1, 2: weights straight to registers; 3, 4: both operands through LDS; 5, 6: the same with
+    # 256-row tiles), wave-tile width and K split gives the same result
+    for tn, splits in ((1, 1), (2, 1), (1, 3), (2, 2), (2, 4), (3, 1), (4, 1), (4, 2), (5, 1), (6, 1), (6, 3)):
         rg.regione_tune_gemm(ctx, tn, splits)
         y2 = torch.full((m + 1, n), 77.0, dtype=torch.float32, device="cuda")
         rg.regione_linear(ctx, dev(x, "bf16"), wp, db, m, n, k, act, rg.FP32, y2)
