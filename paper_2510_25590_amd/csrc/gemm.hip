@@ -221,6 +221,18 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[TM][TN], float* stag
     }
 }
 
+// Tile order inside the launch: groups of `gh` row tiles; inside a group all column tiles, and for each column tile
+// the group's row tiles consecutively.  The workgroups that run at the same time on an XCD then share a weight line
+// among gh CUs and an activation line among the rest, instead of all of them hammering the same weight lines.
+__device__ __forceinline__ void tile_coords(int tile, int m_tiles, int n_tiles, int gh, int& m_tile, int& n_tile) {
+    const int per_group = gh * n_tiles;
+    const int group = tile / per_group, rem = tile - group * per_group;
+    int rows = m_tiles - group * gh;
+    rows = rows < gh ? rows : gh;
+    n_tile = rem / rows;
+    m_tile = group * gh + (rem - n_tile * rows);
+}
+
 // Global loads of the pipeline are written in assembly and waited for by hand.  Left to the compiler, the rotating
 // register sets made its wait-count insertion drain nearly every outstanding load at the top of a K-step (it reuses
 // the registers of a consumed set for LDS fragments and then protects them against loads it believes pending), which
@@ -277,7 +289,7 @@ __device__ __forceinline__ bf16x8 a_frag(const bf16_t* tile, int row, int chunk)
 template <int TN, int KIND>
 __global__ void __launch_bounds__(kThreads)
 gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ Wp,
-                 int M, int N, int K, int m_tiles, int n_tiles, int tiles_per_xcd,
+                 int M, int N, int K, int m_tiles, int n_tiles, int tiles_per_xcd, int group_rows,
                  int steps_per_split, float* __restrict__ partial, GemmEpilogue ep) {
     constexpr int WN = 32 * TN, BN = 4 * WN;
     __shared__ __attribute__((aligned(16))) bf16_t a_lds[2][BM * BK];
@@ -286,7 +298,8 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int tile = xcd * tiles_per_xcd + local;
     if (local >= tiles_per_xcd || tile >= m_tiles * n_tiles) return;
-    const int n_tile = tile / m_tiles, m_tile = tile - n_tile * m_tiles;
+    int n_tile, m_tile;
+    tile_coords(tile, m_tiles, n_tiles, group_rows, m_tile, n_tile);
     const int m0 = m_tile * BM, n0 = n_tile * BN;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -454,7 +467,7 @@ __device__ __forceinline__ void rg_async_copy16(const bf16_t* src, unsigned lds_
 template <int TN, int WM, int KIND>
 __global__ void __launch_bounds__(kThreads * WM) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gemm_lds_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ Wp,
-                int M, int N, int K, int m_tiles, int n_tiles, int tiles_per_xcd,
+                int M, int N, int K, int m_tiles, int n_tiles, int tiles_per_xcd, int group_rows,
                 int steps_per_split, float* __restrict__ partial, GemmEpilogue ep) {
     using G = LdsGemm<TN, WM>;
     constexpr int WN = 32 * TN, BN = 4 * WN;
@@ -464,7 +477,8 @@ gemm_lds_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict_
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int tile = xcd * tiles_per_xcd + local;
     if (local >= tiles_per_xcd || tile >= m_tiles * n_tiles) return;
-    const int n_tile = tile / m_tiles, m_tile = tile - n_tile * m_tiles;
+    int n_tile, m_tile;
+    tile_coords(tile, m_tiles, n_tiles, group_rows, m_tile, n_tile);
     const int m0_wg = m_tile * G::ROWS, n0 = n_tile * BN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
@@ -667,6 +681,9 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, in
     if (used_splits > 1 && static_cast<size_t>(used_splits) * m * n * sizeof(float) > ctx->gemm_part_bytes)
         RG_FAIL(REGIONE_ERR_WORKSPACE, "gemm: %d K-splits of a %d x %d result exceed the workspace", used_splits, m, n);
     float* partial = used_splits > 1 ? ctx->gemm_part : nullptr;
+    // many row tiles: groups of four (measured 2-19 % faster on the 8704-row GEMMs than all row tiles of a column tile
+    // in a row); few row tiles: one group, the previous order
+    const int group_rows = m_tiles > 8 ? 4 : m_tiles;
     if (VARIANT != 0) {
         constexpr unsigned lds_bytes = LdsGemm<TN, WM>::LDS_BYTES;
         static bool attr_set = false;   // per instantiation: more than 64 KiB of LDS has to be granted explicitly
@@ -675,10 +692,10 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, in
             attr_set = true;
         }
         hipLaunchKernelGGL((gemm_lds_kernel<TN, WM, KIND>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads * WM), lds_bytes, ctx->stream,
-                           a, lda, wp, m, n, k, m_tiles, n_tiles, tiles_per_xcd, per, partial, ep);
+                           a, lda, wp, m, n, k, m_tiles, n_tiles, tiles_per_xcd, group_rows, per, partial, ep);
     } else {
         hipLaunchKernelGGL((gemm_bf16_kernel<TN, KIND>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads), 0, ctx->stream,
-                           a, lda, wp, m, n, k, m_tiles, n_tiles, tiles_per_xcd, per, partial, ep);
+                           a, lda, wp, m, n, k, m_tiles, n_tiles, tiles_per_xcd, group_rows, per, partial, ep);
     }
     RG_LAUNCH_CHECK();
     if (used_splits > 1) {
