@@ -30,6 +30,7 @@ int dev_alloc(T** p, size_t count) {
 void free_all(regione_ctx* c) {
     void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->attn_part, c->gemm_part};
     for (void* p : ptrs) if (p) (void)hipFree(p);
+    if (c->n_edited_pinned) (void)hipHostFree(c->n_edited_pinned);
     if (c->prof_ev) {
         for (int i = 0; i < 2 * c->prof_cap; ++i) if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
         delete[] c->prof_ev;
@@ -69,6 +70,17 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
     if (rc == REGIONE_OK) rc = dev_alloc(reinterpret_cast<char**>(&c->attn_part), c->attn_part_bytes);
     c->gemm_part_bytes = n > 0 ? static_cast<size_t>(128) << 20 : 0;
     if (rc == REGIONE_OK) rc = dev_alloc(reinterpret_cast<char**>(&c->gemm_part), c->gemm_part_bytes);
+    if (rc == REGIONE_OK) {   // pinned, device-visible host word for the edited-token count (saves the device-to-host copy)
+        void* host = nullptr; void* dev = nullptr;
+        if (hipHostMalloc(&host, 64, hipHostMallocMapped) != hipSuccess || hipHostGetDevicePointer(&dev, host, 0) != hipSuccess) {
+            if (host) (void)hipHostFree(host);
+            free_all(c); delete c;
+            RG_FAIL(REGIONE_ERR_HIP, "create: cannot allocate pinned host memory");
+        }
+        c->n_edited_pinned = static_cast<int32_t*>(host);
+        c->n_edited_pinned_dev = static_cast<int32_t*>(dev);
+        *c->n_edited_pinned = 0;
+    }
     if (rc != REGIONE_OK) { free_all(c); delete c; return rc; }
     *out = c;
     return REGIONE_OK;

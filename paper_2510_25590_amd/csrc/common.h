@@ -15,6 +15,8 @@ struct regione_ctx {
     // workspace (device)
     int32_t* part_counts;  // per-block edited counts of the partition
     int64_t part_counts_cap;
+    int32_t* n_edited_pinned;      // pinned host copy of the last edited-token count (host address)
+    int32_t* n_edited_pinned_dev;  // the same memory as the device sees it
     bf16_t* u;     // [max_fresh, H]     normalised + modulated rows
     bf16_t* q;     // [max_fresh, H]
     bf16_t* kf;    // [max_fresh, H]     fresh keys when the cache is not used

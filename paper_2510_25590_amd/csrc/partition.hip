@@ -130,7 +130,7 @@ score_mask_kernel(const T* __restrict__ x_t, const T* __restrict__ v, const T* _
 // entries.  Also writes the total.
 constexpr int kScanThreads = 1024;
 __global__ void __launch_bounds__(kScanThreads)
-scan_counts_kernel(int32_t* __restrict__ counts, int n_blocks, int32_t* __restrict__ n_edited) {
+scan_counts_kernel(int32_t* __restrict__ counts, int n_blocks, int32_t* __restrict__ n_edited, int32_t* __restrict__ n_edited_pinned) {
     __shared__ int wave_sum[kScanThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int per = (n_blocks + kScanThreads - 1) / kScanThreads;
@@ -151,16 +151,40 @@ scan_counts_kernel(int32_t* __restrict__ counts, int n_blocks, int32_t* __restri
     for (int w = 0; w < kScanThreads / 64; ++w) { if (w < wave) before += wave_sum[w]; total += wave_sum[w]; }
     int run = before + incl - local;   // exclusive prefix of this thread's first entry
     for (int i = first; i < first + per && i < n_blocks; ++i) { const int cnt = counts[i]; counts[i] = run; run += cnt; }
-    if (threadIdx.x == 0) *n_edited = total;
+    if (threadIdx.x == 0) { *n_edited = total; *n_edited_pinned = total; }
 }
 
+// SUMS = false: `offsets` holds the exclusive prefix sums of the per-block counts (scan_counts_kernel ran).
+// SUMS = true (few blocks): `offsets` holds the raw counts; every block adds up the counts of the blocks before it
+// itself, and the last block writes the total, which saves the scan kernel's launch.
+template <bool SUMS>
 __global__ void __launch_bounds__(kThreads)
 write_index_kernel(const uint8_t* __restrict__ mask, const int32_t* __restrict__ offsets,
                    int64_t n_tokens, int tok_per_block,
-                   int32_t* __restrict__ e_index, int32_t* __restrict__ u_index) {
+                   int32_t* __restrict__ e_index, int32_t* __restrict__ u_index,
+                   int32_t* __restrict__ n_edited, int32_t* __restrict__ n_edited_pinned) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     __shared__ int wave_e[kWaves];
-    int base_e = offsets[blockIdx.x];   // edited tokens in all blocks before this one
+    int base_e;
+    if (SUMS) {
+        int part = 0;
+        for (int b = threadIdx.x; b < static_cast<int>(blockIdx.x); b += kThreads) part += offsets[b];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
+        if (lane == 0) wave_e[wave] = part;
+        __syncthreads();
+        base_e = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) base_e += wave_e[w];
+        if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+            const int total = base_e + offsets[blockIdx.x];
+            *n_edited = total;
+            *n_edited_pinned = total;
+        }
+        // (the first round below starts with a barrier, so wave_e can be reused)
+    } else {
+        base_e = offsets[blockIdx.x];   // edited tokens in all blocks before this one
+    }
     const int64_t block_first = static_cast<int64_t>(blockIdx.x) * tok_per_block;
     int64_t base_u = block_first - base_e;
     for (int off = 0; off < tok_per_block; off += kThreads) {
@@ -186,7 +210,7 @@ write_index_kernel(const uint8_t* __restrict__ mask, const int32_t* __restrict__
     }
 }
 
-__global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
+__global__ void set_i32_kernel(int32_t* p, int32_t* p_pinned, int32_t v) { *p = v; *p_pinned = v; }
 
 template <typename T, int VEC>
 int launch_score(regione_ctx* ctx, int lpt, dim3 grid, const void* x_t, const void* v, const void* x_ref, int64_t n, int c,
@@ -263,6 +287,24 @@ count_mask_kernel(const uint8_t* __restrict__ mask, int64_t n_tokens, int tok_pe
     }
 }
 
+// Index lists from the mask and the per-block counts in ctx->part_counts: few blocks -> one launch, else scan + lists.
+int launch_index_lists(regione_ctx* ctx, dim3 grid, const uint8_t* mask, int64_t n_tokens, int tpb,
+                       int32_t* e_index, int32_t* u_index, int32_t* n_edited_dev) {
+    if (grid.x <= 1024) {
+        hipLaunchKernelGGL((write_index_kernel<true>), grid, dim3(kThreads), 0, ctx->stream,
+                           mask, ctx->part_counts, n_tokens, tpb, e_index, u_index, n_edited_dev, ctx->n_edited_pinned_dev);
+        RG_LAUNCH_CHECK();
+        return REGIONE_OK;
+    }
+    hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, ctx->stream, ctx->part_counts, static_cast<int>(grid.x), n_edited_dev,
+                       ctx->n_edited_pinned_dev);
+    RG_LAUNCH_CHECK();
+    hipLaunchKernelGGL((write_index_kernel<false>), grid, dim3(kThreads), 0, ctx->stream,
+                       mask, ctx->part_counts, n_tokens, tpb, e_index, u_index, n_edited_dev, ctx->n_edited_pinned_dev);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
 }  // namespace
 
 extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* v, const void* x_ref,
@@ -281,7 +323,7 @@ extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* 
     {
     ProfScope prof(ctx, REGIONE_PROF_PARTITION);
     if (n_tokens == 0) {
-        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, n_edited_dev, 0);
+        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, n_edited_dev, ctx->n_edited_pinned_dev, 0);
         RG_LAUNCH_CHECK();
     } else {
         const int full_vec = dtype == REGIONE_BF16 ? 8 : 4;
@@ -306,16 +348,12 @@ extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* 
                           : launch_score<float, 1>(ctx, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask);
         }
         if (rc != REGIONE_OK) return rc;
-        hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, ctx->stream, ctx->part_counts, static_cast<int>(nblocks), n_edited_dev);
-        RG_LAUNCH_CHECK();
-        hipLaunchKernelGGL(write_index_kernel, grid, dim3(kThreads), 0, ctx->stream,
-                           mask, ctx->part_counts, n_tokens, tpb, e_index, u_index);
-        RG_LAUNCH_CHECK();
+        if (int rc2 = launch_index_lists(ctx, grid, mask, n_tokens, tpb, e_index, u_index, n_edited_dev)) return rc2;
     }
     }
-    if (n_edited_host_opt) {
-        RG_HIP(hipMemcpyAsync(n_edited_host_opt, n_edited_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    if (n_edited_host_opt) {   // the kernels wrote the count to pinned host memory too: no copy to wait for, only the stream
         RG_HIP(hipStreamSynchronize(ctx->stream));
+        *n_edited_host_opt = *static_cast<volatile int32_t*>(ctx->n_edited_pinned);
     }
     return REGIONE_OK;
 }
@@ -332,7 +370,7 @@ extern "C" int regione_mask_cleanup(regione_ctx* ctx, const uint8_t* mask_in, in
     {
     ProfScope prof(ctx, REGIONE_PROF_PARTITION);
     if (n_tokens == 0) {
-        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, n_edited_dev, 0);
+        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, n_edited_dev, ctx->n_edited_pinned_dev, 0);
         RG_LAUNCH_CHECK();
     } else {
         if (!mask_in || !mask_out || !e_index || !u_index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "mask_cleanup: null tensor");
@@ -344,15 +382,12 @@ extern "C" int regione_mask_cleanup(regione_ctx* ctx, const uint8_t* mask_in, in
         const dim3 grid(static_cast<unsigned>(nblocks));
         hipLaunchKernelGGL(count_mask_kernel, grid, dim3(kThreads), 0, ctx->stream, mask_out, n_tokens, tpb, ctx->part_counts);
         RG_LAUNCH_CHECK();
-        hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, ctx->stream, ctx->part_counts, static_cast<int>(nblocks), n_edited_dev);
-        RG_LAUNCH_CHECK();
-        hipLaunchKernelGGL(write_index_kernel, grid, dim3(kThreads), 0, ctx->stream, mask_out, ctx->part_counts, n_tokens, tpb, e_index, u_index);
-        RG_LAUNCH_CHECK();
+        if (int rc2 = launch_index_lists(ctx, grid, mask_out, n_tokens, tpb, e_index, u_index, n_edited_dev)) return rc2;
     }
     }
-    if (n_edited_host_opt) {
-        RG_HIP(hipMemcpyAsync(n_edited_host_opt, n_edited_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    if (n_edited_host_opt) {   // the kernels wrote the count to pinned host memory too: no copy to wait for, only the stream
         RG_HIP(hipStreamSynchronize(ctx->stream));
+        *n_edited_host_opt = *static_cast<volatile int32_t*>(ctx->n_edited_pinned);
     }
     return REGIONE_OK;
 }

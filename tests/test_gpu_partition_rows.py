@@ -67,6 +67,31 @@ def test_ragged_sizes(ctx, n, dtype):
     check_partition(ctx, x_t, v, ref, 0.6, 0.9, dtype)
 
 
+def test_many_blocks_take_the_scan_kernel_path():
+    """More than 1024 blocks of tokens: the per-block counts go through the separate scan kernel (with fewer blocks the
+    index kernel adds them up itself).  40 000 tokens of 64 channels are 1250 blocks; the clean-up at 128x128x17 cells
+    is 1088 blocks."""
+    n = 40000
+    rng = np.random.default_rng(77)
+    want = rng.random(n) < 0.2
+    x_t, v, ref = inputs.latents_for_mask(rng, want, 64, 0.6, "bf16")
+    big = rg.Context(256, 4, 64, 1024, 16, 128 * 128 * 17)
+    assert check_partition(big, x_t, v, ref, 0.6, 0.9, "bf16") == int(want.sum())
+    cells, n_images = 128 * 128, 17
+    masks = [rng.random(cells) < 0.4 for _ in range(n_images)]
+    want_clean = np.concatenate([orc.mask_cleanup(m.astype(np.uint8), 128, 128) for m in masks[:2]])
+    d_in = torch.from_numpy(np.concatenate(masks).astype(np.uint8)).cuda()
+    e = torch.empty(cells * n_images, dtype=torch.int32, device="cuda"); u = torch.empty_like(e)
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    n_e = rg.regione_mask_cleanup(big, d_in, 128, 128, n_images, d_in, e, u, cnt)
+    got = d_in.cpu().numpy()
+    assert np.array_equal(got[:2 * cells], want_clean)            # the oracle's loops on two of the images
+    assert n_e == int(got.sum()) == int(cnt.item())
+    assert np.array_equal(e.cpu().numpy()[:n_e], np.nonzero(got)[0].astype(np.int32))
+    assert np.array_equal(u.cpu().numpy()[:cells * n_images - n_e], np.nonzero(got == 0)[0].astype(np.int32))
+    big.close()
+
+
 @pytest.mark.parametrize("c", [8, 16, 48, 128, 512, 1024, 7, 20])
 def test_channel_counts(ctx, c):
     rng = np.random.default_rng(200 + c)
