@@ -55,6 +55,7 @@ template <int D> __device__ __forceinline__ int v_swz(int row, int chunk) {
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+constexpr float kRescaleSlack = 8.0f;   // log2 of the largest probability weight kept without moving the reference
 __device__ __forceinline__ float max3(float a, float b, float c) {
     float r;
     asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
@@ -173,10 +174,16 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
 #pragma unroll
         for (int r = 1; r < 15; r += 2) mx = max3(mx, s[qb][1][r], s[qb][1][r + 1]);
         mx = max3(mx, s[qb][1][15], s[qb][1][15]);
-        mx = max3(mx, __shfl_xor(mx, 32, 64), m_run[qb]);
-        const float m_new = mx;                   // finite: every tile holds at least one live key
-        if (__builtin_amdgcn_ballot_w64(m_new > m_run[qb]) != 0) {   // wave-uniform: the running maximum rarely moves after the first tiles
-            const float alpha = fast_exp2((m_run[qb] - m_new) * c);
+        mx = max3(mx, __shfl_xor(mx, 32, 64), mx);
+        // m_run is the REFERENCE of the exponentials, not the exact running maximum: it only moves when the tile's
+        // maximum exceeds it by more than kRescaleSlack (in the log2 domain), so exp2((s - m_run) c) <= 2^kRescaleSlack
+        // and the 64-multiplication rescale of the accumulators becomes rare.  Any reference gives the same quotient
+        // O / l; the probabilities keep their relative precision in bf16 whatever their scale.
+        const bool move = (mx - m_run[qb]) * c > kRescaleSlack;     // the first tile: m_run = -inf, always true
+        float m_new = m_run[qb];
+        if (__builtin_amdgcn_ballot_w64(move) != 0) {               // wave-uniform branch
+            m_new = move ? mx : m_run[qb];                          // finite: every tile holds at least one live key
+            const float alpha = move ? fast_exp2((m_run[qb] - m_new) * c) : 1.0f;
             l_run[qb] *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
