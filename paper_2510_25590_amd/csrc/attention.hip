@@ -56,11 +56,27 @@ template <int D> __device__ __forceinline__ int v_swz(int row, int chunk) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 constexpr float kRescaleSlack = 8.0f;   // log2 of the largest probability weight kept without moving the reference
+// Three-input maximum in assembly (plain fmaxf costs an extra canonicalising instruction per MFMA result).  The
+// compiler does not check what an assembly statement reads against the MFMAs still in flight, so the FIRST read of an
+// accumulator after its last MFMA must be an ordinary expression (first_max below), which gets the required wait
+// states; everything chained behind it is late enough.
 __device__ __forceinline__ float max3(float a, float b, float c) {
     float r;
     asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
+__device__ __forceinline__ float first_max(float a, float b) { return __builtin_fmaxf(a, b); }
+// The value of lane l and of lane l ^ 32, in both lanes: gfx950's v_permlane32_swap exchanges the upper half of its
+// first operand with the lower half of its second, so two copies of x become (x of the lower lane, x of the upper
+// lane) everywhere.  A vector ALU instruction: no trip through the LDS as with a bpermute.
+__device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const unsigned a = r[0], b = r[1];   // elements copied out before the casts: a bit cast applied to r[1] directly reads r[0]
+    lo = __uint_as_float(a);
+    hi = __uint_as_float(b);
+}
+__device__ __forceinline__ float max_across_halves(float x) { float lo, hi; both_halves(x, lo, hi); return max3(lo, hi, hi); }
+__device__ __forceinline__ float sum_across_halves(float x) { float lo, hi; both_halves(x, lo, hi); return lo + hi; }
 
 // Asynchronous global -> LDS copy of one 16-byte chunk per lane (gfx950 global_load_lds_dwordx4): lane l of the wave
 // writes LDS[lds_base + 16*l].  The copy bypasses the VGPRs and is counted in vmcnt; it is written in assembly so
@@ -88,10 +104,13 @@ template <int D, int NW, int MODE>
 __device__ __forceinline__ void kv_tile_issue(const AttnArgs& a, int head, int key0, int n_keys, unsigned stage_base_bytes) {
     constexpr int CPR = D / 8, LD_N = KT * CPR / (NW * 64), TILE = KT * D;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // All addresses first, the copies afterwards: an index entry is an ordinary load, and a wait for it placed between
+    // two copies would wait for the earlier copy as well.
+    const bf16_t* ksrc[LD_N];
+    const bf16_t* vsrc[LD_N];
 #pragma unroll
     for (int i = 0; i < LD_N; ++i) {
-        const int b = wave * LD_N + i;
-        const int pos = b * 64 + lane;
+        const int pos = (wave * LD_N + i) * 64 + lane;
         const int row = pos / CPR, phys = pos % CPR;
         int key = key0 + row;
         key = key < n_keys ? key : n_keys - 1;   // tail rows repeat a valid row; their scores are masked
@@ -99,13 +118,25 @@ __device__ __forceinline__ void kv_tile_issue(const AttnArgs& a, int head, int k
         int64_t grow = fresh ? key : key - a.n0;
         if (MODE == SRC_INDEXED) { if (!fresh) grow = a.idx1[grow]; }
         const int64_t base = grow * (fresh ? a.ldkv0 : a.ldkv1) + head * D;
-        const unsigned lds_blk = __builtin_amdgcn_readfirstlane(stage_base_bytes + static_cast<unsigned>(b) * 1024u);
-        async_copy16((fresh ? a.k0 : a.k1) + base + (k_swz<D>(row, phys) << 3), lds_blk);
-        async_copy16((fresh ? a.v0 : a.v1) + base + (v_swz<D>(row, phys) << 3), lds_blk + TILE * 2u);
+        ksrc[i] = (fresh ? a.k0 : a.k1) + base + (k_swz<D>(row, phys) << 3);
+        vsrc[i] = (fresh ? a.v0 : a.v1) + base + (v_swz<D>(row, phys) << 3);
+    }
+#pragma unroll
+    for (int i = 0; i < LD_N; ++i) asm volatile("" : "+v"(ksrc[i]), "+v"(vsrc[i]));   // pins the order: addresses, then copies
+#pragma unroll
+    for (int i = 0; i < LD_N; ++i) {
+        const unsigned lds_blk = __builtin_amdgcn_readfirstlane(stage_base_bytes + static_cast<unsigned>(wave * LD_N + i) * 1024u);
+        async_copy16(ksrc[i], lds_blk);
+        async_copy16(vsrc[i], lds_blk + TILE * 2u);
     }
 }
-template <int N> __device__ __forceinline__ void wait_async_copies() {   // at most N of this wave's copies still in flight
-    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+// At most N of this wave's copies still in flight.  The wait is the compiler's own builtin, not assembly: its
+// wait-count pass then knows that its own earlier loads (query fragments, index entries) have landed too and does
+// not put waits of its own for them into the tile loop, where they would also wait for the copies just issued.
+template <int N> __device__ __forceinline__ void wait_async_copies() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a six-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));   // vmcnt(N), other counters untouched
+    asm volatile("" ::: "memory");
 }
 
 // One 64-key tile for the QB*32 queries of a wave.  STAGE selects the LDS buffer (compile time, so that every LDS
@@ -167,14 +198,15 @@ __device__ __forceinline__ void attn_tile(const bf16_t* smem, int t, int n_keys,
     for (int qb = 0; qb < QB; ++qb) {
         // maximum of the lane's 32 scores with three-input maxima (plain fmaxf costs an extra canonicalising
         // instruction per MFMA result); -inf entries of a masked tail are ordinary operands
-        float mx = max3(s[qb][0][0], s[qb][0][1], s[qb][0][2]);
+        float mx = first_max(s[qb][0][0], s[qb][0][1]);   // waits for the last MFMA of block 0
 #pragma unroll
-        for (int r = 3; r < 15; r += 2) mx = max3(mx, s[qb][0][r], s[qb][0][r + 1]);
-        mx = max3(mx, s[qb][0][15], s[qb][1][0]);
+        for (int r = 2; r < 16; r += 2) mx = max3(mx, s[qb][0][r], s[qb][0][r + 1]);
+        mx = first_max(mx, s[qb][1][0]);                  // and of block 1, issued later
+        mx = max3(mx, s[qb][1][1], s[qb][1][15]);
 #pragma unroll
-        for (int r = 1; r < 15; r += 2) mx = max3(mx, s[qb][1][r], s[qb][1][r + 1]);
-        mx = max3(mx, s[qb][1][15], s[qb][1][15]);
-        mx = max3(mx, __shfl_xor(mx, 32, 64), mx);
+        for (int r = 2; r < 14; r += 2) mx = max3(mx, s[qb][1][r], s[qb][1][r + 1]);
+        mx = max3(mx, s[qb][1][14], s[qb][1][14]);
+        mx = max_across_halves(mx);
         // m_run is the REFERENCE of the exponentials, not the exact running maximum: it only moves when the tile's
         // maximum exceeds it by more than kRescaleSlack (in the log2 domain), so exp2((s - m_run) c) <= 2^kRescaleSlack
         // and the 64-multiplication rescale of the accumulators becomes rare.  Any reference gives the same quotient
@@ -361,7 +393,7 @@ attn_kvcache_kernel(AttnArgs a) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const int qrow = q_base + qb * 32 + l32;
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
+        const float l_tot = sum_across_halves(l_run[qb]);
         if (qrow >= a.n_q) continue;
         if (a.splits == 1) {
             const float inv = 1.0f / l_tot;
