@@ -436,22 +436,32 @@ attn_combine_kernel(const float* __restrict__ part, int splits, int heads, int n
     const int g = static_cast<int>(gid % G);
     const int head = static_cast<int>((gid / G) % heads);
     const int qrow = static_cast<int>(gid / (static_cast<int64_t>(G) * heads));
+    // every split's row is requested before the first value is used (rows are 8-byte aligned: D + 2 floats each)
+    constexpr int kMaxSplits = 8;
+    float ms[kMaxSplits], ls[kMaxSplits];
+    float2 lo[kMaxSplits], hi[kMaxSplits];
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s)
+        if (s < splits) {
+            const float* pp = part + ((static_cast<int64_t>(s) * heads + head) * n_q_pad + qrow) * (D + 2);
+            const float2 ml = *reinterpret_cast<const float2*>(pp + D);
+            ms[s] = ml.x; ls[s] = ml.y;
+            lo[s] = *reinterpret_cast<const float2*>(pp + 4 * g);
+            hi[s] = *reinterpret_cast<const float2*>(pp + 4 * g + 2);
+        }
     float m = -INFINITY;
-    for (int s = 0; s < splits; ++s) {
-        const float* pp = part + ((static_cast<int64_t>(s) * heads + head) * n_q_pad + qrow) * (D + 2);
-        if (pp[D + 1] > 0.f) m = fmaxf(m, pp[D]);
-    }
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s)
+        if (s < splits && ls[s] > 0.f) m = fmaxf(m, ms[s]);
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     float l = 0.f;
-    for (int s = 0; s < splits; ++s) {
-        const float* pp = part + ((static_cast<int64_t>(s) * heads + head) * n_q_pad + qrow) * (D + 2);
-        const float ls = pp[D + 1];
-        if (!(ls > 0.f)) continue;  // a split that saw no key
-        const float w = fast_exp2(pp[D] - m);
-        l += w * ls;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] += w * pp[4 * g + e];
-    }
+    for (int s = 0; s < kMaxSplits; ++s)
+        if (s < splits && ls[s] > 0.f) {   // a split with l = 0 saw no key
+            const float w = fast_exp2(ms[s] - m);
+            l += w * ls[s];
+            acc[0] += w * lo[s].x; acc[1] += w * lo[s].y; acc[2] += w * hi[s].x; acc[3] += w * hi[s].y;
+        }
     const float inv = 1.0f / l;
     bf16x4 pk;
 #pragma unroll

@@ -81,6 +81,7 @@ __device__ __forceinline__ void epilogue_store(const GemmEpilogue& ep, int row, 
 }
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+constexpr int kMaxSplits = 8;   // largest K split the planner or a forced plan uses
 
 __device__ __forceinline__ void store8(void* base, int64_t elem, int as_f32, const float (&v)[8]) {
     if (as_f32) {
@@ -617,6 +618,40 @@ splitk_epilogue_kernel(const float* __restrict__ partial, int splits, int M, int
     }
 }
 
+// The same for rows whose columns come in whole groups of eight (the wide epilogue's conditions hold): one thread per
+// group, the partial sums of all splits requested before the first is used, 32-byte pieces throughout.
+template <int KIND>
+__global__ void __launch_bounds__(kThreads)
+splitk_epilogue8_kernel(const float* __restrict__ partial, int splits, int M, int N, GemmEpilogue ep) {
+    const int groups = N >> 3;
+    const int64_t gid = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (gid >= static_cast<int64_t>(M) * groups) return;
+    const int row = static_cast<int>(gid / groups), col0 = static_cast<int>(gid - static_cast<int64_t>(row) * groups) * 8;
+    const int64_t total = static_cast<int64_t>(M) * N;
+    const float* src = partial + static_cast<int64_t>(row) * N + col0;
+    f32x4 lo[kMaxSplits], hi[kMaxSplits];
+#pragma unroll
+    for (int p = 0; p < kMaxSplits; ++p)
+        if (p < splits) {
+            lo[p] = *reinterpret_cast<const f32x4*>(src + p * total);
+            hi[p] = *reinterpret_cast<const f32x4*>(src + p * total + 4);
+        }
+    float bias[8], gate[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        bias[e] = ep.bias ? ep.bias[col0 + e] : 0.f;
+        gate[e] = (KIND == EPI_RESID && ep.gate) ? ep.gate[col0 + e] : 1.f;
+    }
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int p = 0; p < kMaxSplits; ++p)
+        if (p < splits) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[e] += lo[p][e]; v[4 + e] += hi[p][e]; }
+        }
+    epilogue_store8<KIND>(ep, row, col0, v, bias, gate);
+}
+
 // [n, k] row-major -> fragment-major packed layout (rows past n are zero)
 __global__ void __launch_bounds__(kThreads)
 pack_weight_kernel(const bf16_t* __restrict__ w, int n, int k, bf16_t* __restrict__ wp) {
@@ -700,10 +735,16 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, in
     RG_LAUNCH_CHECK();
     if (used_splits > 1) {
         const int64_t total = static_cast<int64_t>(m) * n;
-        int64_t blocks = (total + kThreads - 1) / kThreads;
-        if (blocks > 256 * 16) blocks = 256 * 16;
-        hipLaunchKernelGGL((splitk_epilogue_kernel<KIND>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
-                           partial, used_splits, m, n, ep);
+        if (ep.vec_ok && used_splits <= kMaxSplits) {
+            const int64_t blocks = (total / 8 + kThreads - 1) / kThreads;
+            hipLaunchKernelGGL((splitk_epilogue8_kernel<KIND>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+                               partial, used_splits, m, n, ep);
+        } else {
+            int64_t blocks = (total + kThreads - 1) / kThreads;
+            if (blocks > 256 * 16) blocks = 256 * 16;
+            hipLaunchKernelGGL((splitk_epilogue_kernel<KIND>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+                               partial, used_splits, m, n, ep);
+        }
         RG_LAUNCH_CHECK();
     }
     return REGIONE_OK;
