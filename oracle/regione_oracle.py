@@ -22,6 +22,10 @@ The transformer block is NOT described by the paper (it treats the DiT as a blac
 Phi); the block here is this build's minimal MMDiT block: LayerNorm without affine
 (eps 1e-6) -> optional modulation -> QKV linear -> attention -> gated residual ->
 LayerNorm -> MLP with tanh-GELU -> gated residual.  Linear weights are [out, in].
+Optional extras of real editing models, equally outside the paper (pinned by their
+mathematics in tests/test_oracle_rope_norm.py): RMS normalisation of queries and keys
+over the head dimension, and rotary position embedding whose angles belong to a token's
+position in the FULL sequence, so a gathered token keeps its own.
 """
 from __future__ import annotations
 
@@ -184,6 +188,44 @@ def linear(x: np.ndarray, w: np.ndarray, b=None) -> np.ndarray:
     return y
 
 
+def rms_norm(x: np.ndarray, weight=None, eps: float = 1e-6) -> np.ndarray:
+    """x / sqrt(mean(x^2) + eps) over the last axis, times an optional per-element weight."""
+    x = np.asarray(x, dtype=F64)
+    y = x / np.sqrt((x ** 2).mean(axis=-1, keepdims=True) + eps)
+    if weight is not None:
+        y = y * np.asarray(weight, dtype=F64)
+    return y
+
+
+def rope_angles(pos_ids: np.ndarray, axes_dims, theta: float = 10000.0) -> np.ndarray:
+    """Rotation angles of every token: pos_ids [n, n_axes] (integers or floats), axes_dims
+    the even number of head-dimension elements given to each axis (their sum is the head
+    dimension).  Pair j of an axis of dimension a turns by pos * theta^(-2j/a); the axes'
+    pairs follow each other.  Returns [n, head_dim/2]."""
+    pos = np.asarray(pos_ids, dtype=F64)
+    out = []
+    for ax, a in enumerate(axes_dims):
+        if a % 2:
+            raise ValueError("an axis owns whole pairs")
+        j = np.arange(a // 2, dtype=F64)
+        freq = theta ** (-2.0 * j / a)
+        out.append(pos[:, ax:ax + 1] * freq[None, :])
+    return np.concatenate(out, axis=1)
+
+
+def rope_apply(x: np.ndarray, angles: np.ndarray) -> np.ndarray:
+    """x [n, heads, d]; pair (x[2j], x[2j+1]) of every head is turned by angles[n, j]:
+    (a, b) -> (a cos - b sin, a sin + b cos)."""
+    x = np.asarray(x, dtype=F64)
+    ang = np.asarray(angles, dtype=F64)
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    a, b = x[..., 0::2], x[..., 1::2]
+    y = np.empty_like(x)
+    y[..., 0::2] = a * c - b * s
+    y[..., 1::2] = a * s + b * c
+    return y
+
+
 def attention_kvcache(q, k_fresh, v_fresh, k_cache=None, v_cache=None, cache_index=None, scale=None):
     """Eq.6.  q, k_fresh, v_fresh: [n_q, heads, d]; caches: [n_c, heads, d].
     Keys/values = the fresh rows followed by the cache rows in use (`cache_index`, or all
@@ -225,7 +267,7 @@ def _rows_by_stream(n_rows: int, n_txt_rows: int, n_streams: int):
 
 
 def block_forward(streams, kind: str, h, n_txt_rows: int, slot_index, k_cache, v_cache, flags: int, heads: int,
-                  return_qkv: bool = False):
+                  return_qkv: bool = False, rope=None):
     """One transformer block Phi-layer on the fresh rows `h` [n, H] (Algorithm 1's
     Phi(tokens, C_KV, f) for one layer).
 
@@ -235,6 +277,10 @@ def block_forward(streams, kind: str, h, n_txt_rows: int, slot_index, k_cache, v
     flags: FLAG_STORE -> plain attention over the fresh rows, then their K,V are written
     to the cache rows slot_index (cache arrays are modified in place);
     FLAG_RETRIEVE -> Eq.6 with the cache rows that are not refreshed; 0 -> plain attention.
+    Extras: a stream's "q_norm" / "k_norm" [d] switch on the RMS normalisation of its queries /
+    keys; `rope` [n_all, d/2] holds the angles of every position of the cached sequence and
+    fresh row i takes row slot_index[i] (row i when slot_index is None).  Keys enter the cache
+    normalised and rotated.
     """
     if flags == (FLAG_STORE | FLAG_RETRIEVE):
         raise ValueError("store and retrieve together are not a mode of Algorithm 1")
@@ -256,6 +302,15 @@ def block_forward(streams, kind: str, h, n_txt_rows: int, slot_index, k_cache, v
             m_act[s] = gelu_tanh(y[:, 3 * hidden:])
         q[rows], k[rows], v[rows] = qkv[:, :hidden], qkv[:, hidden:2 * hidden], qkv[:, 2 * hidden:]
     q3, k3, v3 = (x.reshape(n, heads, d) for x in (q, k, v))
+    for w, rows in zip(streams, groups):
+        if w.get("q_norm") is not None:
+            q3[rows] = rms_norm(q3[rows], w["q_norm"])
+        if w.get("k_norm") is not None:
+            k3[rows] = rms_norm(k3[rows], w["k_norm"])
+    if rope is not None:
+        own = np.arange(n) if slot_index is None else np.asarray(slot_index, dtype=np.int64)
+        ang = np.asarray(rope, dtype=F64)[own]
+        q3, k3 = rope_apply(q3, ang), rope_apply(k3, ang)
     if flags == FLAG_RETRIEVE:
         n_all = k_cache.shape[0]
         fresh = np.zeros(n_all, dtype=bool)
