@@ -146,6 +146,8 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="time the steps without the per-kernel event pairs")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device copy three times (calibration of the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--block-extras", action="store_true",
+                    help="time the step with query/key normalisation and rotary embedding in the block (no CPU baseline)")
     ap.add_argument("--loop", action="store_true",
                     help="instead of the step benchmark: time the whole sampling loop (Algorithm 1, 28 steps) of a 3072-wide editor with "
                          "19 double- and 38 single-stream blocks against 28 plain full steps, and print one JSON line about it")
@@ -171,6 +173,10 @@ def main():
         print(json.dumps(loop_benchmark(*[int(v) for v in args.loop_blocks.split(",")])))
         return
     cfg = step.CONFIG_BLOCK
+    if args.block_extras:   # not the headline workload: the same step with the block's query/key extras switched on
+        import dataclasses
+        cfg = dataclasses.replace(cfg, extras=True, name=cfg.name + "; block extras on: query/key RMS normalisation and rotary embedding")
+        args.no_cpu_baseline = True
     wl = step.RegionStepWorkload(cfg)
     for _ in range(args.warmup):
         n = wl.step()

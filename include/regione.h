@@ -64,7 +64,10 @@ typedef struct regione_dims {
  * Double-stream block: w_qkv [3H,H], w_o [H,H], w_1 [M,H], w_2 [H,M].
  * Single-stream block: w_1 [3H+M,H] producing [q|k|v|m], w_2 [H,H+M] applied to
  * [attention | gelu(m)]; w_qkv, w_o and the *2 modulation vectors are ignored.
- * Modulation vectors [H] may be NULL (shift = scale = 0, gate = 1). */
+ * Modulation vectors [H] may be NULL (shift = scale = 0, gate = 1).
+ * q_norm / k_norm [head_dim] float32, 16-byte aligned, or NULL: when given, every head of the
+ * stream's queries / keys is divided by sqrt(mean(x^2) + 1e-6) and multiplied by the vector
+ * (an extra of real editing transformers; the paper keeps the DiT a black box). */
 typedef struct regione_stream_weights {
     const void* w_qkv; const float* b_qkv;
     const void* w_o;   const float* b_o;
@@ -72,11 +75,19 @@ typedef struct regione_stream_weights {
     const void* w_2;   const float* b_2;
     const float* shift1; const float* scale1; const float* gate1;
     const float* shift2; const float* scale2; const float* gate2;
+    const float* q_norm; const float* k_norm;
 } regione_stream_weights;
 
+/* rope: NULL, or the table written by regione_rope_table for ALL rope_rows positions of the
+ * cached sequence [P | X | I].  Queries and keys of fresh row i are then rotated (after the
+ * normalisation) by the angles of position slot_index[i] + slot_offset (of position i when
+ * slot_index is NULL): a gathered token keeps the position it has in the full sequence, and
+ * keys enter the cache rotated.  Positions outside [0, rope_rows) use the nearest table row. */
 typedef struct regione_block_weights {
     regione_stream_weights txt; /* text rows of a double-stream block */
     regione_stream_weights img; /* image / reference rows; the only set of a single-stream block */
+    const float* rope;
+    int32_t rope_rows;
 } regione_block_weights;
 
 /* State of the adaptive velocity decay cache between steps (host). */
@@ -200,6 +211,16 @@ int regione_block_forward(regione_ctx* ctx, const regione_block_weights* w, int3
                           const void* h_in, void* h_out, int32_t h_dtype,
                           int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
                           void* k_cache, void* v_cache, int32_t n_all, int32_t flags);
+
+/* Rotary position embedding table (an extra of real editing transformers, not described by
+ * the paper): pos_ids [n, n_axes] int32 on the device, axes_dims [n_axes] on the HOST, the even
+ * number of head-dimension elements each axis owns (their sum is the context's head_dim, at most
+ * 8 axes).  Pair j of an axis that owns a elements turns by pos * theta^(-2j/a); the pairs of
+ * the axes follow each other, and pair j of a head is elements (2j, 2j+1).
+ * table [n, head_dim] float32: cos of the head_dim/2 angles, then their sin (angles in float64,
+ * rounded once). */
+int regione_rope_table(regione_ctx* ctx, const int32_t* pos_ids, int64_t n, int32_t n_axes,
+                       const int32_t* axes_dims_host, float theta, float* table);
 
 /* dst[i] = src[i] converted between the storage types (to bf16: round to nearest even).  Lets a
  * caller keep the latents of the sampling loop in float32 and feed bf16 rows to the token

@@ -25,7 +25,7 @@ EXPORTS = (
     "regione_scatter", "regione_attn_kvcache", "regione_linear", "regione_block_forward",
     "regione_velocity_decision_host", "regione_velocity_cache", "regione_profile_enable", "regione_profile_read",
     "regione_packed_weight_elems", "regione_pack_weight", "regione_tune_gemm", "regione_tune_attention",
-    "regione_layernorm", "regione_stage_plan_host", "regione_cast", "regione_mask_cleanup",
+    "regione_layernorm", "regione_stage_plan_host", "regione_cast", "regione_mask_cleanup", "regione_rope_table",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -37,7 +37,7 @@ class Dims(C.Structure):
 
 
 _STREAM_FIELDS = ("w_qkv", "b_qkv", "w_o", "b_o", "w_1", "b_1", "w_2", "b_2",
-                  "shift1", "scale1", "gate1", "shift2", "scale2", "gate2")
+                  "shift1", "scale1", "gate1", "shift2", "scale2", "gate2", "q_norm", "k_norm")
 
 
 class StreamWeights(C.Structure):
@@ -45,7 +45,7 @@ class StreamWeights(C.Structure):
 
 
 class BlockWeights(C.Structure):
-    _fields_ = [("txt", StreamWeights), ("img", StreamWeights)]
+    _fields_ = [("txt", StreamWeights), ("img", StreamWeights), ("rope", C.c_void_p), ("rope_rows", C.c_int32)]
 
 
 class AvdState(C.Structure):
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
             "regione_tune_attention": [vp, i32],
             "regione_layernorm": [vp, vp, i32, i32, i32, vp, vp, vp],
             "regione_cast": [vp, vp, i32, vp, i32, i64],
+            "regione_rope_table": [vp, vp, i64, i32, C.POINTER(i32), f32, vp],
             "regione_mask_cleanup": [vp, vp, i32, i32, i32, vp, vp, vp, vp, C.POINTER(i32)],
             "regione_stage_plan_host": [i32, i32, i32, C.POINTER(i32), i32, C.POINTER(PlanStep), i32, C.POINTER(i32)],
             "regione_profile_enable": [vp, i32],
@@ -203,6 +204,12 @@ def regione_velocity_decision_host(t, gamma, n_steps, delta, j, state: AvdState)
 def regione_velocity_cache(ctx, reuse, factor, dt, v_fresh, c_a, v_out, x_e, n_dev, n_max, c, dtype):
     _check(lib().regione_velocity_cache(ctx.handle, int(bool(reuse)), factor, dt, _p(v_fresh), _p(c_a), _p(v_out), _p(x_e),
                                         _p(n_dev), n_max, c, dtype))
+
+
+def regione_rope_table(ctx, pos_ids, n, axes_dims, theta, table):
+    """pos_ids: CUDA int32 [n, len(axes_dims)]; table: CUDA float32 [n, sum(axes_dims)] (cos | sin)."""
+    dims = (C.c_int32 * len(axes_dims))(*axes_dims)
+    _check(lib().regione_rope_table(ctx.handle, _p(pos_ids), n, len(axes_dims), dims, theta, _p(table)))
 
 
 def regione_cast(ctx, src, src_dtype, dst, dst_dtype, n_elems):

@@ -219,6 +219,7 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
         if (n_fresh > 0 && !slot_index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: a flag is set but slot_index is null");
         if ((flags & REGIONE_FLAG_STORE) && n_fresh != n_all) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "block_forward: a storing forward carries every row (n_fresh=%d, n_all=%d)", n_fresh, n_all);
     }
+    if (w->rope && w->rope_rows < (flags ? n_all : n_fresh)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "block_forward: rotation table of %d rows for %d positions", w->rope_rows, flags ? n_all : n_fresh);
     const bool dbl = block_type == REGIONE_BLOCK_DOUBLE;
     const int n_txt = dbl ? n_txt_fresh : 0;
     int rc;
@@ -256,6 +257,10 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
             ep.y = ctx->a + static_cast<size_t>(g.r0) * lda_attn; ep.ldy = lda_attn; ep.y_col0 = H;
             rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_1), g.n, 3 * H + M, H, ep);
         }
+        if (rc != REGIONE_OK) return rc;
+        // extras: normalised and rotated queries and keys, in place where the projection wrote them
+        rc = rg_qk_norm_rope(ctx, ep.q, H, ep.k, H, ep.slot, slot_index ? slot_index + g.r0 : nullptr, g.r0, slot_offset, g.n, heads, D,
+                             g.w->q_norm, g.w->k_norm, w->rope, w->rope_rows);
         if (rc != REGIONE_OK) return rc;
     }
 

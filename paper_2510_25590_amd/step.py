@@ -37,6 +37,7 @@ class StepConfig:
     eta: float = 0.9
     dt: float = 1.0 / 28.0
     seed: int = 2000
+    extras: bool = False      # query/key RMS normalisation and rotary embedding (positions: text (0,0,0), image (0,y,x), reference (1,y,x))
 
 
 CONFIG_TINY = StepConfig(name="tiny: hidden 256, 4x64 heads, MLP 1024, 16x16 image + 256 reference + 32 text tokens, 6x6 rectangle edited",
@@ -65,6 +66,10 @@ def host_inputs(cfg: StepConfig):
     streams = [inputs.stream_weights(rng, cfg.hidden, cfg.mlp, cfg.kind, "bf16") for _ in range(n_streams)]
     w_head = inputs.bf16_round((0.02 * rng.standard_normal((cfg.channels, cfg.hidden))).astype(np.float32))
     b_head = (0.02 * rng.standard_normal(cfg.channels)).astype(np.float32)
+    if cfg.extras:   # drawn last, so the other arrays are those of the plain workload
+        for w in streams:
+            w["q_norm"] = (1.0 + 0.1 * rng.standard_normal(cfg.head_dim)).astype(np.float32)
+            w["k_norm"] = (1.0 + 0.1 * rng.standard_normal(cfg.head_dim)).astype(np.float32)
     return dict(want=want, x_t=x_t, v_prev=v_prev, x_ref=x_ref, h_store=h_store, h_now=h_now, streams=streams,
                 w_head=w_head, b_head=b_head)
 
@@ -89,6 +94,15 @@ class RegionStepWorkload:
             t = {k: (rg.pack_weight(self.ctx, bf(a)) if k.startswith("w_") else f32(a)) for k, a in w.items()}
             self._keep.append(t)
             setattr(self.weights, name, rg.make_stream_weights(t))
+        if cfg.extras:
+            d = cfg.head_dim
+            axes = [d // 8, 7 * d // 16, 7 * d // 16]
+            yy, xx = np.meshgrid(np.arange(cfg.grid), np.arange(cfg.grid), indexing="ij")
+            pos = [np.zeros((cfg.n_txt, 3), dtype=np.int32)]
+            pos += [np.stack([np.full(n_img, img), yy.ravel(), xx.ravel()], axis=1).astype(np.int32) for img in (0, 1)]
+            self.rope_table = torch.empty((self.n_all, d), dtype=torch.float32, device="cuda")
+            rg.regione_rope_table(self.ctx, torch.from_numpy(np.concatenate(pos, axis=0)).cuda(), self.n_all, axes, 10000.0, self.rope_table)
+            self.weights.rope, self.weights.rope_rows = self.rope_table.data_ptr(), self.n_all
         self.block_type = rg.BLOCK_DOUBLE if cfg.kind == "double" else rg.BLOCK_SINGLE
         self.w_head, self.b_head = rg.pack_weight(self.ctx, bf(hst["w_head"])), f32(hst["b_head"])
         dev = "cuda"
