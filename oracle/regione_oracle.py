@@ -25,7 +25,9 @@ LayerNorm -> MLP with tanh-GELU -> gated residual.  Linear weights are [out, in]
 Optional extras of real editing models, equally outside the paper (pinned by their
 mathematics in tests/test_oracle_rope_norm.py): RMS normalisation of queries and keys
 over the head dimension, and rotary position embedding whose angles belong to a token's
-position in the FULL sequence, so a gathered token keeps its own.
+position in the FULL sequence, so a gathered token keeps its own; and the per-step
+conditioning path that yields a block's modulation vectors (sinusoidal embedding of the
+time, vector-times-matrix layers with SiLU), pinned in tests/test_oracle_modulation.py.
 """
 from __future__ import annotations
 
@@ -224,6 +226,35 @@ def rope_apply(x: np.ndarray, angles: np.ndarray) -> np.ndarray:
     y[..., 0::2] = a * c - b * s
     y[..., 1::2] = a * s + b * c
     return y
+
+
+def silu(x: np.ndarray) -> np.ndarray:
+    x = np.asarray(x, dtype=F64)
+    return x / (1.0 + np.exp(-x))
+
+
+def vec_linear(x, w, b=None, pre_act: str = "none") -> np.ndarray:
+    """y = W act(x) + b for ONE vector x [k], W [n, k]: the shape of a block's modulation
+    (shift, scale, gate vectors) computed from a conditioning embedding, act = SiLU there."""
+    x = np.asarray(x, dtype=F64)
+    if pre_act == "silu":
+        x = silu(x)
+    elif pre_act != "none":
+        raise ValueError(pre_act)
+    y = np.asarray(w, dtype=F64) @ x
+    if b is not None:
+        y = y + np.asarray(b, dtype=F64)
+    return y
+
+
+def timestep_embedding(t: float, dim: int, max_period: float = 10000.0) -> np.ndarray:
+    """Sinusoidal embedding of a scalar: [cos(t f_j) for j < dim/2] then [sin(t f_j)],
+    f_j = max_period^(-j / (dim/2))."""
+    if dim % 2:
+        raise ValueError("dim must be even")
+    half = dim // 2
+    f = max_period ** (-np.arange(half, dtype=F64) / half)
+    return np.concatenate([np.cos(t * f), np.sin(t * f)])
 
 
 def attention_kvcache(q, k_fresh, v_fresh, k_cache=None, v_cache=None, cache_index=None, scale=None):
