@@ -94,6 +94,22 @@ def membound(torch, rg):
         ms = rg.regione_profile_read(ctx)["rows"][0] / reps
         nb = n_h * (2 * hidden * 2 + 4)
         res[name] = {"rows": n_h, "row_bytes": 2 * hidden, "ms": ms, "GB/s": nb / ms / 1e6, "frac_hbm": nb / ms / 1e6 / PEAK_HBM_GBS}
+    del src, dst
+    # modulation vectors of 64 double-stream blocks (two streams each) from one conditioning vector: 128 matrices
+    # [6H, H] of bf16, 14.5 GB in all, each read once
+    n_mod, n_mats = 6 * hidden, 128
+    mats = torch.empty((n_mats, n_mod, hidden), dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    emb = torch.randn(hidden, generator=g, device="cuda", dtype=torch.float32)
+    bias = torch.zeros(n_mod, dtype=torch.float32, device="cuda")
+    y = torch.empty((n_mats, n_mod), dtype=torch.float32, device="cuda")
+    bias_all = torch.zeros(n_mats * n_mod, dtype=torch.float32, device="cuda")
+    nb = n_mats * (n_mod * hidden * 2 + n_mod * 8) + hidden * 4
+    for name, run in (("modulation_vec_linear", lambda: rg.regione_vec_linear(ctx, emb, rg.ACT_SILU, mats, bias_all, n_mats * n_mod, hidden, y)),
+                      ("modulation_vec_linear_per_block", lambda: [rg.regione_vec_linear(ctx, emb, rg.ACT_SILU, mats[i], bias, n_mod, hidden, y[i]) for i in range(n_mats)])):
+        run(); rg.regione_profile_read(ctx)
+        run()
+        ms = rg.regione_profile_read(ctx)["gemm"][0]
+        res[name] = {"matrices": n_mats, "rows": n_mod, "cols": hidden, "ms": ms, "GB/s": nb / ms / 1e6, "frac_hbm": nb / ms / 1e6 / PEAK_HBM_GBS}
     ctx.close()
     return res
 

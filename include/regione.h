@@ -46,7 +46,7 @@ enum { REGIONE_BF16 = 0, REGIONE_FP32 = 1 };
 enum { REGIONE_BLOCK_DOUBLE = 0, REGIONE_BLOCK_SINGLE = 1 };
 /* The flag pair f = (store, retrieve) of Algorithm 1. */
 enum { REGIONE_FLAG_STORE = 1, REGIONE_FLAG_RETRIEVE = 2 };
-enum { REGIONE_ACT_NONE = 0, REGIONE_ACT_GELU_TANH = 1 };
+enum { REGIONE_ACT_NONE = 0, REGIONE_ACT_GELU_TANH = 1, REGIONE_ACT_SILU = 2 };
 
 typedef struct regione_ctx regione_ctx;
 
@@ -221,6 +221,19 @@ int regione_block_forward(regione_ctx* ctx, const regione_block_weights* w, int3
  * rounded once). */
 int regione_rope_table(regione_ctx* ctx, const int32_t* pos_ids, int64_t n, int32_t n_axes,
                        const int32_t* axes_dims_host, float theta, float* table);
+
+/* y = W act(x) + b for ONE vector: the shape of a block's modulation (its shift, scale and gate
+ * vectors), which real editing transformers compute once per step from a conditioning embedding
+ * (the paper keeps this inside its black-box DiT; the block itself takes the vectors as given).
+ *   x [k] float32; pre_act REGIONE_ACT_NONE or REGIONE_ACT_SILU, applied to x;
+ *   w [n, k] bf16 ROW-MAJOR (not packed), 16-byte aligned; b_opt [n] float32 or NULL; y [n] float32.
+ * k: a multiple of 8, at most 16384.  Products in float32.  Bound by reading w once from HBM. */
+int regione_vec_linear(regione_ctx* ctx, const float* x, int32_t pre_act, const void* w, const float* b_opt,
+                       int32_t n, int32_t k, float* y);
+
+/* Sinusoidal embedding of a scalar (host value t): out[j] = cos(t f_j), out[dim/2 + j] = sin(t f_j),
+ * f_j = max_period^(-j / (dim/2)), j < dim/2; formed in float64, stored float32 on the device. */
+int regione_timestep_embedding(regione_ctx* ctx, double t, int32_t dim, double max_period, float* out);
 
 /* dst[i] = src[i] converted between the storage types (to bf16: round to nearest even).  Lets a
  * caller keep the latents of the sampling loop in float32 and feed bf16 rows to the token

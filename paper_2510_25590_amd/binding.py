@@ -18,7 +18,7 @@ ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2
 BF16, FP32 = 0, 1
 BLOCK_DOUBLE, BLOCK_SINGLE = 0, 1
 FLAG_STORE, FLAG_RETRIEVE = 1, 2
-ACT_NONE, ACT_GELU_TANH = 0, 1
+ACT_NONE, ACT_GELU_TANH, ACT_SILU = 0, 1, 2
 
 EXPORTS = (
     "regione_last_error", "regione_create", "regione_destroy", "regione_partition", "regione_gather",
@@ -26,6 +26,7 @@ EXPORTS = (
     "regione_velocity_decision_host", "regione_velocity_cache", "regione_profile_enable", "regione_profile_read",
     "regione_packed_weight_elems", "regione_pack_weight", "regione_tune_gemm", "regione_tune_attention",
     "regione_layernorm", "regione_stage_plan_host", "regione_cast", "regione_mask_cleanup", "regione_rope_table",
+    "regione_vec_linear", "regione_timestep_embedding",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -91,6 +92,8 @@ def lib() -> C.CDLL:
             "regione_layernorm": [vp, vp, i32, i32, i32, vp, vp, vp],
             "regione_cast": [vp, vp, i32, vp, i32, i64],
             "regione_rope_table": [vp, vp, i64, i32, C.POINTER(i32), f32, vp],
+            "regione_vec_linear": [vp, vp, i32, vp, vp, i32, i32, vp],
+            "regione_timestep_embedding": [vp, C.c_double, i32, C.c_double, vp],
             "regione_mask_cleanup": [vp, vp, i32, i32, i32, vp, vp, vp, vp, C.POINTER(i32)],
             "regione_stage_plan_host": [i32, i32, i32, C.POINTER(i32), i32, C.POINTER(PlanStep), i32, C.POINTER(i32)],
             "regione_profile_enable": [vp, i32],
@@ -210,6 +213,14 @@ def regione_rope_table(ctx, pos_ids, n, axes_dims, theta, table):
     """pos_ids: CUDA int32 [n, len(axes_dims)]; table: CUDA float32 [n, sum(axes_dims)] (cos | sin)."""
     dims = (C.c_int32 * len(axes_dims))(*axes_dims)
     _check(lib().regione_rope_table(ctx.handle, _p(pos_ids), n, len(axes_dims), dims, theta, _p(table)))
+
+
+def regione_vec_linear(ctx, x, pre_act, w, b, n, k, y):
+    _check(lib().regione_vec_linear(ctx.handle, _p(x), pre_act, _p(w), _p(b), n, k, _p(y)))
+
+
+def regione_timestep_embedding(ctx, t, dim, max_period, out):
+    _check(lib().regione_timestep_embedding(ctx.handle, float(t), dim, float(max_period), _p(out)))
 
 
 def regione_cast(ctx, src, src_dtype, dst, dst_dtype, n_elems):

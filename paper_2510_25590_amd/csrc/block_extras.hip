@@ -145,3 +145,108 @@ extern "C" int regione_rope_table(regione_ctx* ctx, const int32_t* pos_ids, int6
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
 }
+
+// ---- conditioning path: a block's modulation vectors come from ONE conditioning vector per step (time embedding
+// through SiLU and a [6H, H] or [3H, H] matrix).  With a single input row there is nothing for the matrix cores to
+// reuse: the product is bound by reading the matrix once from HBM (2 bytes per multiply-add).
+namespace {
+
+constexpr int kVecRowsPerWave = 4;
+
+// y[r] = sum_c W[r, c] act(x[c]) + b[r].  act(x) is staged once per workgroup in LDS as float32; every wave owns
+// kVecRowsPerWave consecutive rows and streams them 16 bytes per lane and row, so four independent loads are in
+// flight per lane and iteration.
+template <int ACT>
+__global__ void __launch_bounds__(kThreads)
+vec_linear_kernel(const float* __restrict__ x, const bf16_t* __restrict__ w, const float* __restrict__ b, int n, int k, float* __restrict__ y) {
+    extern __shared__ __attribute__((aligned(16))) float xs[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row0 = (blockIdx.x * (kThreads / 64) + wave) * kVecRowsPerWave;
+    const bf16_t* wrow[kVecRowsPerWave];
+#pragma unroll
+    for (int r = 0; r < kVecRowsPerWave; ++r) {
+        const int row = row0 + r < n ? row0 + r : n - 1;       // rows past the end repeat the last one; never stored
+        wrow[r] = w + static_cast<int64_t>(row) * k;
+    }
+    // the first chunk of the matrix rows is requested before the vector is staged: it does not depend on it
+    int c0 = lane * 8;                                         // k is a multiple of 8: a lane's chunk is whole or absent
+    bf16x8 wv[kVecRowsPerWave] = {};
+    if (c0 < k) {
+#pragma unroll
+        for (int r = 0; r < kVecRowsPerWave; ++r) wv[r] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(wrow[r] + c0));
+    }
+    for (int c = threadIdx.x; c < k; c += kThreads) {
+        float v = x[c];
+        if (ACT == REGIONE_ACT_SILU) v = v / (1.0f + __expf(-v));
+        xs[c] = v;
+    }
+    __syncthreads();
+    float acc[kVecRowsPerWave] = {};
+    while (c0 < k) {
+        const int c1 = c0 + 64 * 8;
+        bf16x8 wn[kVecRowsPerWave] = {};
+        if (c1 < k) {                                          // the next chunk is in flight while this one is used
+#pragma unroll
+            for (int r = 0; r < kVecRowsPerWave; ++r) wn[r] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(wrow[r] + c1));
+        }
+        const f32x4 x0 = *reinterpret_cast<const f32x4*>(xs + c0), x1 = *reinterpret_cast<const f32x4*>(xs + c0 + 4);
+#pragma unroll
+        for (int r = 0; r < kVecRowsPerWave; ++r) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[r] += static_cast<float>(wv[r][e]) * x0[e];
+                acc[r] += static_cast<float>(wv[r][4 + e]) * x1[e];
+            }
+            wv[r] = wn[r];
+        }
+        c0 = c1;
+    }
+#pragma unroll
+    for (int r = 0; r < kVecRowsPerWave; ++r) {
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) acc[r] += __shfl_xor(acc[r], m, 64);
+        if (lane == 0 && row0 + r < n) y[row0 + r] = acc[r] + (b ? b[row0 + r] : 0.f);
+    }
+}
+
+// out[j] = cos(t f_j), out[dim/2 + j] = sin(t f_j), f_j = max_period^(-j / (dim/2)); formed in float64.
+__global__ void __launch_bounds__(kThreads)
+timestep_embedding_kernel(double t, int half, double max_period, float* __restrict__ out) {
+    const int j = blockIdx.x * kThreads + threadIdx.x;
+    if (j >= half) return;
+    const double f = pow(max_period, -static_cast<double>(j) / half);
+    out[j] = static_cast<float>(cos(t * f));
+    out[half + j] = static_cast<float>(sin(t * f));
+}
+
+}  // namespace
+
+extern "C" int regione_vec_linear(regione_ctx* ctx, const float* x, int32_t pre_act, const void* w, const float* b_opt,
+                                  int32_t n, int32_t k, float* y) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "vec_linear: null context");
+    if (n < 0 || k <= 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "vec_linear: n=%d k=%d", n, k);
+    if (pre_act != REGIONE_ACT_NONE && pre_act != REGIONE_ACT_SILU) RG_FAIL(REGIONE_ERR_INVALID_ARG, "vec_linear: activation %d (none or SiLU on the input)", pre_act);
+    if (k % 8 || k > 16384) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "vec_linear: k=%d must be a multiple of 8, at most 16384", k);
+    if (n == 0) return REGIONE_OK;
+    if (!x || !w || !y) RG_FAIL(REGIONE_ERR_INVALID_ARG, "vec_linear: null operand");
+    if (!rg_aligned16(w)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "vec_linear: the matrix must be 16-byte aligned");
+    ProfScope prof(ctx, REGIONE_PROF_GEMM);
+    const int rows_per_wg = (kThreads / 64) * kVecRowsPerWave;
+    const dim3 grid(static_cast<unsigned>((n + rows_per_wg - 1) / rows_per_wg));
+    const size_t lds = static_cast<size_t>(k) * sizeof(float);
+    const bf16_t* wb = static_cast<const bf16_t*>(w);
+    if (pre_act == REGIONE_ACT_SILU) hipLaunchKernelGGL(vec_linear_kernel<REGIONE_ACT_SILU>, grid, dim3(kThreads), lds, ctx->stream, x, wb, b_opt, n, k, y);
+    else hipLaunchKernelGGL(vec_linear_kernel<REGIONE_ACT_NONE>, grid, dim3(kThreads), lds, ctx->stream, x, wb, b_opt, n, k, y);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+extern "C" int regione_timestep_embedding(regione_ctx* ctx, double t, int32_t dim, double max_period, float* out) {
+    if (!ctx || !out) RG_FAIL(REGIONE_ERR_INVALID_ARG, "timestep_embedding: null context or output");
+    if (dim <= 0 || (dim & 1)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "timestep_embedding: dim=%d must be positive and even", dim);
+    if (!(max_period > 1.0)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "timestep_embedding: max_period=%g must exceed 1", max_period);
+    const int half = dim / 2;
+    hipLaunchKernelGGL(timestep_embedding_kernel, dim3((half + kThreads - 1) / kThreads), dim3(kThreads), 0, ctx->stream, t, half, max_period, out);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}

@@ -1,0 +1,77 @@
+"""GPU parity of the conditioning path (one-vector linear layer with SiLU, sinusoidal time
+embedding) against the float64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import regione_oracle as orc
+from paper_2510_25590_amd import binding as rg
+from paper_2510_25590_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = rg.Context(256, 4, 64, 1024, 64, 64)
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("n,k", [(18432, 3072), (9216 + 3, 3072), (50, 64), (7, 8), (1, 520), (33, 16384)])
+@pytest.mark.parametrize("act", ["silu", "none"])
+def test_vec_linear_matches_oracle(ctx, n, k, act):
+    rng = np.random.default_rng(4000 + n + k)
+    x = rng.standard_normal(k).astype(np.float32)
+    w = inputs.bf16_round((rng.standard_normal((n, k)) / np.sqrt(k)).astype(np.float32))
+    b = rng.standard_normal(n).astype(np.float32) if n % 2 else None
+    want = orc.vec_linear(x, w, b, act)
+    y = torch.full((n + 1,), 7.0, dtype=torch.float32, device="cuda")
+    rg.regione_vec_linear(ctx, torch.from_numpy(x).cuda(), rg.ACT_SILU if act == "silu" else rg.ACT_NONE,
+                          torch.from_numpy(w).to(torch.bfloat16).cuda(), None if b is None else torch.from_numpy(b).cuda(), n, k, y)
+    got = y.cpu().numpy()
+    assert got[n] == 7.0
+    # float32 products and sums of k terms of size ~1/sqrt(k): far inside 1e-5 for every k here
+    assert np.abs(got[:n] - want).max() <= 1e-5, np.abs(got[:n] - want).max()
+
+
+def test_vec_linear_argument_checks(ctx):
+    x = torch.zeros(16, device="cuda"); w = torch.zeros((4, 16), dtype=torch.bfloat16, device="cuda"); y = torch.zeros(4, device="cuda")
+    rg.regione_vec_linear(ctx, x, rg.ACT_NONE, w, None, 0, 16, y)          # no row: nothing happens
+    with pytest.raises(rg.RegionEError):
+        rg.regione_vec_linear(ctx, x, rg.ACT_GELU_TANH, w, None, 4, 16, y)  # not an input activation
+    with pytest.raises(rg.RegionEError):
+        rg.regione_vec_linear(ctx, x, rg.ACT_NONE, w, None, 4, 12, y)       # k not a multiple of 8
+    with pytest.raises(rg.RegionEError):
+        rg.regione_vec_linear(ctx, None, rg.ACT_NONE, w, None, 4, 16, y)
+
+
+@pytest.mark.parametrize("t,dim", [(0.0, 8), (0.731, 256), (999.0, 256), (28.0, 3072)])
+def test_timestep_embedding_matches_oracle(ctx, t, dim):
+    out = torch.full((dim + 1,), 5.0, dtype=torch.float32, device="cuda")
+    rg.regione_timestep_embedding(ctx, t, dim, 10000.0, out)
+    got = out.cpu().numpy()
+    assert got[dim] == 5.0
+    assert np.abs(got[:dim] - orc.timestep_embedding(t, dim, 10000.0)).max() <= 1e-7
+    with pytest.raises(rg.RegionEError):
+        rg.regione_timestep_embedding(ctx, t, 7, 10000.0, out)
+
+
+def test_modulation_vectors_feed_a_block(ctx):
+    """Time -> embedding -> two layers -> SiLU -> [6H, H] matrix: the six vectors the block takes, against the oracle."""
+    hidden = 256
+    rng = np.random.default_rng(4100)
+    w1 = inputs.bf16_round((rng.standard_normal((hidden, 256)) / 16).astype(np.float32))
+    w2 = inputs.bf16_round((rng.standard_normal((hidden, hidden)) / 16).astype(np.float32))
+    wm = inputs.bf16_round((rng.standard_normal((6 * hidden, hidden)) / 16).astype(np.float32))
+    bm = rng.standard_normal(6 * hidden).astype(np.float32)
+    e = orc.timestep_embedding(0.4375, 256)
+    want = orc.vec_linear(orc.vec_linear(orc.vec_linear(e, w1), w2, None, "silu"), wm, bm, "silu")
+    d = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    emb = torch.empty(256, device="cuda"); h1 = torch.empty(hidden, device="cuda"); h2 = torch.empty(hidden, device="cuda")
+    mod = torch.empty(6 * hidden, device="cuda")
+    rg.regione_timestep_embedding(ctx, 0.4375, 256, 10000.0, emb)
+    rg.regione_vec_linear(ctx, emb, rg.ACT_NONE, d(w1), None, hidden, 256, h1)
+    rg.regione_vec_linear(ctx, h1, rg.ACT_SILU, d(w2), None, hidden, hidden, h2)
+    rg.regione_vec_linear(ctx, h2, rg.ACT_SILU, d(wm), torch.from_numpy(bm).cuda(), 6 * hidden, hidden, mod)
+    assert np.abs(mod.cpu().numpy() - want).max() <= 2e-5
