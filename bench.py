@@ -114,6 +114,55 @@ def membound(torch, rg):
     return res
 
 
+def cfg_benchmark(steps: int, warmup: int):
+    """The block of the headline workload for the TWO branches of classifier-free guidance (the paper's experiments
+    run both at every step): one batched call against two single calls.  Same 820 edited rows and 8704 cache rows
+    per branch; the second branch has its own hidden state and cache."""
+    import torch
+    from paper_2510_25590_amd import binding as rg
+    from paper_2510_25590_amd import step
+    import dataclasses
+    cfg = step.CONFIG_BLOCK
+    wl = step.RegionStepWorkload(cfg)
+    n = wl.step()
+    torch.cuda.synchronize()
+    ctx2 = rg.Context(cfg.hidden, cfg.heads, cfg.head_dim, cfg.mlp, 2 * wl.n_img, 16)
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    h_e = torch.stack([wl.h_e[:n], (wl.h_e[:n].float() + 0.05 * torch.randn((n, cfg.hidden), generator=g, device="cuda")).to(torch.bfloat16)]).contiguous()
+    kc = torch.stack([wl.k_cache, wl.k_cache.flip(0)]).contiguous(); vc = torch.stack([wl.v_cache, wl.v_cache.flip(0)]).contiguous()
+    out = torch.empty_like(h_e)
+    e_index = wl.e_index[:n].contiguous()
+
+    def two_calls():
+        for b in range(2):
+            rg.regione_block_forward(ctx2, wl.weights, wl.block_type, h_e[b], out[b], rg.BF16, n, 0, e_index, cfg.n_txt, kc[b], vc[b], wl.n_all, rg.FLAG_RETRIEVE)
+
+    def batched():
+        rg.regione_block_forward_batched(ctx2, wl.weights, wl.block_type, h_e, out, rg.BF16, 2, n, 0, e_index, cfg.n_txt, kc, vc, wl.n_all, rg.FLAG_RETRIEVE)
+
+    res = {}
+    for name, fn in (("two_calls", two_calls), ("batched", batched)):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        rg.regione_profile_enable(ctx2, True); rg.regione_profile_read(ctx2)
+        for _ in range(steps):
+            fn()
+        prof = rg.regione_profile_read(ctx2)
+        rg.regione_profile_enable(ctx2, False)
+        res[name] = {"ms_per_block": ms, "tokens_per_s": 2 * n / (ms * 1e-3),
+                     "kernels_ms": {k: v[0] / steps for k, v in prof.items() if v[0] > 0}}
+    return {"metric": "edited-token DiT block tokens/s, two guidance branches", "value": res["batched"]["tokens_per_s"], "unit": "tokens/s",
+            "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": res["batched"]["ms_per_block"], "higher_is_better": True,
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": cfg.name + "; block only, two branches", "n_edited_per_branch": n}, "detail": res}
+
+
 def loop_benchmark(n_double: int, n_single: int):
     """Whole sampling loop on the device: the method's 28-step schedule (6 stabilization steps, forced step at k = 16,
     2 smooth steps, velocity-decay cache with delta = 0.04 on a linear schedule) against 28 plain full steps of the same
@@ -164,6 +213,8 @@ def main():
                     help="only run a plain 1 GiB device copy three times (calibration of the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--block-extras", action="store_true",
                     help="time the step with query/key normalisation and rotary embedding in the block (no CPU baseline)")
+    ap.add_argument("--cfg", action="store_true",
+                    help="time the block for the two branches of classifier-free guidance: one batched call against two calls")
     ap.add_argument("--loop", action="store_true",
                     help="instead of the step benchmark: time the whole sampling loop (Algorithm 1, 28 steps) of a 3072-wide editor with "
                          "19 double- and 38 single-stream blocks against 28 plain full steps, and print one JSON line about it")
@@ -185,6 +236,9 @@ def main():
     from paper_2510_25590_amd import step
 
     rg.lib()   # fails loudly if the HIP library has not been built
+    if args.cfg:
+        print(json.dumps(cfg_benchmark(args.steps, args.warmup)))
+        return
     if args.loop:
         print(json.dumps(loop_benchmark(*[int(v) for v in args.loop_blocks.split(",")])))
         return

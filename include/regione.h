@@ -222,6 +222,19 @@ int regione_block_forward(regione_ctx* ctx, const regione_block_weights* w, int3
 int regione_rope_table(regione_ctx* ctx, const int32_t* pos_ids, int64_t n, int32_t n_axes,
                        const int32_t* axes_dims_host, float theta, float* table);
 
+/* The same block for n_branches independent sequences that share weights, slot list and flags:
+ * the conditional and unconditional branch of classifier-free guidance, which the paper's
+ * experiments run at every step ("Experiment settings").  h_in / h_out are
+ * [n_branches, n_fresh, H], k_cache / v_cache [n_branches, n_all, heads, head_dim]; the result is
+ * that of n_branches regione_block_forward calls on the slices.  When no text row is fresh (or
+ * the block is single-stream) every projection runs once over all n_branches * n_fresh rows, so
+ * the weights are read once and the GEMMs get twice the rows; attention runs per branch.
+ * n_branches * n_fresh must fit the context's max_fresh. */
+int regione_block_forward_batched(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
+                                  const void* h_in, void* h_out, int32_t h_dtype, int32_t n_branches,
+                                  int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
+                                  void* k_cache, void* v_cache, int32_t n_all, int32_t flags);
+
 /* y = W act(x) + b for ONE vector: the shape of a block's modulation (its shift, scale and gate
  * vectors), which real editing transformers compute once per step from a conditioning embedding
  * (the paper keeps this inside its black-box DiT; the block itself takes the vectors as given).

@@ -26,7 +26,7 @@ EXPORTS = (
     "regione_velocity_decision_host", "regione_velocity_cache", "regione_profile_enable", "regione_profile_read",
     "regione_packed_weight_elems", "regione_pack_weight", "regione_tune_gemm", "regione_tune_attention",
     "regione_layernorm", "regione_stage_plan_host", "regione_cast", "regione_mask_cleanup", "regione_rope_table",
-    "regione_vec_linear", "regione_timestep_embedding",
+    "regione_vec_linear", "regione_timestep_embedding", "regione_block_forward_batched",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -83,6 +83,7 @@ def lib() -> C.CDLL:
             "regione_attn_kvcache": [vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, i32, i32, i32, f32, vp],
             "regione_linear": [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
             "regione_block_forward": [vp, C.POINTER(BlockWeights), i32, vp, vp, i32, i32, i32, vp, i32, vp, vp, i32, i32],
+            "regione_block_forward_batched": [vp, C.POINTER(BlockWeights), i32, vp, vp, i32, i32, i32, i32, vp, i32, vp, vp, i32, i32],
             "regione_velocity_decision_host": [C.POINTER(f32), C.POINTER(f32), i32, f32, i32, C.POINTER(AvdState),
                                                C.POINTER(i32), C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
@@ -193,6 +194,12 @@ def regione_block_forward(ctx, weights: BlockWeights, block_type, h_in, h_out, h
                           slot_index, slot_offset, k_cache, v_cache, n_all, flags):
     _check(lib().regione_block_forward(ctx.handle, C.byref(weights), block_type, _p(h_in), _p(h_out), h_dtype, n_fresh,
                                        n_txt_fresh, _p(slot_index), slot_offset, _p(k_cache), _p(v_cache), n_all, flags))
+
+
+def regione_block_forward_batched(ctx, weights: BlockWeights, block_type, h_in, h_out, h_dtype, n_branches, n_fresh, n_txt_fresh,
+                                  slot_index, slot_offset, k_cache, v_cache, n_all, flags):
+    _check(lib().regione_block_forward_batched(ctx.handle, C.byref(weights), block_type, _p(h_in), _p(h_out), h_dtype, n_branches, n_fresh,
+                                               n_txt_fresh, _p(slot_index), slot_offset, _p(k_cache), _p(v_cache), n_all, flags))
 
 
 def regione_velocity_decision_host(t, gamma, n_steps, delta, j, state: AvdState):

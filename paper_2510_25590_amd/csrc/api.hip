@@ -28,7 +28,7 @@ int dev_alloc(T** p, size_t count) {
     return REGIONE_OK;
 }
 void free_all(regione_ctx* c) {
-    void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->attn_part, c->gemm_part};
+    void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->slot_all, c->attn_part, c->gemm_part};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     if (c->n_edited_pinned) (void)hipHostFree(c->n_edited_pinned);
     if (c->prof_ev) {
@@ -67,6 +67,7 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
     if (rc == REGIONE_OK) rc = dev_alloc(&c->a, n * (H + M));
     if (rc == REGIONE_OK) rc = dev_alloc(&c->h1, n * H);
     if (rc == REGIONE_OK) rc = dev_alloc(&c->m, n * M);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->slot_all, n);
     if (rc == REGIONE_OK) rc = dev_alloc(reinterpret_cast<char**>(&c->attn_part), c->attn_part_bytes);
     c->gemm_part_bytes = n > 0 ? static_cast<size_t>(128) << 20 : 0;
     if (rc == REGIONE_OK) rc = dev_alloc(reinterpret_cast<char**>(&c->gemm_part), c->gemm_part_bytes);
@@ -202,17 +203,22 @@ int check_stream_weights(const regione_stream_weights& w, int block_type, const 
 
 }  // namespace
 
-extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
-                                     const void* h_in, void* h_out, int32_t h_dtype,
-                                     int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
-                                     void* k_cache, void* v_cache, int32_t n_all, int32_t flags) {
+// n_branches independent sequences (the conditional and unconditional branch of classifier-free guidance) through one
+// set of weights: rows [b*n_fresh, (b+1)*n_fresh) of h and cache rows [b*n_all, (b+1)*n_all) belong to branch b; slots
+// and positions are shared.  When no text row is fresh (or the block is single-stream) all branches' rows form ONE
+// row group, so every projection is one GEMM over n_branches*n_fresh rows; attention runs per branch.
+static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
+                              const void* h_in, void* h_out, int32_t h_dtype, int32_t n_branches,
+                              int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
+                              void* k_cache, void* v_cache, int32_t n_all, int32_t flags) {
     if (!ctx || !w) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: null context or weights");
+    if (n_branches < 1) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: %d branches", n_branches);
     if (block_type != REGIONE_BLOCK_DOUBLE && block_type != REGIONE_BLOCK_SINGLE) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: bad block type %d", block_type);
     if (h_dtype != REGIONE_BF16 && h_dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: bad h_dtype %d", h_dtype);
     if (flags & ~(REGIONE_FLAG_STORE | REGIONE_FLAG_RETRIEVE)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: unknown flag bits %d", flags);
     if (flags == (REGIONE_FLAG_STORE | REGIONE_FLAG_RETRIEVE)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: store and retrieve together are not a mode of the algorithm");
     if (n_fresh < 0 || n_txt_fresh < 0 || n_txt_fresh > n_fresh) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: n_fresh=%d n_txt_fresh=%d", n_fresh, n_txt_fresh);
-    if (n_fresh > ctx->dims.max_fresh) RG_FAIL(REGIONE_ERR_WORKSPACE, "block_forward: %d rows, context made for %d", n_fresh, ctx->dims.max_fresh);
+    if (static_cast<int64_t>(n_fresh) * n_branches > ctx->dims.max_fresh) RG_FAIL(REGIONE_ERR_WORKSPACE, "block_forward: %d rows in %d branch(es), context made for %d", n_fresh, n_branches, ctx->dims.max_fresh);
     if (flags) {
         if (n_all <= 0 || n_fresh > n_all) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "block_forward: n_fresh=%d n_all=%d", n_fresh, n_all);
         if (!k_cache || !v_cache) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: a flag is set but the cache is null");
@@ -231,11 +237,31 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
     const int H = ctx->dims.hidden, M = ctx->dims.mlp, heads = ctx->dims.heads, D = ctx->dims.head_dim;
     const int h_f32 = h_dtype == REGIONE_FP32;
     const size_t h_elem = h_f32 ? 4 : 2;
+    if (n_branches > 1 && n_txt > 0) {
+        // text and image rows alternate between the branches: one pass per branch
+        for (int b = 0; b < n_branches; ++b) {
+            const size_t hoff = static_cast<size_t>(b) * n_fresh * H * h_elem, coff = static_cast<size_t>(b) * n_all * H * sizeof(bf16_t);
+            rc = block_forward_impl(ctx, w, block_type, static_cast<const char*>(h_in) + hoff, static_cast<char*>(h_out) + hoff, h_dtype, 1,
+                                    n_fresh, n_txt_fresh, slot_index, slot_offset,
+                                    k_cache ? static_cast<char*>(k_cache) + coff : nullptr, v_cache ? static_cast<char*>(v_cache) + coff : nullptr, n_all, flags);
+            if (rc != REGIONE_OK) return rc;
+        }
+        return REGIONE_OK;
+    }
+    const int n_rows = n_fresh * n_branches;                       // rows of all branches, one group per stream
+    const int period = n_branches > 1 ? n_fresh : 0;
     const int lda_attn = dbl ? H : H + M;   // single-stream: attention output and gelu(m) share rows of ctx->a
     bf16_t* kc = static_cast<bf16_t*>(k_cache);
     bf16_t* vc = static_cast<bf16_t*>(v_cache);
     struct Rows { int r0, n; const regione_stream_weights* w; };
-    const Rows groups[2] = {{0, n_txt, &w->txt}, {n_txt, n_fresh - n_txt, &w->img}};
+    const Rows groups[2] = {{0, n_txt, &w->txt}, {n_txt, n_rows - n_txt, &w->img}};
+
+    // several branches: the projection's epilogue takes one slot per row, branch b's shifted by b * n_all cache rows
+    const int32_t* gemm_slots = slot_index;
+    if (flags && n_branches > 1) {
+        if ((rc = rg_expand_slots(ctx, slot_index, n_fresh, n_branches, n_all, ctx->slot_all)) != REGIONE_OK) return rc;
+        gemm_slots = ctx->slot_all;
+    }
 
     // ---- first half: LayerNorm + modulation, QKV (and MLP-in for single-stream) projection
     for (const Rows& g : groups) {
@@ -246,7 +272,7 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
         GemmEpilogue ep = {};
         ep.kind = EPI_QKV; ep.hidden = H;
         ep.q = ctx->q + static_cast<size_t>(g.r0) * H; ep.ldq = H;
-        if (flags) { ep.k = kc; ep.v = vc; ep.slot = slot_index + g.r0; ep.slot_offset = slot_offset; }
+        if (flags) { ep.k = kc; ep.v = vc; ep.slot = gemm_slots + g.r0; ep.slot_offset = slot_offset; }
         else { ep.k = ctx->kf + static_cast<size_t>(g.r0) * H; ep.v = ctx->vf + static_cast<size_t>(g.r0) * H; ep.slot = nullptr; }
         ep.ldkv = H;
         if (dbl) {
@@ -259,16 +285,19 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
         }
         if (rc != REGIONE_OK) return rc;
         // extras: normalised and rotated queries and keys, in place where the projection wrote them
-        rc = rg_qk_norm_rope(ctx, ep.q, H, ep.k, H, ep.slot, slot_index ? slot_index + g.r0 : nullptr, g.r0, slot_offset, g.n, heads, D,
+        rc = rg_qk_norm_rope(ctx, ep.q, H, ep.k, H, flags ? slot_index + g.r0 : nullptr, slot_index ? slot_index + g.r0 : nullptr, g.r0, slot_offset, period, n_all, g.n, heads, D,
                              g.w->q_norm, g.w->k_norm, w->rope, w->rope_rows);
         if (rc != REGIONE_OK) return rc;
     }
 
     // ---- attention (Eq.6).  With a flag set the fresh K,V already sit in their cache slots, so the
     // key list is the whole cached sequence; without a flag it is the fresh rows only.
-    if (flags) rc = rg_attention(ctx, ctx->q, H, n_fresh, nullptr, nullptr, H, 0, kc, vc, H, n_all, nullptr, heads, D, 0.f, ctx->a, lda_attn);
-    else rc = rg_attention(ctx, ctx->q, H, n_fresh, ctx->kf, ctx->vf, H, n_fresh, nullptr, nullptr, H, 0, nullptr, heads, D, 0.f, ctx->a, lda_attn);
-    if (rc != REGIONE_OK) return rc;
+    for (int b = 0; b < n_branches; ++b) {
+        const size_t r0 = static_cast<size_t>(b) * n_fresh, c0 = static_cast<size_t>(b) * n_all * H;
+        if (flags) rc = rg_attention(ctx, ctx->q + r0 * H, H, n_fresh, nullptr, nullptr, H, 0, kc + c0, vc + c0, H, n_all, nullptr, heads, D, 0.f, ctx->a + r0 * lda_attn, lda_attn);
+        else rc = rg_attention(ctx, ctx->q + r0 * H, H, n_fresh, ctx->kf + r0 * H, ctx->vf + r0 * H, H, n_fresh, nullptr, nullptr, H, 0, nullptr, heads, D, 0.f, ctx->a + r0 * lda_attn, lda_attn);
+        if (rc != REGIONE_OK) return rc;
+    }
 
     // ---- second half
     for (const Rows& g : groups) {
@@ -304,4 +333,18 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
         if ((rc = rg_gemm(ctx, m, M, static_cast<const bf16_t*>(g.w->w_2), g.n, H, M, dn)) != REGIONE_OK) return rc;
     }
     return REGIONE_OK;
+}
+
+extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
+                                     const void* h_in, void* h_out, int32_t h_dtype,
+                                     int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
+                                     void* k_cache, void* v_cache, int32_t n_all, int32_t flags) {
+    return block_forward_impl(ctx, w, block_type, h_in, h_out, h_dtype, 1, n_fresh, n_txt_fresh, slot_index, slot_offset, k_cache, v_cache, n_all, flags);
+}
+
+extern "C" int regione_block_forward_batched(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
+                                             const void* h_in, void* h_out, int32_t h_dtype, int32_t n_branches,
+                                             int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
+                                             void* k_cache, void* v_cache, int32_t n_all, int32_t flags) {
+    return block_forward_impl(ctx, w, block_type, h_in, h_out, h_dtype, n_branches, n_fresh, n_txt_fresh, slot_index, slot_offset, k_cache, v_cache, n_all, flags);
 }

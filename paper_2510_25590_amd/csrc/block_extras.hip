@@ -39,6 +39,7 @@ struct QkArgs {
     const int32_t* kv_slot;
     const int32_t* pos_slot; int pos0;  // table row of row i: pos_slot[i] + slot_offset, or pos0 + i
     int slot_offset;
+    int slot_period, slot_branch_rows;  // period > 0: rows [b*period, (b+1)*period) are branch b; its slots and positions repeat, its keys sit slot_branch_rows further
     int n, heads;
     const float* q_norm; const float* k_norm;   // [D] or null (no normalisation of that side)
     const float* table; int table_rows;         // [table_rows, D] or null (no rotation)
@@ -62,7 +63,8 @@ qk_norm_rope_kernel(QkArgs a) {
     bf16_t* p;
     if (which == 0) p = a.q + static_cast<int64_t>(row) * a.ldq + head * D + sub * 8;
     else {
-        const int64_t kv_row = a.kv_slot ? static_cast<int64_t>(a.kv_slot[row]) + a.slot_offset : row;
+        const int branch = a.slot_period > 0 ? row / a.slot_period : 0;
+        const int64_t kv_row = a.kv_slot ? static_cast<int64_t>(a.kv_slot[row - branch * a.slot_period]) + a.slot_offset + static_cast<int64_t>(branch) * a.slot_branch_rows : row;
         p = a.k + kv_row * a.ldkv + head * D + sub * 8;
     }
     const bf16x8 in = *reinterpret_cast<const bf16x8*>(p);
@@ -81,7 +83,8 @@ qk_norm_rope_kernel(QkArgs a) {
         for (int e = 0; e < 4; ++e) { x[e] *= rinv * w0[e]; x[4 + e] *= rinv * w1[e]; }
     }
     if (a.table) {
-        int64_t pos = a.pos_slot ? static_cast<int64_t>(a.pos_slot[row]) + a.slot_offset : a.pos0 + row;
+        const int local = a.slot_period > 0 ? row % a.slot_period : row;   // a branch's rows sit at the same positions
+        int64_t pos = a.pos_slot ? static_cast<int64_t>(a.pos_slot[local]) + a.slot_offset : a.pos0 + local;
         pos = pos < 0 ? 0 : (pos >= a.table_rows ? a.table_rows - 1 : pos);   // never read outside the table
         const float* t = a.table + pos * D + sub * 4;
         const f32x4 c = *reinterpret_cast<const f32x4*>(t), s = *reinterpret_cast<const f32x4*>(t + D / 2);
@@ -101,7 +104,7 @@ qk_norm_rope_kernel(QkArgs a) {
 }  // namespace
 
 int rg_qk_norm_rope(regione_ctx* ctx, bf16_t* q, int ldq, bf16_t* k, int ldkv, const int32_t* kv_slot,
-                    const int32_t* pos_slot, int pos0, int slot_offset, int n, int heads, int d,
+                    const int32_t* pos_slot, int pos0, int slot_offset, int slot_period, int slot_branch_rows, int n, int heads, int d,
                     const float* q_norm, const float* k_norm, const float* table, int table_rows) {
     if (n <= 0 || (!q_norm && !k_norm && !table)) return REGIONE_OK;
     if (d != 64 && d != 128) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "qk_norm_rope: head dimension %d (64 or 128 supported)", d);
@@ -110,7 +113,7 @@ int rg_qk_norm_rope(regione_ctx* ctx, bf16_t* q, int ldq, bf16_t* k, int ldkv, c
         RG_FAIL(REGIONE_ERR_INVALID_ARG, "qk_norm_rope: weights and table must be 16-byte aligned");
     if (table && table_rows <= 0) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "qk_norm_rope: a rotation table with %d rows", table_rows);
     ProfScope prof(ctx, REGIONE_PROF_LAYERNORM);
-    QkArgs a = {q, ldq, k, ldkv, kv_slot, pos_slot, pos0, slot_offset, n, heads, q_norm, k_norm, table, table_rows, 1e-6f};
+    QkArgs a = {q, ldq, k, ldkv, kv_slot, pos_slot, pos0, slot_offset, slot_period, slot_branch_rows, n, heads, q_norm, k_norm, table, table_rows, 1e-6f};
     const int64_t total = static_cast<int64_t>(n) * 2 * heads;
     if (d == 128) {
         const int64_t blocks = (total + kThreads / 16 - 1) / (kThreads / 16);
@@ -119,6 +122,25 @@ int rg_qk_norm_rope(regione_ctx* ctx, bf16_t* q, int ldq, bf16_t* k, int ldkv, c
         const int64_t blocks = (total + kThreads / 8 - 1) / (kThreads / 8);
         hipLaunchKernelGGL(qk_norm_rope_kernel<64>, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream, a);
     }
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+namespace {
+// out[b*n + i] = slot[i] + b * branch_rows: the slot list of every branch of a batched block call
+__global__ void __launch_bounds__(kThreads)
+expand_slots_kernel(const int32_t* __restrict__ slot, int n, int n_branches, int branch_rows, int32_t* __restrict__ out) {
+    const int gid = blockIdx.x * kThreads + threadIdx.x;
+    if (gid >= n * n_branches) return;
+    const int b = gid / n;
+    out[gid] = slot[gid - b * n] + b * branch_rows;
+}
+}  // namespace
+
+int rg_expand_slots(regione_ctx* ctx, const int32_t* slot, int n, int n_branches, int branch_rows, int32_t* out) {
+    if (n <= 0 || n_branches <= 0) return REGIONE_OK;
+    if (static_cast<int64_t>(n_branches) * branch_rows > INT32_MAX) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "block_forward: %d branches of %d cache rows exceed 32-bit row numbers", n_branches, branch_rows);
+    hipLaunchKernelGGL(expand_slots_kernel, dim3((n * n_branches + kThreads - 1) / kThreads), dim3(kThreads), 0, ctx->stream, slot, n, n_branches, branch_rows, out);
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
 }

@@ -26,6 +26,7 @@ struct regione_ctx {
     bf16_t* m;     // [max_fresh, M]     activated MLP hidden rows
     float* attn_part;  // split-KV partial results
     size_t attn_part_bytes;
+    int32_t* slot_all; // [max_fresh] slot list of all branches of a batched block call
     float* gemm_part;  // split-K partial sums
     size_t gemm_part_bytes;
     int gemm_force_tn, gemm_force_splits;  // 0 = chosen per call
@@ -87,8 +88,9 @@ struct GemmEpilogue {
 int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w_packed, int m, int n, int k, const GemmEpilogue& ep);
 int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, bf16_t* u);
 int rg_qk_norm_rope(regione_ctx* ctx, bf16_t* q, int ldq, bf16_t* k, int ldkv, const int32_t* kv_slot,
-                    const int32_t* pos_slot, int pos0, int slot_offset, int n, int heads, int d,
+                    const int32_t* pos_slot, int pos0, int slot_offset, int slot_period, int slot_branch_rows, int n, int heads, int d,
                     const float* q_norm, const float* k_norm, const float* table, int table_rows);
+int rg_expand_slots(regione_ctx* ctx, const int32_t* slot, int n, int n_branches, int branch_rows, int32_t* out);
 int rg_attention(regione_ctx* ctx, const bf16_t* q, int ldq, int n_q,
                  const bf16_t* k0, const bf16_t* v0, int ldkv0, int n0,
                  const bf16_t* k1, const bf16_t* v1, int ldkv1, int n1, const int32_t* idx1,

@@ -1,0 +1,84 @@
+"""GPU parity of the batched block call (the two branches of classifier-free guidance through one set of
+weights) against the float64 oracle run once per branch."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import regione_oracle as orc
+from paper_2510_25590_amd import binding as rg
+from paper_2510_25590_amd import inputs
+from gpu_util import dev, host, assert_close, block_to_device
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("kind", ["double", "single"])
+@pytest.mark.parametrize("extras", [False, True])
+def test_batched_block_all_modes(kind, extras):
+    hidden, heads, d, mlp = 256, 4, 64, 1024
+    n_txt, grid, B = 32, 16, 2
+    n_img = grid * grid
+    n_all = n_txt + 2 * n_img
+    rng = np.random.default_rng(inputs.workload_seed(1, 41))
+    streams = [inputs.stream_weights(rng, hidden, mlp, kind, "bf16", std=0.05) for _ in range(2 if kind == "double" else 1)]
+    rope_o = None
+    if extras:
+        for w in streams:
+            w["q_norm"] = (1.0 + 0.2 * rng.standard_normal(d)).astype(np.float32)
+            w["k_norm"] = (1.0 + 0.2 * rng.standard_normal(d)).astype(np.float32)
+        yy, xx = np.meshgrid(np.arange(grid), np.arange(grid), indexing="ij")
+        pos = np.concatenate([np.zeros((n_txt, 3), dtype=np.int32)] +
+                             [np.stack([np.full(n_img, i), yy.ravel(), xx.ravel()], axis=1).astype(np.int32) for i in (0, 1)], axis=0)
+        rope_o = orc.rope_angles(pos, (8, 28, 28))
+    h = inputs.bf16_round(rng.standard_normal((B, n_all, hidden)).astype(np.float32))     # the branches differ everywhere
+    e = np.nonzero(inputs.rect_mask(rng, grid, grid, 6, 6))[0].astype(np.int32)
+
+    ctx = rg.Context(hidden, heads, d, mlp, B * n_all, 4096)
+    bw, keep = block_to_device(streams, kind, ctx)
+    if extras:
+        table = torch.empty((n_all, d), dtype=torch.float32, device="cuda")
+        rg.regione_rope_table(ctx, torch.from_numpy(pos).cuda(), n_all, [8, 28, 28], 10000.0, table)
+        bw.rope, bw.rope_rows = table.data_ptr(), n_all
+    btype = rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE
+
+    # storing full forward of both branches (text rows fresh: the per-branch path for double-stream blocks)
+    kc_o = np.zeros((B, n_all, heads, d)); vc_o = np.zeros_like(kc_o)
+    full_o = np.stack([orc.block_forward(streams, kind, h[b], n_txt, np.arange(n_all), kc_o[b], vc_o[b], orc.FLAG_STORE, heads, rope=rope_o)
+                       for b in range(B)])
+    slots_all = torch.arange(n_all, dtype=torch.int32, device="cuda")
+    kc = torch.zeros((B, n_all, heads, d), dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
+    out = torch.empty((B, n_all, hidden), dtype=torch.bfloat16, device="cuda")
+    rg.regione_block_forward_batched(ctx, bw, btype, dev(h, "bf16"), out, rg.BF16, B, n_all, n_txt, slots_all, 0, kc, vc, n_all, rg.FLAG_STORE)
+    assert_close(host(out), full_o, f"{kind}: batched storing forward", stored_bf16=True)
+    assert_close(host(kc), kc_o, f"{kind}: batched stored K", stored_bf16=True)
+    assert_close(host(vc), vc_o, f"{kind}: batched stored V", stored_bf16=True)
+    # no cache
+    out2 = torch.empty_like(out)
+    rg.regione_block_forward_batched(ctx, bw, btype, dev(h, "bf16"), out2, rg.BF16, B, n_all, n_txt, None, 0, None, None, 0, 0)
+    assert_close(host(out2), full_o, f"{kind}: batched plain forward", stored_bf16=True)
+
+    # region forward, image rows only (all branches' rows in one group) and with the text rows fresh
+    h2 = inputs.bf16_round((h + 0.05 * rng.standard_normal(h.shape)).astype(np.float32))
+    for mode, rows in (("B", n_txt + e), ("A", np.concatenate([np.arange(n_txt), n_txt + e]))):
+        n_txt_fresh = 0 if mode == "B" else n_txt
+        want = np.stack([orc.block_forward(streams, kind, h2[b][rows], n_txt_fresh, rows, kc_o[b].copy(), vc_o[b].copy(), orc.FLAG_RETRIEVE, heads, rope=rope_o)
+                         for b in range(B)])
+        kc_before, vc_before = kc.clone(), vc.clone()
+        o = torch.empty((B, len(rows), hidden), dtype=torch.bfloat16, device="cuda")
+        rg.regione_block_forward_batched(ctx, bw, btype, dev(h2[:, rows], "bf16"), o, rg.BF16, B, len(rows), n_txt_fresh,
+                                         torch.from_numpy(rows.astype(np.int32)).cuda(), 0, kc, vc, n_all, rg.FLAG_RETRIEVE)
+        assert_close(host(o), want, f"{kind}: batched region forward, mode {mode}", stored_bf16=True)
+        untouched = np.setdiff1d(np.arange(n_all), rows)
+        assert torch.equal(kc[:, untouched].view(torch.int16), kc_before[:, untouched].view(torch.int16))
+        # one branch alone gives the same rows as the single call
+        o1 = torch.empty((len(rows), hidden), dtype=torch.bfloat16, device="cuda")
+        kc1, vc1 = kc_before[1].clone(), vc_before[1].clone()
+        rg.regione_block_forward(ctx, bw, btype, dev(h2[1][rows], "bf16"), o1, rg.BF16, len(rows), n_txt_fresh,
+                                 torch.from_numpy(rows.astype(np.int32)).cuda(), 0, kc1, vc1, n_all, rg.FLAG_RETRIEVE)
+        assert_close(host(o[1]), host(o1).astype(np.float64), f"{kind}: branch 1 of the batch vs the single call", stored_bf16=True)
+        kc.copy_(kc_before); vc.copy_(vc_before)
+    with pytest.raises(rg.RegionEError):   # three branches do not fit this context
+        rg.regione_block_forward_batched(ctx, bw, btype, dev(h, "bf16"), out, rg.BF16, 3, n_all, n_txt, slots_all, 0, kc, vc, n_all, rg.FLAG_STORE)
+    with pytest.raises(rg.RegionEError):
+        rg.regione_block_forward_batched(ctx, bw, btype, dev(h, "bf16"), out, rg.BF16, 0, n_all, n_txt, slots_all, 0, kc, vc, n_all, rg.FLAG_STORE)
+    ctx.close()
