@@ -58,7 +58,7 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
     const size_t n = static_cast<size_t>(dims->max_fresh), H = dims->hidden, M = dims->mlp;
     c->part_counts_cap = dims->max_tokens / 4 + 8;
     const size_t split_rows = n < 2048 ? n : 2048;
-    c->attn_part_bytes = static_cast<size_t>(8) * dims->heads * split_rows * (dims->head_dim + 2) * sizeof(float);
+    c->attn_part_bytes = static_cast<size_t>(8) * dims->heads * split_rows * (dims->head_dim + 4) * sizeof(float);
     int rc = dev_alloc(&c->part_counts, static_cast<size_t>(c->part_counts_cap));
     if (rc == REGIONE_OK) rc = dev_alloc(&c->u, n * H);
     if (rc == REGIONE_OK) rc = dev_alloc(&c->q, n * H);

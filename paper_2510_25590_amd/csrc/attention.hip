@@ -37,12 +37,13 @@ struct AttnArgs {
     int heads; float scale_log2e;
     bf16_t* out; int ldo;
     // split-KV
-    int splits; int tiles_per_split; float* part;  // [splits][heads][n_q_pad][D + 2] when splits > 1
+    int splits; int tiles_per_split; float* part;  // [splits][heads][n_q_pad][D + 4] when splits > 1: O, maximum, sum, two unused (rows stay 16-byte aligned)
     int n_q_pad;
     int q_tiles;
 };
 
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // native 16-byte vector (plain loads/stores, no memcpy)
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;   // native 16-byte vector (plain loads/stores, no memcpy)
 
 // LDS swizzles (16-byte chunk index -> physical chunk).  K tile: the 16 rows read together with one logical chunk
 // must cover all 64 banks once; rows are 256 bytes (D = 128) or 128 bytes (D = 64).  V tile: a transposing read
@@ -410,14 +411,13 @@ attn_kvcache_kernel(AttnArgs a) {
                 }
         } else {
             // partial result: unnormalised O, running max (log2 domain) and sum
-            float* pp = a.part + ((static_cast<int64_t>(split) * a.heads + head) * a.n_q_pad + qrow) * (D + 2);
+            float* pp = a.part + ((static_cast<int64_t>(split) * a.heads + head) * a.n_q_pad + qrow) * (D + 4);
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int d = db * 32 + 8 * g + 4 * lh;
-                    *reinterpret_cast<float2*>(pp + d) = make_float2(o[qb][db][4 * g], o[qb][db][4 * g + 1]);
-                    *reinterpret_cast<float2*>(pp + d + 2) = make_float2(o[qb][db][4 * g + 2], o[qb][db][4 * g + 3]);
+                    *reinterpret_cast<f32x4*>(pp + d) = f32x4{o[qb][db][4 * g], o[qb][db][4 * g + 1], o[qb][db][4 * g + 2], o[qb][db][4 * g + 3]};
                 }
             if (lh == 0) { pp[D] = m_run[qb] * c; pp[D + 1] = l_tot; }   // maximum in the log2 domain, as the merge kernel expects
         }
@@ -436,18 +436,17 @@ attn_combine_kernel(const float* __restrict__ part, int splits, int heads, int n
     const int g = static_cast<int>(gid % G);
     const int head = static_cast<int>((gid / G) % heads);
     const int qrow = static_cast<int>(gid / (static_cast<int64_t>(G) * heads));
-    // every split's row is requested before the first value is used (rows are 8-byte aligned: D + 2 floats each)
+    // every split's row is requested before the first value is used; a wave's loads of one split are contiguous
     constexpr int kMaxSplits = 8;
     float ms[kMaxSplits], ls[kMaxSplits];
-    float2 lo[kMaxSplits], hi[kMaxSplits];
+    f32x4 val[kMaxSplits];
 #pragma unroll
     for (int s = 0; s < kMaxSplits; ++s)
         if (s < splits) {
-            const float* pp = part + ((static_cast<int64_t>(s) * heads + head) * n_q_pad + qrow) * (D + 2);
+            const float* pp = part + ((static_cast<int64_t>(s) * heads + head) * n_q_pad + qrow) * (D + 4);
             const float2 ml = *reinterpret_cast<const float2*>(pp + D);
             ms[s] = ml.x; ls[s] = ml.y;
-            lo[s] = *reinterpret_cast<const float2*>(pp + 4 * g);
-            hi[s] = *reinterpret_cast<const float2*>(pp + 4 * g + 2);
+            val[s] = *reinterpret_cast<const f32x4*>(pp + 4 * g);
         }
     float m = -INFINITY;
 #pragma unroll
@@ -460,7 +459,7 @@ attn_combine_kernel(const float* __restrict__ part, int splits, int heads, int n
         if (s < splits && ls[s] > 0.f) {   // a split with l = 0 saw no key
             const float w = fast_exp2(ms[s] - m);
             l += w * ls[s];
-            acc[0] += w * lo[s].x; acc[1] += w * lo[s].y; acc[2] += w * hi[s].x; acc[3] += w * hi[s].y;
+            acc[0] += w * val[s][0]; acc[1] += w * val[s][1]; acc[2] += w * val[s][2]; acc[3] += w * val[s][3];
         }
     const float inv = 1.0f / l;
     bf16x4 pk;
@@ -487,13 +486,13 @@ int launch_attention(regione_ctx* ctx, AttnArgs a) {
         const double passes = load <= 1.0 ? 1.0 : 0.5 * (ceil(load) + load);   // a last, partly filled pass runs faster
         const double fill = wgs * s <= 256.0 ? 0.68 : 1.0;                      // a CU with one workgroup runs it faster
         double t = passes * ((n_tiles + s - 1) / s + 4) * 2.0 * fill;
-        if (s > 1) t += 3.0 + 1.5 * static_cast<double>(s) * a.n_q * a.heads * (D + 2) * 8.0 / 4.0e6;
+        if (s > 1) t += 3.0 + 1.5 * static_cast<double>(s) * a.n_q * a.heads * (D + 4) * 8.0 / 4.0e6;
         if (s == 1 || t < best) { best = t; splits = s; }
     }
     if (ctx->attn_force_splits > 0 && ctx->attn_force_splits * 2 <= n_tiles) splits = ctx->attn_force_splits;
     a.n_q_pad = a.n_q;
     if (splits > 1) {
-        const size_t need = static_cast<size_t>(splits) * a.heads * a.n_q_pad * (D + 2) * sizeof(float);
+        const size_t need = static_cast<size_t>(splits) * a.heads * a.n_q_pad * (D + 4) * sizeof(float);
         if (need > ctx->attn_part_bytes) splits = 1;
     }
     a.splits = splits;

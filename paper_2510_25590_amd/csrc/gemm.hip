@@ -83,65 +83,86 @@ __device__ __forceinline__ void epilogue_store(const GemmEpilogue& ep, int row, 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kMaxSplits = 8;   // largest K split the planner or a forced plan uses
 
-__device__ __forceinline__ void store8(void* base, int64_t elem, int as_f32, const float (&v)[8]) {
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+
+// W = 4 or 8 consecutive elements: 16- or 32-byte (float32), 8- or 16-byte (bf16) pieces
+template <int W>
+__device__ __forceinline__ void store_vec(void* base, int64_t elem, int as_f32, const float (&v)[W]) {
     if (as_f32) {
         float* p = static_cast<float*>(base) + elem;
-        *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]};
-        *reinterpret_cast<f32x4*>(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
-    } else {
+#pragma unroll
+        for (int h = 0; h < W / 4; ++h) *reinterpret_cast<f32x4*>(p + 4 * h) = f32x4{v[4 * h], v[4 * h + 1], v[4 * h + 2], v[4 * h + 3]};
+    } else if (W == 8) {
         bf16x8 o;
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(v[e]);
         *reinterpret_cast<bf16x8*>(static_cast<bf16_t*>(base) + elem) = o;
+    } else {
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = static_cast<__bf16>(v[e]);
+        *reinterpret_cast<bf16x4*>(static_cast<bf16_t*>(base) + elem) = o;
     }
 }
+__device__ __forceinline__ void store8(void* base, int64_t elem, int as_f32, const float (&v)[8]) { store_vec<8>(base, elem, as_f32, v); }
 
-// Epilogue for eight consecutive columns col0..col0+7 of one row (all inside N, col0 a multiple of 8):
-// 16- or 32-byte loads and stores only.
-template <int KIND>
-__device__ __forceinline__ void epilogue_store8(const GemmEpilogue& ep, int row, int col0, const float (&acc)[8],
-                                                const float (&bias)[8], const float (&gate)[8]) {
-    float val[8];
+// Epilogue for W consecutive columns col0..col0+W-1 of one row (all inside N, col0 a multiple of W, W = 4 or 8;
+// the wide-epilogue conditions hold, so a group never straddles two destinations): wide loads and stores only.
+template <int KIND, int W>
+__device__ __forceinline__ void epilogue_store_vec(const GemmEpilogue& ep, int row, int col0, const float (&acc)[W],
+                                                   const float (&bias)[W], const float (&gate)[W]) {
+    float val[W];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) val[e] = acc[e] + bias[e];
+    for (int e = 0; e < W; ++e) val[e] = acc[e] + bias[e];
     if (KIND == EPI_PLAIN) {
         if (ep.act == REGIONE_ACT_GELU_TANH) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) if (col0 + e >= ep.act_from) val[e] = gelu_tanh_f32(val[e]);
+            for (int e = 0; e < W; ++e) if (col0 + e >= ep.act_from) val[e] = gelu_tanh_f32(val[e]);
         }
-        store8(ep.y, static_cast<int64_t>(row) * ep.ldy + col0, ep.y_f32, val);
+        store_vec<W>(ep.y, static_cast<int64_t>(row) * ep.ldy + col0, ep.y_f32, val);
     } else if (KIND == EPI_QKV) {
-        const int H = ep.hidden;   // a multiple of 8, so a group never straddles two destinations
+        const int H = ep.hidden;   // a multiple of 8
         if (col0 < H) {
-            store8(ep.q, static_cast<int64_t>(row) * ep.ldq + col0, 0, val);
+            store_vec<W>(ep.q, static_cast<int64_t>(row) * ep.ldq + col0, 0, val);
         } else if (col0 < 3 * H) {
             const int64_t kv_row = epilogue_kv_row<KIND>(ep, row);
-            if (col0 < 2 * H) store8(ep.k, kv_row * ep.ldkv + (col0 - H), 0, val);
-            else store8(ep.v, kv_row * ep.ldkv + (col0 - 2 * H), 0, val);
+            if (col0 < 2 * H) store_vec<W>(ep.k, kv_row * ep.ldkv + (col0 - H), 0, val);
+            else store_vec<W>(ep.v, kv_row * ep.ldkv + (col0 - 2 * H), 0, val);
         } else {
             if (ep.act == REGIONE_ACT_GELU_TANH) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) val[e] = gelu_tanh_f32(val[e]);
+                for (int e = 0; e < W; ++e) val[e] = gelu_tanh_f32(val[e]);
             }
-            store8(ep.y, static_cast<int64_t>(row) * ep.ldy + ep.y_col0 + (col0 - 3 * H), 0, val);
+            store_vec<W>(ep.y, static_cast<int64_t>(row) * ep.ldy + ep.y_col0 + (col0 - 3 * H), 0, val);
         }
     } else {  // EPI_RESID
         const int64_t ri = static_cast<int64_t>(row) * ep.ldr + col0;
-        float res[8];
+        float res[W];
         if (ep.resid_f32) {
-            const f32x4 a = *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.resid) + ri);
-            const f32x4 b = *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.resid) + ri + 4);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { res[e] = a[e]; res[4 + e] = b[e]; }
-        } else {
+            for (int h = 0; h < W / 4; ++h) {
+                const f32x4 a = *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.resid) + ri + 4 * h);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) res[4 * h + e] = a[e];
+            }
+        } else if (W == 8) {
             const bf16x8 a = *reinterpret_cast<const bf16x8*>(static_cast<const bf16_t*>(ep.resid) + ri);
 #pragma unroll
             for (int e = 0; e < 8; ++e) res[e] = static_cast<float>(a[e]);
+        } else {
+            const bf16x4 a = *reinterpret_cast<const bf16x4*>(static_cast<const bf16_t*>(ep.resid) + ri);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) res[e] = static_cast<float>(a[e]);
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) val[e] = res[e] + gate[e] * val[e];
-        store8(ep.y, static_cast<int64_t>(row) * ep.ldy + col0, ep.y_f32, val);
+        for (int e = 0; e < W; ++e) val[e] = res[e] + gate[e] * val[e];
+        store_vec<W>(ep.y, static_cast<int64_t>(row) * ep.ldy + col0, ep.y_f32, val);
     }
+}
+template <int KIND>
+__device__ __forceinline__ void epilogue_store8(const GemmEpilogue& ep, int row, int col0, const float (&acc)[8],
+                                                const float (&bias)[8], const float (&gate)[8]) {
+    epilogue_store_vec<KIND, 8>(ep, row, col0, acc, bias, gate);
 }
 
 // Writes a wave's accumulators: the 128 x 32*TN tile whose first row is m0 and first column n0 + wn0.  `stage_lds`:
@@ -618,38 +639,41 @@ splitk_epilogue_kernel(const float* __restrict__ partial, int splits, int M, int
     }
 }
 
-// The same for rows whose columns come in whole groups of eight (the wide epilogue's conditions hold): one thread per
-// group, the partial sums of all splits requested before the first is used, 32-byte pieces throughout.
+// The same with the wide epilogue's conditions (N a multiple of 8, aligned rows): one thread per group of FOUR
+// columns, so that every load of a wave is one contiguous kilobyte; the partial sums of all splits are requested
+// before the first is used.
 template <int KIND>
 __global__ void __launch_bounds__(kThreads)
-splitk_epilogue8_kernel(const float* __restrict__ partial, int splits, int M, int N, GemmEpilogue ep) {
-    const int groups = N >> 3;
+splitk_epilogue4_kernel(const float* __restrict__ partial, int splits, int M, int N, GemmEpilogue ep) {
+    const int groups = N >> 2;
     const int64_t gid = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
     if (gid >= static_cast<int64_t>(M) * groups) return;
-    const int row = static_cast<int>(gid / groups), col0 = static_cast<int>(gid - static_cast<int64_t>(row) * groups) * 8;
+    const int row = static_cast<int>(gid / groups), col0 = static_cast<int>(gid - static_cast<int64_t>(row) * groups) * 4;
     const int64_t total = static_cast<int64_t>(M) * N;
     const float* src = partial + static_cast<int64_t>(row) * N + col0;
-    f32x4 lo[kMaxSplits], hi[kMaxSplits];
+    f32x4 part[kMaxSplits];
 #pragma unroll
     for (int p = 0; p < kMaxSplits; ++p)
-        if (p < splits) {
-            lo[p] = *reinterpret_cast<const f32x4*>(src + p * total);
-            hi[p] = *reinterpret_cast<const f32x4*>(src + p * total + 4);
-        }
-    float bias[8], gate[8];
+        if (p < splits) part[p] = *reinterpret_cast<const f32x4*>(src + p * total);
+    float bias[4] = {0.f, 0.f, 0.f, 0.f}, gate[4] = {1.f, 1.f, 1.f, 1.f};
+    if (ep.bias) {
+        const f32x4 b = *reinterpret_cast<const f32x4*>(ep.bias + col0);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        bias[e] = ep.bias ? ep.bias[col0 + e] : 0.f;
-        gate[e] = (KIND == EPI_RESID && ep.gate) ? ep.gate[col0 + e] : 1.f;
+        for (int e = 0; e < 4; ++e) bias[e] = b[e];
     }
-    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (KIND == EPI_RESID && ep.gate) {
+        const f32x4 g = *reinterpret_cast<const f32x4*>(ep.gate + col0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) gate[e] = g[e];
+    }
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int p = 0; p < kMaxSplits; ++p)
         if (p < splits) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { v[e] += lo[p][e]; v[4 + e] += hi[p][e]; }
+            for (int e = 0; e < 4; ++e) v[e] += part[p][e];
         }
-    epilogue_store8<KIND>(ep, row, col0, v, bias, gate);
+    epilogue_store_vec<KIND, 4>(ep, row, col0, v, bias, gate);
 }
 
 // [n, k] row-major -> fragment-major packed layout (rows past n are zero)
@@ -735,9 +759,10 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, in
     RG_LAUNCH_CHECK();
     if (used_splits > 1) {
         const int64_t total = static_cast<int64_t>(m) * n;
-        if (ep.vec_ok && used_splits <= kMaxSplits) {
-            const int64_t blocks = (total / 8 + kThreads - 1) / kThreads;
-            hipLaunchKernelGGL((splitk_epilogue8_kernel<KIND>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+        const bool wide = ep.vec_ok && used_splits <= kMaxSplits && (!ep.bias || rg_aligned16(ep.bias)) && (!ep.gate || rg_aligned16(ep.gate));
+        if (wide) {
+            const int64_t blocks = (total / 4 + kThreads - 1) / kThreads;
+            hipLaunchKernelGGL((splitk_epilogue4_kernel<KIND>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
                                partial, used_splits, m, n, ep);
         } else {
             int64_t blocks = (total + kThreads - 1) / kThreads;
