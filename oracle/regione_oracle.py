@@ -385,6 +385,22 @@ def decay_factor(t, gamma, j: int) -> float:
     return (1.0 - (float(t[j + 1]) - float(t[j]))) * float(gamma[j])
 
 
+def fit_gamma(norms: np.ndarray, t) -> np.ndarray:
+    """Timestep-aware factor of Eq.7 from sampled trajectories ("obtained by fitting on a randomly
+    sampled dataset"; the paper does not say how: here least squares through the origin).
+    norms[s, j] = |v_{t_j}| of sample s for j = 1..T (column 0 is not used); t has T+1 entries.
+    For j = 1..T-1 the slope c_j of |v_{t_j}| against |v_{t_{j+1}}| over the samples is
+    sum_s a_s b_s / sum_s b_s^2, and gamma_j = c_j / (1 - (t_{j+1} - t_j)).  gamma_0 = gamma_T = 1
+    (no ratio exists there)."""
+    norms = np.asarray(norms, dtype=F64)
+    T = norms.shape[1] - 1
+    gamma = np.ones(T + 1, dtype=F64)
+    for j in range(1, T):
+        a, b = norms[:, j], norms[:, j + 1]
+        gamma[j] = (a * b).sum() / (b * b).sum() / (1.0 - (float(t[j + 1]) - float(t[j])))
+    return gamma
+
+
 class AvdState:
     """State of the adaptive velocity decay cache: whether C_A holds a velocity, and the
     product of Eq.7 factors accumulated since it was computed."""
