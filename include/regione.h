@@ -280,6 +280,21 @@ typedef struct regione_plan_step {
 int regione_stage_plan_host(int32_t T, int32_t t_st, int32_t t_sm, const int32_t* forced_k, int32_t n_forced,
                             regione_plan_step* steps_out, int32_t max_steps, int32_t* n_steps_out);
 
+/* Fitting the timestep-aware factor gamma of Eq.7 ("obtained by fitting on a randomly sampled
+ * dataset"; the paper gives no procedure, this is least squares through the origin).
+ * regione_sq_norms: out[i] = sum of squares of vector i, for n_vectors contiguous vectors of
+ *   vec_elems elements of `dtype` (16-byte aligned, vec_elems a multiple of 8 for bf16 / 4 for
+ *   float32); out is [n_vectors] float64 on the device.  Squares and sums in float64, in a fixed
+ *   order.  One call over the velocities a sampler has kept gives every |v_{t_j}|^2.
+ * regione_gamma_fit_host: sq_norms_host [n_samples, n_steps+1] with entry [s][j] = |v_{t_j}|^2
+ *   of sample s for j = 1..n_steps (column 0 unused), t_host as in
+ *   regione_velocity_decision_host.  Writes gamma_out [n_steps+1]:
+ *   gamma_j = (sum_s |v_j||v_{j+1}| / sum_s |v_{j+1}|^2) / (1 - (t_{j+1} - t_j)) for
+ *   1 <= j < n_steps, and 1 at both ends. */
+int regione_sq_norms(regione_ctx* ctx, const void* x, int32_t dtype, int64_t n_vectors, int64_t vec_elems, double* out);
+int regione_gamma_fit_host(const double* sq_norms_host, int32_t n_samples, const float* t_host, int32_t n_steps,
+                           float* gamma_out);
+
 /* Adaptive velocity decay cache, host decision (Eq.7, Eq.8): pure function of the
  * schedule.  t_host has n_steps+1 entries with t[n_steps] = 1 and t[0] = 0; gamma_host has
  * n_steps+1 entries (gamma[j] corrects the step at index j).  For the step at index j

@@ -27,6 +27,7 @@ EXPORTS = (
     "regione_packed_weight_elems", "regione_pack_weight", "regione_tune_gemm", "regione_tune_attention",
     "regione_layernorm", "regione_stage_plan_host", "regione_cast", "regione_mask_cleanup", "regione_rope_table",
     "regione_vec_linear", "regione_timestep_embedding", "regione_block_forward_batched",
+    "regione_sq_norms", "regione_gamma_fit_host",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -86,6 +87,8 @@ def lib() -> C.CDLL:
             "regione_block_forward_batched": [vp, C.POINTER(BlockWeights), i32, vp, vp, i32, i32, i32, i32, vp, i32, vp, vp, i32, i32],
             "regione_velocity_decision_host": [C.POINTER(f32), C.POINTER(f32), i32, f32, i32, C.POINTER(AvdState),
                                                C.POINTER(i32), C.POINTER(f32)],
+            "regione_sq_norms": [vp, vp, i32, i64, i64, vp],
+            "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
             "regione_pack_weight": [vp, vp, i32, i32, vp],
             "regione_tune_gemm": [vp, i32, i32],
@@ -200,6 +203,22 @@ def regione_block_forward_batched(ctx, weights: BlockWeights, block_type, h_in, 
                                   slot_index, slot_offset, k_cache, v_cache, n_all, flags):
     _check(lib().regione_block_forward_batched(ctx.handle, C.byref(weights), block_type, _p(h_in), _p(h_out), h_dtype, n_branches, n_fresh,
                                                n_txt_fresh, _p(slot_index), slot_offset, _p(k_cache), _p(v_cache), n_all, flags))
+
+
+def regione_sq_norms(ctx, x, dtype, n_vectors, vec_elems, out):
+    _check(lib().regione_sq_norms(ctx.handle, _p(x), dtype, n_vectors, vec_elems, _p(out)))
+
+
+def regione_gamma_fit_host(sq_norms, t):
+    """sq_norms: host array [n_samples, T+1] of float64; t: T+1 floats.  Returns the list gamma[0..T]."""
+    import numpy as np
+    a = np.ascontiguousarray(sq_norms, dtype=np.float64)
+    n_samples, cols = a.shape
+    T = cols - 1
+    tt = (C.c_float * (T + 1))(*[float(v) for v in t])
+    out = (C.c_float * (T + 1))()
+    _check(lib().regione_gamma_fit_host(a.ctypes.data_as(C.POINTER(C.c_double)), n_samples, tt, T, out))
+    return list(out)
 
 
 def regione_velocity_decision_host(t, gamma, n_steps, delta, j, state: AvdState):

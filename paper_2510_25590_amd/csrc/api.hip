@@ -190,6 +190,28 @@ extern "C" int regione_velocity_decision_host(const float* t_host, const float* 
     return REGIONE_OK;
 }
 
+extern "C" int regione_gamma_fit_host(const double* sq_norms_host, int32_t n_samples, const float* t_host, int32_t n_steps,
+                                      float* gamma_out) {
+    if (!sq_norms_host || !t_host || !gamma_out) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gamma_fit: null argument");
+    if (n_samples < 1 || n_steps < 1) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gamma_fit: n_samples=%d n_steps=%d", n_samples, n_steps);
+    const int64_t ld = static_cast<int64_t>(n_steps) + 1;
+    for (int32_t j = 0; j <= n_steps; ++j) gamma_out[j] = 1.0f;
+    for (int32_t j = 1; j < n_steps; ++j) {
+        // least squares through the origin of |v_{t_j}| against |v_{t_{j+1}}| over the samples (Eq.7's left-hand side)
+        double ab = 0.0, bb = 0.0;
+        for (int32_t s = 0; s < n_samples; ++s) {
+            const double a2 = sq_norms_host[s * ld + j], b2 = sq_norms_host[s * ld + j + 1];
+            if (!(a2 >= 0.0) || !(b2 >= 0.0)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gamma_fit: squared norm of sample %d is negative or NaN", s);
+            ab += sqrt(a2) * sqrt(b2);
+            bb += b2;
+        }
+        const double solver = 1.0 - (static_cast<double>(t_host[j + 1]) - static_cast<double>(t_host[j]));
+        if (!(bb > 0.0) || !(solver > 0.0)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "gamma_fit: step %d has zero velocities or a time step of one", j);
+        gamma_out[j] = static_cast<float>(ab / bb / solver);
+    }
+    return REGIONE_OK;
+}
+
 namespace {
 
 int check_stream_weights(const regione_stream_weights& w, int block_type, const char* which) {

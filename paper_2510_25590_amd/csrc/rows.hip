@@ -269,3 +269,55 @@ int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidd
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
 }
+
+// ---- squared norms of velocity vectors: the data the timestep-aware factor of Eq.7 is fitted on
+namespace {
+
+// One workgroup per vector.  Squares and sums in float64; the order of the sums is fixed by the launch shape, so
+// the result is reproducible.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+sq_norms_kernel(const T* __restrict__ x, int64_t vec_elems, double* __restrict__ out) {
+    const T* v = x + static_cast<int64_t>(blockIdx.x) * vec_elems;
+    double acc = 0.0;
+    const int64_t groups = vec_elems >> 3;
+    for (int64_t g = threadIdx.x; g < groups; g += kThreads) {
+        float e[8];
+        ld8<T>(v + g * 8, e);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc = fma(static_cast<double>(e[i]), static_cast<double>(e[i]), acc);
+    }
+    for (int64_t i = (groups << 3) + threadIdx.x; i < vec_elems; i += kThreads) {
+        float f;
+        if constexpr (sizeof(T) == 2) f = bf16_to_f32(v[i]); else f = v[i];
+        acc = fma(static_cast<double>(f), static_cast<double>(f), acc);
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    __shared__ double part[kThreads / 64];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < kThreads / 64; ++w) s += part[w];
+        out[blockIdx.x] = s;
+    }
+}
+
+}  // namespace
+
+extern "C" int regione_sq_norms(regione_ctx* ctx, const void* x, int32_t dtype, int64_t n_vectors, int64_t vec_elems, double* out) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "sq_norms: null context");
+    if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "sq_norms: bad dtype %d", dtype);
+    if (n_vectors < 0 || vec_elems < 0 || n_vectors > INT32_MAX) RG_FAIL(REGIONE_ERR_INVALID_ARG, "sq_norms: n_vectors=%lld vec_elems=%lld", static_cast<long long>(n_vectors), static_cast<long long>(vec_elems));
+    if (n_vectors == 0) return REGIONE_OK;
+    if (!out || (!x && vec_elems > 0)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "sq_norms: null operand");
+    const size_t elem = dtype == REGIONE_BF16 ? 2 : 4;
+    if (!rg_aligned16(x) || (vec_elems * elem) % 16) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "sq_norms: vectors must start 16-byte aligned");
+    ProfScope prof(ctx, REGIONE_PROF_VELOCITY);
+    if (dtype == REGIONE_BF16) hipLaunchKernelGGL(sq_norms_kernel<bf16_t>, dim3(static_cast<unsigned>(n_vectors)), dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(x), vec_elems, out);
+    else hipLaunchKernelGGL(sq_norms_kernel<float>, dim3(static_cast<unsigned>(n_vectors)), dim3(kThreads), 0, ctx->stream, static_cast<const float*>(x), vec_elems, out);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}

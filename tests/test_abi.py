@@ -78,3 +78,24 @@ def test_host_stage_plan_rejects_stages_that_do_not_fit():
     for args in ((28, 20, 10, []), (28, 6, 2, [3]), (28, 6, 2, [27]), (28, 6, 2, [16, 16]), (0, 1, 1, [])):
         with pytest.raises(rg.RegionEError):
             rg.regione_stage_plan_host(*args)
+
+
+def test_gamma_fit_host_matches_oracle():
+    """Host-only entry point: least-squares fit of Eq.7's timestep-aware factor, against the oracle's fit."""
+    import numpy as np
+    from oracle import regione_oracle as orc
+    rng = np.random.default_rng(7)
+    T, S = 28, 16
+    t = np.linspace(0.0, 1.0, T + 1) ** 1.2
+    norms = rng.uniform(0.5, 2.0, (S, T + 1))
+    want = orc.fit_gamma(norms, t.astype(np.float32).astype(np.float64))
+    got = np.array(rg.regione_gamma_fit_host(norms ** 2, t))
+    assert got.shape == (T + 1,)
+    assert np.allclose(got, want, rtol=2e-6)
+    assert got[0] == 1.0 and got[T] == 1.0
+    bad = norms ** 2
+    bad[3, 5] = -1.0
+    with pytest.raises(rg.RegionEError):
+        rg.regione_gamma_fit_host(bad, t)
+    with pytest.raises(rg.RegionEError):
+        rg.regione_gamma_fit_host(np.zeros((S, T + 1)), t)

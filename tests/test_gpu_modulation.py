@@ -75,3 +75,44 @@ def test_modulation_vectors_feed_a_block(ctx):
     rg.regione_vec_linear(ctx, h1, rg.ACT_SILU, d(w2), None, hidden, hidden, h2)
     rg.regione_vec_linear(ctx, h2, rg.ACT_SILU, d(wm), torch.from_numpy(bm).cuda(), 6 * hidden, hidden, mod)
     assert np.abs(mod.cpu().numpy() - want).max() <= 2e-5
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("n_vec,elems", [(28 * 3, 4096 * 64), (5, 8), (3, 1000), (1, 0)])
+def test_sq_norms_match_float64_sums(ctx, dtype, n_vec, elems):
+    rng = np.random.default_rng(4200 + n_vec + elems)
+    x = rng.standard_normal((n_vec, elems)).astype(np.float32)
+    if dtype == "bf16":
+        x = inputs.bf16_round(x)
+    d = torch.from_numpy(x).cuda()
+    if dtype == "bf16":
+        d = d.to(torch.bfloat16)
+    out = torch.full((n_vec + 1,), -1.0, dtype=torch.float64, device="cuda")
+    rg.regione_sq_norms(ctx, d, rg.BF16 if dtype == "bf16" else rg.FP32, n_vec, elems, out)
+    got = out.cpu().numpy()
+    assert got[n_vec] == -1.0
+    want = (x.astype(np.float64) ** 2).sum(axis=1)
+    # squares are exact in float64; only the order of the additions differs from numpy's
+    assert np.allclose(got[:n_vec], want, rtol=1e-12, atol=0)
+    out2 = torch.empty_like(out)
+    rg.regione_sq_norms(ctx, d, rg.BF16 if dtype == "bf16" else rg.FP32, n_vec, elems, out2)
+    assert torch.equal(out[:n_vec], out2[:n_vec])          # fixed summation order
+
+
+def test_gamma_fit_from_device_norms(ctx):
+    """Velocity traces that follow Eq.7 with a known table: norms on the device, fit on the host."""
+    from oracle import regione_oracle as orc
+    rng = np.random.default_rng(4300)
+    T, S, n = 12, 4, 2048
+    t = np.linspace(0.0, 1.0, T + 1)
+    gamma = 1.0 + 0.05 * rng.standard_normal(T + 1)
+    v = np.zeros((S, T + 1, n), dtype=np.float32)
+    v[:, T] = rng.standard_normal((S, n))
+    for j in range(T - 1, 0, -1):
+        v[:, j] = v[:, j + 1] * np.float32(orc.decay_factor(t, gamma, j))
+    sq = torch.zeros((S, T + 1), dtype=torch.float64, device="cuda")
+    rg.regione_sq_norms(ctx, torch.from_numpy(v).cuda(), rg.FP32, S * (T + 1), n, sq)
+    got = np.array(rg.regione_gamma_fit_host(sq.cpu().numpy(), t))
+    assert np.allclose(got[1:T], gamma[1:T], rtol=1e-5)
+    want = orc.fit_gamma(np.sqrt((v.astype(np.float64) ** 2).sum(axis=2)), t)
+    assert np.allclose(got, want, rtol=1e-5)
