@@ -82,3 +82,72 @@ def test_batched_block_all_modes(kind, extras):
     with pytest.raises(rg.RegionEError):
         rg.regione_block_forward_batched(ctx, bw, btype, dev(h, "bf16"), out, rg.BF16, 0, n_all, n_txt, slots_all, 0, kc, vc, n_all, rg.FLAG_STORE)
     ctx.close()
+
+
+def test_batched_region_forward_with_extras_at_full_width_sampled():
+    """3072 wide, 24 heads x 128, MLP 12288, 512 text + 4096 image + 4096 reference tokens, 819 edited tokens, two
+    branches in one call, query/key normalisation and rotary embedding on: the launch shapes of `bench.py --cfg`
+    and `--block-extras`.  The oracle builds each branch's cache in full and evaluates sampled edited rows."""
+    hidden, heads, d, mlp = 3072, 24, 128, 12288
+    n_txt, grid, B = 512, 64, 2
+    n_img = grid * grid
+    n_all = n_txt + 2 * n_img
+    rng = np.random.default_rng(inputs.workload_seed(2, 43))
+    streams = [inputs.stream_weights(rng, hidden, mlp, "double", "bf16") for _ in range(2)]
+    for w in streams:
+        w["q_norm"] = (1.0 + 0.1 * rng.standard_normal(d)).astype(np.float32)
+        w["k_norm"] = (1.0 + 0.1 * rng.standard_normal(d)).astype(np.float32)
+    yy, xx = np.meshgrid(np.arange(grid), np.arange(grid), indexing="ij")
+    pos = np.concatenate([np.zeros((n_txt, 3), dtype=np.int32)] +
+                         [np.stack([np.full(n_img, i), yy.ravel(), xx.ravel()], axis=1).astype(np.int32) for i in (0, 1)], axis=0)
+    axes = (16, 56, 56)
+    ang = orc.rope_angles(pos, axes)
+    h_store = np.stack([inputs.hidden_states(rng, n_all, hidden) for _ in range(B)])
+    e = np.nonzero(inputs.rect_mask_fraction(rng, grid, grid, 819))[0].astype(np.int32)
+    rows = n_txt + e
+    h_now = inputs.bf16_round((h_store[:, rows] + 0.05 * rng.standard_normal((B, len(rows), hidden))).astype(np.float32))
+
+    ctx = rg.Context(hidden, heads, d, mlp, n_all, 4096)
+    bw, keep = block_to_device(streams, "double", ctx)
+    table = torch.empty((n_all, d), dtype=torch.float32, device="cuda")
+    rg.regione_rope_table(ctx, torch.from_numpy(pos).cuda(), n_all, list(axes), 10000.0, table)
+    bw.rope, bw.rope_rows = table.data_ptr(), n_all
+    kc = torch.zeros((B, n_all, heads, d), dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
+    slots_all = torch.arange(n_all, dtype=torch.int32, device="cuda")
+    out_full = torch.empty((n_all, hidden), dtype=torch.bfloat16, device="cuda")
+    for b in range(B):   # a storing forward carries every row: one branch at a time fits the context
+        rg.regione_block_forward(ctx, bw, rg.BLOCK_DOUBLE, dev(h_store[b], "bf16"), out_full, rg.BF16, n_all, n_txt, slots_all, 0,
+                                 kc[b], vc[b], n_all, rg.FLAG_STORE)
+    kc_stored = kc.clone()
+    o = torch.empty((B, len(rows), hidden), dtype=torch.bfloat16, device="cuda")
+    rg.regione_block_forward_batched(ctx, bw, rg.BLOCK_DOUBLE, dev(h_now, "bf16"), o, rg.BF16, B, len(rows), 0,
+                                     torch.from_numpy(e).cuda(), n_txt, kc, vc, n_all, rg.FLAG_RETRIEVE)
+    got = host(o)
+    sample = np.sort(rng.choice(len(rows), size=24, replace=False))
+    sample[:2] = [0, len(rows) - 1]
+    for b in range(B):
+        # oracle cache of the branch: normalised, rotated keys and plain values of every row
+        kc_o = np.empty((n_all, heads, d)); vc_o = np.empty_like(kc_o)
+        for sl, w in ((slice(0, n_txt), streams[0]), (slice(n_txt, n_all), streams[1])):
+            u = orc.modulate(orc.layer_norm(h_store[b][sl]), w["shift1"], w["scale1"])
+            kv = orc.linear(u, w["w_qkv"][hidden:], w["b_qkv"][hidden:])
+            kc_o[sl] = orc.rope_apply(orc.rms_norm(kv[:, :hidden].reshape(-1, heads, d), w["k_norm"]), ang[sl])
+            vc_o[sl] = kv[:, hidden:].reshape(-1, heads, d)
+        check = np.sort(rng.choice(n_all, size=48, replace=False))
+        assert_close(host(kc_stored[b][check]), kc_o[check], f"branch {b}: stored K rows (normalised, rotated)", stored_bf16=True)
+        # region forward on the sampled rows; keys of all fresh rows take part
+        w = streams[1]
+        u = orc.modulate(orc.layer_norm(h_now[b]), w["shift1"], w["scale1"])
+        kv = orc.linear(u, w["w_qkv"][hidden:], w["b_qkv"][hidden:])
+        kf = orc.rope_apply(orc.rms_norm(kv[:, :hidden].reshape(-1, heads, d), w["k_norm"]), ang[rows])
+        vf = kv[:, hidden:].reshape(-1, heads, d)
+        q = orc.linear(u[sample], w["w_qkv"][:hidden], w["b_qkv"][:hidden]).reshape(-1, heads, d)
+        q = orc.rope_apply(orc.rms_norm(q, w["q_norm"]), ang[rows[sample]])
+        fresh = np.zeros(n_all, dtype=bool); fresh[rows] = True
+        a = orc.attention_kvcache(q, kf, vf, kc_o, vc_o, np.nonzero(~fresh)[0]).reshape(len(sample), hidden)
+        h1 = h_now[b][sample].astype(np.float64) + w["gate1"] * orc.linear(a, w["w_o"], w["b_o"])
+        u2 = orc.modulate(orc.layer_norm(h1), w["shift2"], w["scale2"])
+        want = h1 + w["gate2"] * orc.linear(orc.gelu_tanh(orc.linear(u2, w["w_1"], w["b_1"])), w["w_2"], w["b_2"])
+        assert_close(got[b][sample], want, f"branch {b}: batched region forward with extras at 3072 wide (sampled rows)",
+                     stored_bf16=True, outlier_frac=1e-5)
+    ctx.close()
