@@ -269,3 +269,46 @@ def test_mask_cleanup_degenerate_and_errors():
     with pytest.raises(rg.RegionEError):
         rg.regione_mask_cleanup(ctx, m, 0, 8, 1, m, e, u, cnt)
     ctx.close()
+
+
+@pytest.mark.parametrize("n", [0, 1, 7, 4096 * 64 + 3])
+def test_cast_between_storage_types(ctx, n):
+    rng = np.random.default_rng(900 + n)
+    x = (rng.standard_normal(n) * 3.0).astype(np.float32)
+    src = torch.from_numpy(x).cuda()
+    dst = torch.full((n + 1,), 5.0, dtype=torch.bfloat16, device="cuda")
+    rg.regione_cast(ctx, src, rg.FP32, dst, rg.BF16, n)
+    assert float(dst[n]) == 5.0
+    # round to nearest even, as torch's conversion
+    assert torch.equal(dst[:n].view(torch.int16), src.to(torch.bfloat16).view(torch.int16))
+    back = torch.full((n + 1,), 7.0, dtype=torch.float32, device="cuda")
+    rg.regione_cast(ctx, dst, rg.BF16, back, rg.FP32, n)
+    assert float(back[n]) == 7.0
+    assert torch.equal(back[:n], dst[:n].float())
+    same = torch.zeros(n + 1, dtype=torch.float32, device="cuda")
+    rg.regione_cast(ctx, src, rg.FP32, same, rg.FP32, n)
+    assert torch.equal(same[:n], src)
+    with pytest.raises(rg.RegionEError):
+        rg.regione_cast(ctx, src, 9, dst, rg.BF16, n)
+
+
+@pytest.mark.parametrize("h_dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("n,hidden,mod", [(5, 256, True), (37, 3072, True), (3, 3072, False), (9, 200, True), (2, 8192, True)])
+def test_layernorm_modulation_matches_oracle(ctx, h_dtype, n, hidden, mod):
+    rng = np.random.default_rng(950 + n + hidden)
+    h = (rng.standard_normal((n, hidden)) * 2.0 + 0.5).astype(np.float32)
+    if h_dtype == "bf16":
+        h = inputs.bf16_round(h)
+    shift = (0.1 * rng.standard_normal(hidden)).astype(np.float32) if mod else None
+    scale = (0.1 * rng.standard_normal(hidden)).astype(np.float32) if mod else None
+    want = orc.modulate(orc.layer_norm(h), shift, scale)
+    dh = torch.from_numpy(h).cuda()
+    if h_dtype == "bf16":
+        dh = dh.to(torch.bfloat16)
+    u = torch.full((n + 1, hidden), 3.0, dtype=torch.bfloat16, device="cuda")
+    rg.regione_layernorm(ctx, dh, rg.BF16 if h_dtype == "bf16" else rg.FP32, n, hidden,
+                         None if shift is None else torch.from_numpy(shift).cuda(), None if scale is None else torch.from_numpy(scale).cuda(), u)
+    got = u.float().cpu().numpy()
+    assert np.all(got[n] == 3.0)
+    # float32 statistics, one rounding to bf16: half an ulp of values up to ~5
+    assert np.abs(got[:n] - want).max() <= 2.0 ** -8 * np.maximum(1.0, np.abs(want)).max()
