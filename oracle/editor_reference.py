@@ -5,7 +5,8 @@ product.  The model: token embedding Linear(C -> H) whose bias carries the times
 double-stream then single-stream blocks over the sequence [text | image | reference], LayerNorm and a
 Linear(H -> C) velocity head on the image rows.  The full forward runs every row (and, in a storing
 step, fills one K,V cache per block); the region forward runs the edited rows only and attends to the
-cached rows of all others (Eq.6).
+cached rows of all others (Eq.6).  With a second set of text rows and a guidance scale both forwards run
+once per branch (each branch has its own caches) and return the guided velocity.
 """
 from __future__ import annotations
 
@@ -15,12 +16,18 @@ from . import regione_oracle as orc
 
 
 class EditorReference:
-    def __init__(self, weights: dict, heads: int, n_img: int, x_ref, t):
+    def __init__(self, weights: dict, heads: int, n_img: int, x_ref, t, h_txt_uncond=None, guidance: float = 1.0):
         self.w = weights
         self.heads = heads
         self.n_img = n_img
         self.h_txt = np.asarray(weights["h_txt"], dtype=np.float64)
         self.n_txt = self.h_txt.shape[0]
+        self.guidance = guidance
+        self.uncond = None
+        if h_txt_uncond is not None:   # the unconditional branch: same weights, other text rows, caches of its own
+            w2 = dict(weights)
+            w2["h_txt"] = h_txt_uncond
+            self.uncond = EditorReference(w2, heads, n_img, x_ref, t)
         self.n_all = self.n_txt + 2 * n_img
         self.hidden = self.h_txt.shape[1]
         self.x_ref = np.asarray(x_ref, dtype=np.float64)
@@ -38,6 +45,12 @@ class EditorReference:
 
     def phi(self, x_rows, row_index, i, mode):
         """Signature of regione_oracle.regione_loop's velocity callback."""
+        if self.uncond is not None:
+            v_c = self._phi_branch(x_rows, row_index, i, mode)
+            return orc.guidance_combine(v_c, self.uncond._phi_branch(x_rows, row_index, i, mode), self.guidance)
+        return self._phi_branch(x_rows, row_index, i, mode)
+
+    def _phi_branch(self, x_rows, row_index, i, mode):
         t = float(self.t[i])
         self.calls.append((i, mode, None if row_index is None else len(row_index)))
         if mode in ("full", "full_store"):

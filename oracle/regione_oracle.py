@@ -385,6 +385,14 @@ def decay_factor(t, gamma, j: int) -> float:
     return (1.0 - (float(t[j + 1]) - float(t[j]))) * float(gamma[j])
 
 
+def guidance_combine(v_cond, v_uncond, scale: float) -> np.ndarray:
+    """Classifier-free guidance, which the paper's experiments keep on ("Experiment settings"):
+    the velocity used by the sampler is v_uncond + scale * (v_cond - v_uncond)."""
+    v_c = np.asarray(v_cond, dtype=F64)
+    v_u = np.asarray(v_uncond, dtype=F64)
+    return v_u + scale * (v_c - v_u)
+
+
 def fit_gamma(norms: np.ndarray, t) -> np.ndarray:
     """Timestep-aware factor of Eq.7 from sampled trajectories ("obtained by fitting on a randomly
     sampled dataset"; the paper does not say how: here least squares through the origin).

@@ -46,3 +46,14 @@ def test_solver_only_decay_gives_gamma_one():
     g = orc.fit_gamma(norms, t)
     for j in range(T - 1, 0, -1):
         assert orc.avd_decision(t, g, 0.04, j, st_a)[0] == orc.avd_decision(t, np.ones(T + 1), 0.04, j, st_b)[0]
+
+
+def test_guidance_combine_special_cases_and_linearity():
+    rng = np.random.default_rng(3)
+    vc, vu = rng.normal(size=(5, 4)), rng.normal(size=(5, 4))
+    assert np.array_equal(orc.guidance_combine(vc, vu, 1.0), vu + (vc - vu))
+    assert np.allclose(orc.guidance_combine(vc, vu, 1.0), vc, atol=1e-15)
+    assert np.array_equal(orc.guidance_combine(vc, vu, 0.0), vu)
+    # extrapolation: scale 2.5 moves 1.5 times the difference past the conditional velocity
+    assert np.allclose(orc.guidance_combine(vc, vu, 2.5), vc + 1.5 * (vc - vu), atol=1e-14)
+    assert np.array_equal(orc.guidance_combine(np.array([3.0]), np.array([1.0]), 4.0), [9.0])
