@@ -163,7 +163,7 @@ def cfg_benchmark(steps: int, warmup: int):
             "config": {"workload": cfg.name + "; block only, two branches", "n_edited_per_branch": n}, "detail": res}
 
 
-def loop_benchmark(n_double: int, n_single: int):
+def loop_benchmark(n_double: int, n_single: int, guidance=None):
     """Whole sampling loop on the device: the method's 28-step schedule (6 stabilization steps, forced step at k = 16,
     2 smooth steps, velocity-decay cache with delta = 0.04 on a linear schedule) against 28 plain full steps of the same
     editor.  3072 wide, 24 heads of 128, MLP 12288, 64x64 image + 4096 reference + 512 text tokens, one 25 % blob edited
@@ -177,12 +177,13 @@ def loop_benchmark(n_double: int, n_single: int):
     rng = np.random.default_rng(inputs.workload_seed(4, 9))
     want = inputs.blob_mask(rng, grid, grid, n_img // 4)
     x_T, x_ref = inputs.loop_latents(rng, want, channels)
-    model = loop.EditorModel.synthetic(3072, 24, 128, 12288, channels, n_img, n_txt, n_double, n_single, seed=4)
+    model = loop.EditorModel.synthetic(3072, 24, 128, 12288, channels, n_img, n_txt, n_double, n_single, seed=4, guidance=guidance)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
     x_T_d, x_ref_d = dev(x_T), dev(x_ref)
     t = [k / T for k in range(T + 1)]
     gamma = [1.0] * (T + 1)
-    out = {"workload": f"28-step sampling loop, {n_double} double + {n_single} single blocks at 3072 wide, 4096 image + 4096 reference + 512 text tokens"}
+    out = {"workload": f"28-step sampling loop, {n_double} double + {n_single} single blocks at 3072 wide, 4096 image + 4096 reference + 512 text tokens"
+                       + ("" if guidance is None else f", classifier-free guidance (two branches per step, scale {guidance})")}
     for name, kwargs in (("regione", dict(t_st=t_st, t_sm=t_sm, forced_k=forced, delta=0.04)),
                          ("vanilla", dict(t_st=T - 1, t_sm=1, forced_k=[], delta=-1.0))):    # every step a full step
         for rep in range(2):    # first pass warms up (allocations, first launches)
@@ -218,6 +219,8 @@ def main():
     ap.add_argument("--loop", action="store_true",
                     help="instead of the step benchmark: time the whole sampling loop (Algorithm 1, 28 steps) of a 3072-wide editor with "
                          "19 double- and 38 single-stream blocks against 28 plain full steps, and print one JSON line about it")
+    ap.add_argument("--loop-guidance", type=float, default=None,
+                    help="with --loop: run both guidance branches at every step with this scale (the paper's setting)")
     ap.add_argument("--loop-blocks", type=str, default="19,38", help="double,single block counts for --loop")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -240,7 +243,7 @@ def main():
         print(json.dumps(cfg_benchmark(args.steps, args.warmup)))
         return
     if args.loop:
-        print(json.dumps(loop_benchmark(*[int(v) for v in args.loop_blocks.split(",")])))
+        print(json.dumps(loop_benchmark(*[int(v) for v in args.loop_blocks.split(",")], guidance=args.loop_guidance)))
         return
     cfg = step.CONFIG_BLOCK
     if args.block_extras:   # not the headline workload: the same step with the block's query/key extras switched on

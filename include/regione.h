@@ -280,6 +280,12 @@ typedef struct regione_plan_step {
 int regione_stage_plan_host(int32_t T, int32_t t_st, int32_t t_sm, const int32_t* forced_k, int32_t n_forced,
                             regione_plan_step* steps_out, int32_t max_steps, int32_t* n_steps_out);
 
+/* Classifier-free guidance ("Experiment settings": on in every experiment of the paper): the
+ * velocity the sampler uses, out[i] = v_uncond[i] + scale * (v_cond[i] - v_uncond[i]), in
+ * float32; the three arrays have n_elems elements of `dtype`, out may be one of the inputs. */
+int regione_guidance_combine(regione_ctx* ctx, const void* v_cond, const void* v_uncond, float scale, void* out,
+                             int64_t n_elems, int32_t dtype);
+
 /* Fitting the timestep-aware factor gamma of Eq.7 ("obtained by fitting on a randomly sampled
  * dataset"; the paper gives no procedure, this is least squares through the origin).
  * regione_sq_norms: out[i] = sum of squares of vector i, for n_vectors contiguous vectors of

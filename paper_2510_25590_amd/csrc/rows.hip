@@ -321,3 +321,38 @@ extern "C" int regione_sq_norms(regione_ctx* ctx, const void* x, int32_t dtype, 
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
 }
+
+// ---- classifier-free guidance: the velocity the sampler uses is v_uncond + scale * (v_cond - v_uncond)
+namespace {
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+guidance_combine_kernel(const T* __restrict__ vc, const T* __restrict__ vu, float scale, T* __restrict__ out, int64_t n) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride) {
+        float c, u;
+        if constexpr (sizeof(T) == 2) { c = bf16_to_f32(vc[i]); u = bf16_to_f32(vu[i]); } else { c = vc[i]; u = vu[i]; }
+        const float r = u + scale * (c - u);
+        if constexpr (sizeof(T) == 2) out[i] = f32_to_bf16(r); else out[i] = r;
+    }
+}
+}  // namespace
+
+extern "C" int regione_guidance_combine(regione_ctx* ctx, const void* v_cond, const void* v_uncond, float scale, void* out,
+                                        int64_t n_elems, int32_t dtype) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "guidance_combine: null context");
+    if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "guidance_combine: bad dtype %d", dtype);
+    if (n_elems < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "guidance_combine: n_elems=%lld", static_cast<long long>(n_elems));
+    if (n_elems == 0) return REGIONE_OK;
+    if (!v_cond || !v_uncond || !out) RG_FAIL(REGIONE_ERR_INVALID_ARG, "guidance_combine: null operand");
+    ProfScope prof(ctx, REGIONE_PROF_VELOCITY);
+    int64_t blocks = (n_elems + kThreads - 1) / kThreads;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (dtype == REGIONE_BF16)
+        hipLaunchKernelGGL(guidance_combine_kernel<bf16_t>, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+                           static_cast<const bf16_t*>(v_cond), static_cast<const bf16_t*>(v_uncond), scale, static_cast<bf16_t*>(out), n_elems);
+    else
+        hipLaunchKernelGGL(guidance_combine_kernel<float>, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+                           static_cast<const float*>(v_cond), static_cast<const float*>(v_uncond), scale, static_cast<float*>(out), n_elems);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}

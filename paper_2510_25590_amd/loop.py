@@ -4,7 +4,9 @@
 blocks with one KV cache per block, velocity head) and runs its two forwards through the library:
 the full forward over [text | image | reference] rows, which can store every block's K,V
 (Algorithm 1, stabilization stage and forced steps), and the region forward over the edited rows
-only, which attends to the cached rows (Eq.6).  `run_loop` walks the plan that
+only, which attends to the cached rows (Eq.6).  With a second set of text rows and a guidance scale the
+model carries both guidance branches through every block in one batched call (own caches per branch)
+and returns the guided velocity.  `run_loop` walks the plan that
 `regione_stage_plan_host` returns: full steps, the partition after the stabilization stage, the
 one-step jump of the unedited rows (Eq.5), region steps under the adaptive velocity decay cache
 (Eq.7-9) and the merges.  Latents, velocities and the velocity cache are float32; rows enter the
@@ -18,30 +20,32 @@ from . import binding as rg
 
 
 class EditorModel:
-    def __init__(self, weights: dict, hidden: int, heads: int, head_dim: int, mlp: int, channels: int, n_img: int):
-        """weights: host arrays as made by inputs.model_weights (embed, blocks, head, h_txt)."""
+    def __init__(self, weights: dict, hidden: int, heads: int, head_dim: int, mlp: int, channels: int, n_img: int,
+                 h_txt_uncond=None, guidance: float = 1.0):
+        """weights: host arrays as made by inputs.model_weights (embed, blocks, head, h_txt).  h_txt_uncond: text rows of
+        the unconditional branch; with them every forward runs both branches and returns
+        v_uncond + guidance * (v_cond - v_uncond)."""
         import torch
         bf = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).cuda()
         f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
-        self._setup(hidden, heads, head_dim, mlp, channels, n_img, weights["h_txt"].shape[0])
+        self._setup(hidden, heads, head_dim, mlp, channels, n_img, weights["h_txt"].shape[0], 1 if h_txt_uncond is None else 2, guidance)
         self.w_embed = rg.pack_weight(self.ctx, bf(weights["embed"]["w"]))
         self.b_embed_host = np.asarray(weights["embed"]["b"], dtype=np.float32)
         self.b_time_host = np.asarray(weights["embed"]["b_time"], dtype=np.float32)
         self.w_head, self.b_head = rg.pack_weight(self.ctx, bf(weights["head"]["w"])), f32(weights["head"]["b"])
-        self.h_txt = bf(weights["h_txt"])
+        self.h_txt = [bf(weights["h_txt"])] + ([] if h_txt_uncond is None else [bf(h_txt_uncond)])
         for kind, streams in weights["blocks"]:
             self._add_block(kind, [{k: (rg.pack_weight(self.ctx, bf(a)) if k.startswith("w_") else f32(a)) for k, a in w.items()}
                                    for w in streams])
-        self.h_a[:self.n_txt].copy_(self.h_txt)     # text rows of the block input never change
 
     @classmethod
     def synthetic(cls, hidden: int, heads: int, head_dim: int, mlp: int, channels: int, n_img: int, n_txt: int,
-                  n_double: int, n_single: int, seed: int = 0, std: float = 0.02):
+                  n_double: int, n_single: int, seed: int = 0, std: float = 0.02, guidance=None):
         """The same architecture with N(0, std) weights drawn on the device (for models too large to draw on the host:
         19 double + 38 single blocks at 3072 wide are 17 GB).  For timing only: no oracle sees these weights."""
         import torch
         self = cls.__new__(cls)
-        self._setup(hidden, heads, head_dim, mlp, channels, n_img, n_txt)
+        self._setup(hidden, heads, head_dim, mlp, channels, n_img, n_txt, 1 if guidance is None else 2, 1.0 if guidance is None else guidance)
         g = torch.Generator(device="cuda")
         g.manual_seed(seed)
         rnd = lambda *shape, scale=std: (torch.randn(shape, device="cuda", generator=g) * scale)
@@ -51,7 +55,7 @@ class EditorModel:
         self.b_time_host = (0.5 * np.random.default_rng(seed + 1).standard_normal(hidden)).astype(np.float32)
         # head scaled so that the velocity has the spread of the small test models (0.02 * sqrt(256) = 0.32) at any width
         self.w_head, self.b_head = wt(channels, hidden, 0.32 / float(np.sqrt(hidden))), rnd(channels)
-        self.h_txt = rnd(n_txt, hidden, scale=1.0).to(torch.bfloat16)
+        self.h_txt = [rnd(n_txt, hidden, scale=1.0).to(torch.bfloat16) for _ in range(self.n_branches)]
 
         def stream(kind):
             t = {}
@@ -70,22 +74,23 @@ class EditorModel:
             self._add_block("double", [stream("double"), stream("double")])
         for _ in range(n_single):
             self._add_block("single", [stream("single")])
-        self.h_a[:self.n_txt].copy_(self.h_txt)
         return self
 
-    def _setup(self, hidden, heads, head_dim, mlp, channels, n_img, n_txt):
+    def _setup(self, hidden, heads, head_dim, mlp, channels, n_img, n_txt, n_branches=1, guidance=1.0):
         import torch
         self.torch = torch
         self.hidden, self.heads, self.head_dim, self.mlp, self.channels = hidden, heads, head_dim, mlp, channels
         self.n_img, self.n_txt = n_img, n_txt
         self.n_all = n_txt + 2 * n_img
-        self.ctx = rg.Context(hidden, heads, head_dim, mlp, self.n_all, n_img)
+        self.n_branches, self.guidance = n_branches, float(guidance)
+        self.ctx = rg.Context(hidden, heads, head_dim, mlp, n_branches * self.n_all, n_img)
         self.blocks, self._keep = [], []
         dev = "cuda"
-        self.h_a = torch.empty((self.n_all, hidden), dtype=torch.bfloat16, device=dev)
+        self.h_a = torch.empty((n_branches, self.n_all, hidden), dtype=torch.bfloat16, device=dev)   # [branch, row, H]
         self.h_b = torch.empty_like(self.h_a)
         self.rows_bf = torch.empty((2 * n_img, channels), dtype=torch.bfloat16, device=dev)
-        self.u = torch.empty((n_img, hidden), dtype=torch.bfloat16, device=dev)
+        self.u = torch.empty((n_branches * n_img, hidden), dtype=torch.bfloat16, device=dev)
+        self.v_branch = torch.empty((n_branches, n_img, channels), dtype=torch.float32, device=dev)
         self.all_slots = torch.arange(self.n_all, dtype=torch.int32, device=dev)
 
     def _add_block(self, kind: str, streams):
@@ -95,7 +100,7 @@ class EditorModel:
         for name, t in zip(("txt", "img") if kind == "double" else ("img",), streams):
             self._keep.append(t)
             setattr(bw, name, rg.make_stream_weights(t))
-        kc = torch.zeros((self.n_all, self.heads, self.head_dim), dtype=torch.bfloat16, device="cuda")
+        kc = torch.zeros((self.n_branches, self.n_all, self.heads, self.head_dim), dtype=torch.bfloat16, device="cuda")
         self.blocks.append((rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE, bw, kc, torch.zeros_like(kc)))
 
     def _embed_bias(self, t: float):
@@ -107,36 +112,56 @@ class EditorModel:
         rg.regione_layernorm(self.ctx, h_rows, rg.BF16, n, self.hidden, None, None, self.u)
         rg.regione_linear(self.ctx, self.u, self.w_head, self.b_head, n, self.channels, self.hidden, rg.ACT_NONE, rg.FP32, v_out)
 
+    def _guided(self, v_branches, n, v_out):
+        """v_branches: [2, >= n, C] float32 (conditional, unconditional) -> the guided velocity in v_out."""
+        rg.regione_guidance_combine(self.ctx, v_branches[0], v_branches[1], self.guidance, v_out, n * self.channels, rg.FP32)
+
     def full_forward(self, x, x_ref, t: float, store: bool, v_out):
         """Velocity of all image rows from the full sequence; with `store`, every block writes its K,V cache."""
-        ctx, n_img, n_txt = self.ctx, self.n_img, self.n_txt
+        ctx, n_img, n_txt, B = self.ctx, self.n_img, self.n_txt, self.n_branches
         rg.regione_cast(ctx, x, rg.FP32, self.rows_bf[:n_img], rg.BF16, n_img * self.channels)
         rg.regione_cast(ctx, x_ref, rg.FP32, self.rows_bf[n_img:], rg.BF16, n_img * self.channels)
         bias = self._embed_bias(t)
         rg.regione_linear(ctx, self.rows_bf, self.w_embed, bias, 2 * n_img, self.hidden, self.channels, rg.ACT_NONE, rg.BF16,
-                          self.h_a[n_txt:])
-        self.h_a[:n_txt].copy_(self.h_txt)
+                          self.h_a[0][n_txt:])
+        for b in range(B):     # the branches differ in their text rows only
+            self.h_a[b][:n_txt].copy_(self.h_txt[b])
+            if b > 0:
+                self.h_a[b][n_txt:].copy_(self.h_a[0][n_txt:])
         src, dst = self.h_a, self.h_b
         for block_type, bw, kc, vc in self.blocks:
-            rg.regione_block_forward(ctx, bw, block_type, src, dst, rg.BF16, self.n_all, n_txt, self.all_slots, 0, kc, vc,
-                                     self.n_all, rg.FLAG_STORE if store else 0)
+            rg.regione_block_forward_batched(ctx, bw, block_type, src, dst, rg.BF16, B, self.n_all, n_txt, self.all_slots, 0, kc, vc,
+                                             self.n_all, rg.FLAG_STORE if store else 0)
             src, dst = dst, src
-        self._head(src[n_txt:n_txt + n_img], n_img, v_out)
+        if B == 1:
+            self._head(src[0][n_txt:n_txt + n_img], n_img, v_out)
+            return
+        for b in range(B):
+            self._head(src[b][n_txt:n_txt + n_img], n_img, self.v_branch[b])
+        self._guided(self.v_branch, n_img, v_out)
 
     def region_forward(self, x_e, e_index, n_e: int, t: float, v_out):
         """Velocity of the edited rows alone; keys and values of all other rows come from the caches (Eq.6)."""
-        ctx = self.ctx
+        ctx, B = self.ctx, self.n_branches
         if n_e == 0:
             return
         rg.regione_cast(ctx, x_e, rg.FP32, self.rows_bf, rg.BF16, n_e * self.channels)
         bias = self._embed_bias(t)
-        rg.regione_linear(ctx, self.rows_bf, self.w_embed, bias, n_e, self.hidden, self.channels, rg.ACT_NONE, rg.BF16, self.h_a)
-        src, dst = self.h_a, self.h_b
+        # rows of all branches form one [B, n_e, H] array at the start of the buffers
+        src, dst = self.h_a.view(-1, self.hidden), self.h_b.view(-1, self.hidden)
+        rg.regione_linear(ctx, self.rows_bf, self.w_embed, bias, n_e, self.hidden, self.channels, rg.ACT_NONE, rg.BF16, src)
+        for b in range(1, B):
+            src[b * n_e:(b + 1) * n_e].copy_(src[:n_e])
         for block_type, bw, kc, vc in self.blocks:
-            rg.regione_block_forward(ctx, bw, block_type, src, dst, rg.BF16, n_e, 0, e_index, self.n_txt, kc, vc, self.n_all,
-                                     rg.FLAG_RETRIEVE)
+            rg.regione_block_forward_batched(ctx, bw, block_type, src, dst, rg.BF16, B, n_e, 0, e_index, self.n_txt, kc, vc, self.n_all,
+                                             rg.FLAG_RETRIEVE)
             src, dst = dst, src
-        self._head(src, n_e, v_out)
+        if B == 1:
+            self._head(src, n_e, v_out)
+            return
+        v = self.v_branch.view(-1, self.channels)
+        self._head(src, B * n_e, v)
+        self._guided((v[:n_e], v[n_e:2 * n_e]), n_e, v_out)
 
     def close(self):
         self.ctx.close()

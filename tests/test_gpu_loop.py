@@ -100,3 +100,28 @@ def test_loop_with_mask_cleanup():
     assert log == log_want
     assert_close(x0.cpu().numpy().astype(np.float64) - x_T, x0_want - x_T, "displacement of the latents, cleaned partition")
     model.close()
+
+
+def test_guided_loop_matches_oracle_loop():
+    """Classifier-free guidance (two branches per step, as in the paper's experiments): the batched model against the
+    oracle's loop on the guided velocity."""
+    want, x_T, x_ref, weights, t = _setup(inputs.workload_seed(4, 3), n_double=1, n_single=2)
+    rng = np.random.default_rng(inputs.workload_seed(4, 4))
+    h_txt_uncond = inputs.bf16_round(rng.standard_normal(weights["h_txt"].shape).astype(np.float32))
+    gamma = np.ones(T + 1)
+    scale = 2.5
+    ref_model = EditorReference(weights, HEADS, GRID * GRID, x_ref, t, h_txt_uncond=h_txt_uncond, guidance=scale)
+    x0_want, log_want = orc.regione_loop(ref_model.phi, x_T, x_ref, t, gamma, T, T_ST, T_SM, FORCED, ETA, 0.04)
+    plain = EditorReference(weights, HEADS, GRID * GRID, x_ref, t)
+    x0_plain, _ = orc.regione_loop(plain.phi, x_T, x_ref, t, gamma, T, T_ST, T_SM, FORCED, ETA, 0.04)
+    assert np.abs(x0_want - x0_plain).max() > 2e-3         # the guidance does change the edit (32 of 544 keys are text rows)
+    model = loop.EditorModel(weights, HIDDEN, HEADS, D, MLP, C, GRID * GRID, h_txt_uncond=h_txt_uncond, guidance=scale)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    x0, log = loop.run_loop(model, dev(x_T), dev(x_ref), [float(v) for v in t], [float(g) for g in gamma], T, T_ST, T_SM, FORCED, ETA, 0.04)
+    assert log == log_want
+    # the guided velocity is scale * v_cond - (scale - 1) * v_unc: each branch's rounding enters with its weight,
+    # so the bound of a single forward grows by (2 * scale - 1)
+    ma, mr = assert_close(x0.cpu().numpy().astype(np.float64) - x_T, x0_want - x_T, "displacement of the latents, guided loop",
+                          max_abs=2e-2 * (2 * scale - 1), mean_rel_tol=5e-3 * (2 * scale - 1))
+    print(f"guided loop: max abs {ma:.3e}, mean rel {mr:.3e}")
+    model.close()
