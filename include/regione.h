@@ -224,7 +224,7 @@ int regione_rope_table(regione_ctx* ctx, const int32_t* pos_ids, int64_t n, int3
 
 /* The same block for n_branches independent sequences that share weights, slot list and flags:
  * the conditional and unconditional branch of classifier-free guidance, which the paper's
- * experiments run at every step ("Experiment settings").  h_in / h_out are
+ * experiments run at every step ("Experimental Settings").  h_in / h_out are
  * [n_branches, n_fresh, H], k_cache / v_cache [n_branches, n_all, heads, head_dim]; the result is
  * that of n_branches regione_block_forward calls on the slices.  When no text row is fresh (or
  * the block is single-stream) every projection runs once over all n_branches * n_fresh rows, so
@@ -280,7 +280,7 @@ typedef struct regione_plan_step {
 int regione_stage_plan_host(int32_t T, int32_t t_st, int32_t t_sm, const int32_t* forced_k, int32_t n_forced,
                             regione_plan_step* steps_out, int32_t max_steps, int32_t* n_steps_out);
 
-/* Classifier-free guidance ("Experiment settings": on in every experiment of the paper): the
+/* Classifier-free guidance ("Experimental Settings": on in every experiment of the paper): the
  * velocity the sampler uses, out[i] = v_uncond[i] + scale * (v_cond[i] - v_uncond[i]), in
  * float32; the three arrays have n_elems elements of `dtype`, out may be one of the inputs. */
 int regione_guidance_combine(regione_ctx* ctx, const void* v_cond, const void* v_uncond, float scale, void* out,

@@ -386,7 +386,7 @@ def decay_factor(t, gamma, j: int) -> float:
 
 
 def guidance_combine(v_cond, v_uncond, scale: float) -> np.ndarray:
-    """Classifier-free guidance, which the paper's experiments keep on ("Experiment settings"):
+    """Classifier-free guidance, which the paper's experiments keep on ("Experimental Settings"):
     the velocity used by the sampler is v_uncond + scale * (v_cond - v_uncond)."""
     v_c = np.asarray(v_cond, dtype=F64)
     v_u = np.asarray(v_uncond, dtype=F64)

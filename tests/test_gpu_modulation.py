@@ -116,3 +116,29 @@ def test_gamma_fit_from_device_norms(ctx):
     assert np.allclose(got[1:T], gamma[1:T], rtol=1e-5)
     want = orc.fit_gamma(np.sqrt((v.astype(np.float64) ** 2).sum(axis=2)), t)
     assert np.allclose(got, want, rtol=1e-5)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_guidance_combine_matches_oracle(ctx, dtype):
+    from oracle import regione_oracle as orc
+    rng = np.random.default_rng(4400)
+    n = 4096 * 64 + 5
+    vc = rng.standard_normal(n).astype(np.float32); vu = rng.standard_normal(n).astype(np.float32)
+    if dtype == "bf16":
+        vc, vu = inputs.bf16_round(vc), inputs.bf16_round(vu)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    code = rg.BF16 if dtype == "bf16" else rg.FP32
+    dc, du = torch.from_numpy(vc).cuda().to(tdt), torch.from_numpy(vu).cuda().to(tdt)
+    out = torch.full((n + 1,), 3.0, dtype=tdt, device="cuda")
+    rg.regione_guidance_combine(ctx, dc, du, 2.5, out, n, code)
+    want = orc.guidance_combine(vc, vu, 2.5)
+    got = out.float().cpu().numpy()
+    assert got[n] == 3.0
+    tol = 2.0 ** -8 * np.abs(want).max() if dtype == "bf16" else 1e-6 * np.abs(want).max()
+    assert np.abs(got[:n] - want).max() <= tol
+    # in place on the conditional velocity; scale 1 returns it, scale 0 the unconditional one
+    rg.regione_guidance_combine(ctx, dc, du, 1.0, dc, n, code)
+    assert np.abs(dc.float().cpu().numpy() - vc).max() <= (2.0 ** -8 if dtype == "bf16" else 1e-6) * np.abs(vc).max()
+    rg.regione_guidance_combine(ctx, dc, du, 0.0, out, n, code)
+    assert torch.equal(out[:n], du)
+    rg.regione_guidance_combine(ctx, dc, du, 2.0, out, 0, code)      # nothing to do
