@@ -34,6 +34,8 @@ class EditorReference:
         self.t = t
         d = self.hidden // heads
         self.caches = [(np.zeros((self.n_all, heads, d)), np.zeros((self.n_all, heads, d))) for _ in weights["blocks"]]
+        # block extras: rotary angles of every position of the sequence (streams may carry q_norm / k_norm as well)
+        self.rope = orc.rope_angles(weights["positions"], weights["rope_axes"]) if "positions" in weights else None
         self.calls = []
 
     def _embed(self, rows, t):
@@ -58,7 +60,7 @@ class EditorReference:
             slots = np.arange(self.n_all)
             flags = orc.FLAG_STORE if mode == "full_store" else 0
             for (kind, streams), (kc, vc) in zip(self.w["blocks"], self.caches):
-                h = orc.block_forward(streams, kind, h, self.n_txt, slots, kc, vc, flags, self.heads)
+                h = orc.block_forward(streams, kind, h, self.n_txt, slots, kc, vc, flags, self.heads, rope=self.rope)
             return self._head(h[self.n_txt:self.n_txt + self.n_img])
         if mode != "region":
             raise ValueError(mode)
@@ -67,5 +69,5 @@ class EditorReference:
         h = self._embed(np.asarray(x_rows, dtype=np.float64), t)
         slots = self.n_txt + np.asarray(row_index, dtype=np.int64)
         for (kind, streams), (kc, vc) in zip(self.w["blocks"], self.caches):
-            h = orc.block_forward(streams, kind, h, 0, slots, kc, vc, orc.FLAG_RETRIEVE, self.heads)
+            h = orc.block_forward(streams, kind, h, 0, slots, kc, vc, orc.FLAG_RETRIEVE, self.heads, rope=self.rope)
         return self._head(h)

@@ -183,6 +183,23 @@ def model_weights(rng: np.random.Generator, hidden: int, mlp: int, channels: int
     return {"embed": embed, "blocks": blocks, "head": head, "h_txt": h_txt}
 
 
+def add_block_extras(rng: np.random.Generator, weights: dict, head_dim: int, grid: int, n_txt: int):
+    """Switches on the block extras of a model made by model_weights: query/key normalisation vectors for every
+    stream, and the positions of the sequence [text | image | reference] on three axes (text (0,0,0), image (0,y,x),
+    reference (1,y,x)) with the axes' shares of the head dimension (1/8, 7/16, 7/16).  Drawn after everything else, so
+    the other arrays are those of the plain model."""
+    for _, streams in weights["blocks"]:
+        for w in streams:
+            w["q_norm"] = (1.0 + 0.1 * rng.standard_normal(head_dim)).astype(np.float32)
+            w["k_norm"] = (1.0 + 0.1 * rng.standard_normal(head_dim)).astype(np.float32)
+    yy, xx = np.meshgrid(np.arange(grid), np.arange(grid), indexing="ij")
+    pos = [np.zeros((n_txt, 3), dtype=np.int32)]
+    pos += [np.stack([np.full(grid * grid, img), yy.ravel(), xx.ravel()], axis=1).astype(np.int32) for img in (0, 1)]
+    weights["positions"] = np.concatenate(pos, axis=0)
+    weights["rope_axes"] = (head_dim // 8, 7 * head_dim // 16, 7 * head_dim // 16)
+    return weights
+
+
 def loop_latents(rng: np.random.Generator, want_edited: np.ndarray, channels: int, noise: float = 0.1):
     """Start of a sampling loop whose partition is decided by construction: reference latents ~ N(0,1); the
     starting latents equal the reference plus a little noise on the rows that should stay unedited and are

@@ -34,6 +34,10 @@ class EditorModel:
         self.b_time_host = np.asarray(weights["embed"]["b_time"], dtype=np.float32)
         self.w_head, self.b_head = rg.pack_weight(self.ctx, bf(weights["head"]["w"])), f32(weights["head"]["b"])
         self.h_txt = [bf(weights["h_txt"])] + ([] if h_txt_uncond is None else [bf(h_txt_uncond)])
+        if "positions" in weights:   # block extras: rotary table of the whole sequence, shared by all blocks
+            self.rope_table = torch.empty((self.n_all, head_dim), dtype=torch.float32, device="cuda")
+            rg.regione_rope_table(self.ctx, torch.from_numpy(np.ascontiguousarray(weights["positions"], dtype=np.int32)).cuda(), self.n_all,
+                                  list(weights["rope_axes"]), 10000.0, self.rope_table)
         for kind, streams in weights["blocks"]:
             self._add_block(kind, [{k: (rg.pack_weight(self.ctx, bf(a)) if k.startswith("w_") else f32(a)) for k, a in w.items()}
                                    for w in streams])
@@ -100,6 +104,8 @@ class EditorModel:
         for name, t in zip(("txt", "img") if kind == "double" else ("img",), streams):
             self._keep.append(t)
             setattr(bw, name, rg.make_stream_weights(t))
+        if getattr(self, "rope_table", None) is not None:
+            bw.rope, bw.rope_rows = self.rope_table.data_ptr(), self.n_all
         kc = torch.zeros((self.n_branches, self.n_all, self.heads, self.head_dim), dtype=torch.bfloat16, device="cuda")
         self.blocks.append((rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE, bw, kc, torch.zeros_like(kc)))
 

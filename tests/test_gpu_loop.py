@@ -125,3 +125,20 @@ def test_guided_loop_matches_oracle_loop():
                           max_abs=2e-2 * (2 * scale - 1), mean_rel_tol=5e-3 * (2 * scale - 1))
     print(f"guided loop: max abs {ma:.3e}, mean rel {mr:.3e}")
     model.close()
+
+
+def test_loop_with_block_extras_matches_oracle_loop():
+    """Query/key normalisation and rotary embedding in every block: edited rows keep their positions through the
+    gathers of the region-aware stage, and the cached keys they attend to were rotated when they were stored."""
+    want, x_T, x_ref, weights, t = _setup(inputs.workload_seed(4, 5), n_double=1, n_single=2)
+    inputs.add_block_extras(np.random.default_rng(inputs.workload_seed(4, 6)), weights, D, GRID, N_TXT)
+    gamma = np.ones(T + 1)
+    ref_model = EditorReference(weights, HEADS, GRID * GRID, x_ref, t)
+    x0_want, log_want = orc.regione_loop(ref_model.phi, x_T, x_ref, t, gamma, T, T_ST, T_SM, FORCED, ETA, 0.04)
+    model = loop.EditorModel(weights, HIDDEN, HEADS, D, MLP, C, GRID * GRID)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    x0, log = loop.run_loop(model, dev(x_T), dev(x_ref), [float(v) for v in t], [float(g) for g in gamma], T, T_ST, T_SM, FORCED, ETA, 0.04)
+    assert log == log_want
+    ma, mr = assert_close(x0.cpu().numpy().astype(np.float64) - x_T, x0_want - x_T, "displacement of the latents, blocks with extras")
+    print(f"loop with block extras: max abs {ma:.3e}, mean rel {mr:.3e}")
+    model.close()
