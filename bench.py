@@ -121,7 +121,6 @@ def cfg_benchmark(steps: int, warmup: int):
     import torch
     from paper_2510_25590_amd import binding as rg
     from paper_2510_25590_amd import step
-    import dataclasses
     cfg = step.CONFIG_BLOCK
     wl = step.RegionStepWorkload(cfg)
     n = wl.step()
