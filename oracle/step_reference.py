@@ -30,14 +30,22 @@ def build_cache(streams, kind, h_store, n_txt, heads):
 
 
 def region_step(x_t, v_prev, x_ref, h_now, streams, kind, w_head, b_head, k_cache, v_cache,
-                n_txt, heads, sigma, eta, dt):
+                n_txt, heads, sigma, eta, dt, h_txt=None):
     """partition -> gather -> block with the retrieve flag (Eq.6) -> velocity head -> velocity cache
-    (fresh step, Eq.9) + Euler (Eq.4) -> scatter.  Returns a dict of every intermediate."""
+    (fresh step, Eq.9) + Euler (Eq.4) -> scatter.  Returns a dict of every intermediate.
+    With h_txt [n_txt, H] the block's input is [X^P, X^E] as in Algorithm 1: the text rows are
+    fresh too (recomputed, their keys and values replace the cached ones)."""
     score, mask, e_index, u_index = orc.partition(x_t, v_prev, x_ref, sigma, eta)
     h_e = orc.gather(np.asarray(h_now, dtype=np.float64), e_index)
     x_e = orc.gather(np.asarray(x_t, dtype=np.float64), e_index)
     slots = n_txt + e_index.astype(np.int64)
-    h_e_out = orc.block_forward(streams, kind, h_e, 0, slots, k_cache, v_cache, orc.FLAG_RETRIEVE, heads)
+    if h_txt is None:
+        h_e_out = orc.block_forward(streams, kind, h_e, 0, slots, k_cache, v_cache, orc.FLAG_RETRIEVE, heads)
+    else:
+        rows = np.concatenate([np.asarray(h_txt, dtype=np.float64), h_e], axis=0)
+        out = orc.block_forward(streams, kind, rows, n_txt, np.concatenate([np.arange(n_txt), slots]), k_cache, v_cache,
+                                orc.FLAG_RETRIEVE, heads)
+        h_e_out = out[n_txt:]
     v_e = orc.linear(h_e_out, w_head, b_head)
     v_used, c_a, x_e_new = orc.velocity_cache_apply(False, 1.0, dt, v_e, None, x_e)
     x_next = orc.scatter(np.asarray(x_t, dtype=np.float64).copy(), e_index, x_e_new)

@@ -37,6 +37,7 @@ class StepConfig:
     eta: float = 0.9
     dt: float = 1.0 / 28.0
     seed: int = 2000
+    text_fresh: bool = False  # region step input [X^P, X^E] as in Algorithm 1 (text rows recomputed), not X^E alone with the text in the cache
     extras: bool = False      # query/key RMS normalisation and rotary embedding (positions: text (0,0,0), image (0,y,x), reference (1,y,x))
 
 
@@ -113,8 +114,15 @@ class RegionStepWorkload:
         self.e_index = torch.empty(n_img, dtype=torch.int32, device=dev)
         self.u_index = torch.empty(n_img, dtype=torch.int32, device=dev)
         self.n_dev = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.h_e = torch.empty((n_img, cfg.hidden), dtype=torch.bfloat16, device=dev)
-        self.h_e_out = torch.empty_like(self.h_e)
+        # fresh rows of the block: [text rows (only with text_fresh) | edited rows]
+        self.n_txt_fresh = cfg.n_txt if cfg.text_fresh else 0
+        self.h_fresh = torch.empty((self.n_txt_fresh + n_img, cfg.hidden), dtype=torch.bfloat16, device=dev)
+        self.h_fresh_out = torch.empty_like(self.h_fresh)
+        self.h_e, self.h_e_out = self.h_fresh[self.n_txt_fresh:], self.h_fresh_out[self.n_txt_fresh:]
+        if cfg.text_fresh:
+            self.h_fresh[:cfg.n_txt].copy_(bf(hst["h_store"][:cfg.n_txt]))
+            self.slots = torch.empty(cfg.n_txt + n_img, dtype=torch.int32, device=dev)   # positions of the fresh rows in [P | X | I]
+            self.slots[:cfg.n_txt].copy_(torch.arange(cfg.n_txt, dtype=torch.int32, device=dev))
         self.x_e = torch.empty((n_img, cfg.channels), dtype=torch.bfloat16, device=dev)
         self.v_e = torch.empty_like(self.x_e)
         self.c_a = torch.zeros_like(self.x_e)
@@ -139,8 +147,14 @@ class RegionStepWorkload:
         self.n_edited = n
         rg.regione_gather(ctx, self.h_now, cfg.hidden, rg.BF16, self.e_index, self.n_dev, n, self.h_e)
         rg.regione_gather(ctx, self.x_t, cfg.channels, rg.BF16, self.e_index, self.n_dev, n, self.x_e)
-        rg.regione_block_forward(ctx, self.weights, self.block_type, self.h_e, self.h_e_out, rg.BF16, n, 0,
-                                 self.e_index, cfg.n_txt, self.k_cache, self.v_cache, self.n_all, rg.FLAG_RETRIEVE)
+        if cfg.text_fresh:
+            torch = self.torch
+            torch.add(self.e_index[:n], cfg.n_txt, out=self.slots[cfg.n_txt:cfg.n_txt + n])
+            rg.regione_block_forward(ctx, self.weights, self.block_type, self.h_fresh, self.h_fresh_out, rg.BF16, cfg.n_txt + n, cfg.n_txt,
+                                     self.slots, 0, self.k_cache, self.v_cache, self.n_all, rg.FLAG_RETRIEVE)
+        else:
+            rg.regione_block_forward(ctx, self.weights, self.block_type, self.h_e, self.h_e_out, rg.BF16, n, 0,
+                                     self.e_index, cfg.n_txt, self.k_cache, self.v_cache, self.n_all, rg.FLAG_RETRIEVE)
         rg.regione_linear(ctx, self.h_e_out, self.w_head, self.b_head, n, cfg.channels, cfg.hidden, rg.ACT_NONE, rg.BF16, self.v_e)
         rg.regione_velocity_cache(ctx, False, 1.0, cfg.dt, self.v_e, self.c_a, None, self.x_e, self.n_dev, n, cfg.channels, rg.BF16)
         rg.regione_scatter(ctx, self.x_next, cfg.channels, rg.BF16, self.e_index, self.n_dev, n, self.x_e)

@@ -40,6 +40,27 @@ def test_tiny_step_matches_oracle_step():
     wl.close()
 
 
+def test_tiny_step_with_fresh_text_rows_matches_oracle_step():
+    """Algorithm 1's region step input [X^P, X^E]: the text rows run through the block again with the edited rows."""
+    import dataclasses
+    cfg = dataclasses.replace(step.CONFIG_TINY, text_fresh=True)
+    wl = step.RegionStepWorkload(cfg)
+    n = wl.step()
+    torch.cuda.synchronize()
+    h = wl.host
+    kc, vc = ref.build_cache(h["streams"], cfg.kind, h["h_store"], cfg.n_txt, cfg.heads)
+    want = ref.region_step(h["x_t"], h["v_prev"], h["x_ref"], h["h_now"], h["streams"], cfg.kind, h["w_head"], h["b_head"],
+                           kc, vc, cfg.n_txt, cfg.heads, cfg.sigma, cfg.eta, cfg.dt, h_txt=h["h_store"][:cfg.n_txt])
+    plain = ref.region_step(h["x_t"], h["v_prev"], h["x_ref"], h["h_now"], h["streams"], cfg.kind, h["w_head"], h["b_head"],
+                            *ref.build_cache(h["streams"], cfg.kind, h["h_store"], cfg.n_txt, cfg.heads), cfg.n_txt, cfg.heads, cfg.sigma, cfg.eta, cfg.dt)
+    assert n == 36
+    assert_close(host(wl.h_e_out)[:n], want["h_e_out"], "block output of the step, text rows fresh", stored_bf16=True)
+    assert_close(host(wl.x_next), want["x_next"], "merged latent, text rows fresh", stored_bf16=True)
+    # the text rows come from the same hidden state the cache was stored from, so both forms agree here
+    assert np.allclose(want["h_e_out"], plain["h_e_out"], atol=1e-9)
+    wl.close()
+
+
 def test_benchmark_step_matches_oracle_step():
     """The launch configuration bench.py times (3072 wide, 820 edited tokens, 8704 keys), full oracle step."""
     cfg = step.CONFIG_BLOCK
