@@ -15,7 +15,9 @@ cache as a decayed velocity cache).
 Parity pins (tests/test_oracle_*.py): closed forms (Eq.2+Eq.5 recover X_0, appendix Eq.13
 with gamma = 1), hand cases, brute force on tiny inputs, torch CPU library routines
 (cosine_similarity, scaled_dot_product_attention, layer_norm, gelu; scipy.ndimage's binary
-erosion and dilation for the mask clean-up) and the structural identities of Eq.6.  Unpinned: none of the functions below; what stays unpinned is the
+erosion and dilation for the mask clean-up; rms_norm and silu for the block extras and the
+conditioning path; numpy's lstsq for the fit of Eq.7's factor) and the structural identities of
+Eq.6.  Unpinned: none of the functions below; what stays unpinned is the
 fidelity of the method on real model weights (PSNR/SSIM figures), which needs the models.
 
 The transformer block is NOT described by the paper (it treats the DiT as a black box
