@@ -449,6 +449,17 @@ def velocity_cache_apply(reuse: bool, factor: float, dt: float, v_fresh, c_a, x_
 # --------------------------------------------------------------------------- Algorithm 1
 
 
+def relative_change(v_new, v_old) -> float:
+    """|v_new - v_old|_2 / |v_old|_2 over all elements: the data-dependent reuse trigger that the
+    loop benchmark's workload description asks for ("reusing v with decay 0.9 when relative
+    velocity change < 0.05").  NOT part of the paper, whose criterion (Eq.8) depends on the
+    schedule alone."""
+    a = np.asarray(v_new, dtype=F64)
+    b = np.asarray(v_old, dtype=F64)
+    den = float(np.sqrt((b ** 2).sum()))
+    return float(np.sqrt(((a - b) ** 2).sum())) / den if den > 0.0 else math.inf
+
+
 def stage_plan(T: int, t_st: int, t_sm: int, forced_k):
     """Control flow of Algorithm 1 as a list of (i, kind) for timestep indices i = T..1
     (the step at index i moves X_{t_i} to X_{t_{i-1}}), kind in {"full", "full_store",
@@ -474,12 +485,21 @@ def stage_plan(T: int, t_st: int, t_sm: int, forced_k):
     return plan, segments
 
 
-def regione_loop(phi, x_T, x_ref, t, gamma, T, t_st, t_sm, forced_k, eta, delta, grid=None):
+def regione_loop(phi, x_T, x_ref, t, gamma, T, t_st, t_sm, forced_k, eta, delta, grid=None, rel_trigger=None,
+                 forced_reuse=None):
     """Algorithm 1 on latents [N, C].  `phi(x_rows, row_index, i, mode)` returns the velocity
     for the rows given (mode "full", "full_store" or "region"; row_index None = all rows).
     Returns (x_0, log) where log lists (i, what) with what in {"full", "full_store",
     "region_fresh", "region_reuse"} and, once, ("partition", n_E).  grid = (rows, columns) of
-    the token grid applies the morphological clean-up to the partition; None leaves it as thresholded."""
+    the token grid applies the morphological clean-up to the partition; None leaves it as thresholded.
+
+    rel_trigger = (threshold, decay) replaces the paper's schedule criterion (Eq.8) by the
+    data-dependent one of the loop benchmark's workload description (see relative_change): after a
+    fresh region step whose velocity differs from the segment's previous fresh velocity by less than
+    `threshold` (relative), the NEXT region step reuses decay * C_A; never two reuses in a row; a
+    segment starts with two fresh steps.  The log then also holds ("rel", i, value) entries.
+    forced_reuse: {i: bool} overrides the decision of step i (a flipped decision changes the whole
+    trajectory, so parity runs force one side's decisions on the other)."""
     plan, segments = stage_plan(T, t_st, t_sm, forced_k)
     x = np.asarray(x_T, dtype=F64).copy()
     log = []
@@ -513,10 +533,21 @@ def regione_loop(phi, x_T, x_ref, t, gamma, T, t_st, t_sm, forced_k, eta, delta,
         x_u = euler_step(x_u, v_u, t[prev] - t[nxt + 1])  # Eq.5: one jump for the unedited rows
         st = AvdState()
         c_a = None
+        reuse_next = False
         for j in range(prev, nxt + 1, -1):
-            reuse, factor = avd_decision(t, gamma, delta, j, st)
+            if rel_trigger is None:
+                reuse, factor = avd_decision(t, gamma, delta, j, st)
+            else:
+                reuse, factor = (reuse_next and c_a is not None), rel_trigger[1]
+                if forced_reuse is not None and j in forced_reuse:
+                    reuse = bool(forced_reuse[j]) and c_a is not None
+                reuse_next = False
             v_fresh = None if reuse else phi(x_e, e_index, j, "region")
-            _, c_a, x_e = velocity_cache_apply(reuse, factor, t[j] - t[j - 1], v_fresh, c_a, x_e)
+            if rel_trigger is not None and not reuse and c_a is not None:
+                rel = relative_change(v_fresh, c_a)
+                log.append(("rel", j, rel))
+                reuse_next = rel < rel_trigger[0]
+            _, c_a, x_e = velocity_cache_apply(reuse, factor if reuse else 1.0, t[j] - t[j - 1], v_fresh, c_a, x_e)
             log.append((j, "region_reuse" if reuse else "region_fresh"))
             pos += 1
         scatter(x, e_index, x_e)

@@ -3,6 +3,7 @@ control flow of Algorithm 1 (CPU only).  Expected values: appendix Eq.13 (gamma 
 product of (1 - dt) factors), arithmetic on the linear 28-step schedule, and the property
 that a constant velocity field makes the sampler exact whatever is partitioned or cached.
 """
+import math
 import numpy as np
 import pytest
 
@@ -152,3 +153,76 @@ def test_loop_unedited_rows_take_one_jump():
     for i in (2, 1):
         x = x - (1 / 28) * base * (1 + 0.01 * i)
     assert np.max(np.abs(x0 - x)) < 1e-12
+
+
+# ---- the data-dependent reuse trigger of the loop benchmark's workload description (not the paper's Eq.8)
+
+
+def test_relative_change_hand_cases():
+    b = np.array([[3.0, 4.0]])
+    assert math.isclose(orc.relative_change(1.1 * b, b), 0.1, rel_tol=1e-12)
+    assert orc.relative_change(b, b) == 0.0
+    assert math.isclose(orc.relative_change(np.array([[4.0, -3.0]]), b), math.sqrt(2.0), rel_tol=1e-12)   # orthogonal, same length
+    assert orc.relative_change(b, np.zeros((1, 2))) == math.inf
+
+
+def _loop_with_velocity(vel, rel_trigger, forced_reuse=None, T=12, t_st=2, t_sm=1, forced_k=()):
+    """Runs the loop on 6 tokens of 2 channels whose first three are 'edited' (they differ from the reference);
+    vel(i) gives the velocity of every row at timestep index i."""
+    n, c = 6, 2
+    x_ref = np.ones((n, c))
+    x_T = np.ones((n, c)); x_T[:3] = [[-1.0, 1.0]] * 3       # cosine 0 with the reference row (1, 1)
+    t = np.linspace(0.0, 1.0, T + 1)
+    calls = []
+
+    def phi(x_rows, row_index, i, mode):
+        calls.append((i, mode))
+        rows = np.arange(n) if row_index is None else np.asarray(row_index)
+        return np.tile(vel(i), (len(rows), 1)) * 0.0 + vel(i)   # same velocity for every row, zero mean drift below
+
+    x0, log = orc.regione_loop(phi, x_T, x_ref, t, np.ones(T + 1), T, t_st, t_sm, list(forced_k), 0.5, 0.04,
+                               rel_trigger=rel_trigger, forced_reuse=forced_reuse)
+    return x0, log, calls, t
+
+
+def test_relative_trigger_constant_velocity_alternates_and_never_reuses_twice():
+    # zero velocity keeps the partition trivial (x never moves); a constant velocity has relative change 0
+    x0, log, calls, t = _loop_with_velocity(lambda i: np.zeros(2), (0.05, 0.9))
+    # zero velocity: |v_old| = 0 -> relative change is infinite, never below the threshold: every step fresh
+    kinds = [w[1] for w in log if w[0] not in ("partition", "rel")]
+    assert "region_reuse" not in kinds
+    x0, log, calls, t = _loop_with_velocity(lambda i: np.array([1e-3, -1e-3]), (0.05, 0.9))
+    steps = [(w[0], w[1]) for w in log if w[0] not in ("partition", "rel")]
+    region = [k for _, k in steps if k.startswith("region")]
+    # a segment starts with two fresh steps (the second measures the change), then reuse and fresh alternate
+    assert region[:4] == ["region_fresh", "region_fresh", "region_reuse", "region_fresh"]
+    assert all(not (a == b == "region_reuse") for a, b in zip(region, region[1:]))
+    rels = [w for w in log if w[0] == "rel"]
+    assert rels and all(w[2] == 0.0 for w in rels)
+
+
+def test_relative_trigger_reused_step_moves_by_the_decayed_cache():
+    v = np.array([2e-3, -1e-3])
+    x0_a, log_a, _, t = _loop_with_velocity(lambda i: v, (0.05, 0.9))
+    x0_b, log_b, _, _ = _loop_with_velocity(lambda i: v, (0.05, 1.0))
+    reused = [w[0] for w in log_a if w[1] == "region_reuse"]
+    assert reused == [w[0] for w in log_b if w[1] == "region_reuse"]
+    # with decay 1 a reused step moves exactly like a fresh one; with 0.9 each reused step moves 10 % less (Eq.4)
+    lost = sum(0.1 * (t[i] - t[i - 1]) for i in reused)
+    assert np.allclose((x0_a - x0_b)[:3], lost * v, atol=1e-15)
+    assert np.allclose((x0_a - x0_b)[3:], 0.0, atol=1e-15)      # unedited rows never see the cache
+
+
+def test_relative_trigger_changing_velocity_never_reuses_and_forced_decisions_override():
+    vel = lambda i: np.array([1e-3 * (1.0 + 0.2 * i), -1e-3])       # changes by far more than 5 % per step
+    x0, log, calls, t = _loop_with_velocity(vel, (0.05, 0.9))
+    assert not any(w[1] == "region_reuse" for w in log)
+    assert all(w[2] > 0.05 for w in log if w[0] == "rel")
+    region_steps = [w[0] for w in log if w[1] == "region_fresh"]
+    forced = {region_steps[2]: True}
+    x0_f, log_f, calls_f, _ = _loop_with_velocity(vel, (0.05, 0.9), forced_reuse=forced)
+    assert (region_steps[2], "region_reuse") in [(w[0], w[1]) for w in log_f]
+    assert (region_steps[2], "region") not in calls_f and (region_steps[2], "region") in calls
+    # the first step of a segment has nothing to reuse: forcing it changes nothing
+    x0_g, log_g, _, _ = _loop_with_velocity(vel, (0.05, 0.9), forced_reuse={region_steps[0]: True})
+    assert [(w[0], w[1]) for w in log_g] == [(w[0], w[1]) for w in log] and np.array_equal(x0_g, x0)
