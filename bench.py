@@ -183,18 +183,24 @@ def loop_benchmark(n_double: int, n_single: int, guidance=None):
     gamma = [1.0] * (T + 1)
     out = {"workload": f"28-step sampling loop, {n_double} double + {n_single} single blocks at 3072 wide, 4096 image + 4096 reference + 512 text tokens"
                        + ("" if guidance is None else f", classifier-free guidance (two branches per step, scale {guidance})")}
+    # "regione": the paper's schedule criterion (Eq.8, gamma = 1, delta = 0.04); "regione_relative_trigger": the data-dependent
+    # trigger of the workload description (reuse 0.9 * cached velocity when two fresh velocities differ by less than 5 %)
     for name, kwargs in (("regione", dict(t_st=t_st, t_sm=t_sm, forced_k=forced, delta=0.04)),
+                         ("regione_relative_trigger", dict(t_st=t_st, t_sm=t_sm, forced_k=forced, delta=0.04, rel_trigger=(0.05, 0.9))),
                          ("vanilla", dict(t_st=T - 1, t_sm=1, forced_k=[], delta=-1.0))):    # every step a full step
         for rep in range(2):    # first pass warms up (allocations, first launches)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            x0, log = loop.run_loop(model, x_T_d, x_ref_d, t, gamma, T, kwargs["t_st"], kwargs["t_sm"], kwargs["forced_k"], 0.8, kwargs["delta"])
+            x0, log = loop.run_loop(model, x_T_d, x_ref_d, t, gamma, T, kwargs["t_st"], kwargs["t_sm"], kwargs["forced_k"], 0.8, kwargs["delta"],
+                                    rel_trigger=kwargs.get("rel_trigger"))
             torch.cuda.synchronize()
             sec = time.perf_counter() - t0
-        kinds = [w[1] for w in log if w[0] != "partition"]
+        kinds = [w[1] for w in log if w[0] not in ("partition", "rel")]
         out[name] = {"seconds": sec, "full_steps": sum(k.startswith("full") for k in kinds), "region_fresh": kinds.count("region_fresh"),
                      "region_reuse": kinds.count("region_reuse"), "n_edited": next((w[1] for w in log if w[0] == "partition"), None),
                      "finite": bool(torch.isfinite(x0).all().item())}
+        if kwargs.get("rel_trigger"):
+            out[name]["relative_changes"] = [round(w[2], 4) for w in log if w[0] == "rel"]
     out["speedup"] = out["vanilla"]["seconds"] / out["regione"]["seconds"]
     out["n_edited_constructed"] = int(want.sum())
     model.close()

@@ -286,6 +286,14 @@ int regione_stage_plan_host(int32_t T, int32_t t_st, int32_t t_sm, const int32_t
 int regione_guidance_combine(regione_ctx* ctx, const void* v_cond, const void* v_uncond, float scale, void* out,
                              int64_t n_elems, int32_t dtype);
 
+/* Sums behind the relative change |v_new - v_old|_2 / |v_old|_2 of two velocities:
+ * out[0] = sum (v_new - v_old)^2, out[1] = sum v_old^2 (float64 on the device, fixed order).
+ * NOT the paper's reuse criterion (Eq.8 depends on the schedule alone): a data-dependent trigger
+ * ("reuse the cached velocity with decay 0.9 when the relative velocity change is below 0.05")
+ * that the loop benchmark's workload description asks for; the sampling loop offers it beside
+ * regione_velocity_decision_host.  The arrays have n_elems elements of `dtype`. */
+int regione_rel_change(regione_ctx* ctx, const void* v_new, const void* v_old, int64_t n_elems, int32_t dtype, double* out);
+
 /* Fitting the timestep-aware factor gamma of Eq.7 ("obtained by fitting on a randomly sampled
  * dataset"; the paper gives no procedure, this is least squares through the origin).
  * regione_sq_norms: out[i] = sum of squares of vector i, for n_vectors contiguous vectors of

@@ -27,7 +27,7 @@ EXPORTS = (
     "regione_packed_weight_elems", "regione_pack_weight", "regione_tune_gemm", "regione_tune_attention",
     "regione_layernorm", "regione_stage_plan_host", "regione_cast", "regione_mask_cleanup", "regione_rope_table",
     "regione_vec_linear", "regione_timestep_embedding", "regione_block_forward_batched",
-    "regione_sq_norms", "regione_gamma_fit_host", "regione_guidance_combine",
+    "regione_sq_norms", "regione_gamma_fit_host", "regione_guidance_combine", "regione_rel_change",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -89,6 +89,7 @@ def lib() -> C.CDLL:
                                                C.POINTER(i32), C.POINTER(f32)],
             "regione_sq_norms": [vp, vp, i32, i64, i64, vp],
             "regione_guidance_combine": [vp, vp, vp, f32, vp, i64, i32],
+            "regione_rel_change": [vp, vp, vp, i64, i32, vp],
             "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
             "regione_pack_weight": [vp, vp, i32, i32, vp],
@@ -204,6 +205,10 @@ def regione_block_forward_batched(ctx, weights: BlockWeights, block_type, h_in, 
                                   slot_index, slot_offset, k_cache, v_cache, n_all, flags):
     _check(lib().regione_block_forward_batched(ctx.handle, C.byref(weights), block_type, _p(h_in), _p(h_out), h_dtype, n_branches, n_fresh,
                                                n_txt_fresh, _p(slot_index), slot_offset, _p(k_cache), _p(v_cache), n_all, flags))
+
+
+def regione_rel_change(ctx, v_new, v_old, n_elems, dtype, out):
+    _check(lib().regione_rel_change(ctx.handle, _p(v_new), _p(v_old), n_elems, dtype, _p(out)))
 
 
 def regione_guidance_combine(ctx, v_cond, v_uncond, scale, out, n_elems, dtype):

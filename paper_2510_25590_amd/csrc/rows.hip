@@ -356,3 +356,46 @@ extern "C" int regione_guidance_combine(regione_ctx* ctx, const void* v_cond, co
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
 }
+
+// ---- relative change of two velocities: the sums behind |a - b|_2 / |b|_2 (a data-dependent reuse trigger that a
+// benchmark description asks for beside the paper's schedule-only criterion of Eq.8)
+namespace {
+template <typename T>
+__global__ void __launch_bounds__(1024)
+rel_change_kernel(const T* __restrict__ a, const T* __restrict__ b, int64_t n, double* __restrict__ out) {
+    double sd = 0.0, sb = 0.0;                       // one workgroup: the order of the sums is fixed
+    for (int64_t i = threadIdx.x; i < n; i += 1024) {
+        float x, y;
+        if constexpr (sizeof(T) == 2) { x = bf16_to_f32(a[i]); y = bf16_to_f32(b[i]); } else { x = a[i]; y = b[i]; }
+        const double d = static_cast<double>(x) - static_cast<double>(y);
+        sd = fma(d, d, sd);
+        sb = fma(static_cast<double>(y), static_cast<double>(y), sb);
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) { sd += __shfl_xor(sd, m, 64); sb += __shfl_xor(sb, m, 64); }
+    __shared__ double part[2][16];
+    if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = sd; part[1][threadIdx.x >> 6] = sb; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) { s0 += part[0][w]; s1 += part[1][w]; }
+        out[0] = s0;
+        out[1] = s1;
+    }
+}
+}  // namespace
+
+extern "C" int regione_rel_change(regione_ctx* ctx, const void* v_new, const void* v_old, int64_t n_elems, int32_t dtype, double* out) {
+    if (!ctx || !out) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rel_change: null context or output");
+    if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rel_change: bad dtype %d", dtype);
+    if (n_elems < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rel_change: n_elems=%lld", static_cast<long long>(n_elems));
+    if (n_elems > 0 && (!v_new || !v_old)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rel_change: null operand");
+    ProfScope prof(ctx, REGIONE_PROF_VELOCITY);
+    if (dtype == REGIONE_BF16)
+        hipLaunchKernelGGL(rel_change_kernel<bf16_t>, dim3(1), dim3(1024), 0, ctx->stream, static_cast<const bf16_t*>(v_new), static_cast<const bf16_t*>(v_old), n_elems, out);
+    else
+        hipLaunchKernelGGL(rel_change_kernel<float>, dim3(1), dim3(1024), 0, ctx->stream, static_cast<const float*>(v_new), static_cast<const float*>(v_old), n_elems, out);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}

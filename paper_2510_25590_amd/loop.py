@@ -173,11 +173,16 @@ class EditorModel:
         self.ctx.close()
 
 
-def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: int, forced_k, eta: float, delta: float, grid=None):
+def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: int, forced_k, eta: float, delta: float, grid=None,
+             rel_trigger=None, forced_reuse=None):
     """Algorithm 1.  x_T, x_ref: float32 CUDA tensors [n_img, channels]; t, gamma: host sequences of T+1 floats
     (t[T] = 1, t[0] = 0).  Returns (x_0 tensor, log) with log entries (i, what) for every step and one
     ("partition", n_edited); what is "full", "full_store", "region_fresh" or "region_reuse".  grid = (rows, columns)
-    of the token grid applies the morphological clean-up to the partition."""
+    of the token grid applies the morphological clean-up to the partition.
+    rel_trigger = (threshold, decay): instead of the paper's schedule criterion (Eq.8) the next region step reuses
+    decay * C_A when the fresh velocity just computed differs from the previous fresh one by less than `threshold`
+    (relative L2 change, `regione_rel_change`); never two reuses in a row; the log then also holds ("rel", i, value).
+    forced_reuse {i: bool} overrides the decision of step i."""
     torch = model.torch
     ctx, n_img, c = model.ctx, model.n_img, model.channels
     dev = "cuda"
@@ -194,6 +199,8 @@ def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: 
     x_u, v_u = torch.empty_like(x), torch.empty_like(x)
     n_e = None
     log = []
+    rel_sums = torch.zeros(2, dtype=torch.float64, device=dev)
+    have_cache, reuse_next = False, False
     state = rg.AvdState()
     steps = rg.regione_stage_plan_host(T, t_st, t_sm, forced_k)
     for pos, st in enumerate(steps):
@@ -217,9 +224,27 @@ def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: 
             # one jump of the unedited rows to the end of the segment with the last full velocity (Eq.5)
             rg.regione_velocity_cache(ctx, True, 1.0, float(t[i] - t[st.seg_next + 1]), None, v_u, None, x_u, n_u_dev, n_img - n_e, c, rg.FP32)
             state = rg.AvdState()
-        reuse, factor = rg.regione_velocity_decision_host(t, gamma, T, delta, i, state)
+            have_cache, reuse_next = False, False
+        if rel_trigger is None:
+            reuse, factor = rg.regione_velocity_decision_host(t, gamma, T, delta, i, state)
+        else:
+            reuse, factor = (reuse_next and have_cache), float(rel_trigger[1])
+            if forced_reuse is not None and i in forced_reuse:
+                reuse = bool(forced_reuse[i]) and have_cache
+            reuse_next = False
         if not reuse:
             model.region_forward(x_e, e_index, n_e, t[i], v_e)
+            if rel_trigger is not None and have_cache:     # c_a still holds the previous fresh velocity
+                rel = float("inf")
+                if n_e > 0:
+                    rg.regione_rel_change(ctx, v_e, c_a, n_e * c, rg.FP32, rel_sums)
+                    torch.cuda.synchronize()                # the decision is taken on the host
+                    s_diff, s_old = rel_sums.tolist()
+                    rel = (s_diff ** 0.5) / (s_old ** 0.5) if s_old > 0.0 else float("inf")
+                log.append(("rel", i, rel))
+                reuse_next = rel < rel_trigger[0]
+            factor = 1.0
+        have_cache = True
         rg.regione_velocity_cache(ctx, reuse, factor, float(t[i] - t[i - 1]), None if reuse else v_e, c_a, None, x_e, n_e_dev, n_e, c, rg.FP32)
         log.append((i, "region_reuse" if reuse else "region_fresh"))
         last_of_segment = pos + 1 == len(steps) or steps[pos + 1].kind != rg.STEP_REGION

@@ -178,7 +178,7 @@ def _loop_with_velocity(vel, rel_trigger, forced_reuse=None, T=12, t_st=2, t_sm=
     def phi(x_rows, row_index, i, mode):
         calls.append((i, mode))
         rows = np.arange(n) if row_index is None else np.asarray(row_index)
-        return np.tile(vel(i), (len(rows), 1)) * 0.0 + vel(i)   # same velocity for every row, zero mean drift below
+        return np.tile(vel(i), (len(rows), 1))   # the same velocity for every row
 
     x0, log = orc.regione_loop(phi, x_T, x_ref, t, np.ones(T + 1), T, t_st, t_sm, list(forced_k), 0.5, 0.04,
                                rel_trigger=rel_trigger, forced_reuse=forced_reuse)
