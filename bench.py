@@ -49,6 +49,17 @@ def membound(torch, rg):
     res = {}
     n_tok, c = 2048 * 4096, 64                      # 2048 images of 64x64 tokens: 3 x 1 GiB of bf16 latents
     ctx = rg.Context(256, 4, 64, 1024, 16, n_tok)
+    # launch floor: the smallest kernel of the library (an 8-element copy), timed like everything else by the event
+    # pairs around its launch; the single-image figures of the step ("kernels" above) are to be read against it
+    tiny_src = torch.zeros(8, dtype=torch.float32, device="cuda"); tiny_dst = torch.zeros_like(tiny_src)
+    rg.regione_profile_enable(ctx, True)
+    for _ in range(5):
+        rg.regione_cast(ctx, tiny_src, rg.FP32, tiny_dst, rg.FP32, 8)
+    rg.regione_profile_read(ctx)
+    for _ in range(50):
+        rg.regione_cast(ctx, tiny_src, rg.FP32, tiny_dst, rg.FP32, 8)
+    res["launch_floor_us"] = rg.regione_profile_read(ctx)["rows"][0] / 50 * 1e3
+    rg.regione_profile_enable(ctx, False)
     g = torch.Generator(device="cuda"); g.manual_seed(5)
     ref = torch.randn((n_tok, c), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     noise = torch.randn((n_tok, c), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
@@ -162,6 +173,47 @@ def cfg_benchmark(steps: int, warmup: int):
             "config": {"workload": cfg.name + "; block only, two branches", "n_edited_per_branch": n}, "detail": res}
 
 
+def stack_benchmark():
+    """The large-image configuration: 60 double-stream blocks at 3072 wide, 96x96 image + 9216 reference + 1024 text
+    tokens (19456 rows, 14.3 GB of KV cache), 15 % of the image edited (1382 tokens of a blob): one storing full step
+    and one region step through the whole stack."""
+    import numpy as np
+    import torch
+    from paper_2510_25590_amd import binding as rg, inputs, loop
+    grid, channels, n_txt, n_blocks = 96, 64, 1024, 60
+    n_img = grid * grid
+    rng = np.random.default_rng(inputs.workload_seed(5, 1))
+    want = inputs.blob_mask(rng, grid, grid, 1382)
+    x_T, x_ref = inputs.loop_latents(rng, want, channels)
+    model = loop.EditorModel.synthetic(3072, 24, 128, 12288, channels, n_img, n_txt, n_blocks, 0, seed=5)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    x, x_r = dev(x_T), dev(x_ref)
+    v = torch.zeros_like(x)
+    e = torch.from_numpy(np.nonzero(want)[0].astype(np.int32)).cuda()
+    n_e = int(want.sum())
+    x_e = x[e.long()].contiguous(); v_e = torch.zeros_like(x_e)
+    out = {"workload": f"{n_blocks} double-stream blocks at 3072 wide, {n_img} image + {n_img} reference + {n_txt} text tokens, {n_e} edited"}
+    for name, fn in (("full_store_step", lambda: model.full_forward(x, x_r, 0.8, True, v)),
+                     ("region_step", lambda: model.region_forward(x_e, e, n_e, 0.75, v_e))):
+        fn(); torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        out[name] = {"seconds": (time.perf_counter() - t0) / 3}
+    n_all = n_txt + 2 * n_img
+    H, M = 3072, 12288
+    full_flops = n_blocks * (2.0 * n_all * H * (4 * H + 2 * M) + 4.0 * n_all * n_all * H)
+    region_flops = n_blocks * (2.0 * n_e * H * (4 * H + 2 * M) + 4.0 * n_e * n_all * H)
+    out["full_store_step"]["TFLOP/s"] = full_flops / out["full_store_step"]["seconds"] / 1e12
+    out["region_step"]["TFLOP/s"] = region_flops / out["region_step"]["seconds"] / 1e12
+    out["region_step"]["edited_tokens_per_s"] = n_e / out["region_step"]["seconds"]
+    out["region_step"]["ms_per_block"] = out["region_step"]["seconds"] / n_blocks * 1e3
+    out["finite"] = bool(torch.isfinite(v).all().item() and torch.isfinite(v_e).all().item())
+    model.close()
+    return out
+
+
 def loop_benchmark(n_double: int, n_single: int, guidance=None):
     """Whole sampling loop on the device: the method's 28-step schedule (6 stabilization steps, forced step at k = 16,
     2 smooth steps, velocity-decay cache with delta = 0.04 on a linear schedule) against 28 plain full steps of the same
@@ -220,6 +272,8 @@ def main():
                     help="only run a plain 1 GiB device copy three times (calibration of the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--block-extras", action="store_true",
                     help="time the step with query/key normalisation and rotary embedding in the block (no CPU baseline)")
+    ap.add_argument("--stack", action="store_true",
+                    help="time one storing full step and one region step through 60 double-stream blocks at the large-image sizes")
     ap.add_argument("--cfg", action="store_true",
                     help="time the block for the two branches of classifier-free guidance: one batched call against two calls")
     ap.add_argument("--loop", action="store_true",
@@ -247,6 +301,9 @@ def main():
     rg.lib()   # fails loudly if the HIP library has not been built
     if args.cfg:
         print(json.dumps(cfg_benchmark(args.steps, args.warmup)))
+        return
+    if args.stack:
+        print(json.dumps(stack_benchmark()))
         return
     if args.loop:
         print(json.dumps(loop_benchmark(*[int(v) for v in args.loop_blocks.split(",")], guidance=args.loop_guidance)))
