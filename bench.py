@@ -25,8 +25,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 MEASURED_GEMM_TRAFFIC_BYTES_PER_STEP = {820: 785.0e6}
 
 
-def cpu_baseline(cfg, hst, reps):
-    """The oracle as it stands, timed on the host cores: the same step on the same inputs."""
+def cpu_baseline(cfg, hst, reps, gpu=None):
+    """The oracle as it stands, timed on the host cores: the same step on the same inputs.  With the GPU's outputs of
+    that step (`gpu`) the line also carries how far the two are apart."""
     from oracle import step_reference as ref
     kc, vc = ref.build_cache(hst["streams"], cfg.kind, hst["h_store"], cfg.n_txt, cfg.heads)   # setup, like the GPU's cache fill
     t0 = time.perf_counter()
@@ -40,8 +41,16 @@ def cpu_baseline(cfg, hst, reps):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count() or 1
-    return {"value": n / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"the whole workload ({n} edited tokens), {reps} step(s) of the numpy float64 oracle, {dt:.2f} s per step"}
+    res = {"value": n / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+           "sample": f"the whole workload ({n} edited tokens), {reps} step(s) of the numpy float64 oracle, {dt:.2f} s per step"}
+    if gpu is not None:
+        import numpy as np
+        diff = np.abs(gpu["h_e_out"][:n].astype(np.float64) - out["h_e_out"])
+        res["parity"] = {"mask_equal": bool(np.array_equal(gpu["mask"], out["mask"])),
+                         "index_lists_equal": bool(np.array_equal(gpu["e_index"][:n], out["e_index"])),
+                         "block_out_max_abs": float(diff.max()), "block_out_mean_rel": float(diff.mean() / np.abs(out["h_e_out"]).mean()),
+                         "merged_latent_max_abs": float(np.abs(gpu["x_next"].astype(np.float64) - out["x_next"]).max())}
+    return res
 
 
 def membound(torch, rg):
@@ -359,6 +368,10 @@ def main():
         out["gemm_plus_attention_tflops"] = (gemm_flops + attn_flops) / ((g_ms + a_ms) * 1e-3) / 1e12
         out["kernels"] = kernels
     host = wl.host
+    gpu_out = None
+    if not args.no_cpu_baseline:   # what the step left on the device, for the parity figures beside the oracle's time
+        gpu_out = {"mask": wl.mask.cpu().numpy(), "e_index": wl.e_index.cpu().numpy(), "h_e_out": wl.h_e_out.float().cpu().numpy(),
+                   "x_next": wl.x_next.float().cpu().numpy()}
     wl.close()
     del wl
     torch.cuda.empty_cache()
@@ -380,7 +393,7 @@ def main():
     if not args.no_membound:
         out["membound"] = membound(torch, rg)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, host, reps=6)
+        out["cpu_baseline"] = cpu_baseline(cfg, host, reps=6, gpu=gpu_out)
     print(json.dumps(out))
 
 
