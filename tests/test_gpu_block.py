@@ -167,3 +167,36 @@ def _oracle_region_rows(streams, kind, h_fresh, slots, kc, vc, heads, sample):
         return h1 + w["gate2"] * orc.linear(orc.gelu_tanh(orc.linear(u2, w["w_1"], w["b_1"])), w["w_2"], w["b_2"])
     m = orc.gelu_tanh(orc.linear(u[sample], w["w_1"][3 * hidden:], w["b_1"][3 * hidden:]))
     return hs + w["gate1"] * orc.linear(np.concatenate([a, m], axis=1), w["w_2"], w["b_2"])
+
+
+@pytest.mark.parametrize("kind", ["double", "single"])
+def test_region_forward_ragged_row_counts(kind):
+    """Row counts around the tile edges of the kernels (1, 63, 64, 65, 127, 129, all image rows minus one, all image rows)
+    on the 256-wide configuration, every one against the oracle."""
+    hidden, heads, d, mlp = 256, 4, 64, 1024
+    n_txt, n_img = 32, 256
+    n_all = n_txt + 2 * n_img
+    streams, rng = _model(inputs.workload_seed(1, 9), kind, hidden, mlp, std=0.05)
+    h = inputs.bf16_round(rng.standard_normal((n_all, hidden)).astype(np.float32))
+    ctx = rg.Context(hidden, heads, d, mlp, n_all, 4096)
+    bw, keep = block_to_device(streams, kind, ctx)
+    btype = rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE
+    kc_o = np.zeros((n_all, heads, d)); vc_o = np.zeros_like(kc_o)
+    orc.block_forward(streams, kind, h, n_txt, np.arange(n_all), kc_o, vc_o, orc.FLAG_STORE, heads)
+    kc = torch.zeros((n_all, heads, d), dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
+    out = torch.empty((n_all, hidden), dtype=torch.bfloat16, device="cuda")
+    rg.regione_block_forward(ctx, bw, btype, dev(h, "bf16"), out, rg.BF16, n_all, n_txt,
+                             torch.arange(n_all, dtype=torch.int32, device="cuda"), 0, kc, vc, n_all, rg.FLAG_STORE)
+    kc0, vc0 = kc.clone(), vc.clone()
+    h2 = inputs.bf16_round((h + 0.05 * rng.standard_normal(h.shape)).astype(np.float32))
+    for n_e in (1, 63, 64, 65, 127, 129, n_img - 1, n_img):
+        e = np.sort(rng.choice(n_img, size=n_e, replace=False)).astype(np.int32)
+        rows = n_txt + e
+        want = orc.block_forward(streams, kind, h2[rows], 0, rows, kc_o.copy(), vc_o.copy(), orc.FLAG_RETRIEVE, heads)
+        o = torch.full((n_e + 1, hidden), 9.0, dtype=torch.bfloat16, device="cuda")
+        kc.copy_(kc0); vc.copy_(vc0)
+        rg.regione_block_forward(ctx, bw, btype, dev(h2[rows], "bf16"), o, rg.BF16, n_e, 0, torch.from_numpy(e).cuda(), n_txt, kc, vc, n_all,
+                                 rg.FLAG_RETRIEVE)
+        assert torch.all(o[n_e] == 9.0)            # nothing written past the last row
+        assert_close(host(o)[:n_e], want, f"{kind} region forward with {n_e} rows", stored_bf16=True)
+    ctx.close()
