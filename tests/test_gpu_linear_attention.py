@@ -162,3 +162,37 @@ def test_attention_errors(ctx):
         rg.regione_attn_kvcache(ctx, q, 4, None, None, 0, None, None, 0, None, 0, 2, 64, 0.0, q)
     assert e.value.code == rg.ERR_BAD_SHAPE
     rg.regione_attn_kvcache(ctx, q, 0, None, None, 0, None, None, 0, None, 0, 2, 64, 0.0, q)   # no query: no-op
+
+
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("n_fresh,use_index", [(0, False), (50, False), (50, True)])
+def test_attention_runs_are_bit_identical(ctx, d, n_fresh, use_index):
+    """No atomics and no order that depends on timing: the same call gives the same bits, for every source layout
+    (one array, fresh + cache, cache through an index list) and with key splits.  A read of matrix-core results that
+    did not wait for them once showed up exactly here, as one-ulp differences between runs."""
+    heads = 2
+    rng = np.random.default_rng(2300 + d + n_fresh)
+    q, kf, vf, kc, vc = _attn_case(rng, 130, n_fresh, 900, heads, d)
+    idx = np.sort(rng.choice(900, size=700, replace=False)) if use_index else None
+    for splits in (1, 3):
+        rg.regione_tune_attention(ctx, splits)
+        runs = [_run_attn(ctx, q, kf, vf, kc, vc, idx, heads, d) for _ in range(4)]
+        rg.regione_tune_attention(ctx, 0)
+        for r in runs[1:]:
+            assert np.array_equal(runs[0], r), f"splits {splits}: max difference between identical runs {np.abs(runs[0] - r).max()}"
+
+
+def test_linear_runs_are_bit_identical(ctx):
+    rng = np.random.default_rng(2400)
+    m, n, k = 300, 520, 1024
+    x = dev(inputs.bf16_round(rng.standard_normal((m, k)).astype(np.float32)), "bf16")
+    wp = rg.pack_weight(ctx, dev(inputs.bf16_round((0.05 * rng.standard_normal((n, k))).astype(np.float32)), "bf16"))
+    for tn, sp in ((0, 0), (1, 2), (2, 1), (4, 2), (6, 1)):
+        rg.regione_tune_gemm(ctx, tn, sp)
+        outs = []
+        for _ in range(3):
+            y = torch.zeros((m, n), dtype=torch.bfloat16, device="cuda")
+            rg.regione_linear(ctx, x, wp, None, m, n, k, rg.ACT_NONE, rg.BF16, y)
+            outs.append(host(y))
+        rg.regione_tune_gemm(ctx, 0, 0)
+        assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2]), (tn, sp)
