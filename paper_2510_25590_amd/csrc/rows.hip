@@ -122,6 +122,16 @@ layernorm_mod_vec_kernel(const T* __restrict__ h, int n, int hidden, const float
             for (int e = 0; e < 8; ++e) sum += x[i][e];
         }
     }
+    // the modulation vectors are requested now, so that they arrive while the two reductions run
+    float sc[MAXV][8], sh[MAXV][8];
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int g = lane + 64 * i;
+        if (g < groups) {
+            if (scale) ld8<float>(scale + g * 8, sc[i]);
+            if (shift) ld8<float>(shift + g * 8, sh[i]);
+        }
+    }
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 64);
     const float mean = sum / hidden;
@@ -141,14 +151,11 @@ layernorm_mod_vec_kernel(const T* __restrict__ h, int n, int hidden, const float
     for (int i = 0; i < MAXV; ++i) {
         const int g = lane + 64 * i;
         if (g < groups) {
-            float sc[8], sh[8];
-            if (scale) ld8<float>(scale + g * 8, sc);
-            if (shift) ld8<float>(shift + g * 8, sh);
             ln_bf16x8 o;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 float y = (x[i][e] - mean) * rstd;
-                y = y * (1.f + (scale ? sc[e] : 0.f)) + (shift ? sh[e] : 0.f);
+                y = y * (1.f + (scale ? sc[i][e] : 0.f)) + (shift ? sh[i][e] : 0.f);
                 o[e] = static_cast<__bf16>(y);
             }
             *reinterpret_cast<ln_bf16x8*>(ur + g * 8) = o;
