@@ -99,3 +99,22 @@ def test_gamma_fit_host_matches_oracle():
         rg.regione_gamma_fit_host(bad, t)
     with pytest.raises(rg.RegionEError):
         rg.regione_gamma_fit_host(np.zeros((S, T + 1)), t)
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 on its own, with every declaration used."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler here")
+    header = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "regione.h")
+    names = re.findall(r"^\s*(?:int|int64_t|const char\*)\s+(regione_\w+)\s*\(", open(header).read(), flags=re.M)
+    assert len(names) >= 25
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "regione.h"\ntypedef void (*fn)(void);\n' + "fn table[] = {" + ", ".join(f"(fn){n}" for n in names) + "};\n"
+                   "int main(void) { regione_dims d = {0}; regione_block_weights w = {0}; regione_avd_state s = {0}; regione_plan_step p = {0};\n"
+                   "  (void)d; (void)w; (void)s; (void)p; return sizeof(table) > 0 ? 0 : 1; }\n")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", os.path.dirname(header), str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
