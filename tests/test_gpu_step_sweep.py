@@ -128,3 +128,34 @@ def test_fraction_sweep_blob_masks(n_edited, h_dtype):
                           outlier_frac=1e-5)   # 3072-wide block output: the bound is 5.5 sigma of the bf16 arithmetic error
     print(f"n_edited {n} ({h_dtype}): max abs {ma:.3e}, mean rel {mr:.3e}")
     ctx.close()
+
+
+def test_large_image_region_forward_sampled():
+    """The large-image configuration: 96x96 image + 9216 reference + 1024 text tokens (19456 keys), 1382 edited tokens of a
+    blob, one double-stream block at 3072 wide; the oracle builds the whole cache and evaluates sampled edited rows."""
+    hidden, heads, d, mlp = 3072, 24, 128, 12288
+    n_txt, grid, n_edited = 1024, 96, 1382
+    n_img = grid * grid
+    n_all = n_txt + 2 * n_img
+    streams, rng = _model(inputs.workload_seed(5, 2), "double", hidden, mlp)
+    want_mask = inputs.blob_mask(rng, grid, grid, n_edited)
+    e = np.nonzero(want_mask)[0].astype(np.int32)
+    rows = n_txt + e
+    h_store = inputs.hidden_states(rng, n_all, hidden)
+    h_now = inputs.bf16_round((h_store[rows] + 0.05 * rng.standard_normal((n_edited, hidden))).astype(np.float32))
+    ctx = rg.Context(hidden, heads, d, mlp, n_all, n_img)
+    bw, keep = block_to_device(streams, "double", ctx)
+    kc = torch.zeros((n_all, heads, d), dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
+    full = torch.empty((n_all, hidden), dtype=torch.bfloat16, device="cuda")
+    rg.regione_block_forward(ctx, bw, rg.BLOCK_DOUBLE, dev(h_store, "bf16"), full, rg.BF16, n_all, n_txt,
+                             torch.arange(n_all, dtype=torch.int32, device="cuda"), 0, kc, vc, n_all, rg.FLAG_STORE)
+    o = torch.empty((n_edited, hidden), dtype=torch.bfloat16, device="cuda")
+    rg.regione_block_forward(ctx, bw, rg.BLOCK_DOUBLE, dev(h_now, "bf16"), o, rg.BF16, n_edited, 0, torch.from_numpy(e).cuda(), n_txt,
+                             kc, vc, n_all, rg.FLAG_RETRIEVE)
+    kc_o, vc_o = ref.build_cache(streams, "double", h_store, n_txt, heads)
+    sample = np.sort(rng.choice(n_edited, size=24, replace=False))
+    sample[:2] = [0, n_edited - 1]
+    want = _oracle_region_rows(streams, "double", h_now, rows, kc_o, vc_o, heads, sample)
+    ma, mr = assert_close(host(o)[sample], want, "region forward at the large-image sizes (sampled rows)", stored_bf16=True, outlier_frac=1e-5)
+    print(f"large image: n_edited {n_edited}, {n_all} keys: max abs {ma:.3e}, mean rel {mr:.3e}")
+    ctx.close()
