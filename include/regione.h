@@ -178,6 +178,33 @@ int regione_pack_weight(regione_ctx* ctx, const void* w /*[n,k] bf16 row-major*/
 int regione_linear(regione_ctx* ctx, const void* x, const void* w_packed, const float* b_opt,
                    int32_t m, int32_t n, int32_t k, int32_t act, int32_t out_dtype, void* y);
 
+/* 8-bit floating point variant of the dense projections (section "Region-Aware Generation":
+ * the DiT's linear layers on the edited rows).  The paper computes in the model's own
+ * precision; this variant is an extension with its own accuracy, never chosen silently.
+ * Format: E4M3 of the OCP 8-bit floating point specification (bias 7, largest value 448,
+ * no infinities), one float32 scale per row.
+ *
+ * regione_quantize_rows_fp8: for every row r of x [rows, cols] (bf16, finite values)
+ *   amax = max |x[r,:]|, scale[r] = amax / 448, q[r,c] = e4m3(x[r,c] * (448 / amax)),
+ * both quotients and the product in float32, the product clamped to +-448 and rounded to
+ * nearest, ties to even.  A row of zeros gets scale 1.  q: uint8 [rows, cols]; scale:
+ * float32 [rows].  cols must be a multiple of 8 and at most 16384; x and q 16-byte aligned.
+ * Serves activations (a row = a token) and weights (a row = an output feature) alike.
+ *
+ * regione_pack_weight_fp8: the quantised weight codes [n, k] (k a multiple of 128) in the
+ * operand layout of the 8-bit matrix-core instruction: for every block of 32 output
+ * features and 32 input features, 64 x 16 bytes with entry (lane, e) =
+ * Wq[32*block_n + lane%32][32*block_k + 16*(lane/32) + e]; rows past n are zero.  The packed
+ * array has regione_packed_weight_elems(n, k) BYTES.
+ *
+ * regione_linear_fp8: y[m,n] = act(x_scale[m] * w_scale[n] * sum_k xq[m,k] wq[n,k] + b[n]),
+ * products exact, sums in float32.  xq uint8 [m,k] row-major, k a multiple of 128; y of
+ * out_dtype (bf16 or float32).  The scales are applied to the float32 sums before the bias. */
+int regione_quantize_rows_fp8(regione_ctx* ctx, const void* x, int64_t rows, int32_t cols, void* q, float* scale);
+int regione_pack_weight_fp8(regione_ctx* ctx, const void* wq /*[n,k] uint8 row-major*/, int32_t n, int32_t k, void* wq_packed);
+int regione_linear_fp8(regione_ctx* ctx, const void* xq, const float* x_scale, const void* wq_packed, const float* w_scale,
+                       const float* b_opt, int32_t m, int32_t n, int32_t k, int32_t act, int32_t out_dtype, void* y);
+
 /* Tuning knob for experiments: forces the GEMM wave tile (1 or 2 blocks of 32 columns; 3 or 4 =
  * the same two widths with the kernel that stages both operands through LDS, 5 or 6 = that
  * kernel with 256-row workgroup tiles) and the number of K splits of every later GEMM of this

@@ -28,6 +28,7 @@ EXPORTS = (
     "regione_layernorm", "regione_stage_plan_host", "regione_cast", "regione_mask_cleanup", "regione_rope_table",
     "regione_vec_linear", "regione_timestep_embedding", "regione_block_forward_batched",
     "regione_sq_norms", "regione_gamma_fit_host", "regione_guidance_combine", "regione_rel_change",
+    "regione_quantize_rows_fp8", "regione_pack_weight_fp8", "regione_linear_fp8",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -93,6 +94,9 @@ def lib() -> C.CDLL:
             "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
             "regione_pack_weight": [vp, vp, i32, i32, vp],
+            "regione_quantize_rows_fp8": [vp, vp, i64, i32, vp, vp],
+            "regione_pack_weight_fp8": [vp, vp, i32, i32, vp],
+            "regione_linear_fp8": [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
             "regione_tune_gemm": [vp, i32, i32],
             "regione_tune_attention": [vp, i32],
             "regione_layernorm": [vp, vp, i32, i32, i32, vp, vp, vp],
@@ -296,6 +300,18 @@ def regione_packed_weight_elems(n: int, k: int) -> int:
 
 def regione_pack_weight(ctx, w, n, k, w_packed):
     _check(lib().regione_pack_weight(ctx.handle, _p(w), n, k, _p(w_packed)))
+
+
+def regione_quantize_rows_fp8(ctx, x, rows, cols, q, scale):
+    _check(lib().regione_quantize_rows_fp8(ctx.handle, _p(x), rows, cols, _p(q), _p(scale)))
+
+
+def regione_pack_weight_fp8(ctx, wq, n, k, wq_packed):
+    _check(lib().regione_pack_weight_fp8(ctx.handle, _p(wq), n, k, _p(wq_packed)))
+
+
+def regione_linear_fp8(ctx, xq, x_scale, wq_packed, w_scale, b, m, n, k, act, out_dtype, y):
+    _check(lib().regione_linear_fp8(ctx.handle, _p(xq), _p(x_scale), _p(wq_packed), _p(w_scale), _p(b), m, n, k, act, out_dtype, _p(y)))
 
 
 def regione_tune_gemm(ctx, wave_tile_blocks: int, k_splits: int):

@@ -83,9 +83,13 @@ struct GemmEpilogue {
     bf16_t* q; int ldq; bf16_t* k; bf16_t* v; int ldkv; const int32_t* slot; int slot_offset; int hidden; int y_col0;
     // EPI_RESID: y[row*ldy+col] = resid[row*ldr+col] + gate[col]*(acc+bias)
     const void* resid; int ldr; int resid_f32; const float* gate;
+    // 8-bit GEMM only: the float32 sums are multiplied by row_scale[row] * col_scale[col] before anything else
+    const float* row_scale; const float* col_scale;
 };
 
 int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w_packed, int m, int n, int k, const GemmEpilogue& ep);
+// E4M3 operands (k counts 8-bit elements, a multiple of 128; lda in bytes, a multiple of 16); ep.row_scale / col_scale set
+int rg_gemm_fp8(regione_ctx* ctx, const uint8_t* a, int lda, const uint8_t* w_packed, int m, int n, int k, const GemmEpilogue& ep);
 int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, bf16_t* u);
 int rg_qk_norm_rope(regione_ctx* ctx, bf16_t* q, int ldq, bf16_t* k, int ldkv, const int32_t* kv_slot,
                     const int32_t* pos_slot, int pos0, int slot_offset, int slot_period, int slot_branch_rows, int n, int heads, int d,

@@ -1,0 +1,96 @@
+// 8-bit floating point (OCP E4M3) variant of the dense projections on the edited rows (section "Region-Aware
+// Generation"); an extension, the paper itself computes in the model's precision.  This file: per-row quantisation
+// and the entry points; the matrix-core kernel is the 8-bit form of the LDS GEMM in gemm.hip.
+#include "common.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+
+constexpr float kE4M3Max = 448.0f;
+
+// One wave per row; the row stays in registers between the maximum and the conversion (MAXV 16-byte pieces per lane).
+//   amax = max |x|;  scale = amax / 448;  code = e4m3(clamp(x * (448 / amax), +-448)), round to nearest even
+// (v_cvt_pk_fp8_f32).  The divisions are IEEE float32 divisions, the product a float32 product.
+template <int MAXV>
+__global__ void __launch_bounds__(256)
+quantize_rows_fp8_kernel(const bf16_t* __restrict__ x, int64_t rows, int cols, uint8_t* __restrict__ q, float* __restrict__ scale) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int pieces = cols >> 3;
+    const bf16x8* src = reinterpret_cast<const bf16x8*>(x + row * cols);
+    bf16x8 v[MAXV];
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int p = i * 64 + lane;
+        if (p < pieces) {
+            v[i] = src[p];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) amax = __builtin_fmaxf(amax, __builtin_fabsf(static_cast<float>(v[i][e])));
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) amax = __builtin_fmaxf(amax, __shfl_xor(amax, off, 64));
+    const bool live = amax > 0.f;
+    const float mult = live ? kE4M3Max / amax : 1.0f;
+    if (lane == 0) scale[row] = live ? amax / kE4M3Max : 1.0f;
+    uint2* dst = reinterpret_cast<uint2*>(q + row * cols);
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int p = i * 64 + lane;
+        if (p < pieces) {
+            float y[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = __builtin_fminf(__builtin_fmaxf(static_cast<float>(v[i][e]) * mult, -kE4M3Max), kE4M3Max);
+            unsigned lo = 0, hi = 0;
+            lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
+            lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
+            hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
+            hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+            dst[p] = make_uint2(lo, hi);
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" int regione_quantize_rows_fp8(regione_ctx* ctx, const void* x, int64_t rows, int32_t cols, void* q, float* scale) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "quantize_rows_fp8: null context");
+    if (rows < 0 || cols <= 0 || (cols & 7) || cols > 16384) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "quantize_rows_fp8: rows=%lld, cols=%d (a multiple of 8, at most 16384)", (long long)rows, cols);
+    if (rows == 0) return REGIONE_OK;
+    if (rows > (int64_t(1) << 31)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "quantize_rows_fp8: rows=%lld too many", (long long)rows);
+    if (!x || !q || !scale || !rg_aligned16(x) || !rg_aligned16(q)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "quantize_rows_fp8: null or unaligned tensor");
+    const unsigned blocks = static_cast<unsigned>((rows + 3) / 4);
+    const bf16_t* xs = static_cast<const bf16_t*>(x);
+    uint8_t* qs = static_cast<uint8_t*>(q);
+    const int per_lane = (cols / 8 + 63) / 64;
+    if (per_lane <= 8) hipLaunchKernelGGL(quantize_rows_fp8_kernel<8>, dim3(blocks), dim3(256), 0, ctx->stream, xs, rows, cols, qs, scale);
+    else hipLaunchKernelGGL(quantize_rows_fp8_kernel<32>, dim3(blocks), dim3(256), 0, ctx->stream, xs, rows, cols, qs, scale);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+extern "C" int regione_pack_weight_fp8(regione_ctx* ctx, const void* wq, int32_t n, int32_t k, void* wq_packed) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "pack_weight_fp8: null context");
+    if (n <= 0 || k <= 0 || (k % 128)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "pack_weight_fp8: n=%d, k=%d (k must be a multiple of 128)", n, k);
+    // the 8-bit layout is the 16-bit one with every pair of codes taken as one element
+    return regione_pack_weight(ctx, wq, n, k / 2, wq_packed);
+}
+
+extern "C" int regione_linear_fp8(regione_ctx* ctx, const void* xq, const float* x_scale, const void* wq_packed, const float* w_scale,
+                                  const float* b_opt, int32_t m, int32_t n, int32_t k, int32_t act, int32_t out_dtype, void* y) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear_fp8: null context");
+    if (m < 0 || n <= 0 || k <= 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear_fp8: m=%d n=%d k=%d", m, n, k);
+    if (act != REGIONE_ACT_NONE && act != REGIONE_ACT_GELU_TANH) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear_fp8: bad act %d", act);
+    if (out_dtype != REGIONE_BF16 && out_dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear_fp8: bad out_dtype %d", out_dtype);
+    if (k % 128) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "linear_fp8: k=%d must be a multiple of 128", k);
+    if (m == 0) return REGIONE_OK;
+    if (!xq || !x_scale || !wq_packed || !w_scale || !y) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear_fp8: null tensor");
+    GemmEpilogue ep = {};
+    ep.kind = EPI_PLAIN; ep.bias = b_opt; ep.act = act; ep.act_from = 0;
+    ep.y = y; ep.ldy = n; ep.y_f32 = out_dtype == REGIONE_FP32;
+    ep.row_scale = x_scale; ep.col_scale = w_scale;
+    return rg_gemm_fp8(ctx, static_cast<const uint8_t*>(xq), k, static_cast<const uint8_t*>(wq_packed), m, n, k, ep);
+}

@@ -28,6 +28,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // a native 16-byte vector: copies are single loads/stores
+typedef __attribute__((ext_vector_type(8))) int i32x8;            // operand of the 8-bit MFMA: 32 E4M3 values per lane
 
 constexpr int BM = 128;       // rows per workgroup tile
 constexpr int TM = BM / 32;
@@ -169,7 +170,9 @@ __device__ __forceinline__ void epilogue_store8(const GemmEpilogue& ep, int row,
 // 8 KiB of LDS per wave (indexed by the wave's number in the workgroup) that no wave reads any more once all waves
 // have passed the barrier inside.  accumulator (i, j, r) of a lane: row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32
 // of the 32x32 block (i, j) of the wave tile.
-template <int TN, int KIND>
+// SCALED (the 8-bit GEMM): every sum is first multiplied by ep.row_scale[row] * ep.col_scale[column], also on its way
+// into a split-K partial result (the scaling is linear, so the merge needs no change).
+template <int TN, int KIND, bool SCALED = false>
 __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[TM][TN], float* stage_lds, int M, int N, int m0, int n0, int wn0,
                                               float* __restrict__ partial, const GemmEpilogue& ep) {
     constexpr int WN = 32 * TN;
@@ -186,11 +189,12 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[TM][TN], float* stag
         const int cg = lane % G, rsub = lane / G;
         const int col0 = n0 + wn0 + cg * 8;
         const bool col_live = col0 < N;      // N is a multiple of 8 on this path
-        float bias[8], gate[8];
+        float bias[8], gate[8], cscale[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             bias[e] = (!partial && col_live && ep.bias) ? ep.bias[col0 + e] : 0.f;
             gate[e] = (!partial && col_live && KIND == EPI_RESID && ep.gate) ? ep.gate[col0 + e] : 1.f;
+            cscale[e] = (SCALED && col_live) ? ep.col_scale[col0 + e] : 1.f;
         }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -205,8 +209,13 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[TM][TN], float* stag
                 const int row = m0 + i * 32 + rr;
                 const f32x4 lo = *reinterpret_cast<const f32x4*>(stage + rr * WN + cg * 8);
                 const f32x4 hi = *reinterpret_cast<const f32x4*>(stage + rr * WN + cg * 8 + 4);
-                const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                 if (row < M && col_live) {
+                    if (SCALED) {
+                        const float rs = ep.row_scale[row];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] *= rs * cscale[e];
+                    }
                     if (partial) store8(part_base, static_cast<int64_t>(row) * N + col0, 1, v);
                     else epilogue_store8<KIND>(ep, row, col0, v, bias, gate);
                 }
@@ -215,11 +224,12 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[TM][TN], float* stag
         return;
     }
     int col[TN];
-    float bias[TN], gate[TN];
+    float bias[TN], gate[TN], cscale[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         col[j] = n0 + wn0 + j * 32 + l32;
         const bool live = col[j] < N;
+        cscale[j] = (SCALED && live) ? ep.col_scale[col[j]] : 1.f;
         bias[j] = (!partial && live && ep.bias) ? ep.bias[col[j]] : 0.f;
         gate[j] = (!partial && live && KIND == EPI_RESID && ep.gate) ? ep.gate[col[j]] : 1.f;
     }
@@ -229,15 +239,16 @@ __device__ __forceinline__ void gemm_epilogue(f32x16 (&acc)[TM][TN], float* stag
         for (int r = 0; r < 16; ++r) {
             const int row = m0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
             if (row >= M) continue;
+            const float rs = SCALED ? ep.row_scale[row] : 1.f;
             if (partial) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    if (col[j] < N) part_base[static_cast<int64_t>(row) * N + col[j]] = acc[i][j][r];
+                    if (col[j] < N) part_base[static_cast<int64_t>(row) * N + col[j]] = SCALED ? acc[i][j][r] * (rs * cscale[j]) : acc[i][j][r];
             } else {
                 const int64_t kv_row = epilogue_kv_row<KIND>(ep, row);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    if (col[j] < N) epilogue_store<KIND>(ep, row, kv_row, col[j], acc[i][j][r], bias[j], gate[j]);
+                    if (col[j] < N) epilogue_store<KIND>(ep, row, kv_row, col[j], SCALED ? acc[i][j][r] * (rs * cscale[j]) : acc[i][j][r], bias[j], gate[j]);
             }
         }
     }
@@ -486,7 +497,12 @@ __device__ __forceinline__ void rg_async_copy16(const bf16_t* src, unsigned lds_
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(src), "s"(lds_base_bytes) : "memory", "m0");
 }
 
-template <int TN, int WM, int KIND>
+// FP8 = true: the same bytes hold E4M3 values (A, lda, K and every k index of this kernel then count PAIRS of
+// them, i.e. 2 bytes).  A stage is ONE k-step of v_mfma_f32_32x32x64_f8f6f4: a lane's 32 operand bytes are the two
+// 16-byte pieces that the bf16 path feeds to two MFMAs, bytes [16*(lane/32), +16) and [32 + 16*(lane/32), +16) of the
+// stage's 64-byte row.  Which k of the instruction each byte becomes does not matter: activations and weights are laid
+// out alike, and the sum over k does not depend on its order.
+template <int TN, int WM, int KIND, bool FP8 = false>
 __global__ void __launch_bounds__(kThreads * WM) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gemm_lds_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ Wp,
                 int M, int N, int K, int m_tiles, int n_tiles, int tiles_per_xcd, int group_rows,
@@ -570,6 +586,72 @@ gemm_lds_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict_
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    if constexpr (FP8) {
+        // Three LDS stages, copies three stages ahead.  A stage is one k-step; its MFMAs run in two halves (row blocks
+        // 0-1, then 2-3) with the same hand-over between them as in the bf16 schedule below:
+        //   first half : read the A fragments of row blocks 2-3 of stage t, run the MFMAs of row blocks 0-1
+        //   middle     : wait for the copies of stage t+1, barrier, issue the copies of stage t+3 into the buffer of
+        //                stage t, read the weight fragments and the A fragments of row blocks 0-1 of stage t+1
+        //   second half: run the MFMAs of row blocks 2-3.
+        static_assert(L_STAGES == 3 && TM == 4, "the schedule below rotates three buffers and splits four row blocks");
+        auto clamp_stage = [&](int t) __attribute__((always_inline)) { return t < n_stages ? t : n_stages - 1; };
+#pragma unroll
+        for (int p = 0; p < L_STAGES; ++p) issue(clamp_stage(p), p * G::STAGE_BYTES);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * G::COPIES) : "memory");
+        __syncthreads();
+        u32x4 a8[TM][2], w8[2][TN][2];      // [..][kk]: the two 16-byte pieces of an operand
+#define RG_F8_AFRAGS(I0, S)                                                                               \
+    {                                                                                                     \
+        const unsigned char* st_ = lds_raw + (S) * G::STAGE_BYTES;                                        \
+        _Pragma("unroll") for (int i = (I0); i < (I0) + 2; ++i)                                           \
+            _Pragma("unroll") for (int kk = 0; kk < 2; ++kk)                                              \
+                a8[i][kk] = *reinterpret_cast<const u32x4*>(st_ + a_off[kk][i]);                          \
+    }
+#define RG_F8_WFRAGS(P, S)                                                                                \
+    {                                                                                                     \
+        const unsigned char* st_ = lds_raw + (S) * G::STAGE_BYTES;                                        \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                    \
+            _Pragma("unroll") for (int kk = 0; kk < 2; ++kk)                                              \
+                w8[P][j][kk] = *reinterpret_cast<const u32x4*>(st_ + w_off + (j * 2 + kk) * 1024);        \
+    }
+#define RG_F8_MFMAS(I0, P)                                                                                \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                        \
+        _Pragma("unroll") for (int i = (I0); i < (I0) + 2; ++i) {                                         \
+            const i32x8 av = {(int)a8[i][0][0], (int)a8[i][0][1], (int)a8[i][0][2], (int)a8[i][0][3],     \
+                              (int)a8[i][1][0], (int)a8[i][1][1], (int)a8[i][1][2], (int)a8[i][1][3]};    \
+            const i32x8 wv = {(int)w8[P][j][0][0], (int)w8[P][j][0][1], (int)w8[P][j][0][2], (int)w8[P][j][0][3], \
+                              (int)w8[P][j][1][0], (int)w8[P][j][1][1], (int)w8[P][j][1][2], (int)w8[P][j][1][3]}; \
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, wv, acc[i][j], 0, 0, 0, 0, 0, 0); \
+        }
+#define RG_F8_STAGE(T, S, P)                                                                              \
+    {                                                                                                     \
+        const int t_ = (T);                                                                               \
+        RG_F8_AFRAGS(2, S)                                                                                \
+        RG_F8_MFMAS(0, P)                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(G::COPIES) : "memory");                                  \
+        __syncthreads();                                                                                  \
+        issue(clamp_stage(t_ + L_STAGES), (S) * G::STAGE_BYTES);                                          \
+        RG_F8_WFRAGS((P) ^ 1, ((S) + 1) % L_STAGES)                                                       \
+        RG_F8_AFRAGS(0, ((S) + 1) % L_STAGES)                                                             \
+        RG_F8_MFMAS(2, P)                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+    }
+        RG_F8_WFRAGS(0, 0)
+        RG_F8_AFRAGS(0, 0)
+        for (int t = 0; t < n_stages; t += 6) {
+            RG_F8_STAGE(t, 0, 0)
+            if (t + 1 < n_stages) RG_F8_STAGE(t + 1, 1, 1)
+            if (t + 2 < n_stages) RG_F8_STAGE(t + 2, 2, 0)
+            if (t + 3 < n_stages) RG_F8_STAGE(t + 3, 0, 1)
+            if (t + 4 < n_stages) RG_F8_STAGE(t + 4, 1, 0)
+            if (t + 5 < n_stages) RG_F8_STAGE(t + 5, 2, 1)
+        }
+#undef RG_F8_STAGE
+#undef RG_F8_MFMAS
+#undef RG_F8_WFRAGS
+#undef RG_F8_AFRAGS
+    } else {
     // Three LDS stages, copies three stages ahead, fragments one half-stage ahead.  A stage is two MFMA k-steps:
     //   first half : read the second k-step's fragments of stage t, run the MFMAs of its first k-step (fragments read
     //                during stage t-1)
@@ -619,8 +701,9 @@ gemm_lds_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict_
 #undef RG_LDS_STAGE
 #undef RG_LDS_MFMAS
 #undef RG_LDS_FRAGS
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may still be writing LDS when the epilogue reuses it
-    gemm_epilogue<TN, KIND>(acc, reinterpret_cast<float*>(lds_raw), M, N, m0, n0, wn0, partial, ep);
+    gemm_epilogue<TN, KIND, FP8>(acc, reinterpret_cast<float*>(lds_raw), M, N, m0, n0, wn0, partial, ep);
 }
 
 // Sums the split-K partial results and applies the epilogue.  One thread per output element, columns fastest.
@@ -791,7 +874,76 @@ int dispatch(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m
     return launch_gemm<2, KIND, 0>(ctx, a, lda, wp, m, n, k, p.splits, ep);
 }
 
+
+// The 8-bit GEMM: 128-row LDS kernel only, plain epilogue.  k2 = K in pairs of E4M3 values (the kernel's unit).
+template <int TN>
+int launch_gemm_fp8(regione_ctx* ctx, const bf16_t* a, int lda2, const bf16_t* wp, int m, int n, int k2, int splits, const GemmEpilogue& ep) {
+    constexpr int BN = 128 * TN;
+    const int m_tiles = (m + BM - 1) / BM, n_tiles = (n + BN - 1) / BN;
+    const int tiles = m_tiles * n_tiles;
+    const int tiles_per_xcd = (tiles + 7) / 8;
+    const int steps = k2 / BK;
+    const int per = (steps + splits - 1) / splits;
+    const int used_splits = (steps + per - 1) / per;
+    if (used_splits > 1 && static_cast<size_t>(used_splits) * m * n * sizeof(float) > ctx->gemm_part_bytes)
+        RG_FAIL(REGIONE_ERR_WORKSPACE, "gemm_fp8: %d K-splits of a %d x %d result exceed the workspace", used_splits, m, n);
+    float* partial = used_splits > 1 ? ctx->gemm_part : nullptr;
+    const int group_rows = m_tiles > 8 ? 4 : m_tiles;
+    constexpr unsigned lds_bytes = LdsGemm<TN, 1>::LDS_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel<TN, 1, EPI_PLAIN, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemm_lds_kernel<TN, 1, EPI_PLAIN, true>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads), lds_bytes, ctx->stream,
+                       a, lda2, wp, m, n, k2, m_tiles, n_tiles, tiles_per_xcd, group_rows, per, partial, ep);
+    RG_LAUNCH_CHECK();
+    if (used_splits > 1) {
+        const int64_t total = static_cast<int64_t>(m) * n;
+        const bool wide = ep.vec_ok && used_splits <= kMaxSplits && (!ep.bias || rg_aligned16(ep.bias));
+        if (wide) {
+            const int64_t blocks = (total / 4 + kThreads - 1) / kThreads;
+            hipLaunchKernelGGL((splitk_epilogue4_kernel<EPI_PLAIN>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+                               partial, used_splits, m, n, ep);
+        } else {
+            int64_t blocks = (total + kThreads - 1) / kThreads;
+            if (blocks > 256 * 16) blocks = 256 * 16;
+            hipLaunchKernelGGL((splitk_epilogue_kernel<EPI_PLAIN>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+                               partial, used_splits, m, n, ep);
+        }
+        RG_LAUNCH_CHECK();
+    }
+    return REGIONE_OK;
+}
+
 }  // namespace
+
+int rg_gemm_fp8(regione_ctx* ctx, const uint8_t* a, int lda, const uint8_t* wp, int m, int n, int k, const GemmEpilogue& ep_in) {
+    if (m <= 0 || n <= 0) return REGIONE_OK;
+    if (k <= 0 || (k % (2 * BK)) || (lda & 15)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "gemm_fp8: k=%d must be a positive multiple of 128 and lda=%d of 16", k, lda);
+    if (!rg_aligned16(a) || !rg_aligned16(wp)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm_fp8: operands must be 16-byte aligned");
+    if (ep_in.kind != EPI_PLAIN || !ep_in.row_scale || !ep_in.col_scale) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm_fp8: plain epilogue with both scales only");
+    ProfScope prof(ctx, REGIONE_PROF_GEMM);
+    GemmEpilogue ep = ep_in;
+    ep.vec_ok = (n % 8 == 0) && (ep.ldy % 8 == 0) && rg_aligned16(ep.y) && (ep.act_from % 8 == 0) && rg_aligned16(ep.col_scale);
+    const int k2 = k / 2, steps = k2 / BK;
+    const int m_tiles = (m + BM - 1) / BM;
+    // Wave tile: the wide one (fewer LDS bytes per MFMA) once it gives most CUs a workgroup; measured at 820 rows:
+    // 9216 columns 34 us wide / 37 us narrow, 3072 columns 26 / 19 us.  K is split only when the narrow tile still
+    // leaves half the CUs idle (every split adds a pass over float32 partial sums, which at 820 x 3072 x 12288
+    // already costs what it gains).
+    int tn = (static_cast<long>(m_tiles) * ((n + 255) / 256) >= 200) ? 2 : 1;
+    int splits = 1;
+    if (ctx->gemm_force_tn > 0) tn = (ctx->gemm_force_tn - 1) % 2 + 1;
+    const long wgs = static_cast<long>(m_tiles) * ((n + 128 * tn - 1) / (128 * tn));
+    while (splits < kMaxSplits && wgs * splits < 128 && steps / (splits + 1) >= 8 &&
+           static_cast<size_t>(splits + 1) * m * n * sizeof(float) <= ctx->gemm_part_bytes) ++splits;
+    if (ctx->gemm_force_splits > 0) splits = ctx->gemm_force_splits;
+    const bf16_t* a2 = reinterpret_cast<const bf16_t*>(a);
+    const bf16_t* w2 = reinterpret_cast<const bf16_t*>(wp);
+    if (tn == 1) return launch_gemm_fp8<1>(ctx, a2, lda / 2, w2, m, n, k2, splits, ep);
+    return launch_gemm_fp8<2>(ctx, a2, lda / 2, w2, m, n, k2, splits, ep);
+}
 
 int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, const GemmEpilogue& ep_in) {
     if (m <= 0 || n <= 0) return REGIONE_OK;
