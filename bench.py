@@ -18,6 +18,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # L2 <-> fabric bytes of the GEMM launches of one step of the default workload (820 edited tokens), from two
 # rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): see
@@ -268,6 +269,54 @@ def loop_benchmark(n_double: int, n_single: int, guidance=None):
     return out
 
 
+def fp8_projections(torch, rg, n_rows: int):
+    """The four dense projections of the headline block on n_rows edited rows, bf16 against the E4M3 variant
+    (row quantisation of the activations timed with it; weights are quantised and packed once, outside)."""
+    hidden, mlp = 3072, 12288
+    ctx = rg.Context(hidden, 24, 128, mlp, max(n_rows, 16), 16)
+    g = torch.Generator(device="cuda"); g.manual_seed(9)
+    res = {"rows": n_rows, "format": "OCP E4M3, one float32 scale per activation row and per output feature", "peak_TFLOPs": PEAK_FP8_TFLOPS, "shapes": {}}
+    tot = {"bf16_us": 0.0, "fp8_us": 0.0, "quantize_us": 0.0, "flops": 0.0}
+    reps = 20
+    for name, n, k in (("qkv", 3 * hidden, hidden), ("attn_out", hidden, hidden), ("mlp_up", mlp, hidden), ("mlp_down", hidden, mlp)):
+        x = torch.randn((n_rows, k), generator=g, device="cuda").to(torch.bfloat16)
+        w = (torch.randn((n, k), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+        wp = rg.pack_weight(ctx, w)
+        xq = torch.empty((n_rows, k), dtype=torch.uint8, device="cuda"); sx = torch.empty(n_rows, dtype=torch.float32, device="cuda")
+        wq = torch.empty((n, k), dtype=torch.uint8, device="cuda"); sw = torch.empty(n, dtype=torch.float32, device="cuda")
+        rg.regione_quantize_rows_fp8(ctx, w, n, k, wq, sw)
+        wqp = torch.zeros(rg.regione_packed_weight_elems(n, k), dtype=torch.uint8, device="cuda")
+        rg.regione_pack_weight_fp8(ctx, wq, n, k, wqp)
+        y16 = torch.empty((n_rows, n), dtype=torch.bfloat16, device="cuda"); y8 = torch.empty_like(y16)
+        run16 = lambda: rg.regione_linear(ctx, x, wp, None, n_rows, n, k, rg.ACT_NONE, rg.BF16, y16)
+        def run8():
+            rg.regione_quantize_rows_fp8(ctx, x, n_rows, k, xq, sx)
+            rg.regione_linear_fp8(ctx, xq, sx, wqp, sw, None, n_rows, n, k, rg.ACT_NONE, rg.BF16, y8)
+        for _ in range(3):
+            run16(); run8()
+        torch.cuda.synchronize()
+        rg.regione_profile_enable(ctx, True); rg.regione_profile_read(ctx)
+        for _ in range(reps):
+            run16()
+        t16 = rg.regione_profile_read(ctx)["gemm"][0] / reps * 1e3
+        for _ in range(reps):
+            run8()
+        prof = rg.regione_profile_read(ctx)
+        rg.regione_profile_enable(ctx, False)
+        t8, tq = prof["gemm"][0] / reps * 1e3, prof["rows"][0] / reps * 1e3
+        fl = 2.0 * n_rows * n * k
+        rel = float((y8.float() - y16.float()).norm() / y16.float().norm())
+        res["shapes"][name] = {"n": n, "k": k, "bf16_us": t16, "fp8_us": t8, "quantize_us": tq, "bf16_TFLOPs": fl / t16 * 1e-6,
+                               "fp8_TFLOPs": fl / t8 * 1e-6, "frac_fp8_peak": fl / t8 * 1e-6 / PEAK_FP8_TFLOPS, "rel_diff_to_bf16": rel}
+        tot["bf16_us"] += t16; tot["fp8_us"] += t8; tot["quantize_us"] += tq; tot["flops"] += fl
+        del x, w, wp, xq, sx, wq, sw, wqp, y16, y8
+    res["all_four"] = {"bf16_us": tot["bf16_us"], "fp8_us": tot["fp8_us"], "quantize_us": tot["quantize_us"],
+                       "speedup_with_quantize": tot["bf16_us"] / (tot["fp8_us"] + tot["quantize_us"]),
+                       "fp8_TFLOPs": tot["flops"] / tot["fp8_us"] * 1e-6}
+    ctx.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -275,6 +324,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-membound", action="store_true")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the secondary measurement of the projections in E4M3")
     ap.add_argument("--no-mode-a", action="store_true", help="skip the secondary measurement with the text rows fresh")
     ap.add_argument("--no-profile", action="store_true", help="time the steps without the per-kernel event pairs")
     ap.add_argument("--copy-probe", action="store_true",
@@ -390,6 +440,8 @@ def main():
         ms_a = (time.perf_counter() - t0) * 1e3 / args.steps
         out["text_fresh"] = {"ms_per_step": ms_a, "edited_tokens_per_s": na / (ms_a * 1e-3), "fresh_rows": cfg.n_txt + na}
         wa.close()
+    if not args.no_fp8:
+        out["fp8_projections"] = fp8_projections(torch, rg, int(n))
     if not args.no_membound:
         out["membound"] = membound(torch, rg)
     if not args.no_cpu_baseline:

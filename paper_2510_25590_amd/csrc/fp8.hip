@@ -9,23 +9,26 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 
 constexpr float kE4M3Max = 448.0f;
 
-// One wave per row; the row stays in registers between the maximum and the conversion (MAXV 16-byte pieces per lane).
+// TPR threads per row (64: four rows per workgroup, 256: one); the row stays in registers between the maximum and the
+// conversion (up to 8 16-byte pieces per thread, so 4096 columns per wave and 16384 per workgroup).
 //   amax = max |x|;  scale = amax / 448;  code = e4m3(clamp(x * (448 / amax), +-448)), round to nearest even
 // (v_cvt_pk_fp8_f32).  The divisions are IEEE float32 divisions, the product a float32 product.
-template <int MAXV>
+template <int TPR>
 __global__ void __launch_bounds__(256)
 quantize_rows_fp8_kernel(const bf16_t* __restrict__ x, int64_t rows, int cols, uint8_t* __restrict__ q, float* __restrict__ scale) {
-    const int lane = threadIdx.x & 63;
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (row >= rows) return;
+    constexpr int MAXV = 8, RPB = 256 / TPR;
+    __shared__ float wave_max[4];
+    const int t = threadIdx.x % TPR;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * RPB + threadIdx.x / TPR;
+    const bool live_row = row < rows;      // (a workgroup of TPR = 256 has one row, so the barrier below is uniform)
     const int pieces = cols >> 3;
-    const bf16x8* src = reinterpret_cast<const bf16x8*>(x + row * cols);
+    const bf16x8* src = reinterpret_cast<const bf16x8*>(x + (live_row ? row : 0) * cols);
     bf16x8 v[MAXV];
     float amax = 0.f;
 #pragma unroll
     for (int i = 0; i < MAXV; ++i) {
-        const int p = i * 64 + lane;
-        if (p < pieces) {
+        const int p = i * TPR + t;
+        if (live_row && p < pieces) {
             v[i] = src[p];
 #pragma unroll
             for (int e = 0; e < 8; ++e) amax = __builtin_fmaxf(amax, __builtin_fabsf(static_cast<float>(v[i][e])));
@@ -33,13 +36,19 @@ quantize_rows_fp8_kernel(const bf16_t* __restrict__ x, int64_t rows, int cols, u
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) amax = __builtin_fmaxf(amax, __shfl_xor(amax, off, 64));
+    if (TPR == 256) {
+        if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = amax;
+        __syncthreads();
+        amax = __builtin_fmaxf(__builtin_fmaxf(wave_max[0], wave_max[1]), __builtin_fmaxf(wave_max[2], wave_max[3]));
+    }
+    if (!live_row) return;
     const bool live = amax > 0.f;
     const float mult = live ? kE4M3Max / amax : 1.0f;
-    if (lane == 0) scale[row] = live ? amax / kE4M3Max : 1.0f;
+    if (t == 0) scale[row] = live ? amax / kE4M3Max : 1.0f;
     uint2* dst = reinterpret_cast<uint2*>(q + row * cols);
 #pragma unroll
     for (int i = 0; i < MAXV; ++i) {
-        const int p = i * 64 + lane;
+        const int p = i * TPR + t;
         if (p < pieces) {
             float y[8];
 #pragma unroll
@@ -62,12 +71,14 @@ extern "C" int regione_quantize_rows_fp8(regione_ctx* ctx, const void* x, int64_
     if (rows == 0) return REGIONE_OK;
     if (rows > (int64_t(1) << 31)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "quantize_rows_fp8: rows=%lld too many", (long long)rows);
     if (!x || !q || !scale || !rg_aligned16(x) || !rg_aligned16(q)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "quantize_rows_fp8: null or unaligned tensor");
-    const unsigned blocks = static_cast<unsigned>((rows + 3) / 4);
+    ProfScope prof(ctx, REGIONE_PROF_ROWS);
     const bf16_t* xs = static_cast<const bf16_t*>(x);
     uint8_t* qs = static_cast<uint8_t*>(q);
-    const int per_lane = (cols / 8 + 63) / 64;
-    if (per_lane <= 8) hipLaunchKernelGGL(quantize_rows_fp8_kernel<8>, dim3(blocks), dim3(256), 0, ctx->stream, xs, rows, cols, qs, scale);
-    else hipLaunchKernelGGL(quantize_rows_fp8_kernel<32>, dim3(blocks), dim3(256), 0, ctx->stream, xs, rows, cols, qs, scale);
+    // short rows: a wave per row; long rows (or few of them): a workgroup per row, so that the launch fills the chip
+    if (cols <= 2048 || (cols <= 4096 && rows >= 4096))
+        hipLaunchKernelGGL(quantize_rows_fp8_kernel<64>, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, ctx->stream, xs, rows, cols, qs, scale);
+    else
+        hipLaunchKernelGGL(quantize_rows_fp8_kernel<256>, dim3(static_cast<unsigned>(rows)), dim3(256), 0, ctx->stream, xs, rows, cols, qs, scale);
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
 }

@@ -45,7 +45,7 @@ def _rows(rng, rows, cols):
     return _bf16(x)
 
 
-@pytest.mark.parametrize("rows,cols", [(1, 8), (7, 64), (130, 3072), (9, 12288), (33, 16384), (5, 4104), (1025, 512)])
+@pytest.mark.parametrize("rows,cols", [(1, 8), (7, 64), (130, 3072), (9, 12288), (33, 16384), (5, 4104), (1025, 512), (4100, 3072), (6, 2048)])
 def test_quantize_rows_bit_exact(ctx, rows, cols):
     rng = np.random.default_rng(rows * 31 + cols)
     x = _rows(rng, rows, cols)
