@@ -317,6 +317,38 @@ def fp8_projections(torch, rg, n_rows: int):
     return res
 
 
+def measured_peaks(torch, rg):
+    """What this chip sustains on register-only MFMA loops (at the clock it holds under that load) and on a plain 1 GiB copy
+    through the library's own row kernel: the figures to read the achieved TFLOP/s and GB/s against, beside the nominal peaks."""
+    ctx = rg.Context(256, 4, 64, 1024, 16, 16)
+    res = {}
+    out = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
+    rg.regione_profile_enable(ctx, True)
+    for name, fmt, nominal in (("mfma_bf16", 0, PEAK_BF16_TFLOPS), ("mfma_fp8_e4m3", 1, PEAK_FP8_TFLOPS)):
+        best = None
+        for wgs in (512, 1024, 2048):           # 2, 4 and 8 waves per SIMD
+            rg.regione_mfma_peak_probe(ctx, fmt, 2000, wgs, out)
+            rg.regione_profile_read(ctx)
+            flops = sum(rg.regione_mfma_peak_probe(ctx, fmt, 20000, wgs, out) for _ in range(3))
+            ms = rg.regione_profile_read(ctx)["gemm"][0]
+            tf = flops / ms * 1e-9
+            if best is None or tf > best[0]:
+                best = (tf, wgs, ms / 3)
+        res[name] = {"TFLOPs": best[0], "workgroups": best[1], "ms": best[2], "nominal_TFLOPs": nominal, "frac_of_nominal": best[0] / nominal,
+                     "implied_clock_GHz": best[0] / nominal * 2.4}
+    n = 1 << 28
+    src = torch.zeros(n, dtype=torch.float32, device="cuda"); dst = torch.empty_like(src)
+    rg.regione_cast(ctx, src, rg.FP32, dst, rg.FP32, n)
+    rg.regione_profile_read(ctx)
+    for _ in range(5):
+        rg.regione_cast(ctx, src, rg.FP32, dst, rg.FP32, n)
+    ms = rg.regione_profile_read(ctx)["rows"][0] / 5
+    rg.regione_profile_enable(ctx, False)
+    res["hbm_copy"] = {"bytes_read_plus_written": 8 * n, "ms": ms, "GB/s": 8 * n / ms / 1e6, "nominal_GB/s": PEAK_HBM_GBS, "frac_of_nominal": 8 * n / ms / 1e6 / PEAK_HBM_GBS}
+    ctx.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -325,6 +357,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-membound", action="store_true")
     ap.add_argument("--no-fp8", action="store_true", help="skip the secondary measurement of the projections in E4M3")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the register-only MFMA loops and the 1 GiB copy that measure the chip's own peaks")
     ap.add_argument("--no-mode-a", action="store_true", help="skip the secondary measurement with the text rows fresh")
     ap.add_argument("--no-profile", action="store_true", help="time the steps without the per-kernel event pairs")
     ap.add_argument("--copy-probe", action="store_true",
@@ -440,6 +473,8 @@ def main():
         ms_a = (time.perf_counter() - t0) * 1e3 / args.steps
         out["text_fresh"] = {"ms_per_step": ms_a, "edited_tokens_per_s": na / (ms_a * 1e-3), "fresh_rows": cfg.n_txt + na}
         wa.close()
+    if not args.no_peaks:
+        out["measured_peaks"] = measured_peaks(torch, rg)
     if not args.no_fp8:
         out["fp8_projections"] = fp8_projections(torch, rg, int(n))
     if not args.no_membound:

@@ -365,6 +365,16 @@ enum { REGIONE_PROF_PARTITION = 0, REGIONE_PROF_ROWS = 1, REGIONE_PROF_LAYERNORM
 int regione_profile_enable(regione_ctx* ctx, int32_t on);
 int regione_profile_read(regione_ctx* ctx, double* total_ms_host, int64_t* launches_host, int32_t n_classes);
 
+/* Matrix-core peak probe for benchmarks (not part of the method): what the MFMA units of THIS
+ * chip sustain at the clock it holds under load, to read the achieved TFLOP/s against.  Every
+ * wave runs `iters` rounds of four independent register-only MFMAs (format 0: bf16
+ * v_mfma_f32_32x32x16_bf16; 1: E4M3 v_mfma_f32_32x32x64_f8f6f4) on pseudo-random finite
+ * operands and stores one float per lane so the work cannot be dropped.  n_workgroups
+ * workgroups of 256 threads; out: float32 [n_workgroups * 256].  The launch is timed under
+ * REGIONE_PROF_GEMM; *flops_host receives the work of the launch (n_workgroups * 4 waves *
+ * iters * 4 * 2 * 32 * 32 * K, K = 16 or 64). */
+int regione_mfma_peak_probe(regione_ctx* ctx, int32_t format, int32_t iters, int32_t n_workgroups, float* out, double* flops_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,7 @@ EXPORTS = (
     "regione_layernorm", "regione_stage_plan_host", "regione_cast", "regione_mask_cleanup", "regione_rope_table",
     "regione_vec_linear", "regione_timestep_embedding", "regione_block_forward_batched",
     "regione_sq_norms", "regione_gamma_fit_host", "regione_guidance_combine", "regione_rel_change",
-    "regione_quantize_rows_fp8", "regione_pack_weight_fp8", "regione_linear_fp8",
+    "regione_quantize_rows_fp8", "regione_pack_weight_fp8", "regione_linear_fp8", "regione_mfma_peak_probe",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -94,6 +94,7 @@ def lib() -> C.CDLL:
             "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
             "regione_pack_weight": [vp, vp, i32, i32, vp],
+            "regione_mfma_peak_probe": [vp, i32, i32, i32, vp, C.POINTER(C.c_double)],
             "regione_quantize_rows_fp8": [vp, vp, i64, i32, vp, vp],
             "regione_pack_weight_fp8": [vp, vp, i32, i32, vp],
             "regione_linear_fp8": [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp],
@@ -300,6 +301,13 @@ def regione_packed_weight_elems(n: int, k: int) -> int:
 
 def regione_pack_weight(ctx, w, n, k, w_packed):
     _check(lib().regione_pack_weight(ctx.handle, _p(w), n, k, _p(w_packed)))
+
+
+def regione_mfma_peak_probe(ctx, fmt: int, iters: int, n_workgroups: int, out) -> float:
+    """Enqueues the probe; returns the floating point operations of the launch."""
+    flops = C.c_double(0.0)
+    _check(lib().regione_mfma_peak_probe(ctx.handle, fmt, iters, n_workgroups, _p(out), C.byref(flops)))
+    return flops.value
 
 
 def regione_quantize_rows_fp8(ctx, x, rows, cols, q, scale):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libregione.so")
-SOURCES = ["api.hip", "partition.hip", "rows.hip", "gemm.hip", "attention.hip", "block_extras.hip", "fp8.hip"]
+SOURCES = ["api.hip", "partition.hip", "rows.hip", "gemm.hip", "attention.hip", "block_extras.hip", "fp8.hip", "peaks.hip"]
 
 
 def build(verbose: bool = False) -> str:

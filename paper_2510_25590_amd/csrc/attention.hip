@@ -502,12 +502,12 @@ int launch_attention(regione_ctx* ctx, AttnArgs a) {
     const int groups_per_xcd = (a.heads * splits + 7) / 8;
     const dim3 grid(static_cast<unsigned>(groups_per_xcd) * q_tiles * 8);
     constexpr size_t lds_bytes = static_cast<size_t>(NSTAGE) * 2 * KT * D * sizeof(bf16_t);
-    static bool attr_set = false;   // per instantiation: more than 64 KiB of LDS has to be granted explicitly
-    if (!attr_set) {
+    constexpr uint32_t grant_bit = 1u << (24 + (D == 128 ? 1 : 0));   // bits 0-23 belong to the GEMM kernels
+    if (!(ctx->lds_grant_mask & grant_bit)) {   // per instantiation: more than 64 KiB of LDS has to be granted explicitly
         RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, SRC_INDEXED>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
         RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, SRC_TWO>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
         RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kvcache_kernel<D, NW, QB, NSTAGE, WPE, SRC_CONTIG>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
-        attr_set = true;
+        ctx->lds_grant_mask |= grant_bit;
     }
     // a lane's byte offset inside a tile of a contiguous source has to fit 32 bits
     const int64_t src_ld = a.n0 > 0 ? a.ldkv0 : a.ldkv1;

@@ -31,6 +31,9 @@ struct regione_ctx {
     size_t gemm_part_bytes;
     int gemm_force_tn, gemm_force_splits;  // 0 = chosen per call
     int attn_force_splits;  // 0 = chosen per call
+    // kernels that need more than 64 KiB of LDS have to be granted it once per device: one bit per kernel family and
+    // instantiation that this context (one device) has already asked for
+    uint32_t lds_grant_mask;
     // optional per-kernel-class timing with HIP events on the context's stream
     int prof_on;
     int prof_used;

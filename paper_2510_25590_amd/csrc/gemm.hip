@@ -829,10 +829,10 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, in
     const int group_rows = m_tiles > 8 ? 4 : m_tiles;
     if (VARIANT != 0) {
         constexpr unsigned lds_bytes = LdsGemm<TN, WM>::LDS_BYTES;
-        static bool attr_set = false;   // per instantiation: more than 64 KiB of LDS has to be granted explicitly
-        if (!attr_set) {
+        constexpr uint32_t grant_bit = 1u << ((TN - 1) + 2 * (WM - 1) + 4 * KIND);   // bits 0-11
+        if (!(ctx->lds_grant_mask & grant_bit)) {   // per instantiation: more than 64 KiB of LDS has to be granted explicitly
             RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel<TN, WM, KIND>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
-            attr_set = true;
+            ctx->lds_grant_mask |= grant_bit;
         }
         hipLaunchKernelGGL((gemm_lds_kernel<TN, WM, KIND>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads * WM), lds_bytes, ctx->stream,
                            a, lda, wp, m, n, k, m_tiles, n_tiles, tiles_per_xcd, group_rows, per, partial, ep);
@@ -890,10 +890,10 @@ int launch_gemm_fp8(regione_ctx* ctx, const bf16_t* a, int lda2, const bf16_t* w
     float* partial = used_splits > 1 ? ctx->gemm_part : nullptr;
     const int group_rows = m_tiles > 8 ? 4 : m_tiles;
     constexpr unsigned lds_bytes = LdsGemm<TN, 1>::LDS_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
+    constexpr uint32_t grant_bit = 1u << (12 + (TN - 1));   // bits 12-13
+    if (!(ctx->lds_grant_mask & grant_bit)) {
         RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel<TN, 1, EPI_PLAIN, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
-        attr_set = true;
+        ctx->lds_grant_mask |= grant_bit;
     }
     hipLaunchKernelGGL((gemm_lds_kernel<TN, 1, EPI_PLAIN, true>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads), lds_bytes, ctx->stream,
                        a, lda2, wp, m, n, k2, m_tiles, n_tiles, tiles_per_xcd, group_rows, per, partial, ep);

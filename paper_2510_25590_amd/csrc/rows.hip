@@ -198,6 +198,40 @@ __global__ void __launch_bounds__(kThreads) cast_kernel(const S* __restrict__ sr
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride) st<D>(dst + i, ld<S>(src + i));
 }
 
+// the same for 16-byte aligned tensors, eight elements per thread and step (n8 groups of eight)
+template <typename S, typename D>
+__global__ void __launch_bounds__(kThreads) cast8_kernel(const S* __restrict__ src, D* __restrict__ dst, int64_t n8) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; g < n8; g += stride) {
+        float v[8];
+        ld8<S>(src + g * 8, v);
+        if constexpr (sizeof(D) == 2) {
+            ln_bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(v[e]);
+            *reinterpret_cast<ln_bf16x8*>(dst + g * 8) = o;
+        } else {
+            *reinterpret_cast<ln_f32x4*>(dst + g * 8) = ln_f32x4{v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<ln_f32x4*>(dst + g * 8 + 4) = ln_f32x4{v[4], v[5], v[6], v[7]};
+        }
+    }
+}
+
+// same storage type on both sides: a plain copy in 16-byte pieces, four requested per thread before the first is stored
+typedef unsigned int copy_u32x4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(kThreads) copy16_kernel(const copy_u32x4* __restrict__ src, copy_u32x4* __restrict__ dst, int64_t n16) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        // streamed once: non-temporal on both sides, so the copy does not push other data out of the caches
+        const copy_u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
+                         c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+        __builtin_nontemporal_store(a, dst + i); __builtin_nontemporal_store(b, dst + i + stride);
+        __builtin_nontemporal_store(c, dst + i + 2 * stride); __builtin_nontemporal_store(d, dst + i + 3 * stride);
+    }
+    for (; i < n16; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
 }  // namespace
 
 extern "C" int regione_gather(regione_ctx* ctx, const void* src, int32_t row_elems, int32_t dtype,
@@ -243,18 +277,41 @@ extern "C" int regione_cast(regione_ctx* ctx, const void* src, int32_t src_dtype
     if (n_elems < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "cast: n_elems=%lld", (long long)n_elems);
     if (n_elems == 0) return REGIONE_OK;
     if (!src || !dst) RG_FAIL(REGIONE_ERR_INVALID_ARG, "cast: null tensor");
-    int64_t blocks = (n_elems + kThreads - 1) / kThreads;
-    if (blocks > 256 * 32) blocks = 256 * 32;
-    const dim3 grid(static_cast<unsigned>(blocks));
     ProfScope prof(ctx, REGIONE_PROF_ROWS);
+    const size_t src_elem = src_dtype == REGIONE_FP32 ? 4 : 2, dst_elem = dst_dtype == REGIONE_FP32 ? 4 : 2;
+    auto grid_for = [](int64_t items) { int64_t b = (items + kThreads - 1) / kThreads; return dim3(static_cast<unsigned>(b > 256 * 32 ? 256 * 32 : b)); };
+    // aligned tensors: everything but a tail of fewer than eight elements goes through the wide kernels
+    int64_t done = 0;
+    if (rg_aligned16(src) && rg_aligned16(dst) && n_elems >= 8) {
+        const int64_t n8 = n_elems / 8;
+        if (src_dtype == dst_dtype) {
+            const int64_t n16 = n8 * 8 * static_cast<int64_t>(src_elem) / 16;
+            // few, long-running workgroups (eight per CU): each thread keeps four 16-byte requests in flight
+            int64_t b = (n16 + 4 * kThreads - 1) / (4 * kThreads);
+            if (b > 256 * 8) b = 256 * 8;
+            hipLaunchKernelGGL(copy16_kernel, dim3(static_cast<unsigned>(b)), dim3(kThreads), 0, ctx->stream,
+                               static_cast<const copy_u32x4*>(src), static_cast<copy_u32x4*>(dst), n16);
+        } else if (src_dtype == REGIONE_FP32) {
+            hipLaunchKernelGGL((cast8_kernel<float, bf16_t>), grid_for(n8), dim3(kThreads), 0, ctx->stream, static_cast<const float*>(src), static_cast<bf16_t*>(dst), n8);
+        } else {
+            hipLaunchKernelGGL((cast8_kernel<bf16_t, float>), grid_for(n8), dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(src), static_cast<float*>(dst), n8);
+        }
+        RG_LAUNCH_CHECK();
+        done = n8 * 8;
+        if (done == n_elems) return REGIONE_OK;
+    }
+    const int64_t rest = n_elems - done;
+    const void* s2 = static_cast<const char*>(src) + done * src_elem;
+    void* d2 = static_cast<char*>(dst) + done * dst_elem;
+    const dim3 grid = grid_for(rest);
     if (src_dtype == REGIONE_FP32 && dst_dtype == REGIONE_BF16)
-        hipLaunchKernelGGL((cast_kernel<float, bf16_t>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(src), static_cast<bf16_t*>(dst), n_elems);
+        hipLaunchKernelGGL((cast_kernel<float, bf16_t>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(s2), static_cast<bf16_t*>(d2), rest);
     else if (src_dtype == REGIONE_BF16 && dst_dtype == REGIONE_FP32)
-        hipLaunchKernelGGL((cast_kernel<bf16_t, float>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(src), static_cast<float*>(dst), n_elems);
+        hipLaunchKernelGGL((cast_kernel<bf16_t, float>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(s2), static_cast<float*>(d2), rest);
     else if (src_dtype == REGIONE_FP32)
-        hipLaunchKernelGGL((cast_kernel<float, float>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(src), static_cast<float*>(dst), n_elems);
+        hipLaunchKernelGGL((cast_kernel<float, float>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(s2), static_cast<float*>(d2), rest);
     else
-        hipLaunchKernelGGL((cast_kernel<bf16_t, bf16_t>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(src), static_cast<bf16_t*>(dst), n_elems);
+        hipLaunchKernelGGL((cast_kernel<bf16_t, bf16_t>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(s2), static_cast<bf16_t*>(d2), rest);
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
 }

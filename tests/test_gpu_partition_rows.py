@@ -271,7 +271,7 @@ def test_mask_cleanup_degenerate_and_errors():
     ctx.close()
 
 
-@pytest.mark.parametrize("n", [0, 1, 7, 4096 * 64 + 3])
+@pytest.mark.parametrize("n", [0, 1, 7, 8, 4096 * 64, 4096 * 64 + 3, 40_000_003])
 def test_cast_between_storage_types(ctx, n):
     rng = np.random.default_rng(900 + n)
     x = (rng.standard_normal(n) * 3.0).astype(np.float32)
@@ -288,6 +288,13 @@ def test_cast_between_storage_types(ctx, n):
     same = torch.zeros(n + 1, dtype=torch.float32, device="cuda")
     rg.regione_cast(ctx, src, rg.FP32, same, rg.FP32, n)
     assert torch.equal(same[:n], src)
+    if n > 8:   # tensors that are not 16-byte aligned take the element-wise kernels
+        odd = torch.zeros(n + 1, dtype=torch.float32, device="cuda")
+        rg.regione_cast(ctx, src[1:], rg.FP32, odd[1:], rg.FP32, n - 1)
+        assert torch.equal(odd[1:n], src[1:]) and float(odd[0]) == 0.0 and float(odd[n]) == 0.0
+        odd16 = torch.zeros(n + 1, dtype=torch.bfloat16, device="cuda")
+        rg.regione_cast(ctx, src[1:], rg.FP32, odd16[1:], rg.BF16, n - 1)
+        assert torch.equal(odd16[1:n].view(torch.int16), src[1:].to(torch.bfloat16).view(torch.int16)) and float(odd16[n]) == 0.0
     with pytest.raises(rg.RegionEError):
         rg.regione_cast(ctx, src, 9, dst, rg.BF16, n)
 
