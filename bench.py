@@ -269,7 +269,7 @@ def loop_benchmark(n_double: int, n_single: int, guidance=None):
     return out
 
 
-def fp8_projections(torch, rg, n_rows: int):
+def fp8_projections(torch, rg, n_rows: int, reps: int = 20):
     """The four dense projections of the headline block on n_rows edited rows, bf16 against the E4M3 variant
     (row quantisation of the activations timed with it; weights are quantised and packed once, outside)."""
     hidden, mlp = 3072, 12288
@@ -277,7 +277,6 @@ def fp8_projections(torch, rg, n_rows: int):
     g = torch.Generator(device="cuda"); g.manual_seed(9)
     res = {"rows": n_rows, "format": "OCP E4M3, one float32 scale per activation row and per output feature", "peak_TFLOPs": PEAK_FP8_TFLOPS, "shapes": {}}
     tot = {"bf16_us": 0.0, "fp8_us": 0.0, "quantize_us": 0.0, "flops": 0.0}
-    reps = 20
     for name, n, k in (("qkv", 3 * hidden, hidden), ("attn_out", hidden, hidden), ("mlp_up", mlp, hidden), ("mlp_down", hidden, mlp)):
         x = torch.randn((n_rows, k), generator=g, device="cuda").to(torch.bfloat16)
         w = (torch.randn((n, k), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
@@ -477,6 +476,8 @@ def main():
         out["measured_peaks"] = measured_peaks(torch, rg)
     if not args.no_fp8:
         out["fp8_projections"] = fp8_projections(torch, rg, int(n))
+        # the same four projections on every row of the sequence (the shapes of a full, cache-storing forward)
+        out["fp8_projections_all_rows"] = fp8_projections(torch, rg, int(out["config"]["keys_per_query"]), reps=5)
     if not args.no_membound:
         out["membound"] = membound(torch, rg)
     if not args.no_cpu_baseline:

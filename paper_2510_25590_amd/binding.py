@@ -73,6 +73,10 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2510_25590_amd.build`")
+        # torch ships its own HIP runtime; the library must bind to THAT copy (the tensors and streams it is handed live
+        # there), so torch has to be loaded first: a process that loaded the library first would end up with two runtimes,
+        # and the second one to initialise finds no device
+        import torch  # noqa: F401
         _lib = C.CDLL(LIB_PATH)
         _lib.regione_last_error.restype = C.c_char_p
         vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float

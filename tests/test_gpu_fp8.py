@@ -183,3 +183,20 @@ def test_fp8_argument_errors(ctx):
         rg.regione_linear_fp8(ctx, q, s, q, None, None, 4, 32, 128, rg.ACT_NONE, rg.FP32, y)   # missing weight scales
     with pytest.raises(rg.RegionEError):
         rg.regione_linear_fp8(ctx, q, s, q, s, None, 4, 32, 192, rg.ACT_NONE, rg.FP32, y)      # k not a multiple of 128
+
+
+def test_mfma_peak_probe_runs_and_reports_its_work(ctx):
+    """The measurement aid: finite, reproducible output and the stated operation count; bad arguments are refused."""
+    out = torch.full((4 * 256,), float("nan"), dtype=torch.float32, device="cuda")
+    for fmt, k in ((0, 16), (1, 64)):
+        flops = rg.regione_mfma_peak_probe(ctx, fmt, 5, 4, out)
+        torch.cuda.synchronize()
+        first = out.clone()
+        assert flops == 4 * 4 * 5 * 4 * 2 * 32 * 32 * k
+        assert bool(torch.isfinite(first).all()) and float(first.abs().max()) > 0
+        rg.regione_mfma_peak_probe(ctx, fmt, 5, 4, out)
+        torch.cuda.synchronize()
+        assert torch.equal(out, first)
+    for bad in ((2, 5, 4), (0, 0, 4), (0, 5, 0)):
+        with pytest.raises(rg.RegionEError):
+            rg.regione_mfma_peak_probe(ctx, *bad, out)
