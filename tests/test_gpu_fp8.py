@@ -200,3 +200,28 @@ def test_mfma_peak_probe_runs_and_reports_its_work(ctx):
     for bad in ((2, 5, 4), (0, 0, 4), (0, 5, 0)):
         with pytest.raises(rg.RegionEError):
             rg.regione_mfma_peak_probe(ctx, *bad, out)
+
+
+def test_linear_fp8_is_reproducible(ctx):
+    """No atomics, fixed summation order: two runs (with another shape in between) give identical bits, with and
+    without a K split."""
+    rng = np.random.default_rng(21)
+    m, n, k = 300, 1024, 2048
+    xq = torch.from_numpy(_codes(rng, m, k)).cuda(); wq = torch.from_numpy(_codes(rng, n, k)).cuda()
+    sx = torch.from_numpy(rng.uniform(0.5, 2, m).astype(np.float32)).cuda(); sw = torch.from_numpy(rng.uniform(0.5, 2, n).astype(np.float32)).cuda()
+    packed = torch.zeros(rg.regione_packed_weight_elems(n, k), dtype=torch.uint8, device="cuda")
+    rg.regione_pack_weight_fp8(ctx, wq, n, k, packed)
+    for tn, splits in ((0, 0), (1, 4), (2, 2)):
+        outs = []
+        for rep in range(3):
+            y = torch.full((m, n), 3.0, dtype=torch.float32, device="cuda")
+            rg.regione_tune_gemm(ctx, tn, splits)
+            try:
+                rg.regione_linear_fp8(ctx, xq, sx, packed, sw, None, m, n, k, rg.ACT_NONE, rg.FP32, y)
+                other = torch.empty((100, n), dtype=torch.float32, device="cuda")
+                rg.regione_linear_fp8(ctx, xq, sx, packed, sw, None, 100, n, k, rg.ACT_NONE, rg.FP32, other)
+            finally:
+                rg.regione_tune_gemm(ctx, 0, 0)
+            torch.cuda.synchronize()
+            outs.append(y)
+        assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2]), (tn, splits)
