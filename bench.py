@@ -348,6 +348,75 @@ def measured_peaks(torch, rg):
     return res
 
 
+def vendor_gemm_comparison(torch, rg):
+    """The block's four projection shapes through this library's bf16 GEMM and through torch.matmul (the vendor's GEMM
+    library underneath), same process, alternating: context for the achieved TFLOP/s, not part of the path."""
+    hidden, mlp = 3072, 12288
+    ctx = rg.Context(hidden, 24, 128, mlp, 8704, 16)
+    g = torch.Generator(device="cuda"); g.manual_seed(13)
+
+    def t_vendor(fn, reps):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    def t_library(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        rg.regione_profile_enable(ctx, True); rg.regione_profile_read(ctx)
+        for _ in range(reps):
+            fn()
+        us = rg.regione_profile_read(ctx)["gemm"][0] / reps * 1e3
+        rg.regione_profile_enable(ctx, False)
+        return us
+
+    res = {}
+    for m in (820, 1640, 4096, 8704):
+        for name, n, k in (("qkv", 3 * hidden, hidden), ("attn_out", hidden, hidden), ("mlp_up", mlp, hidden), ("mlp_down", hidden, mlp)):
+            x = torch.randn((m, k), generator=g, device="cuda").to(torch.bfloat16)
+            w = (torch.randn((n, k), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+            wp = rg.pack_weight(ctx, w)
+            y = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+            reps = 20 if m < 4000 else 6
+            tv = tl = 1e30
+            for _ in range(2):
+                tv = min(tv, t_vendor(lambda: torch.matmul(x, w.t(), out=y), reps))
+                tl = min(tl, t_library(lambda: rg.regione_linear(ctx, x, wp, None, m, n, k, rg.ACT_NONE, rg.BF16, y), reps))
+            fl = 2.0 * m * n * k
+            res[f"{name}_{m}x{n}x{k}"] = {"vendor_us": tv, "library_us": tl, "vendor_TFLOPs": fl / tv * 1e-6, "library_TFLOPs": fl / tl * 1e-6,
+                                          "library_over_vendor_time": tl / tv}
+            del x, w, wp, y
+    # attention of the edited queries over the whole cached sequence, against torch's fused attention
+    heads, d, n_c = 24, 128, 8704
+    for n_q in (820, 4096):
+        q = torch.randn((n_q, heads, d), generator=g, device="cuda").to(torch.bfloat16)
+        kc = torch.randn((n_c, heads, d), generator=g, device="cuda").to(torch.bfloat16)
+        vc = torch.randn((n_c, heads, d), generator=g, device="cuda").to(torch.bfloat16)
+        out = torch.empty_like(q)
+        qh, kh, vh = (t.permute(1, 0, 2).unsqueeze(0).contiguous() for t in (q, kc, vc))     # [1, heads, n, d], as the vendor kernel wants it
+        fl = 4.0 * n_q * n_c * heads * d
+        tv = tl = 1e30
+        for _ in range(2):
+            tv = min(tv, t_vendor(lambda: torch.nn.functional.scaled_dot_product_attention(qh, kh, vh), 10))
+            rg.regione_profile_enable(ctx, True); rg.regione_profile_read(ctx)
+            for _ in range(10):
+                rg.regione_attn_kvcache(ctx, q, n_q, None, None, 0, kc, vc, n_c, None, 0, heads, d, 0.0, out)
+            tl = min(tl, rg.regione_profile_read(ctx)["attention"][0] / 10 * 1e3)
+            rg.regione_profile_enable(ctx, False)
+        ref = torch.nn.functional.scaled_dot_product_attention(qh, kh, vh)[0].permute(1, 0, 2).float()
+        res[f"attention_{n_q}q_{n_c}keys"] = {"vendor_us": tv, "library_us": tl, "vendor_TFLOPs": fl / tv * 1e-6, "library_TFLOPs": fl / tl * 1e-6,
+                                              "library_over_vendor_time": tl / tv, "max_abs_diff": float((out.float() - ref).abs().max())}
+    ctx.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -365,6 +434,8 @@ def main():
                     help="time the step with query/key normalisation and rotary embedding in the block (no CPU baseline)")
     ap.add_argument("--stack", action="store_true",
                     help="time one storing full step and one region step through 60 double-stream blocks at the large-image sizes")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="only compare the bf16 GEMM of this library with torch.matmul on the block's projection shapes (one JSON line)")
     ap.add_argument("--cfg", action="store_true",
                     help="time the block for the two branches of classifier-free guidance: one batched call against two calls")
     ap.add_argument("--loop", action="store_true",
@@ -378,6 +449,10 @@ def main():
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); run it with --gpus 1")
 
     import torch
+    if args.vendor_gemm:
+        from paper_2510_25590_amd import binding as rg_
+        print(json.dumps({"vendor_gemm_comparison": vendor_gemm_comparison(torch, rg_), "data": "synthetic", "dtype": "bf16"}))
+        return
     if args.copy_probe:
         a = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)
