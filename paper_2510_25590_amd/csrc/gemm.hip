@@ -796,10 +796,11 @@ struct GemmPlan { int tn; int splits; int variant; };   // variant 0: register-d
 GemmPlan plan_gemm(const regione_ctx* ctx, int m, int n, int k) {
     if (ctx->gemm_force_tn > 0)
         return {(ctx->gemm_force_tn - 1) % 2 + 1, ctx->gemm_force_splits > 0 ? ctx->gemm_force_splits : 1, (ctx->gemm_force_tn - 1) / 2};
-    // Many rows (the full forward of a storing step): the 256-row tile with both operands through LDS fetches a third
-    // fewer bytes per FLOP and measured 2-8 % faster than the 128-row kernels at 8704 rows, level at 3072-4096; at
-    // 2048 rows its eight row tiles leave CUs idle and it loses 10-40 %.
-    if (m >= 3072 && n >= 512) return {2, 1, 2};
+    // Many rows (the full forward of a storing step) and a narrow result: the 256-row tile with both operands through
+    // LDS fetches a third fewer bytes per FLOP and measured 4-5 % faster than the register kernel at 8704 rows and
+    // 3072 columns.  For wide results (9216, 12288 columns) the register kernel with the wide wave tile is level or
+    // up to 14 % faster at 4096-8704 rows, and at 2048 rows the eight row tiles of the 256-row kernel leave CUs idle.
+    if (m >= 3072 && n >= 512 && n < 6144) return {2, 1, 2};
     const int m_tiles = (m + BM - 1) / BM, steps = k / BK;
     GemmPlan best = {2, 1, 0};
     double best_t = 1e30;
