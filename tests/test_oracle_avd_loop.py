@@ -3,11 +3,17 @@ control flow of Algorithm 1 (CPU only).  Expected values: appendix Eq.13 (gamma 
 product of (1 - dt) factors), arithmetic on the linear 28-step schedule, and the property
 that a constant velocity field makes the sampler exact whatever is partitioned or cached.
 """
+import json
 import math
+import os
+
 import numpy as np
 import pytest
 
 from oracle import regione_oracle as orc
+
+# what the paper prints (section "Experimental Settings", Table 1): steps, stage lengths, thresholds, latencies
+PAPER = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "experimental_settings.json")))
 
 T = 28
 t_lin = np.arange(T + 1) / T          # t[T] = 1, t[0] = 0
@@ -73,7 +79,8 @@ def test_euler_constant_velocity_equals_one_big_step():
 
 def test_stage_plan_counts_for_paper_hyperparameters():
     # 28 steps, 6 stabilization steps, forced update at step 16, 2 smooth steps
-    plan, segments = orc.stage_plan(28, 6, 2, [16])
+    assert (PAPER["sampling_steps"], PAPER["stabilization_steps"], PAPER["forced_update_step"], PAPER["smooth_steps"]) == (28, 6, 16, 2)
+    plan, segments = orc.stage_plan(PAPER["sampling_steps"], PAPER["stabilization_steps"], PAPER["smooth_steps"], [PAPER["forced_update_step"]])
     kinds = [k for _, k in plan]
     assert [i for i, _ in plan] == list(range(28, 0, -1))
     assert kinds.count("region") == 19 and kinds.count("full") + kinds.count("full_store") == 9
@@ -226,3 +233,23 @@ def test_relative_trigger_changing_velocity_never_reuses_and_forced_decisions_ov
     # the first step of a segment has nothing to reuse: forcing it changes nothing
     x0_g, log_g, _, _ = _loop_with_velocity(vel, (0.05, 0.9), forced_reuse={region_steps[0]: True})
     assert [(w[0], w[1]) for w in log_g] == [(w[0], w[1]) for w in log] and np.array_equal(x0_g, x0)
+
+
+def test_paper_thresholds_on_a_uniform_schedule_with_solver_only_decay():
+    """With gamma = 1 (appendix Eq.13) and the uniform 28-step schedule, Eq.8 after one skipped step is 1 - 27/28 = 0.0357 and
+    after two 1 - (27/28)^2 = 0.0702: of the three thresholds the paper prints, only 0.04 lets a step be reused, and never
+    two in a row."""
+    want = {0.02: "F" * 10, 0.03: "F" * 10, 0.04: "FR" * 5}
+    for name, m in PAPER["models"].items():
+        got = "".join("R" if r else "F" for r, _ in _run(m["delta"], range(22, 12, -1)))
+        assert got == want[m["delta"]], name
+
+
+def test_printed_speedups_are_the_ratio_of_the_printed_latencies():
+    """Table 1 is self-consistent (this pins the fixture, not the oracle), and the ratios bound what the stage plan can give:
+    the paper's 9 full steps of 28 alone cap the speedup at 28 / 9 = 3.11, above all three printed values."""
+    plan, _ = orc.stage_plan(PAPER["sampling_steps"], PAPER["stabilization_steps"], PAPER["smooth_steps"], [PAPER["forced_update_step"]])
+    n_full = sum(1 for _, k in plan if k != "region")
+    for name, m in PAPER["models"].items():
+        assert abs(m["latency_vanilla_s"] / m["latency_regione_s"] - m["speedup"]) < 2e-3, name
+        assert m["speedup"] < PAPER["sampling_steps"] / n_full
