@@ -344,6 +344,15 @@ def measured_peaks(torch, rg):
     ms = rg.regione_profile_read(ctx)["rows"][0] / 5
     rg.regione_profile_enable(ctx, False)
     res["hbm_copy"] = {"bytes_read_plus_written": 8 * n, "ms": ms, "GB/s": 8 * n / ms / 1e6, "nominal_GB/s": PEAK_HBM_GBS, "frac_of_nominal": 8 * n / ms / 1e6 / PEAK_HBM_GBS}
+    # the same copy by the HIP runtime (torch's copy_ of a contiguous tensor), for comparison
+    dst.copy_(src); torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record(); torch.cuda.synchronize()
+    ms_rt = e0.elapsed_time(e1) / 5
+    res["hbm_copy_runtime"] = {"ms": ms_rt, "GB/s": 8 * n / ms_rt / 1e6, "frac_of_nominal": 8 * n / ms_rt / 1e6 / PEAK_HBM_GBS}
     ctx.close()
     return res
 

@@ -217,17 +217,19 @@ __global__ void __launch_bounds__(kThreads) cast8_kernel(const S* __restrict__ s
     }
 }
 
-// same storage type on both sides: a plain copy in 16-byte pieces, four requested per thread before the first is stored
+// same storage type on both sides: a plain copy in 16-byte pieces, U requested per thread before the first is stored
 typedef unsigned int copy_u32x4 __attribute__((ext_vector_type(4)));
-__global__ void __launch_bounds__(kThreads) copy16_kernel(const copy_u32x4* __restrict__ src, copy_u32x4* __restrict__ dst, int64_t n16) {
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-    int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
+template <int U, int THREADS>
+__global__ void __launch_bounds__(THREADS) copy16_kernel(const copy_u32x4* __restrict__ src, copy_u32x4* __restrict__ dst, int64_t n16) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * THREADS;
+    int64_t i = static_cast<int64_t>(blockIdx.x) * THREADS + threadIdx.x;
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
         // streamed once: non-temporal on both sides, so the copy does not push other data out of the caches
-        const copy_u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
-                         c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
-        __builtin_nontemporal_store(a, dst + i); __builtin_nontemporal_store(b, dst + i + stride);
-        __builtin_nontemporal_store(c, dst + i + 2 * stride); __builtin_nontemporal_store(d, dst + i + 3 * stride);
+        copy_u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], dst + i + u * stride);
     }
     for (; i < n16; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
@@ -287,9 +289,13 @@ extern "C" int regione_cast(regione_ctx* ctx, const void* src, int32_t src_dtype
         if (src_dtype == dst_dtype) {
             const int64_t n16 = n8 * 8 * static_cast<int64_t>(src_elem) / 16;
             // few, long-running workgroups (eight per CU): each thread keeps four 16-byte requests in flight
-            int64_t b = (n16 + 4 * kThreads - 1) / (4 * kThreads);
-            if (b > 256 * 8) b = 256 * 8;
-            hipLaunchKernelGGL(copy16_kernel, dim3(static_cast<unsigned>(b)), dim3(kThreads), 0, ctx->stream,
+            // one long-running workgroup per CU, sixteen 16-byte requests in flight per thread: 5.6 TB/s on a 1 GiB copy,
+            // against 4.4 TB/s with 2048 workgroups of four requests per thread and 5.0-5.2 TB/s with one request per
+            // thread (and for the HIP runtime's own copy), all measured in one process
+            constexpr int U = 16, THREADS = 512;
+            int64_t b = (n16 + U * THREADS - 1) / (U * THREADS);
+            if (b > 256) b = 256;
+            hipLaunchKernelGGL((copy16_kernel<U, THREADS>), dim3(static_cast<unsigned>(b)), dim3(THREADS), 0, ctx->stream,
                                static_cast<const copy_u32x4*>(src), static_cast<copy_u32x4*>(dst), n16);
         } else if (src_dtype == REGIONE_FP32) {
             hipLaunchKernelGGL((cast8_kernel<float, bf16_t>), grid_for(n8), dim3(kThreads), 0, ctx->stream, static_cast<const float*>(src), static_cast<bf16_t*>(dst), n8);
