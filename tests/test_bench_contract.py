@@ -30,3 +30,24 @@ def test_every_flag_in_a_committed_profile_command_is_a_flag_of_bench():
             seen += 1
             assert set(flags) <= known, (name, set(flags) - known)
     assert seen >= 5
+
+
+def test_product_and_oracle_share_no_code():
+    """The library's Python side never imports the oracle, the oracle never imports the library, and bench.py reaches the
+    oracle only inside its CPU-baseline leg."""
+    pkg = os.path.join(ROOT, "paper_2510_25590_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), f
+                assert "oracle/" not in text and "regione_oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith(".py"):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert not re.search(r"^\s*(from|import)\s+paper_2510_25590_amd\b", text, re.M), f
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    uses = [m.start() for m in re.finditer(r"^\s*(from|import)\s+oracle\b", bench, re.M)]
+    start = bench.index("def cpu_baseline(")
+    end = bench.index("\ndef ", start + 1)
+    assert uses and all(start < u < end for u in uses)
