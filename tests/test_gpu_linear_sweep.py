@@ -73,3 +73,44 @@ def test_linear_fp8_forced_plans(ctx, m, n, k, tn, splits):
     finally:
         rg.regione_tune_gemm(ctx, 0, 0)
     assert np.all(np.abs(y.cpu().numpy() - want) <= mag * 2.0 ** -11 + 1e-30)
+
+
+def _attn_cases(seed, count):
+    rnd = random.Random(seed)
+    out = []
+    for _ in range(count):
+        d = rnd.choice([64, 128])
+        n_q = rnd.choice([1, 7, 32, 33, 127, 128, 129, 200, 300])
+        n_fresh = rnd.choice([0, 0, 1, 17, 64, 65, n_q])
+        n_c = rnd.choice([0, 1, 63, 64, 65, 191, 500, 1200, 2100])
+        if n_fresh + n_c == 0:
+            n_c = 70
+        use_index = n_c > 2 and rnd.random() < 0.4
+        splits = rnd.choice([0, 1, 2, 3, 5, 8])
+        out.append((d, n_q, n_fresh, n_c, use_index, splits))
+    return out
+
+
+@pytest.mark.parametrize("d,n_q,n_fresh,n_c,use_index,splits", _attn_cases(21, 30))
+def test_attention_forced_key_splits(ctx, d, n_q, n_fresh, n_c, use_index, splits):
+    """Eq.6 in all three key-source forms (contiguous cache, fresh + cache, fresh + cache rows by index list) with every
+    number of key-range splits, on key counts around the 64-key tile."""
+    from tests.gpu_util import assert_close
+    heads = 2
+    rng = np.random.default_rng(d + 3 * n_q + 5 * n_fresh + 7 * n_c + splits)
+    bf = lambda a: torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16)
+    q, kf, vf = bf(rng.standard_normal((n_q, heads, d))), bf(rng.standard_normal((n_fresh, heads, d))), bf(rng.standard_normal((n_fresh, heads, d)))
+    kc, vc = bf(rng.standard_normal((n_c, heads, d))), bf(rng.standard_normal((n_c, heads, d)))
+    idx = np.sort(rng.choice(n_c, size=max(1, (2 * n_c) // 3), replace=False)).astype(np.int32) if use_index else None
+    want = orc.attention_kvcache(q.float().numpy(), kf.float().numpy(), vf.float().numpy(), kc.float().numpy() if n_c else None,
+                                 vc.float().numpy() if n_c else None, idx)
+    out = torch.full((n_q, heads, d), 55.0, dtype=torch.bfloat16, device="cuda")
+    rg.regione_tune_attention(ctx, splits)
+    try:
+        rg.regione_attn_kvcache(ctx, q.cuda(), n_q, kf.cuda() if n_fresh else None, vf.cuda() if n_fresh else None, n_fresh,
+                                kc.cuda() if n_c else None, vc.cuda() if n_c else None, n_c,
+                                None if idx is None else torch.from_numpy(idx).cuda(), 0 if idx is None else len(idx), heads, d, 0.0, out)
+        torch.cuda.synchronize()
+    finally:
+        rg.regione_tune_attention(ctx, 0)
+    assert_close(out.float().cpu().numpy(), want, f"attention d={d} q={n_q} fresh={n_fresh} cache={n_c} index={use_index} splits={splits}")
