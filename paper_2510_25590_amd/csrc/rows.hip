@@ -291,7 +291,7 @@ extern "C" int regione_cast(regione_ctx* ctx, const void* src, int32_t src_dtype
             // few, long-running workgroups (eight per CU): each thread keeps four 16-byte requests in flight
             // one long-running workgroup per CU, sixteen 16-byte requests in flight per thread: 5.6 TB/s on a 1 GiB copy,
             // against 4.4 TB/s with 2048 workgroups of four requests per thread and 5.0-5.2 TB/s with one request per
-            // thread (and for the HIP runtime's own copy), all measured in one process
+            // thread, all measured in one process (the HIP runtime's copy kernel: 6.1 TB/s in a kernel trace)
             constexpr int U = 16, THREADS = 512;
             int64_t b = (n16 + U * THREADS - 1) / (U * THREADS);
             if (b > 256) b = 256;
