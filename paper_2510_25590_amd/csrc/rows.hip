@@ -198,6 +198,25 @@ __global__ void __launch_bounds__(kThreads) cast_kernel(const S* __restrict__ sr
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride) st<D>(dst + i, ld<S>(src + i));
 }
 
+// same storage type on both sides: a plain copy in 16-byte pieces; every workgroup owns one contiguous range and every
+// thread requests U pieces before it stores the first (non-temporal on both sides: the data is streamed once)
+typedef unsigned int copy_u32x4 __attribute__((ext_vector_type(4)));
+template <int U, int THREADS>
+__global__ void __launch_bounds__(THREADS) copy16_chunk_kernel(const copy_u32x4* __restrict__ src, copy_u32x4* __restrict__ dst, int64_t n16) {
+    const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    const int64_t begin = blockIdx.x * per;
+    int64_t end = begin + per; end = end < n16 ? end : n16;
+    int64_t i = begin + threadIdx.x;
+    for (; i + (U - 1) * THREADS < end; i += U * THREADS) {
+        copy_u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * THREADS);
+#pragma unroll
+        for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], dst + i + u * THREADS);
+    }
+    for (; i < end; i += THREADS) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
 // the same for 16-byte aligned tensors, eight elements per thread and step (n8 groups of eight)
 template <typename S, typename D>
 __global__ void __launch_bounds__(kThreads) cast8_kernel(const S* __restrict__ src, D* __restrict__ dst, int64_t n8) {
@@ -215,23 +234,6 @@ __global__ void __launch_bounds__(kThreads) cast8_kernel(const S* __restrict__ s
             *reinterpret_cast<ln_f32x4*>(dst + g * 8 + 4) = ln_f32x4{v[4], v[5], v[6], v[7]};
         }
     }
-}
-
-// same storage type on both sides: a plain copy in 16-byte pieces, U requested per thread before the first is stored
-typedef unsigned int copy_u32x4 __attribute__((ext_vector_type(4)));
-template <int U, int THREADS>
-__global__ void __launch_bounds__(THREADS) copy16_kernel(const copy_u32x4* __restrict__ src, copy_u32x4* __restrict__ dst, int64_t n16) {
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * THREADS;
-    int64_t i = static_cast<int64_t>(blockIdx.x) * THREADS + threadIdx.x;
-    for (; i + (U - 1) * stride < n16; i += U * stride) {
-        // streamed once: non-temporal on both sides, so the copy does not push other data out of the caches
-        copy_u32x4 v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
-#pragma unroll
-        for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], dst + i + u * stride);
-    }
-    for (; i < n16; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 }  // namespace
@@ -289,13 +291,14 @@ extern "C" int regione_cast(regione_ctx* ctx, const void* src, int32_t src_dtype
         if (src_dtype == dst_dtype) {
             const int64_t n16 = n8 * 8 * static_cast<int64_t>(src_elem) / 16;
             // few, long-running workgroups (eight per CU): each thread keeps four 16-byte requests in flight
-            // one long-running workgroup per CU, sixteen 16-byte requests in flight per thread: 5.6 TB/s on a 1 GiB copy,
-            // against 4.4 TB/s with 2048 workgroups of four requests per thread and 5.0-5.2 TB/s with one request per
-            // thread, all measured in one process (the HIP runtime's copy kernel: 6.1 TB/s in a kernel trace)
-            constexpr int U = 16, THREADS = 512;
+            // one long-running workgroup of 1024 threads per CU, each on a contiguous range, eight requests in flight per
+            // thread: 5.9 TB/s on a 1 GiB copy; the same with the ranges interleaved (grid stride) 5.4-5.6, 2048 workgroups
+            // of four requests per thread 4.4, one request per thread 5.0-5.2 - all measured in one process (the HIP
+            // runtime's copy kernel: 6.1 TB/s in a kernel trace)
+            constexpr int U = 8, THREADS = 1024;
             int64_t b = (n16 + U * THREADS - 1) / (U * THREADS);
             if (b > 256) b = 256;
-            hipLaunchKernelGGL((copy16_kernel<U, THREADS>), dim3(static_cast<unsigned>(b)), dim3(THREADS), 0, ctx->stream,
+            hipLaunchKernelGGL((copy16_chunk_kernel<U, THREADS>), dim3(static_cast<unsigned>(b)), dim3(THREADS), 0, ctx->stream,
                                static_cast<const copy_u32x4*>(src), static_cast<copy_u32x4*>(dst), n16);
         } else if (src_dtype == REGIONE_FP32) {
             hipLaunchKernelGGL((cast8_kernel<float, bf16_t>), grid_for(n8), dim3(kThreads), 0, ctx->stream, static_cast<const float*>(src), static_cast<bf16_t*>(dst), n8);
