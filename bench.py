@@ -100,6 +100,19 @@ def membound(torch, rg):
         ms = rg.regione_profile_read(ctx)["rows"][0] / reps
         nb = n_e * (2 * c * 2 + 4)
         res[name] = {"rows": n_e, "row_bytes": 2 * c, "ms": ms, "GB/s": nb / ms / 1e6, "frac_hbm": nb / ms / 1e6 / PEAK_HBM_GBS}
+    # velocity cache with the Euler update on the gathered rows (Eq.9, Eq.4): a fresh step reads v and x_e and writes the
+    # cache and x_e; a reusing step reads the cache and x_e and writes x_e
+    xe = torch.empty((n_e, c), dtype=torch.bfloat16, device="cuda").normal_(generator=g)
+    ca = torch.empty_like(xe)
+    for name, reuse, arrays in (("velocity_cache_fresh", False, 4), ("velocity_cache_reuse", True, 3)):
+        fn = lambda: rg.regione_velocity_cache(ctx, reuse, 0.9, 1 / 28, dst, ca, None, xe, cnt, n_e, c, rg.BF16)
+        fn(); rg.regione_profile_read(ctx)
+        for _ in range(reps):
+            fn()
+        ms = rg.regione_profile_read(ctx)["velocity"][0] / reps
+        nb = n_e * c * 2 * arrays
+        res[name] = {"rows": n_e, "row_bytes": 2 * c, "ms": ms, "GB/s": nb / ms / 1e6, "frac_hbm": nb / ms / 1e6 / PEAK_HBM_GBS}
+    del xe, ca
     del x_t, v, ref, score, mask, dst
     # gather / scatter of 6 KiB hidden rows: 20 % of 256 images' tokens
     hidden = 3072

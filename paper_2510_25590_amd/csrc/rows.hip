@@ -198,6 +198,46 @@ __global__ void __launch_bounds__(kThreads) cast_kernel(const S* __restrict__ sr
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride) st<D>(dst + i, ld<S>(src + i));
 }
 
+// Eq.9 / Eq.4 for 16-byte aligned tensors whose element count is a multiple of eight: eight elements per thread and
+// step, the same per-element arithmetic as velocity_cache_kernel (separately rounded product and difference).
+template <typename T> __device__ __forceinline__ void st8(T* p, const float (&v)[8]);
+template <> __device__ __forceinline__ void st8<bf16_t>(bf16_t* p, const float (&v)[8]) {
+    ln_bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(v[e]);
+    *reinterpret_cast<ln_bf16x8*>(p) = o;
+}
+template <> __device__ __forceinline__ void st8<float>(float* p, const float (&v)[8]) {
+    *reinterpret_cast<ln_f32x4*>(p) = ln_f32x4{v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<ln_f32x4*>(p + 4) = ln_f32x4{v[4], v[5], v[6], v[7]};
+}
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+velocity_cache_vec_kernel(int reuse, float factor, float dt, const T* __restrict__ v_fresh, T* __restrict__ c_a,
+                          T* __restrict__ v_out, T* __restrict__ x_e, const int32_t* __restrict__ n_dev, int64_t n_max, int c) {
+    int64_t n = n_max;
+    if (n_dev) { const int64_t nd = *n_dev; n = nd < n_max ? (nd < 0 ? 0 : nd) : n_max; }
+    const int64_t groups = n * c / 8;          // c is a multiple of 8 on this path
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; g < groups; g += stride) {
+        const int64_t i = g * 8;
+        float vu[8], x[8];
+        ld8<T>(x_e + i, x);
+        if (reuse) {
+            ld8<T>(c_a + i, vu);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) vu[e] = __fmul_rn(factor, vu[e]);
+        } else {
+            ld8<T>(v_fresh + i, vu);
+            st8<T>(c_a + i, vu);
+        }
+        if (v_out) st8<T>(v_out + i, vu);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = __fsub_rn(x[e], __fmul_rn(dt, vu[e]));
+        st8<T>(x_e + i, x);
+    }
+}
+
 // same storage type on both sides: a plain copy in 16-byte pieces; every workgroup owns one contiguous range and every
 // thread requests U pieces before it stores the first (non-temporal on both sides: the data is streamed once)
 typedef unsigned int copy_u32x4 __attribute__((ext_vector_type(4)));
@@ -258,10 +298,27 @@ extern "C" int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float fac
     if (!c_a || !x_e) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_cache: null c_a or x_e");
     if (!reuse && !v_fresh_opt) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_cache: a fresh step needs v_fresh");
     const int64_t total = n_max * c;
+    ProfScope prof(ctx, REGIONE_PROF_VELOCITY);
+    const bool wide = (c % 8 == 0) && rg_aligned16(c_a) && rg_aligned16(x_e) && (!v_fresh_opt || rg_aligned16(v_fresh_opt)) &&
+                      (!v_out_opt || rg_aligned16(v_out_opt));
+    if (wide) {
+        int64_t vb = (total / 8 + kThreads - 1) / kThreads;
+        if (vb > 256 * 32) vb = 256 * 32;
+        const dim3 vgrid(static_cast<unsigned>(vb));
+        if (dtype == REGIONE_BF16)
+            hipLaunchKernelGGL(velocity_cache_vec_kernel<bf16_t>, vgrid, dim3(kThreads), 0, ctx->stream, reuse, factor, dt,
+                               static_cast<const bf16_t*>(v_fresh_opt), static_cast<bf16_t*>(c_a), static_cast<bf16_t*>(v_out_opt),
+                               static_cast<bf16_t*>(x_e), n_dev, n_max, c);
+        else
+            hipLaunchKernelGGL(velocity_cache_vec_kernel<float>, vgrid, dim3(kThreads), 0, ctx->stream, reuse, factor, dt,
+                               static_cast<const float*>(v_fresh_opt), static_cast<float*>(c_a), static_cast<float*>(v_out_opt),
+                               static_cast<float*>(x_e), n_dev, n_max, c);
+        RG_LAUNCH_CHECK();
+        return REGIONE_OK;
+    }
     int64_t blocks = (total + kThreads - 1) / kThreads;
     if (blocks > 256 * 32) blocks = 256 * 32;
     dim3 grid(static_cast<unsigned>(blocks));
-    ProfScope prof(ctx, REGIONE_PROF_VELOCITY);
     if (dtype == REGIONE_BF16)
         hipLaunchKernelGGL(velocity_cache_kernel<bf16_t>, grid, dim3(kThreads), 0, ctx->stream, reuse, factor, dt,
                            static_cast<const bf16_t*>(v_fresh_opt), static_cast<bf16_t*>(c_a), static_cast<bf16_t*>(v_out_opt),
