@@ -7,6 +7,11 @@ Linear(H -> C) velocity head on the image rows.  The full forward runs every row
 step, fills one K,V cache per block); the region forward runs the edited rows only and attends to the
 cached rows of all others (Eq.6).  With a second set of text rows and a guidance scale both forwards run
 once per branch (each branch has its own caches) and return the guided velocity.
+
+Pins (tests/test_oracle_compositions.py): embedding and head written out by hand; the full forward equals the
+block chain over [text | image | reference]; a region forward over every token, or over a subset, with a
+same-step cache equals the full forward (restricted); the guided velocity is the combination of two
+single-branch editors, each branch with caches of its own.
 """
 from __future__ import annotations
 

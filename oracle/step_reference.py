@@ -2,6 +2,11 @@
 
 TEST INFRASTRUCTURE ONLY (see regione_oracle.py).  Takes plain numpy arrays and numbers;
 imports nothing from the product.
+
+Pins (tests/test_oracle_compositions.py, tests/test_oracle_block.py): with a cache stored from the step's own
+hidden state the region step equals the full forward restricted to the edited rows, in both readings of which
+rows are fresh; the merge leaves unedited rows bit-identical; velocity head, Eq.9 and Eq.4 written out by hand;
+cached rows come from the right streams; build_cache equals the cache a storing forward writes.
 """
 from __future__ import annotations
 
