@@ -50,7 +50,15 @@ enum { REGIONE_ACT_NONE = 0, REGIONE_ACT_GELU_TANH = 1, REGIONE_ACT_SILU = 2 };
 
 typedef struct regione_ctx regione_ctx;
 
-/* Sizes the workspace is allocated for. */
+/* Sizes the workspace is allocated for, and the arithmetic type of the context.
+ * compute_dtype = REGIONE_BF16 (0, the default): activations, weights and the KV cache are bf16, products run on
+ * the bf16 matrix-core instruction with float32 sums.
+ * compute_dtype = REGIONE_FP32: every tensor that this header calls bf16 for regione_pack_weight, regione_linear,
+ * regione_layernorm (its output), regione_attn_kvcache, regione_block_forward(_batched) (activations, KV cache, and
+ * h_dtype must be REGIONE_FP32) is float32 instead, products run on the float32 matrix-core instruction
+ * (v_mfma_f32_32x32x2_f32) and the softmax in float32: the small float32 configuration the method is first checked
+ * on.  One simple tile shape, built for correctness, not speed.  The block extras (q_norm / k_norm / rope) and the
+ * 8-bit projections are bf16-context features: REGIONE_ERR_UNSUPPORTED in a float32 context. */
 typedef struct regione_dims {
     int32_t hidden;     /* H = heads * head_dim */
     int32_t heads;
@@ -58,6 +66,7 @@ typedef struct regione_dims {
     int32_t mlp;        /* MLP width M */
     int32_t max_fresh;  /* most rows one regione_block_forward call will carry */
     int32_t max_tokens; /* most tokens one regione_partition call will carry */
+    int32_t compute_dtype; /* REGIONE_BF16 or REGIONE_FP32 */
 } regione_dims;
 
 /* Weights of one stream of a block (host struct of device pointers to PACKED weights).
@@ -209,16 +218,6 @@ int regione_pack_weight_fp8(regione_ctx* ctx, const void* wq /*[n,k] uint8 row-m
 int regione_linear_fp8(regione_ctx* ctx, const void* xq, const float* x_scale, const void* wq_packed, const float* w_scale,
                        const float* b_opt, int32_t m, int32_t n, int32_t k, int32_t act, int32_t out_dtype, void* y);
 
-/* Tuning knob for experiments: forces the GEMM wave tile (1 or 2 blocks of 32 columns; 3 or 4 =
- * the same two widths with the kernel that stages both operands through LDS, 5 or 6 = that
- * kernel with 256-row workgroup tiles) and the number of K splits of every later GEMM of this
- * context; 0 restores the automatic choice. */
-int regione_tune_gemm(regione_ctx* ctx, int32_t wave_tile_blocks, int32_t k_splits);
-
-/* Tuning knob for experiments: forces the number of key-range splits (1..8) of every later
- * attention call of this context; 0 restores the automatic choice. */
-int regione_tune_attention(regione_ctx* ctx, int32_t key_splits);
-
 /* One transformer block on the fresh rows: one layer of Phi(tokens, C_KV, f) in
  * Algorithm 1.  The block is LayerNorm (no affine, eps 1e-6) -> modulation -> QKV linear ->
  * attention -> gated residual -> LayerNorm -> modulation -> MLP with tanh-GELU -> gated
@@ -320,13 +319,41 @@ int regione_guidance_combine(regione_ctx* ctx, const void* v_cond, const void* v
 /* Sums behind the relative change |v_new - v_old|_2 / |v_old|_2 of two velocities:
  * out[0] = sum (v_new - v_old)^2, out[1] = sum v_old^2 (float64 on the device, fixed order).
  * NOT the paper's reuse criterion (Eq.8 depends on the schedule alone): a data-dependent trigger
- * ("reuse the cached velocity with decay 0.9 when the relative velocity change is below 0.05")
+ * (reuse of the decayed cached velocity while the velocity changes by less than a threshold in relative norm)
  * that the loop benchmark's workload description asks for; the sampling loop offers it beside
  * regione_velocity_decision_host.  The arrays have n_elems elements of `dtype`. */
-int regione_rel_change(regione_ctx* ctx, const void* v_new, const void* v_old, int64_t n_elems, int32_t dtype, double* out);
+/* out_host_opt: host double[2] or NULL; when given the call waits for the stream and copies the two sums there. */
+int regione_rel_change(regione_ctx* ctx, const void* v_new, const void* v_old, int64_t n_elems, int32_t dtype, double* out,
+                       double* out_host_opt);
 
-/* Fitting the timestep-aware factor gamma of Eq.7 ("obtained by fitting on a randomly sampled
- * dataset"; the paper gives no procedure, this is least squares through the origin).
+/* Host side of that trigger (pure functions of the state, like regione_velocity_decision_host for Eq.8).  The state is
+ * all zeros at the first region step of every segment.
+ * regione_rel_decision_host, before a region step: *reuse = 1 and *factor = decay when the previous fresh step asked
+ *   for a reuse and a cached velocity exists, else *reuse = 0, *factor = 1; the request is consumed, so two reuses
+ *   never follow each other.
+ * regione_rel_update_host, after a FRESH region step and before regione_velocity_cache overwrites the cache:
+ *   sums_host_opt = the two sums of regione_rel_change(new velocity, cached velocity), or NULL when there is nothing to
+ *   compare (no edited row).  With a cached velocity and sums, rel = sqrt(sums[0]) / sqrt(sums[1]) (infinity when the
+ *   old norm is zero) and the NEXT step is asked to reuse iff rel < threshold; otherwise no reuse is asked for and rel
+ *   is infinity.  Marks the cache as filled.  *rel_out_opt receives rel. */
+typedef struct regione_rel_state {
+    int32_t have_cache; /* the velocity cache holds a fresh velocity of this segment */
+    int32_t reuse_next; /* the last fresh step changed little: the next step may reuse */
+} regione_rel_state;
+int regione_rel_decision_host(regione_rel_state* st, float decay, int32_t* reuse, float* factor);
+int regione_rel_update_host(regione_rel_state* st, const double* sums_host_opt, float threshold, double* rel_out_opt);
+
+/* Slot list of a region step whose text rows are fresh as well (Eq.6 as printed: the input is [X^P, X^E]):
+ * slots[i] = i for i < n_txt, slots[n_txt + i] = index[i] + n_txt for i < n (n as in regione_gather): image row r sits
+ * at position n_txt + r of the cached sequence.  slots: [n_txt + n_max] int32. */
+int regione_fresh_slots(regione_ctx* ctx, const int32_t* index, const int32_t* n_dev, int64_t n_max, int32_t n_txt, int32_t* slots);
+
+/* out[i] = b[i] + t * b_time[i] (float32, product and sum rounded separately): the bias of a token embedding that
+ * carries the time, as the small editor around the blocks uses it (the paper keeps such details inside its DiT). */
+int regione_time_bias(regione_ctx* ctx, const float* b, const float* b_time, float t, float* out, int32_t n);
+
+/* Fitting the timestep-aware factor gamma of Eq.7 (the paper says only that it is fitted on sampled data and gives
+ * no procedure; this is least squares through the origin).
  * regione_sq_norms: out[i] = sum of squares of vector i, for n_vectors contiguous vectors of
  *   vec_elems elements of `dtype` (16-byte aligned, vec_elems a multiple of 8 for bf16 / 4 for
  *   float32); out is [n_vectors] float64 on the device.  Squares and sums in float64, in a fixed
@@ -358,26 +385,6 @@ int regione_velocity_decision_host(const float* t_host, const float* gamma_host,
 int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float factor, float dt,
                            const void* v_fresh_opt, void* c_a, void* v_out_opt, void* x_e,
                            const int32_t* n_dev, int64_t n_max, int32_t c, int32_t dtype);
-
-/* Per-kernel-class timing for benchmarks (not part of the method).  While enabled, every
- * kernel launch group of the context is bracketed by a HIP event pair on its stream (at most
- * 8192 pairs between two reads).  regione_profile_read waits for the stream, adds the elapsed
- * milliseconds and the number of launch groups of each class into the two host arrays of
- * n_classes entries (index = REGIONE_PROF_*), and clears the recorded pairs. */
-enum { REGIONE_PROF_PARTITION = 0, REGIONE_PROF_ROWS = 1, REGIONE_PROF_LAYERNORM = 2, REGIONE_PROF_GEMM = 3,
-       REGIONE_PROF_ATTENTION = 4, REGIONE_PROF_VELOCITY = 5, REGIONE_PROF_CLASSES = 6 };
-int regione_profile_enable(regione_ctx* ctx, int32_t on);
-int regione_profile_read(regione_ctx* ctx, double* total_ms_host, int64_t* launches_host, int32_t n_classes);
-
-/* Matrix-core peak probe for benchmarks (not part of the method): what the MFMA units of THIS
- * chip sustain at the clock it holds under load, to read the achieved TFLOP/s against.  Every
- * wave runs `iters` rounds of four independent register-only MFMAs (format 0: bf16
- * v_mfma_f32_32x32x16_bf16; 1: E4M3 v_mfma_f32_32x32x64_f8f6f4) on pseudo-random finite
- * operands and stores one float per lane so the work cannot be dropped.  n_workgroups
- * workgroups of 256 threads; out: float32 [n_workgroups * 256].  The launch is timed under
- * REGIONE_PROF_GEMM; *flops_host receives the work of the launch (n_workgroups * 4 waves *
- * iters * 4 * 2 * 32 * 32 * K, K = 16 or 64). */
-int regione_mfma_peak_probe(regione_ctx* ctx, int32_t format, int32_t iters, int32_t n_workgroups, float* out, double* flops_host);
 
 #ifdef __cplusplus
 }

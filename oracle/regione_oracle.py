@@ -396,8 +396,8 @@ def guidance_combine(v_cond, v_uncond, scale: float) -> np.ndarray:
 
 
 def fit_gamma(norms: np.ndarray, t) -> np.ndarray:
-    """Timestep-aware factor of Eq.7 from sampled trajectories ("obtained by fitting on a randomly
-    sampled dataset"; the paper does not say how: here least squares through the origin).
+    """Timestep-aware factor of Eq.7 from sampled trajectories (the paper says only that the factor is
+    fitted on sampled data, not how: here least squares through the origin).
     norms[s, j] = |v_{t_j}| of sample s for j = 1..T (column 0 is not used); t has T+1 entries.
     For j = 1..T-1 the slope c_j of |v_{t_j}| against |v_{t_{j+1}}| over the samples is
     sum_s a_s b_s / sum_s b_s^2, and gamma_j = c_j / (1 - (t_{j+1} - t_j)).  gamma_0 = gamma_T = 1

@@ -29,6 +29,7 @@ EXPORTS = (
     "regione_vec_linear", "regione_timestep_embedding", "regione_block_forward_batched",
     "regione_sq_norms", "regione_gamma_fit_host", "regione_guidance_combine", "regione_rel_change",
     "regione_quantize_rows_fp8", "regione_pack_weight_fp8", "regione_linear_fp8", "regione_mfma_peak_probe",
+    "regione_rel_decision_host", "regione_rel_update_host", "regione_fresh_slots", "regione_time_bias",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -36,7 +37,7 @@ PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
 
 class Dims(C.Structure):
     _fields_ = [("hidden", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32), ("mlp", C.c_int32),
-                ("max_fresh", C.c_int32), ("max_tokens", C.c_int32)]
+                ("max_fresh", C.c_int32), ("max_tokens", C.c_int32), ("compute_dtype", C.c_int32)]
 
 
 _STREAM_FIELDS = ("w_qkv", "b_qkv", "w_o", "b_o", "w_1", "b_1", "w_2", "b_2",
@@ -53,6 +54,10 @@ class BlockWeights(C.Structure):
 
 class AvdState(C.Structure):
     _fields_ = [("valid", C.c_int32), ("prod", C.c_double)]
+
+
+class RelState(C.Structure):
+    _fields_ = [("have_cache", C.c_int32), ("reuse_next", C.c_int32)]
 
 
 class PlanStep(C.Structure):
@@ -94,7 +99,11 @@ def lib() -> C.CDLL:
                                                C.POINTER(i32), C.POINTER(f32)],
             "regione_sq_norms": [vp, vp, i32, i64, i64, vp],
             "regione_guidance_combine": [vp, vp, vp, f32, vp, i64, i32],
-            "regione_rel_change": [vp, vp, vp, i64, i32, vp],
+            "regione_rel_change": [vp, vp, vp, i64, i32, vp, C.POINTER(C.c_double)],
+            "regione_rel_decision_host": [C.POINTER(RelState), f32, C.POINTER(i32), C.POINTER(f32)],
+            "regione_rel_update_host": [C.POINTER(RelState), C.POINTER(C.c_double), f32, C.POINTER(C.c_double)],
+            "regione_fresh_slots": [vp, vp, vp, i64, i32, vp],
+            "regione_time_bias": [vp, vp, vp, f32, vp, i32],
             "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
             "regione_pack_weight": [vp, vp, i32, i32, vp],
@@ -140,11 +149,14 @@ def _p(t):
 class Context:
     """Owns a regione_ctx bound to a torch stream (default: the current one)."""
 
-    def __init__(self, hidden: int, heads: int, head_dim: int, mlp: int, max_fresh: int, max_tokens: int, stream=None):
+    def __init__(self, hidden: int, heads: int, head_dim: int, mlp: int, max_fresh: int, max_tokens: int, stream=None,
+                 compute_dtype: int = BF16):
         import torch
         self._torch = torch
         self.stream = stream if stream is not None else torch.cuda.current_stream()
-        self.dims = Dims(hidden, heads, head_dim, mlp, max_fresh, max_tokens)
+        self.compute_dtype = compute_dtype
+        self.torch_dtype = torch.float32 if compute_dtype == FP32 else torch.bfloat16   # storage type of activations, weights and caches
+        self.dims = Dims(hidden, heads, head_dim, mlp, max_fresh, max_tokens, compute_dtype)
         handle = C.c_void_p()
         _check(lib().regione_create(C.byref(handle), C.byref(self.dims), C.c_void_p(self.stream.cuda_stream)))
         self.handle = handle
@@ -216,8 +228,32 @@ def regione_block_forward_batched(ctx, weights: BlockWeights, block_type, h_in, 
                                                n_txt_fresh, _p(slot_index), slot_offset, _p(k_cache), _p(v_cache), n_all, flags))
 
 
-def regione_rel_change(ctx, v_new, v_old, n_elems, dtype, out):
-    _check(lib().regione_rel_change(ctx.handle, _p(v_new), _p(v_old), n_elems, dtype, _p(out)))
+def regione_rel_change(ctx, v_new, v_old, n_elems, dtype, out, read_back: bool = False):
+    """With read_back the call waits for the stream and returns the two sums as a ctypes double[2]."""
+    host = (C.c_double * 2)() if read_back else None
+    _check(lib().regione_rel_change(ctx.handle, _p(v_new), _p(v_old), n_elems, dtype, _p(out), host))
+    return host
+
+
+def regione_rel_decision_host(state: RelState, decay: float):
+    reuse, factor = C.c_int32(0), C.c_float(0.0)
+    _check(lib().regione_rel_decision_host(C.byref(state), decay, C.byref(reuse), C.byref(factor)))
+    return bool(reuse.value), factor.value
+
+
+def regione_rel_update_host(state: RelState, sums, threshold: float) -> float:
+    """sums: the ctypes double[2] of regione_rel_change(read_back=True), or None.  Returns the relative change."""
+    rel = C.c_double(0.0)
+    _check(lib().regione_rel_update_host(C.byref(state), sums, threshold, C.byref(rel)))
+    return rel.value
+
+
+def regione_fresh_slots(ctx, index, n_dev, n_max, n_txt, slots):
+    _check(lib().regione_fresh_slots(ctx.handle, _p(index), _p(n_dev), n_max, n_txt, _p(slots)))
+
+
+def regione_time_bias(ctx, b, b_time, t, out, n):
+    _check(lib().regione_time_bias(ctx.handle, _p(b), _p(b_time), float(t), _p(out), n))
 
 
 def regione_guidance_combine(ctx, v_cond, v_uncond, scale, out, n_elems, dtype):
@@ -335,9 +371,10 @@ def regione_tune_attention(ctx, key_splits: int):
 
 
 def pack_weight(ctx, w):
-    """Convenience: packs a row-major bf16 CUDA tensor [n, k] into a new tensor in the library's layout."""
+    """Convenience: packs a row-major CUDA tensor [n, k] of the context's storage type into a new tensor in the library's layout."""
     import torch
     n, k = w.shape
-    out = torch.empty(regione_packed_weight_elems(n, k), dtype=torch.bfloat16, device=w.device)
+    assert w.dtype == ctx.torch_dtype, (w.dtype, ctx.torch_dtype)
+    out = torch.empty(regione_packed_weight_elems(n, k), dtype=w.dtype, device=w.device)
     regione_pack_weight(ctx, w.contiguous(), n, k, out)
     return out

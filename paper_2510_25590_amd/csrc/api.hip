@@ -7,6 +7,7 @@
 #include "common.h"
 #include <string.h>
 #include <new>
+#include <math.h>
 
 static thread_local char g_last_error[512] = "";
 
@@ -49,24 +50,28 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
     if (dims->head_dim != 64 && dims->head_dim != 128)
         RG_FAIL(REGIONE_ERR_UNSUPPORTED, "create: head dimension %d (64 or 128 supported)", dims->head_dim);
     if (dims->hidden % 64 || dims->mlp % 64) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "create: hidden and mlp must be multiples of 64");
+    if (dims->compute_dtype != REGIONE_BF16 && dims->compute_dtype != REGIONE_FP32)
+        RG_FAIL(REGIONE_ERR_INVALID_ARG, "create: compute_dtype %d (REGIONE_BF16 or REGIONE_FP32)", dims->compute_dtype);
     regione_ctx* c = new (std::nothrow) regione_ctx();
     if (!c) RG_FAIL(REGIONE_ERR_HIP, "create: out of host memory");
     memset(c, 0, sizeof(*c));
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->dims = *dims;
+    c->f32 = dims->compute_dtype == REGIONE_FP32;
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; RG_FAIL(REGIONE_ERR_HIP, "create: no HIP device"); }
     const size_t n = static_cast<size_t>(dims->max_fresh), H = dims->hidden, M = dims->mlp;
+    const size_t es = c->f32 ? 4 : 2;   // bytes per activation element
     c->part_counts_cap = dims->max_tokens / 4 + 8;
     const size_t split_rows = n < 2048 ? n : 2048;
     c->attn_part_bytes = static_cast<size_t>(8) * dims->heads * split_rows * (dims->head_dim + 4) * sizeof(float);
     int rc = dev_alloc(&c->part_counts, static_cast<size_t>(c->part_counts_cap));
-    if (rc == REGIONE_OK) rc = dev_alloc(&c->u, n * H);
-    if (rc == REGIONE_OK) rc = dev_alloc(&c->q, n * H);
-    if (rc == REGIONE_OK) rc = dev_alloc(&c->kf, n * H);
-    if (rc == REGIONE_OK) rc = dev_alloc(&c->vf, n * H);
-    if (rc == REGIONE_OK) rc = dev_alloc(&c->a, n * (H + M));
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->u, n * H * es);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->q, n * H * es);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->kf, n * H * es);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->vf, n * H * es);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->a, n * (H + M) * es);
     if (rc == REGIONE_OK) rc = dev_alloc(&c->h1, n * H);
-    if (rc == REGIONE_OK) rc = dev_alloc(&c->m, n * M);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->m, n * M * es);
     if (rc == REGIONE_OK) rc = dev_alloc(&c->slot_all, n);
     if (rc == REGIONE_OK) rc = dev_alloc(reinterpret_cast<char**>(&c->attn_part), c->attn_part_bytes);
     c->gemm_part_bytes = n > 0 ? static_cast<size_t>(128) << 20 : 0;
@@ -129,7 +134,7 @@ extern "C" int regione_layernorm(regione_ctx* ctx, const void* h, int32_t h_dtyp
     if (h_dtype != REGIONE_BF16 && h_dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "layernorm: bad dtype %d", h_dtype);
     if (n == 0) return REGIONE_OK;
     if (!h || !u) RG_FAIL(REGIONE_ERR_INVALID_ARG, "layernorm: null tensor");
-    return rg_layernorm_mod(ctx, h, h_dtype == REGIONE_FP32, n, hidden, shift_opt, scale_opt, static_cast<bf16_t*>(u));
+    return rg_layernorm_mod(ctx, h, h_dtype == REGIONE_FP32, n, hidden, shift_opt, scale_opt, u);
 }
 
 extern "C" int regione_stage_plan_host(int32_t T, int32_t t_st, int32_t t_sm, const int32_t* forced_k, int32_t n_forced,
@@ -190,6 +195,33 @@ extern "C" int regione_velocity_decision_host(const float* t_host, const float* 
     return REGIONE_OK;
 }
 
+// The data-dependent reuse trigger beside Eq.8 (see regione_rel_change): decision before a region step, update after a
+// fresh one.  The state starts as zeros at the first step of every segment.
+extern "C" int regione_rel_decision_host(regione_rel_state* st, float decay, int32_t* reuse, float* factor) {
+    if (!st || !reuse || !factor) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rel_decision: null argument");
+    const bool r = st->reuse_next && st->have_cache;     // never without a cached velocity, never two reuses in a row
+    st->reuse_next = 0;
+    *reuse = r ? 1 : 0;
+    *factor = r ? decay : 1.0f;
+    return REGIONE_OK;
+}
+
+extern "C" int regione_rel_update_host(regione_rel_state* st, const double* sums_host_opt, float threshold, double* rel_out_opt) {
+    if (!st) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rel_update: null state");
+    if (sums_host_opt && st->have_cache) {
+        const double s_diff = sums_host_opt[0], s_old = sums_host_opt[1];
+        if (!(s_diff >= 0.0) || !(s_old >= 0.0)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rel_update: a sum of squares is negative or NaN");
+        const double rel = s_old > 0.0 ? sqrt(s_diff) / sqrt(s_old) : INFINITY;
+        st->reuse_next = rel < static_cast<double>(threshold) ? 1 : 0;
+        if (rel_out_opt) *rel_out_opt = rel;
+    } else {
+        st->reuse_next = 0;
+        if (rel_out_opt) *rel_out_opt = INFINITY;
+    }
+    st->have_cache = 1;
+    return REGIONE_OK;
+}
+
 extern "C" int regione_gamma_fit_host(const double* sq_norms_host, int32_t n_samples, const float* t_host, int32_t n_steps,
                                       float* gamma_out) {
     if (!sq_norms_host || !t_host || !gamma_out) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gamma_fit: null argument");
@@ -237,6 +269,9 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
     if (n_branches < 1) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: %d branches", n_branches);
     if (block_type != REGIONE_BLOCK_DOUBLE && block_type != REGIONE_BLOCK_SINGLE) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: bad block type %d", block_type);
     if (h_dtype != REGIONE_BF16 && h_dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: bad h_dtype %d", h_dtype);
+    if (ctx->f32 && h_dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: a float32 context carries a float32 residual stream");
+    if (ctx->f32 && (w->rope || w->img.q_norm || w->img.k_norm || w->txt.q_norm || w->txt.k_norm))
+        RG_FAIL(REGIONE_ERR_UNSUPPORTED, "block_forward: query/key normalisation and rotary embedding are bf16-context features");
     if (flags & ~(REGIONE_FLAG_STORE | REGIONE_FLAG_RETRIEVE)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: unknown flag bits %d", flags);
     if (flags == (REGIONE_FLAG_STORE | REGIONE_FLAG_RETRIEVE)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: store and retrieve together are not a mode of the algorithm");
     if (n_fresh < 0 || n_txt_fresh < 0 || n_txt_fresh > n_fresh) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: n_fresh=%d n_txt_fresh=%d", n_fresh, n_txt_fresh);
@@ -259,10 +294,11 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
     const int H = ctx->dims.hidden, M = ctx->dims.mlp, heads = ctx->dims.heads, D = ctx->dims.head_dim;
     const int h_f32 = h_dtype == REGIONE_FP32;
     const size_t h_elem = h_f32 ? 4 : 2;
+    const size_t es = ctx->f32 ? 4 : 2;     // bytes per element of activations and KV cache
     if (n_branches > 1 && n_txt > 0) {
         // text and image rows alternate between the branches: one pass per branch
         for (int b = 0; b < n_branches; ++b) {
-            const size_t hoff = static_cast<size_t>(b) * n_fresh * H * h_elem, coff = static_cast<size_t>(b) * n_all * H * sizeof(bf16_t);
+            const size_t hoff = static_cast<size_t>(b) * n_fresh * H * h_elem, coff = static_cast<size_t>(b) * n_all * H * es;
             rc = block_forward_impl(ctx, w, block_type, static_cast<const char*>(h_in) + hoff, static_cast<char*>(h_out) + hoff, h_dtype, 1,
                                     n_fresh, n_txt_fresh, slot_index, slot_offset,
                                     k_cache ? static_cast<char*>(k_cache) + coff : nullptr, v_cache ? static_cast<char*>(v_cache) + coff : nullptr, n_all, flags);
@@ -273,8 +309,8 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
     const int n_rows = n_fresh * n_branches;                       // rows of all branches, one group per stream
     const int period = n_branches > 1 ? n_fresh : 0;
     const int lda_attn = dbl ? H : H + M;   // single-stream: attention output and gelu(m) share rows of ctx->a
-    bf16_t* kc = static_cast<bf16_t*>(k_cache);
-    bf16_t* vc = static_cast<bf16_t*>(v_cache);
+    char* kc = static_cast<char*>(k_cache);
+    char* vc = static_cast<char*>(v_cache);
     struct Rows { int r0, n; const regione_stream_weights* w; };
     const Rows groups[2] = {{0, n_txt, &w->txt}, {n_txt, n_rows - n_txt, &w->img}};
 
@@ -289,25 +325,25 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
     for (const Rows& g : groups) {
         if (g.n <= 0) continue;
         const char* hin = static_cast<const char*>(h_in) + static_cast<size_t>(g.r0) * H * h_elem;
-        bf16_t* u = ctx->u + static_cast<size_t>(g.r0) * H;
+        char* u = ctx->u + static_cast<size_t>(g.r0) * H * es;
         if ((rc = rg_layernorm_mod(ctx, hin, h_f32, g.n, H, g.w->shift1, g.w->scale1, u)) != REGIONE_OK) return rc;
         GemmEpilogue ep = {};
         ep.kind = EPI_QKV; ep.hidden = H;
-        ep.q = ctx->q + static_cast<size_t>(g.r0) * H; ep.ldq = H;
-        if (flags) { ep.k = kc; ep.v = vc; ep.slot = gemm_slots + g.r0; ep.slot_offset = slot_offset; }
-        else { ep.k = ctx->kf + static_cast<size_t>(g.r0) * H; ep.v = ctx->vf + static_cast<size_t>(g.r0) * H; ep.slot = nullptr; }
+        ep.q = reinterpret_cast<bf16_t*>(ctx->q + static_cast<size_t>(g.r0) * H * es); ep.ldq = H;
+        if (flags) { ep.k = reinterpret_cast<bf16_t*>(kc); ep.v = reinterpret_cast<bf16_t*>(vc); ep.slot = gemm_slots + g.r0; ep.slot_offset = slot_offset; }
+        else { ep.k = reinterpret_cast<bf16_t*>(ctx->kf + static_cast<size_t>(g.r0) * H * es); ep.v = reinterpret_cast<bf16_t*>(ctx->vf + static_cast<size_t>(g.r0) * H * es); ep.slot = nullptr; }
         ep.ldkv = H;
         if (dbl) {
             ep.bias = g.w->b_qkv;
-            rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_qkv), g.n, 3 * H, H, ep);
+            rc = rg_gemm(ctx, u, H, g.w->w_qkv, g.n, 3 * H, H, ep);
         } else {
             ep.bias = g.w->b_1; ep.act = REGIONE_ACT_GELU_TANH;
-            ep.y = ctx->a + static_cast<size_t>(g.r0) * lda_attn; ep.ldy = lda_attn; ep.y_col0 = H;
-            rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_1), g.n, 3 * H + M, H, ep);
+            ep.y = ctx->a + static_cast<size_t>(g.r0) * lda_attn * es; ep.ldy = lda_attn; ep.y_col0 = H; ep.y_f32 = ctx->f32;
+            rc = rg_gemm(ctx, u, H, g.w->w_1, g.n, 3 * H + M, H, ep);
         }
         if (rc != REGIONE_OK) return rc;
-        // extras: normalised and rotated queries and keys, in place where the projection wrote them
-        rc = rg_qk_norm_rope(ctx, ep.q, H, ep.k, H, flags ? slot_index + g.r0 : nullptr, slot_index ? slot_index + g.r0 : nullptr, g.r0, slot_offset, period, n_all, g.n, heads, D,
+        // extras: normalised and rotated queries and keys, in place where the projection wrote them (bf16 contexts only)
+        if (!ctx->f32) rc = rg_qk_norm_rope(ctx, ep.q, H, ep.k, H, flags ? slot_index + g.r0 : nullptr, slot_index ? slot_index + g.r0 : nullptr, g.r0, slot_offset, period, n_all, g.n, heads, D,
                              g.w->q_norm, g.w->k_norm, w->rope, w->rope_rows);
         if (rc != REGIONE_OK) return rc;
     }
@@ -315,7 +351,7 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
     // ---- attention (Eq.6).  With a flag set the fresh K,V already sit in their cache slots, so the
     // key list is the whole cached sequence; without a flag it is the fresh rows only.
     for (int b = 0; b < n_branches; ++b) {
-        const size_t r0 = static_cast<size_t>(b) * n_fresh, c0 = static_cast<size_t>(b) * n_all * H;
+        const size_t r0 = static_cast<size_t>(b) * n_fresh * es, c0 = static_cast<size_t>(b) * n_all * H * es;
         if (flags) rc = rg_attention(ctx, ctx->q + r0 * H, H, n_fresh, nullptr, nullptr, H, 0, kc + c0, vc + c0, H, n_all, nullptr, heads, D, 0.f, ctx->a + r0 * lda_attn, lda_attn);
         else rc = rg_attention(ctx, ctx->q + r0 * H, H, n_fresh, ctx->kf + r0 * H, ctx->vf + r0 * H, H, n_fresh, nullptr, nullptr, H, 0, nullptr, heads, D, 0.f, ctx->a + r0 * lda_attn, lda_attn);
         if (rc != REGIONE_OK) return rc;
@@ -326,33 +362,33 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
         if (g.n <= 0) continue;
         const char* hin = static_cast<const char*>(h_in) + static_cast<size_t>(g.r0) * H * h_elem;
         char* hout = static_cast<char*>(h_out) + static_cast<size_t>(g.r0) * H * h_elem;
-        const bf16_t* a = ctx->a + static_cast<size_t>(g.r0) * lda_attn;
+        const char* a = ctx->a + static_cast<size_t>(g.r0) * lda_attn * es;
         GemmEpilogue ep = {};
         ep.kind = EPI_RESID;
         if (!dbl) {
             ep.bias = g.w->b_2; ep.gate = g.w->gate1;
             ep.resid = hin; ep.ldr = H; ep.resid_f32 = h_f32;
             ep.y = hout; ep.ldy = H; ep.y_f32 = h_f32;
-            if ((rc = rg_gemm(ctx, a, lda_attn, static_cast<const bf16_t*>(g.w->w_2), g.n, H, H + M, ep)) != REGIONE_OK) return rc;
+            if ((rc = rg_gemm(ctx, a, lda_attn, g.w->w_2, g.n, H, H + M, ep)) != REGIONE_OK) return rc;
             continue;
         }
         float* h1 = ctx->h1 + static_cast<size_t>(g.r0) * H;
         ep.bias = g.w->b_o; ep.gate = g.w->gate1;
         ep.resid = hin; ep.ldr = H; ep.resid_f32 = h_f32;
         ep.y = h1; ep.ldy = H; ep.y_f32 = 1;
-        if ((rc = rg_gemm(ctx, a, H, static_cast<const bf16_t*>(g.w->w_o), g.n, H, H, ep)) != REGIONE_OK) return rc;
-        bf16_t* u = ctx->u + static_cast<size_t>(g.r0) * H;
+        if ((rc = rg_gemm(ctx, a, H, g.w->w_o, g.n, H, H, ep)) != REGIONE_OK) return rc;
+        char* u = ctx->u + static_cast<size_t>(g.r0) * H * es;
         if ((rc = rg_layernorm_mod(ctx, h1, 1, g.n, H, g.w->shift2, g.w->scale2, u)) != REGIONE_OK) return rc;
-        bf16_t* m = ctx->m + static_cast<size_t>(g.r0) * M;
+        char* m = ctx->m + static_cast<size_t>(g.r0) * M * es;
         GemmEpilogue up = {};
         up.kind = EPI_PLAIN; up.bias = g.w->b_1; up.act = REGIONE_ACT_GELU_TANH; up.act_from = 0;
-        up.y = m; up.ldy = M; up.y_f32 = 0;
-        if ((rc = rg_gemm(ctx, u, H, static_cast<const bf16_t*>(g.w->w_1), g.n, M, H, up)) != REGIONE_OK) return rc;
+        up.y = m; up.ldy = M; up.y_f32 = ctx->f32;
+        if ((rc = rg_gemm(ctx, u, H, g.w->w_1, g.n, M, H, up)) != REGIONE_OK) return rc;
         GemmEpilogue dn = {};
         dn.kind = EPI_RESID; dn.bias = g.w->b_2; dn.gate = g.w->gate2;
         dn.resid = h1; dn.ldr = H; dn.resid_f32 = 1;
         dn.y = hout; dn.ldy = H; dn.y_f32 = h_f32;
-        if ((rc = rg_gemm(ctx, m, M, static_cast<const bf16_t*>(g.w->w_2), g.n, H, M, dn)) != REGIONE_OK) return rc;
+        if ((rc = rg_gemm(ctx, m, M, g.w->w_2, g.n, H, M, dn)) != REGIONE_OK) return rc;
     }
     return REGIONE_OK;
 }

@@ -534,11 +534,18 @@ extern "C" int regione_tune_attention(regione_ctx* ctx, int32_t key_splits) {
     return REGIONE_OK;
 }
 
-int rg_attention(regione_ctx* ctx, const bf16_t* q, int ldq, int n_q,
-                 const bf16_t* k0, const bf16_t* v0, int ldkv0, int n0,
-                 const bf16_t* k1, const bf16_t* v1, int ldkv1, int n1, const int32_t* idx1,
-                 int heads, int d, float scale, bf16_t* out, int ldo) {
+int rg_attention(regione_ctx* ctx, const void* q_any, int ldq, int n_q,
+                 const void* k0_any, const void* v0_any, int ldkv0, int n0,
+                 const void* k1_any, const void* v1_any, int ldkv1, int n1, const int32_t* idx1,
+                 int heads, int d, float scale, void* out_any, int ldo) {
     if (n_q <= 0) return REGIONE_OK;
+    if (ctx->f32)
+        return rg_attention_f32(ctx, static_cast<const float*>(q_any), ldq, n_q, static_cast<const float*>(k0_any), static_cast<const float*>(v0_any), ldkv0, n0,
+                                static_cast<const float*>(k1_any), static_cast<const float*>(v1_any), ldkv1, n1, idx1, heads, d, scale, static_cast<float*>(out_any), ldo);
+    const bf16_t* q = static_cast<const bf16_t*>(q_any);
+    const bf16_t* k0 = static_cast<const bf16_t*>(k0_any); const bf16_t* v0 = static_cast<const bf16_t*>(v0_any);
+    const bf16_t* k1 = static_cast<const bf16_t*>(k1_any); const bf16_t* v1 = static_cast<const bf16_t*>(v1_any);
+    bf16_t* out = static_cast<bf16_t*>(out_any);
     if (n0 + n1 <= 0) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "attention: %d queries but no key", n_q);
     if (d != 64 && d != 128) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "attention: head dimension %d (64 or 128 supported)", d);
     if ((ldq & 7) || (ldo & 3) || (n0 > 0 && (ldkv0 & 7)) || (n1 > 0 && (ldkv1 & 7)))
@@ -574,8 +581,5 @@ extern "C" int regione_attn_kvcache(regione_ctx* ctx, const void* q, int32_t n_q
     if (!rg_aligned16(q) || !rg_aligned16(out) || !rg_aligned16(k_fresh) || !rg_aligned16(v_fresh) || !rg_aligned16(k_cache) || !rg_aligned16(v_cache))
         RG_FAIL(REGIONE_ERR_INVALID_ARG, "attn_kvcache: tensors must be 16-byte aligned");
     const int ld = heads * d;
-    return rg_attention(ctx, static_cast<const bf16_t*>(q), ld, n_q,
-                        static_cast<const bf16_t*>(k_fresh), static_cast<const bf16_t*>(v_fresh), ld, n_fresh,
-                        static_cast<const bf16_t*>(k_cache), static_cast<const bf16_t*>(v_cache), ld, n1, cache_index_opt,
-                        heads, d, scale, static_cast<bf16_t*>(out), ld);
+    return rg_attention(ctx, q, ld, n_q, k_fresh, v_fresh, ld, n_fresh, k_cache, v_cache, ld, n1, cache_index_opt, heads, d, scale, out, ld);
 }

@@ -145,6 +145,47 @@ int rg_expand_slots(regione_ctx* ctx, const int32_t* slot, int n, int n_branches
     return REGIONE_OK;
 }
 
+namespace {
+// slots of the fresh rows of a region step whose text rows are recomputed: [0, n_txt) for the text rows, then
+// index[i] + n_txt for the edited rows (image rows sit behind the text rows in the cached sequence)
+__global__ void __launch_bounds__(kThreads)
+fresh_slots_kernel(const int32_t* __restrict__ index, const int32_t* __restrict__ n_dev, int64_t n_max, int n_txt, int32_t* __restrict__ out) {
+    int64_t n = n_max;
+    if (n_dev) { const int64_t nd = *n_dev; n = nd < n_max ? (nd < 0 ? 0 : nd) : n_max; }
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (i < n_txt) out[i] = static_cast<int32_t>(i);
+    else if (i < n_txt + n) out[i] = index[i - n_txt] + n_txt;
+}
+// out = b + t * b_time, the product and the sum rounded separately
+__global__ void __launch_bounds__(kThreads)
+time_bias_kernel(const float* __restrict__ b, const float* __restrict__ b_time, float t, float* __restrict__ out, int n) {
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) out[i] = __fadd_rn(b[i], __fmul_rn(t, b_time[i]));
+}
+}  // namespace
+
+extern "C" int regione_fresh_slots(regione_ctx* ctx, const int32_t* index, const int32_t* n_dev, int64_t n_max, int32_t n_txt, int32_t* slots) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "fresh_slots: null context");
+    if (n_max < 0 || n_txt < 0 || n_max + n_txt > INT32_MAX) RG_FAIL(REGIONE_ERR_INVALID_ARG, "fresh_slots: n_max=%lld n_txt=%d", static_cast<long long>(n_max), n_txt);
+    if (n_max + n_txt == 0) return REGIONE_OK;
+    if (!slots || (n_max > 0 && !index)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "fresh_slots: null list");
+    const int64_t blocks = (n_max + n_txt + kThreads - 1) / kThreads;
+    ProfScope prof(ctx, REGIONE_PROF_ROWS);
+    hipLaunchKernelGGL(fresh_slots_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream, index, n_dev, n_max, n_txt, slots);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+extern "C" int regione_time_bias(regione_ctx* ctx, const float* b, const float* b_time, float t, float* out, int32_t n) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "time_bias: null context");
+    if (n < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "time_bias: n=%d", n);
+    if (n == 0) return REGIONE_OK;
+    if (!b || !b_time || !out) RG_FAIL(REGIONE_ERR_INVALID_ARG, "time_bias: null vector");
+    hipLaunchKernelGGL(time_bias_kernel, dim3((n + kThreads - 1) / kThreads), dim3(kThreads), 0, ctx->stream, b, b_time, t, out, n);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
 extern "C" int regione_rope_table(regione_ctx* ctx, const int32_t* pos_ids, int64_t n, int32_t n_axes,
                                   const int32_t* axes_dims_host, float theta, float* table) {
     if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rope_table: null context");

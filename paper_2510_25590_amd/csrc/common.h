@@ -5,6 +5,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include "regione.h"
+#include "regione_bench.h"
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits in memory
 
@@ -12,18 +13,20 @@ struct regione_ctx {
     hipStream_t stream;
     regione_dims dims;
     int device;
+    int f32;       // compute dtype of the context is float32: the activation buffers below then hold 4-byte elements
     // workspace (device)
     int32_t* part_counts;  // per-block edited counts of the partition
     int64_t part_counts_cap;
     int32_t* n_edited_pinned;      // pinned host copy of the last edited-token count (host address)
     int32_t* n_edited_pinned_dev;  // the same memory as the device sees it
-    bf16_t* u;     // [max_fresh, H]     normalised + modulated rows
-    bf16_t* q;     // [max_fresh, H]
-    bf16_t* kf;    // [max_fresh, H]     fresh keys when the cache is not used
-    bf16_t* vf;    // [max_fresh, H]
-    bf16_t* a;     // [max_fresh, H+M]   attention output (+ activated MLP part, single-stream)
+    // activation buffers: elements of the compute dtype (bf16, or float32 in a float32 context); addressed in bytes
+    char* u;       // [max_fresh, H]     normalised + modulated rows
+    char* q;       // [max_fresh, H]
+    char* kf;      // [max_fresh, H]     fresh keys when the cache is not used
+    char* vf;      // [max_fresh, H]
+    char* a;       // [max_fresh, H+M]   attention output (+ activated MLP part, single-stream)
     float* h1;     // [max_fresh, H]     residual stream between the two halves of a block
-    bf16_t* m;     // [max_fresh, M]     activated MLP hidden rows
+    char* m;       // [max_fresh, M]     activated MLP hidden rows
     float* attn_part;  // split-KV partial results
     size_t attn_part_bytes;
     int32_t* slot_all; // [max_fresh] slot list of all branches of a batched block call
@@ -90,15 +93,23 @@ struct GemmEpilogue {
     const float* row_scale; const float* col_scale;
 };
 
-int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* w_packed, int m, int n, int k, const GemmEpilogue& ep);
+// a, w_packed (and the epilogue's q, k, v, y, resid where they are activations) are bf16, or float32 in a float32 context
+int rg_gemm(regione_ctx* ctx, const void* a, int lda, const void* w_packed, int m, int n, int k, const GemmEpilogue& ep);
+int rg_gemm_f32(regione_ctx* ctx, const float* a, int lda, const float* w, int m, int n, int k, const GemmEpilogue& ep);
 // E4M3 operands (k counts 8-bit elements, a multiple of 128; lda in bytes, a multiple of 16); ep.row_scale / col_scale set
 int rg_gemm_fp8(regione_ctx* ctx, const uint8_t* a, int lda, const uint8_t* w_packed, int m, int n, int k, const GemmEpilogue& ep);
-int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, bf16_t* u);
+int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, void* u);   // u: compute dtype
 int rg_qk_norm_rope(regione_ctx* ctx, bf16_t* q, int ldq, bf16_t* k, int ldkv, const int32_t* kv_slot,
                     const int32_t* pos_slot, int pos0, int slot_offset, int slot_period, int slot_branch_rows, int n, int heads, int d,
                     const float* q_norm, const float* k_norm, const float* table, int table_rows);
 int rg_expand_slots(regione_ctx* ctx, const int32_t* slot, int n, int n_branches, int branch_rows, int32_t* out);
-int rg_attention(regione_ctx* ctx, const bf16_t* q, int ldq, int n_q,
-                 const bf16_t* k0, const bf16_t* v0, int ldkv0, int n0,
-                 const bf16_t* k1, const bf16_t* v1, int ldkv1, int n1, const int32_t* idx1,
-                 int heads, int d, float scale, bf16_t* out, int ldo);
+int rg_attention(regione_ctx* ctx, const void* q, int ldq, int n_q,
+                 const void* k0, const void* v0, int ldkv0, int n0,
+                 const void* k1, const void* v1, int ldkv1, int n1, const int32_t* idx1,
+                 int heads, int d, float scale, void* out, int ldo);
+int rg_attention_f32(regione_ctx* ctx, const float* q, int ldq, int n_q,
+                     const float* k0, const float* v0, int ldkv0, int n0,
+                     const float* k1, const float* v1, int ldkv1, int n1, const int32_t* idx1,
+                     int heads, int d, float scale, float* out, int ldo);
+int rg_pack_weight_f32(regione_ctx* ctx, const float* w, int n, int k, float* w_packed);
+

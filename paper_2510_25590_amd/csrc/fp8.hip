@@ -85,6 +85,7 @@ extern "C" int regione_quantize_rows_fp8(regione_ctx* ctx, const void* x, int64_
 
 extern "C" int regione_pack_weight_fp8(regione_ctx* ctx, const void* wq, int32_t n, int32_t k, void* wq_packed) {
     if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "pack_weight_fp8: null context");
+    if (ctx->f32) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "pack_weight_fp8: the 8-bit projections belong to bf16 contexts");
     if (n <= 0 || k <= 0 || (k % 128)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "pack_weight_fp8: n=%d, k=%d (k must be a multiple of 128)", n, k);
     // the 8-bit layout is the 16-bit one with every pair of codes taken as one element
     return regione_pack_weight(ctx, wq, n, k / 2, wq_packed);
@@ -93,6 +94,7 @@ extern "C" int regione_pack_weight_fp8(regione_ctx* ctx, const void* wq, int32_t
 extern "C" int regione_linear_fp8(regione_ctx* ctx, const void* xq, const float* x_scale, const void* wq_packed, const float* w_scale,
                                   const float* b_opt, int32_t m, int32_t n, int32_t k, int32_t act, int32_t out_dtype, void* y) {
     if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear_fp8: null context");
+    if (ctx->f32) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "linear_fp8: the 8-bit projections belong to bf16 contexts");
     if (m < 0 || n <= 0 || k <= 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear_fp8: m=%d n=%d k=%d", m, n, k);
     if (act != REGIONE_ACT_NONE && act != REGIONE_ACT_GELU_TANH) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear_fp8: bad act %d", act);
     if (out_dtype != REGIONE_BF16 && out_dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "linear_fp8: bad out_dtype %d", out_dtype);

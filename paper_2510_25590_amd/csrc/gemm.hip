@@ -958,8 +958,11 @@ int rg_gemm_fp8(regione_ctx* ctx, const uint8_t* a, int lda, const uint8_t* wp, 
     return launch_gemm_fp8<2>(ctx, a2, lda / 2, w2, m, n, k2, splits, ep);
 }
 
-int rg_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, const GemmEpilogue& ep_in) {
+int rg_gemm(regione_ctx* ctx, const void* a_any, int lda, const void* wp_any, int m, int n, int k, const GemmEpilogue& ep_in) {
     if (m <= 0 || n <= 0) return REGIONE_OK;
+    if (ctx->f32) return rg_gemm_f32(ctx, static_cast<const float*>(a_any), lda, static_cast<const float*>(wp_any), m, n, k, ep_in);
+    const bf16_t* a = static_cast<const bf16_t*>(a_any);
+    const bf16_t* wp = static_cast<const bf16_t*>(wp_any);
     if (k <= 0 || (k % BK) || (lda & 7)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "gemm: k=%d must be a positive multiple of 64 and lda=%d of 8", k, lda);
     if (!rg_aligned16(a) || !rg_aligned16(wp)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
     ProfScope prof(ctx, REGIONE_PROF_GEMM);
@@ -988,6 +991,7 @@ extern "C" int regione_pack_weight(regione_ctx* ctx, const void* w, int32_t n, i
     if (n <= 0 || k <= 0 || (k % BK)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "pack_weight: n=%d, k=%d (k must be a multiple of 64)", n, k);
     if (!w || !w_packed || !rg_aligned16(w) || !rg_aligned16(w_packed)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "pack_weight: null or unaligned tensor");
     if (w == w_packed) RG_FAIL(REGIONE_ERR_INVALID_ARG, "pack_weight: cannot pack in place");
+    if (ctx->f32) return rg_pack_weight_f32(ctx, static_cast<const float*>(w), n, k, static_cast<float*>(w_packed));
     const int64_t chunks = regione_packed_weight_elems(n, k) / 8;
     int64_t blocks = (chunks + kThreads - 1) / kThreads;
     if (blocks > 256 * 32) blocks = 256 * 32;
@@ -1017,5 +1021,5 @@ extern "C" int regione_linear(regione_ctx* ctx, const void* x, const void* w_pac
     GemmEpilogue ep = {};
     ep.kind = EPI_PLAIN; ep.bias = b_opt; ep.act = act; ep.act_from = 0;
     ep.y = y; ep.ldy = n; ep.y_f32 = out_dtype == REGIONE_FP32;
-    return rg_gemm(ctx, static_cast<const bf16_t*>(x), k, static_cast<const bf16_t*>(w_packed), m, n, k, ep);
+    return rg_gemm(ctx, x, k, w_packed, m, n, k, ep);
 }

@@ -213,11 +213,11 @@ write_index_kernel(const uint8_t* __restrict__ mask, const int32_t* __restrict__
 __global__ void set_i32_kernel(int32_t* p, int32_t* p_pinned, int32_t v) { *p = v; *p_pinned = v; }
 
 template <typename T, int VEC>
-int launch_score(regione_ctx* ctx, int lpt, dim3 grid, const void* x_t, const void* v, const void* x_ref, int64_t n, int c,
+int launch_score(hipStream_t stream, int32_t* counts, int lpt, dim3 grid, const void* x_t, const void* v, const void* x_ref, int64_t n, int c,
                  int tpb, float sigma, float eta, float* score, uint8_t* mask) {
     const T* a = static_cast<const T*>(x_t); const T* b = static_cast<const T*>(v); const T* r = static_cast<const T*>(x_ref);
-#define RG_CASE(L) case L: hipLaunchKernelGGL((score_mask_kernel<T, VEC, L>), grid, dim3(kThreads), 0, ctx->stream, \
-        a, b, r, n, c, tpb, sigma, eta, score, mask, ctx->part_counts); break;
+#define RG_CASE(L) case L: hipLaunchKernelGGL((score_mask_kernel<T, VEC, L>), grid, dim3(kThreads), 0, stream, \
+        a, b, r, n, c, tpb, sigma, eta, score, mask, counts); break;
     switch (lpt) { RG_CASE(1) RG_CASE(2) RG_CASE(4) RG_CASE(8) RG_CASE(16) RG_CASE(32) RG_CASE(64)
         default: RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: bad lane group %d", lpt); }
 #undef RG_CASE
@@ -287,21 +287,67 @@ count_mask_kernel(const uint8_t* __restrict__ mask, int64_t n_tokens, int tok_pe
     }
 }
 
-// Index lists from the mask and the per-block counts in ctx->part_counts: few blocks -> one launch, else scan + lists.
-int launch_index_lists(regione_ctx* ctx, dim3 grid, const uint8_t* mask, int64_t n_tokens, int tpb,
-                       int32_t* e_index, int32_t* u_index, int32_t* n_edited_dev) {
+// Index lists from the mask and the per-block counts in `counts`: few blocks -> one launch, else scan + lists.
+// n_edited_copy: a second place for the count (the context's pinned host word; n_edited_dev itself when there is none).
+int launch_index_lists(hipStream_t stream, int32_t* counts, dim3 grid, const uint8_t* mask, int64_t n_tokens, int tpb,
+                       int32_t* e_index, int32_t* u_index, int32_t* n_edited_dev, int32_t* n_edited_copy) {
     if (grid.x <= 1024) {
-        hipLaunchKernelGGL((write_index_kernel<true>), grid, dim3(kThreads), 0, ctx->stream,
-                           mask, ctx->part_counts, n_tokens, tpb, e_index, u_index, n_edited_dev, ctx->n_edited_pinned_dev);
+        hipLaunchKernelGGL((write_index_kernel<true>), grid, dim3(kThreads), 0, stream,
+                           mask, counts, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy);
         RG_LAUNCH_CHECK();
         return REGIONE_OK;
     }
-    hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, ctx->stream, ctx->part_counts, static_cast<int>(grid.x), n_edited_dev,
-                       ctx->n_edited_pinned_dev);
+    hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, stream, counts, static_cast<int>(grid.x), n_edited_dev, n_edited_copy);
     RG_LAUNCH_CHECK();
-    hipLaunchKernelGGL((write_index_kernel<false>), grid, dim3(kThreads), 0, ctx->stream,
-                       mask, ctx->part_counts, n_tokens, tpb, e_index, u_index, n_edited_dev, ctx->n_edited_pinned_dev);
+    hipLaunchKernelGGL((write_index_kernel<false>), grid, dim3(kThreads), 0, stream,
+                       mask, counts, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy);
     RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+// The launches of the partition on `stream` with the per-block counts in `counts` (room for counts_cap entries).
+int partition_launches(hipStream_t stream, int32_t* counts, int64_t counts_cap, const void* x_t, const void* v, const void* x_ref,
+                       int64_t n_tokens, int32_t c, int32_t dtype, float sigma_t, float eta, float* score_opt, uint8_t* mask,
+                       int32_t* e_index, int32_t* u_index, int32_t* n_edited_dev, int32_t* n_edited_copy) {
+    if (n_tokens == 0) {
+        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, stream, n_edited_dev, n_edited_copy, 0);
+        RG_LAUNCH_CHECK();
+        return REGIONE_OK;
+    }
+    const int full_vec = dtype == REGIONE_BF16 ? 8 : 4;
+    const int vec = (c % full_vec == 0) ? full_vec : 1;
+    const int nchunks = c / vec;
+    int lpt = 1;
+    while (lpt * 2 <= nchunks && lpt < 64) lpt *= 2;
+    const int tok_per_pass = kWaves * (64 / lpt);
+    // small inputs: few passes per block so that one image still spreads over many CUs
+    int passes = 1;
+    while (passes < 32 && (n_tokens / (static_cast<int64_t>(tok_per_pass) * passes * 2)) >= 2048) passes *= 2;
+    const int tpb = tok_per_pass * passes;
+    const int64_t nblocks = (n_tokens + tpb - 1) / tpb;
+    if (nblocks > counts_cap) RG_FAIL(REGIONE_ERR_WORKSPACE, "partition: %lld blocks exceed the %lld the workspace holds", (long long)nblocks, (long long)counts_cap);
+    dim3 grid(static_cast<unsigned>(nblocks));
+    int rc;
+    if (dtype == REGIONE_BF16) {
+        rc = vec == 8 ? launch_score<bf16_t, 8>(stream, counts, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask)
+                      : launch_score<bf16_t, 1>(stream, counts, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask);
+    } else {
+        rc = vec == 4 ? launch_score<float, 4>(stream, counts, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask)
+                      : launch_score<float, 1>(stream, counts, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask);
+    }
+    if (rc != REGIONE_OK) return rc;
+    return launch_index_lists(stream, counts, grid, mask, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy);
+}
+
+int check_partition_args(const char* who, const void* x_t, const void* v, const void* x_ref, int64_t n_tokens, int32_t c, int32_t dtype,
+                         const uint8_t* mask, const int32_t* e_index, const int32_t* u_index, const int32_t* n_edited_dev) {
+    if (n_tokens < 0 || c <= 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "%s: n_tokens=%lld c=%d", who, (long long)n_tokens, c);
+    if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "%s: bad dtype %d", who, dtype);
+    if (!n_edited_dev) RG_FAIL(REGIONE_ERR_INVALID_ARG, "%s: n_edited_dev is null", who);
+    if (n_tokens > 0) {
+        if (!x_t || !v || !x_ref || !mask || !e_index || !u_index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "%s: null tensor", who);
+        if (!rg_aligned16(x_t) || !rg_aligned16(v) || !rg_aligned16(x_ref)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "%s: inputs must be 16-byte aligned", who);
+    }
     return REGIONE_OK;
 }
 
@@ -312,44 +358,12 @@ extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* 
                                  float* score_opt, uint8_t* mask, int32_t* e_index, int32_t* u_index,
                                  int32_t* n_edited_dev, int32_t* n_edited_host_opt) {
     if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: null context");
-    if (n_tokens < 0 || c <= 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: n_tokens=%lld c=%d", (long long)n_tokens, c);
-    if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: bad dtype %d", dtype);
-    if (!n_edited_dev) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: n_edited_dev is null");
+    if (int rc = check_partition_args("partition", x_t, v, x_ref, n_tokens, c, dtype, mask, e_index, u_index, n_edited_dev)) return rc;
     if (n_tokens > ctx->dims.max_tokens) RG_FAIL(REGIONE_ERR_WORKSPACE, "partition: %lld tokens, context made for %d", (long long)n_tokens, ctx->dims.max_tokens);
-    if (n_tokens > 0) {
-        if (!x_t || !v || !x_ref || !mask || !e_index || !u_index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: null tensor");
-        if (!rg_aligned16(x_t) || !rg_aligned16(v) || !rg_aligned16(x_ref)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: inputs must be 16-byte aligned");
-    }
     {
     ProfScope prof(ctx, REGIONE_PROF_PARTITION);
-    if (n_tokens == 0) {
-        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, n_edited_dev, ctx->n_edited_pinned_dev, 0);
-        RG_LAUNCH_CHECK();
-    } else {
-        const int full_vec = dtype == REGIONE_BF16 ? 8 : 4;
-        const int vec = (c % full_vec == 0) ? full_vec : 1;
-        const int nchunks = c / vec;
-        int lpt = 1;
-        while (lpt * 2 <= nchunks && lpt < 64) lpt *= 2;
-        const int tok_per_pass = kWaves * (64 / lpt);
-        // small inputs: few passes per block so that one image still spreads over many CUs
-        int passes = 1;
-        while (passes < 32 && (n_tokens / (static_cast<int64_t>(tok_per_pass) * passes * 2)) >= 2048) passes *= 2;
-        const int tpb = tok_per_pass * passes;
-        const int64_t nblocks = (n_tokens + tpb - 1) / tpb;
-        if (nblocks > ctx->part_counts_cap) RG_FAIL(REGIONE_ERR_WORKSPACE, "partition: %lld blocks exceed the workspace", (long long)nblocks);
-        dim3 grid(static_cast<unsigned>(nblocks));
-        int rc;
-        if (dtype == REGIONE_BF16) {
-            rc = vec == 8 ? launch_score<bf16_t, 8>(ctx, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask)
-                          : launch_score<bf16_t, 1>(ctx, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask);
-        } else {
-            rc = vec == 4 ? launch_score<float, 4>(ctx, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask)
-                          : launch_score<float, 1>(ctx, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask);
-        }
-        if (rc != REGIONE_OK) return rc;
-        if (int rc2 = launch_index_lists(ctx, grid, mask, n_tokens, tpb, e_index, u_index, n_edited_dev)) return rc2;
-    }
+    if (int rc = partition_launches(ctx->stream, ctx->part_counts, ctx->part_counts_cap, x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta,
+                                    score_opt, mask, e_index, u_index, n_edited_dev, ctx->n_edited_pinned_dev)) return rc;
     }
     if (n_edited_host_opt) {   // the kernels wrote the count to pinned host memory too: no copy to wait for, only the stream
         RG_HIP(hipStreamSynchronize(ctx->stream));
@@ -382,7 +396,7 @@ extern "C" int regione_mask_cleanup(regione_ctx* ctx, const uint8_t* mask_in, in
         const dim3 grid(static_cast<unsigned>(nblocks));
         hipLaunchKernelGGL(count_mask_kernel, grid, dim3(kThreads), 0, ctx->stream, mask_out, n_tokens, tpb, ctx->part_counts);
         RG_LAUNCH_CHECK();
-        if (int rc2 = launch_index_lists(ctx, grid, mask_out, n_tokens, tpb, e_index, u_index, n_edited_dev)) return rc2;
+        if (int rc2 = launch_index_lists(ctx->stream, ctx->part_counts, grid, mask_out, n_tokens, tpb, e_index, u_index, n_edited_dev, ctx->n_edited_pinned_dev)) return rc2;
     }
     }
     if (n_edited_host_opt) {   // the kernels wrote the count to pinned host memory too: no copy to wait for, only the stream

@@ -163,11 +163,11 @@ layernorm_mod_vec_kernel(const T* __restrict__ h, int n, int hidden, const float
     }
 }
 
-// Any H: scalar loads, three passes over the row.
-template <typename T>
+// Any H: scalar loads, three passes over the row.  U: the output's storage type (bf16, or float32 in a float32 context).
+template <typename T, typename U = bf16_t>
 __global__ void __launch_bounds__(kThreads)
 layernorm_mod_kernel(const T* __restrict__ h, int n, int hidden, const float* __restrict__ shift,
-                     const float* __restrict__ scale, bf16_t* __restrict__ u) {
+                     const float* __restrict__ scale, U* __restrict__ u) {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
     if (row >= n) return;
@@ -182,12 +182,12 @@ layernorm_mod_kernel(const T* __restrict__ h, int n, int hidden, const float* __
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) sq += __shfl_xor(sq, m, 64);
     const float rstd = rsqrtf(sq / hidden + 1e-6f);
-    bf16_t* ur = u + static_cast<int64_t>(row) * hidden;
+    U* ur = u + static_cast<int64_t>(row) * hidden;
     for (int c = lane; c < hidden; c += 64) {
         float y = (ld<T>(hr + c) - mean) * rstd;
         const float sc = scale ? scale[c] : 0.f, sh = shift ? shift[c] : 0.f;
         y = y * (1.f + sc) + sh;
-        ur[c] = f32_to_bf16(y);
+        st<U>(ur + c, y);
     }
 }
 
@@ -382,10 +382,17 @@ extern "C" int regione_cast(regione_ctx* ctx, const void* src, int32_t src_dtype
     return REGIONE_OK;
 }
 
-int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, bf16_t* u) {
+int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, void* u_any) {
     if (n <= 0) return REGIONE_OK;
     dim3 grid((n + kThreads / 64 - 1) / (kThreads / 64));
     ProfScope prof(ctx, REGIONE_PROF_LAYERNORM);
+    if (ctx->f32) {   // float32 context: float32 rows out
+        if (h_f32) hipLaunchKernelGGL((layernorm_mod_kernel<float, float>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const float*>(h), n, hidden, shift, scale, static_cast<float*>(u_any));
+        else hipLaunchKernelGGL((layernorm_mod_kernel<bf16_t, float>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const bf16_t*>(h), n, hidden, shift, scale, static_cast<float*>(u_any));
+        RG_LAUNCH_CHECK();
+        return REGIONE_OK;
+    }
+    bf16_t* u = static_cast<bf16_t*>(u_any);
     const bool vec = (hidden % 8 == 0) && hidden <= 64 * 8 * 8 && rg_aligned16(h) && rg_aligned16(u) &&
                      (!shift || rg_aligned16(shift)) && (!scale || rg_aligned16(scale));
     if (vec && h_f32)
@@ -516,7 +523,8 @@ rel_change_kernel(const T* __restrict__ a, const T* __restrict__ b, int64_t n, d
 }
 }  // namespace
 
-extern "C" int regione_rel_change(regione_ctx* ctx, const void* v_new, const void* v_old, int64_t n_elems, int32_t dtype, double* out) {
+extern "C" int regione_rel_change(regione_ctx* ctx, const void* v_new, const void* v_old, int64_t n_elems, int32_t dtype, double* out,
+                                  double* out_host_opt) {
     if (!ctx || !out) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rel_change: null context or output");
     if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rel_change: bad dtype %d", dtype);
     if (n_elems < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "rel_change: n_elems=%lld", static_cast<long long>(n_elems));
@@ -527,5 +535,9 @@ extern "C" int regione_rel_change(regione_ctx* ctx, const void* v_new, const voi
     else
         hipLaunchKernelGGL(rel_change_kernel<float>, dim3(1), dim3(1024), 0, ctx->stream, static_cast<const float*>(v_new), static_cast<const float*>(v_old), n_elems, out);
     RG_LAUNCH_CHECK();
+    if (out_host_opt) {   // the decision is taken on the host: 16 bytes back, after the stream has caught up
+        RG_HIP(hipMemcpyAsync(out_host_opt, out, 2 * sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+        RG_HIP(hipStreamSynchronize(ctx->stream));
+    }
     return REGIONE_OK;
 }

@@ -30,8 +30,7 @@ class EditorModel:
         f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
         self._setup(hidden, heads, head_dim, mlp, channels, n_img, weights["h_txt"].shape[0], 1 if h_txt_uncond is None else 2, guidance)
         self.w_embed = rg.pack_weight(self.ctx, bf(weights["embed"]["w"]))
-        self.b_embed_host = np.asarray(weights["embed"]["b"], dtype=np.float32)
-        self.b_time_host = np.asarray(weights["embed"]["b_time"], dtype=np.float32)
+        self.b_embed, self.b_time = f32(weights["embed"]["b"]), f32(weights["embed"]["b_time"])
         self.w_head, self.b_head = rg.pack_weight(self.ctx, bf(weights["head"]["w"])), f32(weights["head"]["b"])
         self.h_txt = [bf(weights["h_txt"])] + ([] if h_txt_uncond is None else [bf(h_txt_uncond)])
         if "positions" in weights:   # block extras: rotary table of the whole sequence, shared by all blocks
@@ -55,8 +54,7 @@ class EditorModel:
         rnd = lambda *shape, scale=std: (torch.randn(shape, device="cuda", generator=g) * scale)
         wt = lambda o, i, scale=std: rg.pack_weight(self.ctx, rnd(o, i, scale=scale).to(torch.bfloat16))
         self.w_embed = wt(hidden, channels, 4 * std)
-        self.b_embed_host = (0.1 * np.random.default_rng(seed).standard_normal(hidden)).astype(np.float32)
-        self.b_time_host = (0.5 * np.random.default_rng(seed + 1).standard_normal(hidden)).astype(np.float32)
+        self.b_embed, self.b_time = rnd(hidden, scale=0.1), rnd(hidden, scale=0.5)
         # head scaled so that the velocity has the spread of the small test models (0.02 * sqrt(256) = 0.32) at any width
         self.w_head, self.b_head = wt(channels, hidden, 0.32 / float(np.sqrt(hidden))), rnd(channels)
         self.h_txt = [rnd(n_txt, hidden, scale=1.0).to(torch.bfloat16) for _ in range(self.n_branches)]
@@ -96,6 +94,7 @@ class EditorModel:
         self.u = torch.empty((n_branches * n_img, hidden), dtype=torch.bfloat16, device=dev)
         self.v_branch = torch.empty((n_branches, n_img, channels), dtype=torch.float32, device=dev)
         self.all_slots = torch.arange(self.n_all, dtype=torch.int32, device=dev)
+        self.bias_t = torch.empty(hidden, dtype=torch.float32, device=dev)
 
     def _add_block(self, kind: str, streams):
         """streams: one dict per stream, name -> device tensor (linear weights already packed)."""
@@ -110,9 +109,9 @@ class EditorModel:
         self.blocks.append((rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE, bw, kc, torch.zeros_like(kc)))
 
     def _embed_bias(self, t: float):
-        """Bias of the token embedding at time t (input marshalling: a float32 vector b + t * b_time)."""
-        b = (self.b_embed_host + np.float32(t) * self.b_time_host).astype(np.float32)
-        return self.torch.from_numpy(b).cuda()
+        """Bias of the token embedding at time t, b + t * b_time, formed on the device."""
+        rg.regione_time_bias(self.ctx, self.b_embed, self.b_time, float(t), self.bias_t, self.hidden)
+        return self.bias_t
 
     def _head(self, h_rows, n, v_out):
         rg.regione_layernorm(self.ctx, h_rows, rg.BF16, n, self.hidden, None, None, self.u)
@@ -200,8 +199,7 @@ def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: 
     n_e = None
     log = []
     rel_sums = torch.zeros(2, dtype=torch.float64, device=dev)
-    have_cache, reuse_next = False, False
-    state = rg.AvdState()
+    state, rel_state = rg.AvdState(), rg.RelState()
     steps = rg.regione_stage_plan_host(T, t_st, t_sm, forced_k)
     for pos, st in enumerate(steps):
         i = st.i
@@ -223,28 +221,22 @@ def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: 
             rg.regione_gather(ctx, v, c, rg.FP32, u_index, n_u_dev, n_img - n_e, v_u)
             # one jump of the unedited rows to the end of the segment with the last full velocity (Eq.5)
             rg.regione_velocity_cache(ctx, True, 1.0, float(t[i] - t[st.seg_next + 1]), None, v_u, None, x_u, n_u_dev, n_img - n_e, c, rg.FP32)
-            state = rg.AvdState()
-            have_cache, reuse_next = False, False
+            state, rel_state = rg.AvdState(), rg.RelState()
         if rel_trigger is None:
             reuse, factor = rg.regione_velocity_decision_host(t, gamma, T, delta, i, state)
         else:
-            reuse, factor = (reuse_next and have_cache), float(rel_trigger[1])
-            if forced_reuse is not None and i in forced_reuse:
-                reuse = bool(forced_reuse[i]) and have_cache
-            reuse_next = False
+            reuse, factor = rg.regione_rel_decision_host(rel_state, float(rel_trigger[1]))
+            if forced_reuse is not None and i in forced_reuse:     # a test harness imposing another run's decisions
+                reuse = bool(forced_reuse[i]) and bool(rel_state.have_cache)
+                factor = float(rel_trigger[1]) if reuse else 1.0
         if not reuse:
             model.region_forward(x_e, e_index, n_e, t[i], v_e)
-            if rel_trigger is not None and have_cache:     # c_a still holds the previous fresh velocity
-                rel = float("inf")
-                if n_e > 0:
-                    rg.regione_rel_change(ctx, v_e, c_a, n_e * c, rg.FP32, rel_sums)
-                    torch.cuda.synchronize()                # the decision is taken on the host
-                    s_diff, s_old = rel_sums.tolist()
-                    rel = (s_diff ** 0.5) / (s_old ** 0.5) if s_old > 0.0 else float("inf")
-                log.append(("rel", i, rel))
-                reuse_next = rel < rel_trigger[0]
-            factor = 1.0
-        have_cache = True
+            if rel_trigger is not None:
+                had_cache = bool(rel_state.have_cache)      # c_a still holds the previous fresh velocity
+                sums = rg.regione_rel_change(ctx, v_e, c_a, n_e * c, rg.FP32, rel_sums, read_back=True) if had_cache and n_e > 0 else None
+                rel = rg.regione_rel_update_host(rel_state, sums, float(rel_trigger[0]))
+                if had_cache:
+                    log.append(("rel", i, rel))
         rg.regione_velocity_cache(ctx, reuse, factor, float(t[i] - t[i - 1]), None if reuse else v_e, c_a, None, x_e, n_e_dev, n_e, c, rg.FP32)
         log.append((i, "region_reuse" if reuse else "region_fresh"))
         last_of_segment = pos + 1 == len(steps) or steps[pos + 1].kind != rg.STEP_REGION

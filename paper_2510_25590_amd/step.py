@@ -39,16 +39,19 @@ class StepConfig:
     seed: int = 2000
     text_fresh: bool = False  # region step input [X^P, X^E] as in Algorithm 1 (text rows recomputed), not X^E alone with the text in the cache
     extras: bool = False      # query/key RMS normalisation and rotary embedding (positions: text (0,0,0), image (0,y,x), reference (1,y,x))
+    dtype: str = "bf16"       # "bf16" | "f32": storage and arithmetic type of the whole step (a float32 context for "f32")
 
 
-CONFIG_TINY = StepConfig(name="tiny: hidden 256, 4x64 heads, MLP 1024, 16x16 image + 256 reference + 32 text tokens, 6x6 rectangle edited",
-                         hidden=256, heads=4, head_dim=64, mlp=1024, grid=16, n_txt=32, n_edited=36, seed=1000)
+CONFIG_TINY = StepConfig(name="tiny float32: hidden 256, 4x64 heads, MLP 1024, 16x16 image + 256 reference + 32 text tokens, 6x6 rectangle edited",
+                         hidden=256, heads=4, head_dim=64, mlp=1024, grid=16, n_txt=32, n_edited=36, seed=1000, dtype="f32")
+CONFIG_TINY_BF16 = StepConfig(name="tiny bf16: the same shapes through the bf16 kernels",
+                              hidden=256, heads=4, head_dim=64, mlp=1024, grid=16, n_txt=32, n_edited=36, seed=1000)
 CONFIG_BLOCK = StepConfig(name="one double-stream block: hidden 3072, 24x128 heads, MLP 12288, 4096 image + 4096 reference + 512 text tokens, "
                                "one rectangle of 20 % edited, KV cache pre-filled")
 
 
 def host_inputs(cfg: StepConfig):
-    """Seeded host arrays of the workload (float32 values that are exactly representable in bf16)."""
+    """Seeded host arrays of the workload (float32 values; exactly representable in bf16 unless cfg.dtype is "f32")."""
     rng = np.random.default_rng(cfg.seed)
     n_img = cfg.grid * cfg.grid
     if cfg.mask == "rect":
@@ -59,13 +62,14 @@ def host_inputs(cfg: StepConfig):
             want = inputs.rect_mask_fraction(rng, cfg.grid, cfg.grid, cfg.n_edited)
     else:
         want = inputs.blob_mask(rng, cfg.grid, cfg.grid, cfg.n_edited)
-    x_t, v_prev, x_ref = inputs.latents_for_mask(rng, want, cfg.channels, cfg.sigma, "bf16")
+    store = inputs.bf16_round if cfg.dtype == "bf16" else (lambda a: np.asarray(a, dtype=np.float32))
+    x_t, v_prev, x_ref = inputs.latents_for_mask(rng, want, cfg.channels, cfg.sigma, cfg.dtype)
     n_all = cfg.n_txt + 2 * n_img
-    h_store = inputs.hidden_states(rng, n_all, cfg.hidden)          # hidden state the cache was stored from
-    h_now = inputs.bf16_round((h_store[cfg.n_txt:cfg.n_txt + n_img] + 0.05 * rng.standard_normal((n_img, cfg.hidden))).astype(np.float32))
+    h_store = inputs.hidden_states(rng, n_all, cfg.hidden, cfg.dtype)          # hidden state the cache was stored from
+    h_now = store((h_store[cfg.n_txt:cfg.n_txt + n_img] + 0.05 * rng.standard_normal((n_img, cfg.hidden))).astype(np.float32))
     n_streams = 2 if cfg.kind == "double" else 1
-    streams = [inputs.stream_weights(rng, cfg.hidden, cfg.mlp, cfg.kind, "bf16") for _ in range(n_streams)]
-    w_head = inputs.bf16_round((0.02 * rng.standard_normal((cfg.channels, cfg.hidden))).astype(np.float32))
+    streams = [inputs.stream_weights(rng, cfg.hidden, cfg.mlp, cfg.kind, cfg.dtype) for _ in range(n_streams)]
+    w_head = store((0.02 * rng.standard_normal((cfg.channels, cfg.hidden))).astype(np.float32))
     b_head = (0.02 * rng.standard_normal(cfg.channels)).astype(np.float32)
     if cfg.extras:   # drawn last, so the other arrays are those of the plain workload
         for w in streams:
@@ -84,9 +88,11 @@ class RegionStepWorkload:
         hst = self.host
         n_img = cfg.grid * cfg.grid
         self.n_img, self.n_all = n_img, cfg.n_txt + 2 * n_img
-        bf = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).cuda()
+        self.dt = rg.FP32 if cfg.dtype == "f32" else rg.BF16          # dtype enum of every tensor of the step
+        self.ctx = rg.Context(cfg.hidden, cfg.heads, cfg.head_dim, cfg.mlp, self.n_all, n_img, compute_dtype=self.dt)
+        tdt = self.ctx.torch_dtype
+        bf = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(tdt).cuda()   # the step's storage type
         f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
-        self.ctx = rg.Context(cfg.hidden, cfg.heads, cfg.head_dim, cfg.mlp, self.n_all, n_img)
         self.x_t, self.v_prev, self.x_ref = bf(hst["x_t"]), bf(hst["v_prev"]), bf(hst["x_ref"])
         self.h_now = bf(hst["h_now"])
         self._keep = []
@@ -107,7 +113,7 @@ class RegionStepWorkload:
         self.block_type = rg.BLOCK_DOUBLE if cfg.kind == "double" else rg.BLOCK_SINGLE
         self.w_head, self.b_head = rg.pack_weight(self.ctx, bf(hst["w_head"])), f32(hst["b_head"])
         dev = "cuda"
-        self.k_cache = torch.zeros((self.n_all, cfg.heads, cfg.head_dim), dtype=torch.bfloat16, device=dev)
+        self.k_cache = torch.zeros((self.n_all, cfg.heads, cfg.head_dim), dtype=tdt, device=dev)
         self.v_cache = torch.zeros_like(self.k_cache)
         self.score = torch.empty(n_img, dtype=torch.float32, device=dev)
         self.mask = torch.empty(n_img, dtype=torch.uint8, device=dev)
@@ -116,14 +122,14 @@ class RegionStepWorkload:
         self.n_dev = torch.zeros(1, dtype=torch.int32, device=dev)
         # fresh rows of the block: [text rows (only with text_fresh) | edited rows]
         self.n_txt_fresh = cfg.n_txt if cfg.text_fresh else 0
-        self.h_fresh = torch.empty((self.n_txt_fresh + n_img, cfg.hidden), dtype=torch.bfloat16, device=dev)
+        self.h_fresh = torch.empty((self.n_txt_fresh + n_img, cfg.hidden), dtype=tdt, device=dev)
         self.h_fresh_out = torch.empty_like(self.h_fresh)
         self.h_e, self.h_e_out = self.h_fresh[self.n_txt_fresh:], self.h_fresh_out[self.n_txt_fresh:]
         if cfg.text_fresh:
             self.h_fresh[:cfg.n_txt].copy_(bf(hst["h_store"][:cfg.n_txt]))
             self.slots = torch.empty(cfg.n_txt + n_img, dtype=torch.int32, device=dev)   # positions of the fresh rows in [P | X | I]
             self.slots[:cfg.n_txt].copy_(torch.arange(cfg.n_txt, dtype=torch.int32, device=dev))
-        self.x_e = torch.empty((n_img, cfg.channels), dtype=torch.bfloat16, device=dev)
+        self.x_e = torch.empty((n_img, cfg.channels), dtype=tdt, device=dev)
         self.v_e = torch.empty_like(self.x_e)
         self.c_a = torch.zeros_like(self.x_e)
         self.x_next = self.x_t.clone()       # unedited rows keep their value; edited rows are scattered in
@@ -136,29 +142,28 @@ class RegionStepWorkload:
         torch = self.torch
         slots = torch.arange(self.n_all, dtype=torch.int32, device="cuda")
         out = torch.empty_like(h_store)
-        rg.regione_block_forward(self.ctx, self.weights, self.block_type, h_store, out, rg.BF16, self.n_all, self.cfg.n_txt,
+        rg.regione_block_forward(self.ctx, self.weights, self.block_type, h_store, out, self.dt, self.n_all, self.cfg.n_txt,
                                  slots, 0, self.k_cache, self.v_cache, self.n_all, rg.FLAG_STORE)
         torch.cuda.synchronize()
 
     def step(self):
         cfg, ctx = self.cfg, self.ctx
-        n = rg.regione_partition(ctx, self.x_t, self.v_prev, self.x_ref, self.n_img, cfg.channels, rg.BF16, cfg.sigma, cfg.eta,
+        n = rg.regione_partition(ctx, self.x_t, self.v_prev, self.x_ref, self.n_img, cfg.channels, self.dt, cfg.sigma, cfg.eta,
                                  self.score, self.mask, self.e_index, self.u_index, self.n_dev)
         self.n_edited = n
-        rg.regione_gather(ctx, self.h_now, cfg.hidden, rg.BF16, self.e_index, self.n_dev, n, self.h_e)
-        rg.regione_gather(ctx, self.x_t, cfg.channels, rg.BF16, self.e_index, self.n_dev, n, self.x_e)
+        rg.regione_gather(ctx, self.h_now, cfg.hidden, self.dt, self.e_index, self.n_dev, n, self.h_e)
+        rg.regione_gather(ctx, self.x_t, cfg.channels, self.dt, self.e_index, self.n_dev, n, self.x_e)
         if cfg.text_fresh:
-            torch = self.torch
-            torch.add(self.e_index[:n], cfg.n_txt, out=self.slots[cfg.n_txt:cfg.n_txt + n])
-            rg.regione_block_forward(ctx, self.weights, self.block_type, self.h_fresh, self.h_fresh_out, rg.BF16, cfg.n_txt + n, cfg.n_txt,
+            rg.regione_fresh_slots(ctx, self.e_index, self.n_dev, n, cfg.n_txt, self.slots)
+            rg.regione_block_forward(ctx, self.weights, self.block_type, self.h_fresh, self.h_fresh_out, self.dt, cfg.n_txt + n, cfg.n_txt,
                                      self.slots, 0, self.k_cache, self.v_cache, self.n_all, rg.FLAG_RETRIEVE)
         else:
-            rg.regione_block_forward(ctx, self.weights, self.block_type, self.h_e, self.h_e_out, rg.BF16, n, 0,
+            rg.regione_block_forward(ctx, self.weights, self.block_type, self.h_e, self.h_e_out, self.dt, n, 0,
                                      self.e_index, cfg.n_txt, self.k_cache, self.v_cache, self.n_all, rg.FLAG_RETRIEVE)
-        rg.regione_linear(ctx, self.h_e_out, self.w_head, self.b_head, n, cfg.channels, cfg.hidden, rg.ACT_NONE, rg.BF16, self.v_e)
-        rg.regione_velocity_cache(ctx, False, 1.0, cfg.dt, self.v_e, self.c_a, None, self.x_e, self.n_dev, n, cfg.channels, rg.BF16)
-        rg.regione_scatter(ctx, self.x_next, cfg.channels, rg.BF16, self.e_index, self.n_dev, n, self.x_e)
-        rg.regione_scatter(ctx, self.h_next, cfg.hidden, rg.BF16, self.e_index, self.n_dev, n, self.h_e_out)
+        rg.regione_linear(ctx, self.h_e_out, self.w_head, self.b_head, n, cfg.channels, cfg.hidden, rg.ACT_NONE, self.dt, self.v_e)
+        rg.regione_velocity_cache(ctx, False, 1.0, cfg.dt, self.v_e, self.c_a, None, self.x_e, self.n_dev, n, cfg.channels, self.dt)
+        rg.regione_scatter(ctx, self.x_next, cfg.channels, self.dt, self.e_index, self.n_dev, n, self.x_e)
+        rg.regione_scatter(ctx, self.h_next, cfg.hidden, self.dt, self.e_index, self.n_dev, n, self.h_e_out)
         return n
 
     def flops(self, n: int):

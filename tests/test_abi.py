@@ -1,5 +1,6 @@
 """Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
 and the pure-host entry point (the velocity-cache decision, Eq.7-8) agrees with the oracle."""
+import ctypes as C
 import os
 import re
 
@@ -12,10 +13,16 @@ from paper_2510_25590_amd import binding as rg
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+HEADERS = ("regione.h", "regione_bench.h")     # the method's ABI, and the measurement aids beside it
+
+
 def _declared():
-    text = open(os.path.join(ROOT, "include", "regione.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(regione_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for h in HEADERS:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(regione_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -36,11 +43,48 @@ def test_error_paths_without_gpu():
     with pytest.raises(rg.RegionEError):
         rg.regione_velocity_decision_host([0.0, 1.0], [1.0, 1.0], 1, 0.1, 1, st)   # j outside [1, n_steps)
     import ctypes as C
-    bad = rg.Dims(256, 4, 32, 1024, 16, 16)
+    bad = rg.Dims(256, 4, 32, 1024, 16, 16, rg.BF16)
     h = C.c_void_p()
     assert lib.regione_create(C.byref(h), C.byref(bad), None) == rg.ERR_BAD_SHAPE
-    bad = rg.Dims(128, 4, 32, 1024, 16, 16)
+    bad = rg.Dims(128, 4, 32, 1024, 16, 16, rg.BF16)
     assert lib.regione_create(C.byref(h), C.byref(bad), None) == rg.ERR_UNSUPPORTED
+    bad = rg.Dims(256, 4, 64, 1024, 16, 16, 7)
+    assert lib.regione_create(C.byref(h), C.byref(bad), None) == rg.ERR_INVALID_ARG
+
+
+def test_relative_change_trigger_host_calls_match_oracle_rule():
+    """The data-dependent reuse trigger (not the paper's Eq.8): a segment starts with two fresh steps, a fresh step whose
+    velocity moved by less than the threshold lets the NEXT step reuse, never two reuses in a row - the rule that
+    oracle.regione_loop(rel_trigger=...) states, replayed here on a sequence of relative changes."""
+    thr, decay = 0.05, 0.9
+    rels = [0.2, 0.01, 0.02, 0.01, 0.3, 0.0499, 0.0501, 0.001]     # relative change measured at the k-th fresh step that has a cache
+    st = rg.RelState()
+    got, k = [], 0
+    want, reuse_next, have = [], False, False
+    k_o = 0
+    for _ in range(14):
+        reuse, factor = rg.regione_rel_decision_host(st, decay)
+        r_o = reuse_next and have
+        reuse_next = False
+        assert reuse == r_o and factor == pytest.approx(decay if r_o else 1.0)
+        if not reuse:
+            if st.have_cache:
+                rel = rels[k % len(rels)]; k += 1
+                sums = (C.c_double * 2)(rel * rel * 4.0, 4.0)
+                assert rg.regione_rel_update_host(st, sums, thr) == pytest.approx(rel, rel=1e-12)
+            else:
+                assert rg.regione_rel_update_host(st, None, thr) == float("inf")
+            if have:
+                reuse_next = rels[k_o % len(rels)] < float(np.float32(thr)); k_o += 1     # the ABI takes the threshold as a float
+            have = True
+        got.append(reuse); want.append(r_o)
+    assert got == want and got[:2] == [False, False] and any(got)
+    assert not any(a and b for a, b in zip(got, got[1:]))
+    # zero old norm: infinite change, no reuse; NaN or negative sums are refused
+    st = rg.RelState(1, 0)
+    assert rg.regione_rel_update_host(st, (C.c_double * 2)(1.0, 0.0), thr) == float("inf") and st.reuse_next == 0
+    with pytest.raises(rg.RegionEError):
+        rg.regione_rel_update_host(st, (C.c_double * 2)(float("nan"), 1.0), thr)
 
 
 @pytest.mark.parametrize("delta", [0.04, 0.03, 0.08, -1.0, 10.0])
@@ -108,13 +152,16 @@ def test_header_is_plain_c(tmp_path):
     gcc = shutil.which("gcc")
     if gcc is None:
         pytest.skip("no C compiler here")
-    header = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "regione.h")
-    names = re.findall(r"^\s*(?:int|int64_t|const char\*)\s+(regione_\w+)\s*\(", open(header).read(), flags=re.M)
-    assert len(names) >= 25
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    header = os.path.join(inc, "regione.h")
+    names = []
+    for h in HEADERS:
+        names += re.findall(r"^\s*(?:int|int64_t|const char\*)\s+(regione_\w+)\s*\(", open(os.path.join(inc, h)).read(), flags=re.M)
+    assert len(names) >= 35
     src = tmp_path / "use_header.c"
-    src.write_text('#include "regione.h"\ntypedef void (*fn)(void);\n' + "fn table[] = {" + ", ".join(f"(fn){n}" for n in names) + "};\n"
+    src.write_text('#include "regione.h"\n#include "regione_bench.h"\ntypedef void (*fn)(void);\n' + "fn table[] = {" + ", ".join(f"(fn){n}" for n in names) + "};\n"
                    "int main(void) { regione_dims d = {0}; regione_block_weights w = {0}; regione_avd_state s = {0}; regione_plan_step p = {0};\n"
-                   "  (void)d; (void)w; (void)s; (void)p; return sizeof(table) > 0 ? 0 : 1; }\n")
+                   "  regione_rel_state r = {0}; (void)d; (void)w; (void)s; (void)p; (void)r; return sizeof(table) > 0 ? 0 : 1; }\n")
     r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", os.path.dirname(header), str(src)],
                        capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
