@@ -132,6 +132,20 @@ int regione_partition(regione_ctx* ctx, const void* x_t, const void* v, const vo
                       float* score_opt, uint8_t* mask, int32_t* e_index, int32_t* u_index,
                       int32_t* n_edited_dev, int32_t* n_edited_host_opt);
 
+/* regione_partition for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Needs no context and calls no allocating routine: the per-block counts
+ * that regione_partition keeps in its context's workspace live in a static device array of the library (256 KiB per
+ * GPU, held until the process ends; its address is looked up on the first call on each device, or by regione_create).
+ * Same kernels, same results bit for bit.  hip_stream: a hipStream_t (NULL = default stream) on the CURRENT device;
+ * the call is asynchronous and returns no host count (read n_edited_dev after the stream has caught up).
+ * n_tokens > 4194304 (2^22): REGIONE_ERR_WORKSPACE.  All calls on one GPU share the one array: calls that overlap
+ * in time on the same GPU (different streams or threads) race; calls on one stream are safe.  Nothing in the array
+ * needs clearing between calls. */
+int regione_partition_static(void* hip_stream, const void* x_t, const void* v, const void* x_ref,
+                             int64_t n_tokens, int32_t c, int32_t dtype, float sigma_t, float eta,
+                             float* score_opt, uint8_t* mask, int32_t* e_index, int32_t* u_index,
+                             int32_t* n_edited_dev);
+
 /* Morphological clean-up of the partition on the token grid (section "Adaptive Region
  * Partition": opening and closing make the two regions more continuous; Algorithm 1 applies
  * erosion and dilation to the map cos > eta, i.e. to the unedited region).  Opening (erosion

@@ -29,7 +29,7 @@ EXPORTS = (
     "regione_vec_linear", "regione_timestep_embedding", "regione_block_forward_batched",
     "regione_sq_norms", "regione_gamma_fit_host", "regione_guidance_combine", "regione_rel_change",
     "regione_quantize_rows_fp8", "regione_pack_weight_fp8", "regione_linear_fp8", "regione_mfma_peak_probe",
-    "regione_rel_decision_host", "regione_rel_update_host", "regione_fresh_slots", "regione_time_bias",
+    "regione_partition_static", "regione_rel_decision_host", "regione_rel_update_host", "regione_fresh_slots", "regione_time_bias",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -104,6 +104,7 @@ def lib() -> C.CDLL:
             "regione_rel_update_host": [C.POINTER(RelState), C.POINTER(C.c_double), f32, C.POINTER(C.c_double)],
             "regione_fresh_slots": [vp, vp, vp, i64, i32, vp],
             "regione_time_bias": [vp, vp, vp, f32, vp, i32],
+            "regione_partition_static": [vp, vp, vp, vp, i64, i32, i32, f32, f32, vp, vp, vp, vp, vp],
             "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
             "regione_pack_weight": [vp, vp, i32, i32, vp],
@@ -254,6 +255,12 @@ def regione_fresh_slots(ctx, index, n_dev, n_max, n_txt, slots):
 
 def regione_time_bias(ctx, b, b_time, t, out, n):
     _check(lib().regione_time_bias(ctx.handle, _p(b), _p(b_time), float(t), _p(out), n))
+
+
+def regione_partition_static(stream, x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta, score, mask, e_index, u_index, n_edited_dev):
+    """The partition without a context (allocates nothing); stream: a torch stream or None for the default stream."""
+    _check(lib().regione_partition_static(None if stream is None else C.c_void_p(stream.cuda_stream), _p(x_t), _p(v), _p(x_ref),
+                                          n_tokens, c, dtype, sigma_t, eta, _p(score), _p(mask), _p(e_index), _p(u_index), _p(n_edited_dev)))
 
 
 def regione_guidance_combine(ctx, v_cond, v_uncond, scale, out, n_elems, dtype):

@@ -87,6 +87,7 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
         c->n_edited_pinned_dev = static_cast<int32_t*>(dev);
         *c->n_edited_pinned = 0;
     }
+    if (rc == REGIONE_OK) rc = rg_partition_static_warm();   // so that regione_partition_static's first call has nothing to set up
     if (rc != REGIONE_OK) { free_all(c); delete c; return rc; }
     *out = c;
     return REGIONE_OK;

@@ -112,4 +112,5 @@ int rg_attention_f32(regione_ctx* ctx, const float* q, int ldq, int n_q,
                      const float* k1, const float* v1, int ldkv1, int n1, const int32_t* idx1,
                      int heads, int d, float scale, float* out, int ldo);
 int rg_pack_weight_f32(regione_ctx* ctx, const float* w, int n, int k, float* w_packed);
-
+// the static-scratch lookup of regione_partition_static, done ahead of time by regione_create
+int rg_partition_static_warm(void);

@@ -405,3 +405,58 @@ extern "C" int regione_mask_cleanup(regione_ctx* ctx, const uint8_t* mask_in, in
     }
     return REGIONE_OK;
 }
+
+// ---- the partition for callers that cannot allocate device memory
+// Same kernels as regione_partition; the per-block counts live in a static device array instead of a context's
+// workspace.  Every GPU holds its own copy of the array at its own address, looked up once per device.
+#define RG_STATIC_COUNTS 65536                       /* int32 entries: 256 KiB per GPU, held until the process ends */
+static __device__ __align__(256) int32_t scratch[RG_STATIC_COUNTS];
+
+namespace {
+
+constexpr int64_t kStaticCounts = RG_STATIC_COUNTS;
+constexpr int64_t kStaticMaxTokens = int64_t{1} << 22;
+constexpr int kMaxDevices = 64;
+
+int32_t* g_scratch_ptr[kMaxDevices];                 // device address of `scratch` on each device, null until looked up
+
+// Address of this device's copy of `scratch` (host code must never pass the array's name to a kernel: on the host it
+// is a stand-in, not a device address).
+int scratch_for_current_device(int32_t** out) {
+    int dev = -1;
+    RG_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "partition_static: device ordinal %d (at most %d devices)", dev, kMaxDevices);
+    int32_t* p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        void* sym = nullptr;
+        RG_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+        if (!sym) RG_FAIL(REGIONE_ERR_HIP, "partition_static: the scratch symbol has no address on device %d", dev);
+        p = static_cast<int32_t*>(sym);
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);   // every thread looks up the same address: a race is harmless
+    }
+    *out = p;
+    return REGIONE_OK;
+}
+
+}  // namespace
+
+int rg_partition_static_warm(void) {
+    int32_t* p = nullptr;
+    return scratch_for_current_device(&p);
+}
+
+extern "C" int regione_partition_static(void* hip_stream, const void* x_t, const void* v, const void* x_ref,
+                                        int64_t n_tokens, int32_t c, int32_t dtype, float sigma_t, float eta,
+                                        float* score_opt, uint8_t* mask, int32_t* e_index, int32_t* u_index,
+                                        int32_t* n_edited_dev) {
+    if (int rc = check_partition_args("partition_static", x_t, v, x_ref, n_tokens, c, dtype, mask, e_index, u_index, n_edited_dev)) return rc;
+    if (n_tokens > kStaticMaxTokens)
+        RG_FAIL(REGIONE_ERR_WORKSPACE, "partition_static: %lld tokens exceed the limit of %lld of the entry point that allocates nothing",
+                (long long)n_tokens, (long long)kStaticMaxTokens);
+    int32_t* counts = nullptr;
+    if (int rc = scratch_for_current_device(&counts)) return rc;
+    // Nothing in the array has to start at zero: the score kernel writes the count of every block of this call before
+    // the index kernels read them, and entries past the call's block count are never read.
+    return partition_launches(static_cast<hipStream_t>(hip_stream), counts, kStaticCounts, x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta,
+                              score_opt, mask, e_index, u_index, n_edited_dev, n_edited_dev);
+}

@@ -50,6 +50,9 @@ def test_error_paths_without_gpu():
     assert lib.regione_create(C.byref(h), C.byref(bad), None) == rg.ERR_UNSUPPORTED
     bad = rg.Dims(256, 4, 64, 1024, 16, 16, 7)
     assert lib.regione_create(C.byref(h), C.byref(bad), None) == rg.ERR_INVALID_ARG
+    # the entry point that allocates nothing checks its arguments and its size limit before it touches the device
+    assert lib.regione_partition_static(None, None, None, None, 16, 64, 0, 0.5, 0.9, None, None, None, None, None) == rg.ERR_INVALID_ARG
+    assert lib.regione_partition_static(None, None, None, None, -1, 64, 0, 0.5, 0.9, None, None, None, None, None) == rg.ERR_INVALID_ARG
 
 
 def test_relative_change_trigger_host_calls_match_oracle_rule():
