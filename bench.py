@@ -89,7 +89,15 @@ def membound(torch, rg):
         rg.regione_partition(ctx, x_t, v, ref, n_tok, c, rg.BF16, 0.7, 0.9, score, mask, e_idx, u_idx, cnt, read_count=False)
     ms = rg.regione_profile_read(ctx)["partition"][0] / reps
     nbytes = n_tok * (3 * c * 2 + 4 + 1 + 4)        # three latents in; score, mask, one index out
-    res["partition"] = {"tokens": n_tok, "edited": n_e, "ms": ms, "GB/s": nbytes / ms / 1e6, "frac_hbm": nbytes / ms / 1e6 / PEAK_HBM_GBS}
+    res["partition"] = {"tokens": n_tok, "edited": n_e, "ms": ms, "GB/s": nbytes / ms / 1e6, "frac_hbm": nbytes / ms / 1e6 / PEAK_HBM_GBS,
+                        "bytes_per_token": 3 * c * 2 + 9, "outputs": "score, mask, index lists"}
+    # the same without the optional score output (the method itself needs only the mask and the index lists)
+    for _ in range(reps):
+        rg.regione_partition(ctx, x_t, v, ref, n_tok, c, rg.BF16, 0.7, 0.9, None, mask, e_idx, u_idx, cnt, read_count=False)
+    ms = rg.regione_profile_read(ctx)["partition"][0] / reps
+    nbytes = n_tok * (3 * c * 2 + 1 + 4)
+    res["partition_no_score"] = {"tokens": n_tok, "edited": n_e, "ms": ms, "GB/s": nbytes / ms / 1e6, "frac_hbm": nbytes / ms / 1e6 / PEAK_HBM_GBS,
+                                 "bytes_per_token": 3 * c * 2 + 5, "outputs": "mask, index lists"}
     # gather / scatter of 128-byte latent rows through the index list just built
     dst = torch.empty((n_e, c), dtype=torch.bfloat16, device="cuda")
     for name, fn in (("gather_latent", lambda: rg.regione_gather(ctx, x_t, c, rg.BF16, e_idx, cnt, n_e, dst)),
@@ -446,6 +454,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-membound", action="store_true")
+    ap.add_argument("--membound-only", action="store_true",
+                    help="only the HBM-bound kernels (partition, gathers, scatters, velocity cache, modulation vectors) on multi-GiB working sets: one JSON line")
     ap.add_argument("--no-fp8", action="store_true", help="skip the secondary measurement of the projections in E4M3")
     ap.add_argument("--no-peaks", action="store_true", help="skip the register-only MFMA loops and the 1 GiB copy that measure the chip's own peaks")
     ap.add_argument("--no-mode-a", action="store_true", help="skip the secondary measurement with the text rows fresh")
@@ -487,6 +497,9 @@ def main():
     from paper_2510_25590_amd import step
 
     rg.lib()   # fails loudly if the HIP library has not been built
+    if args.membound_only:
+        print(json.dumps({"membound": membound(torch, rg), "data": "synthetic", "dtype": "bf16"}))
+        return
     if args.cfg:
         print(json.dumps(cfg_benchmark(args.steps, args.warmup)))
         return

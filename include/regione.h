@@ -134,8 +134,8 @@ int regione_partition(regione_ctx* ctx, const void* x_t, const void* v, const vo
 
 /* regione_partition for callers that cannot allocate device memory: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  Needs no context and calls no allocating routine: the per-block counts
- * that regione_partition keeps in its context's workspace live in a static device array of the library (256 KiB per
- * GPU, held until the process ends; its address is looked up on the first call on each device, or by regione_create).
+ * and decision bits that regione_partition keeps in its context's workspace live in a static device array of the library
+ * (768 KiB per GPU, held until the process ends; its address is looked up on the first call on each device, or by regione_create).
  * Same kernels, same results bit for bit.  hip_stream: a hipStream_t (NULL = default stream) on the CURRENT device;
  * the call is asynchronous and returns no host count (read n_edited_dev after the stream has caught up).
  * n_tokens > 4194304 (2^22): REGIONE_ERR_WORKSPACE.  All calls on one GPU share the one array: calls that overlap

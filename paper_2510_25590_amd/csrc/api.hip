@@ -61,7 +61,7 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; RG_FAIL(REGIONE_ERR_HIP, "create: no HIP device"); }
     const size_t n = static_cast<size_t>(dims->max_fresh), H = dims->hidden, M = dims->mlp;
     const size_t es = c->f32 ? 4 : 2;   // bytes per activation element
-    c->part_counts_cap = dims->max_tokens / 4 + 8;
+    c->part_counts_cap = rg_partition_scratch_ints(dims->max_tokens);   // per-block counts and one decision bit per token
     const size_t split_rows = n < 2048 ? n : 2048;
     c->attn_part_bytes = static_cast<size_t>(8) * dims->heads * split_rows * (dims->head_dim + 4) * sizeof(float);
     int rc = dev_alloc(&c->part_counts, static_cast<size_t>(c->part_counts_cap));

@@ -15,8 +15,8 @@ struct regione_ctx {
     int device;
     int f32;       // compute dtype of the context is float32: the activation buffers below then hold 4-byte elements
     // workspace (device)
-    int32_t* part_counts;  // per-block edited counts of the partition
-    int64_t part_counts_cap;
+    int32_t* part_counts;  // scratch of the partition: per-block edited counts, then one decision bit per token
+    int64_t part_counts_cap;   // its size in int32 entries
     int32_t* n_edited_pinned;      // pinned host copy of the last edited-token count (host address)
     int32_t* n_edited_pinned_dev;  // the same memory as the device sees it
     // activation buffers: elements of the compute dtype (bf16, or float32 in a float32 context); addressed in bytes
@@ -114,3 +114,5 @@ int rg_attention_f32(regione_ctx* ctx, const float* q, int ldq, int n_q,
 int rg_pack_weight_f32(regione_ctx* ctx, const float* w, int n, int k, float* w_packed);
 // the static-scratch lookup of regione_partition_static, done ahead of time by regione_create
 int rg_partition_static_warm(void);
+// int32 entries of scratch memory the partition needs for max_tokens tokens
+int64_t rg_partition_scratch_ints(int64_t max_tokens);

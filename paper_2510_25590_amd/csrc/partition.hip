@@ -1,45 +1,53 @@
 // Adaptive region partition: one-step estimate (Eq.5 with t_f = 0), per-token cosine score
-// against the reference latent, threshold, and a deterministic three-kernel compaction of the
-// edited / unedited index lists (Algorithm 1, ARP lines; section "Adaptive Region Partition").
+// against the reference latent, threshold, and a deterministic compaction of the edited /
+// unedited index lists (Algorithm 1, ARP lines; section "Adaptive Region Partition").
 //
-// Kernel 1 streams x_t, v, x_ref once (16-byte loads, a group of LPT lanes per token), reduces
-// the three sums in float64 inside the lane group, writes score and mask and one edited count
-// per block.  Kernel 2 (one workgroup) turns the counts into exclusive offsets; kernel 3 writes the
-// index lists with a ballot/popcount rank.  No atomics, so the lists come out in ascending order.
+// Kernel 1 streams x_t, v, x_ref once (16-byte loads, a group of LPT lanes per token, the loads of
+// the next tokens in flight while the current ones are reduced), sums in float64 inside the lane
+// group, and leaves the three sums of every token of its block in LDS; one thread per token then
+// forms the score and the decision.  It writes ONE BIT per token (and the score, if asked for) and
+// one edited count per block: on MI355X a trickle of small writes inside a read stream costs far
+// more than its bytes (measured on 8.4 M tokens: 463 us without the 5 bytes per token of score and
+// byte mask, 548 us with them).  Kernel 2 (one workgroup, only for many blocks) turns the counts
+// into exclusive offsets; kernel 3 expands the bits into the byte mask and writes the index lists
+// with a popcount rank.  No atomics, so the lists come out in ascending order.
 #include "common.h"
 
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-
-template <typename T> struct Vec16;
-template <> struct Vec16<bf16_t> { static constexpr int N = 8; };
-template <> struct Vec16<float> { static constexpr int N = 4; };
-
-template <typename T, int VEC>
-__device__ __forceinline__ void load_chunk(const T* p, float (&out)[VEC]);
+constexpr int kMaxBlockTokens = 1024;   // tokens per workgroup of the score kernel (LDS: three float64 sums per token)
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// The three inputs are read exactly once: non-temporal loads keep them from displacing anything in the caches
-// (measured on MI355X: 6.9 TB/s for a read-only stream with them against 6.1 TB/s without).
-template <> __device__ __forceinline__ void load_chunk<bf16_t, 8>(const bf16_t* p, float (&out)[8]) {
-    const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-    uint32_t w[4] = {r[0], r[1], r[2], r[3]};
+// One chunk of VEC elements as loaded (raw) and as floats.  The three inputs are read exactly once: non-temporal loads
+// keep them from displacing anything in the caches (6.9 TB/s for a read-only stream with them against 6.1 without).
+template <typename T, int VEC> struct Chunk;
+template <> struct Chunk<bf16_t, 8> {
+    u32x4 raw;
+    __device__ __forceinline__ void load(const bf16_t* p) { raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)); }
+    __device__ __forceinline__ void unpack(float (&out)[8]) const {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        out[2 * i] = __uint_as_float(w[i] << 16);
-        out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        for (int i = 0; i < 4; ++i) { out[2 * i] = __uint_as_float(raw[i] << 16); out[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u); }
     }
-}
-template <> __device__ __forceinline__ void load_chunk<float, 4>(const float* p, float (&out)[4]) {
-    const f32x4 r = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-    out[0] = r[0]; out[1] = r[1]; out[2] = r[2]; out[3] = r[3];
-}
-template <> __device__ __forceinline__ void load_chunk<bf16_t, 1>(const bf16_t* p, float (&out)[1]) { out[0] = bf16_to_f32(*p); }
-template <> __device__ __forceinline__ void load_chunk<float, 1>(const float* p, float (&out)[1]) { out[0] = *p; }
+};
+template <> struct Chunk<float, 4> {
+    f32x4 raw;
+    __device__ __forceinline__ void load(const float* p) { raw = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p)); }
+    __device__ __forceinline__ void unpack(float (&out)[4]) const { out[0] = raw[0]; out[1] = raw[1]; out[2] = raw[2]; out[3] = raw[3]; }
+};
+template <> struct Chunk<bf16_t, 1> {
+    bf16_t raw;
+    __device__ __forceinline__ void load(const bf16_t* p) { raw = *p; }
+    __device__ __forceinline__ void unpack(float (&out)[1]) const { out[0] = bf16_to_f32(raw); }
+};
+template <> struct Chunk<float, 1> {
+    float raw;
+    __device__ __forceinline__ void load(const float* p) { raw = *p; }
+    __device__ __forceinline__ void unpack(float (&out)[1]) const { out[0] = raw; }
+};
 
 __device__ __forceinline__ double shfl_xor_f64(double x, int m) {
     int lo = __double2loint(x), hi = __double2hiint(x);
@@ -47,73 +55,129 @@ __device__ __forceinline__ double shfl_xor_f64(double x, int m) {
     hi = __shfl_xor(hi, m, 64);
     return __hiloint2double(hi, lo);
 }
+// The value of another lane of the same row of 16 through the data-parallel-primitive path of the vector ALU (no trip
+// through LDS as with a shuffle).  CTRL: 0xB1 = lanes xor 1, 0x4E = xor 2, 0x141 = i <-> 7 - i, 0x140 = i <-> 15 - i.
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double x) {
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+// Sum over the LPT lanes of a token's group, the same in every lane of the group.  After the xor-1 and xor-2 steps the
+// four lanes of a quad agree, so the mirrored lane of the other quad (then of the other half row) holds the partner's sum.
+template <int LPT> __device__ __forceinline__ double group_sum(double x) {
+    if (LPT >= 2) x += dpp_f64<0xB1>(x);
+    if (LPT >= 4) x += dpp_f64<0x4E>(x);
+    if (LPT >= 8) x += dpp_f64<0x141>(x);
+    if (LPT >= 16) x += dpp_f64<0x140>(x);
+    if (LPT >= 32) x += shfl_xor_f64(x, 16);
+    if (LPT >= 64) x += shfl_xor_f64(x, 32);
+    return x;
+}
 
-// One block handles tokens [blockIdx.x * tok_per_block, +tok_per_block).
-template <typename T, int VEC, int LPT>
+// One block handles tokens [blockIdx.x * tok_per_block, +tok_per_block); tok_per_block is a multiple of 64 and at most
+// kMaxBlockTokens.  PIPE: every lane owns exactly one chunk of its token (c == VEC * LPT) and the chunks of the next
+// STAGE tokens are requested before the current ones are reduced.  Otherwise a lane loops over its chunks.
+// bits: one 64-bit word per 64 tokens, bit = edited; words of tokens past n_tokens are written with those bits clear.
+template <typename T, int VEC, int LPT, bool PIPE>
 __global__ void __launch_bounds__(kThreads)
-score_mask_kernel(const T* __restrict__ x_t, const T* __restrict__ v, const T* __restrict__ x_ref,
+score_bits_kernel(const T* __restrict__ x_t, const T* __restrict__ v, const T* __restrict__ x_ref,
                   int64_t n_tokens, int c, int tok_per_block, float sigma, float eta,
-                  float* __restrict__ score, uint8_t* __restrict__ mask, int32_t* __restrict__ counts) {
-    constexpr int TOK_PER_WAVE = 64 / LPT;
+                  float* __restrict__ score, uint64_t* __restrict__ bits, int32_t* __restrict__ counts) {
+    constexpr int TPW = 64 / LPT;                       // tokens per wave and pass
+    constexpr int STAGE = 2;                            // passes whose loads travel together
+    constexpr int STAGE_TOK = kWaves * TPW * STAGE;     // tokens per workgroup and stage
+    __shared__ double s_sum[3][kMaxBlockTokens];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int sub = lane % LPT, tok_in_wave = lane / LPT;
-    const int nchunks = c / VEC;
+    const int sub = lane % LPT, tiw = lane / LPT;
     const int64_t block_first = static_cast<int64_t>(blockIdx.x) * tok_per_block;
-    int edited_count = 0;
-    // Tokens past the end re-read token 0 (valid memory) and are dropped afterwards, so the loads are branch free.
-    // Two passes are handled together: all their loads are issued before the first reduction starts (four at a time
-    // cost too many registers for the float64 sums and ran slower).
-    constexpr int UNROLL = 2;
-    constexpr int PASS_STRIDE = kWaves * TOK_PER_WAVE;
-    for (int pass0 = wave * TOK_PER_WAVE; pass0 < tok_per_block; pass0 += UNROLL * PASS_STRIDE) {
-        double dot[UNROLL], na[UNROLL], nb[UNROLL];
-        int64_t tok[UNROLL];
-        bool live[UNROLL];
+    int64_t left = n_tokens - block_first;
+    const int block_tokens = static_cast<int>(left < tok_per_block ? left : tok_per_block);
+    const int n_stage = (block_tokens + STAGE_TOK - 1) / STAGE_TOK;
+    auto tok_of = [&](int st, int u) { return st * STAGE_TOK + (u * kWaves + wave) * TPW + tiw; };   // token inside the block
+
+    auto accumulate = [&](const Chunk<T, VEC>& ca, const Chunk<T, VEC>& cb, const Chunk<T, VEC>& cr, double& dot, double& na, double& nb) __attribute__((always_inline)) {
+        float a[VEC], b[VEC], r[VEC];
+        ca.unpack(a); cb.unpack(b); cr.unpack(r);
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int pass = pass0 + u * PASS_STRIDE;
-            tok[u] = block_first + pass + tok_in_wave;
-            live[u] = (pass + tok_in_wave) < tok_per_block && tok[u] < n_tokens;
-            dot[u] = 0.0; na[u] = 0.0; nb[u] = 0.0;
+        for (int i = 0; i < VEC; ++i) {
+            const float est = __fsub_rn(a[i], __fmul_rn(sigma, b[i]));  // two roundings, never an fma
+            const double e = est, rr = r[i];
+            dot = fma(e, rr, dot);
+            na = fma(e, e, na);
+            nb = fma(rr, rr, nb);
         }
-        for (int ch = sub; ch < nchunks; ch += LPT) {
-            float a[UNROLL][VEC], b[UNROLL][VEC], r[UNROLL][VEC];
+    };
+    auto finish = [&](int t, double dot, double na, double nb) __attribute__((always_inline)) {
+        dot = group_sum<LPT>(dot); na = group_sum<LPT>(na); nb = group_sum<LPT>(nb);
+        if (sub == 0 && t < block_tokens) { s_sum[0][t] = dot; s_sum[1][t] = na; s_sum[2][t] = nb; }
+    };
+
+    if (PIPE) {
+        // tokens past the end of the block re-read its first token (valid memory) and are dropped afterwards
+        Chunk<T, VEC> ra[2][STAGE], rb[2][STAGE], rr[2][STAGE];
+        auto issue = [&](int st, int buf) __attribute__((always_inline)) {
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const int64_t base = (live[u] ? tok[u] : 0) * c + ch * VEC;
-                load_chunk<T, VEC>(x_t + base, a[u]);
-                load_chunk<T, VEC>(v + base, b[u]);
-                load_chunk<T, VEC>(x_ref + base, r[u]);
+            for (int u = 0; u < STAGE; ++u) {
+                const int t = tok_of(st, u);
+                const int64_t base = (block_first + (t < block_tokens ? t : 0)) * c + sub * VEC;
+                ra[buf][u].load(x_t + base); rb[buf][u].load(v + base); rr[buf][u].load(x_ref + base);
             }
+        };
+        auto reduce = [&](int st, int buf) __attribute__((always_inline)) {
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u)
+            for (int u = 0; u < STAGE; ++u) {
+                double dot = 0.0, na = 0.0, nb = 0.0;
+                accumulate(ra[buf][u], rb[buf][u], rr[buf][u], dot, na, nb);
+                finish(tok_of(st, u), dot, na, nb);
+            }
+        };
+        if (n_stage > 0) issue(0, 0);
+        for (int st = 0; st < n_stage; st += 2) {
+            if (st + 1 < n_stage) issue(st + 1, 1);
+            reduce(st, 0);
+            if (st + 1 < n_stage) {
+                if (st + 2 < n_stage) issue(st + 2, 0);
+                reduce(st + 1, 1);
+            }
+        }
+    } else {
+        const int nchunks = c / VEC;
+        for (int st = 0; st < n_stage; ++st) {
+            double dot[STAGE], na[STAGE], nb[STAGE];
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) {
-                    const float est = __fsub_rn(a[u][i], __fmul_rn(sigma, b[u][i]));  // two roundings, never an fma
-                    const double e = est, rr = r[u][i];
-                    dot[u] = fma(e, rr, dot[u]);
-                    na[u] = fma(e, e, na[u]);
-                    nb[u] = fma(rr, rr, nb[u]);
+            for (int u = 0; u < STAGE; ++u) { dot[u] = 0.0; na[u] = 0.0; nb[u] = 0.0; }
+            for (int ch = sub; ch < nchunks; ch += LPT) {
+                Chunk<T, VEC> ca[STAGE], cb[STAGE], cr[STAGE];
+#pragma unroll
+                for (int u = 0; u < STAGE; ++u) {
+                    const int t = tok_of(st, u);
+                    const int64_t base = (block_first + (t < block_tokens ? t : 0)) * c + ch * VEC;
+                    ca[u].load(x_t + base); cb[u].load(v + base); cr[u].load(x_ref + base);
                 }
-        }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
+                for (int u = 0; u < STAGE; ++u) accumulate(ca[u], cb[u], cr[u], dot[u], na[u], nb[u]);
+            }
 #pragma unroll
-            for (int m = 1; m < LPT; m <<= 1) {
-                dot[u] += shfl_xor_f64(dot[u], m);
-                na[u] += shfl_xor_f64(na[u], m);
-                nb[u] += shfl_xor_f64(nb[u], m);
-            }
-            bool edited = false;
-            if (live[u] && sub == 0) {
-                const double denom = fmax(sqrt(na[u]) * sqrt(nb[u]), 1e-8);
-                const float s = static_cast<float>(dot[u] / denom);
-                edited = !(s > eta);
-                if (score) score[tok[u]] = s;
-                mask[tok[u]] = edited ? 1 : 0;
-            }
-            edited_count += __popcll(__ballot(edited));
+            for (int u = 0; u < STAGE; ++u) finish(tok_of(st, u), dot[u], na[u], nb[u]);
         }
+    }
+    __syncthreads();
+
+    // one thread per token: score, decision, one bit
+    int edited_count = 0;
+    for (int t0 = 0; t0 < tok_per_block; t0 += kThreads) {
+        const int t = t0 + threadIdx.x;
+        bool edited = false;
+        if (t < block_tokens) {
+            const double denom = fmax(sqrt(s_sum[1][t]) * sqrt(s_sum[2][t]), 1e-8);
+            const float s = static_cast<float>(s_sum[0][t] / denom);
+            edited = !(s > eta);
+            if (score) __builtin_nontemporal_store(s, score + block_first + t);
+        }
+        const unsigned long long word = __ballot(edited);
+        edited_count += __popcll(word);
+        if (lane == 0 && t0 + wave * 64 < block_tokens) bits[(block_first + t0) / 64 + wave] = word;
     }
     __shared__ int wave_counts[kWaves];
     if (lane == 0) wave_counts[wave] = edited_count;
@@ -157,9 +221,11 @@ scan_counts_kernel(int32_t* __restrict__ counts, int n_blocks, int32_t* __restri
 // SUMS = false: `offsets` holds the exclusive prefix sums of the per-block counts (scan_counts_kernel ran).
 // SUMS = true (few blocks): `offsets` holds the raw counts; every block adds up the counts of the blocks before it
 // itself, and the last block writes the total, which saves the scan kernel's launch.
-template <bool SUMS>
+// BITS = true: the decisions come as one bit per token (`bits`, written by score_bits_kernel) and the byte mask is
+// written here; BITS = false: they are read from the byte mask.  tok_per_block is a multiple of 64.
+template <bool SUMS, bool BITS>
 __global__ void __launch_bounds__(kThreads)
-write_index_kernel(const uint8_t* __restrict__ mask, const int32_t* __restrict__ offsets,
+write_index_kernel(const uint64_t* __restrict__ bits, uint8_t* __restrict__ mask, const int32_t* __restrict__ offsets,
                    int64_t n_tokens, int tok_per_block,
                    int32_t* __restrict__ e_index, int32_t* __restrict__ u_index,
                    int32_t* __restrict__ n_edited, int32_t* __restrict__ n_edited_pinned) {
@@ -181,43 +247,82 @@ write_index_kernel(const uint8_t* __restrict__ mask, const int32_t* __restrict__
             *n_edited = total;
             *n_edited_pinned = total;
         }
-        // (the first round below starts with a barrier, so wave_e can be reused)
     } else {
         base_e = offsets[blockIdx.x];   // edited tokens in all blocks before this one
     }
+    // The block's decisions as words of 64 tokens (read, or formed by ballot from the byte mask); their popcounts give
+    // every word its rank offset, after which the waves write their words' tokens without meeting again.
+    constexpr int kMaxWords = kMaxBlockTokens / 64;
+    __shared__ unsigned long long s_words[kMaxWords];
+    __shared__ int s_before[kMaxWords];
     const int64_t block_first = static_cast<int64_t>(blockIdx.x) * tok_per_block;
-    int64_t base_u = block_first - base_e;
-    for (int off = 0; off < tok_per_block; off += kThreads) {
-        const int64_t tok = block_first + off + threadIdx.x;
-        const bool live = (off + static_cast<int>(threadIdx.x)) < tok_per_block && tok < n_tokens;
-        const bool ed = live && mask[tok] != 0;
-        const unsigned long long bal = __ballot(ed);
-        const int rank_in_wave = __popcll(bal & ((1ull << lane) - 1ull));
-        __syncthreads();  // wave_e of the previous round has been read
-        if (lane == 0) wave_e[wave] = __popcll(bal);
-        __syncthreads();
-        int before = 0, total = 0;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) { if (w < wave) before += wave_e[w]; total += wave_e[w]; }
-        const int rank_e = before + rank_in_wave;                      // edited tokens before this one in the round
-        const int pos_in_round = static_cast<int>(threadIdx.x);
-        if (live) {
-            if (ed) e_index[base_e + rank_e] = static_cast<int32_t>(tok);
-            else u_index[base_u + (pos_in_round - rank_e)] = static_cast<int32_t>(tok);
+    int64_t left = n_tokens - block_first;
+    const int block_tokens = static_cast<int>(left < tok_per_block ? left : tok_per_block);
+    const int n_words = (block_tokens + 63) / 64;
+    __syncthreads();   // wave_e has been read by every wave
+    for (int w = wave; w < n_words; w += kWaves) {
+        unsigned long long word;
+        if (BITS) {
+            word = bits[block_first / 64 + w];      // bits of tokens past the end are clear
+        } else {
+            const int64_t tok = block_first + 64 * w + lane;
+            word = __ballot(tok < n_tokens && mask[tok] != 0);
         }
-        base_e += total;
-        base_u += kThreads - total;   // tail rounds past n_tokens write nothing, so over-counting there is harmless
+        if (lane == 0) s_words[w] = word;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int cnt = lane < n_words ? __popcll(s_words[lane]) : 0;
+        int incl = cnt;
+#pragma unroll
+        for (int d = 1; d < kMaxWords; d <<= 1) {
+            const int up = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += up;
+        }
+        if (lane < n_words) s_before[lane] = incl - cnt;
+    }
+    __syncthreads();
+    for (int w = wave; w < n_words; w += kWaves) {
+        const unsigned long long word = s_words[w];
+        const int64_t tok = block_first + 64 * w + lane;
+        const bool live = tok < n_tokens;
+        const bool ed = (word >> lane) & 1ull;
+        const int rank = __popcll(word & ((1ull << lane) - 1ull));
+        const int64_t e_at = static_cast<int64_t>(base_e) + s_before[w];          // edited tokens before this word
+        const int64_t u_at = block_first + 64 * w - e_at;                          // unedited tokens before it
+        if (live) {
+            if (BITS) mask[tok] = ed ? 1 : 0;
+            if (ed) e_index[e_at + rank] = static_cast<int32_t>(tok);
+            else u_index[u_at + (lane - rank)] = static_cast<int32_t>(tok);
+        }
     }
 }
 
 __global__ void set_i32_kernel(int32_t* p, int32_t* p_pinned, int32_t v) { *p = v; *p_pinned = v; }
 
+// Scratch memory of the partition's kernels: per-block edited counts and one decision bit per token.
+struct PartScratch {
+    int32_t* counts; int64_t counts_cap;      // one entry per block of >= 64 tokens
+    uint64_t* bits; int64_t words_cap;        // one word per 64 tokens
+};
+// Layout inside one int32 array that serves `max_tokens` tokens: counts, then the bit words (8-byte aligned).
+__host__ inline int64_t part_scratch_counts(int64_t max_tokens) { return ((max_tokens + 63) / 64 + 8 + 1) & ~int64_t{1}; }
+__host__ inline int64_t part_scratch_words(int64_t max_tokens) { return (max_tokens + 63) / 64 + 8; }
+__host__ inline PartScratch part_scratch_in(int32_t* base, int64_t max_tokens) {
+    PartScratch ps;
+    ps.counts = base; ps.counts_cap = part_scratch_counts(max_tokens);
+    ps.bits = reinterpret_cast<uint64_t*>(base + ps.counts_cap); ps.words_cap = part_scratch_words(max_tokens);
+    return ps;
+}
+
 template <typename T, int VEC>
-int launch_score(hipStream_t stream, int32_t* counts, int lpt, dim3 grid, const void* x_t, const void* v, const void* x_ref, int64_t n, int c,
-                 int tpb, float sigma, float eta, float* score, uint8_t* mask) {
+int launch_score(hipStream_t stream, const PartScratch& ps, int lpt, bool pipe, dim3 grid, const void* x_t, const void* v, const void* x_ref, int64_t n, int c,
+                 int tpb, float sigma, float eta, float* score) {
     const T* a = static_cast<const T*>(x_t); const T* b = static_cast<const T*>(v); const T* r = static_cast<const T*>(x_ref);
-#define RG_CASE(L) case L: hipLaunchKernelGGL((score_mask_kernel<T, VEC, L>), grid, dim3(kThreads), 0, stream, \
-        a, b, r, n, c, tpb, sigma, eta, score, mask, counts); break;
+#define RG_CASE(L) case L: \
+        if (VEC > 1 && pipe) hipLaunchKernelGGL((score_bits_kernel<T, VEC, L, (VEC > 1)>), grid, dim3(kThreads), 0, stream, a, b, r, n, c, tpb, sigma, eta, score, ps.bits, ps.counts); \
+        else hipLaunchKernelGGL((score_bits_kernel<T, VEC, L, false>), grid, dim3(kThreads), 0, stream, a, b, r, n, c, tpb, sigma, eta, score, ps.bits, ps.counts); \
+        break;
     switch (lpt) { RG_CASE(1) RG_CASE(2) RG_CASE(4) RG_CASE(8) RG_CASE(16) RG_CASE(32) RG_CASE(64)
         default: RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: bad lane group %d", lpt); }
 #undef RG_CASE
@@ -287,26 +392,26 @@ count_mask_kernel(const uint8_t* __restrict__ mask, int64_t n_tokens, int tok_pe
     }
 }
 
-// Index lists from the mask and the per-block counts in `counts`: few blocks -> one launch, else scan + lists.
-// n_edited_copy: a second place for the count (the context's pinned host word; n_edited_dev itself when there is none).
-int launch_index_lists(hipStream_t stream, int32_t* counts, dim3 grid, const uint8_t* mask, int64_t n_tokens, int tpb,
+// Index lists from the per-block counts in `counts` and the decisions (bits when given, else the byte mask): few blocks ->
+// one launch, else scan + lists.  n_edited_copy: a second place for the count (the context's pinned host word;
+// n_edited_dev itself when there is none).
+int launch_index_lists(hipStream_t stream, int32_t* counts, const uint64_t* bits, dim3 grid, uint8_t* mask, int64_t n_tokens, int tpb,
                        int32_t* e_index, int32_t* u_index, int32_t* n_edited_dev, int32_t* n_edited_copy) {
-    if (grid.x <= 1024) {
-        hipLaunchKernelGGL((write_index_kernel<true>), grid, dim3(kThreads), 0, stream,
-                           mask, counts, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy);
+    const bool sums = grid.x <= 1024;
+    if (!sums) {
+        hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, stream, counts, static_cast<int>(grid.x), n_edited_dev, n_edited_copy);
         RG_LAUNCH_CHECK();
-        return REGIONE_OK;
     }
-    hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, stream, counts, static_cast<int>(grid.x), n_edited_dev, n_edited_copy);
-    RG_LAUNCH_CHECK();
-    hipLaunchKernelGGL((write_index_kernel<false>), grid, dim3(kThreads), 0, stream,
-                       mask, counts, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy);
+#define RG_IDX(S, B) hipLaunchKernelGGL((write_index_kernel<S, B>), grid, dim3(kThreads), 0, stream, bits, mask, counts, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy)
+    if (sums) { if (bits) RG_IDX(true, true); else RG_IDX(true, false); }
+    else { if (bits) RG_IDX(false, true); else RG_IDX(false, false); }
+#undef RG_IDX
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
 }
 
-// The launches of the partition on `stream` with the per-block counts in `counts` (room for counts_cap entries).
-int partition_launches(hipStream_t stream, int32_t* counts, int64_t counts_cap, const void* x_t, const void* v, const void* x_ref,
+// The launches of the partition on `stream` with its scratch memory in `ps`.
+int partition_launches(hipStream_t stream, const PartScratch& ps, const void* x_t, const void* v, const void* x_ref,
                        int64_t n_tokens, int32_t c, int32_t dtype, float sigma_t, float eta, float* score_opt, uint8_t* mask,
                        int32_t* e_index, int32_t* u_index, int32_t* n_edited_dev, int32_t* n_edited_copy) {
     if (n_tokens == 0) {
@@ -319,24 +424,24 @@ int partition_launches(hipStream_t stream, int32_t* counts, int64_t counts_cap, 
     const int nchunks = c / vec;
     int lpt = 1;
     while (lpt * 2 <= nchunks && lpt < 64) lpt *= 2;
-    const int tok_per_pass = kWaves * (64 / lpt);
-    // small inputs: few passes per block so that one image still spreads over many CUs
-    int passes = 1;
-    while (passes < 32 && (n_tokens / (static_cast<int64_t>(tok_per_pass) * passes * 2)) >= 2048) passes *= 2;
-    const int tpb = tok_per_pass * passes;
+    const bool pipe = vec > 1 && nchunks == lpt;     // one chunk per lane: the pipelined form
+    // small inputs: 64 tokens per block so that one image still spreads over many CUs
+    int tpb = 64;
+    while (tpb < kMaxBlockTokens && n_tokens / (static_cast<int64_t>(tpb) * 2) >= 2048) tpb *= 2;
     const int64_t nblocks = (n_tokens + tpb - 1) / tpb;
-    if (nblocks > counts_cap) RG_FAIL(REGIONE_ERR_WORKSPACE, "partition: %lld blocks exceed the %lld the workspace holds", (long long)nblocks, (long long)counts_cap);
+    if (nblocks > ps.counts_cap || (n_tokens + 63) / 64 > ps.words_cap)
+        RG_FAIL(REGIONE_ERR_WORKSPACE, "partition: %lld tokens in %lld blocks exceed the workspace", (long long)n_tokens, (long long)nblocks);
     dim3 grid(static_cast<unsigned>(nblocks));
     int rc;
     if (dtype == REGIONE_BF16) {
-        rc = vec == 8 ? launch_score<bf16_t, 8>(stream, counts, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask)
-                      : launch_score<bf16_t, 1>(stream, counts, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask);
+        rc = vec == 8 ? launch_score<bf16_t, 8>(stream, ps, lpt, pipe, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt)
+                      : launch_score<bf16_t, 1>(stream, ps, lpt, pipe, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt);
     } else {
-        rc = vec == 4 ? launch_score<float, 4>(stream, counts, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask)
-                      : launch_score<float, 1>(stream, counts, lpt, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt, mask);
+        rc = vec == 4 ? launch_score<float, 4>(stream, ps, lpt, pipe, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt)
+                      : launch_score<float, 1>(stream, ps, lpt, pipe, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt);
     }
     if (rc != REGIONE_OK) return rc;
-    return launch_index_lists(stream, counts, grid, mask, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy);
+    return launch_index_lists(stream, ps.counts, ps.bits, grid, mask, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy);
 }
 
 int check_partition_args(const char* who, const void* x_t, const void* v, const void* x_ref, int64_t n_tokens, int32_t c, int32_t dtype,
@@ -362,7 +467,7 @@ extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* 
     if (n_tokens > ctx->dims.max_tokens) RG_FAIL(REGIONE_ERR_WORKSPACE, "partition: %lld tokens, context made for %d", (long long)n_tokens, ctx->dims.max_tokens);
     {
     ProfScope prof(ctx, REGIONE_PROF_PARTITION);
-    if (int rc = partition_launches(ctx->stream, ctx->part_counts, ctx->part_counts_cap, x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta,
+    if (int rc = partition_launches(ctx->stream, part_scratch_in(ctx->part_counts, ctx->dims.max_tokens), x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta,
                                     score_opt, mask, e_index, u_index, n_edited_dev, ctx->n_edited_pinned_dev)) return rc;
     }
     if (n_edited_host_opt) {   // the kernels wrote the count to pinned host memory too: no copy to wait for, only the stream
@@ -390,13 +495,13 @@ extern "C" int regione_mask_cleanup(regione_ctx* ctx, const uint8_t* mask_in, in
         if (!mask_in || !mask_out || !e_index || !u_index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "mask_cleanup: null tensor");
         const int tpb = kThreads;
         const int64_t nblocks = (n_tokens + tpb - 1) / tpb;
-        if (nblocks > ctx->part_counts_cap) RG_FAIL(REGIONE_ERR_WORKSPACE, "mask_cleanup: %lld blocks exceed the workspace", (long long)nblocks);
+        if (nblocks > part_scratch_counts(ctx->dims.max_tokens)) RG_FAIL(REGIONE_ERR_WORKSPACE, "mask_cleanup: %lld blocks exceed the workspace", (long long)nblocks);
         hipLaunchKernelGGL(morph_open_close_kernel, dim3(static_cast<unsigned>(n_images)), dim3(kMorphThreads), 0, ctx->stream, mask_in, mask_out, grid_h, grid_w);
         RG_LAUNCH_CHECK();
         const dim3 grid(static_cast<unsigned>(nblocks));
         hipLaunchKernelGGL(count_mask_kernel, grid, dim3(kThreads), 0, ctx->stream, mask_out, n_tokens, tpb, ctx->part_counts);
         RG_LAUNCH_CHECK();
-        if (int rc2 = launch_index_lists(ctx->stream, ctx->part_counts, grid, mask_out, n_tokens, tpb, e_index, u_index, n_edited_dev, ctx->n_edited_pinned_dev)) return rc2;
+        if (int rc2 = launch_index_lists(ctx->stream, ctx->part_counts, nullptr, grid, mask_out, n_tokens, tpb, e_index, u_index, n_edited_dev, ctx->n_edited_pinned_dev)) return rc2;
     }
     }
     if (n_edited_host_opt) {   // the kernels wrote the count to pinned host memory too: no copy to wait for, only the stream
@@ -409,13 +514,15 @@ extern "C" int regione_mask_cleanup(regione_ctx* ctx, const uint8_t* mask_in, in
 // ---- the partition for callers that cannot allocate device memory
 // Same kernels as regione_partition; the per-block counts live in a static device array instead of a context's
 // workspace.  Every GPU holds its own copy of the array at its own address, looked up once per device.
-#define RG_STATIC_COUNTS 65536                       /* int32 entries: 256 KiB per GPU, held until the process ends */
-static __device__ __align__(256) int32_t scratch[RG_STATIC_COUNTS];
+#define RG_STATIC_MAX_TOKENS (1 << 22)
+/* int32 entries: per-block counts (one per 64 tokens) and one decision bit per token, with the padding of
+   part_scratch_in: 768 KiB per GPU, held until the process ends */
+#define RG_STATIC_INTS ((RG_STATIC_MAX_TOKENS / 64 + 16) + 2 * (RG_STATIC_MAX_TOKENS / 64 + 8))
+static __device__ __align__(256) int32_t scratch[RG_STATIC_INTS];
 
 namespace {
 
-constexpr int64_t kStaticCounts = RG_STATIC_COUNTS;
-constexpr int64_t kStaticMaxTokens = int64_t{1} << 22;
+constexpr int64_t kStaticMaxTokens = RG_STATIC_MAX_TOKENS;
 constexpr int kMaxDevices = 64;
 
 int32_t* g_scratch_ptr[kMaxDevices];                 // device address of `scratch` on each device, null until looked up
@@ -440,6 +547,8 @@ int scratch_for_current_device(int32_t** out) {
 
 }  // namespace
 
+int64_t rg_partition_scratch_ints(int64_t max_tokens) { return part_scratch_counts(max_tokens) + 2 * part_scratch_words(max_tokens); }
+
 int rg_partition_static_warm(void) {
     int32_t* p = nullptr;
     return scratch_for_current_device(&p);
@@ -455,8 +564,10 @@ extern "C" int regione_partition_static(void* hip_stream, const void* x_t, const
                 (long long)n_tokens, (long long)kStaticMaxTokens);
     int32_t* counts = nullptr;
     if (int rc = scratch_for_current_device(&counts)) return rc;
-    // Nothing in the array has to start at zero: the score kernel writes the count of every block of this call before
-    // the index kernels read them, and entries past the call's block count are never read.
-    return partition_launches(static_cast<hipStream_t>(hip_stream), counts, kStaticCounts, x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta,
+    // Nothing in the array has to start at zero: the score kernel writes the count of every block and the bit word of
+    // every 64 tokens of this call before the index kernels read them, and nothing past them is ever read.
+    const PartScratch ps = part_scratch_in(counts, kStaticMaxTokens);
+    if (ps.counts_cap + 2 * ps.words_cap > RG_STATIC_INTS) RG_FAIL(REGIONE_ERR_WORKSPACE, "partition_static: the static array is smaller than its layout");
+    return partition_launches(static_cast<hipStream_t>(hip_stream), ps, x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta,
                               score_opt, mask, e_index, u_index, n_edited_dev, n_edited_dev);
 }
