@@ -20,10 +20,20 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-# L2 <-> fabric bytes of the GEMM launches of one step of the default workload (820 edited tokens), from two
-# rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): see
-# profiles/gemm_attention_hbm_traffic.txt.  Per launch = per step / 5 launches, like `achieved`.
-MEASURED_GEMM_TRAFFIC_BYTES_PER_STEP = {820: 785.0e6}
+
+
+def profiled_traffic():
+    """HBM-side bytes per launch from the committed rocprofv3 counter summaries (FETCH_SIZE / WRITE_SIZE runs, scaled by
+    what the same counters read for a plain copy of known size): the lines `traffic_bytes_per_launch <key> <bytes>` of
+    profiles/*_hbm_traffic.txt.  A key that no summary carries reads as None."""
+    import glob
+    table = {}
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*_hbm_traffic.txt"))):
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch":
+                table[parts[1]] = float(parts[2])
+    return table
 
 
 def cpu_baseline(cfg, hst, reps, gpu=None):
@@ -46,11 +56,22 @@ def cpu_baseline(cfg, hst, reps, gpu=None):
            "sample": f"the whole workload ({n} edited tokens), {reps} step(s) of the numpy float64 oracle, {dt:.2f} s per step"}
     if gpu is not None:
         import numpy as np
-        diff = np.abs(gpu["h_e_out"][:n].astype(np.float64) - out["h_e_out"])
+        want = out["h_e_out"]
+        diff = np.abs(gpu["h_e_out"][:n].astype(np.float64) - want)
+        half_ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 2.0 ** -126))) - 8)     # what bf16 storage of the output can add
         res["parity"] = {"mask_equal": bool(np.array_equal(gpu["mask"], out["mask"])),
                          "index_lists_equal": bool(np.array_equal(gpu["e_index"][:n], out["e_index"])),
-                         "block_out_max_abs": float(diff.max()), "block_out_mean_rel": float(diff.mean() / np.abs(out["h_e_out"]).mean()),
+                         "stated_tolerance": {"max_abs": 2e-2, "mean_rel": 5e-3},
+                         "block_out_max_abs": float(diff.max()), "block_out_mean_rel": float(diff.mean() / np.abs(want).mean()),
+                         "block_out_elements": int(diff.size),
+                         "block_out_over_2e-2": int((diff > 2e-2).sum()), "block_out_over_2e-2_frac": float((diff > 2e-2).mean()),
+                         "block_out_over_2e-2_plus_bf16_half_ulp": int((diff > 2e-2 + half_ulp).sum()),
                          "merged_latent_max_abs": float(np.abs(gpu["x_next"].astype(np.float64) - out["x_next"]).max())}
+        if gpu.get("h_e_out_f32") is not None:   # the same block with a float32 residual stream: no storage rounding in the way
+            d32 = np.abs(gpu["h_e_out_f32"].astype(np.float64) - want)
+            res["parity"]["f32_residual"] = {"block_out_max_abs": float(d32.max()), "block_out_mean_rel": float(d32.mean() / np.abs(want).mean()),
+                                             "block_out_rms": float(np.sqrt((d32 ** 2).mean())),
+                                             "block_out_over_2e-2": int((d32 > 2e-2).sum()), "block_out_over_2e-2_frac": float((d32 > 2e-2).mean())}
     return res
 
 
@@ -530,7 +551,8 @@ def main():
         "metric": "edited-token DiT block tokens/s", "value": n / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": cfg.name, "n_edited": n, "keys_per_query": wl.n_all},
+        "config": {"workload": cfg.name, "n_edited": n, "keys_per_query": wl.n_all,
+                   "note": "every step includes one stream synchronisation (the edited-token count read back after the partition)"},
     }
     if not args.no_profile:
         # timed region 2: the same K steps with a HIP event pair around every kernel launch group, recorded by the library
@@ -549,14 +571,18 @@ def main():
         g_ms = prof["gemm"][0] / args.steps
         a_ms = prof["attention"][0] / args.steps
         ach = gemm_flops / (g_ms * 1e-3) / 1e12
+        traffic = profiled_traffic() if n == 820 else {}     # the committed counter summaries were taken on the default workload
         out["roofline"] = {"kernel": "gemm_bf16_kernel (5 launches per step: QKV, attention output, MLP up, MLP down, velocity head)",
                            "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                           "traffic": (MEASURED_GEMM_TRAFFIC_BYTES_PER_STEP[n] / 5 if n in MEASURED_GEMM_TRAFFIC_BYTES_PER_STEP else None),
-                           "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE at the L2-fabric boundary)",
+                           "traffic": traffic.get("gemm_bf16_kernel"),
+                           "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE at the L2-fabric boundary, from profiles/*_hbm_traffic.txt)",
                            "algorithmic_flops_per_launch": gemm_flops / 5, "avg_launch_ms": prof["gemm"][0] / max(prof["gemm"][1], 1),
                            "measured_in": f"a second timed region of the same {args.steps} steps with HIP event pairs ({ms_profiled:.4f} ms per step there)"}
         out["attention"] = {"achieved": attn_flops / (a_ms * 1e-3) / 1e12, "unit": "TFLOP/s",
                             "frac": attn_flops / (a_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "ms_per_step": a_ms}
+        out["roofline"]["others"] = [{"kernel": "attn_kvcache_kernel + attn_combine_kernel (regione_attn_kvcache inside the block)", "bound": "mfma",
+                                      "achieved": out["attention"]["achieved"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": out["attention"]["frac"],
+                                      "avg_launch_ms": a_ms, "algorithmic_flops_per_launch": attn_flops, "traffic": traffic.get("attn_kvcache_kernel")}]
         out["gemm_plus_attention_tflops"] = (gemm_flops + attn_flops) / ((g_ms + a_ms) * 1e-3) / 1e12
         out["kernels"] = kernels
     host = wl.host
@@ -564,6 +590,13 @@ def main():
     if not args.no_cpu_baseline:   # what the step left on the device, for the parity figures beside the oracle's time
         gpu_out = {"mask": wl.mask.cpu().numpy(), "e_index": wl.e_index.cpu().numpy(), "h_e_out": wl.h_e_out.float().cpu().numpy(),
                    "x_next": wl.x_next.float().cpu().numpy()}
+        # the same block once more with a float32 residual stream (input and output rows float32), outside every timed region
+        h32 = wl.h_e[:n].float().contiguous()
+        o32 = torch.empty_like(h32)
+        rg.regione_block_forward(wl.ctx, wl.weights, wl.block_type, h32, o32, rg.FP32, n, 0, wl.e_index, cfg.n_txt, wl.k_cache, wl.v_cache,
+                                 wl.n_all, rg.FLAG_RETRIEVE)
+        gpu_out["h_e_out_f32"] = o32.cpu().numpy()
+        del h32, o32
     wl.close()
     del wl
     torch.cuda.empty_cache()
@@ -590,6 +623,20 @@ def main():
         out["fp8_projections_all_rows"] = fp8_projections(torch, rg, int(out["config"]["keys_per_query"]), reps=5)
     if not args.no_membound:
         out["membound"] = membound(torch, rg)
+        if "roofline" in out:    # one entry per HBM-bound kernel of the path, on the multi-GiB working sets stated in `membound`
+            traffic = profiled_traffic()
+            names = {"partition": "score_bits_kernel + scan_counts_kernel + write_index_kernel (regione_partition with the score output)",
+                     "partition_no_score": "score_bits_kernel + scan_counts_kernel + write_index_kernel (regione_partition)",
+                     "gather_latent": "rows_by_index_kernel (regione_gather, 128-byte rows)", "scatter_latent": "rows_by_index_kernel (regione_scatter, 128-byte rows)",
+                     "gather_hidden": "rows_by_index_kernel (regione_gather, 6 KiB rows)", "scatter_hidden": "rows_by_index_kernel (regione_scatter, 6 KiB rows)",
+                     "velocity_cache_fresh": "velocity_cache_vec_kernel (regione_velocity_cache, fresh step)",
+                     "velocity_cache_reuse": "velocity_cache_vec_kernel (regione_velocity_cache, reusing step)"}
+            for key, kname in names.items():
+                m = out["membound"].get(key)
+                if m:
+                    out["roofline"]["others"].append({"kernel": kname, "bound": "hbm", "achieved": m["GB/s"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                                      "frac": m["frac_hbm"], "avg_launch_ms": m["ms"], "algorithmic_bytes_per_launch": m["GB/s"] * m["ms"] * 1e6,
+                                                      "traffic": traffic.get("membound_" + key)})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, host, reps=6, gpu=gpu_out)
     print(json.dumps(out))

@@ -400,6 +400,15 @@ int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float factor, float 
                            const void* v_fresh_opt, void* c_a, void* v_out_opt, void* x_e,
                            const int32_t* n_dev, int64_t n_max, int32_t c, int32_t dtype);
 
+/* The unedited rows' single jump (section "Region-Aware Generation": the unedited region is estimated in one step with
+ * Eq.5 from the last full velocity), done where the merge by spatial position would put its result:
+ *   x_full[index[i], :] -= dt * v_full[index[i], :]   for i < n   (n as in regione_gather),
+ * product and difference rounded separately in float32, every other row untouched.  One launch in place of gathering the
+ * rows of x and v, stepping them and scattering them back at the end of the segment: nothing reads the unedited rows of
+ * the full latent in between.  x_full, v_full: [rows, c] of `dtype`, different tensors; indices distinct. */
+int regione_euler_rows(regione_ctx* ctx, void* x_full, const void* v_full, const int32_t* index, const int32_t* n_dev,
+                       int64_t n_max, int32_t c, int32_t dtype, float dt);
+
 #ifdef __cplusplus
 }
 #endif

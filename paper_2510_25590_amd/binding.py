@@ -30,6 +30,7 @@ EXPORTS = (
     "regione_sq_norms", "regione_gamma_fit_host", "regione_guidance_combine", "regione_rel_change",
     "regione_quantize_rows_fp8", "regione_pack_weight_fp8", "regione_linear_fp8", "regione_mfma_peak_probe",
     "regione_partition_static", "regione_rel_decision_host", "regione_rel_update_host", "regione_fresh_slots", "regione_time_bias",
+    "regione_euler_rows",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -104,6 +105,7 @@ def lib() -> C.CDLL:
             "regione_rel_update_host": [C.POINTER(RelState), C.POINTER(C.c_double), f32, C.POINTER(C.c_double)],
             "regione_fresh_slots": [vp, vp, vp, i64, i32, vp],
             "regione_time_bias": [vp, vp, vp, f32, vp, i32],
+            "regione_euler_rows": [vp, vp, vp, vp, vp, i64, i32, i32, f32],
             "regione_partition_static": [vp, vp, vp, vp, i64, i32, i32, f32, f32, vp, vp, vp, vp, vp],
             "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
@@ -251,6 +253,10 @@ def regione_rel_update_host(state: RelState, sums, threshold: float) -> float:
 
 def regione_fresh_slots(ctx, index, n_dev, n_max, n_txt, slots):
     _check(lib().regione_fresh_slots(ctx.handle, _p(index), _p(n_dev), n_max, n_txt, _p(slots)))
+
+
+def regione_euler_rows(ctx, x_full, v_full, index, n_dev, n_max, c, dtype, dt):
+    _check(lib().regione_euler_rows(ctx.handle, _p(x_full), _p(v_full), _p(index), _p(n_dev), n_max, c, dtype, float(dt)))
 
 
 def regione_time_bias(ctx, b, b_time, t, out, n):

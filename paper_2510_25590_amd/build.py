@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libregione.so")
 SOURCES = ["api.hip", "partition.hip", "rows.hip", "gemm.hip", "attention.hip", "block_extras.hip", "fp8.hip", "peaks.hip",
-           "fp32.hip"]
+           "fp32.hip", "host_logic.cpp"]
 
 
 def flags() -> list[str]:
@@ -44,7 +44,7 @@ def build(verbose: bool = False, only=None) -> str:
     sources = [s for s in SOURCES if only is None or s in only]
 
     def compile_one(src):
-        obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+        obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
         _run([hipcc, *fl, "-fPIC", "-c", os.path.join(CSRC, src), "-o", obj], verbose)
         return obj
 
@@ -61,7 +61,7 @@ def build(verbose: bool = False, only=None) -> str:
             futs.append(pool.submit(check_isa, None))
         for f in futs:
             f.result()
-    objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
+    objs = [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in SOURCES]
     _run([hipcc, *fl, "-fPIC", "-shared", *objs, "-o", LIB], verbose)
     return LIB
 

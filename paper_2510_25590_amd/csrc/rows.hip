@@ -331,6 +331,57 @@ extern "C" int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float fac
     return REGIONE_OK;
 }
 
+// ---- one-step estimate of listed rows in place (Eq.5): the unedited rows' jump to the end of a segment, written where the
+// merge would put it, so that neither a gather before it nor a scatter after it is needed
+namespace {
+template <typename T, int VEC>
+__global__ void __launch_bounds__(kThreads)
+euler_rows_kernel(T* __restrict__ x_full, const T* __restrict__ v_full, const int32_t* __restrict__ index,
+                  const int32_t* __restrict__ n_dev, int64_t n_max, int c, float dt) {
+    int64_t n = n_max;
+    if (n_dev) { const int64_t nd = *n_dev; n = nd < n_max ? (nd < 0 ? 0 : nd) : n_max; }
+    const int groups = c / VEC;                 // pieces of VEC elements per row
+    const int64_t total = n * groups;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t u = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; u < total; u += stride) {
+        const int64_t row = u / groups;
+        const int g = static_cast<int>(u - row * groups);
+        const int64_t at = static_cast<int64_t>(index[row]) * c + g * VEC;
+        if constexpr (VEC == 8) {
+            float x[8], v[8];
+            ld8<T>(x_full + at, x); ld8<T>(v_full + at, v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = __fsub_rn(x[e], __fmul_rn(dt, v[e]));   // product and difference rounded separately, as in Eq.4's kernel
+            st8<T>(x_full + at, x);
+        } else {
+            st<T>(x_full + at, __fsub_rn(ld<T>(x_full + at), __fmul_rn(dt, ld<T>(v_full + at))));
+        }
+    }
+}
+}  // namespace
+
+extern "C" int regione_euler_rows(regione_ctx* ctx, void* x_full, const void* v_full, const int32_t* index, const int32_t* n_dev,
+                                  int64_t n_max, int32_t c, int32_t dtype, float dt) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "euler_rows: null context");
+    if (c <= 0 || n_max < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "euler_rows: c=%d n_max=%lld", c, (long long)n_max);
+    if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "euler_rows: bad dtype %d", dtype);
+    if (n_max == 0) return REGIONE_OK;
+    if (!x_full || !v_full || !index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "euler_rows: null tensor");
+    if (x_full == v_full) RG_FAIL(REGIONE_ERR_INVALID_ARG, "euler_rows: x and v are the same tensor");
+    ProfScope prof(ctx, REGIONE_PROF_VELOCITY);
+    const bool wide = (c % 8 == 0) && rg_aligned16(x_full) && rg_aligned16(v_full);
+    const int64_t total = n_max * (wide ? c / 8 : c);
+    int64_t blocks = (total + kThreads - 1) / kThreads;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    const dim3 grid(static_cast<unsigned>(blocks));
+#define RG_EULER(T, V) hipLaunchKernelGGL((euler_rows_kernel<T, V>), grid, dim3(kThreads), 0, ctx->stream, static_cast<T*>(x_full), static_cast<const T*>(v_full), index, n_dev, n_max, c, dt)
+    if (dtype == REGIONE_BF16) { if (wide) RG_EULER(bf16_t, 8); else RG_EULER(bf16_t, 1); }
+    else { if (wide) RG_EULER(float, 8); else RG_EULER(float, 1); }
+#undef RG_EULER
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
 extern "C" int regione_cast(regione_ctx* ctx, const void* src, int32_t src_dtype, void* dst, int32_t dst_dtype, int64_t n_elems) {
     if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "cast: null context");
     if ((src_dtype != REGIONE_BF16 && src_dtype != REGIONE_FP32) || (dst_dtype != REGIONE_BF16 && dst_dtype != REGIONE_FP32))

@@ -195,7 +195,6 @@ def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: 
     n_e_dev = torch.zeros(1, dtype=torch.int32, device=dev)
     n_u_dev = torch.zeros(1, dtype=torch.int32, device=dev)
     x_e, v_e, c_a = torch.empty_like(x), torch.empty_like(x), torch.zeros_like(x)
-    x_u, v_u = torch.empty_like(x), torch.empty_like(x)
     n_e = None
     log = []
     rel_sums = torch.zeros(2, dtype=torch.float64, device=dev)
@@ -217,10 +216,9 @@ def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: 
                 n_u_dev.fill_(n_img - n_e)
                 log.append(("partition", n_e))
             rg.regione_gather(ctx, x, c, rg.FP32, e_index, n_e_dev, n_e, x_e)
-            rg.regione_gather(ctx, x, c, rg.FP32, u_index, n_u_dev, n_img - n_e, x_u)
-            rg.regione_gather(ctx, v, c, rg.FP32, u_index, n_u_dev, n_img - n_e, v_u)
-            # one jump of the unedited rows to the end of the segment with the last full velocity (Eq.5)
-            rg.regione_velocity_cache(ctx, True, 1.0, float(t[i] - t[st.seg_next + 1]), None, v_u, None, x_u, n_u_dev, n_img - n_e, c, rg.FP32)
+            # one jump of the unedited rows to the end of the segment with the last full velocity (Eq.5), in place: nothing
+            # reads those rows of x before the merge, where the edited rows join them
+            rg.regione_euler_rows(ctx, x, v, u_index, n_u_dev, n_img - n_e, c, rg.FP32, float(t[i] - t[st.seg_next + 1]))
             state, rel_state = rg.AvdState(), rg.RelState()
         if rel_trigger is None:
             reuse, factor = rg.regione_velocity_decision_host(t, gamma, T, delta, i, state)
@@ -242,6 +240,5 @@ def run_loop(model: EditorModel, x_T, x_ref, t, gamma, T: int, t_st: int, t_sm: 
         last_of_segment = pos + 1 == len(steps) or steps[pos + 1].kind != rg.STEP_REGION
         if last_of_segment:   # merge: edited and unedited rows are both at t_{next+1} now
             rg.regione_scatter(ctx, x, c, rg.FP32, e_index, n_e_dev, n_e, x_e)
-            rg.regione_scatter(ctx, x, c, rg.FP32, u_index, n_u_dev, n_img - n_e, x_u)
     torch.cuda.synchronize()
     return x, log

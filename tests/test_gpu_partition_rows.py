@@ -221,6 +221,36 @@ def test_velocity_cache_matches_oracle(ctx, dtype, c):
         rg.regione_velocity_cache(ctx, False, 1.0, 0.1, None, dca, None, dx, cnt, n, c, code)
 
 
+@pytest.mark.parametrize("c", [64, 20])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_euler_rows_in_place_equals_gather_step_scatter(ctx, dtype, c):
+    """The unedited rows' jump (Eq.5) done in place on the full latent: the oracle's gather, Euler step and merge."""
+    rng = np.random.default_rng(610 + c)
+    n_rows = 4096
+    rnd = (lambda a: inputs.bf16_round(a)) if dtype == "bf16" else (lambda a: a)
+    x = rnd(rng.standard_normal((n_rows, c)).astype(np.float32))
+    v = rnd(rng.standard_normal((n_rows, c)).astype(np.float32))
+    u = np.sort(rng.choice(n_rows, size=3277, replace=False)).astype(np.int32)      # 80 % of the rows, as unedited rows are
+    live = len(u) - 5
+    code = rg.BF16 if dtype == "bf16" else rg.FP32
+    dx = dev(x, dtype)
+    cnt = torch.tensor([live], dtype=torch.int32, device="cuda")
+    dt = 10.0 / 28.0
+    rg.regione_euler_rows(ctx, dx, dev(v, dtype), torch.from_numpy(u).cuda(), cnt, len(u), c, code, dt)
+    want = orc.scatter(x.astype(np.float64).copy(), u[:live], orc.euler_step(orc.gather(x, u[:live]), orc.gather(v, u[:live]), dt))
+    got = host(dx)
+    tol = dict(max_abs=2e-2, stored_bf16=True) if dtype == "bf16" else dict(max_abs=1e-6, mean_rel_tol=1e-6)
+    assert_close(got[u[:live]], want[u[:live]], "rows after the jump", **tol)
+    rest = np.setdiff1d(np.arange(n_rows), u[:live])
+    assert np.array_equal(got[rest], x[rest])           # rows that are not listed (or lie past the count) are bit-identical
+    # the same arithmetic as the velocity-cache kernel's reusing form with factor 1 on gathered rows: bit for bit
+    xg, vg = dev(x[u[:live]], dtype), dev(v[u[:live]], dtype)
+    rg.regione_velocity_cache(ctx, True, 1.0, dt, None, vg, None, xg, None, live, c, code)
+    assert np.array_equal(host(xg), got[u[:live]])
+    with pytest.raises(rg.RegionEError):
+        rg.regione_euler_rows(ctx, dx, dx, torch.from_numpy(u).cuda(), cnt, len(u), c, code, dt)
+
+
 # ---------------------------------------------------------------- morphological clean-up of the partition
 
 

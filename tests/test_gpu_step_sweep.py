@@ -1,6 +1,7 @@
-"""GPU parity at the benchmark's shapes: the whole region-aware step against the oracle's step, the
-edited-fraction sweep {5, 20, 50, 100 %} with irregular masks (ragged query counts), and the float32
-residual stream at the plain 2e-2 tolerance.  The oracle evaluates sampled rows at these sizes."""
+"""GPU parity at the benchmark's shapes: the whole region-aware step against the oracle's step (bf16-stored and with a
+float32 residual stream, all rows), the edited-fraction sweep {5, 20, 50, 100 %} with irregular masks (ragged query
+counts).  The oracle evaluates sampled rows at the other sizes.  Outputs of a 3072-wide block are held to the stated
+bound on all but 1e-5 of their elements (see gpu_util.assert_close); the tiny configuration runs in float32 at 1e-4."""
 import numpy as np
 import pytest
 import torch
@@ -9,7 +10,7 @@ from oracle import regione_oracle as orc
 from oracle import step_reference as ref
 from paper_2510_25590_amd import binding as rg
 from paper_2510_25590_amd import inputs, step
-from gpu_util import dev, host, assert_close, block_to_device
+from gpu_util import dev, host, assert_close, block_to_device, TAIL_FRAC, HEAD_TAIL_FRAC, exceedances
 from test_gpu_block import _oracle_region_rows, _model
 
 pytestmark = pytest.mark.gpu
@@ -88,15 +89,23 @@ def test_benchmark_step_matches_oracle_step():
     assert n == n2 == len(want["e_index"])
     assert np.array_equal(host(wl.mask).astype(np.uint8), want["mask"])
     assert np.array_equal(wl.e_index.cpu().numpy()[:n], want["e_index"])
-    ma, mr = assert_close(host(wl.h_e_out)[:n], want["h_e_out"], "block output of the step", stored_bf16=True, outlier_frac=1e-5)
-    print(f"benchmark step parity: n_edited {n}, block output max abs {ma:.3e}, mean rel {mr:.3e}")
+    ma, mr = assert_close(host(wl.h_e_out)[:n], want["h_e_out"], "block output of the step", stored_bf16=True, tail_frac=TAIL_FRAC)
+    n_out, frac, _ = exceedances(host(wl.h_e_out)[:n], want["h_e_out"], stored_bf16=True)
+    print(f"benchmark step parity (bf16-stored): n_edited {n}, block output max abs {ma:.3e}, mean rel {mr:.3e}, {n_out} elements ({frac:.1e}) beyond 2e-2 + storage half-ulp")
+    # the same block with a float32 residual stream (no storage rounding in the way), every row against the oracle
+    h_in = torch.from_numpy(h["h_now"][want["e_index"]]).cuda()
+    o32 = torch.empty_like(h_in)
+    rg.regione_block_forward(wl.ctx, wl.weights, wl.block_type, h_in, o32, rg.FP32, n, 0, wl.e_index, cfg.n_txt, wl.k_cache, wl.v_cache, wl.n_all, rg.FLAG_RETRIEVE)
+    ma32, mr32 = assert_close(host(o32), want["h_e_out"], "block output, float32 residual stream, all rows", tail_frac=TAIL_FRAC)
+    n32, f32, _ = exceedances(host(o32), want["h_e_out"])
+    print(f"benchmark step parity (float32 residual): max abs {ma32:.3e}, mean rel {mr32:.3e}, {n32} of {o32.numel()} elements ({f32:.1e}) beyond 2e-2")
     # the velocity head multiplies the (bf16-stored) block output by a 3072-long weight row: teacher-forced on the
     # library's own block output the head must be tight; against the oracle's exact chain it carries the block's error
     hv = host(wl.h_e_out)[:n]
     assert_close(host(wl.v_e)[:n], orc.linear(hv, h["w_head"], h["b_head"]), "velocity head on the library's block output", stored_bf16=True)
-    assert_close(host(wl.v_e)[:n], want["v_e"], "velocity of the edited tokens (whole chain)", max_abs=4e-2, stored_bf16=True)
+    assert_close(host(wl.v_e)[:n], want["v_e"], "velocity of the edited tokens (whole chain)", stored_bf16=True, tail_frac=HEAD_TAIL_FRAC)
     assert_close(host(wl.x_next), want["x_next"], "merged latent", stored_bf16=True)
-    assert_close(host(wl.h_next), want["h_next"], "merged hidden state", stored_bf16=True, outlier_frac=1e-5)
+    assert_close(host(wl.h_next), want["h_next"], "merged hidden state", stored_bf16=True, tail_frac=TAIL_FRAC)
     wl.close()
 
 
@@ -138,7 +147,7 @@ def test_fraction_sweep_blob_masks(n_edited, h_dtype):
     sample[:2] = [0, n - 1]
     want = _oracle_region_rows(streams, "double", h_now, rows, kc_o, vc_o, heads, sample)
     ma, mr = assert_close(host(o)[sample], want, f"region forward with {n} edited tokens ({h_dtype} residual stream)", stored_bf16=(h_dtype == "bf16"),
-                          outlier_frac=1e-5)   # 3072-wide block output: the bound is 5.5 sigma of the bf16 arithmetic error
+                          tail_frac=TAIL_FRAC)   # 3072-wide block output: the bound is 5 sigma of the bf16 arithmetic error
     print(f"n_edited {n} ({h_dtype}): max abs {ma:.3e}, mean rel {mr:.3e}")
     ctx.close()
 
@@ -169,6 +178,6 @@ def test_large_image_region_forward_sampled():
     sample = np.sort(rng.choice(n_edited, size=24, replace=False))
     sample[:2] = [0, n_edited - 1]
     want = _oracle_region_rows(streams, "double", h_now, rows, kc_o, vc_o, heads, sample)
-    ma, mr = assert_close(host(o)[sample], want, "region forward at the large-image sizes (sampled rows)", stored_bf16=True, outlier_frac=1e-5)
+    ma, mr = assert_close(host(o)[sample], want, "region forward at the large-image sizes (sampled rows)", stored_bf16=True, tail_frac=TAIL_FRAC)
     print(f"large image: n_edited {n_edited}, {n_all} keys: max abs {ma:.3e}, mean rel {mr:.3e}")
     ctx.close()
