@@ -400,6 +400,27 @@ int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float factor, float 
                            const void* v_fresh_opt, void* c_a, void* v_out_opt, void* x_e,
                            const int32_t* n_dev, int64_t n_max, int32_t c, int32_t dtype);
 
+/* regione_gather / regione_scatter for two tensors that share the index list, in one launch: the hidden rows and the
+ * latent rows of the edited tokens (Algorithm 1 gathers both at the start of a region step and merges both at its end).
+ * Arguments as in regione_gather / regione_scatter, once per tensor. */
+int regione_gather_pair(regione_ctx* ctx, const void* src_a, int32_t row_elems_a, int32_t dtype_a, void* dst_a,
+                        const void* src_b, int32_t row_elems_b, int32_t dtype_b, void* dst_b,
+                        const int32_t* index, const int32_t* n_dev, int64_t n_max);
+int regione_scatter_pair(regione_ctx* ctx, void* dst_full_a, int32_t row_elems_a, int32_t dtype_a, const void* src_a,
+                         void* dst_full_b, int32_t row_elems_b, int32_t dtype_b, const void* src_b,
+                         const int32_t* index, const int32_t* n_dev, int64_t n_max);
+
+/* The velocity head of a fresh region step together with what Algorithm 1 does with its result, in two launches
+ * instead of four: v = h_rows W^T + b (regione_linear), rounded to `dtype`; the velocity cache takes it and the edited
+ * rows take their Euler step (regione_velocity_cache with reuse = 0: c_a = v, x_e -= dt * v, Eq.9 and Eq.4); and the
+ * updated rows are written to x_full[index[i], :] (regione_scatter) when x_full_opt is given.  Results are those of the
+ * three calls bit for bit.
+ *   h_rows [n, hidden] bf16 (float32 in a float32 context), w_head_packed from [c, hidden], b_head_opt [c] float32,
+ *   v_out_opt / c_a / x_e [n, c] and x_full_opt [rows, c] of `dtype`; n is a host count; hidden a multiple of 64. */
+int regione_velocity_head(regione_ctx* ctx, const void* h_rows, const void* w_head_packed, const float* b_head_opt,
+                          int32_t n, int32_t c, int32_t hidden, float dt, void* v_out_opt, void* c_a, void* x_e,
+                          void* x_full_opt, const int32_t* index_opt, int32_t dtype);
+
 /* The unedited rows' single jump (section "Region-Aware Generation": the unedited region is estimated in one step with
  * Eq.5 from the last full velocity), done where the merge by spatial position would put its result:
  *   x_full[index[i], :] -= dt * v_full[index[i], :]   for i < n   (n as in regione_gather),

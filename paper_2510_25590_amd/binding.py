@@ -30,7 +30,7 @@ EXPORTS = (
     "regione_sq_norms", "regione_gamma_fit_host", "regione_guidance_combine", "regione_rel_change",
     "regione_quantize_rows_fp8", "regione_pack_weight_fp8", "regione_linear_fp8", "regione_mfma_peak_probe",
     "regione_partition_static", "regione_rel_decision_host", "regione_rel_update_host", "regione_fresh_slots", "regione_time_bias",
-    "regione_euler_rows",
+    "regione_euler_rows", "regione_gather_pair", "regione_scatter_pair", "regione_velocity_head",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -106,6 +106,9 @@ def lib() -> C.CDLL:
             "regione_fresh_slots": [vp, vp, vp, i64, i32, vp],
             "regione_time_bias": [vp, vp, vp, f32, vp, i32],
             "regione_euler_rows": [vp, vp, vp, vp, vp, i64, i32, i32, f32],
+            "regione_gather_pair": [vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, i64],
+            "regione_scatter_pair": [vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, i64],
+            "regione_velocity_head": [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, i32],
             "regione_partition_static": [vp, vp, vp, vp, i64, i32, i32, f32, f32, vp, vp, vp, vp, vp],
             "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
@@ -253,6 +256,21 @@ def regione_rel_update_host(state: RelState, sums, threshold: float) -> float:
 
 def regione_fresh_slots(ctx, index, n_dev, n_max, n_txt, slots):
     _check(lib().regione_fresh_slots(ctx.handle, _p(index), _p(n_dev), n_max, n_txt, _p(slots)))
+
+
+def regione_gather_pair(ctx, src_a, row_elems_a, dtype_a, dst_a, src_b, row_elems_b, dtype_b, dst_b, index, n_dev, n_max):
+    _check(lib().regione_gather_pair(ctx.handle, _p(src_a), row_elems_a, dtype_a, _p(dst_a), _p(src_b), row_elems_b, dtype_b, _p(dst_b),
+                                     _p(index), _p(n_dev), n_max))
+
+
+def regione_scatter_pair(ctx, dst_full_a, row_elems_a, dtype_a, src_a, dst_full_b, row_elems_b, dtype_b, src_b, index, n_dev, n_max):
+    _check(lib().regione_scatter_pair(ctx.handle, _p(dst_full_a), row_elems_a, dtype_a, _p(src_a), _p(dst_full_b), row_elems_b, dtype_b, _p(src_b),
+                                      _p(index), _p(n_dev), n_max))
+
+
+def regione_velocity_head(ctx, h_rows, w_head, b_head, n, c, hidden, dt, v_out, c_a, x_e, x_full, index, dtype):
+    _check(lib().regione_velocity_head(ctx.handle, _p(h_rows), _p(w_head), _p(b_head), n, c, hidden, float(dt), _p(v_out), _p(c_a), _p(x_e),
+                                       _p(x_full), _p(index), dtype))
 
 
 def regione_euler_rows(ctx, x_full, v_full, index, n_dev, n_max, c, dtype, dt):

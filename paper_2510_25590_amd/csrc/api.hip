@@ -127,6 +127,32 @@ extern "C" int regione_layernorm(regione_ctx* ctx, const void* h, int32_t h_dtyp
     return rg_layernorm_mod(ctx, h, h_dtype == REGIONE_FP32, n, hidden, shift_opt, scale_opt, u);
 }
 
+// Velocity head of the step, fused with what follows it in a fresh region step: v = h W^T + b in the storage type, the
+// velocity cache takes v (Eq.9, fresh branch), x_e <- x_e - dt v (Eq.4), and the updated rows are written to their
+// positions in the full latent (the merge).  One GEMM launch and one merge launch in bf16 contexts.
+extern "C" int regione_velocity_head(regione_ctx* ctx, const void* h_rows, const void* w_head_packed, const float* b_head_opt,
+                                     int32_t n, int32_t c, int32_t hidden, float dt, void* v_out_opt, void* c_a, void* x_e,
+                                     void* x_full_opt, const int32_t* index_opt, int32_t dtype) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_head: null context");
+    if (n < 0 || c <= 0 || hidden <= 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_head: n=%d c=%d hidden=%d", n, c, hidden);
+    if (dtype != REGIONE_BF16 && dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_head: bad dtype %d", dtype);
+    if (n == 0) return REGIONE_OK;
+    if (!h_rows || !w_head_packed || !c_a || !x_e) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_head: null tensor");
+    if (x_full_opt && !index_opt) RG_FAIL(REGIONE_ERR_INVALID_ARG, "velocity_head: a full latent needs the index list");
+    if (ctx->f32 || hidden < 128) {
+        // float32 contexts (and heads too short to split): the three calls the fused path stands for; v needs a place
+        void* v = v_out_opt ? v_out_opt : c_a;      // the cache receives the fresh velocity anyway
+        if (int rc = regione_linear(ctx, h_rows, w_head_packed, b_head_opt, n, c, hidden, REGIONE_ACT_NONE, dtype, v)) return rc;
+        if (int rc = regione_velocity_cache(ctx, 0, 1.0f, dt, v, c_a, nullptr, x_e, nullptr, n, c, dtype)) return rc;
+        if (x_full_opt) return regione_scatter(ctx, x_full_opt, c, dtype, index_opt, nullptr, n, x_e);
+        return REGIONE_OK;
+    }
+    GemmEpilogue ep = {};
+    ep.bias = b_head_opt; ep.y = v_out_opt; ep.ldy = c; ep.y_f32 = dtype == REGIONE_FP32;
+    ep.vel_ca = c_a; ep.vel_xe = x_e; ep.vel_xfull = x_full_opt; ep.vel_index = index_opt; ep.vel_dt = dt;
+    return rg_gemm_velocity(ctx, h_rows, hidden, w_head_packed, n, c, hidden, ep);
+}
+
 namespace {
 
 int check_stream_weights(const regione_stream_weights& w, int block_type, const char* which) {

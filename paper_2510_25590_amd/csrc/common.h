@@ -74,7 +74,7 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
 }
 
 // ---- internal launchers (each enqueues on ctx->stream and returns an error code)
-enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESID = 2 };
+enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESID = 2, EPI_VELOCITY = 3 };   // EPI_VELOCITY exists only as the merge step of a K-split GEMM
 
 struct GemmEpilogue {
     int kind;            // EPI_*
@@ -91,10 +91,16 @@ struct GemmEpilogue {
     const void* resid; int ldr; int resid_f32; const float* gate;
     // 8-bit GEMM only: the float32 sums are multiplied by row_scale[row] * col_scale[col] before anything else
     const float* row_scale; const float* col_scale;
+    // merge_kind == EPI_VELOCITY (a plain K-split GEMM whose merge kernel finishes the step, Eq.9 fresh branch + Eq.4 + merge):
+    //   v = storage-rounded(acc + bias); y (if non-null) = v; vel_ca = v; vel_xe -= vel_dt * v; vel_xfull[vel_index[row]] = vel_xe
+    int merge_kind;
+    void* vel_ca; void* vel_xe; void* vel_xfull; const int32_t* vel_index; float vel_dt;
 };
 
 // a, w_packed (and the epilogue's q, k, v, y, resid where they are activations) are bf16, or float32 in a float32 context
 int rg_gemm(regione_ctx* ctx, const void* a, int lda, const void* w_packed, int m, int n, int k, const GemmEpilogue& ep);
+// y = x W^T + b as a K-split GEMM whose merge kernel applies the velocity step described at GemmEpilogue::merge_kind (bf16 contexts)
+int rg_gemm_velocity(regione_ctx* ctx, const void* a, int lda, const void* w_packed, int m, int n, int k, const GemmEpilogue& ep);
 int rg_gemm_f32(regione_ctx* ctx, const float* a, int lda, const float* w, int m, int n, int k, const GemmEpilogue& ep);
 // E4M3 operands (k counts 8-bit elements, a multiple of 128; lda in bytes, a multiple of 16); ep.row_scale / col_scale set
 int rg_gemm_fp8(regione_ctx* ctx, const uint8_t* a, int lda, const uint8_t* w_packed, int m, int n, int k, const GemmEpilogue& ep);

@@ -71,6 +71,26 @@ __device__ __forceinline__ void epilogue_store(const GemmEpilogue& ep, int row, 
             if (ep.act == REGIONE_ACT_GELU_TANH) val = gelu_tanh_f32(val);
             static_cast<bf16_t*>(ep.y)[static_cast<int64_t>(row) * ep.ldy + ep.y_col0 + (col - 3 * H)] = f32_to_bf16(val);
         }
+    } else if (KIND == EPI_VELOCITY) {
+        // the velocity in its storage type, the cache takes it (Eq.9, fresh branch), the Euler update (Eq.4) with the
+        // product and the difference rounded separately, and the row written where the merge by position puts it
+        const int64_t o = static_cast<int64_t>(row) * ep.ldy + col;
+        const int64_t full = ep.vel_index ? static_cast<int64_t>(ep.vel_index[row]) * ep.ldy + col : o;
+        if (ep.y_f32) {
+            if (ep.y) static_cast<float*>(ep.y)[o] = val;
+            static_cast<float*>(ep.vel_ca)[o] = val;
+            const float x = __fsub_rn(static_cast<float*>(ep.vel_xe)[o], __fmul_rn(ep.vel_dt, val));
+            static_cast<float*>(ep.vel_xe)[o] = x;
+            if (ep.vel_xfull) static_cast<float*>(ep.vel_xfull)[full] = x;
+        } else {
+            const bf16_t vb = f32_to_bf16(val);
+            const float v = bf16_to_f32(vb);
+            if (ep.y) static_cast<bf16_t*>(ep.y)[o] = vb;
+            static_cast<bf16_t*>(ep.vel_ca)[o] = vb;
+            const bf16_t xb = f32_to_bf16(__fsub_rn(bf16_to_f32(static_cast<bf16_t*>(ep.vel_xe)[o]), __fmul_rn(ep.vel_dt, v)));
+            static_cast<bf16_t*>(ep.vel_xe)[o] = xb;
+            if (ep.vel_xfull) static_cast<bf16_t*>(ep.vel_xfull)[full] = xb;
+        }
     } else {  // EPI_RESID
         const int64_t ri = static_cast<int64_t>(row) * ep.ldr + col;
         const float res = ep.resid_f32 ? static_cast<const float*>(ep.resid)[ri] : bf16_to_f32(static_cast<const bf16_t*>(ep.resid)[ri]);
@@ -857,7 +877,12 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, in
     if (used_splits > 1) {
         const int64_t total = static_cast<int64_t>(m) * n;
         const bool wide = ep.vec_ok && used_splits <= kMaxSplits && (!ep.bias || rg_aligned16(ep.bias)) && (!ep.gate || rg_aligned16(ep.gate));
-        if (wide) {
+        if (ep.merge_kind == EPI_VELOCITY) {
+            int64_t blocks = (total + kThreads - 1) / kThreads;
+            if (blocks > 256 * 16) blocks = 256 * 16;
+            hipLaunchKernelGGL((splitk_epilogue_kernel<EPI_VELOCITY>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+                               partial, used_splits, m, n, ep);
+        } else if (wide) {
             const int64_t blocks = (total / 4 + kThreads - 1) / kThreads;
             hipLaunchKernelGGL((splitk_epilogue4_kernel<KIND>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
                                partial, used_splits, m, n, ep);
@@ -874,7 +899,8 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, in
 
 template <int KIND>
 int dispatch(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, const GemmEpilogue& ep) {
-    const GemmPlan p = plan_gemm(ctx, m, n, k);
+    GemmPlan p = plan_gemm(ctx, m, n, k);
+    if (ep.merge_kind == EPI_VELOCITY && p.splits < 2) p.splits = 2;   // the velocity step lives in the merge kernel: there has to be one
     if (p.variant == 2) {
         if (p.tn == 1) return launch_gemm<1, KIND, 2>(ctx, a, lda, wp, m, n, k, p.splits, ep);
         return launch_gemm<2, KIND, 2>(ctx, a, lda, wp, m, n, k, p.splits, ep);
@@ -956,6 +982,18 @@ int rg_gemm_fp8(regione_ctx* ctx, const uint8_t* a, int lda, const uint8_t* wp, 
     const bf16_t* w2 = reinterpret_cast<const bf16_t*>(wp);
     if (tn == 1) return launch_gemm_fp8<1>(ctx, a2, lda / 2, w2, m, n, k2, splits, ep);
     return launch_gemm_fp8<2>(ctx, a2, lda / 2, w2, m, n, k2, splits, ep);
+}
+
+int rg_gemm_velocity(regione_ctx* ctx, const void* a_any, int lda, const void* wp_any, int m, int n, int k, const GemmEpilogue& ep_in) {
+    if (m <= 0 || n <= 0) return REGIONE_OK;
+    if (ctx->f32) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "gemm: the fused velocity step is a bf16-context path");
+    if (k < 2 * BK || (k % BK) || (lda & 7)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "gemm: k=%d must be a multiple of 64, at least 128, and lda=%d a multiple of 8", k, lda);
+    if (!rg_aligned16(a_any) || !rg_aligned16(wp_any)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
+    if (static_cast<size_t>(2) * m * n * sizeof(float) > ctx->gemm_part_bytes) RG_FAIL(REGIONE_ERR_WORKSPACE, "gemm: the partial sums of a %d x %d result exceed the workspace", m, n);
+    ProfScope prof(ctx, REGIONE_PROF_GEMM);
+    GemmEpilogue ep = ep_in;
+    ep.kind = EPI_PLAIN; ep.merge_kind = EPI_VELOCITY; ep.vec_ok = 0;
+    return dispatch<EPI_PLAIN>(ctx, static_cast<const bf16_t*>(a_any), lda, static_cast<const bf16_t*>(wp_any), m, n, k, ep);
 }
 
 int rg_gemm(regione_ctx* ctx, const void* a_any, int lda, const void* wp_any, int m, int n, int k, const GemmEpilogue& ep_in) {

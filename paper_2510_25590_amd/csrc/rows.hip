@@ -6,6 +6,7 @@
 namespace {
 
 constexpr int kThreads = 256;
+typedef unsigned int rows_u32x4 __attribute__((ext_vector_type(4)));
 
 // unit = one 16-byte (or ELEM-byte) piece of one row; GATHER: dst[i] = src[index[i]], else dst[index[i]] = src[i]
 template <typename V, bool GATHER>
@@ -53,6 +54,55 @@ int rows_by_index(regione_ctx* ctx, const void* src, void* dst, int32_t row_elem
     else
         hipLaunchKernelGGL((rows_by_index_kernel<uint16_t, GATHER>), grid, dim3(kThreads), 0, ctx->stream,
                            static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), index, n_dev, n_max, ppr);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+
+// Two tensors by one index list in one launch (the hidden rows and the latent rows of the edited tokens): a row of the
+// pair is pa + pb 16-byte pieces, the first pa of tensor A.
+template <bool GATHER>
+__global__ void __launch_bounds__(kThreads)
+rows_pair_by_index_kernel(const rows_u32x4* __restrict__ src_a, rows_u32x4* __restrict__ dst_a, int pa,
+                          const rows_u32x4* __restrict__ src_b, rows_u32x4* __restrict__ dst_b, int pb,
+                          const int32_t* __restrict__ index, const int32_t* __restrict__ n_dev, int64_t n_max) {
+    int64_t n = n_max;
+    if (n_dev) { const int64_t nd = *n_dev; n = nd < n_max ? (nd < 0 ? 0 : nd) : n_max; }
+    const int ppr = pa + pb;
+    const int64_t total = n * ppr;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t u = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; u < total; u += stride) {
+        const int64_t row = u / ppr;
+        int piece = static_cast<int>(u - row * ppr);
+        const int64_t other = index[row];
+        const bool first = piece < pa;
+        const rows_u32x4* src = first ? src_a : src_b;
+        rows_u32x4* dst = first ? dst_a : dst_b;
+        const int p = first ? pa : pb;
+        piece = first ? piece : piece - pa;
+        if (GATHER) __builtin_nontemporal_store(__builtin_nontemporal_load(src + other * p + piece), dst + row * p + piece);
+        else __builtin_nontemporal_store(__builtin_nontemporal_load(src + row * p + piece), dst + other * p + piece);
+    }
+}
+
+template <bool GATHER>
+int rows_pair(regione_ctx* ctx, const void* src_a, void* dst_a, int32_t elems_a, int32_t dtype_a, const void* src_b, void* dst_b, int32_t elems_b, int32_t dtype_b,
+              const int32_t* index, const int32_t* n_dev, int64_t n_max, const char* who) {
+    if (!ctx) RG_FAIL(REGIONE_ERR_INVALID_ARG, "%s: null context", who);
+    const int64_t bytes_a = static_cast<int64_t>(elems_a) * (dtype_a == REGIONE_BF16 ? 2 : 4), bytes_b = static_cast<int64_t>(elems_b) * (dtype_b == REGIONE_BF16 ? 2 : 4);
+    const bool wide = elems_a > 0 && elems_b > 0 && n_max > 0 && src_a && dst_a && src_b && dst_b && index && (bytes_a % 16 == 0) && (bytes_b % 16 == 0) &&
+                      rg_aligned16(src_a) && rg_aligned16(dst_a) && rg_aligned16(src_b) && rg_aligned16(dst_b) &&
+                      (dtype_a == REGIONE_BF16 || dtype_a == REGIONE_FP32) && (dtype_b == REGIONE_BF16 || dtype_b == REGIONE_FP32);
+    if (!wide) {   // anything unusual (odd row widths, empty lists, bad arguments): the single-tensor path, with its checks
+        if (int rc = rows_by_index<GATHER>(ctx, src_a, dst_a, elems_a, dtype_a, index, n_dev, n_max, who)) return rc;
+        return rows_by_index<GATHER>(ctx, src_b, dst_b, elems_b, dtype_b, index, n_dev, n_max, who);
+    }
+    const int pa = static_cast<int>(bytes_a / 16), pb = static_cast<int>(bytes_b / 16);
+    int64_t blocks = (n_max * (pa + pb) + kThreads - 1) / kThreads;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    ProfScope prof(ctx, REGIONE_PROF_ROWS);
+    hipLaunchKernelGGL((rows_pair_by_index_kernel<GATHER>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+                       static_cast<const rows_u32x4*>(src_a), static_cast<rows_u32x4*>(dst_a), pa, static_cast<const rows_u32x4*>(src_b), static_cast<rows_u32x4*>(dst_b), pb,
+                       index, n_dev, n_max);
     RG_LAUNCH_CHECK();
     return REGIONE_OK;
 }
@@ -286,6 +336,18 @@ extern "C" int regione_gather(regione_ctx* ctx, const void* src, int32_t row_ele
 extern "C" int regione_scatter(regione_ctx* ctx, void* dst_full, int32_t row_elems, int32_t dtype,
                                const int32_t* index, const int32_t* n_dev, int64_t n_max, const void* src) {
     return rows_by_index<false>(ctx, src, dst_full, row_elems, dtype, index, n_dev, n_max, "scatter");
+}
+
+extern "C" int regione_gather_pair(regione_ctx* ctx, const void* src_a, int32_t row_elems_a, int32_t dtype_a, void* dst_a,
+                                   const void* src_b, int32_t row_elems_b, int32_t dtype_b, void* dst_b,
+                                   const int32_t* index, const int32_t* n_dev, int64_t n_max) {
+    return rows_pair<true>(ctx, src_a, dst_a, row_elems_a, dtype_a, src_b, dst_b, row_elems_b, dtype_b, index, n_dev, n_max, "gather_pair");
+}
+
+extern "C" int regione_scatter_pair(regione_ctx* ctx, void* dst_full_a, int32_t row_elems_a, int32_t dtype_a, const void* src_a,
+                                    void* dst_full_b, int32_t row_elems_b, int32_t dtype_b, const void* src_b,
+                                    const int32_t* index, const int32_t* n_dev, int64_t n_max) {
+    return rows_pair<false>(ctx, src_a, dst_full_a, row_elems_a, dtype_a, src_b, dst_full_b, row_elems_b, dtype_b, index, n_dev, n_max, "scatter_pair");
 }
 
 extern "C" int regione_velocity_cache(regione_ctx* ctx, int32_t reuse, float factor, float dt,

@@ -4,9 +4,9 @@
 states, one block's weights, the layer's KV cache) and `step()` issues the hot path of the
 method's region-aware generation stage (Algorithm 1, inner loop) through the binding:
 
-  regione_partition -> regione_gather (hidden rows, latent rows) -> regione_block_forward
-  with the retrieve flag (Eq.6) -> regione_linear (velocity head) -> regione_velocity_cache
-  (Eq.9 + Eq.4) -> regione_scatter (latent rows, hidden rows)
+  regione_partition -> regione_gather_pair (hidden rows, latent rows) -> regione_block_forward
+  with the retrieve flag (Eq.6) -> regione_velocity_head (velocity head, velocity cache of Eq.9,
+  Euler update of Eq.4, merge of the latent rows) -> regione_scatter (hidden rows)
 
 No arithmetic of the method happens here; torch is used for device memory only.
 """
@@ -151,8 +151,7 @@ class RegionStepWorkload:
         n = rg.regione_partition(ctx, self.x_t, self.v_prev, self.x_ref, self.n_img, cfg.channels, self.dt, cfg.sigma, cfg.eta,
                                  self.score, self.mask, self.e_index, self.u_index, self.n_dev)
         self.n_edited = n
-        rg.regione_gather(ctx, self.h_now, cfg.hidden, self.dt, self.e_index, self.n_dev, n, self.h_e)
-        rg.regione_gather(ctx, self.x_t, cfg.channels, self.dt, self.e_index, self.n_dev, n, self.x_e)
+        rg.regione_gather_pair(ctx, self.h_now, cfg.hidden, self.dt, self.h_e, self.x_t, cfg.channels, self.dt, self.x_e, self.e_index, self.n_dev, n)
         if cfg.text_fresh:
             rg.regione_fresh_slots(ctx, self.e_index, self.n_dev, n, cfg.n_txt, self.slots)
             rg.regione_block_forward(ctx, self.weights, self.block_type, self.h_fresh, self.h_fresh_out, self.dt, cfg.n_txt + n, cfg.n_txt,
@@ -160,9 +159,9 @@ class RegionStepWorkload:
         else:
             rg.regione_block_forward(ctx, self.weights, self.block_type, self.h_e, self.h_e_out, self.dt, n, 0,
                                      self.e_index, cfg.n_txt, self.k_cache, self.v_cache, self.n_all, rg.FLAG_RETRIEVE)
-        rg.regione_linear(ctx, self.h_e_out, self.w_head, self.b_head, n, cfg.channels, cfg.hidden, rg.ACT_NONE, self.dt, self.v_e)
-        rg.regione_velocity_cache(ctx, False, 1.0, cfg.dt, self.v_e, self.c_a, None, self.x_e, self.n_dev, n, cfg.channels, self.dt)
-        rg.regione_scatter(ctx, self.x_next, cfg.channels, self.dt, self.e_index, self.n_dev, n, self.x_e)
+        # velocity head, velocity cache (fresh step, Eq.9), Euler update (Eq.4) and the merge of the latent rows: one fused call
+        rg.regione_velocity_head(ctx, self.h_e_out, self.w_head, self.b_head, n, cfg.channels, cfg.hidden, cfg.dt, self.v_e, self.c_a, self.x_e,
+                                 self.x_next, self.e_index, self.dt)
         rg.regione_scatter(ctx, self.h_next, cfg.hidden, self.dt, self.e_index, self.n_dev, n, self.h_e_out)
         return n
 

@@ -251,6 +251,73 @@ def test_euler_rows_in_place_equals_gather_step_scatter(ctx, dtype, c):
         rg.regione_euler_rows(ctx, dx, dx, torch.from_numpy(u).cuda(), cnt, len(u), c, code, dt)
 
 
+@pytest.mark.parametrize("elems_a,elems_b,dt_a,dt_b", [(3072, 64, "bf16", "bf16"), (256, 64, "f32", "f32"), (3072, 64, "bf16", "f32"), (40, 20, "bf16", "bf16")])
+def test_pair_gather_and_scatter_equal_the_single_calls(ctx, elems_a, elems_b, dt_a, dt_b):
+    rng = np.random.default_rng(620 + elems_a)
+    n_rows, n = 2000, 377
+    idx = np.sort(rng.choice(n_rows, size=n, replace=False)).astype(np.int32)
+    a = rng.standard_normal((n_rows, elems_a)).astype(np.float32); b = rng.standard_normal((n_rows, elems_b)).astype(np.float32)
+    da, db = dev(a, dt_a), dev(b, dt_b)
+    ca, cb = (rg.BF16 if dt_a == "bf16" else rg.FP32), (rg.BF16 if dt_b == "bf16" else rg.FP32)
+    didx = torch.from_numpy(idx).cuda()
+    cnt = torch.tensor([n - 7], dtype=torch.int32, device="cuda")
+    ga, gb = torch.zeros((n, elems_a), dtype=da.dtype, device="cuda"), torch.zeros((n, elems_b), dtype=db.dtype, device="cuda")
+    ga1, gb1 = torch.zeros_like(ga), torch.zeros_like(gb)
+    rg.regione_gather_pair(ctx, da, elems_a, ca, ga, db, elems_b, cb, gb, didx, cnt, n)
+    rg.regione_gather(ctx, da, elems_a, ca, didx, cnt, n, ga1); rg.regione_gather(ctx, db, elems_b, cb, didx, cnt, n, gb1)
+    assert torch.equal(ga, ga1) and torch.equal(gb, gb1)
+    assert torch.equal(ga[:n - 7], da[didx[:n - 7].long()]) and bool((ga[n - 7:] == 0).all())
+    fa, fb = torch.zeros_like(da), torch.zeros_like(db)
+    fa1, fb1 = torch.zeros_like(da), torch.zeros_like(db)
+    rg.regione_scatter_pair(ctx, fa, elems_a, ca, ga, fb, elems_b, cb, gb, didx, cnt, n)
+    rg.regione_scatter(ctx, fa1, elems_a, ca, didx, cnt, n, ga); rg.regione_scatter(ctx, fb1, elems_b, cb, didx, cnt, n, gb)
+    assert torch.equal(fa, fa1) and torch.equal(fb, fb1)
+    # nothing to move: not an error
+    rg.regione_gather_pair(ctx, da, elems_a, ca, ga, db, elems_b, cb, gb, didx, cnt, 0)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("n", [1, 36, 820])
+def test_velocity_head_equals_linear_cache_and_scatter(dtype, n):
+    """The fused head of a fresh region step against the three calls it stands for (bit for bit), and against the oracle."""
+    hidden, c, n_rows = 3072, 64, 4096
+    rng = np.random.default_rng(630 + n)
+    ctx2 = rg.Context(hidden, 24, 128, 12288, 1024, 16)
+    h = inputs.bf16_round(rng.standard_normal((n, hidden)).astype(np.float32))
+    w = inputs.bf16_round((0.02 * rng.standard_normal((c, hidden))).astype(np.float32))
+    b = (0.02 * rng.standard_normal(c)).astype(np.float32)
+    rnd = inputs.bf16_round if dtype == "bf16" else (lambda a: a)
+    x_e = rnd(rng.standard_normal((n, c)).astype(np.float32)); x_full = rnd(rng.standard_normal((n_rows, c)).astype(np.float32))
+    idx = np.sort(rng.choice(n_rows, size=n, replace=False)).astype(np.int32)
+    code = rg.BF16 if dtype == "bf16" else rg.FP32
+    wp = rg.pack_weight(ctx2, dev(w, "bf16")); db = torch.from_numpy(b).cuda(); dh = dev(h, "bf16"); didx = torch.from_numpy(idx).cuda()
+    dt = 1.0 / 28.0
+    # fused
+    v1, ca1, xe1, xf1 = dev(np.zeros((n, c), np.float32), dtype), dev(np.ones((n, c), np.float32), dtype), dev(x_e, dtype), dev(x_full, dtype)
+    rg.regione_velocity_head(ctx2, dh, wp, db, n, c, hidden, dt, v1, ca1, xe1, xf1, didx, code)
+    # the three calls
+    v2, ca2, xe2, xf2 = dev(np.zeros((n, c), np.float32), dtype), dev(np.ones((n, c), np.float32), dtype), dev(x_e, dtype), dev(x_full, dtype)
+    rg.regione_linear(ctx2, dh, wp, db, n, c, hidden, rg.ACT_NONE, code, v2)
+    rg.regione_velocity_cache(ctx2, False, 1.0, dt, v2, ca2, None, xe2, None, n, c, code)
+    rg.regione_scatter(ctx2, xf2, c, code, didx, None, n, xe2)
+    for name, p, q in (("v", v1, v2), ("c_a", ca1, ca2), ("x_e", xe1, xe2), ("x_full", xf1, xf2)):
+        assert torch.equal(p, q), name
+    # the oracle: linear, fresh cache step, Euler, merge
+    v_o = orc.linear(h, w, b)
+    _, ca_o, xe_o = orc.velocity_cache_apply(False, 1.0, dt, v_o, None, x_e)
+    xf_o = orc.scatter(x_full.astype(np.float64).copy(), idx, xe_o)
+    tol = dict(stored_bf16=True) if dtype == "bf16" else dict(max_abs=2e-3, mean_rel_tol=1e-4)   # float32 sums of exact bf16 products over 3072 terms
+    assert_close(host(v1), v_o, "velocity", **tol)
+    assert_close(host(xf1), xf_o, "merged latent", **tol)
+    rest = np.setdiff1d(np.arange(n_rows), idx)
+    assert np.array_equal(host(xf1)[rest], x_full[rest])
+    # without the optional outputs
+    ca3, xe3 = dev(np.ones((n, c), np.float32), dtype), dev(x_e, dtype)
+    rg.regione_velocity_head(ctx2, dh, wp, db, n, c, hidden, dt, None, ca3, xe3, None, None, code)
+    assert torch.equal(ca3, ca1) and torch.equal(xe3, xe1)
+    ctx2.close()
+
+
 # ---------------------------------------------------------------- morphological clean-up of the partition
 
 
