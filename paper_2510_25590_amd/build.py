@@ -42,6 +42,12 @@ def build(verbose: bool = False, only=None) -> str:
     fl = flags()
     os.makedirs(OBJ, exist_ok=True)
     sources = [s for s in SOURCES if only is None or s in only]
+    if only is not None:   # a partial build is only sound while no header is newer than the objects that are kept
+        headers = [os.path.join(CSRC, "common.h")] + [os.path.join(ROOT, "include", h) for h in os.listdir(os.path.join(ROOT, "include"))]
+        newest = max(os.path.getmtime(h) for h in headers)
+        kept = [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in SOURCES if s not in sources]
+        if any(not os.path.exists(o) or os.path.getmtime(o) < newest for o in kept):
+            sources = list(SOURCES)
 
     def compile_one(src):
         obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")

@@ -21,6 +21,9 @@ void free_all(regione_ctx* c) {
     void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->slot_all, c->attn_part, c->gemm_part};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     if (c->n_edited_pinned) (void)hipHostFree(c->n_edited_pinned);
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
     if (c->prof_ev) {
         for (int i = 0; i < 2 * c->prof_cap; ++i) if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
         delete[] c->prof_ev;
@@ -85,6 +88,7 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
 extern "C" int regione_destroy(regione_ctx* ctx) {
     if (!ctx) return REGIONE_OK;
     (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->side_stream) (void)hipStreamSynchronize(ctx->side_stream);
     free_all(ctx);
     delete ctx;
     return REGIONE_OK;
@@ -154,6 +158,45 @@ extern "C" int regione_velocity_head(regione_ctx* ctx, const void* h_rows, const
 }
 
 namespace {
+
+// The second lane: its stream and events exist from the first call that wants them.
+int ensure_side_lane(regione_ctx* ctx) {
+    if (ctx->side_stream) return REGIONE_OK;
+    RG_HIP(hipStreamCreateWithFlags(&ctx->side_stream, hipStreamNonBlocking));   // default priority
+    RG_HIP(hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
+    RG_HIP(hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming));
+    return REGIONE_OK;
+}
+// The side lane starts after everything enqueued on the main stream so far ...
+int lane_fork(regione_ctx* ctx) {
+    RG_HIP(hipEventRecord(ctx->ev_fork, ctx->stream));
+    RG_HIP(hipStreamWaitEvent(ctx->side_stream, ctx->ev_fork, 0));
+    return REGIONE_OK;
+}
+// ... and the main stream goes on after everything enqueued on the side lane.
+int lane_join(regione_ctx* ctx) {
+    RG_HIP(hipEventRecord(ctx->ev_join, ctx->side_stream));
+    RG_HIP(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
+    return REGIONE_OK;
+}
+// While alive, launches through the context go to the side lane: its stream and the upper half of the K-split workspace
+// (the main lane is left the lower half for the same time by LaneHalf).
+struct LaneSwap {
+    regione_ctx* c; hipStream_t stream; float* part; size_t bytes; bool on;
+    LaneSwap(regione_ctx* ctx, bool side) : c(ctx), stream(ctx->stream), part(ctx->gemm_part), bytes(ctx->gemm_part_bytes), on(side) {
+        if (!on) return;
+        const size_t half = (bytes / 2) & ~static_cast<size_t>(255);
+        c->stream = c->side_stream;
+        c->gemm_part = reinterpret_cast<float*>(reinterpret_cast<char*>(part) + half);
+        c->gemm_part_bytes = half;
+    }
+    ~LaneSwap() { if (on) { c->stream = stream; c->gemm_part = part; c->gemm_part_bytes = bytes; } }
+};
+struct LaneHalf {
+    regione_ctx* c; size_t bytes; bool on;
+    LaneHalf(regione_ctx* ctx, bool forked) : c(ctx), bytes(ctx->gemm_part_bytes), on(forked) { if (on) c->gemm_part_bytes = (bytes / 2) & ~static_cast<size_t>(255); }
+    ~LaneHalf() { if (on) c->gemm_part_bytes = bytes; }
+};
 
 int check_stream_weights(const regione_stream_weights& w, int block_type, const char* which) {
     if (block_type == REGIONE_BLOCK_DOUBLE) {
@@ -230,9 +273,18 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
         gemm_slots = ctx->slot_all;
     }
 
+    // Text and image rows of a double-stream block go through different weights: until the attention joins them, and
+    // again after it, the two groups are independent, so the text group runs on the context's second lane and the
+    // workgroups of both fill the chip together (each group alone leaves part of its last round of tiles empty).
+    const bool two_lanes = groups[0].n > 0 && groups[1].n > 0 && !ctx->prof_on;
+    if (two_lanes && (rc = ensure_side_lane(ctx)) != REGIONE_OK) return rc;
+
     // ---- first half: LayerNorm + modulation, QKV (and MLP-in for single-stream) projection
+    if (two_lanes && (rc = lane_fork(ctx)) != REGIONE_OK) return rc;
     for (const Rows& g : groups) {
         if (g.n <= 0) continue;
+        LaneSwap swap(ctx, two_lanes && &g == &groups[0]);
+        LaneHalf half(ctx, two_lanes && &g == &groups[1]);
         const char* hin = static_cast<const char*>(h_in) + static_cast<size_t>(g.r0) * H * h_elem;
         char* u = ctx->u + static_cast<size_t>(g.r0) * H * es;
         if ((rc = rg_layernorm_mod(ctx, hin, h_f32, g.n, H, g.w->shift1, g.w->scale1, u)) != REGIONE_OK) return rc;
@@ -257,6 +309,8 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
         if (rc != REGIONE_OK) return rc;
     }
 
+    if (two_lanes && (rc = lane_join(ctx)) != REGIONE_OK) return rc;
+
     // ---- attention (Eq.6).  With a flag set the fresh K,V already sit in their cache slots, so the
     // key list is the whole cached sequence; without a flag it is the fresh rows only.
     for (int b = 0; b < n_branches; ++b) {
@@ -267,8 +321,11 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
     }
 
     // ---- second half
+    if (two_lanes && (rc = lane_fork(ctx)) != REGIONE_OK) return rc;
     for (const Rows& g : groups) {
         if (g.n <= 0) continue;
+        LaneSwap swap(ctx, two_lanes && &g == &groups[0]);
+        LaneHalf half(ctx, two_lanes && &g == &groups[1]);
         const char* hin = static_cast<const char*>(h_in) + static_cast<size_t>(g.r0) * H * h_elem;
         char* hout = static_cast<char*>(h_out) + static_cast<size_t>(g.r0) * H * h_elem;
         const char* a = ctx->a + static_cast<size_t>(g.r0) * lda_attn * es;
@@ -299,6 +356,7 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
         dn.y = hout; dn.ldy = H; dn.y_f32 = h_f32;
         if ((rc = rg_gemm(ctx, m, M, g.w->w_2, g.n, H, M, dn)) != REGIONE_OK) return rc;
     }
+    if (two_lanes && (rc = lane_join(ctx)) != REGIONE_OK) return rc;
     return REGIONE_OK;
 }
 

@@ -32,6 +32,11 @@ struct regione_ctx {
     int32_t* slot_all; // [max_fresh] slot list of all branches of a batched block call
     float* gemm_part;  // split-K partial sums
     size_t gemm_part_bytes;
+    // second lane for independent work inside one call (text and image rows of a double-stream block use different
+    // weights, so their projections do not depend on each other): a stream of the default priority and two events,
+    // created on first use; while a lane swap is active, `stream` and `gemm_part` name the lane's own stream and half
+    hipStream_t side_stream;
+    hipEvent_t ev_fork, ev_join;
     int gemm_force_tn, gemm_force_splits;  // 0 = chosen per call
     int attn_force_splits;  // 0 = chosen per call
     // kernels that need more than 64 KiB of LDS have to be granted it once per device: one bit per kernel family and
