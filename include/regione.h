@@ -430,6 +430,39 @@ int regione_velocity_head(regione_ctx* ctx, const void* h_rows, const void* w_he
 int regione_euler_rows(regione_ctx* ctx, void* x_full, const void* v_full, const int32_t* index, const int32_t* n_dev,
                        int64_t n_max, int32_t c, int32_t dtype, float dt);
 
+/* One region-aware step in one call: the body of Algorithm 1's region-aware stage for a stack of blocks, i.e. the
+ * calls above in the order of the algorithm, queued by the library without returning to the caller in between:
+ *   1. adaptive region partition (regione_partition on x_t, v, x_ref): mask, E/U index lists, count;
+ *   2. gather of the edited tokens' hidden rows and latent rows (regione_gather_pair);
+ *   3. every block with the retrieve flag on those rows (regione_block_forward, Eq.6), block i on k_caches[i],
+ *      v_caches[i]; with n_txt_fresh > 0 the first n_txt_fresh rows of h_rows are text rows that the caller has put
+ *      there, the gathered rows follow them, and `slots` receives the slot list (regione_fresh_slots);
+ *   4. velocity head, velocity cache of a fresh step, Euler update and merge of the latent rows into x_next_full
+ *      (regione_velocity_head; Eq.9, Eq.4);
+ *   5. merge of the hidden rows into h_next_full (regione_scatter) when h_next_full_opt is given.
+ * Results are those of the separate calls bit for bit.  What the single call saves is the wait between 1 and 2: the
+ * count that sizes every later launch reaches the host through a pinned word that the index kernel writes first, so
+ * the host queues the launches of 2-5 while the partition still runs, instead of waiting for the stream.
+ *   x_t, v, x_ref, score_opt, mask, e_index, u_index, n_edited_dev: as in regione_partition (n_tokens image tokens).
+ *   h_full [n_tokens, hidden] of h_dtype: hidden state of the image tokens entering the stack.
+ *   h_rows, h_rows_out [n_txt_fresh + n_tokens, hidden] of h_dtype: work rows (may be the same buffer).
+ *   x_e, c_a, v_out_opt [n_tokens, c] of `dtype`; x_next_full [n_tokens, c]: receives the edited rows' new latents.
+ *   blocks / block_types / k_caches / v_caches: host arrays of n_blocks entries; slot_offset: slot of image token 0 in
+ *   the cached sequence (the number of text tokens); slots [n_txt_fresh + n_tokens] int32, needed when n_txt_fresh > 0.
+ *   *n_edited_host receives the count.  With no edited token the call ends after step 1. */
+typedef struct regione_region_step_args {
+    const void* x_t; const void* v; const void* x_ref;
+    int64_t n_tokens; int32_t c; int32_t dtype; float sigma_t; float eta;
+    float* score_opt; uint8_t* mask; int32_t* e_index; int32_t* u_index; int32_t* n_edited_dev;
+    const void* h_full; int32_t h_dtype; int32_t n_txt_fresh;
+    void* h_rows; void* h_rows_out; int32_t* slots;
+    int32_t n_blocks; int32_t n_all; int32_t slot_offset; int32_t reserved;
+    const regione_block_weights* blocks; const int32_t* block_types; void* const* k_caches; void* const* v_caches;
+    const void* w_head_packed; const float* b_head_opt; float dt; int32_t reserved2;
+    void* v_out_opt; void* c_a; void* x_e; void* x_next_full; void* h_next_full_opt;
+} regione_region_step_args;
+int regione_region_step(regione_ctx* ctx, const regione_region_step_args* args, int32_t* n_edited_host);
+
 #ifdef __cplusplus
 }
 #endif

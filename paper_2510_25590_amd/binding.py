@@ -30,7 +30,7 @@ EXPORTS = (
     "regione_sq_norms", "regione_gamma_fit_host", "regione_guidance_combine", "regione_rel_change",
     "regione_quantize_rows_fp8", "regione_pack_weight_fp8", "regione_linear_fp8", "regione_mfma_peak_probe",
     "regione_partition_static", "regione_rel_decision_host", "regione_rel_update_host", "regione_fresh_slots", "regione_time_bias",
-    "regione_euler_rows", "regione_gather_pair", "regione_scatter_pair", "regione_velocity_head",
+    "regione_euler_rows", "regione_gather_pair", "regione_scatter_pair", "regione_velocity_head", "regione_region_step",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -51,6 +51,19 @@ class StreamWeights(C.Structure):
 
 class BlockWeights(C.Structure):
     _fields_ = [("txt", StreamWeights), ("img", StreamWeights), ("rope", C.c_void_p), ("rope_rows", C.c_int32)]
+
+
+class RegionStepArgs(C.Structure):
+    """regione_region_step_args, field for field."""
+    _fields_ = [("x_t", C.c_void_p), ("v", C.c_void_p), ("x_ref", C.c_void_p),
+                ("n_tokens", C.c_int64), ("c", C.c_int32), ("dtype", C.c_int32), ("sigma_t", C.c_float), ("eta", C.c_float),
+                ("score_opt", C.c_void_p), ("mask", C.c_void_p), ("e_index", C.c_void_p), ("u_index", C.c_void_p), ("n_edited_dev", C.c_void_p),
+                ("h_full", C.c_void_p), ("h_dtype", C.c_int32), ("n_txt_fresh", C.c_int32),
+                ("h_rows", C.c_void_p), ("h_rows_out", C.c_void_p), ("slots", C.c_void_p),
+                ("n_blocks", C.c_int32), ("n_all", C.c_int32), ("slot_offset", C.c_int32), ("reserved", C.c_int32),
+                ("blocks", C.POINTER(BlockWeights)), ("block_types", C.POINTER(C.c_int32)), ("k_caches", C.POINTER(C.c_void_p)), ("v_caches", C.POINTER(C.c_void_p)),
+                ("w_head_packed", C.c_void_p), ("b_head_opt", C.c_void_p), ("dt", C.c_float), ("reserved2", C.c_int32),
+                ("v_out_opt", C.c_void_p), ("c_a", C.c_void_p), ("x_e", C.c_void_p), ("x_next_full", C.c_void_p), ("h_next_full_opt", C.c_void_p)]
 
 
 class AvdState(C.Structure):
@@ -109,6 +122,7 @@ def lib() -> C.CDLL:
             "regione_gather_pair": [vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, i64],
             "regione_scatter_pair": [vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, i64],
             "regione_velocity_head": [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, i32],
+            "regione_region_step": [vp, C.POINTER(RegionStepArgs), C.POINTER(i32)],
             "regione_partition_static": [vp, vp, vp, vp, i64, i32, i32, f32, f32, vp, vp, vp, vp, vp],
             "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
@@ -271,6 +285,39 @@ def regione_scatter_pair(ctx, dst_full_a, row_elems_a, dtype_a, src_a, dst_full_
 def regione_velocity_head(ctx, h_rows, w_head, b_head, n, c, hidden, dt, v_out, c_a, x_e, x_full, index, dtype):
     _check(lib().regione_velocity_head(ctx.handle, _p(h_rows), _p(w_head), _p(b_head), n, c, hidden, float(dt), _p(v_out), _p(c_a), _p(x_e),
                                        _p(x_full), _p(index), dtype))
+
+
+def make_region_step_args(*, x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta, score, mask, e_index, u_index, n_edited_dev,
+                          h_full, h_dtype, n_txt_fresh, h_rows, h_rows_out, slots, blocks, block_types, k_caches, v_caches, n_all, slot_offset,
+                          w_head, b_head, dt, v_out, c_a, x_e, x_next_full, h_next_full):
+    """Fills a RegionStepArgs from tensors; blocks: list of BlockWeights, k_caches / v_caches: lists of tensors.  The
+    returned object keeps the host arrays it points to alive (attribute `_keep`)."""
+    n_blocks = len(blocks)
+    a = RegionStepArgs()
+    arr_b = (BlockWeights * max(n_blocks, 1))(*blocks)
+    arr_t = (C.c_int32 * max(n_blocks, 1))(*block_types)
+    arr_k = (C.c_void_p * max(n_blocks, 1))(*[t.data_ptr() for t in k_caches])
+    arr_v = (C.c_void_p * max(n_blocks, 1))(*[t.data_ptr() for t in v_caches])
+    a._keep = (arr_b, arr_t, arr_k, arr_v)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    a.x_t, a.v, a.x_ref = ptr(x_t), ptr(v), ptr(x_ref)
+    a.n_tokens, a.c, a.dtype, a.sigma_t, a.eta = n_tokens, c, dtype, sigma_t, eta
+    a.score_opt, a.mask, a.e_index, a.u_index, a.n_edited_dev = ptr(score), ptr(mask), ptr(e_index), ptr(u_index), ptr(n_edited_dev)
+    a.h_full, a.h_dtype, a.n_txt_fresh = ptr(h_full), h_dtype, n_txt_fresh
+    a.h_rows, a.h_rows_out, a.slots = ptr(h_rows), ptr(h_rows_out), ptr(slots)
+    a.n_blocks, a.n_all, a.slot_offset = n_blocks, n_all, slot_offset
+    a.blocks = C.cast(arr_b, C.POINTER(BlockWeights)); a.block_types = C.cast(arr_t, C.POINTER(C.c_int32))
+    a.k_caches = C.cast(arr_k, C.POINTER(C.c_void_p)); a.v_caches = C.cast(arr_v, C.POINTER(C.c_void_p))
+    a.w_head_packed, a.b_head_opt, a.dt = ptr(w_head), ptr(b_head), dt
+    a.v_out_opt, a.c_a, a.x_e, a.x_next_full, a.h_next_full_opt = ptr(v_out), ptr(c_a), ptr(x_e), ptr(x_next_full), ptr(h_next_full)
+    return a
+
+
+def regione_region_step(ctx, args: RegionStepArgs) -> int:
+    """One region-aware step in one call; returns the edited-token count."""
+    n = C.c_int32(0)
+    _check(lib().regione_region_step(ctx.handle, C.byref(args), C.byref(n)))
+    return n.value
 
 
 def regione_euler_rows(ctx, x_full, v_full, index, n_dev, n_max, c, dtype, dt):

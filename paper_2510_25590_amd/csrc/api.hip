@@ -157,6 +157,43 @@ extern "C" int regione_velocity_head(regione_ctx* ctx, const void* h_rows, const
     return rg_gemm_velocity(ctx, h_rows, hidden, w_head_packed, n, c, hidden, ep);
 }
 
+extern "C" int regione_region_step(regione_ctx* ctx, const regione_region_step_args* a, int32_t* n_edited_host) {
+    if (!ctx || !a || !n_edited_host) RG_FAIL(REGIONE_ERR_INVALID_ARG, "region_step: null argument");
+    if (a->n_blocks < 0 || a->n_txt_fresh < 0) RG_FAIL(REGIONE_ERR_INVALID_ARG, "region_step: n_blocks=%d n_txt_fresh=%d", a->n_blocks, a->n_txt_fresh);
+    if (a->h_dtype != REGIONE_BF16 && a->h_dtype != REGIONE_FP32) RG_FAIL(REGIONE_ERR_INVALID_ARG, "region_step: bad h_dtype %d", a->h_dtype);
+    if (a->n_tokens > 0 && (!a->h_full || !a->h_rows || !a->h_rows_out || !a->x_e || !a->c_a || !a->x_next_full || !a->w_head_packed))
+        RG_FAIL(REGIONE_ERR_INVALID_ARG, "region_step: null tensor");
+    if (a->n_blocks > 0 && (!a->blocks || !a->block_types || !a->k_caches || !a->v_caches)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "region_step: null block array");
+    if (a->n_txt_fresh > 0 && !a->slots) RG_FAIL(REGIONE_ERR_INVALID_ARG, "region_step: fresh text rows need the slot list");
+    const int H = ctx->dims.hidden;
+    int32_t n = 0;
+    if (int rc = rg_partition_early_count(ctx, a->x_t, a->v, a->x_ref, a->n_tokens, a->c, a->dtype, a->sigma_t, a->eta, a->score_opt, a->mask,
+                                          a->e_index, a->u_index, a->n_edited_dev, &n)) return rc;
+    *n_edited_host = n;
+    if (n == 0) return REGIONE_OK;
+    const size_t h_es = a->h_dtype == REGIONE_FP32 ? 4 : 2;
+    const size_t txt_bytes = static_cast<size_t>(a->n_txt_fresh) * H * h_es;
+    char* rows_in = static_cast<char*>(a->h_rows) + txt_bytes;          // the gathered rows follow the text rows
+    if (int rc = regione_gather_pair(ctx, a->h_full, H, a->h_dtype, rows_in, a->x_t, a->c, a->dtype, a->x_e, a->e_index, a->n_edited_dev, n)) return rc;
+    const int32_t* slot_index = a->e_index;
+    int32_t slot_offset = a->slot_offset;
+    if (a->n_txt_fresh > 0) {
+        if (int rc = regione_fresh_slots(ctx, a->e_index, a->n_edited_dev, n, a->n_txt_fresh, a->slots)) return rc;
+        slot_index = a->slots; slot_offset = 0;
+    }
+    const void* in = a->h_rows;
+    for (int b = 0; b < a->n_blocks; ++b) {
+        if (int rc = regione_block_forward(ctx, &a->blocks[b], a->block_types[b], in, a->h_rows_out, a->h_dtype, a->n_txt_fresh + n, a->n_txt_fresh,
+                                           slot_index, slot_offset, a->k_caches[b], a->v_caches[b], a->n_all, REGIONE_FLAG_RETRIEVE)) return rc;
+        in = a->h_rows_out;
+    }
+    const char* rows_out = static_cast<const char*>(in) + txt_bytes;
+    if (int rc = regione_velocity_head(ctx, rows_out, a->w_head_packed, a->b_head_opt, n, a->c, H, a->dt, a->v_out_opt, a->c_a, a->x_e,
+                                       a->x_next_full, a->e_index, a->dtype)) return rc;
+    if (a->h_next_full_opt) return regione_scatter(ctx, a->h_next_full_opt, H, a->h_dtype, a->e_index, a->n_edited_dev, n, rows_out);
+    return REGIONE_OK;
+}
+
 namespace {
 
 // The second lane: its stream and events exist from the first call that wants them.

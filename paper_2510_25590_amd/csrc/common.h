@@ -19,6 +19,7 @@ struct regione_ctx {
     int64_t part_counts_cap;   // its size in int32 entries
     int32_t* n_edited_pinned;      // pinned host copy of the last edited-token count (host address)
     int32_t* n_edited_pinned_dev;  // the same memory as the device sees it
+    int32_t count_ticket;          // last ticket handed to a partition whose count the host polls for (word 1 of the pinned memory)
     // activation buffers: elements of the compute dtype (bf16, or float32 in a float32 context); addressed in bytes
     char* u;       // [max_fresh, H]     normalised + modulated rows
     char* q;       // [max_fresh, H]
@@ -123,6 +124,11 @@ int rg_attention_f32(regione_ctx* ctx, const float* q, int ldq, int n_q,
                      const float* k1, const float* v1, int ldkv1, int n1, const int32_t* idx1,
                      int heads, int d, float scale, float* out, int ldo);
 int rg_pack_weight_f32(regione_ctx* ctx, const float* w, int n, int k, float* w_packed);
+// regione_partition whose host count arrives through a ticketed pinned word instead of a stream synchronisation
+int rg_partition_early_count(regione_ctx* ctx, const void* x_t, const void* v, const void* x_ref,
+                             int64_t n_tokens, int32_t c, int32_t dtype, float sigma_t, float eta,
+                             float* score_opt, uint8_t* mask, int32_t* e_index, int32_t* u_index,
+                             int32_t* n_edited_dev, int32_t* n_edited_host);
 // the static-scratch lookup of regione_partition_static, done ahead of time by regione_create
 int rg_partition_static_warm(void);
 // int32 entries of scratch memory the partition needs for max_tokens tokens

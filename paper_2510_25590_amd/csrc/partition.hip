@@ -12,6 +12,9 @@
 // into exclusive offsets; kernel 3 expands the bits into the byte mask and writes the index lists
 // with a popcount rank.  No atomics, so the lists come out in ascending order.
 #include "common.h"
+#include <atomic>
+#include <chrono>
+#include <climits>
 
 namespace {
 
@@ -190,11 +193,22 @@ score_bits_kernel(const T* __restrict__ x_t, const T* __restrict__ v, const T* _
     }
 }
 
+// The count's second destination.  With a ticket (a host waits for THIS call's count on a pinned host word without
+// waiting for the stream) the ticket follows the count into the next word, behind a system-scope fence, so that a host
+// that sees the ticket reads the count that belongs to it.
+__device__ __forceinline__ void publish_count(int32_t* __restrict__ dst, int32_t total, int32_t ticket) {
+    *dst = total;
+    if (ticket) {
+        __threadfence_system();
+        *reinterpret_cast<volatile int32_t*>(dst + 1) = ticket;
+    }
+}
+
 // Exclusive prefix sum of the per-block counts, in place, by one workgroup: thread t owns a contiguous run of
 // entries.  Also writes the total.
 constexpr int kScanThreads = 1024;
 __global__ void __launch_bounds__(kScanThreads)
-scan_counts_kernel(int32_t* __restrict__ counts, int n_blocks, int32_t* __restrict__ n_edited, int32_t* __restrict__ n_edited_pinned) {
+scan_counts_kernel(int32_t* __restrict__ counts, int n_blocks, int32_t* __restrict__ n_edited, int32_t* __restrict__ n_edited_pinned, int32_t ticket) {
     __shared__ int wave_sum[kScanThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int per = (n_blocks + kScanThreads - 1) / kScanThreads;
@@ -215,7 +229,7 @@ scan_counts_kernel(int32_t* __restrict__ counts, int n_blocks, int32_t* __restri
     for (int w = 0; w < kScanThreads / 64; ++w) { if (w < wave) before += wave_sum[w]; total += wave_sum[w]; }
     int run = before + incl - local;   // exclusive prefix of this thread's first entry
     for (int i = first; i < first + per && i < n_blocks; ++i) { const int cnt = counts[i]; counts[i] = run; run += cnt; }
-    if (threadIdx.x == 0) { *n_edited = total; *n_edited_pinned = total; }
+    if (threadIdx.x == 0) { *n_edited = total; publish_count(n_edited_pinned, total, ticket); }
 }
 
 // SUMS = false: `offsets` holds the exclusive prefix sums of the per-block counts (scan_counts_kernel ran).
@@ -228,7 +242,7 @@ __global__ void __launch_bounds__(kThreads)
 write_index_kernel(const uint64_t* __restrict__ bits, uint8_t* __restrict__ mask, const int32_t* __restrict__ offsets,
                    int64_t n_tokens, int tok_per_block,
                    int32_t* __restrict__ e_index, int32_t* __restrict__ u_index,
-                   int32_t* __restrict__ n_edited, int32_t* __restrict__ n_edited_pinned) {
+                   int32_t* __restrict__ n_edited, int32_t* __restrict__ n_edited_pinned, int32_t ticket) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     __shared__ int wave_e[kWaves];
     int base_e;
@@ -245,7 +259,7 @@ write_index_kernel(const uint64_t* __restrict__ bits, uint8_t* __restrict__ mask
         if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
             const int total = base_e + offsets[blockIdx.x];
             *n_edited = total;
-            *n_edited_pinned = total;
+            publish_count(n_edited_pinned, total, ticket);
         }
     } else {
         base_e = offsets[blockIdx.x];   // edited tokens in all blocks before this one
@@ -298,7 +312,7 @@ write_index_kernel(const uint64_t* __restrict__ bits, uint8_t* __restrict__ mask
     }
 }
 
-__global__ void set_i32_kernel(int32_t* p, int32_t* p_pinned, int32_t v) { *p = v; *p_pinned = v; }
+__global__ void set_i32_kernel(int32_t* p, int32_t* p_pinned, int32_t v, int32_t ticket) { *p = v; publish_count(p_pinned, v, ticket); }
 
 // Scratch memory of the partition's kernels: per-block edited counts and one decision bit per token.
 struct PartScratch {
@@ -396,13 +410,13 @@ count_mask_kernel(const uint8_t* __restrict__ mask, int64_t n_tokens, int tok_pe
 // one launch, else scan + lists.  n_edited_copy: a second place for the count (the context's pinned host word;
 // n_edited_dev itself when there is none).
 int launch_index_lists(hipStream_t stream, int32_t* counts, const uint64_t* bits, dim3 grid, uint8_t* mask, int64_t n_tokens, int tpb,
-                       int32_t* e_index, int32_t* u_index, int32_t* n_edited_dev, int32_t* n_edited_copy) {
+                       int32_t* e_index, int32_t* u_index, int32_t* n_edited_dev, int32_t* n_edited_copy, int32_t ticket = 0) {
     const bool sums = grid.x <= 1024;
     if (!sums) {
-        hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, stream, counts, static_cast<int>(grid.x), n_edited_dev, n_edited_copy);
+        hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(kScanThreads), 0, stream, counts, static_cast<int>(grid.x), n_edited_dev, n_edited_copy, ticket);
         RG_LAUNCH_CHECK();
     }
-#define RG_IDX(S, B) hipLaunchKernelGGL((write_index_kernel<S, B>), grid, dim3(kThreads), 0, stream, bits, mask, counts, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy)
+#define RG_IDX(S, B) hipLaunchKernelGGL((write_index_kernel<S, B>), grid, dim3(kThreads), 0, stream, bits, mask, counts, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy, sums ? ticket : 0)
     if (sums) { if (bits) RG_IDX(true, true); else RG_IDX(true, false); }
     else { if (bits) RG_IDX(false, true); else RG_IDX(false, false); }
 #undef RG_IDX
@@ -413,9 +427,9 @@ int launch_index_lists(hipStream_t stream, int32_t* counts, const uint64_t* bits
 // The launches of the partition on `stream` with its scratch memory in `ps`.
 int partition_launches(hipStream_t stream, const PartScratch& ps, const void* x_t, const void* v, const void* x_ref,
                        int64_t n_tokens, int32_t c, int32_t dtype, float sigma_t, float eta, float* score_opt, uint8_t* mask,
-                       int32_t* e_index, int32_t* u_index, int32_t* n_edited_dev, int32_t* n_edited_copy) {
+                       int32_t* e_index, int32_t* u_index, int32_t* n_edited_dev, int32_t* n_edited_copy, int32_t ticket = 0) {
     if (n_tokens == 0) {
-        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, stream, n_edited_dev, n_edited_copy, 0);
+        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, stream, n_edited_dev, n_edited_copy, 0, ticket);
         RG_LAUNCH_CHECK();
         return REGIONE_OK;
     }
@@ -441,7 +455,7 @@ int partition_launches(hipStream_t stream, const PartScratch& ps, const void* x_
                       : launch_score<float, 1>(stream, ps, lpt, pipe, grid, x_t, v, x_ref, n_tokens, c, tpb, sigma_t, eta, score_opt);
     }
     if (rc != REGIONE_OK) return rc;
-    return launch_index_lists(stream, ps.counts, ps.bits, grid, mask, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy);
+    return launch_index_lists(stream, ps.counts, ps.bits, grid, mask, n_tokens, tpb, e_index, u_index, n_edited_dev, n_edited_copy, ticket);
 }
 
 int check_partition_args(const char* who, const void* x_t, const void* v, const void* x_ref, int64_t n_tokens, int32_t c, int32_t dtype,
@@ -477,6 +491,39 @@ extern "C" int regione_partition(regione_ctx* ctx, const void* x_t, const void* 
     return REGIONE_OK;
 }
 
+// regione_partition for a caller inside the library that goes on launching on the same stream: the host gets the count
+// as soon as the kernels have published it (a ticketed pinned host word, polled), not when the stream has drained, so
+// the launches that need the count are queued while the index kernel still writes its lists.
+int rg_partition_early_count(regione_ctx* ctx, const void* x_t, const void* v, const void* x_ref,
+                             int64_t n_tokens, int32_t c, int32_t dtype, float sigma_t, float eta,
+                             float* score_opt, uint8_t* mask, int32_t* e_index, int32_t* u_index,
+                             int32_t* n_edited_dev, int32_t* n_edited_host) {
+    if (!ctx || !n_edited_host) RG_FAIL(REGIONE_ERR_INVALID_ARG, "partition: null context or count");
+    if (int rc = check_partition_args("partition", x_t, v, x_ref, n_tokens, c, dtype, mask, e_index, u_index, n_edited_dev)) return rc;
+    if (n_tokens > ctx->dims.max_tokens) RG_FAIL(REGIONE_ERR_WORKSPACE, "partition: %lld tokens, context made for %d", (long long)n_tokens, ctx->dims.max_tokens);
+    ctx->count_ticket = ctx->count_ticket == INT32_MAX ? 1 : ctx->count_ticket + 1;
+    const int32_t ticket = ctx->count_ticket;
+    {
+    ProfScope prof(ctx, REGIONE_PROF_PARTITION);
+    if (int rc = partition_launches(ctx->stream, part_scratch_in(ctx->part_counts, ctx->dims.max_tokens), x_t, v, x_ref, n_tokens, c, dtype, sigma_t, eta,
+                                    score_opt, mask, e_index, u_index, n_edited_dev, ctx->n_edited_pinned_dev, ticket)) return rc;
+    }
+    volatile int32_t* word = ctx->n_edited_pinned;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (;;) {
+        if (word[1] == ticket) break;
+        // bounded: a launch that failed on the device never publishes; after 5 ms the stream decides
+        if (std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(5)) {
+            RG_HIP(hipStreamSynchronize(ctx->stream));
+            if (word[1] != ticket) RG_FAIL(REGIONE_ERR_HIP, "partition: the count was not published");
+            break;
+        }
+    }
+    std::atomic_thread_fence(std::memory_order_acquire);
+    *n_edited_host = word[0];
+    return REGIONE_OK;
+}
+
 extern "C" int regione_mask_cleanup(regione_ctx* ctx, const uint8_t* mask_in, int32_t grid_h, int32_t grid_w, int32_t n_images,
                                     uint8_t* mask_out, int32_t* e_index, int32_t* u_index,
                                     int32_t* n_edited_dev, int32_t* n_edited_host_opt) {
@@ -489,7 +536,7 @@ extern "C" int regione_mask_cleanup(regione_ctx* ctx, const uint8_t* mask_in, in
     {
     ProfScope prof(ctx, REGIONE_PROF_PARTITION);
     if (n_tokens == 0) {
-        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, n_edited_dev, ctx->n_edited_pinned_dev, 0);
+        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, n_edited_dev, ctx->n_edited_pinned_dev, 0, 0);
         RG_LAUNCH_CHECK();
     } else {
         if (!mask_in || !mask_out || !e_index || !u_index) RG_FAIL(REGIONE_ERR_INVALID_ARG, "mask_cleanup: null tensor");

@@ -135,6 +135,7 @@ class RegionStepWorkload:
         self.x_next = self.x_t.clone()       # unedited rows keep their value; edited rows are scattered in
         self.h_next = self.h_now.clone()
         self.n_edited = -1
+        self._args = None
         self._fill_cache(bf(hst["h_store"]))
 
     def _fill_cache(self, h_store):
@@ -147,6 +148,24 @@ class RegionStepWorkload:
         torch.cuda.synchronize()
 
     def step(self):
+        """One region-aware step as ONE library call (regione_region_step)."""
+        cfg = self.cfg
+        if self._args is None:
+            self._args = rg.make_region_step_args(
+                x_t=self.x_t, v=self.v_prev, x_ref=self.x_ref, n_tokens=self.n_img, c=cfg.channels, dtype=self.dt, sigma_t=cfg.sigma, eta=cfg.eta,
+                score=self.score, mask=self.mask, e_index=self.e_index, u_index=self.u_index, n_edited_dev=self.n_dev,
+                h_full=self.h_now, h_dtype=self.dt, n_txt_fresh=self.n_txt_fresh, h_rows=self.h_fresh, h_rows_out=self.h_fresh_out,
+                slots=self.slots if cfg.text_fresh else None, blocks=[self.weights], block_types=[self.block_type],
+                k_caches=[self.k_cache], v_caches=[self.v_cache], n_all=self.n_all, slot_offset=cfg.n_txt,
+                w_head=self.w_head, b_head=self.b_head, dt=cfg.dt, v_out=self.v_e, c_a=self.c_a, x_e=self.x_e,
+                x_next_full=self.x_next, h_next_full=self.h_next)
+        n = rg.regione_region_step(self.ctx, self._args)
+        self.n_edited = n
+        return n
+
+    def step_separate(self):
+        """The same step call by call (what regione_region_step stands for); the host waits for the stream after the
+        partition to learn the count."""
         cfg, ctx = self.cfg, self.ctx
         n = rg.regione_partition(ctx, self.x_t, self.v_prev, self.x_ref, self.n_img, cfg.channels, self.dt, cfg.sigma, cfg.eta,
                                  self.score, self.mask, self.e_index, self.u_index, self.n_dev)
