@@ -358,6 +358,58 @@ def fp8_projections(torch, rg, n_rows: int, reps: int = 20):
     return res
 
 
+def fp8_block(torch, rg, steps: int, warmup: int):
+    """The headline block (820 edited rows, 8704 cache rows, retrieve flag) with its four projections in E4M3
+    (regione_block_forward_fp8: quantisation fused into the LayerNorms, two quantisation launches for the attention
+    output and the MLP rows) against the bf16 block, same process, alternating.  Secondary figure: an extension with its
+    own accuracy (tests/test_gpu_block_fp8.py), never the headline."""
+    from paper_2510_25590_amd import step
+    cfg = step.CONFIG_BLOCK
+    wl = step.RegionStepWorkload(cfg)
+    n = wl.step()
+    torch.cuda.synchronize()
+    ctx = wl.ctx
+    bf = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    w8 = rg.BlockWeightsFp8()
+    w8.txt, keep_t = rg.make_stream_weights_fp8(ctx, {k: bf(v) for k, v in wl.host["streams"][0].items() if k.startswith("w_")})
+    w8.img, keep_i = rg.make_stream_weights_fp8(ctx, {k: bf(v) for k, v in wl.host["streams"][1].items() if k.startswith("w_")})
+    for kp in (keep_t, keep_i):          # the unpacked codes are not needed here
+        for name in kp:
+            kp[name] = kp[name][:2]
+    out16 = torch.empty((n, cfg.hidden), dtype=torch.bfloat16, device="cuda"); out8 = torch.empty_like(out16)
+    h_e = wl.h_e[:n].clone()
+    run16 = lambda: rg.regione_block_forward(ctx, wl.weights, wl.block_type, h_e, out16, rg.BF16, n, 0, wl.e_index, cfg.n_txt, wl.k_cache, wl.v_cache, wl.n_all, rg.FLAG_RETRIEVE)
+    run8 = lambda: rg.regione_block_forward_fp8(ctx, wl.weights, w8, h_e, out8, rg.BF16, n, 0, wl.e_index, cfg.n_txt, wl.k_cache, wl.v_cache, wl.n_all, rg.FLAG_RETRIEVE)
+    res = {"rows": int(n), "keys_per_query": wl.n_all}
+    for rnd in range(2):
+        for name, fn in (("bf16", run16), ("fp8", run8)):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / steps
+            res[name + "_block_ms"] = min(ms, res.get(name + "_block_ms", ms))
+    rg.regione_profile_enable(ctx, True); rg.regione_profile_read(ctx)
+    for _ in range(steps):
+        run8()
+    prof = rg.regione_profile_read(ctx)
+    rg.regione_profile_enable(ctx, False)
+    res["fp8_kernels_ms"] = {k: v[0] / steps for k, v in prof.items() if v[1]}
+    gemm_flops, _ = wl.flops(n)
+    gemm_flops -= 2.0 * n * cfg.hidden * cfg.channels          # the velocity head is not part of the block
+    g_ms = prof["gemm"][0] / steps
+    res["fp8_gemm_TFLOPs"] = gemm_flops / (g_ms * 1e-3) / 1e12
+    res["fp8_gemm_frac_of_fp8_peak"] = res["fp8_gemm_TFLOPs"] / PEAK_FP8_TFLOPS
+    res["speedup"] = res["bf16_block_ms"] / res["fp8_block_ms"]
+    upd16, upd8 = out16.float() - h_e.float(), out8.float() - h_e.float()
+    res["rel_diff_of_block_update_to_bf16"] = float((upd8 - upd16).norm() / upd16.norm())
+    wl.close()
+    return res
+
+
 def measured_peaks(torch, rg):
     """What this chip sustains on register-only MFMA loops (at the clock it holds under that load) and on a plain 1 GiB copy
     through the library's own row kernel: the figures to read the achieved TFLOP/s and GB/s against, beside the nominal peaks."""
@@ -621,6 +673,7 @@ def main():
         out["fp8_projections"] = fp8_projections(torch, rg, int(n))
         # the same four projections on every row of the sequence (the shapes of a full, cache-storing forward)
         out["fp8_projections_all_rows"] = fp8_projections(torch, rg, int(out["config"]["keys_per_query"]), reps=5)
+        out["fp8_block"] = fp8_block(torch, rg, args.steps, args.warmup)
     if not args.no_membound:
         out["membound"] = membound(torch, rg)
         if "roofline" in out:    # one entry per HBM-bound kernel of the path, on the multi-GiB working sets stated in `membound`

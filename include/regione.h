@@ -430,6 +430,39 @@ int regione_velocity_head(regione_ctx* ctx, const void* h_rows, const void* w_he
 int regione_euler_rows(regione_ctx* ctx, void* x_full, const void* v_full, const int32_t* index, const int32_t* n_dev,
                        int64_t n_max, int32_t c, int32_t dtype, float dt);
 
+/* regione_block_forward for a double-stream block with its four dense projections in 8-bit floating point (the
+ * E4M3 variant above: an extension with its own accuracy, selected only by calling this entry point).  Arguments as in
+ * regione_block_forward; `w` supplies biases and modulation vectors (its bf16 weight pointers are not read), `w8` the
+ * quantised weights: per stream and projection the packed codes (regione_pack_weight_fp8) and one float32 scale per
+ * output feature (regione_quantize_rows_fp8 on the weight rows).  What is quantised, with one scale per row (token):
+ *   - the LayerNorm + modulation results feeding the QKV and the MLP-up projection, quantised from their float32
+ *     values inside the LayerNorm kernel (no bf16 rounding in between);
+ *   - the attention output and the activated MLP rows (bf16 as in the bf16 block), by regione_quantize_rows_fp8's
+ *     kernel.
+ * Everything else — attention, K/V cache (bf16), gates, residual stream, flags, slots — is the bf16 block's.
+ * Restrictions: bf16 context, block_type REGIONE_BLOCK_DOUBLE, hidden <= 4096, hidden and mlp multiples of 128.
+ * taps_opt (verification aid): when given, every non-null member receives a copy of that intermediate as the library
+ * computed it, rows in the order of h_in, so that each stage can be checked against a reference fed with the
+ * library's own input of that stage:
+ *   u1_codes [n, H] uint8, u1_scale [n] (input of the QKV projection);   q [n, H] bf16 (its query rows);
+ *   attn [n, H] bf16;   a_codes [n, H], a_scale [n] (input of the output projection);   h1 [n, H] float32;
+ *   u2_codes [n, H], u2_scale [n] (input of MLP up);   m [n, M] bf16;   m_codes [n, M], m_scale [n]. */
+typedef struct regione_stream_weights_fp8 {
+    const void* w_qkv; const float* s_qkv;   /* codes packed from [3H, H]; scales [3H] */
+    const void* w_o;   const float* s_o;     /* [H, H];  [H]  */
+    const void* w_1;   const float* s_1;     /* [M, H];  [M]  */
+    const void* w_2;   const float* s_2;     /* [H, M];  [H]  */
+} regione_stream_weights_fp8;
+typedef struct regione_block_weights_fp8 { regione_stream_weights_fp8 txt, img; } regione_block_weights_fp8;
+typedef struct regione_fp8_taps {
+    void* u1_codes; float* u1_scale; void* q; void* attn; void* a_codes; float* a_scale; float* h1;
+    void* u2_codes; float* u2_scale; void* m; void* m_codes; float* m_scale;
+} regione_fp8_taps;
+int regione_block_forward_fp8(regione_ctx* ctx, const regione_block_weights* w, const regione_block_weights_fp8* w8,
+                              const void* h_in, void* h_out, int32_t h_dtype,
+                              int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
+                              void* k_cache, void* v_cache, int32_t n_all, int32_t flags, const regione_fp8_taps* taps_opt);
+
 /* One region-aware step in one call: the body of Algorithm 1's region-aware stage for a stack of blocks, i.e. the
  * calls above in the order of the algorithm, queued by the library without returning to the caller in between:
  *   1. adaptive region partition (regione_partition on x_t, v, x_ref): mask, E/U index lists, count;

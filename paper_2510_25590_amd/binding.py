@@ -31,6 +31,7 @@ EXPORTS = (
     "regione_quantize_rows_fp8", "regione_pack_weight_fp8", "regione_linear_fp8", "regione_mfma_peak_probe",
     "regione_partition_static", "regione_rel_decision_host", "regione_rel_update_host", "regione_fresh_slots", "regione_time_bias",
     "regione_euler_rows", "regione_gather_pair", "regione_scatter_pair", "regione_velocity_head", "regione_region_step",
+    "regione_block_forward_fp8",
 )
 STEP_FULL, STEP_FULL_STORE, STEP_REGION = 0, 1, 2
 PROF_NAMES = ("partition", "rows", "layernorm", "gemm", "attention", "velocity")
@@ -51,6 +52,22 @@ class StreamWeights(C.Structure):
 
 class BlockWeights(C.Structure):
     _fields_ = [("txt", StreamWeights), ("img", StreamWeights), ("rope", C.c_void_p), ("rope_rows", C.c_int32)]
+
+
+_FP8_STREAM_FIELDS = ("w_qkv", "s_qkv", "w_o", "s_o", "w_1", "s_1", "w_2", "s_2")
+_FP8_TAP_FIELDS = ("u1_codes", "u1_scale", "q", "attn", "a_codes", "a_scale", "h1", "u2_codes", "u2_scale", "m", "m_codes", "m_scale")
+
+
+class StreamWeightsFp8(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in _FP8_STREAM_FIELDS]
+
+
+class BlockWeightsFp8(C.Structure):
+    _fields_ = [("txt", StreamWeightsFp8), ("img", StreamWeightsFp8)]
+
+
+class Fp8Taps(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in _FP8_TAP_FIELDS]
 
 
 class RegionStepArgs(C.Structure):
@@ -123,6 +140,8 @@ def lib() -> C.CDLL:
             "regione_scatter_pair": [vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, i64],
             "regione_velocity_head": [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, i32],
             "regione_region_step": [vp, C.POINTER(RegionStepArgs), C.POINTER(i32)],
+            "regione_block_forward_fp8": [vp, C.POINTER(BlockWeights), C.POINTER(BlockWeightsFp8), vp, vp, i32, i32, i32, vp, i32, vp, vp, i32, i32,
+                                          C.POINTER(Fp8Taps)],
             "regione_partition_static": [vp, vp, vp, vp, i64, i32, i32, f32, f32, vp, vp, vp, vp, vp],
             "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
             "regione_velocity_cache": [vp, i32, f32, f32, vp, vp, vp, vp, vp, i64, i32, i32],
@@ -240,6 +259,41 @@ def regione_block_forward(ctx, weights: BlockWeights, block_type, h_in, h_out, h
                           slot_index, slot_offset, k_cache, v_cache, n_all, flags):
     _check(lib().regione_block_forward(ctx.handle, C.byref(weights), block_type, _p(h_in), _p(h_out), h_dtype, n_fresh,
                                        n_txt_fresh, _p(slot_index), slot_offset, _p(k_cache), _p(v_cache), n_all, flags))
+
+
+def regione_block_forward_fp8(ctx, weights: BlockWeights, weights8: BlockWeightsFp8, h_in, h_out, h_dtype, n_fresh, n_txt_fresh,
+                              slot_index, slot_offset, k_cache, v_cache, n_all, flags, taps: "Fp8Taps | None" = None):
+    _check(lib().regione_block_forward_fp8(ctx.handle, C.byref(weights), C.byref(weights8), _p(h_in), _p(h_out), h_dtype, n_fresh, n_txt_fresh,
+                                           _p(slot_index), slot_offset, _p(k_cache), _p(v_cache), n_all, flags,
+                                           None if taps is None else C.byref(taps)))
+
+
+def make_stream_weights_fp8(ctx, tensors: dict):
+    """dict with the bf16 row-major weights w_qkv, w_o, w_1, w_2 (CUDA tensors) -> (StreamWeightsFp8, tensors to keep
+    alive): each is quantised with one scale per output feature (regione_quantize_rows_fp8) and packed
+    (regione_pack_weight_fp8).  The unpacked codes are kept as well (tests feed them to the reference)."""
+    import torch
+    w8, keep = StreamWeightsFp8(), {}
+    for name in ("w_qkv", "w_o", "w_1", "w_2"):
+        w = tensors[name].contiguous()
+        n, k = w.shape
+        codes = torch.empty((n, k), dtype=torch.uint8, device=w.device)
+        scale = torch.empty(n, dtype=torch.float32, device=w.device)
+        regione_quantize_rows_fp8(ctx, w, n, k, codes, scale)
+        packed = torch.zeros(regione_packed_weight_elems(n, k), dtype=torch.uint8, device=w.device)
+        regione_pack_weight_fp8(ctx, codes, n, k, packed)
+        keep[name] = (packed, scale, codes)
+        setattr(w8, name, packed.data_ptr())
+        setattr(w8, "s_" + name[2:], scale.data_ptr())
+    return w8, keep
+
+
+def make_fp8_taps(tensors: dict) -> Fp8Taps:
+    t = Fp8Taps()
+    for name in _FP8_TAP_FIELDS:
+        x = tensors.get(name)
+        setattr(t, name, None if x is None else x.data_ptr())
+    return t
 
 
 def regione_block_forward_batched(ctx, weights: BlockWeights, block_type, h_in, h_out, h_dtype, n_branches, n_fresh, n_txt_fresh,

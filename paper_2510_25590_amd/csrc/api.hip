@@ -18,7 +18,7 @@ int dev_alloc(T** p, size_t count) {
     return REGIONE_OK;
 }
 void free_all(regione_ctx* c) {
-    void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->slot_all, c->attn_part, c->gemm_part};
+    void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->slot_all, c->attn_part, c->gemm_part, c->q8, c->q8_scale};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     if (c->n_edited_pinned) (void)hipHostFree(c->n_edited_pinned);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
@@ -235,6 +235,28 @@ struct LaneHalf {
     ~LaneHalf() { if (on) c->gemm_part_bytes = bytes; }
 };
 
+int check_stream_weights_fp8(const regione_stream_weights_fp8& w, const char* which) {
+    if (!w.w_qkv || !w.w_o || !w.w_1 || !w.w_2 || !w.s_qkv || !w.s_o || !w.s_1 || !w.s_2)
+        RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward_fp8: null weight or scale in the %s stream", which);
+    return REGIONE_OK;
+}
+
+// Codes of one projection's input rows ([max_fresh, max(H, M)] bytes) and their row scales: allocated by the first
+// 8-bit block call of a context, freed with it.
+int ensure_fp8_workspace(regione_ctx* ctx) {
+    if (ctx->q8) return REGIONE_OK;
+    const size_t cols = static_cast<size_t>(ctx->dims.hidden > ctx->dims.mlp ? ctx->dims.hidden : ctx->dims.mlp);
+    const size_t rows = static_cast<size_t>(ctx->dims.max_fresh);
+    if (rows == 0) return REGIONE_OK;
+    RG_HIP(hipMalloc(reinterpret_cast<void**>(&ctx->q8), rows * cols));
+    ctx->q8_bytes = rows * cols;
+    if (hipMalloc(reinterpret_cast<void**>(&ctx->q8_scale), rows * sizeof(float)) != hipSuccess) {
+        (void)hipFree(ctx->q8); ctx->q8 = nullptr;
+        RG_FAIL(REGIONE_ERR_HIP, "block_forward_fp8: cannot allocate the scale workspace");
+    }
+    return REGIONE_OK;
+}
+
 int check_stream_weights(const regione_stream_weights& w, int block_type, const char* which) {
     if (block_type == REGIONE_BLOCK_DOUBLE) {
         if (!w.w_qkv || !w.w_o || !w.w_1 || !w.w_2) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: null weight in the %s stream", which);
@@ -250,10 +272,13 @@ int check_stream_weights(const regione_stream_weights& w, int block_type, const 
 // set of weights: rows [b*n_fresh, (b+1)*n_fresh) of h and cache rows [b*n_all, (b+1)*n_all) belong to branch b; slots
 // and positions are shared.  When no text row is fresh (or the block is single-stream) all branches' rows form ONE
 // row group, so every projection is one GEMM over n_branches*n_fresh rows; attention runs per branch.
+// w8 != null: the 8-bit form of the four projections of a double-stream block (regione_block_forward_fp8); `taps`
+// then names the places that receive copies of the intermediates.
 static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
                               const void* h_in, void* h_out, int32_t h_dtype, int32_t n_branches,
                               int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
-                              void* k_cache, void* v_cache, int32_t n_all, int32_t flags) {
+                              void* k_cache, void* v_cache, int32_t n_all, int32_t flags,
+                              const regione_block_weights_fp8* w8 = nullptr, const regione_fp8_taps* taps = nullptr) {
     if (!ctx || !w) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: null context or weights");
     if (n_branches < 1) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: %d branches", n_branches);
     if (block_type != REGIONE_BLOCK_DOUBLE && block_type != REGIONE_BLOCK_SINGLE) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: bad block type %d", block_type);
@@ -275,8 +300,13 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
     const bool dbl = block_type == REGIONE_BLOCK_DOUBLE;
     const int n_txt = dbl ? n_txt_fresh : 0;
     int rc;
-    if (n_fresh - n_txt > 0 && (rc = check_stream_weights(w->img, block_type, "image")) != REGIONE_OK) return rc;
-    if (n_txt > 0 && (rc = check_stream_weights(w->txt, block_type, "text")) != REGIONE_OK) return rc;
+    if (w8) {
+        if (n_fresh - n_txt > 0 && (rc = check_stream_weights_fp8(w8->img, "image")) != REGIONE_OK) return rc;
+        if (n_txt > 0 && (rc = check_stream_weights_fp8(w8->txt, "text")) != REGIONE_OK) return rc;
+    } else {
+        if (n_fresh - n_txt > 0 && (rc = check_stream_weights(w->img, block_type, "image")) != REGIONE_OK) return rc;
+        if (n_txt > 0 && (rc = check_stream_weights(w->txt, block_type, "text")) != REGIONE_OK) return rc;
+    }
     if (n_fresh == 0) return REGIONE_OK;
     if (!h_in || !h_out) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward: null hidden state");
 
@@ -313,7 +343,15 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
     // Text and image rows of a double-stream block go through different weights: until the attention joins them, and
     // again after it, the two groups are independent, so the text group runs on the context's second lane and the
     // workgroups of both fill the chip together (each group alone leaves part of its last round of tiles empty).
-    const bool two_lanes = groups[0].n > 0 && groups[1].n > 0 && !ctx->prof_on;
+    // (the 8-bit form keeps one lane: its groups share the workspace of the codes)
+    const bool two_lanes = groups[0].n > 0 && groups[1].n > 0 && !ctx->prof_on && !w8;
+    if (w8 && (rc = ensure_fp8_workspace(ctx)) != REGIONE_OK) return rc;
+    // copy of an intermediate into the caller's tap (8-bit form only), rows of the group at their place
+    auto tap = [&](void* dst, const void* src, size_t row0, size_t rows, size_t row_bytes) -> int {
+        if (!dst) return REGIONE_OK;
+        RG_HIP(hipMemcpyAsync(static_cast<char*>(dst) + row0 * row_bytes, src, rows * row_bytes, hipMemcpyDeviceToDevice, ctx->stream));
+        return REGIONE_OK;
+    };
     if (two_lanes && (rc = ensure_side_lane(ctx)) != REGIONE_OK) return rc;
 
     // ---- first half: LayerNorm + modulation, QKV (and MLP-in for single-stream) projection
@@ -324,14 +362,21 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
         LaneHalf half(ctx, two_lanes && &g == &groups[1]);
         const char* hin = static_cast<const char*>(h_in) + static_cast<size_t>(g.r0) * H * h_elem;
         char* u = ctx->u + static_cast<size_t>(g.r0) * H * es;
-        if ((rc = rg_layernorm_mod(ctx, hin, h_f32, g.n, H, g.w->shift1, g.w->scale1, u)) != REGIONE_OK) return rc;
+        const regione_stream_weights_fp8* g8 = w8 ? (&g == &groups[0] ? &w8->txt : &w8->img) : nullptr;
+        if (g8) rc = rg_layernorm_mod_fp8(ctx, hin, h_f32, g.n, H, g.w->shift1, g.w->scale1, ctx->q8, ctx->q8_scale);
+        else rc = rg_layernorm_mod(ctx, hin, h_f32, g.n, H, g.w->shift1, g.w->scale1, u);
+        if (rc != REGIONE_OK) return rc;
+        if (g8 && taps && ((rc = tap(taps->u1_codes, ctx->q8, g.r0, g.n, H)) != REGIONE_OK || (rc = tap(taps->u1_scale, ctx->q8_scale, g.r0, g.n, 4)) != REGIONE_OK)) return rc;
         GemmEpilogue ep = {};
         ep.kind = EPI_QKV; ep.hidden = H;
         ep.q = reinterpret_cast<bf16_t*>(ctx->q + static_cast<size_t>(g.r0) * H * es); ep.ldq = H;
         if (flags) { ep.k = reinterpret_cast<bf16_t*>(kc); ep.v = reinterpret_cast<bf16_t*>(vc); ep.slot = gemm_slots + g.r0; ep.slot_offset = slot_offset; }
         else { ep.k = reinterpret_cast<bf16_t*>(ctx->kf + static_cast<size_t>(g.r0) * H * es); ep.v = reinterpret_cast<bf16_t*>(ctx->vf + static_cast<size_t>(g.r0) * H * es); ep.slot = nullptr; }
         ep.ldkv = H;
-        if (dbl) {
+        if (g8) {
+            ep.bias = g.w->b_qkv; ep.row_scale = ctx->q8_scale; ep.col_scale = g8->s_qkv;
+            rc = rg_gemm_fp8(ctx, ctx->q8, H, static_cast<const uint8_t*>(g8->w_qkv), g.n, 3 * H, H, ep);
+        } else if (dbl) {
             ep.bias = g.w->b_qkv;
             rc = rg_gemm(ctx, u, H, g.w->w_qkv, g.n, 3 * H, H, ep);
         } else {
@@ -344,6 +389,7 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
         if (!ctx->f32) rc = rg_qk_norm_rope(ctx, ep.q, H, ep.k, H, flags ? slot_index + g.r0 : nullptr, slot_index ? slot_index + g.r0 : nullptr, g.r0, slot_offset, period, n_all, g.n, heads, D,
                              g.w->q_norm, g.w->k_norm, w->rope, w->rope_rows);
         if (rc != REGIONE_OK) return rc;
+        if (g8 && taps && (rc = tap(taps->q, ep.q, g.r0, g.n, static_cast<size_t>(H) * 2)) != REGIONE_OK) return rc;
     }
 
     if (two_lanes && (rc = lane_join(ctx)) != REGIONE_OK) return rc;
@@ -356,6 +402,8 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
         else rc = rg_attention(ctx, ctx->q + r0 * H, H, n_fresh, ctx->kf + r0 * H, ctx->vf + r0 * H, H, n_fresh, nullptr, nullptr, H, 0, nullptr, heads, D, 0.f, ctx->a + r0 * lda_attn, lda_attn);
         if (rc != REGIONE_OK) return rc;
     }
+
+    if (w8 && taps && (rc = tap(taps->attn, ctx->a, 0, n_fresh, static_cast<size_t>(H) * 2)) != REGIONE_OK) return rc;
 
     // ---- second half
     if (two_lanes && (rc = lane_fork(ctx)) != REGIONE_OK) return rc;
@@ -375,22 +423,42 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
             if ((rc = rg_gemm(ctx, a, lda_attn, g.w->w_2, g.n, H, H + M, ep)) != REGIONE_OK) return rc;
             continue;
         }
+        const regione_stream_weights_fp8* g8 = w8 ? (&g == &groups[0] ? &w8->txt : &w8->img) : nullptr;
         float* h1 = ctx->h1 + static_cast<size_t>(g.r0) * H;
         ep.bias = g.w->b_o; ep.gate = g.w->gate1;
         ep.resid = hin; ep.ldr = H; ep.resid_f32 = h_f32;
         ep.y = h1; ep.ldy = H; ep.y_f32 = 1;
-        if ((rc = rg_gemm(ctx, a, H, g.w->w_o, g.n, H, H, ep)) != REGIONE_OK) return rc;
         char* u = ctx->u + static_cast<size_t>(g.r0) * H * es;
-        if ((rc = rg_layernorm_mod(ctx, h1, 1, g.n, H, g.w->shift2, g.w->scale2, u)) != REGIONE_OK) return rc;
         char* m = ctx->m + static_cast<size_t>(g.r0) * M * es;
         GemmEpilogue up = {};
         up.kind = EPI_PLAIN; up.bias = g.w->b_1; up.act = REGIONE_ACT_GELU_TANH; up.act_from = 0;
         up.y = m; up.ldy = M; up.y_f32 = ctx->f32;
-        if ((rc = rg_gemm(ctx, u, H, g.w->w_1, g.n, M, H, up)) != REGIONE_OK) return rc;
         GemmEpilogue dn = {};
         dn.kind = EPI_RESID; dn.bias = g.w->b_2; dn.gate = g.w->gate2;
         dn.resid = h1; dn.ldr = H; dn.resid_f32 = 1;
         dn.y = hout; dn.ldy = H; dn.y_f32 = h_f32;
+        if (g8) {
+            // every projection's input rows become E4M3 codes with one scale per row in the shared workspace; the GEMM
+            // that follows on the stream consumes them before the next stage overwrites them
+            const uint8_t* q8 = ctx->q8;
+            ep.row_scale = up.row_scale = dn.row_scale = ctx->q8_scale;
+            ep.col_scale = g8->s_o; up.col_scale = g8->s_1; dn.col_scale = g8->s_2;
+            if ((rc = regione_quantize_rows_fp8(ctx, a, g.n, H, ctx->q8, ctx->q8_scale)) != REGIONE_OK) return rc;
+            if (taps && ((rc = tap(taps->a_codes, q8, g.r0, g.n, H)) != REGIONE_OK || (rc = tap(taps->a_scale, ctx->q8_scale, g.r0, g.n, 4)) != REGIONE_OK)) return rc;
+            if ((rc = rg_gemm_fp8(ctx, q8, H, static_cast<const uint8_t*>(g8->w_o), g.n, H, H, ep)) != REGIONE_OK) return rc;
+            if (taps && (rc = tap(taps->h1, h1, g.r0, g.n, static_cast<size_t>(H) * 4)) != REGIONE_OK) return rc;
+            if ((rc = rg_layernorm_mod_fp8(ctx, h1, 1, g.n, H, g.w->shift2, g.w->scale2, ctx->q8, ctx->q8_scale)) != REGIONE_OK) return rc;
+            if (taps && ((rc = tap(taps->u2_codes, q8, g.r0, g.n, H)) != REGIONE_OK || (rc = tap(taps->u2_scale, ctx->q8_scale, g.r0, g.n, 4)) != REGIONE_OK)) return rc;
+            if ((rc = rg_gemm_fp8(ctx, q8, H, static_cast<const uint8_t*>(g8->w_1), g.n, M, H, up)) != REGIONE_OK) return rc;
+            if (taps && (rc = tap(taps->m, m, g.r0, g.n, static_cast<size_t>(M) * 2)) != REGIONE_OK) return rc;
+            if ((rc = regione_quantize_rows_fp8(ctx, m, g.n, M, ctx->q8, ctx->q8_scale)) != REGIONE_OK) return rc;
+            if (taps && ((rc = tap(taps->m_codes, q8, g.r0, g.n, M)) != REGIONE_OK || (rc = tap(taps->m_scale, ctx->q8_scale, g.r0, g.n, 4)) != REGIONE_OK)) return rc;
+            if ((rc = rg_gemm_fp8(ctx, q8, M, static_cast<const uint8_t*>(g8->w_2), g.n, H, M, dn)) != REGIONE_OK) return rc;
+            continue;
+        }
+        if ((rc = rg_gemm(ctx, a, H, g.w->w_o, g.n, H, H, ep)) != REGIONE_OK) return rc;
+        if ((rc = rg_layernorm_mod(ctx, h1, 1, g.n, H, g.w->shift2, g.w->scale2, u)) != REGIONE_OK) return rc;
+        if ((rc = rg_gemm(ctx, u, H, g.w->w_1, g.n, M, H, up)) != REGIONE_OK) return rc;
         if ((rc = rg_gemm(ctx, m, M, g.w->w_2, g.n, H, M, dn)) != REGIONE_OK) return rc;
     }
     if (two_lanes && (rc = lane_join(ctx)) != REGIONE_OK) return rc;
@@ -402,6 +470,18 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
                                      int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
                                      void* k_cache, void* v_cache, int32_t n_all, int32_t flags) {
     return block_forward_impl(ctx, w, block_type, h_in, h_out, h_dtype, 1, n_fresh, n_txt_fresh, slot_index, slot_offset, k_cache, v_cache, n_all, flags);
+}
+
+extern "C" int regione_block_forward_fp8(regione_ctx* ctx, const regione_block_weights* w, const regione_block_weights_fp8* w8,
+                                         const void* h_in, void* h_out, int32_t h_dtype,
+                                         int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
+                                         void* k_cache, void* v_cache, int32_t n_all, int32_t flags, const regione_fp8_taps* taps_opt) {
+    if (!ctx || !w8) RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward_fp8: null context or weights");
+    if (ctx->f32) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "block_forward_fp8: the 8-bit projections belong to bf16 contexts");
+    if (ctx->dims.hidden > 4096 || (ctx->dims.hidden % 128) || (ctx->dims.mlp % 128))
+        RG_FAIL(REGIONE_ERR_UNSUPPORTED, "block_forward_fp8: hidden=%d (at most 4096) and mlp=%d must be multiples of 128", ctx->dims.hidden, ctx->dims.mlp);
+    return block_forward_impl(ctx, w, REGIONE_BLOCK_DOUBLE, h_in, h_out, h_dtype, 1, n_fresh, n_txt_fresh, slot_index, slot_offset, k_cache, v_cache, n_all, flags,
+                              w8, taps_opt);
 }
 
 extern "C" int regione_block_forward_batched(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,

@@ -31,6 +31,8 @@ struct regione_ctx {
     float* attn_part;  // split-KV partial results
     size_t attn_part_bytes;
     int32_t* slot_all; // [max_fresh] slot list of all branches of a batched block call
+    // workspace of the 8-bit block (allocated by its first call): codes of one projection's input rows and their scales
+    uint8_t* q8; size_t q8_bytes; float* q8_scale;
     float* gemm_part;  // split-K partial sums
     size_t gemm_part_bytes;
     // second lane for independent work inside one call (text and image rows of a double-stream block use different
@@ -109,6 +111,9 @@ int rg_gemm(regione_ctx* ctx, const void* a, int lda, const void* w_packed, int 
 int rg_gemm_velocity(regione_ctx* ctx, const void* a, int lda, const void* w_packed, int m, int n, int k, const GemmEpilogue& ep);
 int rg_gemm_f32(regione_ctx* ctx, const float* a, int lda, const float* w, int m, int n, int k, const GemmEpilogue& ep);
 // E4M3 operands (k counts 8-bit elements, a multiple of 128; lda in bytes, a multiple of 16); ep.row_scale / col_scale set
+// LayerNorm + modulation with the E4M3 row quantisation of its float32 result: codes [n, hidden], one scale per row
+int rg_layernorm_mod_fp8(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale,
+                         uint8_t* q, float* row_scale);
 int rg_gemm_fp8(regione_ctx* ctx, const uint8_t* a, int lda, const uint8_t* w_packed, int m, int n, int k, const GemmEpilogue& ep);
 int rg_layernorm_mod(regione_ctx* ctx, const void* h, int h_f32, int n, int hidden, const float* shift, const float* scale, void* u);   // u: compute dtype
 int rg_qk_norm_rope(regione_ctx* ctx, bf16_t* q, int ldq, bf16_t* k, int ldkv, const int32_t* kv_slot,

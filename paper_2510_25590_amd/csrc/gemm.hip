@@ -914,8 +914,17 @@ int dispatch(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m
 }
 
 
-// The 8-bit GEMM: 128-row LDS kernel only, plain epilogue.  k2 = K in pairs of E4M3 values (the kernel's unit).
-template <int TN>
+// the wide epilogue needs every eight-column group whole (n % 8, checked by the caller) and every touched row 16-byte aligned
+bool wide_epilogue_ok(const GemmEpilogue& ep, int n) {
+    if (ep.kind == EPI_PLAIN) return (ep.ldy % 8 == 0) && rg_aligned16(ep.y) && (ep.act_from % 8 == 0);
+    if (ep.kind == EPI_QKV) return (ep.hidden % 8 == 0) && (ep.ldq % 8 == 0) && (ep.ldkv % 8 == 0) && rg_aligned16(ep.q) && rg_aligned16(ep.k) && rg_aligned16(ep.v) &&
+                                   (n <= 3 * ep.hidden || ((ep.ldy % 8 == 0) && (ep.y_col0 % 8 == 0) && rg_aligned16(ep.y)));
+    if (ep.kind == EPI_RESID) return (ep.ldy % 8 == 0) && (ep.ldr % 8 == 0) && rg_aligned16(ep.y) && rg_aligned16(ep.resid);
+    return false;
+}
+
+// The 8-bit GEMM: 128-row LDS kernel only.  k2 = K in pairs of E4M3 values (the kernel's unit).
+template <int TN, int KIND>
 int launch_gemm_fp8(regione_ctx* ctx, const bf16_t* a, int lda2, const bf16_t* wp, int m, int n, int k2, int splits, const GemmEpilogue& ep) {
     constexpr int BN = 128 * TN;
     const int m_tiles = (m + BM - 1) / BM, n_tiles = (n + BN - 1) / BN;
@@ -929,12 +938,14 @@ int launch_gemm_fp8(regione_ctx* ctx, const bf16_t* a, int lda2, const bf16_t* w
     float* partial = used_splits > 1 ? ctx->gemm_part : nullptr;
     const int group_rows = m_tiles > 8 ? 4 : m_tiles;
     constexpr unsigned lds_bytes = LdsGemm<TN, 1>::LDS_BYTES;
-    constexpr uint32_t grant_bit = 1u << (12 + (TN - 1));   // bits 12-13
+    constexpr uint32_t grant_bit = 1u << (12 + (TN - 1));   // bits 12-13: one grant covers the three epilogue kinds of a width
     if (!(ctx->lds_grant_mask & grant_bit)) {
         RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel<TN, 1, EPI_PLAIN, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel<TN, 1, EPI_QKV, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
+        RG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_lds_kernel<TN, 1, EPI_RESID, true>), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)));
         ctx->lds_grant_mask |= grant_bit;
     }
-    hipLaunchKernelGGL((gemm_lds_kernel<TN, 1, EPI_PLAIN, true>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads), lds_bytes, ctx->stream,
+    hipLaunchKernelGGL((gemm_lds_kernel<TN, 1, KIND, true>), dim3(tiles_per_xcd * 8, used_splits), dim3(kThreads), lds_bytes, ctx->stream,
                        a, lda2, wp, m, n, k2, m_tiles, n_tiles, tiles_per_xcd, group_rows, per, partial, ep);
     RG_LAUNCH_CHECK();
     if (used_splits > 1) {
@@ -942,12 +953,12 @@ int launch_gemm_fp8(regione_ctx* ctx, const bf16_t* a, int lda2, const bf16_t* w
         const bool wide = ep.vec_ok && used_splits <= kMaxSplits && (!ep.bias || rg_aligned16(ep.bias));
         if (wide) {
             const int64_t blocks = (total / 4 + kThreads - 1) / kThreads;
-            hipLaunchKernelGGL((splitk_epilogue4_kernel<EPI_PLAIN>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+            hipLaunchKernelGGL((splitk_epilogue4_kernel<KIND>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
                                partial, used_splits, m, n, ep);
         } else {
             int64_t blocks = (total + kThreads - 1) / kThreads;
             if (blocks > 256 * 16) blocks = 256 * 16;
-            hipLaunchKernelGGL((splitk_epilogue_kernel<EPI_PLAIN>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
+            hipLaunchKernelGGL((splitk_epilogue_kernel<KIND>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, ctx->stream,
                                partial, used_splits, m, n, ep);
         }
         RG_LAUNCH_CHECK();
@@ -961,10 +972,11 @@ int rg_gemm_fp8(regione_ctx* ctx, const uint8_t* a, int lda, const uint8_t* wp, 
     if (m <= 0 || n <= 0) return REGIONE_OK;
     if (k <= 0 || (k % (2 * BK)) || (lda & 15)) RG_FAIL(REGIONE_ERR_BAD_SHAPE, "gemm_fp8: k=%d must be a positive multiple of 128 and lda=%d of 16", k, lda);
     if (!rg_aligned16(a) || !rg_aligned16(wp)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm_fp8: operands must be 16-byte aligned");
-    if (ep_in.kind != EPI_PLAIN || !ep_in.row_scale || !ep_in.col_scale) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm_fp8: plain epilogue with both scales only");
+    if (!ep_in.row_scale || !ep_in.col_scale) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm_fp8: both scales are needed");
+    if (ep_in.kind != EPI_PLAIN && ep_in.kind != EPI_QKV && ep_in.kind != EPI_RESID) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm_fp8: epilogue kind %d", ep_in.kind);
     ProfScope prof(ctx, REGIONE_PROF_GEMM);
     GemmEpilogue ep = ep_in;
-    ep.vec_ok = (n % 8 == 0) && (ep.ldy % 8 == 0) && rg_aligned16(ep.y) && (ep.act_from % 8 == 0) && rg_aligned16(ep.col_scale);
+    ep.vec_ok = (n % 8 == 0) && rg_aligned16(ep.col_scale) && wide_epilogue_ok(ep, n);
     const int k2 = k / 2, steps = k2 / BK;
     const int m_tiles = (m + BM - 1) / BM;
     // Wave tile: the wide one (fewer LDS bytes per MFMA) once it gives most CUs a workgroup; measured at 820 rows:
@@ -980,8 +992,11 @@ int rg_gemm_fp8(regione_ctx* ctx, const uint8_t* a, int lda, const uint8_t* wp, 
     if (ctx->gemm_force_splits > 0) splits = ctx->gemm_force_splits;
     const bf16_t* a2 = reinterpret_cast<const bf16_t*>(a);
     const bf16_t* w2 = reinterpret_cast<const bf16_t*>(wp);
-    if (tn == 1) return launch_gemm_fp8<1>(ctx, a2, lda / 2, w2, m, n, k2, splits, ep);
-    return launch_gemm_fp8<2>(ctx, a2, lda / 2, w2, m, n, k2, splits, ep);
+#define RG_FP8(KIND) (tn == 1 ? launch_gemm_fp8<1, KIND>(ctx, a2, lda / 2, w2, m, n, k2, splits, ep) : launch_gemm_fp8<2, KIND>(ctx, a2, lda / 2, w2, m, n, k2, splits, ep))
+    if (ep.kind == EPI_QKV) return RG_FP8(EPI_QKV);
+    if (ep.kind == EPI_RESID) return RG_FP8(EPI_RESID);
+    return RG_FP8(EPI_PLAIN);
+#undef RG_FP8
 }
 
 int rg_gemm_velocity(regione_ctx* ctx, const void* a_any, int lda, const void* wp_any, int m, int n, int k, const GemmEpilogue& ep_in) {
@@ -1005,12 +1020,7 @@ int rg_gemm(regione_ctx* ctx, const void* a_any, int lda, const void* wp_any, in
     if (!rg_aligned16(a) || !rg_aligned16(wp)) RG_FAIL(REGIONE_ERR_INVALID_ARG, "gemm: operands must be 16-byte aligned");
     ProfScope prof(ctx, REGIONE_PROF_GEMM);
     GemmEpilogue ep = ep_in;
-    // the wide epilogue needs every eight-column group whole and every touched row 16-byte aligned
-    ep.vec_ok = (n % 8 == 0);
-    if (ep.kind == EPI_PLAIN) ep.vec_ok = ep.vec_ok && (ep.ldy % 8 == 0) && rg_aligned16(ep.y) && (ep.act_from % 8 == 0);
-    if (ep.kind == EPI_QKV) ep.vec_ok = ep.vec_ok && (ep.hidden % 8 == 0) && (ep.ldq % 8 == 0) && (ep.ldkv % 8 == 0) && rg_aligned16(ep.q) &&
-                                        rg_aligned16(ep.k) && rg_aligned16(ep.v) && (n <= 3 * ep.hidden || ((ep.ldy % 8 == 0) && (ep.y_col0 % 8 == 0) && rg_aligned16(ep.y)));
-    if (ep.kind == EPI_RESID) ep.vec_ok = ep.vec_ok && (ep.ldy % 8 == 0) && (ep.ldr % 8 == 0) && rg_aligned16(ep.y) && rg_aligned16(ep.resid);
+    ep.vec_ok = (n % 8 == 0) && wide_epilogue_ok(ep, n);
     switch (ep.kind) {
         case EPI_PLAIN: return dispatch<EPI_PLAIN>(ctx, a, lda, wp, m, n, k, ep);
         case EPI_QKV: return dispatch<EPI_QKV>(ctx, a, lda, wp, m, n, k, ep);
