@@ -21,7 +21,12 @@ so no passage of the paper defines what is computed here.  What fixes it instead
 Parity pins (tests/test_oracle_fp8.py): code values the format's definition fixes, brute
 force nearest-value search with ties to even over the whole code table, the round trip of
 all codes, powers of two scaling, the error bound of a 3-bit mantissa, and exact integer
-matrix products.
+matrix products; e4m3_half_step against the gaps of the decoded code table.
+
+The 8-bit form of a whole block (regione_block_forward_fp8) has no reference of its own: it is checked stage by
+stage with the functions of this file and of regione_oracle.py on the library's own input of every stage
+(tests/test_gpu_block_fp8.py), because a block that quantises its own intermediates differs from any other
+implementation by whole code steps wherever an input sits on a rounding boundary.
 """
 from __future__ import annotations
 
@@ -61,6 +66,14 @@ def e4m3_encode(values) -> np.ndarray:
     code = np.where(is_sub, n2, (e2 + 7) * 8 + (n2 - 8)).astype(np.int64)
     assert np.all(code <= 0x7E), "clamped input cannot reach the NaN code"
     return (code | np.where(neg, 0x80, 0)).astype(np.uint8)
+
+
+def e4m3_half_step(values) -> np.ndarray:
+    """Half the distance between the neighbouring E4M3 values around |v| (|v| <= 448): what rounding to the format may
+    move a value by.  Spacing 2^(floor(log2 |v|) - 3) for normals, 2^-9 below 2^-6."""
+    a = np.maximum(np.abs(np.asarray(values, dtype=np.float64)), 2.0 ** -9)
+    e = np.maximum(np.floor(np.log2(a)), -6.0)
+    return np.exp2(e - 3.0) / 2.0
 
 
 def quantize_rows(x):

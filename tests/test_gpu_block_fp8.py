@@ -26,19 +26,12 @@ pytestmark = pytest.mark.gpu
 MFMA_SUM_ERR = 2.0 ** -11      # accumulation bound of the 8-bit matrix-core instruction (see test_gpu_fp8.py)
 
 
-def _e4m3_half_step(v):
-    """Half the distance between neighbouring E4M3 values around |v| (v in the scaled domain, |v| <= 448)."""
-    a = np.maximum(np.abs(v), 2.0 ** -9)
-    e = np.maximum(np.floor(np.log2(a)), -6.0)
-    return 2.0 ** (e - 3) / 2
-
-
 def _check_ln_quant(what, h_rows, shift, scale, codes, row_scale):
     y = orc.modulate(orc.layer_norm(h_rows), shift, scale)                       # float64
     amax = np.max(np.abs(y), axis=1)
     assert np.allclose(row_scale, amax / 448.0, rtol=2e-5, atol=0), f"{what}: row scales"
     deq = f8.e4m3_decode(codes) * row_scale[:, None].astype(np.float64)
-    tol = _e4m3_half_step(y / row_scale[:, None]) * row_scale[:, None] * 1.001 + np.abs(y) * 2e-5
+    tol = f8.e4m3_half_step(y / row_scale[:, None]) * row_scale[:, None] * 1.001 + np.abs(y) * 2e-5
     bad = np.abs(deq - y) > tol
     assert not bad.any(), f"{what}: {bad.sum()} dequantised values farther than half a code step from the float64 result"
     want_codes, _ = f8.quantize_rows(y.astype(np.float32))

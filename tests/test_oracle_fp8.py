@@ -74,6 +74,19 @@ def test_error_bound_of_three_mantissa_bits():
     assert np.max(np.abs(f8.e4m3_decode(f8.e4m3_encode(sub)) - sub)) <= 2.0 ** -10
 
 
+def test_half_step_equals_half_the_gap_of_the_code_table():
+    vals = f8.e4m3_decode(np.arange(0, 0x7F, dtype=np.uint8))        # 0 .. 448, increasing
+    gaps = np.diff(vals)
+    mid = (vals[:-1] + vals[1:]) / 2
+    assert np.array_equal(f8.e4m3_half_step(mid), gaps / 2)                      # anywhere inside a gap
+    assert np.array_equal(f8.e4m3_half_step(vals[1:-1] * 1.0001), gaps[1:] / 2)  # just above a code: the gap above it
+    assert np.array_equal(f8.e4m3_half_step(-mid), gaps / 2)
+    # rounding never moves a value by more than the half step there
+    x = np.random.default_rng(5).uniform(-448, 448, 20000).astype(np.float32)
+    err = np.abs(f8.e4m3_decode(f8.e4m3_encode(x)) - x.astype(np.float64))
+    assert np.all(err <= f8.e4m3_half_step(x))
+
+
 def test_quantize_rows_scale_and_codes():
     rng = np.random.default_rng(7)
     x = rng.normal(0, 1, (9, 64)).astype(np.float32)
