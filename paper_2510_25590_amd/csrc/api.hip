@@ -77,7 +77,8 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
         }
         c->n_edited_pinned = static_cast<int32_t*>(host);
         c->n_edited_pinned_dev = static_cast<int32_t*>(dev);
-        *c->n_edited_pinned = 0;
+        c->n_edited_pinned[0] = 0;      // the count ...
+        c->n_edited_pinned[1] = 0;      // ... and the ticket of the call it belongs to (recycled pinned memory may hold an old context's ticket)
     }
     if (rc == REGIONE_OK) rc = rg_partition_static_warm();   // so that regione_partition_static's first call has nothing to set up
     if (rc != REGIONE_OK) { free_all(c); delete c; return rc; }

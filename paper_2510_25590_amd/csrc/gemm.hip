@@ -897,6 +897,71 @@ int launch_gemm(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, in
     return REGIONE_OK;
 }
 
+// Results of at most 64 columns (the velocity head: hidden -> latent channels): a workgroup owns 32 rows x 32 columns,
+// its sixteen waves split K, fragments come straight from global memory (A rows as the MFMA's row operand, the packed
+// weights as they lie), the partial tiles meet in LDS and are added in wave order, and the epilogue runs on the sums.
+// Such a launch is a chain of memory round trips, not arithmetic: with K over sixteen waves a wave has all its loads
+// in flight at once (four waves per workgroup, twelve round trips each: 25 us at 820 x 64 x 3072 inside the step,
+// slower than the general kernel's K split + merge launch, 15 + 5 us).
+// KIND: EPI_PLAIN, or EPI_VELOCITY (the fresh region step's velocity cache, Euler update and latent merge).
+constexpr int kSkinnyWaves = 16;
+template <int KIND>
+__global__ void __launch_bounds__(kSkinnyWaves * 64)
+gemm_skinny_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ Wp, int M, int N, int K, GemmEpilogue ep) {
+    constexpr int LDR = 32;                      // row stride of a partial tile in LDS
+    __shared__ float red[kSkinnyWaves][32 * LDR];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int m0 = blockIdx.x * 32, nb = blockIdx.y;
+    const int steps = K >> 4, per = (steps + kSkinnyWaves - 1) / kSkinnyWaves;
+    const int s0 = wave * per;
+    const int s1 = s0 + per < steps ? s0 + per : steps;
+    int row = m0 + l32;
+    row = row < M ? row : M - 1;                 // rows past the end repeat the last one; their sums are not stored
+    const bf16_t* ap = A + static_cast<int64_t>(row) * lda + 8 * lh;
+    const bf16_t* wp = Wp + (static_cast<int64_t>(nb) * steps * 64 + lane) * 8;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    // all loads of a chunk of ten K-steps are issued before its first MFMA: one memory round trip per chunk
+    constexpr int CH = 10;
+    for (int base = s0; base < s1; base += CH) {
+        bf16x8 a[CH], w[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int sidx = base + i < s1 ? base + i : s1 - 1;     // past the end: a valid address, the product is dropped below
+            a[i] = *reinterpret_cast<const bf16x8*>(ap + sidx * 16);
+            w[i] = *reinterpret_cast<const bf16x8*>(wp + static_cast<int64_t>(sidx) * 512);
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+            if (base + i < s1) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], w[i], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][(8 * (r >> 2) + 4 * lh + (r & 3)) * LDR + l32] = acc[r];
+    __syncthreads();
+    {
+        const int i = threadIdx.x;               // 32 x 32 sums, one per thread
+        const int rr = i >> 5, cc = i & 31;
+        const int at = rr * LDR + cc;
+        float sum = red[0][at];
+#pragma unroll
+        for (int w = 1; w < kSkinnyWaves; ++w) sum += red[w][at];
+        const int grow = m0 + rr, gcol = nb * 32 + cc;
+        if (grow < M && gcol < N) epilogue_store<KIND>(ep, grow, grow, gcol, sum, ep.bias ? ep.bias[gcol] : 0.f, 1.f);
+    }
+}
+
+template <int KIND>
+int launch_gemm_skinny(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, const GemmEpilogue& ep) {
+    hipLaunchKernelGGL((gemm_skinny_kernel<KIND>), dim3(static_cast<unsigned>((m + 31) / 32), static_cast<unsigned>((n + 31) / 32)), dim3(kSkinnyWaves * 64), 0, ctx->stream,
+                       a, lda, wp, m, n, k, ep);
+    RG_LAUNCH_CHECK();
+    return REGIONE_OK;
+}
+// the shapes the small-N kernel takes: narrow results, unless a comparison forces a plan of the general kernels
+bool skinny_shape(const regione_ctx* ctx, int n) { return n <= 64 && ctx->gemm_force_tn == 0 && ctx->gemm_force_splits == 0; }
+
 template <int KIND>
 int dispatch(regione_ctx* ctx, const bf16_t* a, int lda, const bf16_t* wp, int m, int n, int k, const GemmEpilogue& ep) {
     GemmPlan p = plan_gemm(ctx, m, n, k);
@@ -1008,6 +1073,7 @@ int rg_gemm_velocity(regione_ctx* ctx, const void* a_any, int lda, const void* w
     ProfScope prof(ctx, REGIONE_PROF_GEMM);
     GemmEpilogue ep = ep_in;
     ep.kind = EPI_PLAIN; ep.merge_kind = EPI_VELOCITY; ep.vec_ok = 0;
+    if (skinny_shape(ctx, n)) return launch_gemm_skinny<EPI_VELOCITY>(ctx, static_cast<const bf16_t*>(a_any), lda, static_cast<const bf16_t*>(wp_any), m, n, k, ep);
     return dispatch<EPI_PLAIN>(ctx, static_cast<const bf16_t*>(a_any), lda, static_cast<const bf16_t*>(wp_any), m, n, k, ep);
 }
 
@@ -1021,6 +1087,7 @@ int rg_gemm(regione_ctx* ctx, const void* a_any, int lda, const void* wp_any, in
     ProfScope prof(ctx, REGIONE_PROF_GEMM);
     GemmEpilogue ep = ep_in;
     ep.vec_ok = (n % 8 == 0) && wide_epilogue_ok(ep, n);
+    if (ep.kind == EPI_PLAIN && skinny_shape(ctx, n)) return launch_gemm_skinny<EPI_PLAIN>(ctx, a, lda, wp, m, n, k, ep);
     switch (ep.kind) {
         case EPI_PLAIN: return dispatch<EPI_PLAIN>(ctx, a, lda, wp, m, n, k, ep);
         case EPI_QKV: return dispatch<EPI_QKV>(ctx, a, lda, wp, m, n, k, ep);
