@@ -624,7 +624,7 @@ def main():
         a_ms = prof["attention"][0] / args.steps
         ach = gemm_flops / (g_ms * 1e-3) / 1e12
         traffic = profiled_traffic() if n == 820 else {}     # the committed counter summaries were taken on the default workload
-        out["roofline"] = {"kernel": "gemm_bf16_kernel (5 launches per step: QKV, attention output, MLP up, MLP down, velocity head)",
+        out["roofline"] = {"kernel": "gemm_bf16_kernel (QKV, attention output, MLP up, MLP down) + gemm_skinny_kernel (velocity head): 5 launches per step",
                            "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
                            "traffic": traffic.get("gemm_bf16_kernel"),
                            "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE at the L2-fabric boundary, from profiles/*_hbm_traffic.txt)",
