@@ -410,7 +410,7 @@ int regione_scatter_pair(regione_ctx* ctx, void* dst_full_a, int32_t row_elems_a
                          void* dst_full_b, int32_t row_elems_b, int32_t dtype_b, const void* src_b,
                          const int32_t* index, const int32_t* n_dev, int64_t n_max);
 
-/* The velocity head of a fresh region step together with what Algorithm 1 does with its result, in two launches
+/* The velocity head of a fresh region step together with what Algorithm 1 does with its result, in one launch
  * instead of four: v = h_rows W^T + b (regione_linear), rounded to `dtype`; the velocity cache takes it and the edited
  * rows take their Euler step (regione_velocity_cache with reuse = 0: c_a = v, x_e -= dt * v, Eq.9 and Eq.4); and the
  * updated rows are written to x_full[index[i], :] (regione_scatter) when x_full_opt is given.  Results are those of the
