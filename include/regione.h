@@ -76,7 +76,9 @@ typedef struct regione_dims {
  * Modulation vectors [H] may be NULL (shift = scale = 0, gate = 1).
  * q_norm / k_norm [head_dim] float32, 16-byte aligned, or NULL: when given, every head of the
  * stream's queries / keys is divided by sqrt(mean(x^2) + 1e-6) and multiplied by the vector
- * (an extra of real editing transformers; the paper keeps the DiT a black box). */
+ * (an extra of real editing transformers; the paper keeps the DiT a black box).
+ * w_mod / b_mod: NULL, or the stream's modulation layer (bf16 ROW-MAJOR [6H, H] and float32 [6H]; single-stream blocks
+ * [3H, H] and [3H]); used when the block's `cond` is given, see regione_block_weights. */
 typedef struct regione_stream_weights {
     const void* w_qkv; const float* b_qkv;
     const void* w_o;   const float* b_o;
@@ -85,18 +87,25 @@ typedef struct regione_stream_weights {
     const float* shift1; const float* scale1; const float* gate1;
     const float* shift2; const float* scale2; const float* gate2;
     const float* q_norm; const float* k_norm;
+    const void* w_mod; const float* b_mod;
 } regione_stream_weights;
 
 /* rope: NULL, or the table written by regione_rope_table for ALL rope_rows positions of the
  * cached sequence [P | X | I].  Queries and keys of fresh row i are then rotated (after the
  * normalisation) by the angles of position slot_index[i] + slot_offset (of position i when
  * slot_index is NULL): a gathered token keeps the position it has in the full sequence, and
- * keys enter the cache rotated.  Positions outside [0, rope_rows) use the nearest table row. */
+ * keys enter the cache rotated.  Positions outside [0, rope_rows) use the nearest table row.
+ * cond: NULL, or the step's conditioning vector [H] float32 on the device.  Every stream that carries rows in the call
+ * and has a w_mod then gets its modulation vectors from it inside the block call, before anything else runs:
+ *   [shift1 | scale1 | gate1 | shift2 | scale2 | gate2] = w_mod silu(cond) + b_mod   (regione_vec_linear, SiLU on the
+ * input; single-stream blocks: the first three), into the context's workspace; the stream's six pointers are then
+ * ignored.  bf16 contexts only.  (The paper keeps this layer inside its black-box DiT.) */
 typedef struct regione_block_weights {
     regione_stream_weights txt; /* text rows of a double-stream block */
     regione_stream_weights img; /* image / reference rows; the only set of a single-stream block */
     const float* rope;
     int32_t rope_rows;
+    const float* cond;
 } regione_block_weights;
 
 /* State of the adaptive velocity decay cache between steps (host). */

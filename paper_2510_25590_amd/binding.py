@@ -43,7 +43,7 @@ class Dims(C.Structure):
 
 
 _STREAM_FIELDS = ("w_qkv", "b_qkv", "w_o", "b_o", "w_1", "b_1", "w_2", "b_2",
-                  "shift1", "scale1", "gate1", "shift2", "scale2", "gate2", "q_norm", "k_norm")
+                  "shift1", "scale1", "gate1", "shift2", "scale2", "gate2", "q_norm", "k_norm", "w_mod", "b_mod")
 
 
 class StreamWeights(C.Structure):
@@ -51,7 +51,7 @@ class StreamWeights(C.Structure):
 
 
 class BlockWeights(C.Structure):
-    _fields_ = [("txt", StreamWeights), ("img", StreamWeights), ("rope", C.c_void_p), ("rope_rows", C.c_int32)]
+    _fields_ = [("txt", StreamWeights), ("img", StreamWeights), ("rope", C.c_void_p), ("rope_rows", C.c_int32), ("cond", C.c_void_p)]
 
 
 _FP8_STREAM_FIELDS = ("w_qkv", "s_qkv", "w_o", "s_o", "w_1", "s_1", "w_2", "s_2")

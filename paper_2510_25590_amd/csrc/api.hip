@@ -18,7 +18,7 @@ int dev_alloc(T** p, size_t count) {
     return REGIONE_OK;
 }
 void free_all(regione_ctx* c) {
-    void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->slot_all, c->attn_part, c->gemm_part, c->q8, c->q8_scale};
+    void* ptrs[] = {c->part_counts, c->u, c->q, c->kf, c->vf, c->a, c->h1, c->m, c->slot_all, c->mod_ws, c->attn_part, c->gemm_part, c->q8, c->q8_scale};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     if (c->n_edited_pinned) (void)hipHostFree(c->n_edited_pinned);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
@@ -65,6 +65,7 @@ extern "C" int regione_create(regione_ctx** out, const regione_dims* dims, void*
     if (rc == REGIONE_OK) rc = dev_alloc(&c->h1, n * H);
     if (rc == REGIONE_OK) rc = dev_alloc(&c->m, n * M * es);
     if (rc == REGIONE_OK) rc = dev_alloc(&c->slot_all, n);
+    if (rc == REGIONE_OK) rc = dev_alloc(&c->mod_ws, static_cast<size_t>(12) * H);
     if (rc == REGIONE_OK) rc = dev_alloc(reinterpret_cast<char**>(&c->attn_part), c->attn_part_bytes);
     c->gemm_part_bytes = n > 0 ? static_cast<size_t>(128) << 20 : 0;
     if (rc == REGIONE_OK) rc = dev_alloc(reinterpret_cast<char**>(&c->gemm_part), c->gemm_part_bytes);
@@ -331,8 +332,21 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
     const int lda_attn = dbl ? H : H + M;   // single-stream: attention output and gelu(m) share rows of ctx->a
     char* kc = static_cast<char*>(k_cache);
     char* vc = static_cast<char*>(v_cache);
+    // modulation vectors formed here from the step's conditioning vector (one one-vector linear layer per stream)
+    regione_stream_weights sw[2] = {w->txt, w->img};
+    if (w->cond) {
+        if (ctx->f32) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "block_forward: forming the modulation vectors inside the call is a bf16-context feature");
+        const int n_vec = dbl ? 6 : 3;
+        for (int s = 0; s < 2; ++s) {
+            if (!sw[s].w_mod || (s == 0 ? n_txt : n_rows - n_txt) <= 0) continue;
+            float* mod = ctx->mod_ws + static_cast<size_t>(s) * 6 * H;
+            if ((rc = regione_vec_linear(ctx, w->cond, REGIONE_ACT_SILU, sw[s].w_mod, sw[s].b_mod, n_vec * H, H, mod)) != REGIONE_OK) return rc;
+            sw[s].shift1 = mod; sw[s].scale1 = mod + H; sw[s].gate1 = mod + 2 * H;
+            if (dbl) { sw[s].shift2 = mod + 3 * H; sw[s].scale2 = mod + 4 * H; sw[s].gate2 = mod + 5 * H; }
+        }
+    }
     struct Rows { int r0, n; const regione_stream_weights* w; };
-    const Rows groups[2] = {{0, n_txt, &w->txt}, {n_txt, n_rows - n_txt, &w->img}};
+    const Rows groups[2] = {{0, n_txt, &sw[0]}, {n_txt, n_rows - n_txt, &sw[1]}};
 
     // several branches: the projection's epilogue takes one slot per row, branch b's shifted by b * n_all cache rows
     const int32_t* gemm_slots = slot_index;

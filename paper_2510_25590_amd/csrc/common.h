@@ -31,6 +31,7 @@ struct regione_ctx {
     float* attn_part;  // split-KV partial results
     size_t attn_part_bytes;
     int32_t* slot_all; // [max_fresh] slot list of all branches of a batched block call
+    float* mod_ws;     // [2][6H] modulation vectors of the two streams when a block call forms them itself
     // workspace of the 8-bit block (allocated by its first call): codes of one projection's input rows and their scales
     uint8_t* q8; size_t q8_bytes; float* q8_scale;
     float* gemm_part;  // split-K partial sums

@@ -77,6 +77,68 @@ def test_modulation_vectors_feed_a_block(ctx):
     assert np.abs(mod.cpu().numpy() - want).max() <= 2e-5
 
 
+@pytest.mark.parametrize("kind", ["double", "single"])
+def test_block_forms_its_modulation_vectors_itself(kind):
+    """A block given the step's conditioning vector and each stream's modulation layer equals, bit for bit, the same block
+    given the six (three) vectors that regione_vec_linear makes of them; against the oracle's block with the oracle's
+    vectors it holds the block tolerance."""
+    from gpu_util import dev, host, assert_close, block_to_device
+    hidden, heads, d, mlp, n_txt, n_img = 256, 4, 64, 1024, 24, 200
+    n = n_txt + n_img
+    n_vec = 6 if kind == "double" else 3
+    rng = np.random.default_rng(4200 + n_vec)
+    streams = [inputs.stream_weights(rng, hidden, mlp, kind, "bf16", std=0.05) for _ in range(2 if kind == "double" else 1)]
+    cond = rng.standard_normal(hidden).astype(np.float32)
+    mods = [(inputs.bf16_round((rng.standard_normal((n_vec * hidden, hidden)) / 64).astype(np.float32)), (0.1 * rng.standard_normal(n_vec * hidden)).astype(np.float32))
+            for _ in streams]
+    names = ("shift1", "scale1", "gate1", "shift2", "scale2", "gate2")[:n_vec]
+    for w, (wm, bm) in zip(streams, mods):          # the oracle's vectors for the oracle's block
+        vec = orc.vec_linear(cond, wm, bm, "silu")
+        for i, name in enumerate(names):
+            w[name] = vec[i * hidden:(i + 1) * hidden].astype(np.float32)
+        if kind == "double":
+            w["gate1"] = w["gate1"] + 1.0; w["gate2"] = w["gate2"] + 1.0      # gates near one, as in the synthetic model
+        else:
+            w["gate1"] = w["gate1"] + 1.0
+    for (wm, bm), w in zip(mods, streams):          # the same shift of the gates through the layer's bias
+        for i, name in enumerate(names):
+            if name.startswith("gate"):
+                bm[i * hidden:(i + 1) * hidden] += 1.0
+    h = inputs.bf16_round(rng.standard_normal((n, hidden)).astype(np.float32))
+    n_txt_rows = n_txt if kind == "double" else 0
+    want = orc.block_forward(streams, kind, h, n_txt_rows, None, None, None, 0, heads)
+    ctx = rg.Context(hidden, heads, d, mlp, n, 64)
+    btype = rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE
+    # (a) vectors made by the caller with regione_vec_linear
+    dcond = torch.from_numpy(cond).cuda()
+    bw, keep = block_to_device(streams, kind, ctx)
+    made = []
+    for s_i, (wm, bm) in enumerate(mods):
+        vec = torch.empty(n_vec * hidden, dtype=torch.float32, device="cuda")
+        wmd, bmd = torch.from_numpy(wm).to(torch.bfloat16).cuda(), torch.from_numpy(bm).cuda()
+        rg.regione_vec_linear(ctx, dcond, rg.ACT_SILU, wmd, bmd, n_vec * hidden, hidden, vec)
+        made.append((vec, wmd, bmd))
+        sw = bw.img if (kind == "single" or s_i == 1) else bw.txt
+        for i, name in enumerate(names):
+            setattr(sw, name, vec.data_ptr() + 4 * i * hidden)
+    out_a = torch.empty((n, hidden), dtype=torch.bfloat16, device="cuda")
+    rg.regione_block_forward(ctx, bw, btype, dev(h, "bf16"), out_a, rg.BF16, n, n_txt_rows, None, 0, None, None, 0, 0)
+    # (b) the block forms them itself; its own six pointers hold nonsense that must not be read
+    junk = torch.full((hidden,), 1e30, dtype=torch.float32, device="cuda")
+    for s_i, (vec, wmd, bmd) in enumerate(made):
+        sw = bw.img if (kind == "single" or s_i == 1) else bw.txt
+        for name in names:
+            setattr(sw, name, junk.data_ptr())
+        sw.w_mod, sw.b_mod = wmd.data_ptr(), bmd.data_ptr()
+    bw.cond = dcond.data_ptr()
+    out_b = torch.empty_like(out_a)
+    rg.regione_block_forward(ctx, bw, btype, dev(h, "bf16"), out_b, rg.BF16, n, n_txt_rows, None, 0, None, None, 0, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a.view(torch.int16), out_b.view(torch.int16))
+    assert_close(host(out_b), want, f"{kind} block with modulation vectors formed inside the call", stored_bf16=True)
+    ctx.close()
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("n_vec,elems", [(28 * 3, 4096 * 64), (5, 8), (3, 1000), (1, 0)])
 def test_sq_norms_match_float64_sums(ctx, dtype, n_vec, elems):
