@@ -379,7 +379,7 @@ def fp8_block(torch, rg, steps: int, warmup: int):
     out16 = torch.empty((n, cfg.hidden), dtype=torch.bfloat16, device="cuda"); out8 = torch.empty_like(out16)
     h_e = wl.h_e[:n].clone()
     run16 = lambda: rg.regione_block_forward(ctx, wl.weights, wl.block_type, h_e, out16, rg.BF16, n, 0, wl.e_index, cfg.n_txt, wl.k_cache, wl.v_cache, wl.n_all, rg.FLAG_RETRIEVE)
-    run8 = lambda: rg.regione_block_forward_fp8(ctx, wl.weights, w8, h_e, out8, rg.BF16, n, 0, wl.e_index, cfg.n_txt, wl.k_cache, wl.v_cache, wl.n_all, rg.FLAG_RETRIEVE)
+    run8 = lambda: rg.regione_block_forward_fp8(ctx, wl.weights, w8, wl.block_type, h_e, out8, rg.BF16, n, 0, wl.e_index, cfg.n_txt, wl.k_cache, wl.v_cache, wl.n_all, rg.FLAG_RETRIEVE)
     res = {"rows": int(n), "keys_per_query": wl.n_all}
     for rnd in range(2):
         for name, fn in (("bf16", run16), ("fp8", run8)):

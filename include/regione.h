@@ -439,7 +439,7 @@ int regione_velocity_head(regione_ctx* ctx, const void* h_rows, const void* w_he
 int regione_euler_rows(regione_ctx* ctx, void* x_full, const void* v_full, const int32_t* index, const int32_t* n_dev,
                        int64_t n_max, int32_t c, int32_t dtype, float dt);
 
-/* regione_block_forward for a double-stream block with its four dense projections in 8-bit floating point (the
+/* regione_block_forward with the block's dense projections in 8-bit floating point (the
  * E4M3 variant above: an extension with its own accuracy, selected only by calling this entry point).  Arguments as in
  * regione_block_forward; `w` supplies biases and modulation vectors (its bf16 weight pointers are not read), `w8` the
  * quantised weights: per stream and projection the packed codes (regione_pack_weight_fp8) and one float32 scale per
@@ -449,13 +449,17 @@ int regione_euler_rows(regione_ctx* ctx, void* x_full, const void* v_full, const
  *   - the attention output and the activated MLP rows (bf16 as in the bf16 block), by regione_quantize_rows_fp8's
  *     kernel.
  * Everything else — attention, K/V cache (bf16), gates, residual stream, flags, slots — is the bf16 block's.
- * Restrictions: bf16 context, block_type REGIONE_BLOCK_DOUBLE, hidden <= 4096, hidden and mlp multiples of 128.
+ * A single-stream block has two projections: w_1 [3H+M, H] and w_2 [H, H+M] (w_qkv, w_o unused); the input of the
+ * second is the joint row [attention | GELU(m)] of H + M columns, quantised as one row.
+ * Restrictions: bf16 context, hidden <= 4096, hidden and mlp multiples of 128, hidden + mlp <= 16384 for single-stream
+ * blocks; one guidance branch per call.
  * taps_opt (verification aid): when given, every non-null member receives a copy of that intermediate as the library
  * computed it, rows in the order of h_in, so that each stage can be checked against a reference fed with the
  * library's own input of that stage:
  *   u1_codes [n, H] uint8, u1_scale [n] (input of the QKV projection);   q [n, H] bf16 (its query rows);
  *   attn [n, H] bf16;   a_codes [n, H], a_scale [n] (input of the output projection);   h1 [n, H] float32;
- *   u2_codes [n, H], u2_scale [n] (input of MLP up);   m [n, M] bf16;   m_codes [n, M], m_scale [n]. */
+ *   u2_codes [n, H], u2_scale [n] (input of MLP up);   m [n, M] bf16;   m_codes [n, M], m_scale [n].
+ * Single-stream blocks: attn [n, H+M] (the joint row), a_codes [n, H+M], a_scale; h1, u2_*, m, m_* are not written. */
 typedef struct regione_stream_weights_fp8 {
     const void* w_qkv; const float* s_qkv;   /* codes packed from [3H, H]; scales [3H] */
     const void* w_o;   const float* s_o;     /* [H, H];  [H]  */
@@ -467,7 +471,7 @@ typedef struct regione_fp8_taps {
     void* u1_codes; float* u1_scale; void* q; void* attn; void* a_codes; float* a_scale; float* h1;
     void* u2_codes; float* u2_scale; void* m; void* m_codes; float* m_scale;
 } regione_fp8_taps;
-int regione_block_forward_fp8(regione_ctx* ctx, const regione_block_weights* w, const regione_block_weights_fp8* w8,
+int regione_block_forward_fp8(regione_ctx* ctx, const regione_block_weights* w, const regione_block_weights_fp8* w8, int32_t block_type,
                               const void* h_in, void* h_out, int32_t h_dtype,
                               int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
                               void* k_cache, void* v_cache, int32_t n_all, int32_t flags, const regione_fp8_taps* taps_opt);

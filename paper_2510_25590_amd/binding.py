@@ -140,7 +140,7 @@ def lib() -> C.CDLL:
             "regione_scatter_pair": [vp, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, i64],
             "regione_velocity_head": [vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, i32],
             "regione_region_step": [vp, C.POINTER(RegionStepArgs), C.POINTER(i32)],
-            "regione_block_forward_fp8": [vp, C.POINTER(BlockWeights), C.POINTER(BlockWeightsFp8), vp, vp, i32, i32, i32, vp, i32, vp, vp, i32, i32,
+            "regione_block_forward_fp8": [vp, C.POINTER(BlockWeights), C.POINTER(BlockWeightsFp8), i32, vp, vp, i32, i32, i32, vp, i32, vp, vp, i32, i32,
                                           C.POINTER(Fp8Taps)],
             "regione_partition_static": [vp, vp, vp, vp, i64, i32, i32, f32, f32, vp, vp, vp, vp, vp],
             "regione_gamma_fit_host": [C.POINTER(C.c_double), i32, C.POINTER(f32), i32, C.POINTER(f32)],
@@ -261,9 +261,9 @@ def regione_block_forward(ctx, weights: BlockWeights, block_type, h_in, h_out, h
                                        n_txt_fresh, _p(slot_index), slot_offset, _p(k_cache), _p(v_cache), n_all, flags))
 
 
-def regione_block_forward_fp8(ctx, weights: BlockWeights, weights8: BlockWeightsFp8, h_in, h_out, h_dtype, n_fresh, n_txt_fresh,
+def regione_block_forward_fp8(ctx, weights: BlockWeights, weights8: BlockWeightsFp8, block_type, h_in, h_out, h_dtype, n_fresh, n_txt_fresh,
                               slot_index, slot_offset, k_cache, v_cache, n_all, flags, taps: "Fp8Taps | None" = None):
-    _check(lib().regione_block_forward_fp8(ctx.handle, C.byref(weights), C.byref(weights8), _p(h_in), _p(h_out), h_dtype, n_fresh, n_txt_fresh,
+    _check(lib().regione_block_forward_fp8(ctx.handle, C.byref(weights), C.byref(weights8), block_type, _p(h_in), _p(h_out), h_dtype, n_fresh, n_txt_fresh,
                                            _p(slot_index), slot_offset, _p(k_cache), _p(v_cache), n_all, flags,
                                            None if taps is None else C.byref(taps)))
 
@@ -275,6 +275,8 @@ def make_stream_weights_fp8(ctx, tensors: dict):
     import torch
     w8, keep = StreamWeightsFp8(), {}
     for name in ("w_qkv", "w_o", "w_1", "w_2"):
+        if name not in tensors:          # a single-stream block has w_1 and w_2 only
+            continue
         w = tensors[name].contiguous()
         n, k = w.shape
         codes = torch.empty((n, k), dtype=torch.uint8, device=w.device)

@@ -237,17 +237,18 @@ struct LaneHalf {
     ~LaneHalf() { if (on) c->gemm_part_bytes = bytes; }
 };
 
-int check_stream_weights_fp8(const regione_stream_weights_fp8& w, const char* which) {
-    if (!w.w_qkv || !w.w_o || !w.w_1 || !w.w_2 || !w.s_qkv || !w.s_o || !w.s_1 || !w.s_2)
+int check_stream_weights_fp8(const regione_stream_weights_fp8& w, int block_type, const char* which) {
+    const bool dbl = block_type == REGIONE_BLOCK_DOUBLE;
+    if (!w.w_1 || !w.w_2 || !w.s_1 || !w.s_2 || (dbl && (!w.w_qkv || !w.w_o || !w.s_qkv || !w.s_o)))
         RG_FAIL(REGIONE_ERR_INVALID_ARG, "block_forward_fp8: null weight or scale in the %s stream", which);
     return REGIONE_OK;
 }
 
-// Codes of one projection's input rows ([max_fresh, max(H, M)] bytes) and their row scales: allocated by the first
+// Codes of one projection's input rows ([max_fresh, H + M] bytes) and their row scales: allocated by the first
 // 8-bit block call of a context, freed with it.
 int ensure_fp8_workspace(regione_ctx* ctx) {
     if (ctx->q8) return REGIONE_OK;
-    const size_t cols = static_cast<size_t>(ctx->dims.hidden > ctx->dims.mlp ? ctx->dims.hidden : ctx->dims.mlp);
+    const size_t cols = static_cast<size_t>(ctx->dims.hidden) + ctx->dims.mlp;    // the joint row of a single-stream block
     const size_t rows = static_cast<size_t>(ctx->dims.max_fresh);
     if (rows == 0) return REGIONE_OK;
     RG_HIP(hipMalloc(reinterpret_cast<void**>(&ctx->q8), rows * cols));
@@ -274,7 +275,7 @@ int check_stream_weights(const regione_stream_weights& w, int block_type, const 
 // set of weights: rows [b*n_fresh, (b+1)*n_fresh) of h and cache rows [b*n_all, (b+1)*n_all) belong to branch b; slots
 // and positions are shared.  When no text row is fresh (or the block is single-stream) all branches' rows form ONE
 // row group, so every projection is one GEMM over n_branches*n_fresh rows; attention runs per branch.
-// w8 != null: the 8-bit form of the four projections of a double-stream block (regione_block_forward_fp8); `taps`
+// w8 != null: the 8-bit form of the block's projections (regione_block_forward_fp8); `taps`
 // then names the places that receive copies of the intermediates.
 static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, int32_t block_type,
                               const void* h_in, void* h_out, int32_t h_dtype, int32_t n_branches,
@@ -303,8 +304,8 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
     const int n_txt = dbl ? n_txt_fresh : 0;
     int rc;
     if (w8) {
-        if (n_fresh - n_txt > 0 && (rc = check_stream_weights_fp8(w8->img, "image")) != REGIONE_OK) return rc;
-        if (n_txt > 0 && (rc = check_stream_weights_fp8(w8->txt, "text")) != REGIONE_OK) return rc;
+        if (n_fresh - n_txt > 0 && (rc = check_stream_weights_fp8(w8->img, block_type, "image")) != REGIONE_OK) return rc;
+        if (n_txt > 0 && (rc = check_stream_weights_fp8(w8->txt, block_type, "text")) != REGIONE_OK) return rc;
     } else {
         if (n_fresh - n_txt > 0 && (rc = check_stream_weights(w->img, block_type, "image")) != REGIONE_OK) return rc;
         if (n_txt > 0 && (rc = check_stream_weights(w->txt, block_type, "text")) != REGIONE_OK) return rc;
@@ -388,9 +389,13 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
         if (flags) { ep.k = reinterpret_cast<bf16_t*>(kc); ep.v = reinterpret_cast<bf16_t*>(vc); ep.slot = gemm_slots + g.r0; ep.slot_offset = slot_offset; }
         else { ep.k = reinterpret_cast<bf16_t*>(ctx->kf + static_cast<size_t>(g.r0) * H * es); ep.v = reinterpret_cast<bf16_t*>(ctx->vf + static_cast<size_t>(g.r0) * H * es); ep.slot = nullptr; }
         ep.ldkv = H;
-        if (g8) {
+        if (g8 && dbl) {
             ep.bias = g.w->b_qkv; ep.row_scale = ctx->q8_scale; ep.col_scale = g8->s_qkv;
             rc = rg_gemm_fp8(ctx, ctx->q8, H, static_cast<const uint8_t*>(g8->w_qkv), g.n, 3 * H, H, ep);
+        } else if (g8) {
+            ep.bias = g.w->b_1; ep.act = REGIONE_ACT_GELU_TANH; ep.row_scale = ctx->q8_scale; ep.col_scale = g8->s_1;
+            ep.y = ctx->a + static_cast<size_t>(g.r0) * lda_attn * es; ep.ldy = lda_attn; ep.y_col0 = H; ep.y_f32 = 0;
+            rc = rg_gemm_fp8(ctx, ctx->q8, H, static_cast<const uint8_t*>(g8->w_1), g.n, 3 * H + M, H, ep);
         } else if (dbl) {
             ep.bias = g.w->b_qkv;
             rc = rg_gemm(ctx, u, H, g.w->w_qkv, g.n, 3 * H, H, ep);
@@ -418,7 +423,7 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
         if (rc != REGIONE_OK) return rc;
     }
 
-    if (w8 && taps && (rc = tap(taps->attn, ctx->a, 0, n_fresh, static_cast<size_t>(H) * 2)) != REGIONE_OK) return rc;
+    if (w8 && taps && (rc = tap(taps->attn, ctx->a, 0, n_fresh, static_cast<size_t>(lda_attn) * 2)) != REGIONE_OK) return rc;
 
     // ---- second half
     if (two_lanes && (rc = lane_fork(ctx)) != REGIONE_OK) return rc;
@@ -431,14 +436,22 @@ static int block_forward_impl(regione_ctx* ctx, const regione_block_weights* w, 
         const char* a = ctx->a + static_cast<size_t>(g.r0) * lda_attn * es;
         GemmEpilogue ep = {};
         ep.kind = EPI_RESID;
+        const regione_stream_weights_fp8* g8 = w8 ? (&g == &groups[0] ? &w8->txt : &w8->img) : nullptr;
         if (!dbl) {
             ep.bias = g.w->b_2; ep.gate = g.w->gate1;
             ep.resid = hin; ep.ldr = H; ep.resid_f32 = h_f32;
             ep.y = hout; ep.ldy = H; ep.y_f32 = h_f32;
-            if ((rc = rg_gemm(ctx, a, lda_attn, g.w->w_2, g.n, H, H + M, ep)) != REGIONE_OK) return rc;
+            if (g8) {     // the joint row [attention | GELU(m)] becomes one row of codes
+                ep.row_scale = ctx->q8_scale; ep.col_scale = g8->s_2;
+                if ((rc = regione_quantize_rows_fp8(ctx, a, g.n, H + M, ctx->q8, ctx->q8_scale)) != REGIONE_OK) return rc;
+                if (taps && ((rc = tap(taps->a_codes, ctx->q8, g.r0, g.n, static_cast<size_t>(H) + M)) != REGIONE_OK || (rc = tap(taps->a_scale, ctx->q8_scale, g.r0, g.n, 4)) != REGIONE_OK)) return rc;
+                rc = rg_gemm_fp8(ctx, ctx->q8, H + M, static_cast<const uint8_t*>(g8->w_2), g.n, H, H + M, ep);
+            } else {
+                rc = rg_gemm(ctx, a, lda_attn, g.w->w_2, g.n, H, H + M, ep);
+            }
+            if (rc != REGIONE_OK) return rc;
             continue;
         }
-        const regione_stream_weights_fp8* g8 = w8 ? (&g == &groups[0] ? &w8->txt : &w8->img) : nullptr;
         float* h1 = ctx->h1 + static_cast<size_t>(g.r0) * H;
         ep.bias = g.w->b_o; ep.gate = g.w->gate1;
         ep.resid = hin; ep.ldr = H; ep.resid_f32 = h_f32;
@@ -487,7 +500,7 @@ extern "C" int regione_block_forward(regione_ctx* ctx, const regione_block_weigh
     return block_forward_impl(ctx, w, block_type, h_in, h_out, h_dtype, 1, n_fresh, n_txt_fresh, slot_index, slot_offset, k_cache, v_cache, n_all, flags);
 }
 
-extern "C" int regione_block_forward_fp8(regione_ctx* ctx, const regione_block_weights* w, const regione_block_weights_fp8* w8,
+extern "C" int regione_block_forward_fp8(regione_ctx* ctx, const regione_block_weights* w, const regione_block_weights_fp8* w8, int32_t block_type,
                                          const void* h_in, void* h_out, int32_t h_dtype,
                                          int32_t n_fresh, int32_t n_txt_fresh, const int32_t* slot_index, int32_t slot_offset,
                                          void* k_cache, void* v_cache, int32_t n_all, int32_t flags, const regione_fp8_taps* taps_opt) {
@@ -495,7 +508,9 @@ extern "C" int regione_block_forward_fp8(regione_ctx* ctx, const regione_block_w
     if (ctx->f32) RG_FAIL(REGIONE_ERR_UNSUPPORTED, "block_forward_fp8: the 8-bit projections belong to bf16 contexts");
     if (ctx->dims.hidden > 4096 || (ctx->dims.hidden % 128) || (ctx->dims.mlp % 128))
         RG_FAIL(REGIONE_ERR_UNSUPPORTED, "block_forward_fp8: hidden=%d (at most 4096) and mlp=%d must be multiples of 128", ctx->dims.hidden, ctx->dims.mlp);
-    return block_forward_impl(ctx, w, REGIONE_BLOCK_DOUBLE, h_in, h_out, h_dtype, 1, n_fresh, n_txt_fresh, slot_index, slot_offset, k_cache, v_cache, n_all, flags,
+    if (block_type == REGIONE_BLOCK_SINGLE && ctx->dims.hidden + ctx->dims.mlp > 16384)
+        RG_FAIL(REGIONE_ERR_UNSUPPORTED, "block_forward_fp8: a single-stream block's joint row of %d columns exceeds the row quantiser's 16384", ctx->dims.hidden + ctx->dims.mlp);
+    return block_forward_impl(ctx, w, block_type, h_in, h_out, h_dtype, 1, n_fresh, n_txt_fresh, slot_index, slot_offset, k_cache, v_cache, n_all, flags,
                               w8, taps_opt);
 }
 

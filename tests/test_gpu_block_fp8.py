@@ -105,7 +105,7 @@ def test_block_fp8_stage_by_stage(hidden, heads, d, mlp, n_txt, n_img, n_e, h_dt
          "h1": torch.zeros((n, hidden), dtype=torch.float32, device="cuda"), "u2_codes": z8(hidden), "u2_scale": zf(),
          "m": torch.zeros((n, mlp), dtype=torch.bfloat16, device="cuda"), "m_codes": z8(mlp), "m_scale": zf()}
     out = torch.empty((n, hidden), dtype=tdt, device="cuda")
-    rg.regione_block_forward_fp8(ctx, bw, w8, dev(h_in, h_dtype), out, hcode, n, n_txt_fresh, dslots, 0,
+    rg.regione_block_forward_fp8(ctx, bw, w8, rg.BLOCK_DOUBLE, dev(h_in, h_dtype), out, hcode, n, n_txt_fresh, dslots, 0,
                                  kc if flags else None, vc if flags else None, n_all if flags else 0, flags, rg.make_fp8_taps(t))
     torch.cuda.synchronize()
     T = {k: (v.cpu().numpy() if v.dtype != torch.bfloat16 else host(v)) for k, v in t.items()}
@@ -163,17 +163,73 @@ def test_block_fp8_stage_by_stage(hidden, heads, d, mlp, n_txt, n_img, n_e, h_dt
     ctx.close()
 
 
+@pytest.mark.parametrize("hidden,heads,d,mlp,n_txt,n_img,n_e", [(256, 4, 64, 1024, 32, 256, 36), (1024, 8, 128, 4096, 64, 400, 333)])
+@pytest.mark.parametrize("mode", ["retrieve", "store"])
+def test_single_stream_block_fp8_stage_by_stage(hidden, heads, d, mlp, n_txt, n_img, n_e, mode):
+    """The single-stream form: one projection [q | k | v | m] from the quantised LayerNorm result, attention, the joint
+    row [attention | GELU(m)] quantised as one row, one projection back with the gated residual."""
+    n_all = n_txt + 2 * n_img
+    H = hidden
+    rng = np.random.default_rng(inputs.workload_seed(9, hidden + n_e))
+    w = inputs.stream_weights(rng, hidden, mlp, "single", "bf16", std=0.03)
+    h_all = inputs.bf16_round(rng.standard_normal((n_all, hidden)).astype(np.float32))
+    ctx = rg.Context(hidden, heads, d, mlp, n_all, 4096)
+    bw, keep = block_to_device([w], "single", ctx)
+    w8 = rg.BlockWeightsFp8()
+    w8.img, keep8 = rg.make_stream_weights_fp8(ctx, {k: dev(v, "bf16") for k, v in w.items() if k.startswith("w_")})
+    q8 = {k: (t[2].cpu().numpy(), t[1].cpu().numpy()) for k, t in keep8.items()}
+    kc = torch.zeros((n_all, heads, d), dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
+    slots_all = torch.arange(n_all, dtype=torch.int32, device="cuda")
+    tmp = torch.empty((n_all, hidden), dtype=torch.bfloat16, device="cuda")
+    rg.regione_block_forward(ctx, bw, rg.BLOCK_SINGLE, dev(h_all, "bf16"), tmp, rg.BF16, n_all, 0, slots_all, 0, kc, vc, n_all, rg.FLAG_STORE)
+    h_moved = inputs.bf16_round((h_all + 0.05 * rng.standard_normal(h_all.shape)).astype(np.float32))
+    if mode == "retrieve":
+        rows, flags = (n_txt + np.sort(rng.choice(n_img, size=n_e, replace=False))).astype(np.int32), rg.FLAG_RETRIEVE
+    else:
+        rows, flags = np.arange(n_all, dtype=np.int32), rg.FLAG_STORE
+    n = len(rows)
+    h_in = h_moved[rows]
+    kc_before = kc.clone()
+    t = {"u1_codes": torch.full((n, H), 0x55, dtype=torch.uint8, device="cuda"), "u1_scale": torch.full((n,), -1.0, device="cuda"),
+         "q": torch.zeros((n, H), dtype=torch.bfloat16, device="cuda"), "attn": torch.zeros((n, H + mlp), dtype=torch.bfloat16, device="cuda"),
+         "a_codes": torch.full((n, H + mlp), 0x55, dtype=torch.uint8, device="cuda"), "a_scale": torch.full((n,), -1.0, device="cuda")}
+    out = torch.empty((n, hidden), dtype=torch.bfloat16, device="cuda")
+    rg.regione_block_forward_fp8(ctx, bw, w8, rg.BLOCK_SINGLE, dev(h_in, "bf16"), out, rg.BF16, n, 0, torch.from_numpy(rows).cuda(), 0,
+                                 kc, vc, n_all, flags, rg.make_fp8_taps(t))
+    torch.cuda.synchronize()
+    T = {k: (v.cpu().numpy() if v.dtype != torch.bfloat16 else host(v)) for k, v in t.items()}
+    kc_h, vc_h = host(kc).reshape(n_all, hidden), host(vc).reshape(n_all, hidden)
+    _check_ln_quant("LayerNorm", h_in, w["shift1"], w["scale1"], T["u1_codes"], T["u1_scale"])
+    c1, s1 = q8["w_1"]
+    args = (T["u1_codes"], T["u1_scale"], c1, s1, w["b_1"])
+    _check_linear("queries", *args, T["q"], out_bf16=True, cols=slice(0, H))
+    _check_linear("keys", *args, kc_h[rows], out_bf16=True, cols=slice(H, 2 * H))
+    _check_linear("values", *args, vc_h[rows], out_bf16=True, cols=slice(2 * H, 3 * H))
+    _check_linear("MLP part + GELU", *args, T["attn"][:, H:], post=lambda lin, b: (orc.gelu_tanh(lin), 1.13 * b), out_bf16=True, cols=slice(3 * H, 3 * H + mlp))
+    untouched = np.setdiff1d(np.arange(n_all), rows)
+    assert torch.equal(kc[untouched].view(torch.int16), kc_before[untouched].view(torch.int16))
+    keys = np.arange(n_all) if flags == rg.FLAG_RETRIEVE else rows
+    want_attn = orc.attention_kvcache(T["q"].reshape(n, heads, d), kc_h.reshape(n_all, heads, d)[keys], vc_h.reshape(n_all, heads, d)[keys])
+    assert_close(T["attn"][:, :H], want_attn.reshape(n, hidden), "attention on the library's queries and cache rows")
+    want_c, want_s = f8.quantize_rows(T["attn"])
+    assert np.array_equal(T["a_codes"], want_c) and np.array_equal(T["a_scale"].view(np.uint32), want_s.view(np.uint32)), "codes of the joint row"
+    gate1, resid = w["gate1"].astype(np.float64), h_in.astype(np.float64)
+    _check_linear("projection back + residual", T["a_codes"], T["a_scale"], q8["w_2"][0], q8["w_2"][1], w["b_2"], host(out),
+                  post=lambda lin, b: (resid + gate1 * lin, np.abs(gate1) * b), out_bf16=True)
+    ctx.close()
+
+
 def test_block_fp8_argument_checks():
     ctx = rg.Context(256, 4, 64, 1024, 64, 64)
     bw, w8 = rg.BlockWeights(), rg.BlockWeightsFp8()
     h = torch.zeros((8, 256), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(rg.RegionEError) as err:      # no weights
-        rg.regione_block_forward_fp8(ctx, bw, w8, h, h, rg.BF16, 8, 0, None, 0, None, None, 0, 0)
+        rg.regione_block_forward_fp8(ctx, bw, w8, rg.BLOCK_DOUBLE, h, h, rg.BF16, 8, 0, None, 0, None, None, 0, 0)
     assert err.value.code == rg.ERR_INVALID_ARG
-    rg.regione_block_forward_fp8(ctx, bw, w8, None, None, rg.BF16, 0, 0, None, 0, None, None, 0, 0)     # no row: nothing happens
+    rg.regione_block_forward_fp8(ctx, bw, w8, rg.BLOCK_SINGLE, None, None, rg.BF16, 0, 0, None, 0, None, None, 0, 0)     # no row: nothing happens
     ctx.close()
     ctx32 = rg.Context(256, 4, 64, 1024, 64, 64, compute_dtype=rg.FP32)
     with pytest.raises(rg.RegionEError) as err:
-        rg.regione_block_forward_fp8(ctx32, bw, w8, h, h, rg.FP32, 8, 0, None, 0, None, None, 0, 0)
+        rg.regione_block_forward_fp8(ctx32, bw, w8, rg.BLOCK_DOUBLE, h, h, rg.FP32, 8, 0, None, 0, None, None, 0, 0)
     assert err.value.code == rg.ERR_UNSUPPORTED
     ctx32.close()
