@@ -449,6 +449,8 @@ int regione_euler_rows(regione_ctx* ctx, void* x_full, const void* v_full, const
  *   - the attention output and the activated MLP rows (bf16 as in the bf16 block), by regione_quantize_rows_fp8's
  *     kernel.
  * Everything else — attention, K/V cache (bf16), gates, residual stream, flags, slots — is the bf16 block's.
+ * The first call on a context allocates the workspace of the codes (max_fresh x (H + M) bytes and max_fresh scales),
+ * which lives as long as the context.
  * A single-stream block has two projections: w_1 [3H+M, H] and w_2 [H, H+M] (w_qkv, w_o unused); the input of the
  * second is the joint row [attention | GELU(m)] of H + M columns, quantised as one row.
  * Restrictions: bf16 context, hidden <= 4096, hidden and mlp multiples of 128, hidden + mlp <= 16384 for single-stream

@@ -315,6 +315,19 @@ def test_velocity_head_equals_linear_cache_and_scatter(dtype, n):
     ca3, xe3 = dev(np.ones((n, c), np.float32), dtype), dev(x_e, dtype)
     rg.regione_velocity_head(ctx2, dh, wp, db, n, c, hidden, dt, None, ca3, xe3, None, None, code)
     assert torch.equal(ca3, ca1) and torch.equal(xe3, xe1)
+    # a forced plan of the general GEMM kernels takes the other road (K splits, the step in their merge kernel): same
+    # three calls bit for bit there as well, and the oracle's result
+    rg.regione_tune_gemm(ctx2, 1, 4)
+    try:
+        v4, ca4, xe4, xf4 = dev(np.zeros((n, c), np.float32), dtype), dev(np.ones((n, c), np.float32), dtype), dev(x_e, dtype), dev(x_full, dtype)
+        rg.regione_velocity_head(ctx2, dh, wp, db, n, c, hidden, dt, v4, ca4, xe4, xf4, didx, code)
+        v5, ca5, xe5 = dev(np.zeros((n, c), np.float32), dtype), dev(np.ones((n, c), np.float32), dtype), dev(x_e, dtype)
+        rg.regione_linear(ctx2, dh, wp, db, n, c, hidden, rg.ACT_NONE, code, v5)
+        rg.regione_velocity_cache(ctx2, False, 1.0, dt, v5, ca5, None, xe5, None, n, c, code)
+        assert torch.equal(v4, v5) and torch.equal(ca4, ca5) and torch.equal(xe4, xe5)
+        assert_close(host(xf4), xf_o, "merged latent, general kernels", **tol)
+    finally:
+        rg.regione_tune_gemm(ctx2, 0, 0)
     ctx2.close()
 
 
