@@ -261,6 +261,29 @@ template <> __device__ __forceinline__ void st8<float>(float* p, const float (&v
     *reinterpret_cast<ln_f32x4*>(p) = ln_f32x4{v[0], v[1], v[2], v[3]};
     *reinterpret_cast<ln_f32x4*>(p + 4) = ln_f32x4{v[4], v[5], v[6], v[7]};
 }
+// streamed once: non-temporal on both sides
+template <typename T> __device__ __forceinline__ void ld8_nt(const T* p, float (&v)[8]);
+template <> __device__ __forceinline__ void ld8_nt<bf16_t>(const bf16_t* p, float (&v)[8]) {
+    const ln_bf16x8 x = __builtin_nontemporal_load(reinterpret_cast<const ln_bf16x8*>(p));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = static_cast<float>(x[e]);
+}
+template <> __device__ __forceinline__ void ld8_nt<float>(const float* p, float (&v)[8]) {
+    const ln_f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const ln_f32x4*>(p)), b = __builtin_nontemporal_load(reinterpret_cast<const ln_f32x4*>(p + 4));
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] = a[e]; v[4 + e] = b[e]; }
+}
+template <typename T> __device__ __forceinline__ void st8_nt(T* p, const float (&v)[8]);
+template <> __device__ __forceinline__ void st8_nt<bf16_t>(bf16_t* p, const float (&v)[8]) {
+    ln_bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(v[e]);
+    __builtin_nontemporal_store(o, reinterpret_cast<ln_bf16x8*>(p));
+}
+template <> __device__ __forceinline__ void st8_nt<float>(float* p, const float (&v)[8]) {
+    __builtin_nontemporal_store(ln_f32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<ln_f32x4*>(p));
+    __builtin_nontemporal_store(ln_f32x4{v[4], v[5], v[6], v[7]}, reinterpret_cast<ln_f32x4*>(p + 4));
+}
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
 velocity_cache_vec_kernel(int reuse, float factor, float dt, const T* __restrict__ v_fresh, T* __restrict__ c_a,
@@ -269,22 +292,31 @@ velocity_cache_vec_kernel(int reuse, float factor, float dt, const T* __restrict
     if (n_dev) { const int64_t nd = *n_dev; n = nd < n_max ? (nd < 0 ? 0 : nd) : n_max; }
     const int64_t groups = n * c / 8;          // c is a multiple of 8 on this path
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-    for (int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; g < groups; g += stride) {
-        const int64_t i = g * 8;
-        float vu[8], x[8];
-        ld8<T>(x_e + i, x);
-        if (reuse) {
-            ld8<T>(c_a + i, vu);
+    const T* vsrc = reuse ? c_a : v_fresh;
+    constexpr int U = 2;                       // groups per thread in flight (four measured the same): all loads of a round before its first store
+    for (int64_t g0 = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; g0 < groups; g0 += U * stride) {
+        float vu[U][8], x[U][8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) vu[e] = __fmul_rn(factor, vu[e]);
-        } else {
-            ld8<T>(v_fresh + i, vu);
-            st8<T>(c_a + i, vu);
+        for (int u = 0; u < U; ++u) {
+            const int64_t g = g0 + u * stride;
+            if (g < groups) { ld8_nt<T>(x_e + g * 8, x[u]); ld8_nt<T>(vsrc + g * 8, vu[u]); }
         }
-        if (v_out) st8<T>(v_out + i, vu);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = __fsub_rn(x[e], __fmul_rn(dt, vu[e]));
-        st8<T>(x_e + i, x);
+        for (int u = 0; u < U; ++u) {
+            const int64_t g = g0 + u * stride;
+            if (g >= groups) continue;
+            const int64_t i = g * 8;
+            if (reuse) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vu[u][e] = __fmul_rn(factor, vu[u][e]);
+            } else {
+                st8_nt<T>(c_a + i, vu[u]);
+            }
+            if (v_out) st8_nt<T>(v_out + i, vu[u]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[u][e] = __fsub_rn(x[u][e], __fmul_rn(dt, vu[u][e]));
+            st8_nt<T>(x_e + i, x[u]);
+        }
     }
 }
 
