@@ -22,7 +22,10 @@ def _outputs(wl, n):
 
 
 CASES = [step.CONFIG_TINY, step.CONFIG_TINY_BF16, dataclasses.replace(step.CONFIG_TINY_BF16, text_fresh=True),
-         dataclasses.replace(step.CONFIG_TINY_BF16, kind="single"), step.CONFIG_BLOCK]
+         dataclasses.replace(step.CONFIG_TINY_BF16, kind="single"), step.CONFIG_BLOCK,
+         dataclasses.replace(step.CONFIG_TINY_BF16, n_edited=1, name="tiny bf16, one token edited"),
+         dataclasses.replace(step.CONFIG_TINY_BF16, n_edited=256, name="tiny bf16, every token edited"),
+         dataclasses.replace(step.CONFIG_TINY_BF16, n_edited=77, mask="blob", text_fresh=True, extras=True, name="tiny bf16, blobs, extras")]
 
 
 @pytest.mark.parametrize("cfg", CASES, ids=lambda c: f"{c.name[:24]}-{c.dtype}-{c.kind}-{'txt' if c.text_fresh else 'img'}")
