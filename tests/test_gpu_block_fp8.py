@@ -61,12 +61,15 @@ def _check_linear(what, codes, row_scale, w_codes, w_scale, bias, got, post=None
     (256, 4, 64, 1024, 32, 256, 36, "bf16"),
     (256, 4, 64, 1024, 32, 256, 36, "f32"),
     (1024, 8, 128, 4096, 64, 400, 333, "bf16"),
+    (3072, 24, 128, 12288, 128, 1024, 300, "bf16"),       # the headline block's widths
 ])
 @pytest.mark.parametrize("mode", ["retrieve_img", "retrieve_txt_img", "store", "plain"])
 def test_block_fp8_stage_by_stage(hidden, heads, d, mlp, n_txt, n_img, n_e, h_dtype, mode):
+    if hidden == 3072 and mode != "retrieve_txt_img":
+        pytest.skip("the 3072-wide block runs once, in the mode that uses both streams")
     n_all = n_txt + 2 * n_img
     rng = np.random.default_rng(inputs.workload_seed(8, hidden + n_e))
-    streams = [inputs.stream_weights(rng, hidden, mlp, "double", "bf16", std=0.03) for _ in range(2)]
+    streams = [inputs.stream_weights(rng, hidden, mlp, "double", "bf16", std=0.03 if hidden < 3072 else 0.02) for _ in range(2)]
     h_all = inputs.bf16_round(rng.standard_normal((n_all, hidden)).astype(np.float32))
     ctx = rg.Context(hidden, heads, d, mlp, n_all, 4096)
     bw, keep = block_to_device(streams, "double", ctx)
