@@ -57,3 +57,57 @@ def test_single_call_step_without_edited_tokens():
         assert int(wl.mask.sum().item()) == 0 and torch.equal(wl.h_next, before)
     finally:
         wl.close()
+
+
+def test_single_call_step_through_a_stack_of_blocks():
+    """Three blocks (double, single, double) with a cache each: the one call against partition, gather, the three block
+    calls, the velocity head and the scatter made one by one."""
+    import numpy as np
+    from paper_2510_25590_amd import binding as rg
+    from paper_2510_25590_amd import inputs
+    from gpu_util import dev, block_to_device
+    cfg = step.CONFIG_TINY_BF16
+    wl = step.RegionStepWorkload(cfg)          # supplies latents, the hidden state, head weights and the first block with its cache
+    try:
+        ctx, n_all = wl.ctx, wl.n_all
+        rng = np.random.default_rng(77)
+        kinds = ["double", "single", "double"]
+        blocks, types, kcs, vcs, keep = [wl.weights], [wl.block_type], [wl.k_cache], [wl.v_cache], []
+        h_store = dev(wl.host["h_store"], "bf16")
+        slots = torch.arange(n_all, dtype=torch.int32, device="cuda")
+        for kind in kinds[1:]:
+            streams = [inputs.stream_weights(rng, cfg.hidden, cfg.mlp, kind, "bf16", std=0.05) for _ in range(2 if kind == "double" else 1)]
+            bw, kp = block_to_device(streams, kind, ctx)
+            kc = torch.zeros_like(wl.k_cache); vc = torch.zeros_like(kc)
+            bt = rg.BLOCK_DOUBLE if kind == "double" else rg.BLOCK_SINGLE
+            tmp = torch.empty_like(h_store)
+            rg.regione_block_forward(ctx, bw, bt, h_store, tmp, rg.BF16, n_all, cfg.n_txt if kind == "double" else 0, slots, 0, kc, vc, n_all, rg.FLAG_STORE)
+            blocks.append(bw); types.append(bt); kcs.append(kc); vcs.append(vc); keep.append(kp)
+        torch.cuda.synchronize()
+        # one by one
+        n = rg.regione_partition(ctx, wl.x_t, wl.v_prev, wl.x_ref, wl.n_img, cfg.channels, wl.dt, cfg.sigma, cfg.eta, wl.score, wl.mask, wl.e_index, wl.u_index, wl.n_dev)
+        rg.regione_gather_pair(ctx, wl.h_now, cfg.hidden, wl.dt, wl.h_e, wl.x_t, cfg.channels, wl.dt, wl.x_e, wl.e_index, wl.n_dev, n)
+        src = wl.h_e
+        for bw, bt, kc, vc in zip(blocks, types, kcs, vcs):
+            rg.regione_block_forward(ctx, bw, bt, src, wl.h_e_out, wl.dt, n, 0, wl.e_index, cfg.n_txt, kc, vc, n_all, rg.FLAG_RETRIEVE)
+            src = wl.h_e_out
+        rg.regione_velocity_head(ctx, wl.h_e_out, wl.w_head, wl.b_head, n, cfg.channels, cfg.hidden, cfg.dt, wl.v_e, wl.c_a, wl.x_e, wl.x_next, wl.e_index, wl.dt)
+        rg.regione_scatter(ctx, wl.h_next, cfg.hidden, wl.dt, wl.e_index, wl.n_dev, n, wl.h_e_out)
+        want = _outputs(wl, n)
+        want_caches = [(k.clone(), v.clone()) for k, v in zip(kcs, vcs)]
+        wl.h_next.copy_(wl.h_now); wl.x_next.copy_(wl.x_t); wl.v_e.fill_(0); wl.c_a.fill_(0)
+        # one call
+        args = rg.make_region_step_args(
+            x_t=wl.x_t, v=wl.v_prev, x_ref=wl.x_ref, n_tokens=wl.n_img, c=cfg.channels, dtype=wl.dt, sigma_t=cfg.sigma, eta=cfg.eta,
+            score=wl.score, mask=wl.mask, e_index=wl.e_index, u_index=wl.u_index, n_edited_dev=wl.n_dev,
+            h_full=wl.h_now, h_dtype=wl.dt, n_txt_fresh=0, h_rows=wl.h_fresh, h_rows_out=wl.h_fresh_out, slots=None,
+            blocks=blocks, block_types=types, k_caches=kcs, v_caches=vcs, n_all=n_all, slot_offset=cfg.n_txt,
+            w_head=wl.w_head, b_head=wl.b_head, dt=cfg.dt, v_out=wl.v_e, c_a=wl.c_a, x_e=wl.x_e, x_next_full=wl.x_next, h_next_full=wl.h_next)
+        assert rg.regione_region_step(ctx, args) == n
+        got = _outputs(wl, n)
+        for k, w in want.items():
+            assert torch.equal(got[k], w), k
+        for (k0, v0), k1, v1 in zip(want_caches, kcs, vcs):
+            assert torch.equal(k0, k1) and torch.equal(v0, v1)
+    finally:
+        wl.close()
