@@ -53,6 +53,11 @@ def test_error_paths_without_gpu():
     # the entry point that allocates nothing checks its arguments and its size limit before it touches the device
     assert lib.regione_partition_static(None, None, None, None, 16, 64, 0, 0.5, 0.9, None, None, None, None, None) == rg.ERR_INVALID_ARG
     assert lib.regione_partition_static(None, None, None, None, -1, 64, 0, 0.5, 0.9, None, None, None, None, None) == rg.ERR_INVALID_ARG
+    # the step as one call and the 8-bit block refuse null arguments before anything else
+    n = C.c_int32(-1)
+    assert lib.regione_region_step(None, None, C.byref(n)) == rg.ERR_INVALID_ARG and n.value == -1
+    assert b"region_step" in lib.regione_last_error()
+    assert lib.regione_block_forward_fp8(None, None, None, rg.BLOCK_DOUBLE, None, None, rg.BF16, 0, 0, None, 0, None, None, 0, 0, None) == rg.ERR_INVALID_ARG
 
 
 def test_relative_change_trigger_host_calls_match_oracle_rule():
@@ -146,6 +151,29 @@ def test_gamma_fit_host_matches_oracle():
         rg.regione_gamma_fit_host(bad, t)
     with pytest.raises(rg.RegionEError):
         rg.regione_gamma_fit_host(np.zeros((S, T + 1)), t)
+
+
+def test_struct_layouts_match_the_binding(tmp_path):
+    """Every struct that crosses the boundary by pointer has the same size in C and in the ctypes binding (a field added on
+    one side only would shift everything behind it)."""
+    import shutil
+    import subprocess
+    import ctypes as C
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler here")
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    pairs = [("regione_dims", rg.Dims), ("regione_stream_weights", rg.StreamWeights), ("regione_block_weights", rg.BlockWeights),
+             ("regione_avd_state", rg.AvdState), ("regione_rel_state", rg.RelState), ("regione_region_step_args", rg.RegionStepArgs),
+             ("regione_stream_weights_fp8", rg.StreamWeightsFp8), ("regione_block_weights_fp8", rg.BlockWeightsFp8), ("regione_fp8_taps", rg.Fp8Taps)]
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include "regione.h"\nint main(void) {\n' +
+                   "".join(f'    printf("%zu\\n", sizeof({c_name}));\n' for c_name, _ in pairs) + "    return 0;\n}\n")
+    exe = tmp_path / "sizes"
+    subprocess.run([gcc, "-std=c99", "-I", inc, str(src), "-o", str(exe)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    for (c_name, cls), size in zip(pairs, got):
+        assert C.sizeof(cls) == size, (c_name, C.sizeof(cls), size)
 
 
 def test_header_is_plain_c(tmp_path):
